@@ -1,0 +1,159 @@
+"""CPU oracle of the offloading-interval rule -- TEST INFRASTRUCTURE, not product code.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+file.  It shares no code with the HIP path and imports nothing from it.
+
+Contents (all exact integer arithmetic; times are nanoseconds):
+
+  offloaded_layers / trigger_layers  placement for an interval N        (Sec. 4.3)
+  timeline                           iteration time under that placement (Sec. 4.3, Fig. 7)
+  pick_interval                      smallest N that meets the SLO       (Sec. 4.3 last par., 4.4)
+  resident_bytes / max_interval      GPU-capacity bound on N             (Sec. 4.5)
+  paper_rule                         the analyzer's closed form          (Sec. 4.4)
+
+Layers are 0-indexed here; the paper counts from 1.
+
+Readings of the paper taken here (each listed in the design notes):
+  * interval N: in every group of N consecutive layers the last one is host
+    resident; a trailing group shorter than N keeps all its layers on the GPU.
+  * the load of an offloaded layer is issued when compute reaches the first layer
+    of its group (Sec. 4.3).  For N = 1 that would be the layer itself, yet the
+    paper says N = 1 behaves like DeepSpeed, which fetches one layer ahead; so the
+    trigger is the previous layer when N = 1.
+  * one copy stream, served in issue order; an iteration starts with nothing in
+    flight.
+  * the analyzer's printed formula divides one layer's compute time by one layer's
+    transfer time, which is zero in the paper's own regime (transfer 3.5x / 13.8x
+    compute, Sec. 3.2).  It is read with the whole iteration's budget in the
+    numerator, and the interval is rounded so that no more than L_offload layers
+    are offloaded.  It is reported, never used for the decision.
+
+Parity pins (tests/test_oracle_schedule.py): Fig. 7's worked example, closed forms
+for uniform times, a separately written two-queue event simulation, brute force on
+tiny cases, monotonicity in the SLO, Table 1's shape.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence, Tuple
+
+
+# ---------------------------------------------------------------------------
+# placement (Sec. 4.3, "Offloading interval")
+# ---------------------------------------------------------------------------
+
+def offloaded_layers(L: int, N: int) -> List[int]:
+    """Host-resident layers for interval N: the last layer of every full group of N.
+    N <= 0 or N > L: nothing is offloaded."""
+    if N <= 0 or N > L:
+        return []
+    return [l for l in range(L) if (l + 1) % N == 0]
+
+
+def trigger_layers(L: int, N: int) -> List[int]:
+    """For each offloaded layer (same order), the layer at whose start its load is issued."""
+    back = max(N - 1, 1)
+    return [max(0, o - back) for o in offloaded_layers(L, N)]
+
+
+# ---------------------------------------------------------------------------
+# iteration timeline (Fig. 7: compute stream above, copy stream below, sync
+# point before each offloaded layer)
+# ---------------------------------------------------------------------------
+
+def timeline(tc: Sequence[int], tx: Sequence[int], N: int) -> Tuple[int, List[int]]:
+    """Iteration time and the stall before each offloaded layer.
+
+    tc[l]: compute time of layer l; tx[l]: host-to-GPU transfer time of layer l's state.
+    """
+    L = len(tc)
+    off = offloaded_layers(L, N)
+    trig = trigger_layers(L, N)
+    t = 0                 # compute-stream clock
+    copy_free = 0         # time the copy stream finishes what it has been given
+    ready = {}            # offloaded layer -> time its state is on the GPU
+    stalls = []
+    for l in range(L):
+        for o, g in zip(off, trig):
+            if g == l:
+                start = max(copy_free, t)
+                copy_free = start + tx[o]
+                ready[o] = copy_free
+        if l in ready:
+            stall = max(0, ready[l] - t)
+            stalls.append(stall)
+            t += stall
+        t += tc[l]
+    return t, stalls
+
+
+def hidden_fraction(tx: Sequence[int], N: int, stalls: Sequence[int]) -> float:
+    """Share of transfer time that did not delay compute (1.0 when nothing is offloaded)."""
+    tot = sum(tx[o] for o in offloaded_layers(len(tx), N))
+    return 1.0 if tot == 0 else 1.0 - sum(stalls) / tot
+
+
+# ---------------------------------------------------------------------------
+# GPU-capacity bound (Sec. 4.5: maximum interval from the memory of the GPU)
+# ---------------------------------------------------------------------------
+
+def resident_bytes(L: int, N: int, state_bytes: int, slot_bytes: int, fixed_bytes: int) -> int:
+    """GPU bytes held for interval N: resident layers' state, two staging slots when
+    anything is offloaded, plus what does not depend on N (workspace)."""
+    K = len(offloaded_layers(L, N))
+    return (L - K) * state_bytes + (2 * slot_bytes if K else 0) + fixed_bytes
+
+
+def max_interval(L: int, budget: int, state_bytes: int, slot_bytes: int, fixed_bytes: int) -> int:
+    """Largest interval whose footprint fits the budget; L+1 stands for "no offloading"
+    (infinite maximum, Sec. 4.5); 0 when not even N = 1 fits.  budget <= 0: no cap."""
+    if budget <= 0:
+        return L + 1
+    best = 0
+    for N in range(1, L + 2):
+        if resident_bytes(L, N, state_bytes, slot_bytes, fixed_bytes) <= budget:
+            best = N
+    return best
+
+
+# ---------------------------------------------------------------------------
+# picker: the optimal interval is the smallest one that meets the SLO (Sec. 4.3,
+# 4.4); the request is rejected when minimum > maximum (Sec. 4.5, Fig. 8)
+# ---------------------------------------------------------------------------
+
+def min_interval(tc: Sequence[int], tx: Sequence[int], slo: int) -> Optional[int]:
+    """Smallest N in 1..L with iteration time <= slo; L+1 if only the un-offloaded
+    iteration meets it; None if even that does not."""
+    L = len(tc)
+    for N in range(1, L + 1):
+        if timeline(tc, tx, N)[0] <= slo:
+            return N
+    return L + 1 if sum(tc) <= slo else None
+
+
+def pick_interval(tc: Sequence[int], tx: Sequence[int], slo: int, n_max: int) -> Optional[int]:
+    """The interval to run with, or None when the SLO cannot be met within capacity."""
+    n_min = min_interval(tc, tx, slo)
+    if n_min is None or n_min > n_max:
+        return None
+    return n_min
+
+
+# ---------------------------------------------------------------------------
+# the analyzer's closed form (Sec. 4.4, "Design"), reported beside the pick
+# ---------------------------------------------------------------------------
+
+def paper_rule(L: int, t_compute: int, t_trans: int, slo: int) -> int:
+    """L_offload = floor(slo / t_trans) layer transfers fit a saturated copy stream
+    within the SLO (slo = (1 + delta) * L * t_compute); the interval is the smallest N
+    that offloads no more than that: floor(L / (L_offload + 1)) + 1."""
+    if t_trans <= 0:
+        return 1
+    l_off = slo // t_trans
+    return L // (l_off + 1) + 1
+
+
+def paper_rule_as_printed(L: int, t_compute: int, t_trans: int, delta_num: int, delta_den: int):
+    """The formula exactly as printed: L_offload = floor(t_compute (1+delta) / t_trans),
+    interval = floor(L / L_offload).  None where it divides by zero."""
+    l_off = (t_compute * (delta_den + delta_num)) // (t_trans * delta_den)
+    return None if l_off == 0 else L // l_off

@@ -1,0 +1,242 @@
+"""Pins for oracle/schedule.py: the paper's worked example (Fig. 7), closed forms for
+uniform layer times, a separately written two-queue event simulation, hand-worked
+numbers, brute force and the invariants the method promises."""
+import itertools
+import os
+import random
+
+import pytest
+
+from oracle import schedule as osch
+
+
+def _read_kv(path):
+    out = {}
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        k, *v = line.split()
+        out[k] = [int(t) for t in v]
+    return out
+
+
+def test_fig7_worked_example(golden_dir):
+    g = _read_kv(os.path.join(golden_dir, "fig7_schedule.txt"))
+    L, N = g["layers"][0], g["interval"][0]
+    off = osch.offloaded_layers(L, N)
+    assert [o + 1 for o in off] == g["offloaded"]
+    assert [t + 1 for t in osch.trigger_layers(L, N)] == g["prefetch_issued_before"]
+    assert sorted(set(range(1, L + 1)) - {o + 1 for o in off}) == g["gpu_resident"]
+    assert [o + 1 for o in off] == g["sync_before"]
+
+
+def test_config1_placement(golden_dir):
+    g = _read_kv(os.path.join(golden_dir, "config1_placement.txt"))
+    assert osch.offloaded_layers(g["layers"][0], g["interval"][0]) == g["offloaded_zero_indexed"]
+
+
+def test_placement_special_cases():
+    assert osch.offloaded_layers(6, 1) == [0, 1, 2, 3, 4, 5]       # every layer on the host
+    assert osch.trigger_layers(6, 1) == [0, 0, 1, 2, 3, 4]          # fetched one layer ahead
+    assert osch.offloaded_layers(6, 7) == [] and osch.offloaded_layers(6, 0) == []
+    assert osch.offloaded_layers(10, 4) == [3, 7]                   # trailing 2 layers stay on the GPU
+    assert osch.offloaded_layers(10, 10) == [9]
+    for L in range(1, 40):
+        for N in range(1, L + 3):
+            off = osch.offloaded_layers(L, N)
+            assert len(off) == (L // N if N <= L else 0)
+            for o, g in zip(off, osch.trigger_layers(L, N)):
+                assert g == (o - (N - 1) if N > 1 else max(0, o - 1))
+
+
+def test_timeline_hand_worked():
+    # L=4, N=2: layers 1 and 3 offloaded, loads issued at layers 0 and 2.
+    # tc = 10 each, tx = 25 each.
+    # t=0: load(1) runs 0..25.  layer0 0..10.  layer1 waits until 25 (stall 15), runs 25..35.
+    # layer2 starts 35: load(3) runs 35..60; layer2 35..45; layer3 waits to 60 (stall 15), 60..70.
+    T, stalls = osch.timeline([10] * 4, [25] * 4, 2)
+    assert (T, stalls) == (70, [15, 15])
+    # fully hidden when tx <= tc
+    assert osch.timeline([10] * 4, [9] * 4, 2) == (40, [0, 0])
+    # N=1, L=3, tc=10, tx=25: loads of 0 and 1 issued at layer 0 (0..25, 25..50); load of 2 at
+    # layer 1.  layer0 25..35; layer1 starts 35 -> load(2) 50..75; waits to 50, runs 50..60;
+    # layer2 waits to 75, runs 75..85.
+    assert osch.timeline([10] * 3, [25] * 3, 1) == (85, [25, 15, 15])
+    # non-uniform: only the offloaded layers' tx matter
+    T, stalls = osch.timeline([5, 7, 11, 13], [1000, 20, 1000, 3], 2)
+    assert (T, stalls) == (5 + 15 + 7 + 11 + 13, [15, 0])
+    assert osch.hidden_fraction([1000, 20, 1000, 3], 2, stalls) == pytest.approx(1 - 15 / 23)
+
+
+def test_timeline_degenerate():
+    tc = [3, 1, 4, 1, 5, 9, 2, 6]
+    assert osch.timeline(tc, [100] * 8, 9)[0] == sum(tc)            # N > L: nothing offloaded
+    assert osch.timeline(tc, [100] * 8, 0)[0] == sum(tc)
+    for N in range(1, 9):
+        assert osch.timeline(tc, [0] * 8, N)[0] == sum(tc)          # free transfers never stall
+
+
+def test_timeline_closed_forms_uniform():
+    rnd = random.Random(1)
+    for _ in range(3000):
+        L, c, x = rnd.randint(1, 48), rnd.randint(1, 1000), rnd.randint(0, 20000)
+        N = rnd.randint(1, L + 1)
+        T, stalls = osch.timeline([c] * L, [x] * L, N)
+        K = L // N if N <= L else 0
+        if N >= 2:
+            want = L * c + K * max(0, x - (N - 1) * c)
+        else:
+            want = x + (L - 1) * max(c, x) + c
+        assert T == want, (L, c, x, N)
+        if N >= 2 and K and x:
+            assert osch.hidden_fraction([x] * L, N, stalls) == pytest.approx(min(1.0, (N - 1) * c / x))
+
+
+def _two_queue_simulation(tc, tx, N):
+    """Independent formulation: build the list of operations each stream is given, with
+    explicit cross-stream dependencies, then resolve start/end times by relaxation."""
+    L = len(tc)
+    off = [l for l in range(L) if N >= 1 and N <= L and (l + 1) % N == 0]
+    trig = {o: max(0, o - max(N - 1, 1)) for o in off}
+    compute = [("layer", l) for l in range(L)]
+    copy = [("load", o) for o in sorted(off, key=lambda o: (trig[o], o))]
+    end = {}
+    start = {}
+    changed = True
+    while changed:
+        changed = False
+        for queue in (compute, copy):
+            prev_end = 0
+            for op in queue:
+                deps = [prev_end]
+                kind, l = op
+                if kind == "layer" and l in off:
+                    deps.append(end.get(("load", l)))
+                if kind == "load":
+                    g = trig[l]
+                    deps.append(start.get(("layer", g)) if g > 0 else 0)
+                    if g > 0:
+                        # issued when compute *reaches* layer g = when layer g-1 ends
+                        deps[-1] = end.get(("layer", g - 1))
+                if any(d is None for d in deps):
+                    break
+                s = max(deps)
+                e = s + (tc[l] if kind == "layer" else tx[l])
+                if start.get(op) != s or end.get(op) != e:
+                    start[op], end[op] = s, e
+                    changed = True
+                prev_end = e
+    return end[("layer", L - 1)]
+
+
+def test_timeline_equals_independent_event_simulation():
+    rnd = random.Random(2)
+    for _ in range(1500):
+        L = rnd.randint(1, 20)
+        tc = [rnd.randint(1, 100) for _ in range(L)]
+        tx = [rnd.randint(0, 400) for _ in range(L)]
+        N = rnd.randint(1, L + 1)
+        assert osch.timeline(tc, tx, N)[0] == _two_queue_simulation(tc, tx, N), (tc, tx, N)
+
+
+def test_picker_is_min_feasible_and_monotone_in_slo():
+    rnd = random.Random(3)
+    for _ in range(400):
+        L = rnd.randint(1, 16)
+        tc = [rnd.randint(1, 100) for _ in range(L)]
+        tx = [rnd.randint(0, 600) for _ in range(L)]
+        prev = None
+        for slo in sorted(rnd.randint(1, 4000) for _ in range(8)):
+            n = osch.min_interval(tc, tx, slo)
+            feas = [N for N in range(1, L + 1) if osch.timeline(tc, tx, N)[0] <= slo]
+            if feas:
+                assert n == min(feas)
+            elif sum(tc) <= slo:
+                assert n == L + 1
+            else:
+                assert n is None
+            if prev is not None:            # a looser SLO never needs a larger interval
+                assert n is not None and n <= prev
+            prev = n if n is not None else prev
+
+
+def test_pick_respects_capacity():
+    tc, tx = [10] * 8, [35] * 8
+    # T(N): N=1: 35+7*35+10=290; N=2: 80+4*25=180; N=3: 80+2*15=110; N=4: 80+2*5=90; N>=5: 80
+    assert [osch.timeline(tc, tx, N)[0] for N in range(1, 10)] == [290, 180, 110, 90, 80, 80, 80, 80, 80]
+    assert osch.min_interval(tc, tx, 100) == 4
+    assert osch.pick_interval(tc, tx, 100, n_max=9) == 4
+    assert osch.pick_interval(tc, tx, 100, n_max=4) == 4
+    assert osch.pick_interval(tc, tx, 100, n_max=3) is None       # minimum > maximum: reject
+    assert osch.pick_interval(tc, tx, 79, n_max=9) is None        # below the un-offloaded time
+    assert osch.pick_interval(tc, tx, 80, n_max=9) == 5
+    assert osch.min_interval([10] * 4, [100] * 4, 40) == 5         # only "offload nothing" meets it
+
+
+def test_capacity_bound():
+    L, state, slot, fixed = 8, 100, 100, 50
+    # R(N) = (L-K)*100 + 200 (if K) + 50
+    assert osch.resident_bytes(L, 1, state, slot, fixed) == 250
+    assert osch.resident_bytes(L, 2, state, slot, fixed) == 650
+    assert osch.resident_bytes(L, 8, state, slot, fixed) == 950
+    assert osch.resident_bytes(L, 9, state, slot, fixed) == 850   # nothing offloaded: no slots
+    assert osch.max_interval(L, 250, state, slot, fixed) == 1
+    assert osch.max_interval(L, 249, state, slot, fixed) == 0
+    assert osch.max_interval(L, 700, state, slot, fixed) == 2
+    assert osch.max_interval(L, 850, state, slot, fixed) == 9     # model fits: no upper limit
+    assert osch.max_interval(L, 0, state, slot, fixed) == 9
+    prev = 0
+    for N in range(1, L + 1):
+        r = osch.resident_bytes(L, N, state, slot, fixed)
+        assert r >= prev
+        prev = r
+
+
+def test_paper_rule_never_exceeds_timeline_pick():
+    rnd = random.Random(4)
+    for _ in range(5000):
+        L, c, x = rnd.randint(1, 80), rnd.randint(1, 500), rnd.randint(1, 60000)
+        slo = rnd.randint(L * c, 4 * L * c)
+        n_paper = osch.paper_rule(L, c, x, slo)
+        assert len(osch.offloaded_layers(L, n_paper)) <= slo // x
+        if n_paper > 1:
+            assert len(osch.offloaded_layers(L, n_paper - 1)) > slo // x
+        n_pick = osch.min_interval([c] * L, [x] * L, slo)
+        assert n_pick is not None and n_paper <= n_pick
+
+
+def test_printed_formula_breaks_in_the_papers_own_regime():
+    # Sec. 3.2: a layer's transfer is 13.8x its compute in decoding; delta = 50 %
+    assert osch.paper_rule_as_printed(32, 1000, 13800, 1, 2) is None
+    assert osch.paper_rule_as_printed(32, 1000, 300, 1, 2) == 32 // 5
+
+
+def test_table1_shape(golden_dir):
+    rows = [l.split() for l in open(os.path.join(golden_dir, "table1_record.txt"))
+            if l.strip() and not l.startswith("#")]
+    seqs = [int(v) for v in rows[0][1:]]
+    table = {int(r[0]): [int(v) for v in r[1:]] for r in rows[1:]}
+    batches = sorted(table)
+    # the printed record: non-increasing along both axes, ends at 1
+    for b in batches:
+        assert table[b] == sorted(table[b], reverse=True)
+    for j in range(len(seqs)):
+        col = [table[b][j] for b in batches]
+        assert col == sorted(col, reverse=True)
+    assert table[batches[-1]][-1] == 1
+    # the picker has the same shape when layer compute grows with batch*seq and the transfer is fixed
+    L, x = 32, 150_000
+    for delta_pct in (20, 50, 100):
+        ours = {}
+        for b, s in itertools.product(batches, seqs):
+            c = 2_000 + 3 * b * s
+            slo = L * c * (100 + delta_pct) // 100
+            ours[(b, s)] = osch.min_interval([c] * L, [x] * L, slo)
+        for b in batches:
+            r = [ours[(b, s)] for s in seqs]
+            assert r == sorted(r, reverse=True)
+        for s in seqs:
+            r = [ours[(b, s)] for b in batches]
+            assert r == sorted(r, reverse=True)
+        assert ours[(batches[-1], seqs[-1])] == 1       # compute of a layer exceeds its transfer
