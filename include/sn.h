@@ -1,0 +1,190 @@
+/*
+ * sn.h -- C ABI of the SELECT-N offloaded serving iteration for one MI355X (gfx950).
+ *
+ * The library runs a decoder-only model layer by layer (paper Sec. 2.1).  With an
+ * offloading interval N, the last layer of every group of N layers keeps its state
+ * (weights and KV-cache slice) in pinned host memory; its load into one of two
+ * device staging slots is issued on a copy stream when compute reaches the first
+ * layer of the group, and a fence precedes the offloaded layer (Sec. 4.3, Fig. 7).
+ * A profiler measures each layer's compute time and transfer time (Sec. 4.4) and a
+ * picker returns the smallest interval whose iteration time meets a latency SLO,
+ * bounded above by the GPU memory budget (Sec. 4.3 last paragraph, Sec. 4.5).
+ *
+ * Conventions
+ *   - every function returns SN_OK (0) or a negative SN_E_* code; nothing aborts or
+ *     throws across this boundary.  sn_last_error() gives a message for the last
+ *     failing call on that context (or on the calling thread when ctx is NULL).
+ *   - "host" / "device" is stated for every pointer.  Device pointers are plain HIP
+ *     device addresses on the current device; the compute stream is a hipStream_t
+ *     passed as void* (NULL = the default stream).
+ *   - layers are numbered from 0; the paper numbers them from 1.
+ *   - one context is used from one host thread at a time.
+ */
+#ifndef SN_H_
+#define SN_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sn_ctx sn_ctx;
+
+enum { SN_F16 = 0, SN_BF16 = 1 };
+enum { SN_ACT_GELU = 0, SN_ACT_SWIGLU = 1 };
+enum { SN_NORM_LN = 0, SN_NORM_RMS = 1 };
+
+enum {
+  SN_OK = 0,
+  SN_E_INVAL = -1,      /* bad argument (null, out of range, unsupported shape)            */
+  SN_E_STATE = -2,      /* call order: e.g. sn_step before sn_place, profile not taken      */
+  SN_E_BUDGET = -3,     /* resident bytes for this interval exceed the HBM budget           */
+  SN_E_INFEASIBLE = -4, /* no interval meets the SLO within capacity: reject (Sec. 4.2/4.5) */
+  SN_E_NOMEM = -5,      /* host or device allocation failed                                 */
+  SN_E_HIP = -6         /* a HIP runtime call failed                                        */
+};
+
+/* Decoder layer shape (Sec. 2.1: all layers share one structure). */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn;
+  int32_t act;        /* SN_ACT_*  : GELU MLP (up, down) or SwiGLU MLP (gate, up, down)   */
+  int32_t norm;       /* SN_NORM_* : LayerNorm (gain, shift) or RMSNorm (gain)            */
+  int32_t rope;       /* 1: rotary embedding on q,k (pairs i, i+head_dim/2)               */
+  int32_t has_bias;   /* 1: every projection has a bias vector                            */
+  int32_t dtype;      /* SN_F16 / SN_BF16: storage of weights, KV cache, hidden in/out    */
+  float norm_eps, rope_theta;
+  int32_t max_batch;  /* most sequences in one iteration                                   */
+  int32_t max_seq;    /* sum of per-sequence KV capacities may not exceed max_batch*max_seq*/
+  int32_t max_tokens; /* most tokens in one iteration (0: max_batch*max_seq)               */
+} sn_model_shape;
+
+/* One iteration's input (Sec. 2.1: prefill processes the whole prompt, decoding one
+ * token per sequence).  Tokens of sequence b are rows tok_start(b)..+n_new[b] of
+ * hidden_in, sequences in order. */
+typedef struct {
+  int32_t batch;
+  int32_t is_prefill;       /* 0: decode (every n_new[b] == 1); 1: prefill / chunk          */
+  const int32_t* n_new;     /* host, [batch]                                                */
+  const void* hidden_in;    /* device, [sum n_new, hidden], shape.dtype                     */
+} sn_batch;
+
+/* KV bookkeeping.  Storage belongs to the context; the caller owns this small struct. */
+typedef struct {
+  int32_t* len;             /* host, [batch]: tokens cached per sequence; advanced by sn_step */
+} sn_kv;
+
+/* Timings of the most recent sn_step (valid once the compute stream has been
+ * synchronised).  All times in nanoseconds from HIP events. */
+typedef struct {
+  int64_t iter_ns;          /* whole iteration on the compute stream                        */
+  int64_t stall_ns;         /* time compute waited at fences (sum over offloaded layers)    */
+  int64_t h2d_ns, h2d_bytes;/* summed duration and bytes of this iteration's prefetches     */
+  int64_t d2h_ns, d2h_bytes;/* write-back copies (prefill); decode writes rows through      */
+  double hidden_fraction;   /* 1 - stall_ns / h2d_ns (1 when nothing is offloaded)          */
+  int32_t interval;         /* N in effect (n_layers+1: nothing offloaded)                  */
+  int32_t n_offloaded;
+  uint64_t resident_bytes;  /* device bytes held for this placement                         */
+  int64_t kernel_ns[8];     /* per kernel class, summed over layers, when kernel timing on  */
+  int32_t kernel_calls[8];
+} sn_step_stats;
+
+/* Kernel classes for sn_step_stats.kernel_ns / sn_set_timing(level 2). */
+enum { SN_K_NORM = 0, SN_K_QKV = 1, SN_K_ROPE_APPEND = 2, SN_K_ATTN = 3, SN_K_OPROJ = 4,
+       SN_K_FFN_UP = 5, SN_K_FFN_DOWN = 6, SN_K_OTHER = 7 };
+
+/* --- life cycle ---------------------------------------------------------------- */
+
+/* Create a context for a model of this shape under an HBM budget (Sec. 4.5: the
+ * maximum interval follows from the GPU's capacity).  hbm_budget_bytes == 0: no cap.
+ * Allocates the pinned host master for all layers' weights and the device workspace.
+ * hip_compute_stream: caller-owned hipStream_t on which sn_step enqueues kernels. */
+int sn_init(sn_ctx** out, const sn_model_shape* shape, uint64_t hbm_budget_bytes,
+            void* hip_compute_stream);
+void sn_destroy(sn_ctx* ctx);
+const char* sn_last_error(const sn_ctx* ctx);
+
+/* --- weights -------------------------------------------------------------------
+ * Caller-side layer blob: the tensors below in this order, 16-bit (shape.dtype),
+ * matrices [out_features, in_features] row-major, each tensor starting on a 256-byte
+ * boundary; tensors that the shape does not have are absent:
+ *   wqkv [(Hq+2Hkv)*d, hidden] (q heads, then k heads, then v heads), bqkv,
+ *   wo [hidden, Hq*d], bo, wg [ffn, hidden] (SwiGLU gate), bg, wu [ffn, hidden], bu,
+ *   wd [hidden, ffn], bd, n1g [hidden], n1b (LayerNorm only), n2g, n2b.
+ * sn_layer_blob_bytes gives the total size.  sn_set_layer_weights copies (and
+ * re-tiles for the matrix cores) into the context's pinned master; host_blob is a
+ * host pointer and may be freed afterwards.  If the layer is GPU resident at the
+ * time, its device copy is refreshed too. */
+uint64_t sn_layer_blob_bytes(const sn_model_shape* shape);
+int sn_set_layer_weights(sn_ctx* ctx, int32_t layer, const void* host_blob, uint64_t bytes);
+
+/* --- placement (Sec. 4.3) ------------------------------------------------------
+ * Apply offloading interval N: layer l is host resident iff (l+1) % N == 0.
+ * N == 0 or N > n_layers: everything GPU resident.  Synchronous; moves weights and
+ * live KV between host and device as needed; its cost is not part of an iteration.
+ * Fails with SN_E_BUDGET when sn_resident_bytes(N) exceeds the budget, unless
+ * enforcement was switched off with sn_set_budget_enforce(ctx, 0). */
+int sn_place(sn_ctx* ctx, int32_t N);
+int sn_set_budget_enforce(sn_ctx* ctx, int32_t on);
+/* Device bytes interval N needs: resident layers' state + two staging slots (if any
+ * layer is offloaded) + workspace. */
+uint64_t sn_resident_bytes(const sn_ctx* ctx, int32_t N);
+/* Largest N whose footprint fits the budget; n_layers+1 = "no offloading fits"
+ * (infinite maximum, Sec. 4.5); 0 = not even N = 1 fits. */
+int32_t sn_max_interval(const sn_ctx* ctx);
+
+/* Pure helpers (host only, no GPU): the placement map and prefetch triggers for
+ * (L, N).  offloaded[l] in {0,1}; trigger[l] = layer at whose start the load of
+ * layer l is issued, or -1 for resident layers.  Both host arrays of length L. */
+int sn_placement(int32_t L, int32_t N, uint8_t* offloaded, int32_t* trigger);
+
+/* --- KV cache ------------------------------------------------------------------
+ * Start a new set of sequences: per-sequence capacities in tokens (host, [batch]);
+ * sum must fit max_batch*max_seq.  All lengths become 0. */
+int sn_kv_reset(sn_ctx* ctx, int32_t batch, const int32_t* capacity);
+
+/* --- one serving iteration (Sec. 4.3, Fig. 7) ----------------------------------
+ * Enqueues the whole layer loop and returns without waiting for the GPU.
+ * hidden_out: device, [sum n_new, hidden], shape.dtype: hidden states after the last
+ * layer.  kv->len[b] must equal the context's own count and is advanced by n_new[b].
+ * Results are valid after the caller synchronises the compute stream. */
+int sn_step(sn_ctx* ctx, const sn_batch* batch, sn_kv* kv, void* hidden_out);
+
+/* timing level: 0 iteration + copies only, 1 also per layer, 2 also per kernel class */
+int sn_set_timing(sn_ctx* ctx, int32_t level);
+/* Waits for the compute and copy streams, then fills *out for the last sn_step. */
+int sn_get_stats(sn_ctx* ctx, sn_step_stats* out);
+/* Per-layer figures of the last sn_step (timing level >= 1): host arrays [n_layers];
+ * stall_ns[l] is 0 for resident layers.  Any pointer may be NULL. */
+int sn_get_layer_times(sn_ctx* ctx, int64_t* compute_ns, int64_t* stall_ns, int64_t* h2d_ns);
+
+/* --- profiler and picker (Sec. 4.4) --------------------------------------------
+ * Runs `reps` iterations of the given kind (prefill of `seq` tokens per sequence, or
+ * one decode step on `seq` cached tokens) on generated inputs under the current
+ * placement and reports per layer the median compute time tc_ns[l] (fence waits
+ * excluded) and the time tx_ns[l] of a solo host-to-device transfer of that layer's
+ * state (weights; plus its KV prefix for decode).  Host arrays [n_layers]; either
+ * may be NULL.  Discards any live KV contents (lengths return to 0). */
+int sn_profile_layers(sn_ctx* ctx, int32_t is_prefill, int32_t batch, int32_t seq, int32_t reps,
+                      int64_t* tc_ns, int64_t* tx_ns);
+
+/* Iteration time (ns) of the Fig. 7 schedule for interval N given per-layer times;
+ * stall_total_ns may be NULL.  Pure, host only. */
+int sn_timeline(int32_t L, const int64_t* tc_ns, const int64_t* tx_ns, int32_t N,
+                int64_t* iter_ns, int64_t* stall_total_ns);
+/* Smallest N in 1..L whose timeline meets slo_ns; L+1 if only the un-offloaded
+ * iteration does; then N must not exceed N_max (Sec. 4.5), else SN_E_INFEASIBLE.
+ * Pure, host only. */
+int sn_pick_interval_from_times(int32_t L, const int64_t* tc_ns, const int64_t* tx_ns,
+                                int64_t slo_ns, int32_t N_max, int32_t* N_out);
+/* Same, using the last sn_profile_layers result and the context's budget. */
+int sn_pick_interval(sn_ctx* ctx, double slo_ms, int32_t* N_out);
+
+/* The analyzer's closed form (Sec. 4.4) for uniform times, reported beside the pick:
+ * L_offload = floor(slo / t_trans); interval = floor(L / (L_offload + 1)) + 1. */
+int32_t sn_paper_rule(int32_t L, int64_t t_trans_ns, int64_t slo_ns);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SN_H_ */

@@ -1,0 +1,75 @@
+/*
+ * sn_kernels.h -- C ABI of the individual layer kernels (gfx950), one entry per step of
+ * the decoder layer (paper Sec. 2.1: attention computations, then MLP computations), so
+ * that each step can be checked against the oracle on its own.  sn_step (sn.h) launches
+ * exactly these kernels.  All pointers are device pointers unless marked host; `stream`
+ * is a hipStream_t passed as void*.  Return value: 0 or a negative SN_E_* code.
+ * dtype: SN_F16 / SN_BF16 for all 16-bit buffers.
+ */
+#ifndef SN_KERNELS_H_
+#define SN_KERNELS_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Host only: re-tile a row-major [N][K] 16-bit matrix (N % 16 == 0, K % 32 == 0) into
+ * the 16x32-tile order the GEMM kernels read: tile (nb, kb) at (nb*K/32 + kb)*512
+ * elements, element (n, k) of the tile at ((n%16) + 16*((k%32)/8))*8 + k%8.
+ * dst_row_block_stride / offset: source block j lands at block j*stride + offset
+ * (2,0 and 2,1 interleave a gate and an up matrix for the SwiGLU epilogue). */
+int sn_k_tile_weights(const void* host_src, void* host_dst, int32_t N, int32_t K,
+                      int32_t dst_row_block_stride, int32_t dst_row_block_offset);
+
+/* out16[t][:] = normalise(x32[t][:]) * gain (+ shift).  is_ln: LayerNorm (biased
+ * variance) else RMSNorm (shift ignored).  x32 fp32 [T][h]; gain/shift 16-bit [h]. */
+int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, const void* shift,
+              void* out16, int32_t T, int32_t h, float eps, void* stream);
+
+/* out = epilogue(X[M][K] * W^T + bias), W tiled as above with N rows, bias 16-bit or NULL.
+ * epilogue 0: 16-bit store; 1: GELU (erf) then 16-bit store; 2: out is the fp32 residual
+ * stream [M][N], updated in place (+=); 3: SwiGLU -- W holds gate and up in alternating
+ * 16-row blocks (N = 2*ffn rows), bias = [gate | up], out16[M][N/2] = silu(g)*u.
+ * path 0: weight-streaming decode kernel (M <= 64); path 1: tiled prefill kernel. */
+int sn_k_gemm(int32_t dtype, int32_t epilogue, int32_t path, const void* W, const void* X,
+              const void* bias, void* out, int32_t M, int32_t N, int32_t K, void* stream);
+
+/* Index arrays shared by the attention-side kernels (device int32):
+ *   len_before[B], n_new[B], tok_start[B], kv_off[B] (token offset of the sequence in the
+ *   KV slice), cap[B]; tok_seq[T], tok_pos[T]; tile_seq[n_qtiles], tile_q0[n_qtiles].
+ * KV slice layout: for sequence b at element offset kv_off[b]*2*Hkv*d:
+ *   [Hkv][2 (K then V)][cap[b]][d], 16-bit. */
+
+/* Rotate q (in place in qkv16 [T][(Hq+2Hkv)*d]) and k by the rotary embedding when
+ * rope != 0 (pairs i, i+d/2; angle tok_pos * inv_freq[i], inv_freq fp32 [d/2]); write the
+ * new k and v rows into kv (and into mirror, a second copy of the slice, if non-NULL). */
+int sn_k_rope_append(int32_t dtype, void* qkv16, const int32_t* tok_seq, const int32_t* tok_pos,
+                     const int32_t* kv_off, const int32_t* cap, void* kv, void* mirror,
+                     const float* inv_freq, int32_t T, int32_t Hq, int32_t Hkv, int32_t d,
+                     int32_t rope, void* stream);
+
+/* One query per sequence (row b of qkv16) over keys 0..len_before[b] (the new row was
+ * appended first).  out16 [B][Hq*d].  splits S >= 1 key ranges; part: fp32 scratch
+ * [B][Hq][S][d+2] (may be NULL when S == 1).  S == 0: the library's own choice for
+ * max_len = max_b(len_before[b]) + 1, which must then be given. */
+int sn_k_attn_decode(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
+                     const int32_t* kv_off, const int32_t* cap, void* out16, float* part, int32_t B,
+                     int32_t Hq, int32_t Hkv, int32_t d, int32_t S, int32_t max_len, void* stream);
+
+/* Causal attention of each sequence's n_new tokens over len_before+n_new keys.
+ * out16 [T][Hq*d]. */
+int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
+                      const int32_t* n_new, const int32_t* tok_start, const int32_t* kv_off,
+                      const int32_t* cap, const int32_t* tile_seq, const int32_t* tile_q0,
+                      void* out16, int32_t n_qtiles, int32_t Hq, int32_t Hkv, int32_t d, void* stream);
+
+/* 16-bit <-> fp32 residual stream conversions at the boundary of an iteration. */
+int sn_k_cast_in(int32_t dtype, const void* in16, void* x32, uint64_t n, void* stream);
+int sn_k_cast_out(int32_t dtype, const void* x32, void* out16, uint64_t n, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SN_KERNELS_H_ */

@@ -107,6 +107,29 @@ def cache_lens(cache) -> List[int]:
 
 
 # ---------------------------------------------------------------------------
+# attention of one sequence's new tokens over its cache
+# ---------------------------------------------------------------------------
+
+def causal_attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, start: int) -> np.ndarray:
+    """q: [n_new, Hq, d] (new token t sits at position start + t); K, V: [len, Hkv, d]
+    with len >= start + n_new.  Token at position p sees keys 0..p; scores are scaled by
+    1/sqrt(d); query head i reads KV head floor(i * Hkv / Hq).  Returns [n_new, Hq, d]."""
+    n_new, Hq, d = q.shape
+    Hkv = K.shape[1]
+    a = np.zeros((n_new, Hq, d))
+    scale = 1.0 / math.sqrt(d)
+    for t in range(n_new):
+        p = start + t
+        for i in range(Hq):
+            g = (i * Hkv) // Hq
+            s = (K[:p + 1, g, :] @ q[t, i, :]) * scale
+            s = s - s.max()
+            e = np.exp(s)
+            a[t, i, :] = (e / e.sum()) @ V[:p + 1, g, :]
+    return a
+
+
+# ---------------------------------------------------------------------------
 # one layer, one sequence
 # ---------------------------------------------------------------------------
 
@@ -145,17 +168,8 @@ def layer_forward(shape: dict, w: Dict[str, np.ndarray], x: np.ndarray, kv: dict
     kv["v"] = np.concatenate([kv["v"], round_to_storage(v, kv_dtype)], axis=0)
     K, V = kv["k"], kv["v"]
 
-    # 5. causal softmax attention; query head i reads KV head floor(i * Hkv / Hq)
-    a = np.zeros((n_new, Hq, d))
-    scale = 1.0 / math.sqrt(d)
-    for t in range(n_new):
-        p = start + t                                   # keys 0..p are visible
-        for i in range(Hq):
-            g = (i * Hkv) // Hq
-            s = (K[:p + 1, g, :] @ q[t, i, :]) * scale
-            s = s - s.max()
-            e = np.exp(s)
-            a[t, i, :] = (e / e.sum()) @ V[:p + 1, g, :]
+    # 5. causal softmax attention over the cached keys
+    a = causal_attention(q, K, V, start)
 
     # 6. output projection + residual
     o = a.reshape(n_new, Hq * d) @ w["wo"].T

@@ -1,0 +1,72 @@
+// Shared device-side helpers for the gfx950 kernels: 16-bit storage types, wave64
+// reductions, vector typedefs for the matrix-core builtins.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sn {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+// ---- 16-bit storage <-> fp32 --------------------------------------------------
+struct F16 {};
+struct BF16 {};
+
+template <class T> __device__ __forceinline__ float to_f32(uint16_t b);
+template <> __device__ __forceinline__ float to_f32<F16>(uint16_t b) {
+  return (float)__builtin_bit_cast(_Float16, b);
+}
+template <> __device__ __forceinline__ float to_f32<BF16>(uint16_t b) {
+  return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+template <class T> __device__ __forceinline__ uint16_t from_f32(float v);
+template <> __device__ __forceinline__ uint16_t from_f32<F16>(float v) {
+  return __builtin_bit_cast(uint16_t, (_Float16)v);   // round to nearest even
+}
+template <> __device__ __forceinline__ uint16_t from_f32<BF16>(float v) {
+  uint32_t u = __builtin_bit_cast(uint32_t, v);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                                            // nearest even
+  return (uint16_t)(u >> 16);
+}
+
+// ---- matrix-core step: D[16x16] += A[16x32] * B[32x16], fp32 accumulate ---------
+// Lane l supplies A[row l%16][k = 8*(l/16) .. +8] and B[k = 8*(l/16) .. +8][col l%16];
+// it receives D[rows 4*(l/16) .. +4][col l%16].
+template <class T> __device__ __forceinline__ f32x4 mma16x16x32(u16x8 a, u16x8 b, f32x4 c);
+template <> __device__ __forceinline__ f32x4 mma16x16x32<F16>(u16x8 a, u16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x4 mma16x16x32<BF16>(u16x8 a, u16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// ---- wave64 reductions ----------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+__device__ __forceinline__ float gelu_erf(float x) {
+  return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
+}
+__device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x)); }
+
+}  // namespace sn

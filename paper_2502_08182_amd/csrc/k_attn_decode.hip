@@ -1,0 +1,224 @@
+// Decode attention: one query per sequence against its cached keys and values.
+//
+// Memory-bound (paper Sec. 2.1, decoding): every cached K and V element is read once.
+// The KV slice keeps, for each (sequence, KV head), K rows [cap][d] and then V rows
+// [cap][d], so a workgroup assigned to one (sequence, KV head, key range) streams two
+// contiguous regions.  Lanes are laid along the head dimension: d/8 lanes share one key
+// row (16 bytes each), so one wavefront load covers 64/(d/8) consecutive keys = 1 KiB.
+// The dot product is finished with xor-shuffles inside those d/8 lanes; every
+// (wavefront, key slot) keeps its own running softmax (max, sum, weighted V), merged
+// at the end by shuffles, then across the 4 wavefronts through LDS, then across key
+// ranges by a second small kernel.  All merges run in a fixed order.
+#include "common.h"
+#include "kernels.h"
+
+namespace sn {
+
+constexpr float kNegBig = -1.0e30f;
+
+struct SoftAcc {
+  float m, l, a[8];
+};
+
+__device__ __forceinline__ void merge_into(float& m, float& l, float (&a)[8], float m2, float l2,
+                                           const float (&a2)[8]) {
+  const float mn = fmaxf(m, m2);
+  const float c1 = __expf(m - mn), c2 = __expf(m2 - mn);
+  l = l * c1 + l2 * c2;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a[e] = a[e] * c1 + a2[e] * c2;
+  m = mn;
+}
+
+template <class T, int D, int G>
+__global__ __launch_bounds__(256) void attn_decode_kernel(
+    const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
+    const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ out,
+    float* __restrict__ part, int Hq, int Hkv, int S) {
+  constexpr int LPK = D / 8;          // lanes per key row
+  constexpr int KPW = 64 / LPK;       // keys per wavefront load
+  __shared__ float lds[4][G][LPK][10];
+
+  const int b = blockIdx.x / Hkv;
+  const int hk = blockIdx.x % Hkv;
+  const int split = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int slot = lane / LPK, c = lane % LPK;
+
+  const int len = len_before[b] + 1;
+  const int chunk = (len + S - 1) / S;
+  const int j0 = split * chunk;
+  const int j1 = min(len, j0 + chunk);
+
+  const int qkv_ld = (Hq + 2 * Hkv) * D;
+  const float scale = rsqrtf((float)D);
+  float q[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const u16x8 v = *reinterpret_cast<const u16x8*>(qkv + (size_t)b * qkv_ld + (size_t)(hk * G + g) * D + c * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[g][e] = to_f32<T>(v[e]) * scale;
+  }
+
+  const int cp = cap[b];
+  const uint16_t* Kb = kv + (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D + c * 8;
+  const uint16_t* Vb = Kb + (size_t)cp * D;
+
+  float m[G], l[G], acc[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = kNegBig;
+    l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+  }
+
+  for (int jb = j0 + wave * KPW; jb < j1; jb += 4 * KPW) {
+    const int j = jb + slot;
+    const bool ok = j < j1;
+    const int jc = ok ? j : j1 - 1;                    // clamped: loads stay inside the cached rows
+    const u16x8 kr = *reinterpret_cast<const u16x8*>(Kb + (size_t)jc * D);
+    const u16x8 vr = *reinterpret_cast<const u16x8*>(Vb + (size_t)jc * D);
+    float kf[8], vf[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      kf[e] = to_f32<T>(kr[e]);
+      vf[e] = to_f32<T>(vr[e]);
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += q[g][e] * kf[e];
+#pragma unroll
+      for (int o = LPK / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      if (ok) {
+        const float mn = fmaxf(m[g], s);
+        const float corr = __expf(m[g] - mn);
+        const float p = __expf(s - mn);
+        l[g] = l[g] * corr + p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vf[e];
+        m[g] = mn;
+      }
+    }
+  }
+
+  // merge the key slots of this wavefront (lanes that hold the same d-chunk)
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int o = LPK; o < 64; o <<= 1) {
+      const float m2 = __shfl_xor(m[g], o, 64);
+      const float l2 = __shfl_xor(l[g], o, 64);
+      float a2[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a2[e] = __shfl_xor(acc[g][e], o, 64);
+      merge_into(m[g], l[g], acc[g], m2, l2, a2);
+    }
+    if (slot == 0) {
+      lds[wave][g][c][0] = m[g];
+      lds[wave][g][c][1] = l[g];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) lds[wave][g][c][2 + e] = acc[g][e];
+    }
+  }
+  __syncthreads();
+
+  // merge the 4 wavefronts: thread (g, c)
+  if (threadIdx.x < G * LPK) {
+    const int g = threadIdx.x / LPK, cc = threadIdx.x % LPK;
+    float mm = lds[0][g][cc][0], ll = lds[0][g][cc][1], aa[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) aa[e] = lds[0][g][cc][2 + e];
+    for (int w = 1; w < 4; ++w) {
+      float a2[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a2[e] = lds[w][g][cc][2 + e];
+      merge_into(mm, ll, aa, lds[w][g][cc][0], lds[w][g][cc][1], a2);
+    }
+    const int hq = hk * G + g;
+    if (S == 1) {
+      const float inv = 1.0f / ll;
+      u16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = from_f32<T>(aa[e] * inv);
+      *reinterpret_cast<u16x8*>(out + ((size_t)b * Hq + hq) * D + cc * 8) = o;
+    } else {
+      float* p = part + (((size_t)b * Hq + hq) * S + split) * (D + 2);
+      if (cc == 0) {
+        p[0] = mm;
+        p[1] = ll;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p[2 + cc * 8 + e] = aa[e];
+    }
+  }
+}
+
+// Merge the S key-range partials of one (sequence, query head); thread = output element.
+template <class T, int D>
+__global__ void attn_combine_kernel(const float* __restrict__ part, uint16_t* __restrict__ out, int S) {
+  const float* p = part + (size_t)blockIdx.x * S * (D + 2);
+  const int e = threadIdx.x;
+  float mx = kNegBig;
+  for (int s = 0; s < S; ++s) mx = fmaxf(mx, p[(size_t)s * (D + 2)]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float w = __expf(p[(size_t)s * (D + 2)] - mx);
+    den += w * p[(size_t)s * (D + 2) + 1];
+    num += w * p[(size_t)s * (D + 2) + 2 + e];
+  }
+  out[(size_t)blockIdx.x * D + e] = from_f32<T>(num / den);
+}
+
+// Key-range splits: aim for ~512 workgroups, at least 128 keys per split, at most 16.
+int attn_decode_splits(int B, int Hkv, int max_len) {
+  const int pairs = B * Hkv;
+  int S = (512 + pairs - 1) / pairs;
+  const int by_len = (max_len + 127) / 128;
+  if (S > by_len) S = by_len;
+  if (S > 16) S = 16;
+  if (S < 1) S = 1;
+  return S;
+}
+
+template <class T, int D>
+static hipError_t launch_d(const uint16_t* qkv, const uint16_t* kv, const StepIndex& ix, uint16_t* out,
+                           float* part, int B, int Hq, int Hkv, int S, hipStream_t st) {
+  dim3 grid(B * Hkv, S), block(256);
+  const int G = Hq / Hkv;
+#define SN_LAUNCH_G(GV)                                                                                   \
+  hipLaunchKernelGGL((attn_decode_kernel<T, D, GV>), grid, block, 0, st, qkv, kv, ix.len_before, ix.kv_off, \
+                     ix.cap, out, part, Hq, Hkv, S)
+  switch (G) {
+    case 1: SN_LAUNCH_G(1); break;
+    case 2: SN_LAUNCH_G(2); break;
+    case 4: SN_LAUNCH_G(4); break;
+    case 8: SN_LAUNCH_G(8); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef SN_LAUNCH_G
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || S == 1) return e;
+  hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3(B * Hq), dim3(D), 0, st, part, out, S);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_decode(int dtype, const void* qkv16, const void* kv, const StepIndex& ix, void* out16,
+                              float* part, int B, int Hq, int Hkv, int d, int S, hipStream_t st) {
+  if (B <= 0) return hipSuccess;
+  const uint16_t* q = (const uint16_t*)qkv16;
+  const uint16_t* k = (const uint16_t*)kv;
+  uint16_t* o = (uint16_t*)out16;
+  if (dtype == 0) {
+    if (d == 64) return launch_d<F16, 64>(q, k, ix, o, part, B, Hq, Hkv, S, st);
+    if (d == 128) return launch_d<F16, 128>(q, k, ix, o, part, B, Hq, Hkv, S, st);
+  } else {
+    if (d == 64) return launch_d<BF16, 64>(q, k, ix, o, part, B, Hq, Hkv, S, st);
+    if (d == 128) return launch_d<BF16, 128>(q, k, ix, o, part, B, Hq, Hkv, S, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace sn

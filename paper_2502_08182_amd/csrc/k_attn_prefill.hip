@@ -1,0 +1,165 @@
+// Prefill attention: causal attention of a sequence's new tokens over its cached and
+// new keys, on the matrix cores (prefill is the computation-intensive phase, paper
+// Sec. 2.1).  One 256-thread workgroup handles 64 query rows of one (sequence, query
+// head); each wavefront owns 16 of them.  Keys are consumed 32 at a time:
+//
+//   S^T = K Q^T   A operand = 16 key rows x 32 of d (read from the KV slice),
+//                 B operand = Q^T (this wavefront's 16 queries), result D[key][query].
+//                 The 16 rows of the two key sub-tiles are chosen as keys
+//                 8*(r/4) + 4*t + r%4 so that a lane ends up holding the scores of
+//                 8 *consecutive* keys (8*(lane/16) .. +8) for query lane%16 --
+//                 exactly the B-operand layout the next product needs.
+//   O^T = V^T P^T A operand = V^T (16 of d x 32 keys) read from an LDS tile that was
+//                 transposed while being staged, B operand = P^T from registers,
+//                 result D[d][query]: the query index stays on lane%16, so the online
+//                 softmax rescale is lane-local.
+#include "common.h"
+#include "kernels.h"
+
+namespace sn {
+
+constexpr float kMasked = -1.0e30f;
+
+template <class T, int D>
+__global__ __launch_bounds__(256) void attn_prefill_kernel(
+    const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
+    const int32_t* __restrict__ n_new, const int32_t* __restrict__ tok_start, const int32_t* __restrict__ kv_off,
+    const int32_t* __restrict__ cap, const int32_t* __restrict__ tile_seq, const int32_t* __restrict__ tile_q0,
+    uint16_t* __restrict__ out, int Hq, int Hkv) {
+  constexpr int KT = 32;              // keys per step
+  constexpr int LD = 40;              // LDS row stride (elements) of the transposed V tile: 80 B, 16 B aligned
+  constexpr int DK = D / 32;          // k-steps over the head dimension
+  constexpr int DT = D / 16;          // 16-wide output tiles over the head dimension
+  __shared__ __attribute__((aligned(16))) uint16_t vt[D * LD];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int b = tile_seq[blockIdx.x];
+  const int q0 = tile_q0[blockIdx.x];
+  const int hq = blockIdx.y;
+  const int hk = hq / (Hq / Hkv);
+  const int nn = n_new[b];
+  const int lb = len_before[b];
+  const int total = lb + nn;                             // keys that exist after the append
+  const int kend = lb + min(nn, q0 + 64);                // keys any query of this tile may see
+
+  const int qi = q0 + wave * 16 + r;                     // this lane's query (new-token index)
+  const bool qok = qi < nn;
+  const int qpos = lb + qi;
+  const int qkv_ld = (Hq + 2 * Hkv) * D;
+
+  u16x8 qf[DK];
+#pragma unroll
+  for (int kk = 0; kk < DK; ++kk) {
+    qf[kk] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    if (qok)
+      qf[kk] = *reinterpret_cast<const u16x8*>(qkv + (size_t)(tok_start[b] + qi) * qkv_ld + (size_t)hq * D +
+                                               kk * 32 + g * 8);
+  }
+
+  const int cp = cap[b];
+  const uint16_t* Kb = kv + (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D;
+  const uint16_t* Vb = Kb + (size_t)cp * D;
+  const float scale = rsqrtf((float)D);
+
+  float m = kMasked, l = 0.f;
+  f32x4 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int j0 = 0; j0 < kend; j0 += KT) {
+    // ---- stage V[j0..j0+32) transposed into LDS: vt[dcol][key] ----
+    constexpr int CHUNKS = KT * D / 8;                   // 16-byte pieces in the tile
+#pragma unroll
+    for (int cid = threadIdx.x; cid < CHUNKS; cid += 256) {
+      const int key = cid / (D / 8), dc = cid % (D / 8);
+      u16x8 v = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      if (j0 + key < total) v = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + key) * D + dc * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vt[(dc * 8 + e) * LD + key] = v[e];
+    }
+    __syncthreads();
+
+    // ---- scores of 32 keys for this wavefront's 16 queries ----
+    f32x4 st[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      st[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      int key = j0 + 8 * (r >> 2) + 4 * t + (r & 3);
+      key = min(key, total - 1);                         // stay inside the cached rows; masked below
+      const uint16_t* kp = Kb + (size_t)key * D + g * 8;
+#pragma unroll
+      for (int kk = 0; kk < DK; ++kk) {
+        const u16x8 kf = *reinterpret_cast<const u16x8*>(kp + kk * 32);
+        st[t] = mma16x16x32<T>(kf, qf[kk], st[t]);
+      }
+    }
+    // lane now holds scores of keys j0 + 8g + e (e = 4t + i) for query lane%16
+    float s[8];
+    float mx = kMasked;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int key = j0 + 8 * g + e;
+      const bool ok = qok && key <= qpos;
+      s[e] = ok ? st[e >> 2][e & 3] * scale : kMasked;
+      mx = fmaxf(mx, s[e]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx);
+    const float corr = __expf(m - mn);
+    float rs = 0.f;
+    u16x8 pb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float p = s[e] > 0.5f * kMasked ? __expf(s[e] - mn) : 0.f;
+      rs += p;
+      pb[e] = from_f32<T>(p);
+    }
+    l = l * corr + rs;                                   // per-lane partial; lanes of a query are summed at the end
+    m = mn;
+
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const u16x8 vf = *reinterpret_cast<const u16x8*>(&vt[(dt * 16 + r) * LD + g * 8]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[dt][i] *= corr;
+      o[dt] = mma16x16x32<T>(vf, pb, o[dt]);
+    }
+    __syncthreads();
+  }
+
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  if (qok) {
+    const float inv = 1.0f / l;
+    uint16_t* op = out + (size_t)(tok_start[b] + qi) * Hq * D + (size_t)hq * D + g * 4;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      u16x4 w;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w[i] = from_f32<T>(o[dt][i] * inv);
+      *reinterpret_cast<u16x4*>(op + dt * 16) = w;
+    }
+  }
+}
+
+hipError_t launch_attn_prefill(int dtype, const void* qkv16, const void* kv, const StepIndex& ix, void* out16,
+                               int n_qtiles, int Hq, int Hkv, int d, hipStream_t st) {
+  if (n_qtiles <= 0) return hipSuccess;
+  dim3 grid(n_qtiles, Hq), block(256);
+#define SN_LAUNCH(TT, DD)                                                                                    \
+  hipLaunchKernelGGL((attn_prefill_kernel<TT, DD>), grid, block, 0, st, (const uint16_t*)qkv16,               \
+                     (const uint16_t*)kv, ix.len_before, ix.n_new, ix.tok_start, ix.kv_off, ix.cap, ix.tile_seq, \
+                     ix.tile_q0, (uint16_t*)out16, Hq, Hkv)
+  if (dtype == 0 && d == 64) SN_LAUNCH(F16, 64);
+  else if (dtype == 0 && d == 128) SN_LAUNCH(F16, 128);
+  else if (dtype == 1 && d == 64) SN_LAUNCH(BF16, 64);
+  else if (dtype == 1 && d == 128) SN_LAUNCH(BF16, 128);
+  else return hipErrorInvalidValue;
+#undef SN_LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace sn

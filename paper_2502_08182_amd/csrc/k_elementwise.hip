@@ -1,0 +1,175 @@
+// Small bandwidth-trivial kernels of the layer: casts between the 16-bit boundary
+// type and the fp32 residual stream, the two normalisations, rotary embedding with
+// the KV-cache append, and a hash fill used by the profiler for generated inputs.
+#include "common.h"
+#include "kernels.h"
+
+namespace sn {
+
+#define SN_DISPATCH_T(dtype, ...)                   \
+  do {                                              \
+    if ((dtype) == 0) { using T = F16; __VA_ARGS__; } \
+    else { using T = BF16; __VA_ARGS__; }           \
+  } while (0)
+
+// ---------------------------------------------------------------------------------
+template <class T>
+__global__ void cast_in_kernel(const uint16_t* __restrict__ in, float* __restrict__ x, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    x[i] = to_f32<T>(in[i]);
+}
+template <class T>
+__global__ void cast_out_kernel(const float* __restrict__ x, uint16_t* __restrict__ out, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    out[i] = from_f32<T>(x[i]);
+}
+// Values in [-1, 1) from an integer hash of the element index (generated profiler inputs).
+template <class T>
+__global__ void fill_hash_kernel(uint16_t* __restrict__ out, size_t n, uint32_t seed) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    uint32_t v = (uint32_t)i * 2654435761u + seed;
+    v ^= v >> 16; v *= 0x7feb352du; v ^= v >> 15; v *= 0x846ca68bu; v ^= v >> 16;
+    out[i] = from_f32<T>((float)(v >> 8) * (1.0f / 8388608.0f) - 1.0f);
+  }
+}
+
+static inline int grid_for(size_t n, int block) {
+  size_t g = (n + block - 1) / block;
+  return (int)(g < 1 ? 1 : (g > 4096 ? 4096 : g));
+}
+
+hipError_t launch_cast_in(int dtype, const void* in16, float* x32, size_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  SN_DISPATCH_T(dtype, hipLaunchKernelGGL(cast_in_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
+                                          (const uint16_t*)in16, x32, n));
+  return hipGetLastError();
+}
+hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  SN_DISPATCH_T(dtype, hipLaunchKernelGGL(cast_out_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
+                                          x32, (uint16_t*)out16, n));
+  return hipGetLastError();
+}
+hipError_t launch_fill_hash(int dtype, void* out16, size_t n, uint32_t seed, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  SN_DISPATCH_T(dtype, hipLaunchKernelGGL(fill_hash_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
+                                          (uint16_t*)out16, n, seed));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Normalisation over the hidden dimension: one 256-thread workgroup per token row,
+// fp32 statistics, 16-bit output.  LayerNorm uses the two-pass (centred) variance.
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();                 // red may still be read from a previous call
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+template <class T, bool LN>
+__global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x,
+                                                   const uint16_t* __restrict__ gain,
+                                                   const uint16_t* __restrict__ shift,
+                                                   uint16_t* __restrict__ u, int h, float eps) {
+  __shared__ float red[4];
+  const float* row = x + (size_t)blockIdx.x * h;
+  uint16_t* out = u + (size_t)blockIdx.x * h;
+  const float inv_h = 1.0f / (float)h;
+  float mu = 0.f;
+  if (LN) {
+    float s = 0.f;
+    for (int i = threadIdx.x; i < h; i += 256) s += row[i];
+    mu = block_sum_256(s, red) * inv_h;
+  }
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < h; i += 256) {
+    const float c = row[i] - mu;
+    ss += c * c;
+  }
+  const float rstd = rsqrtf(block_sum_256(ss, red) * inv_h + eps);
+  for (int i = threadIdx.x; i < h; i += 256) {
+    float v = (row[i] - mu) * rstd * to_f32<T>(gain[i]);
+    if (LN) v += to_f32<T>(shift[i]);
+    out[i] = from_f32<T>(v);
+  }
+}
+
+hipError_t launch_norm(int dtype, int is_ln, const float* x32, const void* gain, const void* shift,
+                       void* u16, int Tn, int h, float eps, hipStream_t st) {
+  if (Tn == 0) return hipSuccess;
+  SN_DISPATCH_T(dtype, {
+    if (is_ln)
+      hipLaunchKernelGGL((norm_kernel<T, true>), dim3(Tn), dim3(256), 0, st, x32, (const uint16_t*)gain,
+                         (const uint16_t*)shift, (uint16_t*)u16, h, eps);
+    else
+      hipLaunchKernelGGL((norm_kernel<T, false>), dim3(Tn), dim3(256), 0, st, x32, (const uint16_t*)gain,
+                         (const uint16_t*)nullptr, (uint16_t*)u16, h, eps);
+  });
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Rotary embedding (pairs i, i + d/2; angle = position * inv_freq[i]) on q and k, and
+// append of the new k, v rows to the KV slice.  One thread per (token, head slot, pair).
+template <class T>
+__global__ __launch_bounds__(256) void rope_append_kernel(
+    uint16_t* __restrict__ qkv, const int32_t* __restrict__ tok_seq, const int32_t* __restrict__ tok_pos,
+    const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ kv,
+    uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int Tn, int Hq, int Hkv, int d,
+    int rope) {
+  const int half = d >> 1;
+  const int slots = Hq + 2 * Hkv;
+  const size_t total = (size_t)Tn * slots * half;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int i = (int)(idx % half);
+  const int hs = (int)((idx / half) % slots);
+  const int t = (int)(idx / ((size_t)half * slots));
+  uint16_t* row = qkv + ((size_t)t * slots + hs) * d;
+  float a = to_f32<T>(row[i]), b = to_f32<T>(row[i + half]);
+  const int pos = tok_pos[t];
+  if (rope && hs < Hq + Hkv) {
+    float sn_, cs_;
+    sincosf((float)pos * inv_freq[i], &sn_, &cs_);
+    const float ra = a * cs_ - b * sn_;
+    const float rb = a * sn_ + b * cs_;
+    a = ra;
+    b = rb;
+  }
+  const uint16_t oa = from_f32<T>(a), ob = from_f32<T>(b);
+  if (hs < Hq) {
+    if (rope) {
+      row[i] = oa;
+      row[i + half] = ob;
+    }
+    return;
+  }
+  const int s = tok_seq[t];
+  const int c = cap[s];
+  const bool is_v = hs >= Hq + Hkv;
+  const int g = is_v ? hs - Hq - Hkv : hs - Hq;
+  const size_t off = (size_t)kv_off[s] * 2 * Hkv * d + ((size_t)(g * 2 + (is_v ? 1 : 0)) * c + pos) * d;
+  kv[off + i] = oa;
+  kv[off + i + half] = ob;
+  if (mirror) {
+    mirror[off + i] = oa;
+    mirror[off + i + half] = ob;
+  }
+}
+
+hipError_t launch_rope_append(int dtype, void* qkv16, const StepIndex& ix, void* kv, void* mirror,
+                              const float* inv_freq, int Tn, int Hq, int Hkv, int d, int rope,
+                              hipStream_t st) {
+  const size_t total = (size_t)Tn * (Hq + 2 * Hkv) * (d / 2);
+  if (total == 0) return hipSuccess;
+  const unsigned grid = (unsigned)((total + 255) / 256);
+  SN_DISPATCH_T(dtype, hipLaunchKernelGGL(rope_append_kernel<T>, dim3(grid), dim3(256), 0, st,
+                                          (uint16_t*)qkv16, ix.tok_seq, ix.tok_pos, ix.kv_off, ix.cap,
+                                          (uint16_t*)kv, (uint16_t*)mirror, inv_freq, Tn, Hq, Hkv, d, rope));
+  return hipGetLastError();
+}
+
+}  // namespace sn

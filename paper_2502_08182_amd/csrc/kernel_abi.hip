@@ -1,0 +1,94 @@
+// C ABI of the individual layer kernels (include/sn_kernels.h): argument checks, then
+// the same launchers sn_step uses.
+#include <hip/hip_runtime.h>
+
+#include "../../include/sn.h"
+#include "../../include/sn_kernels.h"
+#include "kernels.h"
+#include "layout.h"
+
+using namespace sn;
+
+static int rc_of(hipError_t e) { return e == hipSuccess ? SN_OK : (e == hipErrorInvalidValue ? SN_E_INVAL : SN_E_HIP); }
+static bool bad_dtype(int d) { return d != SN_F16 && d != SN_BF16; }
+
+extern "C" int sn_k_tile_weights(const void* src, void* dst, int32_t N, int32_t K, int32_t stride, int32_t offset) {
+  if (!src || !dst || N < 16 || K < 32 || N % 16 || K % 32 || stride < 1 || offset < 0 || offset >= stride)
+    return SN_E_INVAL;
+  tile_matrix(static_cast<uint16_t*>(dst), static_cast<const uint16_t*>(src), N, K, stride, offset);
+  return SN_OK;
+}
+
+extern "C" int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, const void* shift,
+                         void* out16, int32_t T, int32_t h, float eps, void* stream) {
+  if (bad_dtype(dtype) || !x32 || !gain || !out16 || T < 0 || h < 1 || (is_ln && !shift)) return SN_E_INVAL;
+  return rc_of(launch_norm(dtype, is_ln, (const float*)x32, gain, shift, out16, T, h, eps, (hipStream_t)stream));
+}
+
+extern "C" int sn_k_gemm(int32_t dtype, int32_t epi, int32_t path, const void* W, const void* X, const void* bias,
+                         void* out, int32_t M, int32_t N, int32_t K, void* stream) {
+  if (bad_dtype(dtype) || !W || !X || !out || M < 0 || N < 16 || K < 32 || epi < 0 || epi > 3) return SN_E_INVAL;
+  if (path == 0) return rc_of(launch_gemm_skinny(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream));
+  if (path == 1) return rc_of(launch_gemm_tile(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream));
+  return SN_E_INVAL;
+}
+
+extern "C" int sn_k_rope_append(int32_t dtype, void* qkv16, const int32_t* tok_seq, const int32_t* tok_pos,
+                                const int32_t* kv_off, const int32_t* cap, void* kv, void* mirror,
+                                const float* inv_freq, int32_t T, int32_t Hq, int32_t Hkv, int32_t d, int32_t rope,
+                                void* stream) {
+  if (bad_dtype(dtype) || !qkv16 || !tok_seq || !tok_pos || !kv_off || !cap || !kv || (rope && !inv_freq) ||
+      T < 0 || Hq < 1 || Hkv < 1 || (d != 64 && d != 128))
+    return SN_E_INVAL;
+  StepIndex ix{};
+  ix.tok_seq = tok_seq;
+  ix.tok_pos = tok_pos;
+  ix.kv_off = kv_off;
+  ix.cap = cap;
+  return rc_of(launch_rope_append(dtype, qkv16, ix, kv, mirror, inv_freq, T, Hq, Hkv, d, rope, (hipStream_t)stream));
+}
+
+extern "C" int sn_k_attn_decode(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
+                                const int32_t* kv_off, const int32_t* cap, void* out16, float* part, int32_t B,
+                                int32_t Hq, int32_t Hkv, int32_t d, int32_t S, int32_t max_len, void* stream) {
+  if (bad_dtype(dtype) || !qkv16 || !kv || !len_before || !kv_off || !cap || !out16 || B < 0 || Hq < 1 || Hkv < 1 ||
+      Hq % Hkv || (d != 64 && d != 128) || S < 0 || S > 16)
+    return SN_E_INVAL;
+  if (S == 0) {
+    if (max_len < 1) return SN_E_INVAL;
+    S = attn_decode_splits(B, Hkv, max_len);
+  }
+  if (S > 1 && !part) return SN_E_INVAL;
+  StepIndex ix{};
+  ix.len_before = len_before;
+  ix.kv_off = kv_off;
+  ix.cap = cap;
+  return rc_of(launch_attn_decode(dtype, qkv16, kv, ix, out16, part, B, Hq, Hkv, d, S, (hipStream_t)stream));
+}
+
+extern "C" int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
+                                 const int32_t* n_new, const int32_t* tok_start, const int32_t* kv_off,
+                                 const int32_t* cap, const int32_t* tile_seq, const int32_t* tile_q0, void* out16,
+                                 int32_t n_qtiles, int32_t Hq, int32_t Hkv, int32_t d, void* stream) {
+  if (bad_dtype(dtype) || !qkv16 || !kv || !len_before || !n_new || !tok_start || !kv_off || !cap || !tile_seq ||
+      !tile_q0 || !out16 || n_qtiles < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv || (d != 64 && d != 128))
+    return SN_E_INVAL;
+  StepIndex ix{};
+  ix.len_before = len_before;
+  ix.n_new = n_new;
+  ix.tok_start = tok_start;
+  ix.kv_off = kv_off;
+  ix.cap = cap;
+  ix.tile_seq = tile_seq;
+  ix.tile_q0 = tile_q0;
+  return rc_of(launch_attn_prefill(dtype, qkv16, kv, ix, out16, n_qtiles, Hq, Hkv, d, (hipStream_t)stream));
+}
+
+extern "C" int sn_k_cast_in(int32_t dtype, const void* in16, void* x32, uint64_t n, void* stream) {
+  if (bad_dtype(dtype) || !in16 || !x32) return SN_E_INVAL;
+  return rc_of(launch_cast_in(dtype, in16, (float*)x32, n, (hipStream_t)stream));
+}
+extern "C" int sn_k_cast_out(int32_t dtype, const void* x32, void* out16, uint64_t n, void* stream) {
+  if (bad_dtype(dtype) || !x32 || !out16) return SN_E_INVAL;
+  return rc_of(launch_cast_out(dtype, (const float*)x32, out16, n, (hipStream_t)stream));
+}

@@ -1,0 +1,64 @@
+// Host-callable launchers of the gfx950 layer kernels.  Every launcher enqueues on
+// the given stream and returns the hipError_t of the launch.  Launch geometry depends
+// only on sizes, never on pointer values, so the same inputs give the same bits
+// whether a layer's state sits in a resident buffer or in a staging slot.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sn {
+
+enum Epilogue {
+  EPI_STORE16 = 0,   // out16[m][n] = acc + bias
+  EPI_GELU16 = 1,    // out16[m][n] = gelu(acc + bias)
+  EPI_RESID32 = 2,   // x32[m][n] += acc + bias
+  EPI_SWIGLU16 = 3   // weights hold gate/up in alternating 16-row blocks: out16[m][n] = silu(g)*u
+};
+
+// Per-iteration index arrays (device int32), built on the host by sn_step.
+struct StepIndex {
+  const int32_t* len_before;  // [B] tokens cached before this iteration
+  const int32_t* n_new;       // [B]
+  const int32_t* tok_start;   // [B] first row of the sequence in the token-major buffers
+  const int32_t* kv_off;      // [B] token offset of the sequence inside a layer's KV slice
+  const int32_t* cap;         // [B] KV capacity of the sequence (tokens)
+  const int32_t* tok_seq;     // [T] sequence of each token row
+  const int32_t* tok_pos;     // [T] absolute position of each token row
+  const int32_t* tile_seq;    // [n_qtiles] prefill attention: sequence of each 64-row query tile
+  const int32_t* tile_q0;     // [n_qtiles] first new-token index of the tile inside its sequence
+};
+
+hipError_t launch_cast_in(int dtype, const void* in16, float* x32, size_t n, hipStream_t st);
+hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, hipStream_t st);
+hipError_t launch_fill_hash(int dtype, void* out16, size_t n, uint32_t seed, hipStream_t st);
+
+// u16[t][:] = norm(x32[t][:]) * gain (+ shift); shift == nullptr for RMSNorm.
+hipError_t launch_norm(int dtype, int is_ln, const float* x32, const void* gain, const void* shift,
+                       void* u16, int T, int h, float eps, hipStream_t st);
+
+// out = epilogue(X[M][K] * W^T), W tiled [N/16][K/32][64][8].  N counts weight rows
+// (2*ffn for EPI_SWIGLU16, whose output has N/2 columns).  Decode path: M <= 64.
+hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, const void* bias,
+                              void* out, int M, int N, int K, hipStream_t st);
+// Prefill path: any M.
+hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, const void* bias,
+                            void* out, int M, int N, int K, hipStream_t st);
+
+// Rotates q (in place) and k, and appends k, v rows to the layer's KV slice
+// ([seq][Hkv][K|V][cap][d]); mirror (may be null) is a second copy of the slice that
+// receives the same rows (host-resident master of an offloaded layer).
+hipError_t launch_rope_append(int dtype, void* qkv16, const StepIndex& ix, void* kv, void* mirror,
+                              const float* inv_freq, int T, int Hq, int Hkv, int d, int rope,
+                              hipStream_t st);
+
+// One query per sequence over len_before+1 cached keys.  part: fp32 scratch for
+// split partials, [B][Hq][S][d+2].
+int attn_decode_splits(int B, int Hkv, int max_len);
+hipError_t launch_attn_decode(int dtype, const void* qkv16, const void* kv, const StepIndex& ix,
+                              void* out16, float* part, int B, int Hq, int Hkv, int d, int S,
+                              hipStream_t st);
+// Causal attention of each sequence's new tokens over its cached + new keys.
+hipError_t launch_attn_prefill(int dtype, const void* qkv16, const void* kv, const StepIndex& ix,
+                               void* out16, int n_qtiles, int Hq, int Hkv, int d, hipStream_t st);
+
+}  // namespace sn

@@ -1,0 +1,864 @@
+// The runtime memory manager and the C ABI (include/sn.h).
+//
+// Paper Sec. 4.3 / Fig. 7: compute proceeds layer by layer on one stream; the state of
+// each offloaded layer is loaded on a copy stream, the load being issued when compute
+// reaches the first layer of the group, and a synchronisation point precedes the
+// offloaded layer; afterwards its mutated state returns to the host.  Here:
+//   * every layer has a pinned host master of its (re-tiled) weights; offloaded layers
+//     also keep their KV slice in pinned host memory;
+//   * two device staging slots, used alternately (offloaded layer k -> slot k mod 2);
+//   * an H2D stream (prefetch) and a D2H stream (write-back after prefill); during
+//     decode the append kernel writes the new K/V rows through to the host slice, so
+//     there is nothing left to copy back;
+//   * HIP events as fences: trigger (compute -> copy), ready (copy -> compute),
+//     slot-free (last reader of a slot -> next prefetch into it).
+// Sec. 4.4: sn_profile_layers measures per-layer compute and transfer time; the picker
+// (schedule.cpp) chooses the smallest interval whose timeline meets the SLO.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/sn.h"
+#include "kernels.h"
+#include "layout.h"
+#include "schedule.h"
+
+using namespace sn;
+
+namespace {
+
+thread_local std::string g_err;
+
+constexpr int kMetaRing = 8;
+constexpr int kKernelsPerLayer = 9;
+
+struct LayerState {
+  uint8_t* host_w = nullptr;    // pinned, tiled weights record (always present)
+  uint8_t* host_kv = nullptr;   // pinned KV slice (present once the layer has been offloaded)
+  uint8_t* host_kv_dev = nullptr;   // the same slice as the GPU addresses it (for write-through)
+  uint8_t* dev = nullptr;       // device [weights | KV] when GPU resident
+  bool offloaded = false;
+  int slot = 0;
+  int trigger = -1;
+};
+
+}  // namespace
+
+struct sn_ctx {
+  sn_model_shape shape{};
+  PackedLayout pl{};
+  BlobLayout bl{};
+  uint64_t budget = 0;
+  bool enforce = true;
+  hipStream_t compute = nullptr, h2d = nullptr, d2h = nullptr;
+  int N = 0;                     // interval in effect (L+1: nothing offloaded)
+  bool placed = false;
+  int timing = 0;
+
+  uint64_t w_bytes = 0, kv_bytes = 0, state_bytes = 0, ws_bytes = 0;
+  int64_t max_tokens = 0;
+  std::vector<LayerState> layers;
+  uint8_t* slot[2] = {nullptr, nullptr};
+
+  // workspace (device)
+  float* x32 = nullptr;
+  uint16_t *u16 = nullptr, *qkv16 = nullptr, *attn16 = nullptr, *act16 = nullptr;
+  float* part = nullptr;
+  float* inv_freq = nullptr;
+  int32_t* meta_dev = nullptr;
+  size_t meta_ints = 0;
+  int32_t* meta_host[kMetaRing] = {};
+  hipEvent_t ev_meta[kMetaRing] = {};
+  bool meta_used[kMetaRing] = {};
+  int meta_next = 0;
+
+  // KV bookkeeping
+  int batch = 0;
+  std::vector<int32_t> cap, kv_off, len;
+  int64_t kv_used_tokens = 0;
+
+  // events
+  std::vector<hipEvent_t> ev_layer, ev_after_wait, ev_trig, ev_copy_start, ev_ready, ev_done, ev_d2h_start,
+      ev_d2h_end;
+  hipEvent_t ev_slot_free[2] = {};
+  bool slot_free_valid[2] = {false, false};
+  hipEvent_t ev_iter_start = nullptr, ev_iter_end = nullptr;
+  std::vector<hipEvent_t> kev;   // [L][kKernelsPerLayer][2], created on demand
+
+  // what the last step did (for stats)
+  bool last_valid = false;
+  bool last_prefill = false;
+  int last_timing = 0;
+  int64_t last_h2d_bytes = 0, last_d2h_bytes = 0;
+  std::vector<uint8_t> last_kernel_class;   // [kKernelsPerLayer] class of each per-layer kernel slot
+
+  // profile
+  std::vector<int64_t> prof_tc, prof_tx;
+  bool has_profile = false;
+
+  std::string err;
+};
+
+namespace {
+
+int fail(sn_ctx* c, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf;
+  g_err = buf;
+  return code;
+}
+
+#define SN_HIP(c, call)                                                                          \
+  do {                                                                                           \
+    hipError_t e_ = (call);                                                                      \
+    if (e_ != hipSuccess)                                                                        \
+      return fail((c), e_ == hipErrorOutOfMemory ? SN_E_NOMEM : SN_E_HIP, "%s: %s (%s:%d)", #call, \
+                  hipGetErrorString(e_), __FILE__, __LINE__);                                    \
+  } while (0)
+
+uint64_t kv_token_bytes(const sn_model_shape& s) { return (uint64_t)2 * s.n_kv_heads * s.head_dim * 2; }
+
+int64_t elapsed_ns(hipEvent_t a, hipEvent_t b) {
+  float ms = 0.f;
+  if (hipEventElapsedTime(&ms, a, b) != hipSuccess) return -1;
+  return (int64_t)std::llround((double)ms * 1.0e6);
+}
+
+int make_events(sn_ctx* c, std::vector<hipEvent_t>& v, int n, bool timing) {
+  v.assign(n, nullptr);
+  for (int i = 0; i < n; ++i)
+    SN_HIP(c, hipEventCreateWithFlags(&v[i], timing ? hipEventDefault : hipEventDisableTiming));
+  return SN_OK;
+}
+
+void free_events(std::vector<hipEvent_t>& v) {
+  for (auto e : v)
+    if (e) (void)hipEventDestroy(e);
+  v.clear();
+}
+
+uint64_t fixed_bytes(const sn_ctx* c) { return c->ws_bytes; }
+
+int sync_all(sn_ctx* c) {
+  SN_HIP(c, hipStreamSynchronize(c->compute));
+  SN_HIP(c, hipStreamSynchronize(c->h2d));
+  SN_HIP(c, hipStreamSynchronize(c->d2h));
+  return SN_OK;
+}
+
+uint8_t* kv_of(uint8_t* state_base, const sn_ctx* c) { return state_base + c->w_bytes; }
+
+}  // namespace
+
+// =================================================================================
+// pure helpers
+// =================================================================================
+extern "C" int sn_placement(int32_t L, int32_t N, uint8_t* offloaded, int32_t* trigger) {
+  if (L < 1 || !offloaded || !trigger) return fail(nullptr, SN_E_INVAL, "sn_placement: bad argument");
+  for (int l = 0; l < L; ++l) {
+    offloaded[l] = is_offloaded(L, N, l) ? 1 : 0;
+    trigger[l] = offloaded[l] ? trigger_of(N, l) : -1;
+  }
+  return SN_OK;
+}
+
+extern "C" int sn_timeline(int32_t L, const int64_t* tc, const int64_t* tx, int32_t N, int64_t* iter_ns,
+                           int64_t* stall_total_ns) {
+  if (L < 1 || !tc || !tx || !iter_ns) return fail(nullptr, SN_E_INVAL, "sn_timeline: bad argument");
+  for (int l = 0; l < L; ++l)
+    if (tc[l] < 0 || tx[l] < 0) return fail(nullptr, SN_E_INVAL, "sn_timeline: negative time");
+  *iter_ns = iteration_time(L, tc, tx, N, stall_total_ns);
+  return SN_OK;
+}
+
+extern "C" int sn_pick_interval_from_times(int32_t L, const int64_t* tc, const int64_t* tx, int64_t slo_ns,
+                                           int32_t N_max, int32_t* N_out) {
+  if (L < 1 || !tc || !tx || !N_out) return fail(nullptr, SN_E_INVAL, "sn_pick_interval_from_times: bad argument");
+  for (int l = 0; l < L; ++l)
+    if (tc[l] < 0 || tx[l] < 0) return fail(nullptr, SN_E_INVAL, "sn_pick_interval_from_times: negative time");
+  const int n = min_interval(L, tc, tx, slo_ns);
+  if (n < 0) return fail(nullptr, SN_E_INFEASIBLE, "SLO %lld ns is below the un-offloaded iteration time", (long long)slo_ns);
+  if (n > N_max)
+    return fail(nullptr, SN_E_INFEASIBLE, "minimum interval %d exceeds the maximum %d allowed by GPU capacity", n, N_max);
+  *N_out = n;
+  return SN_OK;
+}
+
+extern "C" int32_t sn_paper_rule(int32_t L, int64_t t_trans_ns, int64_t slo_ns) {
+  return paper_rule(L, t_trans_ns, slo_ns);
+}
+
+extern "C" uint64_t sn_layer_blob_bytes(const sn_model_shape* shape) {
+  if (!shape || check_shape(*shape)) return 0;
+  return blob_layout(*shape).total;
+}
+
+extern "C" const char* sn_last_error(const sn_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+// =================================================================================
+// life cycle
+// =================================================================================
+extern "C" void sn_destroy(sn_ctx* c) {
+  if (!c) return;
+  if (c->compute || c->h2d) {
+    (void)hipStreamSynchronize(c->compute);
+    if (c->h2d) (void)hipStreamSynchronize(c->h2d);
+    if (c->d2h) (void)hipStreamSynchronize(c->d2h);
+  }
+  for (auto& ls : c->layers) {
+    if (ls.host_w) (void)hipHostFree(ls.host_w);
+    if (ls.host_kv) (void)hipHostFree(ls.host_kv);
+    if (ls.dev) (void)hipFree(ls.dev);
+  }
+  for (auto& s : c->slot)
+    if (s) (void)hipFree(s);
+  void* dev[] = {c->x32, c->u16, c->qkv16, c->attn16, c->act16, c->part, c->inv_freq, c->meta_dev};
+  for (void* p : dev)
+    if (p) (void)hipFree(p);
+  for (int i = 0; i < kMetaRing; ++i) {
+    if (c->meta_host[i]) (void)hipHostFree(c->meta_host[i]);
+    if (c->ev_meta[i]) (void)hipEventDestroy(c->ev_meta[i]);
+  }
+  free_events(c->ev_layer);
+  free_events(c->ev_after_wait);
+  free_events(c->ev_trig);
+  free_events(c->ev_copy_start);
+  free_events(c->ev_ready);
+  free_events(c->ev_done);
+  free_events(c->ev_d2h_start);
+  free_events(c->ev_d2h_end);
+  free_events(c->kev);
+  for (auto& e : c->ev_slot_free)
+    if (e) (void)hipEventDestroy(e);
+  if (c->ev_iter_start) (void)hipEventDestroy(c->ev_iter_start);
+  if (c->ev_iter_end) (void)hipEventDestroy(c->ev_iter_end);
+  if (c->h2d) (void)hipStreamDestroy(c->h2d);
+  if (c->d2h) (void)hipStreamDestroy(c->d2h);
+  delete c;
+}
+
+static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, void* stream) {
+  c->shape = *shape;
+  const sn_model_shape& s = c->shape;
+  c->budget = budget;
+  c->compute = (hipStream_t)stream;
+  c->pl = packed_layout(s);
+  c->bl = blob_layout(s);
+  c->w_bytes = c->pl.total;
+  c->kv_bytes = align_up((uint64_t)s.max_batch * s.max_seq * kv_token_bytes(s));
+  c->state_bytes = c->w_bytes + c->kv_bytes;
+  c->max_tokens = s.max_tokens > 0 ? s.max_tokens : (int64_t)s.max_batch * s.max_seq;
+  if (c->max_tokens < s.max_batch) c->max_tokens = s.max_batch;
+  if (c->max_tokens > (int64_t)1 << 24) return fail(c, SN_E_INVAL, "max_tokens too large");
+  const int L = s.n_layers;
+  const uint64_t T = (uint64_t)c->max_tokens;
+  const uint64_t qkv_ld = (uint64_t)c->pl.n_qkv, qd = (uint64_t)s.n_q_heads * s.head_dim;
+
+  const uint64_t b_x32 = align_up(T * s.hidden * 4), b_u = align_up(T * s.hidden * 2);
+  const uint64_t b_qkv = align_up(T * qkv_ld * 2), b_attn = align_up(T * qd * 2);
+  const uint64_t b_act = align_up(T * (uint64_t)s.ffn * 2);
+  const uint64_t b_part = align_up((uint64_t)s.max_batch * s.n_q_heads * 16 * (s.head_dim + 2) * 4);
+  const uint64_t n_tiles_max = T / 64 + s.max_batch + 1;
+  c->meta_ints = (size_t)(5 * (uint64_t)s.max_batch + 2 * T + 2 * n_tiles_max);
+  const uint64_t b_meta = align_up(c->meta_ints * 4);
+  const uint64_t b_freq = align_up((uint64_t)s.head_dim / 2 * 4);
+  c->ws_bytes = b_x32 + b_u + b_qkv + b_attn + b_act + b_part + b_meta + b_freq;
+
+  SN_HIP(c, hipStreamCreateWithFlags(&c->h2d, hipStreamNonBlocking));
+  SN_HIP(c, hipStreamCreateWithFlags(&c->d2h, hipStreamNonBlocking));
+  SN_HIP(c, hipMalloc(&c->x32, b_x32));
+  SN_HIP(c, hipMalloc(&c->u16, b_u));
+  SN_HIP(c, hipMalloc(&c->qkv16, b_qkv));
+  SN_HIP(c, hipMalloc(&c->attn16, b_attn));
+  SN_HIP(c, hipMalloc(&c->act16, b_act));
+  SN_HIP(c, hipMalloc(&c->part, b_part));
+  SN_HIP(c, hipMalloc(&c->meta_dev, b_meta));
+  SN_HIP(c, hipMalloc(&c->inv_freq, b_freq));
+  {
+    std::vector<float> f(s.head_dim / 2);
+    for (int i = 0; i < s.head_dim / 2; ++i)
+      f[i] = (float)std::pow((double)s.rope_theta, -2.0 * i / (double)s.head_dim);
+    SN_HIP(c, hipMemcpy(c->inv_freq, f.data(), f.size() * 4, hipMemcpyHostToDevice));
+  }
+  for (int i = 0; i < kMetaRing; ++i) {
+    SN_HIP(c, hipHostMalloc((void**)&c->meta_host[i], b_meta, hipHostMallocDefault));
+    SN_HIP(c, hipEventCreateWithFlags(&c->ev_meta[i], hipEventDisableTiming));
+  }
+  c->layers.resize(L);
+  for (int l = 0; l < L; ++l) SN_HIP(c, hipHostMalloc((void**)&c->layers[l].host_w, c->w_bytes, hipHostMallocDefault));
+
+  int rc;
+  if ((rc = make_events(c, c->ev_layer, L + 1, true))) return rc;
+  if ((rc = make_events(c, c->ev_after_wait, L, true))) return rc;
+  if ((rc = make_events(c, c->ev_trig, L, false))) return rc;
+  if ((rc = make_events(c, c->ev_copy_start, L, true))) return rc;
+  if ((rc = make_events(c, c->ev_ready, L, true))) return rc;
+  if ((rc = make_events(c, c->ev_done, L, false))) return rc;
+  if ((rc = make_events(c, c->ev_d2h_start, L, true))) return rc;
+  if ((rc = make_events(c, c->ev_d2h_end, L, true))) return rc;
+  for (auto& e : c->ev_slot_free) SN_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  SN_HIP(c, hipEventCreate(&c->ev_iter_start));
+  SN_HIP(c, hipEventCreate(&c->ev_iter_end));
+  c->prof_tc.assign(L, 0);
+  c->prof_tx.assign(L, 0);
+  return SN_OK;
+}
+
+extern "C" int sn_init(sn_ctx** out, const sn_model_shape* shape, uint64_t hbm_budget_bytes, void* stream) {
+  if (!out || !shape) return fail(nullptr, SN_E_INVAL, "sn_init: null argument");
+  *out = nullptr;
+  if (const char* why = check_shape(*shape)) return fail(nullptr, SN_E_INVAL, "sn_init: %s", why);
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1)
+    return fail(nullptr, SN_E_HIP, "sn_init: no HIP device available");
+  sn_ctx* c = new sn_ctx();
+  const int rc = init_impl(c, shape, hbm_budget_bytes, stream);
+  if (rc != SN_OK) {
+    g_err = c->err;
+    sn_destroy(c);
+    return rc;
+  }
+  *out = c;
+  return SN_OK;
+}
+
+// =================================================================================
+// weights, capacity accounting, placement
+// =================================================================================
+extern "C" int sn_set_layer_weights(sn_ctx* c, int32_t layer, const void* host_blob, uint64_t bytes) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "sn_set_layer_weights: null context");
+  if (!host_blob || layer < 0 || layer >= c->shape.n_layers) return fail(c, SN_E_INVAL, "sn_set_layer_weights: bad layer or blob");
+  if (bytes != c->bl.total)
+    return fail(c, SN_E_INVAL, "sn_set_layer_weights: blob is %llu bytes, layout needs %llu", (unsigned long long)bytes,
+                (unsigned long long)c->bl.total);
+  int rc = sync_all(c);
+  if (rc) return rc;
+  LayerState& ls = c->layers[layer];
+  pack_layer(c->shape, static_cast<const uint8_t*>(host_blob), ls.host_w);
+  if (ls.dev) SN_HIP(c, hipMemcpy(ls.dev, ls.host_w, c->w_bytes, hipMemcpyHostToDevice));
+  return SN_OK;
+}
+
+extern "C" uint64_t sn_resident_bytes(const sn_ctx* c, int32_t N) {
+  if (!c) return 0;
+  return resident_bytes(c->shape.n_layers, N, c->state_bytes, c->state_bytes, fixed_bytes(c));
+}
+
+extern "C" int32_t sn_max_interval(const sn_ctx* c) {
+  if (!c) return 0;
+  return max_interval(c->shape.n_layers, c->budget, c->state_bytes, c->state_bytes, fixed_bytes(c));
+}
+
+extern "C" int sn_set_budget_enforce(sn_ctx* c, int32_t on) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "null context");
+  c->enforce = on != 0;
+  return SN_OK;
+}
+
+extern "C" int sn_place(sn_ctx* c, int32_t N) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "sn_place: null context");
+  const int L = c->shape.n_layers;
+  if (N < 0) return fail(c, SN_E_INVAL, "sn_place: negative interval");
+  if (N == 0 || N > L) N = L + 1;
+  const uint64_t need = sn_resident_bytes(c, N);
+  if (c->enforce && c->budget && need > c->budget)
+    return fail(c, SN_E_BUDGET, "interval %d needs %llu device bytes, budget is %llu", N, (unsigned long long)need,
+                (unsigned long long)c->budget);
+  int rc = sync_all(c);
+  if (rc) return rc;
+  const uint64_t kv_used = (uint64_t)c->kv_used_tokens * kv_token_bytes(c->shape);
+
+  // first release what leaves the GPU, then allocate what enters it
+  for (int l = 0; l < L; ++l) {
+    LayerState& ls = c->layers[l];
+    if (!is_offloaded(L, N, l)) continue;
+    if (!ls.host_kv) {
+      SN_HIP(c, hipHostMalloc((void**)&ls.host_kv, c->kv_bytes, hipHostMallocDefault));
+      std::memset(ls.host_kv, 0, c->kv_bytes);
+      SN_HIP(c, hipHostGetDevicePointer((void**)&ls.host_kv_dev, ls.host_kv, 0));
+    }
+    if (ls.dev) {
+      if (kv_used) SN_HIP(c, hipMemcpy(ls.host_kv, kv_of(ls.dev, c), kv_used, hipMemcpyDeviceToHost));
+      SN_HIP(c, hipFree(ls.dev));
+      ls.dev = nullptr;
+    }
+  }
+  const int K = offloaded_count(L, N);
+  if (K == 0) {
+    for (auto& s : c->slot)
+      if (s) {
+        SN_HIP(c, hipFree(s));
+        s = nullptr;
+      }
+  }
+  for (int l = 0; l < L; ++l) {
+    LayerState& ls = c->layers[l];
+    if (is_offloaded(L, N, l) || ls.dev) continue;
+    SN_HIP(c, hipMalloc((void**)&ls.dev, c->state_bytes));
+    SN_HIP(c, hipMemcpy(ls.dev, ls.host_w, c->w_bytes, hipMemcpyHostToDevice));
+    if (ls.host_kv && ls.offloaded && kv_used)
+      SN_HIP(c, hipMemcpy(kv_of(ls.dev, c), ls.host_kv, kv_used, hipMemcpyHostToDevice));
+    else
+      SN_HIP(c, hipMemset(kv_of(ls.dev, c), 0, c->kv_bytes));
+  }
+  if (K > 0)
+    for (auto& s : c->slot)
+      if (!s) SN_HIP(c, hipMalloc((void**)&s, c->state_bytes));
+  int k = 0;
+  for (int l = 0; l < L; ++l) {
+    LayerState& ls = c->layers[l];
+    ls.offloaded = is_offloaded(L, N, l);
+    ls.trigger = ls.offloaded ? trigger_of(N, l) : -1;
+    ls.slot = ls.offloaded ? (k++ & 1) : 0;
+  }
+  c->slot_free_valid[0] = c->slot_free_valid[1] = false;
+  c->N = N;
+  c->placed = true;
+  c->last_valid = false;
+  return SN_OK;
+}
+
+// =================================================================================
+// KV bookkeeping
+// =================================================================================
+extern "C" int sn_kv_reset(sn_ctx* c, int32_t batch, const int32_t* capacity) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "sn_kv_reset: null context");
+  if (batch < 1 || batch > c->shape.max_batch || !capacity) return fail(c, SN_E_INVAL, "sn_kv_reset: bad batch");
+  int64_t tot = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (capacity[b] < 1) return fail(c, SN_E_INVAL, "sn_kv_reset: capacity must be positive");
+    tot += capacity[b];
+  }
+  if (tot > (int64_t)c->shape.max_batch * c->shape.max_seq)
+    return fail(c, SN_E_INVAL, "sn_kv_reset: capacities sum to %lld tokens, context holds %lld", (long long)tot,
+                (long long)c->shape.max_batch * c->shape.max_seq);
+  c->batch = batch;
+  c->cap.assign(capacity, capacity + batch);
+  c->kv_off.assign(batch, 0);
+  c->len.assign(batch, 0);
+  int32_t off = 0;
+  for (int b = 0; b < batch; ++b) {
+    c->kv_off[b] = off;
+    off += capacity[b];
+  }
+  c->kv_used_tokens = tot;
+  return SN_OK;
+}
+
+// =================================================================================
+// one iteration
+// =================================================================================
+namespace {
+
+struct KTimer {   // optional per-kernel event pairs (timing level 2)
+  sn_ctx* c;
+  int layer;
+  int slot = 0;
+  bool on;
+  void begin() {
+    if (on) (void)hipEventRecord(c->kev[((size_t)layer * kKernelsPerLayer + slot) * 2], c->compute);
+  }
+  void end(int cls) {
+    if (on) {
+      (void)hipEventRecord(c->kev[((size_t)layer * kKernelsPerLayer + slot) * 2 + 1], c->compute);
+      c->last_kernel_class[slot] = (uint8_t)cls;
+    }
+    ++slot;
+  }
+};
+
+int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepIndex& ix, int T, int B,
+              bool prefill, int n_qtiles, int S) {
+  const sn_model_shape& s = c->shape;
+  const PackedLayout& p = c->pl;
+  const int dt = s.dtype, h = s.hidden, F = s.ffn, Hq = s.n_q_heads, Hkv = s.n_kv_heads, d = s.head_dim;
+  const int qd = Hq * d;
+  auto at = [&](uint64_t off) -> const void* { return off == kNone ? nullptr : base + off; };
+  uint8_t* kv = kv_of(base, c);
+  hipStream_t st = c->compute;
+  const bool small = !prefill;   // decode path: T == B <= 64
+  KTimer kt{c, l, 0, c->timing >= 2};
+  auto gemm = [&](int epi, const void* W, const void* X, const void* bias, void* out, int N, int K) {
+    return small ? launch_gemm_skinny(dt, epi, W, X, bias, out, T, N, K, st)
+                 : launch_gemm_tile(dt, epi, W, X, bias, out, T, N, K, st);
+  };
+  kt.begin();
+  SN_HIP(c, launch_norm(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, st));
+  kt.end(SN_K_NORM);
+  kt.begin();
+  SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h));
+  kt.end(SN_K_QKV);
+  kt.begin();
+  SN_HIP(c, launch_rope_append(dt, c->qkv16, ix, kv, mirror_kv, c->inv_freq, T, Hq, Hkv, d, s.rope, st));
+  kt.end(SN_K_ROPE_APPEND);
+  kt.begin();
+  if (prefill)
+    SN_HIP(c, launch_attn_prefill(dt, c->qkv16, kv, ix, c->attn16, n_qtiles, Hq, Hkv, d, st));
+  else
+    SN_HIP(c, launch_attn_decode(dt, c->qkv16, kv, ix, c->attn16, c->part, B, Hq, Hkv, d, S, st));
+  kt.end(SN_K_ATTN);
+  kt.begin();
+  SN_HIP(c, gemm(EPI_RESID32, at(p.wo), c->attn16, at(p.bo), c->x32, h, qd));
+  kt.end(SN_K_OPROJ);
+  kt.begin();
+  SN_HIP(c, launch_norm(dt, s.norm == SN_NORM_LN, c->x32, at(p.n2g), at(p.n2b), c->u16, T, h, s.norm_eps, st));
+  kt.end(SN_K_NORM);
+  kt.begin();
+  SN_HIP(c, gemm(s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup), c->act16, p.n_up, h));
+  kt.end(SN_K_FFN_UP);
+  kt.begin();
+  SN_HIP(c, gemm(EPI_RESID32, at(p.wd), c->act16, at(p.bd), c->x32, h, F));
+  kt.end(SN_K_FFN_DOWN);
+  return SN_OK;
+}
+
+}  // namespace
+
+extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_out) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "sn_step: null context");
+  if (!c->placed) return fail(c, SN_E_STATE, "sn_step before sn_place");
+  if (!bt || !kv || !kv->len || !bt->n_new || !bt->hidden_in || !hidden_out)
+    return fail(c, SN_E_INVAL, "sn_step: null argument");
+  if (c->batch == 0) return fail(c, SN_E_STATE, "sn_step before sn_kv_reset");
+  if (bt->batch != c->batch) return fail(c, SN_E_INVAL, "sn_step: batch %d, KV was reset for %d", bt->batch, c->batch);
+  const sn_model_shape& s = c->shape;
+  const int B = c->batch, L = s.n_layers;
+  const bool prefill = bt->is_prefill != 0;
+  int64_t T64 = 0;
+  bool any_cached = false;
+  for (int b = 0; b < B; ++b) {
+    if (kv->len[b] != c->len[b])
+      return fail(c, SN_E_INVAL, "sn_step: kv.len[%d] = %d but the context holds %d", b, kv->len[b], c->len[b]);
+    const int n = bt->n_new[b];
+    if (n < 0 || (!prefill && n != 1)) return fail(c, SN_E_INVAL, "sn_step: n_new[%d] = %d", b, n);
+    if (c->len[b] + n > c->cap[b])
+      return fail(c, SN_E_INVAL, "sn_step: sequence %d would hold %d tokens, capacity %d", b, c->len[b] + n, c->cap[b]);
+    any_cached |= c->len[b] > 0;
+    T64 += n;
+  }
+  if (T64 == 0) return fail(c, SN_E_INVAL, "sn_step: no tokens");
+  if (T64 > c->max_tokens) return fail(c, SN_E_INVAL, "sn_step: %lld tokens exceed max_tokens %lld", (long long)T64, (long long)c->max_tokens);
+  if (!prefill && B > 64) return fail(c, SN_E_INVAL, "sn_step: decode batch above 64");
+  const int T = (int)T64;
+
+  // ---- index arrays: host ring buffer -> device ----
+  const int ring = c->meta_next;
+  c->meta_next = (ring + 1) % kMetaRing;
+  if (c->meta_used[ring]) SN_HIP(c, hipEventSynchronize(c->ev_meta[ring]));
+  int32_t* mh = c->meta_host[ring];
+  int32_t *m_len = mh, *m_new = mh + B, *m_start = mh + 2 * B, *m_off = mh + 3 * B, *m_cap = mh + 4 * B;
+  int32_t *m_seq = mh + 5 * B, *m_pos = m_seq + T, *m_tseq = m_pos + T;
+  int n_qtiles = 0, max_len = 0;
+  {
+    int t = 0;
+    for (int b = 0; b < B; ++b) {
+      m_len[b] = c->len[b];
+      m_new[b] = bt->n_new[b];
+      m_start[b] = t;
+      m_off[b] = c->kv_off[b];
+      m_cap[b] = c->cap[b];
+      for (int i = 0; i < bt->n_new[b]; ++i, ++t) {
+        m_seq[t] = b;
+        m_pos[t] = c->len[b] + i;
+      }
+      if (prefill) n_qtiles += (bt->n_new[b] + 63) / 64;
+      max_len = std::max(max_len, c->len[b] + bt->n_new[b]);
+    }
+  }
+  int32_t* m_tq0 = m_tseq + n_qtiles;
+  if (prefill) {
+    int q = 0;
+    for (int b = 0; b < B; ++b)
+      for (int q0 = 0; q0 < bt->n_new[b]; q0 += 64, ++q) {
+        m_tseq[q] = b;
+        m_tq0[q] = q0;
+      }
+  }
+  const size_t used_ints = (size_t)5 * B + 2 * (size_t)T + 2 * (size_t)n_qtiles;
+  if (used_ints > c->meta_ints) return fail(c, SN_E_INVAL, "sn_step: index arrays overflow");
+  SN_HIP(c, hipMemcpyAsync(c->meta_dev, mh, used_ints * 4, hipMemcpyHostToDevice, c->compute));
+  SN_HIP(c, hipEventRecord(c->ev_meta[ring], c->compute));
+  c->meta_used[ring] = true;
+  int32_t* md = c->meta_dev;
+  StepIndex ix;
+  ix.len_before = md;
+  ix.n_new = md + B;
+  ix.tok_start = md + 2 * B;
+  ix.kv_off = md + 3 * B;
+  ix.cap = md + 4 * B;
+  ix.tok_seq = md + 5 * B;
+  ix.tok_pos = ix.tok_seq + T;
+  ix.tile_seq = ix.tok_pos + T;
+  ix.tile_q0 = ix.tile_seq + n_qtiles;
+  const int S = prefill ? 1 : attn_decode_splits(B, s.n_kv_heads, max_len);
+
+  if (c->timing >= 2 && c->kev.empty()) {
+    int rc = make_events(c, c->kev, L * kKernelsPerLayer * 2, true);
+    if (rc) return rc;
+  }
+  c->last_kernel_class.assign(kKernelsPerLayer, SN_K_OTHER);
+
+  const uint64_t kv_used = (uint64_t)c->kv_used_tokens * kv_token_bytes(s);
+  const bool fetch_kv = any_cached;             // prefill from empty caches produces the KV itself
+  c->last_h2d_bytes = c->last_d2h_bytes = 0;
+
+  SN_HIP(c, hipEventRecord(c->ev_iter_start, c->compute));
+  SN_HIP(c, launch_cast_in(s.dtype, bt->hidden_in, c->x32, (size_t)T * s.hidden, c->compute));
+
+  for (int l = 0; l < L; ++l) {
+    LayerState& ls = c->layers[l];
+    if (c->timing >= 1 || ls.offloaded) SN_HIP(c, hipEventRecord(c->ev_layer[l], c->compute));
+    // prefetches triggered by reaching this layer (paper Sec. 4.3: first layer of the group)
+    for (int o = l; o < L && o <= l + std::max(c->N - 1, 1); ++o) {
+      LayerState& os = c->layers[o];
+      if (!os.offloaded || os.trigger != l) continue;
+      SN_HIP(c, hipEventRecord(c->ev_trig[o], c->compute));
+      SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_trig[o], 0));
+      if (c->slot_free_valid[os.slot]) SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_slot_free[os.slot], 0));
+      SN_HIP(c, hipEventRecord(c->ev_copy_start[o], c->h2d));
+      SN_HIP(c, hipMemcpyAsync(c->slot[os.slot], os.host_w, c->w_bytes, hipMemcpyHostToDevice, c->h2d));
+      c->last_h2d_bytes += (int64_t)c->w_bytes;
+      if (fetch_kv && kv_used) {
+        SN_HIP(c, hipMemcpyAsync(kv_of(c->slot[os.slot], c), os.host_kv, kv_used, hipMemcpyHostToDevice, c->h2d));
+        c->last_h2d_bytes += (int64_t)kv_used;
+      }
+      SN_HIP(c, hipEventRecord(c->ev_ready[o], c->h2d));
+    }
+    uint8_t* base = ls.dev;
+    uint8_t* mirror = nullptr;
+    if (ls.offloaded) {
+      SN_HIP(c, hipStreamWaitEvent(c->compute, c->ev_ready[l], 0));     // the fence "S" of Fig. 7
+      SN_HIP(c, hipEventRecord(c->ev_after_wait[l], c->compute));
+      base = c->slot[ls.slot];
+      if (!prefill) mirror = ls.host_kv_dev;                                 // decode: rows written through
+    }
+    int rc = run_layer(c, l, base, mirror, ix, T, B, prefill, n_qtiles, S);
+    if (rc) return rc;
+    if (ls.offloaded) {
+      if (prefill) {
+        SN_HIP(c, hipEventRecord(c->ev_done[l], c->compute));
+        SN_HIP(c, hipStreamWaitEvent(c->d2h, c->ev_done[l], 0));
+        SN_HIP(c, hipEventRecord(c->ev_d2h_start[l], c->d2h));
+        SN_HIP(c, hipMemcpyAsync(ls.host_kv, kv_of(base, c), kv_used, hipMemcpyDeviceToHost, c->d2h));
+        SN_HIP(c, hipEventRecord(c->ev_d2h_end[l], c->d2h));
+        SN_HIP(c, hipEventRecord(c->ev_slot_free[ls.slot], c->d2h));
+        c->last_d2h_bytes += (int64_t)kv_used;
+      } else {
+        SN_HIP(c, hipEventRecord(c->ev_slot_free[ls.slot], c->compute));
+        c->last_d2h_bytes += (int64_t)B * (int64_t)kv_token_bytes(s);
+      }
+      c->slot_free_valid[ls.slot] = true;
+    }
+  }
+  SN_HIP(c, hipEventRecord(c->ev_layer[L], c->compute));
+  SN_HIP(c, launch_cast_out(s.dtype, c->x32, hidden_out, (size_t)T * s.hidden, c->compute));
+  SN_HIP(c, hipEventRecord(c->ev_iter_end, c->compute));
+
+  for (int b = 0; b < B; ++b) {
+    c->len[b] += bt->n_new[b];
+    kv->len[b] = c->len[b];
+  }
+  c->last_valid = true;
+  c->last_prefill = prefill;
+  c->last_timing = c->timing;
+  return SN_OK;
+}
+
+// =================================================================================
+// stats
+// =================================================================================
+extern "C" int sn_set_timing(sn_ctx* c, int32_t level) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "null context");
+  if (level < 0 || level > 2) return fail(c, SN_E_INVAL, "sn_set_timing: level must be 0, 1 or 2");
+  c->timing = level;
+  return SN_OK;
+}
+
+extern "C" int sn_get_stats(sn_ctx* c, sn_step_stats* out) {
+  if (!c || !out) return fail(c, SN_E_INVAL, "sn_get_stats: null argument");
+  if (!c->last_valid) return fail(c, SN_E_STATE, "sn_get_stats: no iteration has run under this placement");
+  int rc = sync_all(c);
+  if (rc) return rc;
+  std::memset(out, 0, sizeof *out);
+  const int L = c->shape.n_layers;
+  out->iter_ns = elapsed_ns(c->ev_iter_start, c->ev_iter_end);
+  out->interval = c->N;
+  out->resident_bytes = sn_resident_bytes(c, c->N);
+  out->h2d_bytes = c->last_h2d_bytes;
+  out->d2h_bytes = c->last_d2h_bytes;
+  for (int l = 0; l < L; ++l) {
+    const LayerState& ls = c->layers[l];
+    if (!ls.offloaded) continue;
+    ++out->n_offloaded;
+    out->h2d_ns += std::max<int64_t>(0, elapsed_ns(c->ev_copy_start[l], c->ev_ready[l]));
+    out->stall_ns += std::max<int64_t>(0, elapsed_ns(c->ev_layer[l], c->ev_after_wait[l]));
+    if (c->last_prefill) out->d2h_ns += std::max<int64_t>(0, elapsed_ns(c->ev_d2h_start[l], c->ev_d2h_end[l]));
+  }
+  out->hidden_fraction = out->h2d_ns > 0 ? 1.0 - (double)std::min(out->stall_ns, out->h2d_ns) / (double)out->h2d_ns : 1.0;
+  if (c->last_timing >= 2 && !c->kev.empty()) {
+    for (int l = 0; l < L; ++l)
+      for (int k = 0; k < 8; ++k) {   // run_layer records 8 kernel slots
+        const int cls = c->last_kernel_class[k];
+        const int64_t ns = elapsed_ns(c->kev[((size_t)l * kKernelsPerLayer + k) * 2],
+                                      c->kev[((size_t)l * kKernelsPerLayer + k) * 2 + 1]);
+        if (ns >= 0) {
+          out->kernel_ns[cls] += ns;
+          out->kernel_calls[cls] += 1;
+        }
+      }
+  }
+  return SN_OK;
+}
+
+extern "C" int sn_get_layer_times(sn_ctx* c, int64_t* compute_ns, int64_t* stall_ns, int64_t* h2d_ns) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "null context");
+  if (!c->last_valid) return fail(c, SN_E_STATE, "sn_get_layer_times: no iteration has run under this placement");
+  if (c->last_timing < 1) return fail(c, SN_E_STATE, "sn_get_layer_times: needs timing level >= 1 during the step");
+  int rc = sync_all(c);
+  if (rc) return rc;
+  const int L = c->shape.n_layers;
+  for (int l = 0; l < L; ++l) {
+    const LayerState& ls = c->layers[l];
+    if (compute_ns) compute_ns[l] = elapsed_ns(ls.offloaded ? c->ev_after_wait[l] : c->ev_layer[l], c->ev_layer[l + 1]);
+    if (stall_ns) stall_ns[l] = ls.offloaded ? std::max<int64_t>(0, elapsed_ns(c->ev_layer[l], c->ev_after_wait[l])) : 0;
+    if (h2d_ns) h2d_ns[l] = ls.offloaded ? elapsed_ns(c->ev_copy_start[l], c->ev_ready[l]) : 0;
+  }
+  return SN_OK;
+}
+
+// =================================================================================
+// profiler and picker (paper Sec. 4.4)
+// =================================================================================
+static int64_t median_of(std::vector<int64_t> v) {
+  std::sort(v.begin(), v.end());
+  return v[v.size() / 2];
+}
+
+extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, int32_t seq, int32_t reps,
+                                 int64_t* tc_ns, int64_t* tx_ns) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "sn_profile_layers: null context");
+  if (!c->placed) return fail(c, SN_E_STATE, "sn_profile_layers before sn_place");
+  const sn_model_shape& s = c->shape;
+  const int L = s.n_layers;
+  if (batch < 1 || batch > s.max_batch || seq < 1 || reps < 1 || reps > 1000)
+    return fail(c, SN_E_INVAL, "sn_profile_layers: bad batch/seq/reps");
+  if (!is_prefill && batch > 64) return fail(c, SN_E_INVAL, "sn_profile_layers: decode batch above 64");
+  const int cap1 = is_prefill ? seq : seq + 1;
+  if ((int64_t)cap1 * batch > (int64_t)s.max_batch * s.max_seq)
+    return fail(c, SN_E_INVAL, "sn_profile_layers: batch*seq exceeds the context's KV capacity");
+  const int64_t T = is_prefill ? (int64_t)batch * seq : batch;
+  if (T > c->max_tokens) return fail(c, SN_E_INVAL, "sn_profile_layers: too many tokens for max_tokens");
+
+  int rc = sync_all(c);
+  if (rc) return rc;
+  std::vector<int32_t> caps(batch, cap1), n_new(batch, is_prefill ? seq : 1), lens(batch, 0);
+  if ((rc = sn_kv_reset(c, batch, caps.data()))) return rc;
+
+  void *hin = nullptr, *hout = nullptr;
+  const size_t hbytes = (size_t)T * s.hidden * 2;
+  SN_HIP(c, hipMalloc(&hin, hbytes));
+  if (hipMalloc(&hout, hbytes) != hipSuccess) {
+    (void)hipFree(hin);
+    return fail(c, SN_E_NOMEM, "sn_profile_layers: device allocation failed");
+  }
+  const int saved_timing = c->timing;
+  c->timing = 1;
+  std::vector<std::vector<int64_t>> samples(L);
+  std::vector<int64_t> tcur(L);
+  sn_batch bt{batch, is_prefill ? 1 : 0, n_new.data(), hin};
+  sn_kv kvh{lens.data()};
+  rc = SN_OK;
+  hipError_t he = launch_fill_hash(s.dtype, hin, (size_t)T * s.hidden, 12345u, c->compute);
+  if (he != hipSuccess) rc = fail(c, SN_E_HIP, "fill: %s", hipGetErrorString(he));
+  for (int r = 0; r < reps + 1 && rc == SN_OK; ++r) {   // first pass is a warm-up
+    for (int b = 0; b < batch; ++b) c->len[b] = lens[b] = is_prefill ? 0 : seq;
+    rc = sn_step(c, &bt, &kvh, hout);
+    if (rc) break;
+    rc = sn_get_layer_times(c, tcur.data(), nullptr, nullptr);
+    if (rc) break;
+    if (r > 0)
+      for (int l = 0; l < L; ++l) samples[l].push_back(tcur[l]);
+  }
+  c->timing = saved_timing;
+  (void)hipFree(hin);
+  (void)hipFree(hout);
+  if (rc) return rc;
+  for (int l = 0; l < L; ++l) c->prof_tc[l] = median_of(samples[l]);
+
+  // solo transfer of each layer's state (weights; + KV prefix when decoding)
+  uint8_t* dst = c->slot[0];
+  bool temp = false;
+  if (!dst) {
+    SN_HIP(c, hipMalloc((void**)&dst, c->state_bytes));
+    temp = true;
+  }
+  const uint64_t kv_used = is_prefill ? 0 : (uint64_t)c->kv_used_tokens * kv_token_bytes(s);
+  uint8_t* kv_src_tmp = nullptr;
+  for (int l = 0; l < L && rc == SN_OK; ++l) {
+    LayerState& ls = c->layers[l];
+    const uint8_t* kv_src = ls.host_kv;
+    if (kv_used && !kv_src) {   // resident layer: time the same bytes from a pinned scratch slice
+      if (!kv_src_tmp) {
+        if (hipHostMalloc((void**)&kv_src_tmp, c->kv_bytes, hipHostMallocDefault) != hipSuccess) {
+          rc = fail(c, SN_E_NOMEM, "sn_profile_layers: pinned allocation failed");
+          break;
+        }
+        std::memset(kv_src_tmp, 0, c->kv_bytes);
+      }
+      kv_src = kv_src_tmp;
+    }
+    std::vector<int64_t> v;
+    for (int r = 0; r < reps + 1; ++r) {
+      hipError_t e = hipEventRecord(c->ev_copy_start[l], c->h2d);
+      if (e == hipSuccess) e = hipMemcpyAsync(dst, ls.host_w, c->w_bytes, hipMemcpyHostToDevice, c->h2d);
+      if (e == hipSuccess && kv_used) e = hipMemcpyAsync(dst + c->w_bytes, kv_src, kv_used, hipMemcpyHostToDevice, c->h2d);
+      if (e == hipSuccess) e = hipEventRecord(c->ev_ready[l], c->h2d);
+      if (e == hipSuccess) e = hipStreamSynchronize(c->h2d);
+      if (e != hipSuccess) {
+        rc = fail(c, SN_E_HIP, "sn_profile_layers: transfer timing: %s", hipGetErrorString(e));
+        break;
+      }
+      if (r > 0) v.push_back(elapsed_ns(c->ev_copy_start[l], c->ev_ready[l]));
+    }
+    if (rc == SN_OK) c->prof_tx[l] = median_of(v);
+  }
+  if (kv_src_tmp) (void)hipHostFree(kv_src_tmp);
+  if (temp) (void)hipFree(dst);
+  if (rc) return rc;
+
+  for (int b = 0; b < batch; ++b) c->len[b] = 0;
+  c->last_valid = false;
+  c->has_profile = true;
+  if (tc_ns) std::copy(c->prof_tc.begin(), c->prof_tc.end(), tc_ns);
+  if (tx_ns) std::copy(c->prof_tx.begin(), c->prof_tx.end(), tx_ns);
+  return SN_OK;
+}
+
+extern "C" int sn_pick_interval(sn_ctx* c, double slo_ms, int32_t* N_out) {
+  if (!c || !N_out) return fail(c, SN_E_INVAL, "sn_pick_interval: null argument");
+  if (!c->has_profile) return fail(c, SN_E_STATE, "sn_pick_interval before sn_profile_layers");
+  if (!(slo_ms > 0)) return fail(c, SN_E_INVAL, "sn_pick_interval: SLO must be positive");
+  const int64_t slo_ns = (int64_t)std::llround(slo_ms * 1.0e6);
+  const int L = c->shape.n_layers;
+  const int rc = sn_pick_interval_from_times(L, c->prof_tc.data(), c->prof_tx.data(), slo_ns, sn_max_interval(c), N_out);
+  if (rc) {
+    c->err = g_err;
+    return rc;
+  }
+  // The two staging slots make an interval close to L cost more device memory than
+  // keeping the whole model resident.  If the pick does not fit although "no
+  // offloading" does (the only way minimum <= maximum can still not fit), run without
+  // offloading: its iteration time is no longer and it is within capacity.
+  if (c->budget && sn_resident_bytes(c, *N_out) > c->budget) *N_out = L + 1;
+  return SN_OK;
+}

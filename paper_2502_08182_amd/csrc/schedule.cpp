@@ -1,0 +1,87 @@
+// Placement map, prefetch triggers, the iteration timeline and the interval picker.
+// Host only, exact int64 arithmetic.
+//
+// Paper: an offloading interval of i keeps, for every i layers, the last one on the
+// host (Sec. 4.3); its load is issued when compute reaches the first layer of that
+// group, and a synchronisation point precedes the offloaded layer (Fig. 7); the
+// optimal interval is the smallest one that meets the SLO (Sec. 4.3, 4.4) and must not
+// exceed the maximum allowed by GPU capacity (Sec. 4.5).
+#include "schedule.h"
+
+#include <algorithm>
+#include <vector>
+
+namespace sn {
+
+int offloaded_count(int L, int N) { return (N >= 1 && N <= L) ? L / N : 0; }
+
+bool is_offloaded(int L, int N, int l) { return N >= 1 && N <= L && (l + 1) % N == 0; }
+
+int trigger_of(int N, int o) {
+  // first layer of the group; one layer ahead when every layer is offloaded (N == 1)
+  const int lead = N > 1 ? N - 1 : 1;
+  return o >= lead ? o - lead : 0;
+}
+
+int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total) {
+  // Walk the offloaded layers in order.  `now` is the compute stream's clock at the
+  // start of the layer under consideration, `copy_idle` the time the (single, FIFO)
+  // copy stream runs dry.  Prefix sums give the clock at any trigger layer without
+  // stepping through resident layers one by one; stalls shift everything after them.
+  std::vector<int64_t> pre(L + 1, 0);
+  for (int l = 0; l < L; ++l) pre[l + 1] = pre[l] + tc[l];
+  int64_t shift = 0;        // total stall so far
+  int64_t copy_idle = 0;
+  int64_t stalls = 0;
+  const int K = offloaded_count(L, N);
+  // Stalls at offloaded layers strictly before a trigger layer delay that trigger.
+  // Offloaded layers are visited in increasing order; a trigger g_k may precede the
+  // previous offloaded layer only when N == 1, where g_k = o_k - 1 = o_{k-1}: the
+  // trigger fires at the *start* of o_{k-1}, i.e. before that layer's own stall.
+  std::vector<int64_t> shift_before(L + 1, 0);   // stall accumulated before layer l starts waiting
+  int next_fill = 0;
+  for (int k = 1; k <= K; ++k) {
+    const int o = k * N - 1;
+    const int g = trigger_of(N, o);
+    for (; next_fill <= o; ++next_fill) shift_before[next_fill] = shift;
+    const int64_t issue = pre[g] + shift_before[g];
+    const int64_t begin = std::max(copy_idle, issue);
+    copy_idle = begin + tx[o];
+    const int64_t arrive_at_fence = pre[o] + shift;
+    const int64_t wait = std::max<int64_t>(0, copy_idle - arrive_at_fence);
+    stalls += wait;
+    shift += wait;
+  }
+  if (stall_total) *stall_total = stalls;
+  return pre[L] + shift;
+}
+
+int min_interval(int L, const int64_t* tc, const int64_t* tx, int64_t slo) {
+  // Measured layer times need not make T(N) monotone in N, so every N is tried.
+  for (int N = 1; N <= L; ++N)
+    if (iteration_time(L, tc, tx, N, nullptr) <= slo) return N;
+  int64_t all = 0;
+  for (int l = 0; l < L; ++l) all += tc[l];
+  return all <= slo ? L + 1 : -1;
+}
+
+uint64_t resident_bytes(int L, int N, uint64_t state, uint64_t slot, uint64_t fixed) {
+  const int K = offloaded_count(L, N);
+  return (uint64_t)(L - K) * state + (K ? 2 * slot : 0) + fixed;
+}
+
+int max_interval(int L, uint64_t budget, uint64_t state, uint64_t slot, uint64_t fixed) {
+  if (budget == 0) return L + 1;
+  int best = 0;
+  for (int N = 1; N <= L + 1; ++N)
+    if (resident_bytes(L, N, state, slot, fixed) <= budget) best = N;
+  return best;
+}
+
+int32_t paper_rule(int L, int64_t t_trans, int64_t slo) {
+  if (t_trans <= 0) return 1;
+  const int64_t l_off = slo / t_trans;
+  return (int32_t)(L / (l_off + 1) + 1);
+}
+
+}  // namespace sn

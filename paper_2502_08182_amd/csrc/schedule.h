@@ -1,0 +1,14 @@
+// Host-only schedule arithmetic (placement, timeline, picker, capacity bound).
+#pragma once
+#include <stdint.h>
+
+namespace sn {
+int offloaded_count(int L, int N);
+bool is_offloaded(int L, int N, int l);
+int trigger_of(int N, int offloaded_layer);
+int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total);
+int min_interval(int L, const int64_t* tc, const int64_t* tx, int64_t slo);   // -1: none
+uint64_t resident_bytes(int L, int N, uint64_t state, uint64_t slot, uint64_t fixed);
+int max_interval(int L, uint64_t budget, uint64_t state, uint64_t slot, uint64_t fixed);
+int32_t paper_rule(int L, int64_t t_trans, int64_t slo);
+}  // namespace sn

@@ -1,0 +1,235 @@
+"""End-to-end GPU parity through the C ABI (sn_init / sn_place / sn_step / profiler /
+picker) against the CPU oracle, plus the invariants the method promises:
+the output does not depend on the offloading interval (bit-identical runs), the picked
+interval equals the oracle's for the same measured times, error paths return codes."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import forward as ofw
+from oracle import schedule as osch
+from paper_2502_08182_amd import sn, synth
+from paper_2502_08182_amd.runner import Session
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2      # max |delta| <= 2e-2 x RMS(oracle output): fp16/bf16 storage, fp32 accumulation
+
+
+def rms(a):
+    return math.sqrt(float((a ** 2).mean()))
+
+
+def oracle_run(w, layers_bits, prompt_bits, table_bits):
+    s = w.shape
+    layers = [synth.widen_layer(s, t) for t in layers_bits]
+    return ofw.run_workload(s.as_dict(), layers, synth.widen(prompt_bits, s.dtype), w.prompt_lens,
+                            synth.widen(table_bits, s.dtype))
+
+
+def gpu_run(w, layers_bits, prompt_bits, table_bits, N, max_tokens=0):
+    with Session(w.shape, w.batch, w.max_seq, max_tokens) as se:
+        se.load_synthetic_weights(layers=layers_bits)
+        se.place(N)
+        pre, dec = se.run_workload(w, prompt_bits, table_bits)
+        st = se.stats()
+    return pre, dec, st
+
+
+def assert_close(got_bits, want, dtype, what):
+    got = synth.widen(got_bits, dtype)
+    assert np.isfinite(got).all(), what
+    err = float(np.abs(got - want).max())
+    r = rms(want)
+    print(f"{what}: max|d|={err:.4e} = {err / r:.3e} x RMS ({r:.3e})", flush=True)
+    assert err <= TOL * r, (what, err, r)
+
+
+def _inputs(w):
+    layers = [synth.make_layer(w.shape, l, 0) for l in range(w.shape.n_layers)]
+    return layers, synth.make_prompt(w), synth.make_decode_table(w)
+
+
+@pytest.fixture(scope="module")
+def c1():
+    w = synth.workload("c1")
+    layers, prompt, table = _inputs(w)
+    pre, dec = oracle_run(w, layers, prompt, table)
+    return w, layers, prompt, table, pre, dec
+
+
+def test_config1_matches_oracle_at_interval_2(c1):
+    w, layers, prompt, table, pre, dec = c1
+    gpre, gdec, st = gpu_run(w, layers, prompt, table, 2)
+    assert st["interval"] == 2 and st["n_offloaded"] == 2
+    assert_close(gpre, pre, w.shape.dtype, "c1 prefill")
+    for t in range(w.decode_steps):
+        assert_close(gdec[t], dec[t], w.shape.dtype, f"c1 decode step {t}")
+
+
+def test_output_is_bit_identical_for_every_interval(c1):
+    w, layers, prompt, table, *_ = c1
+    ref = gpu_run(w, layers, prompt, table, 0)                 # everything resident
+    assert ref[2]["n_offloaded"] == 0 and ref[2]["h2d_bytes"] == 0
+    for N in (1, 2, 3, 4):
+        got = gpu_run(w, layers, prompt, table, N)
+        assert got[2]["n_offloaded"] == w.shape.n_layers // N
+        assert got[2]["h2d_bytes"] > 0
+        assert np.array_equal(got[0], ref[0]), f"prefill differs at N={N}"
+        assert np.array_equal(got[1], ref[1]), f"decode differs at N={N}"
+
+
+def test_replacing_between_iterations_keeps_the_cache(c1):
+    """Sec. 4.2: a new interval is applied before the next iteration; live KV must move with it."""
+    w, layers, prompt, table, *_ = c1
+    ref = gpu_run(w, layers, prompt, table, 0)
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        se.load_synthetic_weights(layers=layers)
+        se.place(2)
+        se.kv_reset([p + w.decode_steps for p in w.prompt_lens])
+        pre = se.step(list(w.prompt_lens), True, prompt)
+        outs = []
+        for t, N in enumerate([1, 3, 0, 2, 4, 1, 0, 2]):
+            se.place(N)
+            outs.append(se.step([1] * w.batch, False, table[t]))
+    assert np.array_equal(pre, ref[0])
+    assert np.array_equal(np.stack(outs), ref[1])
+
+
+@pytest.mark.parametrize("name", ["c2t", "c3t", "c4t", "c5t"])
+def test_truncated_real_shapes_match_oracle(name):
+    w = synth.workload(name)
+    layers, prompt, table = _inputs(w)
+    pre, dec = oracle_run(w, layers, prompt, table)
+    N = w.intervals[0]
+    gpre, gdec, st = gpu_run(w, layers, prompt, table, N)
+    assert_close(gpre, pre, w.shape.dtype, f"{name} prefill")
+    for t in range(w.decode_steps):
+        assert_close(gdec[t], dec[t], w.shape.dtype, f"{name} decode {t}")
+    ref = gpu_run(w, layers, prompt, table, 0)
+    assert np.array_equal(gpre, ref[0]) and np.array_equal(gdec, ref[1])
+
+
+@pytest.mark.parametrize("batch", [17, 33, 64])
+def test_decode_batches_spanning_row_tiles(batch):
+    base = synth.workload("c1")
+    shape = synth.ModelShape(2, 256, 8, 2, 64, 512, act="swiglu", norm="rms", rope=True, has_bias=False, dtype="bf16")
+    lens = tuple(int(v) for v in np.random.default_rng(batch).integers(1, 40, size=batch))
+    w = synth.Workload("mix", shape, batch, lens, 2)
+    layers, prompt, table = _inputs(w)
+    pre, dec = oracle_run(w, layers, prompt, table)
+    gpre, gdec, _ = gpu_run(w, layers, prompt, table, 2)
+    assert_close(gpre, pre, shape.dtype, f"B={batch} prefill")
+    for t in range(2):
+        assert_close(gdec[t], dec[t], shape.dtype, f"B={batch} decode {t}")
+
+
+def test_chunked_prefill_equals_oracle(c1):
+    w, layers, prompt, table, pre, dec = c1
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        se.load_synthetic_weights(layers=layers)
+        se.place(2)
+        se.kv_reset([p + w.decode_steps for p in w.prompt_lens])
+        # sequence 0: 20 + 12 tokens, sequence 1: 5 + 27
+        a = np.concatenate([prompt[0:20], prompt[32:37]])
+        b = np.concatenate([prompt[20:32], prompt[37:64]])
+        oa = se.step([20, 5], True, a)
+        ob = se.step([12, 27], True, b)
+        d0 = se.step([1, 1], False, table[0])
+    got = np.concatenate([oa[:20], ob[:12], oa[20:], ob[12:]])
+    assert_close(got, pre, w.shape.dtype, "chunked prefill")
+    assert_close(d0, dec[0], w.shape.dtype, "decode after chunked prefill")
+
+
+def test_profiler_and_picker_agree_with_oracle(c1):
+    w, layers, *_ = c1
+    L = w.shape.n_layers
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        se.load_synthetic_weights(layers=layers)
+        se.place(2)
+        for is_prefill in (False, True):
+            tc, tx = sn.sn_profile_layers(se.ctx, L, is_prefill, 2, 32, reps=3)
+            assert (tc > 0).all() and (tx > 0).all()
+            print("prefill" if is_prefill else "decode", "tc", tc.tolist(), "tx", tx.tolist(), flush=True)
+            n_max = sn.sn_max_interval(se.ctx)
+            assert n_max == L + 1                                   # no budget: no upper limit
+            base = int(tc.sum())
+            for factor in (0.9, 1.0, 1.2, 1.5, 2.0, 5.0, 50.0):
+                slo_ns = int(base * factor)
+                want = osch.pick_interval(tc.tolist(), tx.tolist(), slo_ns, n_max)
+                if want is None:
+                    with pytest.raises(sn.SnError) as e:
+                        sn.sn_pick_interval(se.ctx, slo_ns / 1e6)
+                    assert e.value.code == sn.SN_E_INFEASIBLE
+                else:
+                    assert sn.sn_pick_interval(se.ctx, slo_ns / 1e6) == want
+                    assert sn.sn_timeline(tc, tx, want)[0] <= slo_ns
+
+
+def test_budget_and_call_order_errors():
+    w = synth.workload("c1")
+    cs = sn.make_shape(w.shape, w.batch, w.max_seq)
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        x = torch.zeros(2, 256, dtype=torch.int16, device="cuda")
+        lens = np.zeros(2, dtype=np.int32)
+        with pytest.raises(sn.SnError) as e:
+            sn.sn_step(se.ctx, [1, 1], False, x, lens, x)
+        assert e.value.code == sn.SN_E_STATE                       # before sn_place
+        with pytest.raises(sn.SnError) as e:
+            sn.sn_pick_interval(se.ctx, 1.0)
+        assert e.value.code == sn.SN_E_STATE                       # before a profile
+        se.place(2)
+        with pytest.raises(sn.SnError) as e:
+            sn.sn_step(se.ctx, [1, 1], False, x, lens, x)
+        assert e.value.code == sn.SN_E_STATE                       # before sn_kv_reset
+        se.kv_reset([4, 4])
+        with pytest.raises(sn.SnError) as e:
+            sn.sn_step(se.ctx, [5, 1], True, x, se.kv_len, x)      # over capacity
+        assert e.value.code == sn.SN_E_INVAL
+        with pytest.raises(sn.SnError) as e:
+            sn.sn_kv_reset(se.ctx, [w.max_seq * 2, w.max_seq])
+        assert e.value.code == sn.SN_E_INVAL
+        full = sn.sn_resident_bytes(se.ctx, 0)
+        r = [sn.sn_resident_bytes(se.ctx, N) for N in range(1, 6)]
+        state = (r[1] - r[0]) // 2                                 # N=1 -> N=2 makes two more layers resident
+        assert r[4] == full and r[0] == full - 2 * state          # N=1: no resident layer, two slots
+        assert r[2] == r[3] == full + state                        # one offloaded layer + two slots
+        assert r == sorted(r[:4]) + [full]
+    # a budget that only N = 1 fits
+    ctx = sn.sn_init(cs, r[0], 0)
+    try:
+        assert sn.sn_max_interval(ctx) == 1
+        sn.sn_place(ctx, 1)
+        with pytest.raises(sn.SnError) as e:
+            sn.sn_place(ctx, 2)
+        assert e.value.code == sn.SN_E_BUDGET
+        sn.sn_set_budget_enforce(ctx, False)
+        sn.sn_place(ctx, 2)                                        # over the cap, allowed when enforcement is off
+    finally:
+        sn.sn_destroy(ctx)
+    ctx = sn.sn_init(cs, r[0] - 1, 0)
+    try:
+        assert sn.sn_max_interval(ctx) == 0
+        with pytest.raises(sn.SnError) as e:
+            sn.sn_place(ctx, 1)
+        assert e.value.code == sn.SN_E_BUDGET
+    finally:
+        sn.sn_destroy(ctx)
+
+
+def test_stall_and_hidden_fraction_are_reported(c1):
+    w, layers, prompt, table, *_ = c1
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        se.load_synthetic_weights(layers=layers)
+        se.place(2)
+        sn.sn_set_timing(se.ctx, 2)
+        se.run_workload(w, prompt, table)
+        st = se.stats()
+        comp, stall, h2d = sn.sn_get_layer_times(se.ctx, w.shape.n_layers)
+    print(st, comp.tolist(), stall.tolist(), h2d.tolist(), flush=True)
+    assert st["iter_ns"] > 0 and st["h2d_ns"] > 0 and 0.0 <= st["hidden_fraction"] <= 1.0
+    assert st["h2d_bytes"] > 0 and st["h2d_bytes"] % 2 == 0 and st["n_offloaded"] == 2
+    assert (comp > 0).all() and stall[0] == 0 and stall[2] == 0 and h2d[1] > 0 and h2d[3] > 0
+    assert st["kernel_calls"]["ffn_up"] == w.shape.n_layers and st["kernel_ns"]["ffn_up"] > 0

@@ -1,0 +1,239 @@
+"""GPU parity of each layer kernel against the matching piece of the CPU oracle, through
+the per-kernel C ABI.  Sizes span several tiles and ragged tails.  Tolerances: the
+kernels accumulate in fp32 and round once to the 16-bit output type, so the bound used
+is a few output ulps relative to the RMS of the expected tensor -- far inside the
+end-to-end bar of 2e-2 x RMS."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import forward as ofw
+from paper_2502_08182_amd import sn, synth
+from paper_2502_08182_amd import sn_kernels as K
+
+pytestmark = pytest.mark.gpu
+
+DT = {"f16": sn.SN_F16, "bf16": sn.SN_BF16}
+TOL = {"f16": 2.5e-3, "bf16": 1.2e-2}     # x RMS(expected); >= 4 ulp of the output type at 1 RMS... see docstring
+
+
+def dev16(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+
+
+def host16(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def rms(a):
+    return math.sqrt(float((np.asarray(a, dtype=np.float64) ** 2).mean()))
+
+
+def check(got, want, dtype, what, factor=1.0):
+    err = float(np.abs(got - want).max())
+    bound = TOL[dtype] * factor * rms(want)
+    print(f"{what}: max|d|={err:.3e} bound={bound:.3e} rms={rms(want):.3e}", flush=True)
+    assert np.isfinite(got).all(), what
+    assert err <= bound, (what, err, bound)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("is_ln", [True, False])
+def test_norm(dtype, is_ln):
+    rng = np.random.default_rng(1)
+    T, h = 37, 1184
+    x = (rng.standard_normal((T, h)) * 3 + 0.5).astype(np.float32)
+    g = synth.to_bits(1 + 0.1 * rng.standard_normal(h), dtype)
+    b = synth.to_bits(0.1 * rng.standard_normal(h), dtype)
+    out = torch.zeros(T, h, dtype=torch.int16, device="cuda")
+    K.sn_k_norm(DT[dtype], is_ln, torch.from_numpy(x).cuda(), dev16(g), dev16(b), out, T, h, 1e-5)
+    torch.cuda.synchronize()
+    got = synth.widen(host16(out), dtype)
+    x64 = x.astype(np.float64)
+    want = (ofw.layer_norm(x64, synth.widen(g, dtype), synth.widen(b, dtype), 1e-5) if is_ln
+            else ofw.rms_norm(x64, synth.widen(g, dtype), 1e-5))
+    check(got, want, dtype, f"norm ln={is_ln}")
+
+
+def _gemm_case(dtype, path, epi, M, N, Kd, bias, seed):
+    rng = np.random.default_rng(seed)
+    Wrows = 2 * N if epi == K.EPI_SWIGLU16 else N
+    xb = synth.to_bits(rng.standard_normal((M, Kd)), dtype)
+    if epi == K.EPI_SWIGLU16:
+        wg = synth.to_bits(rng.standard_normal((N, Kd)) * 0.05, dtype)
+        wu = synth.to_bits(rng.standard_normal((N, Kd)) * 0.05, dtype)
+        tiled = np.zeros(2 * N * Kd, dtype=np.uint16)
+        K.sn_k_tile_weights(wg, N, Kd, tiled, 2, 0)
+        K.sn_k_tile_weights(wu, N, Kd, tiled, 2, 1)
+    else:
+        wb = synth.to_bits(rng.standard_normal((N, Kd)) * 0.05, dtype)
+        tiled = K.sn_k_tile_weights(wb, N, Kd)
+    bb = synth.to_bits(rng.standard_normal(Wrows) * 0.3, dtype) if bias else None
+    x64 = synth.widen(xb, dtype)
+    b64 = synth.widen(bb, dtype) if bias else np.zeros(Wrows)
+    if epi == K.EPI_RESID32:
+        r0 = rng.standard_normal((M, N)).astype(np.float32)
+        out = torch.from_numpy(r0.copy()).cuda()
+    else:
+        out = torch.full((M, N), 0x7e00 if dtype == "f16" else 0x7fc0, dtype=torch.int16, device="cuda")
+    K.sn_k_gemm(DT[dtype], epi, path, dev16(tiled), dev16(xb), dev16(bb) if bias else None, out, M, Wrows, Kd)
+    torch.cuda.synchronize()
+    if epi == K.EPI_SWIGLU16:
+        g = x64 @ synth.widen(wg, dtype).T + b64[:N]
+        u = x64 @ synth.widen(wu, dtype).T + b64[N:]
+        want = ofw.silu(g) * u
+    else:
+        lin = x64 @ synth.widen(wb, dtype).T + b64
+        want = {K.EPI_STORE16: lin, K.EPI_GELU16: ofw.gelu(lin), K.EPI_RESID32: r0.astype(np.float64) + lin}[epi]
+    got = out.cpu().numpy().astype(np.float64) if epi == K.EPI_RESID32 else synth.widen(host16(out), dtype)
+    check(got, want, dtype, f"gemm path={path} epi={epi} M={M} N={N} K={Kd} bias={bias}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("epi", [0, 1, 2, 3])
+def test_gemm_skinny(dtype, epi):
+    for i, M in enumerate([1, 8, 17, 33, 64]):
+        _gemm_case(dtype, K.PATH_SKINNY, epi, M, 192, 416, bias=(i % 2 == 0), seed=10 + i)
+    _gemm_case(dtype, K.PATH_SKINNY, epi, 5, 4096, 1024, bias=True, seed=20)     # 16-way K split
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("epi", [0, 1, 2, 3])
+def test_gemm_tile(dtype, epi):
+    for i, M in enumerate([1, 127, 300]):
+        _gemm_case(dtype, K.PATH_TILE, epi, M, 192, 416, bias=(i % 2 == 0), seed=30 + i)
+    _gemm_case(dtype, K.PATH_TILE, epi, 130, 384, 64, bias=True, seed=40)
+
+
+def _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope):
+    """Random qkv rows for the new tokens and a random cache prefix; returns device index
+    arrays, device buffers and float64 views for the oracle."""
+    B = len(caps)
+    T = sum(n_new)
+    qkv = synth.to_bits(rng.standard_normal((T, (Hq + 2 * Hkv) * d)), dtype)
+    kv_off = np.concatenate([[0], np.cumsum(caps)[:-1]]).astype(np.int32)
+    kv = np.zeros(int(sum(caps)) * 2 * Hkv * d, dtype=np.uint16)
+    Kc, Vc = [], []
+    for b in range(B):
+        kb = synth.to_bits(rng.standard_normal((lens_before[b], Hkv, d)), dtype)
+        vb = synth.to_bits(rng.standard_normal((lens_before[b], Hkv, d)), dtype)
+        Kc.append(kb)
+        Vc.append(vb)
+        base = int(kv_off[b]) * 2 * Hkv * d
+        blk = kv[base: base + caps[b] * 2 * Hkv * d].reshape(Hkv, 2, caps[b], d)
+        blk[:, 0, :lens_before[b]] = kb.transpose(1, 0, 2)
+        blk[:, 1, :lens_before[b]] = vb.transpose(1, 0, 2)
+    tok_seq = np.concatenate([[b] * n_new[b] for b in range(B)]).astype(np.int32)
+    tok_pos = np.concatenate([np.arange(lens_before[b], lens_before[b] + n_new[b]) for b in range(B)]).astype(np.int32)
+    tok_start = np.concatenate([[0], np.cumsum(n_new)[:-1]]).astype(np.int32)
+    inv_freq = (10000.0 ** (-2.0 * np.arange(d // 2) / d)).astype(np.float32)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+    dev = dict(qkv=dev16(qkv), kv=dev16(kv), tok_seq=i32(tok_seq), tok_pos=i32(tok_pos), kv_off=i32(kv_off),
+               cap=i32(caps), len_before=i32(lens_before), n_new=i32(n_new), tok_start=i32(tok_start),
+               inv_freq=torch.from_numpy(inv_freq).cuda())
+    return qkv, Kc, Vc, kv_off, tok_start, dev
+
+
+def _oracle_attention(dtype, qkv, Kc, Vc, lens_before, n_new, tok_start, Hq, Hkv, d, rope):
+    outs, k_new, v_new, q_rot = [], [], [], []
+    for b in range(len(n_new)):
+        rows = synth.widen(qkv[tok_start[b]: tok_start[b] + n_new[b]], dtype)
+        q = rows[:, :Hq * d].reshape(-1, Hq, d)
+        k = rows[:, Hq * d:(Hq + Hkv) * d].reshape(-1, Hkv, d)
+        v = rows[:, (Hq + Hkv) * d:].reshape(-1, Hkv, d)
+        pos = np.arange(lens_before[b], lens_before[b] + n_new[b])
+        if rope:
+            q = ofw.rope(q, pos[:, None], 10000.0)
+            k = ofw.rope(k, pos[:, None], 10000.0)
+        k = ofw.round_to_storage(k, dtype)
+        v = ofw.round_to_storage(v, dtype)
+        Kf = np.concatenate([synth.widen(Kc[b], dtype), k], axis=0)
+        Vf = np.concatenate([synth.widen(Vc[b], dtype), v], axis=0)
+        outs.append(ofw.causal_attention(q, Kf, Vf, lens_before[b]).reshape(n_new[b], Hq * d))
+        k_new.append(k)
+        v_new.append(v)
+        q_rot.append(q)
+    return np.concatenate(outs, axis=0), k_new, v_new, q_rot
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,rope", [("f16", 4, 4, 64, False), ("bf16", 8, 8, 128, True),
+                                                 ("bf16", 16, 2, 128, True), ("f16", 6, 3, 64, True)])
+def test_rope_append_and_attn_decode(dtype, Hq, Hkv, d, rope):
+    rng = np.random.default_rng(3)
+    lens_before = [0, 1, 130, 517, 63]
+    B = len(lens_before)
+    caps = [l + 3 for l in lens_before]
+    n_new = [1] * B
+    qkv, Kc, Vc, kv_off, tok_start, dv = _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope)
+    mirror = torch.zeros_like(dv["kv"])
+    K.sn_k_rope_append(DT[dtype], dv["qkv"], dv["tok_seq"], dv["tok_pos"], dv["kv_off"], dv["cap"], dv["kv"], mirror,
+                       dv["inv_freq"], B, Hq, Hkv, d, rope)
+    want, k_new, v_new, q_rot = _oracle_attention(dtype, qkv, Kc, Vc, lens_before, n_new, tok_start, Hq, Hkv, d, rope)
+    torch.cuda.synchronize()
+    kv_host = host16(dv["kv"])
+    mir_host = host16(mirror)
+    for b in range(B):
+        base = int(kv_off[b]) * 2 * Hkv * d
+        blk = kv_host[base: base + caps[b] * 2 * Hkv * d].reshape(Hkv, 2, caps[b], d)
+        mblk = mir_host[base: base + caps[b] * 2 * Hkv * d].reshape(Hkv, 2, caps[b], d)
+        p = lens_before[b]
+        check(synth.widen(blk[:, 0, p], dtype), k_new[b][0], dtype, f"appended k seq {b}")
+        assert np.array_equal(synth.widen(blk[:, 1, p], dtype), v_new[b][0])          # v is copied bit for bit
+        assert np.array_equal(blk[:, :, p], mblk[:, :, p])                              # mirror gets the same rows
+        assert np.array_equal(blk[:, 0, :p], Kc[b].transpose(1, 0, 2))                  # the prefix is untouched
+        assert not mblk[:, :, :p].any() and not mblk[:, :, p + 1:].any()
+    q_got = synth.widen(host16(dv["qkv"]), dtype)[:, :Hq * d].reshape(B, Hq, d)
+    check(q_got, np.concatenate(q_rot, axis=0), dtype, "rotated q")
+    for S in (0, 1, 3, 16):
+        out = torch.zeros(B, Hq * d, dtype=torch.int16, device="cuda")
+        part = torch.zeros(B * Hq * 16 * (d + 2), dtype=torch.float32, device="cuda")
+        K.sn_k_attn_decode(DT[dtype], dv["qkv"], dv["kv"], dv["len_before"], dv["kv_off"], dv["cap"], out, part, B, Hq,
+                           Hkv, d, S, max(lens_before) + 1)
+        torch.cuda.synchronize()
+        check(synth.widen(host16(out), dtype), want, dtype, f"attn_decode S={S}", factor=2.0)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,rope", [("f16", 4, 4, 64, False), ("bf16", 8, 8, 128, True),
+                                                 ("bf16", 8, 2, 128, True)])
+def test_attn_prefill(dtype, Hq, Hkv, d, rope):
+    rng = np.random.default_rng(4)
+    lens_before = [0, 0, 40, 0]
+    n_new = [1, 64, 37, 150]          # single token, exact tile, chunk on top of a cached prefix, ragged multi-tile
+    B = len(n_new)
+    caps = [lens_before[b] + n_new[b] + 2 for b in range(B)]
+    qkv, Kc, Vc, kv_off, tok_start, dv = _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope)
+    T = sum(n_new)
+    K.sn_k_rope_append(DT[dtype], dv["qkv"], dv["tok_seq"], dv["tok_pos"], dv["kv_off"], dv["cap"], dv["kv"], None,
+                       dv["inv_freq"], T, Hq, Hkv, d, rope)
+    tile_seq, tile_q0 = [], []
+    for b in range(B):
+        for q0 in range(0, n_new[b], 64):
+            tile_seq.append(b)
+            tile_q0.append(q0)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+    out = torch.zeros(T, Hq * d, dtype=torch.int16, device="cuda")
+    K.sn_k_attn_prefill(DT[dtype], dv["qkv"], dv["kv"], dv["len_before"], dv["n_new"], dv["tok_start"], dv["kv_off"],
+                        dv["cap"], i32(tile_seq), i32(tile_q0), out, len(tile_seq), Hq, Hkv, d)
+    torch.cuda.synchronize()
+    want, *_ = _oracle_attention(dtype, qkv, Kc, Vc, lens_before, n_new, tok_start, Hq, Hkv, d, rope)
+    check(synth.widen(host16(out), dtype), want, dtype, "attn_prefill", factor=2.0)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_casts_are_exact(dtype):
+    rng = np.random.default_rng(5)
+    bits = synth.to_bits(rng.standard_normal(5000) * 4, dtype)
+    x = torch.zeros(5000, dtype=torch.float32, device="cuda")
+    K.sn_k_cast_in(DT[dtype], dev16(bits), x, 5000)
+    back = torch.zeros(5000, dtype=torch.int16, device="cuda")
+    K.sn_k_cast_out(DT[dtype], x, back, 5000)
+    torch.cuda.synchronize()
+    assert np.array_equal(x.cpu().numpy().astype(np.float64), synth.widen(bits, dtype))
+    assert np.array_equal(host16(back), bits)
+    # rounding fp32 -> 16 bit is nearest-even, as the oracle's storage rounding
+    f = (rng.standard_normal(5000) * 4).astype(np.float32)
+    K.sn_k_cast_out(DT[dtype], torch.from_numpy(f).cuda(), back, 5000)
+    torch.cuda.synchronize()
+    assert np.array_equal(synth.widen(host16(back), dtype), ofw.round_to_storage(f.astype(np.float64), dtype))

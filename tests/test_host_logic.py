@@ -1,0 +1,141 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header
+declares, and its host-side schedule arithmetic (placement, timeline, picker, capacity
+bound, closed form) agrees exactly with the oracle.  No GPU compute is called."""
+import ctypes
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+
+from oracle import schedule as osch
+from paper_2502_08182_amd import sn, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions(header="sn.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sn_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert len(names) >= 18
+    L = sn.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(sn.EXPORTS) == names          # the binding covers exactly the header
+    from paper_2502_08182_amd import sn_kernels
+    knames = _declared_functions("sn_kernels.h")
+    for n in knames:
+        assert hasattr(L, n), n
+    assert sorted(sn_kernels.EXPORTS) == knames
+
+
+def test_weight_tiling_is_a_permutation_with_the_documented_index():
+    from paper_2502_08182_amd import sn_kernels
+    N, K = 48, 96
+    src = np.arange(N * K, dtype=np.uint16).reshape(N, K)
+    dst = sn_kernels.sn_k_tile_weights(src, N, K)
+    assert sorted(dst.tolist()) == sorted(src.reshape(-1).tolist())
+    for n, k in [(0, 0), (5, 7), (17, 40), (47, 95), (31, 64), (16, 31)]:
+        at = ((n // 16) * (K // 32) + k // 32) * 512 + ((n % 16) + 16 * ((k % 32) // 8)) * 8 + k % 8
+        assert dst[at] == src[n, k]
+    # interleaving two matrices block by block (gate / up)
+    a = np.full((32, 32), 1, dtype=np.uint16)
+    b = np.full((32, 32), 2, dtype=np.uint16)
+    out = np.zeros(2 * 32 * 32, dtype=np.uint16)
+    sn_kernels.sn_k_tile_weights(a, 32, 32, out, 2, 0)
+    sn_kernels.sn_k_tile_weights(b, 32, 32, out, 2, 1)
+    assert out.reshape(4, 512)[:, 0].tolist() == [1, 2, 1, 2]
+
+
+def test_struct_sizes_match_header():
+    assert ctypes.sizeof(sn.sn_model_shape) == 16 * 4
+    assert ctypes.sizeof(sn.sn_step_stats) == 6 * 8 + 8 + 2 * 4 + 8 + 8 * 8 + 8 * 4
+
+
+def test_placement_matches_oracle_and_fig7():
+    off, trig = sn.sn_placement(8, 4)
+    assert list(np.nonzero(off)[0] + 1) == [4, 8]               # Fig. 7, layers counted from 1
+    assert [int(trig[3]) + 1, int(trig[7]) + 1] == [1, 5]
+    for L in range(1, 34):
+        for N in range(0, L + 3):
+            off, trig = sn.sn_placement(L, N)
+            want = osch.offloaded_layers(L, N)
+            assert list(np.nonzero(off)[0]) == want
+            assert [int(trig[o]) for o in want] == osch.trigger_layers(L, N)
+            assert all(int(trig[l]) == -1 for l in range(L) if not off[l])
+
+
+def test_timeline_matches_oracle():
+    rnd = random.Random(11)
+    for _ in range(3000):
+        L = rnd.randint(1, 40)
+        tc = [rnd.randint(0, 5000) for _ in range(L)]
+        tx = [rnd.randint(0, 40000) for _ in range(L)]
+        N = rnd.randint(0, L + 2)
+        T, stalls = osch.timeline(tc, tx, N)
+        assert sn.sn_timeline(tc, tx, N) == (T, sum(stalls)), (tc, tx, N)
+
+
+def test_picker_matches_oracle():
+    rnd = random.Random(12)
+    seen = {"ok": 0, "none": 0}
+    for _ in range(2000):
+        L = rnd.randint(1, 32)
+        tc = [rnd.randint(1, 3000) for _ in range(L)]
+        tx = [rnd.randint(0, 30000) for _ in range(L)]
+        slo = rnd.randint(1, 3 * sum(tc))
+        n_max = rnd.randint(0, L + 1)
+        want = osch.pick_interval(tc, tx, slo, n_max)
+        if want is None:
+            with pytest.raises(sn.SnError) as e:
+                sn.sn_pick_interval_from_times(tc, tx, slo, n_max)
+            assert e.value.code == sn.SN_E_INFEASIBLE
+            seen["none"] += 1
+        else:
+            assert sn.sn_pick_interval_from_times(tc, tx, slo, n_max) == want
+            seen["ok"] += 1
+    assert seen["ok"] > 200 and seen["none"] > 200
+
+
+def test_paper_rule_matches_oracle():
+    rnd = random.Random(13)
+    for _ in range(2000):
+        L, c, x = rnd.randint(1, 80), rnd.randint(1, 500), rnd.randint(1, 60000)
+        slo = rnd.randint(1, 4 * L * c)
+        assert sn.sn_paper_rule(L, x, slo) == osch.paper_rule(L, c, x, slo)
+
+
+def test_bad_arguments_are_errors_not_crashes():
+    with pytest.raises(sn.SnError) as e:
+        sn.sn_timeline([1, 2], [-1, 0], 1)
+    assert e.value.code == sn.SN_E_INVAL
+    with pytest.raises(sn.SnError):
+        sn.sn_pick_interval_from_times([1], [-5], 10, 2)
+    bad = sn.make_shape(synth.workload("c1").shape, 2, 40)
+    bad.head_dim = 48
+    assert sn.sn_layer_blob_bytes(bad) == 0
+    with pytest.raises(sn.SnError) as e:
+        sn.sn_init(bad)
+    assert e.value.code == sn.SN_E_INVAL and "head_dim" in str(e.value)
+
+
+def test_blob_layout_matches_generator():
+    for name in ("c1", "c2t", "c3t", "c5t"):
+        w = synth.workload(name)
+        _, total = synth.blob_layout(w.shape)
+        assert sn.sn_layer_blob_bytes(sn.make_shape(w.shape, 2, 64)) == total
+
+
+def test_init_without_gpu_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(sn.SnError) as e:
+        sn.sn_init(sn.make_shape(synth.workload("c1").shape, 2, 40))
+    assert e.value.code == sn.SN_E_HIP
