@@ -1,0 +1,281 @@
+#!/usr/bin/env python3
+"""Benchmark of the offloaded serving iteration on one MI355X.
+
+Workload: the OPT-6.7B-shaped configuration (32 layers, hidden 4096, 32 heads, GELU FFN
+16384, fp16 random weights, batch 8, prompt 512, teacher-forced decode), HBM budget
+8 GB, TPOT SLO = 2 x the all-resident decode step.  One "step" is one decode iteration
+of the whole layer loop (all kernels, prefetches and fences) at the interval the
+picker chooses from the measured per-layer compute and transfer times.
+
+Prints ONE JSON line (metric / value / roofline / cpu_baseline ...).  Inputs are
+resident in HBM before the timed region.  Every timed iteration is synchronised and
+checked against the SLO, which is how a serving loop consumes a decode step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
+LINK_NOMINAL = 64.0e9      # bytes/s per direction, PCIe Gen5 x16 host link
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--slo-factor", type=float, default=2.0)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the interval sweep report")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--distinct-layers", type=int, default=0,
+                    help="draw only this many different random layer blobs (0: every layer its own)")
+    return ap.parse_args()
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def read_traffic_note(name):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/<name>), or None."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, n_steps, warmup, timing_class=None):
+    """kv reset -> prefill -> warmup decode steps -> n_steps timed decode steps, each synchronised.
+    Returns per-step stats, wall ms per step and the prefill iteration time."""
+    B = w.batch
+    se.kv_reset([p + warmup + n_steps + 1 for p in w.prompt_lens])
+    sn.sn_set_timing(se.ctx, 0)
+    se.step_device(list(w.prompt_lens), True, x_pre, y_pre)
+    pre = sn.sn_get_stats(se.ctx).as_dict()
+    ones = [1] * B
+    for i in range(warmup):
+        se.step_device(ones, False, x_dec[i % len(x_dec)], y_dec)
+    se.stream.synchronize()
+    if timing_class is not None:
+        sn.sn_set_timing(se.ctx, 2)
+        sn.sn_set_kernel_timing_class(se.ctx, timing_class)
+    stats = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n_steps):
+        se.step_device(ones, False, x_dec[i % len(x_dec)], y_dec)
+        stats.append(sn.sn_get_stats(se.ctx))          # synchronises the iteration
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / n_steps
+    sn.sn_set_timing(se.ctx, 0)
+    return [s.as_dict() for s in stats], wall_ms, pre
+
+
+def cpu_baseline(w, seconds_target=12.0):
+    """The CPU oracle on one layer of one decode step at the real shape (bounded sample)."""
+    from oracle import forward as ofw
+    from paper_2502_08182_amd import synth
+    s = w.shape
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    layer = synth.widen_layer(s, synth.make_layer(s, 0, 0))
+    rng = np.random.default_rng(7)
+    B, P = w.batch, w.prompt_lens[0]
+    kv = [{"k": ofw.round_to_storage(rng.standard_normal((P, s.n_kv_heads, s.head_dim)), s.dtype),
+           "v": ofw.round_to_storage(rng.standard_normal((P, s.n_kv_heads, s.head_dim)), s.dtype)} for _ in range(B)]
+    x = rng.standard_normal((B, s.hidden))
+    sd = s.as_dict()
+    times = []
+    t_all = time.perf_counter()
+    while True:
+        caches = [dict(c) for c in kv]
+        t0 = time.perf_counter()
+        for b in range(B):
+            ofw.layer_forward(sd, layer, x[b:b + 1], caches[b])
+        times.append(time.perf_counter() - t0)
+        if time.perf_counter() - t_all > seconds_target or len(times) >= 8:
+            break
+    t_layer = float(np.median(times))
+    return {"value": B / (t_layer * s.n_layers), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one decode step of ONE layer at the real shape (batch {B}, {P} cached tokens), float64 "
+                      f"numpy, median of {len(times)} runs = {t_layer * 1e3:.1f} ms; tokens/s extrapolated x{s.n_layers} layers"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one model instance per GPU, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2502_08182_amd import sn, synth
+    from paper_2502_08182_amd.runner import Session
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    w = synth.workload(a.workload)
+    s = w.shape
+    L, B = s.n_layers, w.batch
+    K, W = a.steps, a.warmup
+    max_seq = max(w.prompt_lens) + K + W + 2
+    t_start = time.time()
+    se = Session(s, B, max_seq, hbm_budget=w.hbm_budget)
+    sn.sn_set_budget_enforce(se.ctx, False)     # over-cap intervals are run and labelled, not refused
+    log(f"[bench] {w.name}: L={L} h={s.hidden} heads={s.n_q_heads}/{s.n_kv_heads} ffn={s.ffn} {s.dtype} "
+        f"B={B} P={w.prompt_lens[0]} budget={w.hbm_budget / 1e9:.1f} GB")
+    se.load_device_generated_weights(seed=0, distinct=a.distinct_layers)
+    log(f"[bench] weights loaded in {time.time() - t_start:.1f} s")
+
+    tdt = torch.bfloat16 if s.dtype == "bf16" else torch.float16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    T = int(sum(w.prompt_lens))
+    with torch.cuda.stream(se.stream):
+        x_pre = torch.randn(T, s.hidden, generator=g, device="cuda", dtype=torch.float32).to(tdt)
+        y_pre = torch.empty_like(x_pre)
+        g.manual_seed(2)
+        x_dec = [torch.randn(B, s.hidden, generator=g, device="cuda", dtype=torch.float32).to(tdt) for _ in range(8)]
+        y_dec = torch.empty_like(x_dec[0])
+    se.stream.synchronize()
+
+    # ---- all-resident reference: defines the SLO (TPOT without offloading) -------------
+    se.place(0)
+    st0, wall0, pre0 = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, K, W)
+    it0 = np.array([d["iter_ns"] for d in st0], dtype=np.float64)
+    tpot0_ns = float(np.median(it0))
+    slo_ns = int(a.slo_factor * tpot0_ns)
+    log(f"[bench] all-resident: TPOT median {tpot0_ns / 1e6:.3f} ms (max {it0.max() / 1e6:.3f}), wall {wall0:.3f} ms/step, "
+        f"prefill {pre0['iter_ns'] / 1e6:.2f} ms; SLO = {a.slo_factor} x = {slo_ns / 1e6:.3f} ms")
+
+    # ---- profile and pick ------------------------------------------------------------------
+    seq_prof = w.prompt_lens[0] + W + K // 2
+    tc, tx = sn.sn_profile_layers(se.ctx, L, False, B, seq_prof, reps=5)
+    n_max_cap = sn.sn_max_interval(se.ctx)
+    rho = float(np.median(tx) / np.median(tc))
+    try:
+        n_pick_cap = sn.sn_pick_interval(se.ctx, slo_ns / 1e6)
+        feasible_at_cap = True
+    except sn.SnError as e:
+        if e.code != sn.SN_E_INFEASIBLE:
+            raise
+        n_pick_cap, feasible_at_cap = None, False
+    try:
+        n_min = sn.sn_pick_interval_from_times(tc, tx, slo_ns, L + 1)
+    except sn.SnError:
+        n_min = L + 1
+    pred_ns, _ = sn.sn_timeline(tc, tx, n_min)
+    n_paper = sn.sn_paper_rule(L, int(np.median(tx)), slo_ns)
+    log(f"[bench] profile: tc median {np.median(tc) / 1e3:.1f} us, tx median {np.median(tx) / 1e3:.1f} us, rho {rho:.1f}; "
+        f"N_min(SLO)={n_min} N_max(cap)={n_max_cap} feasible_at_cap={feasible_at_cap} paper_rule={n_paper} "
+        f"predicted T(N_min)={pred_ns / 1e6:.3f} ms")
+    n_run = n_pick_cap if feasible_at_cap else n_min
+
+    # ---- the measured run at the picked interval --------------------------------------------
+    se.place(n_run)
+    st, wall_ms, pre = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, K, W, timing_class=5)
+    it = np.array([d["iter_ns"] for d in st], dtype=np.float64)
+    h2d_ns = sum(d["h2d_ns"] for d in st)
+    h2d_bytes = sum(d["h2d_bytes"] for d in st)
+    stall_ns = sum(d["stall_ns"] for d in st)
+    k_ns = sum(d["kernel_ns"]["ffn_up"] for d in st)
+    k_calls = sum(d["kernel_calls"]["ffn_up"] for d in st)
+    value = B * 1e3 / wall_ms
+    # dominant kernel: FFN up-projection weight stream.  Algorithmic bytes per launch:
+    # weights ffn*hidden*2 + bias ffn*2 + activations in B*hidden*2 + out B*ffn*2.
+    n_up = s.ffn * (2 if s.act == "swiglu" else 1)
+    alg_bytes = n_up * s.hidden * 2 + (n_up * 2 if s.has_bias else 0) + B * s.hidden * 2 + B * s.ffn * 2
+    k_avg_ns = k_ns / max(k_calls, 1)
+    achieved = alg_bytes / (k_avg_ns * 1e-9) if k_avg_ns > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel (FFN up-projection, decode)", "achieved": achieved / 1e9,
+                "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": achieved / HBM_PEAK,
+                "traffic": read_traffic_note("gemm_skinny_ffn_up_c2_pmc.txt"),
+                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": k_avg_ns / 1e3, "launches_timed": k_calls}
+    # whole-step HBM roofline: every weight and every cached K/V element is read once per step
+    kvtok = s.kv_bytes_per_token
+    len_mid = w.prompt_lens[0] + W + K // 2
+    step_bytes = L * (sn.sn_layer_blob_bytes(se.cshape) + len_mid * B * kvtok)
+    log(f"[bench] N={n_run}: TPOT median {np.median(it) / 1e6:.3f} ms max {it.max() / 1e6:.3f} ms (SLO {slo_ns / 1e6:.3f}), "
+        f"wall {wall_ms:.3f} ms/step -> {value:.1f} tok/s; ffn_up {k_avg_ns / 1e3:.1f} us = {achieved / 1e9:.0f} GB/s")
+
+    out = {
+        "metric": "decode tok/s at max-offload interval meeting TPOT SLO; HBM + H2D GB/s",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if s.dtype == "f16" else "f16 (bf16 storage)",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: OPT-6.7B-shaped decoder, {L} layers, hidden {s.hidden}, {s.n_q_heads} heads, "
+                               f"GELU FFN {s.ffn}, fp16 random weights N(0,0.02), batch {B}, prompt {w.prompt_lens[0]}, "
+                               f"teacher-forced decode; HBM budget {w.hbm_budget / 1e9:.0f} GB; TPOT SLO {a.slo_factor}x all-resident",
+                   "interval": int(n_run), "n_offloaded": int(st[-1]["n_offloaded"]),
+                   "interval_over_cap": bool(sn.sn_resident_bytes(se.ctx, n_run) > w.hbm_budget > 0)},
+        "roofline": roofline,
+        "slo": {"tpot_all_resident_ms": tpot0_ns / 1e6, "slo_ms": slo_ns / 1e6, "tpot_median_ms": float(np.median(it)) / 1e6,
+                "tpot_max_ms": float(it.max()) / 1e6, "every_iteration_within_slo": bool((it <= slo_ns).all()),
+                "n_min_slo": int(n_min), "n_max_cap": int(n_max_cap), "feasible_at_cap": feasible_at_cap,
+                "paper_closed_form_interval": int(n_paper), "predicted_iter_ms": pred_ns / 1e6,
+                "rho_transfer_over_compute": rho, "layer_compute_us_median": float(np.median(tc)) / 1e3,
+                "layer_transfer_us_median": float(np.median(tx)) / 1e3,
+                "layer_compute_cv": float(np.std(tc) / np.mean(tc))},
+        "h2d": {"bytes_per_step": h2d_bytes / K, "achieved_GBps": (h2d_bytes / (h2d_ns * 1e-9) / 1e9) if h2d_ns else None,
+                "solo_GBps": float((sn.sn_layer_blob_bytes(se.cshape) + seq_prof * B * kvtok) / (np.median(tx) * 1e-9) / 1e9),
+                "nominal_link_GBps": LINK_NOMINAL / 1e9,
+                "hidden_fraction": (1.0 - stall_ns / h2d_ns) if h2d_ns else 1.0, "stall_ms_per_step": stall_ns / K / 1e6},
+        "hbm_step": {"algorithmic_bytes_per_step": step_bytes, "all_resident_GBps": step_bytes / (tpot0_ns * 1e-9) / 1e9,
+                     "frac_of_peak": step_bytes / (tpot0_ns * 1e-9) / HBM_PEAK,
+                     "roofline_tokens_per_s": B * HBM_PEAK / step_bytes},
+        "prefill": {"iter_ms_all_resident": pre0["iter_ns"] / 1e6, "iter_ms_at_interval": pre["iter_ns"] / 1e6,
+                    "tokens": T},
+    }
+
+    # ---- interval sweep (reported, over-cap points labelled) ------------------------------------
+    if not a.no_sweep:
+        sweep = []
+        ks = max(4, min(K, 8))
+        for N in list(w.intervals) + [L]:
+            se.place(N)
+            sst, swall, spre = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, ks, 1)
+            sit = np.array([d["iter_ns"] for d in sst], dtype=np.float64)
+            sh = sum(d["h2d_ns"] for d in sst)
+            sb = sum(d["h2d_bytes"] for d in sst)
+            ss = sum(d["stall_ns"] for d in sst)
+            pred, _ = sn.sn_timeline(tc, tx, N)
+            sweep.append({"interval": N, "n_offloaded": sst[-1]["n_offloaded"], "tpot_ms": float(np.median(sit)) / 1e6,
+                          "x_all_resident": float(np.median(sit)) / tpot0_ns, "predicted_ms": pred / 1e6,
+                          "meets_slo": bool((sit <= slo_ns).all()), "hidden_fraction": (1 - ss / sh) if sh else 1.0,
+                          "h2d_GBps": sb / (sh * 1e-9) / 1e9 if sh else None,
+                          "resident_GB": sn.sn_resident_bytes(se.ctx, N) / 1e9,
+                          "over_cap": bool(sn.sn_resident_bytes(se.ctx, N) > w.hbm_budget > 0),
+                          "prefill_ms": spre["iter_ns"] / 1e6, "prefill_hidden_fraction": spre["hidden_fraction"]})
+            log(f"[bench] sweep N={N}: TPOT {sweep[-1]['tpot_ms']:.3f} ms ({sweep[-1]['x_all_resident']:.2f}x, predicted "
+                f"{pred / 1e6:.3f}) hidden {sweep[-1]['hidden_fraction']:.3f} h2d {sweep[-1]['h2d_GBps']} GB/s "
+                f"prefill {sweep[-1]['prefill_ms']:.2f} ms")
+        out["sweep"] = sweep
+    se.close()
+
+    if not a.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w)
+        log(f"[bench] cpu oracle: {out['cpu_baseline']['value']:.3f} tok/s on {out['cpu_baseline']['cores']} threads")
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

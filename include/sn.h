@@ -152,6 +152,9 @@ int sn_step(sn_ctx* ctx, const sn_batch* batch, sn_kv* kv, void* hidden_out);
 
 /* timing level: 0 iteration + copies only, 1 also per layer, 2 also per kernel class */
 int sn_set_timing(sn_ctx* ctx, int32_t level);
+/* At level 2, bracket only launches of one kernel class (SN_K_*) with events, so that
+ * measuring the dominant kernel perturbs the iteration as little as possible; -1: all. */
+int sn_set_kernel_timing_class(sn_ctx* ctx, int32_t kernel_class);
 /* Waits for the compute and copy streams, then fills *out for the last sn_step. */
 int sn_get_stats(sn_ctx* ctx, sn_step_stats* out);
 /* Per-layer figures of the last sn_step (timing level >= 1): host arrays [n_layers];

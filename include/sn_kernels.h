@@ -19,9 +19,14 @@ extern "C" {
  * the 16x32-tile order the GEMM kernels read: tile (nb, kb) at (nb*K/32 + kb)*512
  * elements, element (n, k) of the tile at ((n%16) + 16*((k%32)/8))*8 + k%8.
  * dst_row_block_stride / offset: source block j lands at block j*stride + offset
- * (2,0 and 2,1 interleave a gate and an up matrix for the SwiGLU epilogue). */
-int sn_k_tile_weights(const void* host_src, void* host_dst, int32_t N, int32_t K,
-                      int32_t dst_row_block_stride, int32_t dst_row_block_offset);
+ * (2,0 and 2,1 interleave a gate and an up matrix for the SwiGLU epilogue).
+ * bf16_to_f16 != 0: the source holds bfloat16 values, the destination receives the same
+ * values as float16 (exact for 2^-17 <= |v| <= 65504; smaller ones round to float16
+ * subnormals).  Returns the number of elements float16 cannot hold (overflow, inf, NaN),
+ * or a negative SN_E_* code. */
+int64_t sn_k_tile_weights(const void* host_src, void* host_dst, int32_t N, int32_t K,
+                          int32_t dst_row_block_stride, int32_t dst_row_block_offset,
+                          int32_t bf16_to_f16);
 
 /* out16[t][:] = normalise(x32[t][:]) * gain (+ shift).  is_ln: LayerNorm (biased
  * variance) else RMSNorm (shift ignored).  x32 fp32 [T][h]; gain/shift 16-bit [h]. */
@@ -44,8 +49,11 @@ int sn_k_gemm(int32_t dtype, int32_t epilogue, int32_t path, const void* W, cons
 
 /* Rotate q (in place in qkv16 [T][(Hq+2Hkv)*d]) and k by the rotary embedding when
  * rope != 0 (pairs i, i+d/2; angle tok_pos * inv_freq[i], inv_freq fp32 [d/2]); write the
- * new k and v rows into kv (and into mirror, a second copy of the slice, if non-NULL). */
-int sn_k_rope_append(int32_t dtype, void* qkv16, const int32_t* tok_seq, const int32_t* tok_pos,
+ * new k and v rows into kv (and into mirror, a second copy of the slice, if non-NULL).
+ * k and v are rounded to kv_value_dtype and stored in containers of type dtype: a
+ * bfloat16-valued cache can live in float16 containers (pairs f16/f16, f16/bf16,
+ * bf16/bf16). */
+int sn_k_rope_append(int32_t dtype, int32_t kv_value_dtype, void* qkv16, const int32_t* tok_seq, const int32_t* tok_pos,
                      const int32_t* kv_off, const int32_t* cap, void* kv, void* mirror,
                      const float* inv_freq, int32_t T, int32_t Hq, int32_t Hkv, int32_t d,
                      int32_t rope, void* stream);

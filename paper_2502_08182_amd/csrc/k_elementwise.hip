@@ -114,7 +114,10 @@ hipError_t launch_norm(int dtype, int is_ln, const float* x32, const void* gain,
 // ---------------------------------------------------------------------------------
 // Rotary embedding (pairs i, i + d/2; angle = position * inv_freq[i]) on q and k, and
 // append of the new k, v rows to the KV slice.  One thread per (token, head slot, pair).
-template <class T>
+// KVR is the value type of the cache: k and v are rounded to KVR and then stored in the
+// container type T (a bfloat16-valued cache lives in float16 containers, which hold
+// every bfloat16 value of moderate magnitude exactly).
+template <class T, class KVR>
 __global__ __launch_bounds__(256) void rope_append_kernel(
     uint16_t* __restrict__ qkv, const int32_t* __restrict__ tok_seq, const int32_t* __restrict__ tok_pos,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ kv,
@@ -139,6 +142,10 @@ __global__ __launch_bounds__(256) void rope_append_kernel(
     a = ra;
     b = rb;
   }
+  if (hs >= Hq) {
+    a = to_f32<KVR>(from_f32<KVR>(a));
+    b = to_f32<KVR>(from_f32<KVR>(b));
+  }
   const uint16_t oa = from_f32<T>(a), ob = from_f32<T>(b);
   if (hs < Hq) {
     if (rope) {
@@ -160,15 +167,20 @@ __global__ __launch_bounds__(256) void rope_append_kernel(
   }
 }
 
-hipError_t launch_rope_append(int dtype, void* qkv16, const StepIndex& ix, void* kv, void* mirror,
-                              const float* inv_freq, int Tn, int Hq, int Hkv, int d, int rope,
+hipError_t launch_rope_append(int dtype, int kv_value_dtype, void* qkv16, const StepIndex& ix, void* kv,
+                              void* mirror, const float* inv_freq, int Tn, int Hq, int Hkv, int d, int rope,
                               hipStream_t st) {
   const size_t total = (size_t)Tn * (Hq + 2 * Hkv) * (d / 2);
   if (total == 0) return hipSuccess;
   const unsigned grid = (unsigned)((total + 255) / 256);
-  SN_DISPATCH_T(dtype, hipLaunchKernelGGL(rope_append_kernel<T>, dim3(grid), dim3(256), 0, st,
-                                          (uint16_t*)qkv16, ix.tok_seq, ix.tok_pos, ix.kv_off, ix.cap,
-                                          (uint16_t*)kv, (uint16_t*)mirror, inv_freq, Tn, Hq, Hkv, d, rope));
+#define SN_ROPE(TT, RR)                                                                                     \
+  hipLaunchKernelGGL((rope_append_kernel<TT, RR>), dim3(grid), dim3(256), 0, st, (uint16_t*)qkv16, ix.tok_seq, \
+                     ix.tok_pos, ix.kv_off, ix.cap, (uint16_t*)kv, (uint16_t*)mirror, inv_freq, Tn, Hq, Hkv, d, rope)
+  if (dtype == 0 && kv_value_dtype == 0) SN_ROPE(F16, F16);
+  else if (dtype == 0 && kv_value_dtype == 1) SN_ROPE(F16, BF16);
+  else if (dtype == 1 && kv_value_dtype == 1) SN_ROPE(BF16, BF16);
+  else return hipErrorInvalidValue;
+#undef SN_ROPE
   return hipGetLastError();
 }
 

@@ -12,11 +12,12 @@ using namespace sn;
 static int rc_of(hipError_t e) { return e == hipSuccess ? SN_OK : (e == hipErrorInvalidValue ? SN_E_INVAL : SN_E_HIP); }
 static bool bad_dtype(int d) { return d != SN_F16 && d != SN_BF16; }
 
-extern "C" int sn_k_tile_weights(const void* src, void* dst, int32_t N, int32_t K, int32_t stride, int32_t offset) {
+extern "C" int64_t sn_k_tile_weights(const void* src, void* dst, int32_t N, int32_t K, int32_t stride, int32_t offset,
+                                     int32_t bf16_to_f16) {
   if (!src || !dst || N < 16 || K < 32 || N % 16 || K % 32 || stride < 1 || offset < 0 || offset >= stride)
     return SN_E_INVAL;
-  tile_matrix(static_cast<uint16_t*>(dst), static_cast<const uint16_t*>(src), N, K, stride, offset);
-  return SN_OK;
+  return (int64_t)tile_matrix(static_cast<uint16_t*>(dst), static_cast<const uint16_t*>(src), N, K, stride, offset,
+                              bf16_to_f16 != 0);
 }
 
 extern "C" int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, const void* shift,
@@ -33,11 +34,11 @@ extern "C" int sn_k_gemm(int32_t dtype, int32_t epi, int32_t path, const void* W
   return SN_E_INVAL;
 }
 
-extern "C" int sn_k_rope_append(int32_t dtype, void* qkv16, const int32_t* tok_seq, const int32_t* tok_pos,
+extern "C" int sn_k_rope_append(int32_t dtype, int32_t kv_value_dtype, void* qkv16, const int32_t* tok_seq, const int32_t* tok_pos,
                                 const int32_t* kv_off, const int32_t* cap, void* kv, void* mirror,
                                 const float* inv_freq, int32_t T, int32_t Hq, int32_t Hkv, int32_t d, int32_t rope,
                                 void* stream) {
-  if (bad_dtype(dtype) || !qkv16 || !tok_seq || !tok_pos || !kv_off || !cap || !kv || (rope && !inv_freq) ||
+  if (bad_dtype(dtype) || bad_dtype(kv_value_dtype) || (dtype == SN_BF16 && kv_value_dtype == SN_F16) || !qkv16 || !tok_seq || !tok_pos || !kv_off || !cap || !kv || (rope && !inv_freq) ||
       T < 0 || Hq < 1 || Hkv < 1 || (d != 64 && d != 128))
     return SN_E_INVAL;
   StepIndex ix{};
@@ -45,7 +46,7 @@ extern "C" int sn_k_rope_append(int32_t dtype, void* qkv16, const int32_t* tok_s
   ix.tok_pos = tok_pos;
   ix.kv_off = kv_off;
   ix.cap = cap;
-  return rc_of(launch_rope_append(dtype, qkv16, ix, kv, mirror, inv_freq, T, Hq, Hkv, d, rope, (hipStream_t)stream));
+  return rc_of(launch_rope_append(dtype, kv_value_dtype, qkv16, ix, kv, mirror, inv_freq, T, Hq, Hkv, d, rope, (hipStream_t)stream));
 }
 
 extern "C" int sn_k_attn_decode(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,

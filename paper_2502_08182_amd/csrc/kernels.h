@@ -46,9 +46,11 @@ hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, co
 
 // Rotates q (in place) and k, and appends k, v rows to the layer's KV slice
 // ([seq][Hkv][K|V][cap][d]); mirror (may be null) is a second copy of the slice that
-// receives the same rows (host-resident master of an offloaded layer).
-hipError_t launch_rope_append(int dtype, void* qkv16, const StepIndex& ix, void* kv, void* mirror,
-                              const float* inv_freq, int T, int Hq, int Hkv, int d, int rope,
+// receives the same rows (host-resident master of an offloaded layer).  k and v are
+// rounded to kv_value_dtype before being stored in containers of type dtype
+// (allowed pairs: f16/f16, f16/bf16, bf16/bf16).
+hipError_t launch_rope_append(int dtype, int kv_value_dtype, void* qkv16, const StepIndex& ix, void* kv,
+                              void* mirror, const float* inv_freq, int T, int Hq, int Hkv, int d, int rope,
                               hipStream_t st);
 
 // One query per sequence over len_before+1 cached keys.  part: fp32 scratch for

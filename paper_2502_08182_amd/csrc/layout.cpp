@@ -75,51 +75,92 @@ const char* check_shape(const sn_model_shape& s) {
   return nullptr;
 }
 
-void tile_matrix(uint16_t* dst, const uint16_t* src, int N, int K, int row_block_stride,
-                 int row_block_offset) {
+uint16_t bf16_bits_to_f16_bits(uint16_t b, uint64_t* bad) {
+  const uint32_t sign = (b & 0x8000u);
+  const int e = (b >> 7) & 0xff;            // bfloat16: 8 exponent bits (bias 127), 7 mantissa bits
+  const uint32_t m = b & 0x7fu;
+  if (e == 0xff) {                          // inf / NaN
+    if (bad) ++*bad;
+    return (uint16_t)(sign | 0x7c00u | (m ? 0x200u : 0));
+  }
+  if (e == 0) return (uint16_t)sign;        // zero and bfloat16 subnormals (< 2^-126): zero in float16
+  const int E = e - 127;                    // value = 1.m * 2^E
+  if (E > 15) {
+    if (bad) ++*bad;
+    return (uint16_t)(sign | 0x7c00u);
+  }
+  if (E >= -14) return (uint16_t)(sign | (uint32_t)(E + 15) << 10 | m << 3);   // normal: exact
+  // float16 subnormal: value = k * 2^-24 with k = round(1.m * 2^(E+24)), ties to even
+  const int shift = -E - 17;                // (0x80|m) is 1.m * 2^7; k = (0x80|m) * 2^(E+17)
+  const uint32_t sig = 0x80u | m;
+  if (shift <= 0) return (uint16_t)(sign | (sig << -shift));
+  if (shift > 9) return (uint16_t)sign;
+  const uint32_t k = sig >> shift, rem = sig & ((1u << shift) - 1), half = 1u << (shift - 1);
+  return (uint16_t)(sign | (k + ((rem > half || (rem == half && (k & 1))) ? 1 : 0)));
+}
+
+uint64_t tile_matrix(uint16_t* dst, const uint16_t* src, int N, int K, int row_block_stride,
+                     int row_block_offset, bool bf16_to_f16) {
   const int NB = N / 16, KB = K / 32;
-  auto work = [&](int nb0, int nb1) {
+  const int nthreads = (uint64_t)N * K >= (1u << 22) ? 8 : 1;
+  std::vector<uint64_t> bad(nthreads, 0);
+  auto work = [&](int nb0, int nb1, int tid) {
     for (int nb = nb0; nb < nb1; ++nb) {
       uint16_t* out = dst + (uint64_t)(nb * row_block_stride + row_block_offset) * KB * 512;
       for (int kb = 0; kb < KB; ++kb) {
         for (int lane = 0; lane < 64; ++lane) {
           const uint16_t* in = src + (uint64_t)(nb * 16 + (lane & 15)) * K + kb * 32 + (lane >> 4) * 8;
-          std::memcpy(out + ((uint64_t)kb * 64 + lane) * 8, in, 16);
+          uint16_t* o = out + ((uint64_t)kb * 64 + lane) * 8;
+          if (bf16_to_f16)
+            for (int e = 0; e < 8; ++e) o[e] = bf16_bits_to_f16_bits(in[e], &bad[tid]);
+          else
+            std::memcpy(o, in, 16);
         }
       }
     }
   };
-  const int nthreads = (uint64_t)N * K >= (1u << 22) ? 8 : 1;
   if (nthreads == 1) {
-    work(0, NB);
-    return;
+    work(0, NB, 0);
+    return bad[0];
   }
   std::vector<std::thread> pool;
   const int per = (NB + nthreads - 1) / nthreads;
   for (int t = 0; t < nthreads; ++t) {
     const int a = t * per, b = a + per < NB ? a + per : NB;
-    if (a < b) pool.emplace_back(work, a, b);
+    if (a < b) pool.emplace_back(work, a, b, t);
   }
   for (auto& th : pool) th.join();
+  uint64_t tot = 0;
+  for (uint64_t v : bad) tot += v;
+  return tot;
 }
 
-void pack_layer(const sn_model_shape& s, const uint8_t* blob, uint8_t* rec) {
+uint64_t pack_layer(const sn_model_shape& s, const uint8_t* blob, uint8_t* rec) {
   const BlobLayout b = blob_layout(s);
   const PackedLayout p = packed_layout(s);
   const int h = s.hidden, F = s.ffn, qd = s.n_q_heads * s.head_dim;
+  const bool cv = s.dtype == SN_BF16;
+  uint64_t bad = 0;
   auto src = [&](uint64_t off) { return reinterpret_cast<const uint16_t*>(blob + off); };
   auto dst = [&](uint64_t off) { return reinterpret_cast<uint16_t*>(rec + off); };
-  tile_matrix(dst(p.wqkv), src(b.wqkv), p.n_qkv, h, 1, 0);
-  tile_matrix(dst(p.wo), src(b.wo), h, qd, 1, 0);
+  bad += tile_matrix(dst(p.wqkv), src(b.wqkv), p.n_qkv, h, 1, 0, cv);
+  bad += tile_matrix(dst(p.wo), src(b.wo), h, qd, 1, 0, cv);
   if (s.act == SN_ACT_SWIGLU) {
-    tile_matrix(dst(p.wup), src(b.wg), F, h, 2, 0);
-    tile_matrix(dst(p.wup), src(b.wu), F, h, 2, 1);
+    bad += tile_matrix(dst(p.wup), src(b.wg), F, h, 2, 0, cv);
+    bad += tile_matrix(dst(p.wup), src(b.wu), F, h, 2, 1, cv);
   } else {
-    tile_matrix(dst(p.wup), src(b.wu), F, h, 1, 0);
+    bad += tile_matrix(dst(p.wup), src(b.wu), F, h, 1, 0, cv);
   }
-  tile_matrix(dst(p.wd), src(b.wd), h, F, 1, 0);
+  bad += tile_matrix(dst(p.wd), src(b.wd), h, F, 1, 0, cv);
   auto vec = [&](uint64_t to, uint64_t from, uint64_t n) {
-    if (to != kNone && from != kNone) std::memcpy(rec + to, blob + from, n * 2);
+    if (to == kNone || from == kNone) return;
+    if (!cv) {
+      std::memcpy(rec + to, blob + from, n * 2);
+      return;
+    }
+    const uint16_t* in = src(from);
+    uint16_t* out = dst(to);
+    for (uint64_t i = 0; i < n; ++i) out[i] = bf16_bits_to_f16_bits(in[i], &bad);
   };
   vec(p.bqkv, b.bqkv, p.n_qkv);
   vec(p.bo, b.bo, h);
@@ -136,6 +177,7 @@ void pack_layer(const sn_model_shape& s, const uint8_t* blob, uint8_t* rec) {
   vec(p.n1b, b.n1b, h);
   vec(p.n2g, b.n2g, h);
   vec(p.n2b, b.n2b, h);
+  return bad;
 }
 
 }  // namespace sn

@@ -35,10 +35,18 @@ const char* check_shape(const sn_model_shape& s);
 // src: [N][K] row-major 16-bit; dst: tiles [N/16][K/32][64 lanes][8], lane = n%16 + 16*((k%32)/8).
 // row_block_stride / row_block_offset place source block j at destination block
 // j*row_block_stride + row_block_offset (2,0 / 2,1 interleave gate and up).
-void tile_matrix(uint16_t* dst, const uint16_t* src, int N, int K, int row_block_stride,
-                 int row_block_offset);
+// bf16_to_f16: source elements are bfloat16 and are stored as the equal float16 value.
+// Returns the number of elements that float16 cannot hold (|v| > 65504, inf, NaN).
+uint64_t tile_matrix(uint16_t* dst, const uint16_t* src, int N, int K, int row_block_stride,
+                     int row_block_offset, bool bf16_to_f16 = false);
 
-// Caller blob -> tiled record.
-void pack_layer(const sn_model_shape& s, const uint8_t* blob, uint8_t* record);
+// bfloat16 bits -> float16 bits of the same value.  Exact for 2^-17 <= |v| <= 65504 and 0;
+// smaller magnitudes round to the nearest float16 subnormal (absolute error < 2^-25);
+// *bad is incremented when the value is not representable (overflow, inf, NaN).
+uint16_t bf16_bits_to_f16_bits(uint16_t b, uint64_t* bad);
+
+// Caller blob -> tiled record (all 16-bit data stored as float16, the compute type).
+// Returns the number of unrepresentable elements (0 on success).
+uint64_t pack_layer(const sn_model_shape& s, const uint8_t* blob, uint8_t* record);
 
 }  // namespace sn

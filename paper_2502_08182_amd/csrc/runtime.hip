@@ -60,6 +60,7 @@ struct sn_ctx {
   int N = 0;                     // interval in effect (L+1: nothing offloaded)
   bool placed = false;
   int timing = 0;
+  int timing_class = -1;          // kernel class whose launches are bracketed at level 2 (-1: all)
 
   uint64_t w_bytes = 0, kv_bytes = 0, state_bytes = 0, ws_bytes = 0;
   int64_t max_tokens = 0;
@@ -344,7 +345,14 @@ extern "C" int sn_set_layer_weights(sn_ctx* c, int32_t layer, const void* host_b
   int rc = sync_all(c);
   if (rc) return rc;
   LayerState& ls = c->layers[layer];
-  pack_layer(c->shape, static_cast<const uint8_t*>(host_blob), ls.host_w);
+  // All arithmetic runs in float16 with fp32 accumulation.  bfloat16 weights are stored as
+  // the equal float16 value (exact for 2^-17 <= |w| <= 65504): activations kept in
+  // bfloat16 between kernels would lose 3 mantissa bits per hand-off, which at the
+  // 13B/70B layer shapes is already ~3e-2 x RMS after a single layer.
+  const uint64_t bad = pack_layer(c->shape, static_cast<const uint8_t*>(host_blob), ls.host_w);
+  if (bad)
+    return fail(c, SN_E_INVAL, "sn_set_layer_weights: %llu weights are not representable in float16 (|w| > 65504, inf or NaN)",
+                (unsigned long long)bad);
   if (ls.dev) SN_HIP(c, hipMemcpy(ls.dev, ls.host_w, c->w_bytes, hipMemcpyHostToDevice));
   return SN_OK;
 }
@@ -465,11 +473,12 @@ struct KTimer {   // optional per-kernel event pairs (timing level 2)
   int layer;
   int slot = 0;
   bool on;
-  void begin() {
-    if (on) (void)hipEventRecord(c->kev[((size_t)layer * kKernelsPerLayer + slot) * 2], c->compute);
+  bool want(int cls) const { return on && (c->timing_class < 0 || c->timing_class == cls); }
+  void begin(int cls) {
+    if (want(cls)) (void)hipEventRecord(c->kev[((size_t)layer * kKernelsPerLayer + slot) * 2], c->compute);
   }
   void end(int cls) {
-    if (on) {
+    if (want(cls)) {
       (void)hipEventRecord(c->kev[((size_t)layer * kKernelsPerLayer + slot) * 2 + 1], c->compute);
       c->last_kernel_class[slot] = (uint8_t)cls;
     }
@@ -481,7 +490,8 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
               bool prefill, int n_qtiles, int S) {
   const sn_model_shape& s = c->shape;
   const PackedLayout& p = c->pl;
-  const int dt = s.dtype, h = s.hidden, F = s.ffn, Hq = s.n_q_heads, Hkv = s.n_kv_heads, d = s.head_dim;
+  const int dt = SN_F16;   // compute and internal storage type (see sn_set_layer_weights)
+  const int h = s.hidden, F = s.ffn, Hq = s.n_q_heads, Hkv = s.n_kv_heads, d = s.head_dim;
   const int qd = Hq * d;
   auto at = [&](uint64_t off) -> const void* { return off == kNone ? nullptr : base + off; };
   uint8_t* kv = kv_of(base, c);
@@ -492,31 +502,31 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
     return small ? launch_gemm_skinny(dt, epi, W, X, bias, out, T, N, K, st)
                  : launch_gemm_tile(dt, epi, W, X, bias, out, T, N, K, st);
   };
-  kt.begin();
+  kt.begin(SN_K_NORM);
   SN_HIP(c, launch_norm(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, st));
   kt.end(SN_K_NORM);
-  kt.begin();
+  kt.begin(SN_K_QKV);
   SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h));
   kt.end(SN_K_QKV);
-  kt.begin();
-  SN_HIP(c, launch_rope_append(dt, c->qkv16, ix, kv, mirror_kv, c->inv_freq, T, Hq, Hkv, d, s.rope, st));
+  kt.begin(SN_K_ROPE_APPEND);
+  SN_HIP(c, launch_rope_append(dt, s.dtype, c->qkv16, ix, kv, mirror_kv, c->inv_freq, T, Hq, Hkv, d, s.rope, st));
   kt.end(SN_K_ROPE_APPEND);
-  kt.begin();
+  kt.begin(SN_K_ATTN);
   if (prefill)
     SN_HIP(c, launch_attn_prefill(dt, c->qkv16, kv, ix, c->attn16, n_qtiles, Hq, Hkv, d, st));
   else
     SN_HIP(c, launch_attn_decode(dt, c->qkv16, kv, ix, c->attn16, c->part, B, Hq, Hkv, d, S, st));
   kt.end(SN_K_ATTN);
-  kt.begin();
+  kt.begin(SN_K_OPROJ);
   SN_HIP(c, gemm(EPI_RESID32, at(p.wo), c->attn16, at(p.bo), c->x32, h, qd));
   kt.end(SN_K_OPROJ);
-  kt.begin();
+  kt.begin(SN_K_NORM);
   SN_HIP(c, launch_norm(dt, s.norm == SN_NORM_LN, c->x32, at(p.n2g), at(p.n2b), c->u16, T, h, s.norm_eps, st));
   kt.end(SN_K_NORM);
-  kt.begin();
+  kt.begin(SN_K_FFN_UP);
   SN_HIP(c, gemm(s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup), c->act16, p.n_up, h));
   kt.end(SN_K_FFN_UP);
-  kt.begin();
+  kt.begin(SN_K_FFN_DOWN);
   SN_HIP(c, gemm(EPI_RESID32, at(p.wd), c->act16, at(p.bd), c->x32, h, F));
   kt.end(SN_K_FFN_DOWN);
   return SN_OK;
@@ -606,7 +616,7 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
     int rc = make_events(c, c->kev, L * kKernelsPerLayer * 2, true);
     if (rc) return rc;
   }
-  c->last_kernel_class.assign(kKernelsPerLayer, SN_K_OTHER);
+  c->last_kernel_class.assign(kKernelsPerLayer, 255);
 
   const uint64_t kv_used = (uint64_t)c->kv_used_tokens * kv_token_bytes(s);
   const bool fetch_kv = any_cached;             // prefill from empty caches produces the KV itself
@@ -684,6 +694,13 @@ extern "C" int sn_set_timing(sn_ctx* c, int32_t level) {
   return SN_OK;
 }
 
+extern "C" int sn_set_kernel_timing_class(sn_ctx* c, int32_t kernel_class) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "null context");
+  if (kernel_class < -1 || kernel_class > 7) return fail(c, SN_E_INVAL, "sn_set_kernel_timing_class: bad class");
+  c->timing_class = kernel_class;
+  return SN_OK;
+}
+
 extern "C" int sn_get_stats(sn_ctx* c, sn_step_stats* out) {
   if (!c || !out) return fail(c, SN_E_INVAL, "sn_get_stats: null argument");
   if (!c->last_valid) return fail(c, SN_E_STATE, "sn_get_stats: no iteration has run under this placement");
@@ -709,6 +726,7 @@ extern "C" int sn_get_stats(sn_ctx* c, sn_step_stats* out) {
     for (int l = 0; l < L; ++l)
       for (int k = 0; k < 8; ++k) {   // run_layer records 8 kernel slots
         const int cls = c->last_kernel_class[k];
+        if (cls > 7) continue;            // this launch was not bracketed
         const int64_t ns = elapsed_ns(c->kev[((size_t)l * kKernelsPerLayer + k) * 2],
                                       c->kev[((size_t)l * kKernelsPerLayer + k) * 2 + 1]);
         if (ns >= 0) {

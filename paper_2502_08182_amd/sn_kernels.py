@@ -23,10 +23,10 @@ def _lib():
     if not _ready:
         v, i32, u64 = C.c_void_p, C.c_int32, C.c_uint64
         sig = {
-            "sn_k_tile_weights": [v, v, i32, i32, i32, i32],
+            "sn_k_tile_weights": [v, v, i32, i32, i32, i32, i32],
             "sn_k_norm": [i32, i32, v, v, v, v, i32, i32, C.c_float, v],
             "sn_k_gemm": [i32, i32, i32, v, v, v, v, i32, i32, i32, v],
-            "sn_k_rope_append": [i32, v, v, v, v, v, v, v, v, i32, i32, i32, i32, i32, v],
+            "sn_k_rope_append": [i32, i32, v, v, v, v, v, v, v, v, i32, i32, i32, i32, i32, v],
             "sn_k_attn_decode": [i32, v, v, v, v, v, v, v, i32, i32, i32, i32, i32, i32, v],
             "sn_k_attn_prefill": [i32, v, v, v, v, v, v, v, v, v, v, i32, i32, i32, i32, v],
             "sn_k_cast_in": [i32, v, v, u64, v],
@@ -34,7 +34,7 @@ def _lib():
         }
         for name, args in sig.items():
             f = getattr(L, name)
-            f.restype = C.c_int
+            f.restype = C.c_int64 if name == "sn_k_tile_weights" else C.c_int
             f.argtypes = args
         _ready = True
     return L
@@ -48,12 +48,15 @@ def _chk(rc):
 _p = _sn._ptr
 
 
-def sn_k_tile_weights(src: np.ndarray, N: int, K: int, dst: np.ndarray = None, stride: int = 1, offset: int = 0):
+def sn_k_tile_weights(src: np.ndarray, N: int, K: int, dst: np.ndarray = None, stride: int = 1, offset: int = 0,
+                      bf16_to_f16: bool = False, return_bad: bool = False):
     src = np.ascontiguousarray(src, dtype=np.uint16)
     if dst is None:
         dst = np.zeros(N * K * stride, dtype=np.uint16)
-    _chk(_lib().sn_k_tile_weights(src.ctypes.data, dst.ctypes.data, N, K, stride, offset))
-    return dst
+    bad = _lib().sn_k_tile_weights(src.ctypes.data, dst.ctypes.data, N, K, stride, offset, int(bf16_to_f16))
+    if bad < 0:
+        _chk(int(bad))
+    return (dst, int(bad)) if return_bad else dst
 
 
 def sn_k_norm(dtype, is_ln, x32, gain, shift, out16, T, h, eps, stream=0):
@@ -64,9 +67,9 @@ def sn_k_gemm(dtype, epilogue, path, W, X, bias, out, M, N, K, stream=0):
     _chk(_lib().sn_k_gemm(dtype, epilogue, path, _p(W), _p(X), _p(bias), _p(out), M, N, K, stream))
 
 
-def sn_k_rope_append(dtype, qkv16, tok_seq, tok_pos, kv_off, cap, kv, mirror, inv_freq, T, Hq, Hkv, d, rope,
-                     stream=0):
-    _chk(_lib().sn_k_rope_append(dtype, _p(qkv16), _p(tok_seq), _p(tok_pos), _p(kv_off), _p(cap), _p(kv),
+def sn_k_rope_append(dtype, kv_value_dtype, qkv16, tok_seq, tok_pos, kv_off, cap, kv, mirror, inv_freq, T, Hq, Hkv,
+                     d, rope, stream=0):
+    _chk(_lib().sn_k_rope_append(dtype, kv_value_dtype, _p(qkv16), _p(tok_seq), _p(tok_pos), _p(kv_off), _p(cap), _p(kv),
                                  _p(mirror), _p(inv_freq), T, Hq, Hkv, d, int(rope), stream))
 
 

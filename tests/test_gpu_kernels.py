@@ -16,7 +16,7 @@ from paper_2502_08182_amd import sn_kernels as K
 pytestmark = pytest.mark.gpu
 
 DT = {"f16": sn.SN_F16, "bf16": sn.SN_BF16}
-TOL = {"f16": 2.5e-3, "bf16": 1.2e-2}     # x RMS(expected); >= 4 ulp of the output type at 1 RMS... see docstring
+TOL = {"f16": 2.0 ** -10, "bf16": 2.0 ** -8}     # x max|expected|: one ulp of the output type
 
 
 def dev16(bits):
@@ -33,7 +33,7 @@ def rms(a):
 
 def check(got, want, dtype, what, factor=1.0):
     err = float(np.abs(got - want).max())
-    bound = TOL[dtype] * factor * rms(want)
+    bound = TOL[dtype] * factor * float(np.abs(want).max())
     print(f"{what}: max|d|={err:.3e} bound={bound:.3e} rms={rms(want):.3e}", flush=True)
     assert np.isfinite(got).all(), what
     assert err <= bound, (what, err, bound)
@@ -86,7 +86,12 @@ def _gemm_case(dtype, path, epi, M, N, Kd, bias, seed):
         want = ofw.silu(g) * u
     else:
         lin = x64 @ synth.widen(wb, dtype).T + b64
-        want = {K.EPI_STORE16: lin, K.EPI_GELU16: ofw.gelu(lin), K.EPI_RESID32: r0.astype(np.float64) + lin}[epi]
+        if epi == K.EPI_GELU16:
+            want = ofw.gelu(lin)
+        elif epi == K.EPI_RESID32:
+            want = r0.astype(np.float64) + lin
+        else:
+            want = lin
     got = out.cpu().numpy().astype(np.float64) if epi == K.EPI_RESID32 else synth.widen(host16(out), dtype)
     check(got, want, dtype, f"gemm path={path} epi={epi} M={M} N={N} K={Kd} bias={bias}")
 
@@ -168,7 +173,7 @@ def test_rope_append_and_attn_decode(dtype, Hq, Hkv, d, rope):
     n_new = [1] * B
     qkv, Kc, Vc, kv_off, tok_start, dv = _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope)
     mirror = torch.zeros_like(dv["kv"])
-    K.sn_k_rope_append(DT[dtype], dv["qkv"], dv["tok_seq"], dv["tok_pos"], dv["kv_off"], dv["cap"], dv["kv"], mirror,
+    K.sn_k_rope_append(DT[dtype], DT[dtype], dv["qkv"], dv["tok_seq"], dv["tok_pos"], dv["kv_off"], dv["cap"], dv["kv"], mirror,
                        dv["inv_freq"], B, Hq, Hkv, d, rope)
     want, k_new, v_new, q_rot = _oracle_attention(dtype, qkv, Kc, Vc, lens_before, n_new, tok_start, Hq, Hkv, d, rope)
     torch.cuda.synchronize()
@@ -205,7 +210,7 @@ def test_attn_prefill(dtype, Hq, Hkv, d, rope):
     caps = [lens_before[b] + n_new[b] + 2 for b in range(B)]
     qkv, Kc, Vc, kv_off, tok_start, dv = _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope)
     T = sum(n_new)
-    K.sn_k_rope_append(DT[dtype], dv["qkv"], dv["tok_seq"], dv["tok_pos"], dv["kv_off"], dv["cap"], dv["kv"], None,
+    K.sn_k_rope_append(DT[dtype], DT[dtype], dv["qkv"], dv["tok_seq"], dv["tok_pos"], dv["kv_off"], dv["cap"], dv["kv"], None,
                        dv["inv_freq"], T, Hq, Hkv, d, rope)
     tile_seq, tile_q0 = [], []
     for b in range(B):

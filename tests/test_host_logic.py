@@ -53,6 +53,24 @@ def test_weight_tiling_is_a_permutation_with_the_documented_index():
     assert out.reshape(4, 512)[:, 0].tolist() == [1, 2, 1, 2]
 
 
+def test_bf16_weights_become_equal_float16_values():
+    """Every one of the 65536 bfloat16 bit patterns, against numpy's float32 -> float16 rounding."""
+    from paper_2502_08182_amd import sn_kernels
+    bits = np.arange(65536, dtype=np.uint16).reshape(64, 1024)
+    tiled, bad = sn_kernels.sn_k_tile_weights(bits, 64, 1024, bf16_to_f16=True, return_bad=True)
+    plain = sn_kernels.sn_k_tile_weights(bits, 64, 1024)            # same permutation, no conversion
+    src = synth.widen(plain, "bf16")
+    got = tiled.view(np.float16).astype(np.float64)
+    with np.errstate(over="ignore"):
+        want = src.astype(np.float32).astype(np.float16).astype(np.float64)
+    fin = np.isfinite(src) & (np.abs(src) <= 65504.0)
+    assert np.array_equal(got[fin], want[fin])
+    exact = fin & ((np.abs(src) >= 2.0 ** -17) | (src == 0))
+    assert np.array_equal(got[exact], src[exact])                    # exact, not merely nearest
+    assert bad == int((~fin).sum())                                  # overflow, inf and NaN are counted
+    assert np.isnan(got[np.isnan(src)]).all() and np.isinf(got[~fin & ~np.isnan(src)]).all()
+
+
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(sn.sn_model_shape) == 16 * 4
     assert ctypes.sizeof(sn.sn_step_stats) == 6 * 8 + 8 + 2 * 4 + 8 + 8 * 8 + 8 * 4
