@@ -150,6 +150,12 @@ int sn_kv_reset(sn_ctx* ctx, int32_t batch, const int32_t* capacity);
  * Results are valid after the caller synchronises the compute stream. */
 int sn_step(sn_ctx* ctx, const sn_batch* batch, sn_kv* kv, void* hidden_out);
 
+/* The hidden states of the last sn_step before their final rounding to shape.dtype:
+ * the fp32 residual stream, [sum n_new, hidden].  dst: device, dst_bytes its size.
+ * Enqueued on the compute stream; hidden_out of that step is exactly this tensor
+ * rounded to nearest-even. */
+int sn_read_hidden_f32(sn_ctx* ctx, void* dst, uint64_t dst_bytes);
+
 /* timing level: 0 iteration + copies only, 1 also per layer, 2 also per kernel class */
 int sn_set_timing(sn_ctx* ctx, int32_t level);
 /* At level 2, bracket only launches of one kernel class (SN_K_*) with events, so that

@@ -95,6 +95,7 @@ struct sn_ctx {
   // what the last step did (for stats)
   bool last_valid = false;
   bool last_prefill = false;
+  int last_tokens = 0;
   int last_timing = 0;
   int64_t last_h2d_bytes = 0, last_d2h_bytes = 0;
   std::vector<uint8_t> last_kernel_class;   // [kKernelsPerLayer] class of each per-layer kernel slot
@@ -509,7 +510,7 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
   SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h));
   kt.end(SN_K_QKV);
   kt.begin(SN_K_ROPE_APPEND);
-  SN_HIP(c, launch_rope_append(dt, s.dtype, c->qkv16, ix, kv, mirror_kv, c->inv_freq, T, Hq, Hkv, d, s.rope, st));
+  SN_HIP(c, launch_rope_append(dt, dt, c->qkv16, ix, kv, mirror_kv, c->inv_freq, T, Hq, Hkv, d, s.rope, st));
   kt.end(SN_K_ROPE_APPEND);
   kt.begin(SN_K_ATTN);
   if (prefill)
@@ -679,8 +680,19 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
     kv->len[b] = c->len[b];
   }
   c->last_valid = true;
+  c->last_tokens = T;
   c->last_prefill = prefill;
   c->last_timing = c->timing;
+  return SN_OK;
+}
+
+extern "C" int sn_read_hidden_f32(sn_ctx* c, void* dst, uint64_t dst_bytes) {
+  if (!c || !dst) return fail(c, SN_E_INVAL, "sn_read_hidden_f32: null argument");
+  if (!c->last_valid) return fail(c, SN_E_STATE, "sn_read_hidden_f32: no iteration has run under this placement");
+  const uint64_t need = (uint64_t)c->last_tokens * c->shape.hidden * 4;
+  if (dst_bytes < need) return fail(c, SN_E_INVAL, "sn_read_hidden_f32: destination holds %llu bytes, %llu needed",
+                                    (unsigned long long)dst_bytes, (unsigned long long)need);
+  SN_HIP(c, hipMemcpyAsync(dst, c->x32, need, hipMemcpyDeviceToDevice, c->compute));
   return SN_OK;
 }
 

@@ -87,23 +87,32 @@ class Session:
                     hidden_out: torch.Tensor):
         sn.sn_step(self.ctx, n_new, is_prefill, hidden_in, self.kv_len, hidden_out)
 
-    def step(self, n_new: Sequence[int], is_prefill: bool, hidden_bits: np.ndarray) -> np.ndarray:
-        """hidden_bits: uint16 [sum n_new, hidden]; returns the output as uint16 bits."""
+    def step(self, n_new: Sequence[int], is_prefill: bool, hidden_bits: np.ndarray, want_f32: bool = False):
+        """hidden_bits: uint16 [sum n_new, hidden]; returns the output as uint16 bits
+        (and, if want_f32, also the fp32 hidden states before the final rounding)."""
         with torch.cuda.stream(self.stream):
             x = _dev_bits(hidden_bits)
             y = torch.empty_like(x)
+            f = torch.empty(hidden_bits.shape, dtype=torch.float32, device="cuda") if want_f32 else None
             self.stream.synchronize()
             self.step_device(n_new, is_prefill, x, y)
+            if want_f32:
+                sn.sn_read_hidden_f32(self.ctx, f, f.numel() * 4)
             self.stream.synchronize()
-            return _host_bits(y).reshape(hidden_bits.shape)
+            out = _host_bits(y).reshape(hidden_bits.shape)
+            return (out, f.cpu().numpy()) if want_f32 else out
 
-    def run_workload(self, w: synth.Workload, prompt_bits: np.ndarray, table_bits: np.ndarray):
-        """Prefill then teacher-forced decode; returns (prefill_out_bits, decode_out_bits)."""
+    def run_workload(self, w: synth.Workload, prompt_bits: np.ndarray, table_bits: np.ndarray, want_f32: bool = False):
+        """Prefill then teacher-forced decode; returns (prefill_out_bits, decode_out_bits)
+        [, prefill_f32, decode_f32]."""
         self.kv_reset([p + w.decode_steps for p in w.prompt_lens])
-        pre = self.step(list(w.prompt_lens), True, prompt_bits)
-        outs = [self.step([1] * w.batch, False, table_bits[t]) for t in range(table_bits.shape[0])]
-        dec = np.stack(outs, axis=0) if outs else np.zeros((0, w.batch, self.ms.hidden), dtype=np.uint16)
-        return pre, dec
+        pre = self.step(list(w.prompt_lens), True, prompt_bits, want_f32)
+        outs = [self.step([1] * w.batch, False, table_bits[t], want_f32) for t in range(table_bits.shape[0])]
+        if not want_f32:
+            dec = np.stack(outs, axis=0) if outs else np.zeros((0, w.batch, self.ms.hidden), dtype=np.uint16)
+            return pre, dec
+        dec = np.stack([o[0] for o in outs], axis=0)
+        return pre[0], dec, pre[1], np.stack([o[1] for o in outs], axis=0)
 
     def stats(self) -> dict:
         return sn.sn_get_stats(self.ctx).as_dict()

@@ -25,6 +25,7 @@ ERROR_NAMES = {-1: "SN_E_INVAL", -2: "SN_E_STATE", -3: "SN_E_BUDGET", -4: "SN_E_
 EXPORTS = (
     "sn_init", "sn_destroy", "sn_last_error", "sn_layer_blob_bytes", "sn_set_layer_weights", "sn_place",
     "sn_set_budget_enforce", "sn_resident_bytes", "sn_max_interval", "sn_placement", "sn_kv_reset", "sn_step",
+    "sn_read_hidden_f32",
     "sn_set_timing", "sn_set_kernel_timing_class", "sn_get_stats", "sn_get_layer_times", "sn_profile_layers", "sn_timeline",
     "sn_pick_interval_from_times", "sn_pick_interval", "sn_paper_rule",
 )
@@ -93,6 +94,7 @@ def lib() -> C.CDLL:
         "sn_placement": (C.c_int, [i32, i32, C.POINTER(C.c_uint8), pi32]),
         "sn_kv_reset": (C.c_int, [ctx, i32, pi32]),
         "sn_step": (C.c_int, [ctx, C.POINTER(sn_batch), C.POINTER(sn_kv), C.c_void_p]),
+        "sn_read_hidden_f32": (C.c_int, [ctx, C.c_void_p, u64]),
         "sn_set_timing": (C.c_int, [ctx, i32]),
         "sn_set_kernel_timing_class": (C.c_int, [ctx, i32]),
         "sn_get_stats": (C.c_int, [ctx, C.POINTER(sn_step_stats)]),
@@ -208,6 +210,10 @@ def sn_step(ctx, n_new: Sequence[int], is_prefill: bool, hidden_in, kv_len: np.n
                  hidden_in=C.c_void_p(_ptr(hidden_in)))
     kv = sn_kv(len=kv_len.ctypes.data_as(C.POINTER(C.c_int32)))
     _check(lib().sn_step(ctx, C.byref(b), C.byref(kv), C.c_void_p(_ptr(hidden_out))), ctx)
+
+
+def sn_read_hidden_f32(ctx, dst, dst_bytes: int) -> None:
+    _check(lib().sn_read_hidden_f32(ctx, C.c_void_p(_ptr(dst)), int(dst_bytes)), ctx)
 
 
 def sn_set_timing(ctx, level: int) -> None:
