@@ -161,6 +161,14 @@ int sn_set_timing(sn_ctx* ctx, int32_t level);
 /* At level 2, bracket only launches of one kernel class (SN_K_*) with events, so that
  * measuring the dominant kernel perturbs the iteration as little as possible; -1: all. */
 int sn_set_kernel_timing_class(sn_ctx* ctx, int32_t kernel_class);
+/* Times one decode-phase projection kernel class (SN_K_QKV, SN_K_OPROJ, SN_K_FFN_UP,
+ * SN_K_FFN_DOWN) on its own: launches it once per GPU-resident layer on that layer's
+ * weights, `reps` rounds back to back on the compute stream for `batch` token rows,
+ * bracketed by one pair of HIP events.  The workspace activations are used as they
+ * are and are overwritten; call it between requests.  *total_ns / *launches is the
+ * average launch duration (launch gaps included). */
+int sn_time_kernel_class(sn_ctx* ctx, int32_t kernel_class, int32_t batch, int32_t reps,
+                         int64_t* total_ns, int32_t* launches);
 /* Waits for the compute and copy streams, then fills *out for the last sn_step. */
 int sn_get_stats(sn_ctx* ctx, sn_step_stats* out);
 /* Per-layer figures of the last sn_step (timing level >= 1): host arrays [n_layers];

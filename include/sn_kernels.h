@@ -77,6 +77,10 @@ int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* kv, const in
 int sn_k_cast_in(int32_t dtype, const void* in16, void* x32, uint64_t n, void* stream);
 int sn_k_cast_out(int32_t dtype, const void* x32, void* out16, uint64_t n, void* stream);
 
+/* Plain device-to-device copy of `bytes` (multiple of 16): a kernel whose HBM traffic is
+ * known exactly (bytes read + bytes written), used to calibrate hardware counters. */
+int sn_k_copy(const void* src, void* dst, uint64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -2,6 +2,7 @@
 // reductions, vector typedefs for the matrix-core builtins.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace sn {
@@ -70,3 +71,15 @@ __device__ __forceinline__ float gelu_erf(float x) {
 __device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x)); }
 
 }  // namespace sn
+
+// Launch through this macro so that a pending LaunchEvents pair (kernels.h) is honoured.
+#define SN_LAUNCH(kernel, grid, block, lds, stream, ...)                                            \
+  do {                                                                                              \
+    ::sn::LaunchEvents& le_ = ::sn::next_launch_events();                                           \
+    if (le_.start) {                                                                                \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, le_.start, le_.stop, 0, __VA_ARGS__); \
+      le_ = ::sn::LaunchEvents{};                                                                   \
+    } else {                                                                                        \
+      hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                            \
+    }                                                                                               \
+  } while (0)

@@ -7,18 +7,14 @@
 // row (16 bytes each), so one wavefront load covers 64/(d/8) consecutive keys = 1 KiB.
 // The dot product is finished with xor-shuffles inside those d/8 lanes; every
 // (wavefront, key slot) keeps its own running softmax (max, sum, weighted V), merged
-// at the end by shuffles, then across the 4 wavefronts through LDS, then across key
+// at the end by shuffles, then across the wavefronts through LDS, then across key
 // ranges by a second small kernel.  All merges run in a fixed order.
-#include "common.h"
 #include "kernels.h"
+#include "common.h"
 
 namespace sn {
 
 constexpr float kNegBig = -1.0e30f;
-
-struct SoftAcc {
-  float m, l, a[8];
-};
 
 __device__ __forceinline__ void merge_into(float& m, float& l, float (&a)[8], float m2, float l2,
                                            const float (&a2)[8]) {
@@ -30,14 +26,18 @@ __device__ __forceinline__ void merge_into(float& m, float& l, float (&a)[8], fl
   m = mn;
 }
 
+constexpr int kDecWaves = 8;        // wavefronts per workgroup
+constexpr int kDecUnroll = 4;       // key groups (one wavefront load each for K and V) in flight
+
 template <class T, int D, int G>
-__global__ __launch_bounds__(256) void attn_decode_kernel(
+__global__ __launch_bounds__(kDecWaves * 64) void attn_decode_kernel(
     const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ out,
     float* __restrict__ part, int Hq, int Hkv, int S) {
   constexpr int LPK = D / 8;          // lanes per key row
   constexpr int KPW = 64 / LPK;       // keys per wavefront load
-  __shared__ float lds[4][G][LPK][10];
+  constexpr int NW = kDecWaves, UK = kDecUnroll;
+  __shared__ float lds[NW][G][LPK][10];
 
   const int b = blockIdx.x / Hkv;
   const int hk = blockIdx.x % Hkv;
@@ -73,33 +73,43 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
   }
 
-  for (int jb = j0 + wave * KPW; jb < j1; jb += 4 * KPW) {
-    const int j = jb + slot;
-    const bool ok = j < j1;
-    const int jc = ok ? j : j1 - 1;                    // clamped: loads stay inside the cached rows
-    const u16x8 kr = *reinterpret_cast<const u16x8*>(Kb + (size_t)jc * D);
-    const u16x8 vr = *reinterpret_cast<const u16x8*>(Vb + (size_t)jc * D);
-    float kf[8], vf[8];
+  // wavefront `wave` takes key groups wave, wave+NW, ...; UK groups per trip are loaded
+  // before any is used so that 2*UK KiB per wavefront are in flight
+  for (int jb = j0 + wave * KPW; jb < j1; jb += NW * KPW * UK) {
+    u16x8 kr[UK], vr[UK];
+    bool ok[UK];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      kf[e] = to_f32<T>(kr[e]);
-      vf[e] = to_f32<T>(vr[e]);
+    for (int u = 0; u < UK; ++u) {
+      const int j = jb + u * NW * KPW + slot;
+      ok[u] = j < j1;
+      const int jc = ok[u] ? j : j1 - 1;               // clamped: loads stay inside the cached rows
+      kr[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Kb + (size_t)jc * D));
+      vr[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vb + (size_t)jc * D));
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float s = 0.f;
+    for (int u = 0; u < UK; ++u) {
+      float kf[8], vf[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s += q[g][e] * kf[e];
+      for (int e = 0; e < 8; ++e) {
+        kf[e] = to_f32<T>(kr[u][e]);
+        vf[e] = to_f32<T>(vr[u][e]);
+      }
 #pragma unroll
-      for (int o = LPK / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-      if (ok) {
-        const float mn = fmaxf(m[g], s);
-        const float corr = __expf(m[g] - mn);
-        const float p = __expf(s - mn);
-        l[g] = l[g] * corr + p;
+      for (int g = 0; g < G; ++g) {
+        float s = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vf[e];
-        m[g] = mn;
+        for (int e = 0; e < 8; ++e) s += q[g][e] * kf[e];
+#pragma unroll
+        for (int o = LPK / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        if (ok[u]) {
+          const float mn = fmaxf(m[g], s);
+          const float corr = __expf(m[g] - mn);
+          const float p = __expf(s - mn);
+          l[g] = l[g] * corr + p;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vf[e];
+          m[g] = mn;
+        }
       }
     }
   }
@@ -125,13 +135,13 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   }
   __syncthreads();
 
-  // merge the 4 wavefronts: thread (g, c)
+  // merge the wavefronts in order: thread (g, c)
   if (threadIdx.x < G * LPK) {
     const int g = threadIdx.x / LPK, cc = threadIdx.x % LPK;
     float mm = lds[0][g][cc][0], ll = lds[0][g][cc][1], aa[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) aa[e] = lds[0][g][cc][2 + e];
-    for (int w = 1; w < 4; ++w) {
+    for (int w = 1; w < NW; ++w) {
       float a2[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) a2[e] = lds[w][g][cc][2 + e];
@@ -172,11 +182,12 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, uint16_t* __
   out[(size_t)blockIdx.x * D + e] = from_f32<T>(num / den);
 }
 
-// Key-range splits: aim for ~512 workgroups, at least 128 keys per split, at most 16.
+// Key-range splits: one workgroup per CU (256) is enough once each keeps 64 KiB in
+// flight; below that, split the keys, at least 256 per split, at most 16 splits.
 int attn_decode_splits(int B, int Hkv, int max_len) {
   const int pairs = B * Hkv;
-  int S = (512 + pairs - 1) / pairs;
-  const int by_len = (max_len + 127) / 128;
+  int S = (256 + pairs - 1) / pairs;
+  const int by_len = (max_len + 255) / 256;
   if (S > by_len) S = by_len;
   if (S > 16) S = 16;
   if (S < 1) S = 1;
@@ -186,10 +197,10 @@ int attn_decode_splits(int B, int Hkv, int max_len) {
 template <class T, int D>
 static hipError_t launch_d(const uint16_t* qkv, const uint16_t* kv, const StepIndex& ix, uint16_t* out,
                            float* part, int B, int Hq, int Hkv, int S, hipStream_t st) {
-  dim3 grid(B * Hkv, S), block(256);
+  dim3 grid(B * Hkv, S), block(kDecWaves * 64);
   const int G = Hq / Hkv;
 #define SN_LAUNCH_G(GV)                                                                                   \
-  hipLaunchKernelGGL((attn_decode_kernel<T, D, GV>), grid, block, 0, st, qkv, kv, ix.len_before, ix.kv_off, \
+  SN_LAUNCH((attn_decode_kernel<T, D, GV>), grid, block, 0, st, qkv, kv, ix.len_before, ix.kv_off, \
                      ix.cap, out, part, Hq, Hkv, S)
   switch (G) {
     case 1: SN_LAUNCH_G(1); break;
@@ -201,7 +212,7 @@ static hipError_t launch_d(const uint16_t* qkv, const uint16_t* kv, const StepIn
 #undef SN_LAUNCH_G
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || S == 1) return e;
-  hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3(B * Hq), dim3(D), 0, st, part, out, S);
+  SN_LAUNCH((attn_combine_kernel<T, D>), dim3(B * Hq), dim3(D), 0, st, part, out, S);
   return hipGetLastError();
 }
 

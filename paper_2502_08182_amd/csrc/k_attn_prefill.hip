@@ -13,8 +13,8 @@
 //                 transposed while being staged, B operand = P^T from registers,
 //                 result D[d][query]: the query index stays on lane%16, so the online
 //                 softmax rescale is lane-local.
-#include "common.h"
 #include "kernels.h"
+#include "common.h"
 
 namespace sn {
 
@@ -149,16 +149,16 @@ hipError_t launch_attn_prefill(int dtype, const void* qkv16, const void* kv, con
                                int n_qtiles, int Hq, int Hkv, int d, hipStream_t st) {
   if (n_qtiles <= 0) return hipSuccess;
   dim3 grid(n_qtiles, Hq), block(256);
-#define SN_LAUNCH(TT, DD)                                                                                    \
-  hipLaunchKernelGGL((attn_prefill_kernel<TT, DD>), grid, block, 0, st, (const uint16_t*)qkv16,               \
+#define SN_PREFILL(TT, DD)                                                                                    \
+  SN_LAUNCH((attn_prefill_kernel<TT, DD>), grid, block, 0, st, (const uint16_t*)qkv16,               \
                      (const uint16_t*)kv, ix.len_before, ix.n_new, ix.tok_start, ix.kv_off, ix.cap, ix.tile_seq, \
                      ix.tile_q0, (uint16_t*)out16, Hq, Hkv)
-  if (dtype == 0 && d == 64) SN_LAUNCH(F16, 64);
-  else if (dtype == 0 && d == 128) SN_LAUNCH(F16, 128);
-  else if (dtype == 1 && d == 64) SN_LAUNCH(BF16, 64);
-  else if (dtype == 1 && d == 128) SN_LAUNCH(BF16, 128);
+  if (dtype == 0 && d == 64) SN_PREFILL(F16, 64);
+  else if (dtype == 0 && d == 128) SN_PREFILL(F16, 128);
+  else if (dtype == 1 && d == 64) SN_PREFILL(BF16, 64);
+  else if (dtype == 1 && d == 128) SN_PREFILL(BF16, 128);
   else return hipErrorInvalidValue;
-#undef SN_LAUNCH
+#undef SN_PREFILL
   return hipGetLastError();
 }
 

@@ -1,8 +1,8 @@
 // Small bandwidth-trivial kernels of the layer: casts between the 16-bit boundary
 // type and the fp32 residual stream, the two normalisations, rotary embedding with
 // the KV-cache append, and a hash fill used by the profiler for generated inputs.
-#include "common.h"
 #include "kernels.h"
+#include "common.h"
 
 namespace sn {
 
@@ -33,6 +33,19 @@ __global__ void fill_hash_kernel(uint16_t* __restrict__ out, size_t n, uint32_t 
   }
 }
 
+// Plain device-to-device copy, 16 bytes per thread per trip: a kernel of exactly known
+// HBM traffic (n bytes read, n written) against which hardware counters are calibrated.
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
+  if (bytes == 0) return hipSuccess;
+  if (bytes % 16) return hipErrorInvalidValue;
+  SN_LAUNCH(copy_kernel, dim3(2048), dim3(256), 0, st, (const u32x4*)src, (u32x4*)dst, bytes / 16);
+  return hipGetLastError();
+}
+
 static inline int grid_for(size_t n, int block) {
   size_t g = (n + block - 1) / block;
   return (int)(g < 1 ? 1 : (g > 4096 ? 4096 : g));
@@ -40,73 +53,112 @@ static inline int grid_for(size_t n, int block) {
 
 hipError_t launch_cast_in(int dtype, const void* in16, float* x32, size_t n, hipStream_t st) {
   if (n == 0) return hipSuccess;
-  SN_DISPATCH_T(dtype, hipLaunchKernelGGL(cast_in_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
+  SN_DISPATCH_T(dtype, SN_LAUNCH(cast_in_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
                                           (const uint16_t*)in16, x32, n));
   return hipGetLastError();
 }
 hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, hipStream_t st) {
   if (n == 0) return hipSuccess;
-  SN_DISPATCH_T(dtype, hipLaunchKernelGGL(cast_out_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
+  SN_DISPATCH_T(dtype, SN_LAUNCH(cast_out_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
                                           x32, (uint16_t*)out16, n));
   return hipGetLastError();
 }
 hipError_t launch_fill_hash(int dtype, void* out16, size_t n, uint32_t seed, hipStream_t st) {
   if (n == 0) return hipSuccess;
-  SN_DISPATCH_T(dtype, hipLaunchKernelGGL(fill_hash_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
+  SN_DISPATCH_T(dtype, SN_LAUNCH(fill_hash_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
                                           (uint16_t*)out16, n, seed));
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------
-// Normalisation over the hidden dimension: one 256-thread workgroup per token row,
-// fp32 statistics, 16-bit output.  LayerNorm uses the two-pass (centred) variance.
-__device__ __forceinline__ float block_sum_256(float v, float* red) {
+// Normalisation over the hidden dimension: one workgroup per token row, the row is read
+// once into registers (float4 per thread per trip), fp32 statistics, 16-bit output.
+// LayerNorm uses the two-pass (centred) variance.  BLOCK threads, at most MAXV float4
+// per thread: 1024 x 4 covers hidden <= 16384 for the few rows of a decode step,
+// 256 x 16 for the many rows of a prefill.
+template <int BLOCK>
+__device__ __forceinline__ float block_sum(float v, float* red) {
   v = wave_sum(v);
-  const int w = threadIdx.x >> 6;
   __syncthreads();                 // red may still be read from a previous call
-  if ((threadIdx.x & 63) == 0) red[w] = v;
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
-  return red[0] + red[1] + red[2] + red[3];
+  float t = 0.f;
+#pragma unroll
+  for (int w = 0; w < BLOCK / 64; ++w) t += red[w];
+  return t;
+}
+
+template <class T, bool LN, int BLOCK, int MAXV>
+__global__ __launch_bounds__(BLOCK) void norm_kernel(const float* __restrict__ x,
+                                                     const uint16_t* __restrict__ gain,
+                                                     const uint16_t* __restrict__ shift,
+                                                     uint16_t* __restrict__ u, int h, float eps) {
+  __shared__ float red[BLOCK / 64];
+  const f32x4* row = reinterpret_cast<const f32x4*>(x + (size_t)blockIdx.x * h);
+  uint16_t* out = u + (size_t)blockIdx.x * h;
+  const int nv = h >> 2;
+  const float inv_h = 1.0f / (float)h;
+  f32x4 v[MAXV];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int idx = threadIdx.x + i * BLOCK;
+    v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (idx < nv) v[i] = row[idx];
+    s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+  }
+  float mu = 0.f;
+  if (LN) mu = block_sum<BLOCK>(s, red) * inv_h;
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int idx = threadIdx.x + i * BLOCK;
+    if (idx < nv) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float c = v[i][e] - mu;
+        ss += c * c;
+      }
+    }
+  }
+  const float rstd = rsqrtf(block_sum<BLOCK>(ss, red) * inv_h + eps);
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int idx = threadIdx.x + i * BLOCK;
+    if (idx < nv) {
+      const u16x4 g = *reinterpret_cast<const u16x4*>(gain + idx * 4);
+      u16x4 b = u16x4{0, 0, 0, 0};
+      if (LN) b = *reinterpret_cast<const u16x4*>(shift + idx * 4);
+      u16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float r = (v[i][e] - mu) * rstd * to_f32<T>(g[e]);
+        if (LN) r += to_f32<T>(b[e]);
+        o[e] = from_f32<T>(r);
+      }
+      *reinterpret_cast<u16x4*>(out + idx * 4) = o;
+    }
+  }
 }
 
 template <class T, bool LN>
-__global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x,
-                                                   const uint16_t* __restrict__ gain,
-                                                   const uint16_t* __restrict__ shift,
-                                                   uint16_t* __restrict__ u, int h, float eps) {
-  __shared__ float red[4];
-  const float* row = x + (size_t)blockIdx.x * h;
-  uint16_t* out = u + (size_t)blockIdx.x * h;
-  const float inv_h = 1.0f / (float)h;
-  float mu = 0.f;
-  if (LN) {
-    float s = 0.f;
-    for (int i = threadIdx.x; i < h; i += 256) s += row[i];
-    mu = block_sum_256(s, red) * inv_h;
-  }
-  float ss = 0.f;
-  for (int i = threadIdx.x; i < h; i += 256) {
-    const float c = row[i] - mu;
-    ss += c * c;
-  }
-  const float rstd = rsqrtf(block_sum_256(ss, red) * inv_h + eps);
-  for (int i = threadIdx.x; i < h; i += 256) {
-    float v = (row[i] - mu) * rstd * to_f32<T>(gain[i]);
-    if (LN) v += to_f32<T>(shift[i]);
-    out[i] = from_f32<T>(v);
-  }
+static void launch_norm_t(const float* x32, const uint16_t* gain, const uint16_t* shift, uint16_t* u16, int Tn, int h,
+                          float eps, hipStream_t st) {
+  if (Tn <= 64)
+    SN_LAUNCH((norm_kernel<T, LN, 1024, 4>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps);
+  else
+    SN_LAUNCH((norm_kernel<T, LN, 256, 16>), dim3(Tn), dim3(256), 0, st, x32, gain, shift, u16, h, eps);
 }
 
 hipError_t launch_norm(int dtype, int is_ln, const float* x32, const void* gain, const void* shift,
                        void* u16, int Tn, int h, float eps, hipStream_t st) {
   if (Tn == 0) return hipSuccess;
+  if (h % 4 || h > 16384) return hipErrorInvalidValue;
   SN_DISPATCH_T(dtype, {
     if (is_ln)
-      hipLaunchKernelGGL((norm_kernel<T, true>), dim3(Tn), dim3(256), 0, st, x32, (const uint16_t*)gain,
-                         (const uint16_t*)shift, (uint16_t*)u16, h, eps);
+      launch_norm_t<T, true>(x32, (const uint16_t*)gain, (const uint16_t*)shift, (uint16_t*)u16, Tn, h, eps, st);
     else
-      hipLaunchKernelGGL((norm_kernel<T, false>), dim3(Tn), dim3(256), 0, st, x32, (const uint16_t*)gain,
-                         (const uint16_t*)nullptr, (uint16_t*)u16, h, eps);
+      launch_norm_t<T, false>(x32, (const uint16_t*)gain, nullptr, (uint16_t*)u16, Tn, h, eps, st);
   });
   return hipGetLastError();
 }
@@ -174,7 +226,7 @@ hipError_t launch_rope_append(int dtype, int kv_value_dtype, void* qkv16, const 
   if (total == 0) return hipSuccess;
   const unsigned grid = (unsigned)((total + 255) / 256);
 #define SN_ROPE(TT, RR)                                                                                     \
-  hipLaunchKernelGGL((rope_append_kernel<TT, RR>), dim3(grid), dim3(256), 0, st, (uint16_t*)qkv16, ix.tok_seq, \
+  SN_LAUNCH((rope_append_kernel<TT, RR>), dim3(grid), dim3(256), 0, st, (uint16_t*)qkv16, ix.tok_seq, \
                      ix.tok_pos, ix.kv_off, ix.cap, (uint16_t*)kv, (uint16_t*)mirror, inv_freq, Tn, Hq, Hkv, d, rope)
   if (dtype == 0 && kv_value_dtype == 0) SN_ROPE(F16, F16);
   else if (dtype == 0 && kv_value_dtype == 1) SN_ROPE(F16, BF16);

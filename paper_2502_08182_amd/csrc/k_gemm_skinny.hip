@@ -6,21 +6,26 @@
 // ((nb * K/32) + kb) * 1 KiB, so a wavefront reads each tile as one fully coalesced
 // 1 KiB request and feeds it straight to v_mfma_f32_16x16x32 as the A operand
 // (16 output features x 32 inputs); the B operand is the activation tile
-// (32 inputs x 16 token rows).  One workgroup owns 16 output features (or a gate/up
-// pair of 16 for SwiGLU); its KS wavefronts split K into contiguous ranges and their
-// fp32 partial tiles are summed through LDS in a fixed order (deterministic).
-#include "common.h"
+// (32 inputs x 16 token rows).  One workgroup owns 16*C output features; its KS
+// wavefronts split K into contiguous ranges and their fp32 partial tiles are summed
+// through LDS in a fixed order (deterministic).
 #include "kernels.h"
+#include "common.h"
 
 namespace sn {
 
-template <class T, int MT, int EPI>
+// MT: 16-row tiles of token rows; C: adjacent 16-column blocks per wavefront (each
+// activation fragment read from L2 is reused for C weight tiles, keeping activation
+// traffic at or below weight traffic for every M <= 64).
+template <class T, int MT, int C, int EPI>
 __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
     void* __restrict__ out, int M, int N, int K) {
   constexpr bool DUAL = EPI == EPI_SWIGLU16;
-  constexpr int NW = DUAL ? 2 : 1;          // weight tiles per k-block
-  extern __shared__ float red[];            // [KS][MT*NW][64][4]
+  static_assert(!DUAL || C % 2 == 0, "SwiGLU needs gate/up pairs");
+  constexpr int U = C >= 4 ? 1 : (C == 2 ? 2 : 4);     // k-blocks in flight per column block
+  constexpr bool SPLIT_ACC = MT * C == 1;              // lone accumulator: alternate two to hide MFMA latency
+  extern __shared__ float red[];                       // [KS][C][64][4], reused for each row tile
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int KS = blockDim.x >> 6;
@@ -28,12 +33,11 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
   const int per = (KB + KS - 1) / KS;
   const int kb0 = wave * per;
   const int kb1 = min(KB, kb0 + per);
-  const int nb = blockIdx.x;                // output block (16 columns of the result)
+  const int cb = blockIdx.x * C;                       // first 16-row block of the weight matrix
 
-  const uint16_t* w0 = W + ((size_t)(nb * NW) * KB) * 512 + lane * 8;
-  const uint16_t* w1 = w0 + (size_t)KB * 512;
+  const uint16_t* wp = W + ((size_t)cb * KB) * 512 + lane * 8;
+  const size_t wstride = (size_t)KB * 512;             // next column block
 
-  // activation rows this lane supplies (B operand: column = token row, 8 consecutive k)
   const uint16_t* xrow[MT];
   bool xok[MT];
 #pragma unroll
@@ -43,145 +47,173 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
     xrow[mt] = X + (size_t)(xok[mt] ? m : 0) * K + (lane >> 4) * 8;
   }
 
-  f32x4 acc[MT][NW];
+  f32x4 acc[MT][C];
+  f32x4 acc_b = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int j = 0; j < NW; ++j) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < C; ++c) acc[mt][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  constexpr int U = 4;
   int kb = kb0;
   for (; kb + U <= kb1; kb += U) {
-    u16x8 a0[U], a1[U];
+    u16x8 a[U][C], b[U][MT];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      a0[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(w0 + (size_t)(kb + u) * 512));
-      if (DUAL) a1[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(w1 + (size_t)(kb + u) * 512));
-    }
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+      for (int c = 0; c < C; ++c)
+        a[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(wp + c * wstride + (size_t)(kb + u) * 512));
+#pragma unroll
+    for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        u16x8 b = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-        if (xok[mt]) b = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)(kb + u) * 32);
-        acc[mt][0] = mma16x16x32<T>(a0[u], b, acc[mt][0]);
-        if (DUAL) acc[mt][NW - 1] = mma16x16x32<T>(a1[u], b, acc[mt][NW - 1]);
+        b[u][mt] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        if (xok[mt]) b[u][mt] = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)(kb + u) * 32);
       }
-    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+          if (SPLIT_ACC && (u & 1))
+            acc_b = mma16x16x32<T>(a[u][c], b[u][mt], acc_b);
+          else
+            acc[mt][c] = mma16x16x32<T>(a[u][c], b[u][mt], acc[mt][c]);
+        }
   }
   for (; kb < kb1; ++kb) {
-    const u16x8 a0 = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(w0 + (size_t)kb * 512));
-    u16x8 a1 = a0;
-    if (DUAL) a1 = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(w1 + (size_t)kb * 512));
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       u16x8 b = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
       if (xok[mt]) b = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)kb * 32);
-      acc[mt][0] = mma16x16x32<T>(a0, b, acc[mt][0]);
-      if (DUAL) acc[mt][NW - 1] = mma16x16x32<T>(a1, b, acc[mt][NW - 1]);
+#pragma unroll
+      for (int c = 0; c < C; ++c) {
+        const u16x8 a = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(wp + c * wstride + (size_t)kb * 512));
+        acc[mt][c] = mma16x16x32<T>(a, b, acc[mt][c]);
+      }
     }
   }
+  if (SPLIT_ACC) acc[0][0] += acc_b;
 
-  // fixed-order reduction of the KS partial tiles
-  constexpr int NACC = MT * NW;
+  // fixed-order reduction of the KS partial tiles, one row tile at a time
+  constexpr int ITEMS = DUAL ? C / 2 : C;              // epilogue work items per row tile
+  const int nl = (lane >> 4) * 4;                      // first of this lane's 4 columns in a block
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+  for (int mt = 0; mt < MT; ++mt) {
+    if (mt) __syncthreads();
 #pragma unroll
-    for (int j = 0; j < NW; ++j)
-      *reinterpret_cast<f32x4*>(red + ((size_t)(wave * NACC + mt * NW + j) * 64 + lane) * 4) = acc[mt][j];
-  __syncthreads();
-
-  for (int mt = wave; mt < MT; mt += KS) {
-    f32x4 s[NW];
-#pragma unroll
-    for (int j = 0; j < NW; ++j) {
-      s[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int w = 0; w < KS; ++w)
-        s[j] += *reinterpret_cast<const f32x4*>(red + ((size_t)(w * NACC + mt * NW + j) * 64 + lane) * 4);
-    }
+    for (int c = 0; c < C; ++c)
+      *reinterpret_cast<f32x4*>(red + ((size_t)(wave * C + c) * 64 + lane) * 4) = acc[mt][c];
+    __syncthreads();
     const int m = mt * 16 + (lane & 15);
-    if (m >= M) continue;
-    const int nl = (lane >> 4) * 4;                  // first of this lane's 4 columns in the block
-    const int n = nb * 16 + nl;                      // result column
-    if (EPI == EPI_SWIGLU16) {
-      const int F = N >> 1;
-      u16x4 o;
+    if (wave < ITEMS && m < M) {
+      const int c0 = DUAL ? wave * 2 : wave;
+      f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int w = 0; w < KS; ++w) {
+        s0 += *reinterpret_cast<const f32x4*>(red + ((size_t)(w * C + c0) * 64 + lane) * 4);
+        if (DUAL) s1 += *reinterpret_cast<const f32x4*>(red + ((size_t)(w * C + c0 + 1) * 64 + lane) * 4);
+      }
+      if (EPI == EPI_SWIGLU16) {
+        const int F = N >> 1;
+        const int n = ((cb >> 1) + wave) * 16 + nl;
+        u16x4 o;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float g = s[0][i], u = s[NW - 1][i];
-        if (bias) {
-          g += to_f32<T>(bias[n + i]);
-          u += to_f32<T>(bias[F + n + i]);
+        for (int i = 0; i < 4; ++i) {
+          float g = s0[i], u = s1[i];
+          if (bias) {
+            g += to_f32<T>(bias[n + i]);
+            u += to_f32<T>(bias[F + n + i]);
+          }
+          o[i] = from_f32<T>(silu(g) * u);
         }
-        o[i] = from_f32<T>(silu(g) * u);
-      }
-      *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + (size_t)m * F + n) = o;
-    } else if (EPI == EPI_RESID32) {
-      float* xr = static_cast<float*>(out) + (size_t)m * N + n;
-      f32x4 r = *reinterpret_cast<const f32x4*>(xr);
+        *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + (size_t)m * F + n) = o;
+      } else {
+        const int n = (cb + c0) * 16 + nl;
+        if (EPI == EPI_RESID32) {
+          float* xr = static_cast<float*>(out) + (size_t)m * N + n;
+          f32x4 r = *reinterpret_cast<const f32x4*>(xr);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) r[i] += s[0][i] + (bias ? to_f32<T>(bias[n + i]) : 0.f);
-      *reinterpret_cast<f32x4*>(xr) = r;
-    } else {
-      u16x4 o;
+          for (int i = 0; i < 4; ++i) r[i] += s0[i] + (bias ? to_f32<T>(bias[n + i]) : 0.f);
+          *reinterpret_cast<f32x4*>(xr) = r;
+        } else {
+          u16x4 o;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float v = s[0][i] + (bias ? to_f32<T>(bias[n + i]) : 0.f);
-        if (EPI == EPI_GELU16) v = gelu_erf(v);
-        o[i] = from_f32<T>(v);
+          for (int i = 0; i < 4; ++i) {
+            float v = s0[i] + (bias ? to_f32<T>(bias[n + i]) : 0.f);
+            if (EPI == EPI_GELU16) v = gelu_erf(v);
+            o[i] = from_f32<T>(v);
+          }
+          *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + (size_t)m * N + n) = o;
+        }
       }
-      *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + (size_t)m * N + n) = o;
     }
   }
 }
 
-// K-split per workgroup: enough wavefronts in flight to cover HBM latency on 256 CUs
-// (target ~4096 wavefronts), a power of two in [4, 16], never more than K/32 blocks
-// allow usefully, and at least as many as the epilogue needs.
-static int pick_ks(int n_blocks, int KB) {
-  int ks = 4;
-  while (ks < 16 && n_blocks * ks < 4096) ks <<= 1;
-  while (ks > 4 && ks > KB) ks >>= 1;
+// K-split per workgroup (wavefronts per workgroup).  Measured on MI355X with M = 8:
+// 8 wavefronts reach 6.0-6.2 TB/s on [12288|16384] x 4096 and 5.2 TB/s on 4096 x 4096;
+// 16 are better (5.35 vs 5.0 TB/s) only when few column groups meet a long K
+// (4096 x 16384).  Never fewer wavefronts than epilogue items (C <= 4).
+static int pick_ks(int groups, int KB) {
+  int ks = 8;
+  if (groups * ks < 4096 && KB / (2 * ks) >= 16) ks = 16;
   return ks;
 }
 
-template <class T, int MT>
-static hipError_t launch_mt(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
+template <class T, int MT, int C>
+static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
                             int M, int N, int K, hipStream_t st) {
   const int KB = K / 32;
-  const int nblk = epi == EPI_SWIGLU16 ? N / 32 : N / 16;
-  const int ks0 = pick_ks(nblk, KB);
-  const int nacc = MT * (epi == EPI_SWIGLU16 ? 2 : 1);
-  int ks = ks0;
-  while (ks * nacc > 64) ks >>= 1;          // partial tiles must fit 64 KiB of LDS
-  const size_t lds = (size_t)ks * nacc * 64 * 4 * sizeof(float);
-  dim3 grid(nblk), block(ks * 64);
+  const int groups = N / (16 * C);
+  const int ks = pick_ks(groups, KB);
+  const size_t lds = (size_t)ks * C * 64 * 4 * sizeof(float);     // <= 64 KiB (ks <= 16, C <= 4)
+  dim3 grid(groups), block(ks * 64);
   switch (epi) {
     case EPI_STORE16:
-      hipLaunchKernelGGL((gemm_skinny_kernel<T, MT, EPI_STORE16>), grid, block, lds, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_STORE16>), grid, block, lds, st, W, X, bias, out, M, N, K);
       break;
     case EPI_GELU16:
-      hipLaunchKernelGGL((gemm_skinny_kernel<T, MT, EPI_GELU16>), grid, block, lds, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_GELU16>), grid, block, lds, st, W, X, bias, out, M, N, K);
       break;
     case EPI_RESID32:
-      hipLaunchKernelGGL((gemm_skinny_kernel<T, MT, EPI_RESID32>), grid, block, lds, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_RESID32>), grid, block, lds, st, W, X, bias, out, M, N, K);
       break;
     case EPI_SWIGLU16:
-      hipLaunchKernelGGL((gemm_skinny_kernel<T, MT, EPI_SWIGLU16>), grid, block, lds, st, W, X, bias, out, M, N, K);
-      break;
+      if constexpr (C % 2 == 0) {
+        SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_SWIGLU16>), grid, block, lds, st, W, X, bias, out, M, N, K);
+        break;
+      }
+      return hipErrorInvalidValue;
     default:
       return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
+// Column blocks per wavefront: as many as row tiles (activation traffic <= weight
+// traffic), limited by what divides the number of 16-row weight blocks; SwiGLU needs
+// an even count (gate/up pairs).
 template <class T>
 static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out, int M,
                            int N, int K, hipStream_t st) {
-  if (M <= 16) return launch_mt<T, 1>(epi, W, X, bias, out, M, N, K, st);
-  if (M <= 32) return launch_mt<T, 2>(epi, W, X, bias, out, M, N, K, st);
-  if (M <= 48) return launch_mt<T, 3>(epi, W, X, bias, out, M, N, K, st);
-  return launch_mt<T, 4>(epi, W, X, bias, out, M, N, K, st);
+  const int nb = N / 16;
+  const bool dual = epi == EPI_SWIGLU16;
+  if (M <= 16) {
+    if (dual) return launch_mc<T, 1, 2>(epi, W, X, bias, out, M, N, K, st);
+    return launch_mc<T, 1, 1>(epi, W, X, bias, out, M, N, K, st);
+  }
+  if (M <= 32) {
+    if (nb % 2 == 0) return launch_mc<T, 2, 2>(epi, W, X, bias, out, M, N, K, st);
+    return launch_mc<T, 2, 1>(epi, W, X, bias, out, M, N, K, st);
+  }
+  if (M <= 48) {
+    if (nb % 4 == 0) return launch_mc<T, 3, 4>(epi, W, X, bias, out, M, N, K, st);
+    if (nb % 2 == 0) return launch_mc<T, 3, 2>(epi, W, X, bias, out, M, N, K, st);
+    return launch_mc<T, 3, 1>(epi, W, X, bias, out, M, N, K, st);
+  }
+  if (nb % 4 == 0) return launch_mc<T, 4, 4>(epi, W, X, bias, out, M, N, K, st);
+  if (nb % 2 == 0) return launch_mc<T, 4, 2>(epi, W, X, bias, out, M, N, K, st);
+  return launch_mc<T, 4, 1>(epi, W, X, bias, out, M, N, K, st);
 }
 
 hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, const void* bias, void* out,

@@ -8,8 +8,8 @@
 // activation rows are read as the B operand (8 consecutive k per lane).
 // D[feature][token]: a lane ends up with 4 consecutive features of one token, which
 // makes the row-major output store a short vector.
-#include "common.h"
 #include "kernels.h"
+#include "common.h"
 
 namespace sn {
 
@@ -116,16 +116,16 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
   dim3 grid((N / 16 + 7) / 8, (M + 127) / 128), block(256);
   switch (epi) {
     case EPI_STORE16:
-      hipLaunchKernelGGL((gemm_tile_kernel<T, EPI_STORE16>), grid, block, 0, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_tile_kernel<T, EPI_STORE16>), grid, block, 0, st, W, X, bias, out, M, N, K);
       break;
     case EPI_GELU16:
-      hipLaunchKernelGGL((gemm_tile_kernel<T, EPI_GELU16>), grid, block, 0, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_tile_kernel<T, EPI_GELU16>), grid, block, 0, st, W, X, bias, out, M, N, K);
       break;
     case EPI_RESID32:
-      hipLaunchKernelGGL((gemm_tile_kernel<T, EPI_RESID32>), grid, block, 0, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_tile_kernel<T, EPI_RESID32>), grid, block, 0, st, W, X, bias, out, M, N, K);
       break;
     case EPI_SWIGLU16:
-      hipLaunchKernelGGL((gemm_tile_kernel<T, EPI_SWIGLU16>), grid, block, 0, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_tile_kernel<T, EPI_SWIGLU16>), grid, block, 0, st, W, X, bias, out, M, N, K);
       break;
     default:
       return hipErrorInvalidValue;

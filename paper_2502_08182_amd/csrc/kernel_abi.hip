@@ -93,3 +93,8 @@ extern "C" int sn_k_cast_out(int32_t dtype, const void* x32, void* out16, uint64
   if (bad_dtype(dtype) || !x32 || !out16) return SN_E_INVAL;
   return rc_of(launch_cast_out(dtype, (const float*)x32, out16, n, (hipStream_t)stream));
 }
+
+extern "C" int sn_k_copy(const void* src, void* dst, uint64_t bytes, void* stream) {
+  if (!src || !dst || bytes % 16) return SN_E_INVAL;
+  return rc_of(launch_copy(src, dst, bytes, (hipStream_t)stream));
+}

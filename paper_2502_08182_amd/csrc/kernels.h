@@ -8,6 +8,14 @@
 
 namespace sn {
 
+// Optional timing of the NEXT kernel launch on this host thread: when start/stop are
+// set, the launch records the kernel's own begin and end timestamps into them (no
+// extra marker packets on the stream) and clears the pair.
+struct LaunchEvents {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+LaunchEvents& next_launch_events();
+
 enum Epilogue {
   EPI_STORE16 = 0,   // out16[m][n] = acc + bias
   EPI_GELU16 = 1,    // out16[m][n] = gelu(acc + bias)
@@ -30,6 +38,7 @@ struct StepIndex {
 
 hipError_t launch_cast_in(int dtype, const void* in16, float* x32, size_t n, hipStream_t st);
 hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, hipStream_t st);
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 hipError_t launch_fill_hash(int dtype, void* out16, size_t n, uint32_t seed, hipStream_t st);
 
 // u16[t][:] = norm(x32[t][:]) * gain (+ shift); shift == nullptr for RMSNorm.

@@ -31,6 +31,13 @@
 
 using namespace sn;
 
+namespace sn {
+LaunchEvents& next_launch_events() {
+  thread_local LaunchEvents le;
+  return le;
+}
+}  // namespace sn
+
 namespace {
 
 thread_local std::string g_err;
@@ -475,14 +482,17 @@ struct KTimer {   // optional per-kernel event pairs (timing level 2)
   int slot = 0;
   bool on;
   bool want(int cls) const { return on && (c->timing_class < 0 || c->timing_class == cls); }
+  // The first kernel launched after begin() records its own start/stop timestamps.
   void begin(int cls) {
-    if (want(cls)) (void)hipEventRecord(c->kev[((size_t)layer * kKernelsPerLayer + slot) * 2], c->compute);
+    if (want(cls)) {
+      LaunchEvents& le = next_launch_events();
+      le.start = c->kev[((size_t)layer * kKernelsPerLayer + slot) * 2];
+      le.stop = c->kev[((size_t)layer * kKernelsPerLayer + slot) * 2 + 1];
+    }
   }
   void end(int cls) {
-    if (want(cls)) {
-      (void)hipEventRecord(c->kev[((size_t)layer * kKernelsPerLayer + slot) * 2 + 1], c->compute);
-      c->last_kernel_class[slot] = (uint8_t)cls;
-    }
+    if (want(cls)) c->last_kernel_class[slot] = (uint8_t)cls;
+    next_launch_events() = LaunchEvents{};
     ++slot;
   }
 };
@@ -747,6 +757,53 @@ extern "C" int sn_get_stats(sn_ctx* c, sn_step_stats* out) {
         }
       }
   }
+  return SN_OK;
+}
+
+extern "C" int sn_time_kernel_class(sn_ctx* c, int32_t kernel_class, int32_t batch, int32_t reps, int64_t* total_ns,
+                                    int32_t* launches) {
+  if (!c || !total_ns || !launches) return fail(c, SN_E_INVAL, "sn_time_kernel_class: null argument");
+  if (!c->placed) return fail(c, SN_E_STATE, "sn_time_kernel_class before sn_place");
+  if (batch < 1 || batch > 64 || batch > c->shape.max_batch || reps < 1 || reps > 1000)
+    return fail(c, SN_E_INVAL, "sn_time_kernel_class: bad batch or reps");
+  const sn_model_shape& s = c->shape;
+  const PackedLayout& p = c->pl;
+  const int h = s.hidden, F = s.ffn, qd = s.n_q_heads * s.head_dim;
+  int rc = sync_all(c);
+  if (rc) return rc;
+  int n = 0;
+  SN_HIP(c, hipEventRecord(c->ev_iter_start, c->compute));
+  for (int r = 0; r < reps; ++r)
+    for (const LayerState& ls : c->layers) {
+      if (!ls.dev) continue;
+      auto at = [&](uint64_t off) -> const void* { return off == kNone ? nullptr : ls.dev + off; };
+      hipError_t e;
+      switch (kernel_class) {
+        case SN_K_QKV:
+          e = launch_gemm_skinny(SN_F16, EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, batch, p.n_qkv, h, c->compute);
+          break;
+        case SN_K_OPROJ:
+          e = launch_gemm_skinny(SN_F16, EPI_RESID32, at(p.wo), c->attn16, at(p.bo), c->x32, batch, h, qd, c->compute);
+          break;
+        case SN_K_FFN_UP:
+          e = launch_gemm_skinny(SN_F16, s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup),
+                                 c->act16, batch, p.n_up, h, c->compute);
+          break;
+        case SN_K_FFN_DOWN:
+          e = launch_gemm_skinny(SN_F16, EPI_RESID32, at(p.wd), c->act16, at(p.bd), c->x32, batch, h, F, c->compute);
+          break;
+        default:
+          return fail(c, SN_E_INVAL, "sn_time_kernel_class: only the four projection classes can be timed alone");
+      }
+      if (e != hipSuccess) return fail(c, SN_E_HIP, "sn_time_kernel_class: %s", hipGetErrorString(e));
+      ++n;
+    }
+  SN_HIP(c, hipEventRecord(c->ev_iter_end, c->compute));
+  SN_HIP(c, hipStreamSynchronize(c->compute));
+  if (n == 0) return fail(c, SN_E_STATE, "sn_time_kernel_class: no GPU-resident layer under this placement");
+  *total_ns = elapsed_ns(c->ev_iter_start, c->ev_iter_end);
+  *launches = n;
+  c->last_valid = false;
   return SN_OK;
 }
 

@@ -26,7 +26,7 @@ EXPORTS = (
     "sn_init", "sn_destroy", "sn_last_error", "sn_layer_blob_bytes", "sn_set_layer_weights", "sn_place",
     "sn_set_budget_enforce", "sn_resident_bytes", "sn_max_interval", "sn_placement", "sn_kv_reset", "sn_step",
     "sn_read_hidden_f32",
-    "sn_set_timing", "sn_set_kernel_timing_class", "sn_get_stats", "sn_get_layer_times", "sn_profile_layers", "sn_timeline",
+    "sn_set_timing", "sn_set_kernel_timing_class", "sn_time_kernel_class", "sn_get_stats", "sn_get_layer_times", "sn_profile_layers", "sn_timeline",
     "sn_pick_interval_from_times", "sn_pick_interval", "sn_paper_rule",
 )
 
@@ -97,6 +97,7 @@ def lib() -> C.CDLL:
         "sn_read_hidden_f32": (C.c_int, [ctx, C.c_void_p, u64]),
         "sn_set_timing": (C.c_int, [ctx, i32]),
         "sn_set_kernel_timing_class": (C.c_int, [ctx, i32]),
+        "sn_time_kernel_class": (C.c_int, [ctx, i32, i32, i32, pi64, pi32]),
         "sn_get_stats": (C.c_int, [ctx, C.POINTER(sn_step_stats)]),
         "sn_get_layer_times": (C.c_int, [ctx, pi64, pi64, pi64]),
         "sn_profile_layers": (C.c_int, [ctx, i32, i32, i32, i32, pi64, pi64]),
@@ -222,6 +223,13 @@ def sn_set_timing(ctx, level: int) -> None:
 
 def sn_set_kernel_timing_class(ctx, kernel_class: int) -> None:
     _check(lib().sn_set_kernel_timing_class(ctx, kernel_class), ctx)
+
+
+def sn_time_kernel_class(ctx, kernel_class: int, batch: int, reps: int = 1):
+    """Returns (total_ns, launches)."""
+    ns, n = C.c_int64(), C.c_int32()
+    _check(lib().sn_time_kernel_class(ctx, kernel_class, batch, reps, C.byref(ns), C.byref(n)), ctx)
+    return ns.value, n.value
 
 
 def sn_get_stats(ctx) -> sn_step_stats:

@@ -9,7 +9,7 @@ import numpy as np
 from . import sn as _sn
 
 EXPORTS = ("sn_k_tile_weights", "sn_k_norm", "sn_k_gemm", "sn_k_rope_append", "sn_k_attn_decode",
-           "sn_k_attn_prefill", "sn_k_cast_in", "sn_k_cast_out")
+           "sn_k_attn_prefill", "sn_k_cast_in", "sn_k_cast_out", "sn_k_copy")
 
 EPI_STORE16, EPI_GELU16, EPI_RESID32, EPI_SWIGLU16 = 0, 1, 2, 3
 PATH_SKINNY, PATH_TILE = 0, 1
@@ -31,6 +31,7 @@ def _lib():
             "sn_k_attn_prefill": [i32, v, v, v, v, v, v, v, v, v, v, i32, i32, i32, i32, v],
             "sn_k_cast_in": [i32, v, v, u64, v],
             "sn_k_cast_out": [i32, v, v, u64, v],
+            "sn_k_copy": [v, v, u64, v],
         }
         for name, args in sig.items():
             f = getattr(L, name)
@@ -90,3 +91,7 @@ def sn_k_cast_in(dtype, in16, x32, n, stream=0):
 
 def sn_k_cast_out(dtype, x32, out16, n, stream=0):
     _chk(_lib().sn_k_cast_out(dtype, _p(x32), _p(out16), n, stream))
+
+
+def sn_k_copy(src, dst, nbytes, stream=0):
+    _chk(_lib().sn_k_copy(_p(src), _p(dst), nbytes, stream))
