@@ -40,6 +40,8 @@ def parse():
                          "over the timeline's prediction: copies slow down slightly under concurrent compute)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB copy kernel (known HBM traffic) for counter calibration")
+    ap.add_argument("--slo-points", default="3,5,10",
+                    help="extra SLO factors (x all-resident TPOT) at which the picker is exercised and verified")
     ap.add_argument("--no-sweep", action="store_true", help="skip the interval sweep report")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--distinct-layers", type=int, default=0,
@@ -260,6 +262,36 @@ def main():
         sn_kernels.sn_k_copy(src, dst, 1 << 30, se.stream.cuda_stream)
         se.stream.synchronize()
         del src, dst
+
+    # ---- the picker at looser SLOs: pick, run, check every iteration (over-cap points labelled) ----
+    if not a.no_sweep and a.slo_points:
+        pts = []
+        for f in [float(v) for v in a.slo_points.split(",") if v]:
+            slo_f = int(f * tpot0_ns)
+            try:
+                n_f = sn.sn_pick_interval_from_times(tc, tx, int(slo_f * (1.0 - a.guard)), L + 1)
+            except sn.SnError:
+                n_f = L + 1
+            se.place(n_f)
+            fst, fwall, _ = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, max(4, min(K, 8)), 1)
+            fit = np.array([d["iter_ns"] for d in fst], dtype=np.float64)
+            fh = sum(d["h2d_ns"] for d in fst)
+            fs = sum(d["stall_ns"] for d in fst)
+            fb = sum(d["h2d_bytes"] for d in fst)
+            pred, _ = sn.sn_timeline(tc, tx, n_f)
+            pts.append({"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f),
+                        "n_offloaded": int(fst[-1]["n_offloaded"]), "tpot_median_ms": float(np.median(fit)) / 1e6,
+                        "tpot_max_ms": float(fit.max()) / 1e6, "predicted_ms": pred / 1e6,
+                        "every_iteration_within_slo": bool((fit <= slo_f).all()),
+                        "hidden_fraction": (1 - fs / fh) if fh else 1.0,
+                        "h2d_GBps": fb / (fh * 1e-9) / 1e9 if fh else None,
+                        "resident_GB": sn.sn_resident_bytes(se.ctx, n_f) / 1e9,
+                        "over_cap": bool(sn.sn_resident_bytes(se.ctx, n_f) > w.hbm_budget > 0),
+                        "tokens_per_s": B * 1e3 / fwall})
+            log(f"[bench] SLO {f}x = {slo_f / 1e6:.2f} ms: picked N={n_f} (K={pts[-1]['n_offloaded']}), TPOT median "
+                f"{pts[-1]['tpot_median_ms']:.3f} max {pts[-1]['tpot_max_ms']:.3f} (predicted {pred / 1e6:.3f}) "
+                f"within={pts[-1]['every_iteration_within_slo']} hidden {pts[-1]['hidden_fraction']:.3f}")
+        out["slo_points"] = pts
 
     # ---- interval sweep (reported, over-cap points labelled) ------------------------------------
     if not a.no_sweep:

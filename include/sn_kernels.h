@@ -41,6 +41,24 @@ int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, c
 int sn_k_gemm(int32_t dtype, int32_t epilogue, int32_t path, const void* W, const void* X,
               const void* bias, void* out, int32_t M, int32_t N, int32_t K, void* stream);
 
+/* Decode-phase residual projection with the K dimension split over `splits` workgroup
+ * ranges (1..8; 0: the library's choice): part[s][M][N] (fp32, device) receives the
+ * partial product of range s, without bias.  The consumer folds them into the residual
+ * stream in ascending s (sn_k_norm_fold, sn_k_cast_out_fold), which keeps the sum order
+ * fixed.  Returns the number of splits used (> 0) or a negative SN_E_* code. */
+int sn_k_gemm_splitk(int32_t dtype, const void* W, const void* X, void* part, int32_t M, int32_t N,
+                     int32_t K, int32_t splits, void* stream);
+
+/* sn_k_norm preceded by x32[t][:] += bias + sum_s part[s][t][:] (x32 is updated in place;
+ * bias 16-bit [h] or NULL; splits == 0: plain sn_k_norm). */
+int sn_k_norm_fold(int32_t dtype, int32_t is_ln, void* x32, const void* gain, const void* shift,
+                   void* out16, int32_t T, int32_t h, float eps, const void* part, int32_t splits,
+                   const void* bias, void* stream);
+
+/* The same fold followed by the fp32 -> 16-bit output cast (x32 updated in place). */
+int sn_k_cast_out_fold(int32_t dtype, void* x32, void* out16, int32_t T, int32_t h, const void* part,
+                       int32_t splits, const void* bias, void* stream);
+
 /* Index arrays shared by the attention-side kernels (device int32):
  *   len_before[B], n_new[B], tok_start[B], kv_off[B] (token offset of the sequence in the
  *   KV slice), cap[B]; tok_seq[T], tok_pos[T]; tile_seq[n_qtiles], tile_q0[n_qtiles].

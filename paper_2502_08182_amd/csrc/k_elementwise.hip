@@ -88,13 +88,29 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
-template <class T, bool LN, int BLOCK, int MAXV>
-__global__ __launch_bounds__(BLOCK) void norm_kernel(const float* __restrict__ x,
+// x32 row element group idx (4 floats) after folding pending split-K partials:
+// x += bias + part[0] + part[1] + ... (fixed order).
+template <class T>
+__device__ __forceinline__ f32x4 folded(f32x4 v, const float* __restrict__ part, int nsplit, size_t split_stride,
+                                        size_t off, const uint16_t* __restrict__ bias, int col) {
+  if (bias) {
+    const u16x4 b = *reinterpret_cast<const u16x4*>(bias + col);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += to_f32<T>(b[e]);
+  }
+  for (int s = 0; s < nsplit; ++s) v += *reinterpret_cast<const f32x4*>(part + (size_t)s * split_stride + off);
+  return v;
+}
+
+template <class T, bool LN, int BLOCK, int MAXV, bool FOLD>
+__global__ __launch_bounds__(BLOCK) void norm_kernel(float* __restrict__ x,
                                                      const uint16_t* __restrict__ gain,
                                                      const uint16_t* __restrict__ shift,
-                                                     uint16_t* __restrict__ u, int h, float eps) {
+                                                     uint16_t* __restrict__ u, int h, float eps,
+                                                     const float* __restrict__ part, int nsplit,
+                                                     const uint16_t* __restrict__ fbias) {
   __shared__ float red[BLOCK / 64];
-  const f32x4* row = reinterpret_cast<const f32x4*>(x + (size_t)blockIdx.x * h);
+  f32x4* row = reinterpret_cast<f32x4*>(x + (size_t)blockIdx.x * h);
   uint16_t* out = u + (size_t)blockIdx.x * h;
   const int nv = h >> 2;
   const float inv_h = 1.0f / (float)h;
@@ -104,7 +120,13 @@ __global__ __launch_bounds__(BLOCK) void norm_kernel(const float* __restrict__ x
   for (int i = 0; i < MAXV; ++i) {
     const int idx = threadIdx.x + i * BLOCK;
     v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (idx < nv) v[i] = row[idx];
+    if (idx < nv) {
+      v[i] = row[idx];
+      if (FOLD) {
+        v[i] = folded<T>(v[i], part, nsplit, (size_t)gridDim.x * h, (size_t)blockIdx.x * h + idx * 4, fbias, idx * 4);
+        row[idx] = v[i];
+      }
+    }
     s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
   }
   float mu = 0.f;
@@ -141,25 +163,72 @@ __global__ __launch_bounds__(BLOCK) void norm_kernel(const float* __restrict__ x
   }
 }
 
-template <class T, bool LN>
-static void launch_norm_t(const float* x32, const uint16_t* gain, const uint16_t* shift, uint16_t* u16, int Tn, int h,
-                          float eps, hipStream_t st) {
+template <class T, bool LN, bool FOLD>
+static void launch_norm_t(float* x32, const uint16_t* gain, const uint16_t* shift, uint16_t* u16, int Tn, int h,
+                          float eps, const Fold& f, hipStream_t st) {
+  const uint16_t* fb = (const uint16_t*)f.bias;
   if (Tn <= 64)
-    SN_LAUNCH((norm_kernel<T, LN, 1024, 4>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps);
+    SN_LAUNCH((norm_kernel<T, LN, 1024, 4, FOLD>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps, f.part,
+              f.nsplit, fb);
   else
-    SN_LAUNCH((norm_kernel<T, LN, 256, 16>), dim3(Tn), dim3(256), 0, st, x32, gain, shift, u16, h, eps);
+    SN_LAUNCH((norm_kernel<T, LN, 256, 16, FOLD>), dim3(Tn), dim3(256), 0, st, x32, gain, shift, u16, h, eps, f.part,
+              f.nsplit, fb);
+}
+
+hipError_t launch_norm_fold(int dtype, int is_ln, float* x32, const void* gain, const void* shift, void* u16, int Tn,
+                            int h, float eps, const Fold& fold, hipStream_t st) {
+  if (Tn == 0) return hipSuccess;
+  if (h % 4 || h > 16384) return hipErrorInvalidValue;
+  const bool f = fold.nsplit > 0;
+  SN_DISPATCH_T(dtype, {
+    const uint16_t* g = (const uint16_t*)gain;
+    const uint16_t* b = is_ln ? (const uint16_t*)shift : nullptr;
+    uint16_t* o = (uint16_t*)u16;
+    if (is_ln && f) launch_norm_t<T, true, true>(x32, g, b, o, Tn, h, eps, fold, st);
+    else if (is_ln) launch_norm_t<T, true, false>(x32, g, b, o, Tn, h, eps, fold, st);
+    else if (f) launch_norm_t<T, false, true>(x32, g, b, o, Tn, h, eps, fold, st);
+    else launch_norm_t<T, false, false>(x32, g, b, o, Tn, h, eps, fold, st);
+  });
+  return hipGetLastError();
 }
 
 hipError_t launch_norm(int dtype, int is_ln, const float* x32, const void* gain, const void* shift,
                        void* u16, int Tn, int h, float eps, hipStream_t st) {
+  return launch_norm_fold(dtype, is_ln, const_cast<float*>(x32), gain, shift, u16, Tn, h, eps, Fold{}, st);
+}
+
+// Fold pending partials into the residual stream, write it back and emit the 16-bit output.
+template <class T, class TB>
+__global__ __launch_bounds__(256) void cast_out_fold_kernel(float* __restrict__ x, uint16_t* __restrict__ out, int Tn,
+                                                            int h, const float* __restrict__ part, int nsplit,
+                                                            const uint16_t* __restrict__ fbias) {
+  const size_t nv = (size_t)Tn * h / 4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
+    f32x4 v = reinterpret_cast<f32x4*>(x)[i];
+    v = folded<TB>(v, part, nsplit, (size_t)Tn * h, i * 4, fbias, (int)((i * 4) % h));
+    reinterpret_cast<f32x4*>(x)[i] = v;
+    u16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = from_f32<T>(v[e]);
+    reinterpret_cast<u16x4*>(out)[i] = o;
+  }
+}
+
+hipError_t launch_cast_out_fold(int dtype, int bias_dtype, float* x32, void* out16, int Tn, int h, const Fold& fold,
+                                hipStream_t st) {
   if (Tn == 0) return hipSuccess;
-  if (h % 4 || h > 16384) return hipErrorInvalidValue;
-  SN_DISPATCH_T(dtype, {
-    if (is_ln)
-      launch_norm_t<T, true>(x32, (const uint16_t*)gain, (const uint16_t*)shift, (uint16_t*)u16, Tn, h, eps, st);
-    else
-      launch_norm_t<T, false>(x32, (const uint16_t*)gain, nullptr, (uint16_t*)u16, Tn, h, eps, st);
-  });
+  if (h % 4) return hipErrorInvalidValue;
+  const size_t nv = (size_t)Tn * h / 4;
+  const dim3 grid(grid_for(nv, 256)), block(256);
+  const uint16_t* fb = (const uint16_t*)fold.bias;
+#define SN_COF(TT, TB) \
+  SN_LAUNCH((cast_out_fold_kernel<TT, TB>), grid, block, 0, st, x32, (uint16_t*)out16, Tn, h, fold.part, fold.nsplit, fb)
+  if (dtype == 0 && bias_dtype == 0) SN_COF(F16, F16);
+  else if (dtype == 1 && bias_dtype == 0) SN_COF(BF16, F16);
+  else if (dtype == 1 && bias_dtype == 1) SN_COF(BF16, BF16);
+  else if (dtype == 0 && bias_dtype == 1) SN_COF(F16, BF16);
+  else return hipErrorInvalidValue;
+#undef SN_COF
   return hipGetLastError();
 }
 

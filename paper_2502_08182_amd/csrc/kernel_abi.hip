@@ -98,3 +98,35 @@ extern "C" int sn_k_copy(const void* src, void* dst, uint64_t bytes, void* strea
   if (!src || !dst || bytes % 16) return SN_E_INVAL;
   return rc_of(launch_copy(src, dst, bytes, (hipStream_t)stream));
 }
+
+extern "C" int sn_k_gemm_splitk(int32_t dtype, const void* W, const void* X, void* part, int32_t M, int32_t N, int32_t K,
+                                int32_t splits, void* stream) {
+  if (bad_dtype(dtype) || !W || !X || !part || M < 0 || M > 64 || N < 16 || K < 32) return SN_E_INVAL;
+  if (splits == 0) splits = gemm_skinny_splits(M, N, K);
+  if (splits < 1 || splits > kMaxSplits) return SN_E_INVAL;
+  const hipError_t e = launch_gemm_skinny(dtype, EPI_PART32, W, X, nullptr, part, M, N, K, (hipStream_t)stream, splits);
+  return e == hipSuccess ? splits : rc_of(e);
+}
+
+extern "C" int sn_k_norm_fold(int32_t dtype, int32_t is_ln, void* x32, const void* gain, const void* shift, void* out16,
+                              int32_t T, int32_t h, float eps, const void* part, int32_t splits, const void* bias,
+                              void* stream) {
+  if (bad_dtype(dtype) || !x32 || !gain || !out16 || T < 0 || h < 1 || (is_ln && !shift) || splits < 0 ||
+      splits > kMaxSplits || (splits > 0 && !part))
+    return SN_E_INVAL;
+  Fold f;
+  f.part = (const float*)part;
+  f.nsplit = splits;
+  f.bias = bias;
+  return rc_of(launch_norm_fold(dtype, is_ln, (float*)x32, gain, shift, out16, T, h, eps, f, (hipStream_t)stream));
+}
+
+extern "C" int sn_k_cast_out_fold(int32_t dtype, void* x32, void* out16, int32_t T, int32_t h, const void* part,
+                                  int32_t splits, const void* bias, void* stream) {
+  if (bad_dtype(dtype) || !x32 || !out16 || T < 0 || h < 4 || splits < 1 || splits > kMaxSplits || !part) return SN_E_INVAL;
+  Fold f;
+  f.part = (const float*)part;
+  f.nsplit = splits;
+  f.bias = bias;
+  return rc_of(launch_cast_out_fold(dtype, dtype, (float*)x32, out16, T, h, f, (hipStream_t)stream));
+}

@@ -20,7 +20,17 @@ enum Epilogue {
   EPI_STORE16 = 0,   // out16[m][n] = acc + bias
   EPI_GELU16 = 1,    // out16[m][n] = gelu(acc + bias)
   EPI_RESID32 = 2,   // x32[m][n] += acc + bias
-  EPI_SWIGLU16 = 3   // weights hold gate/up in alternating 16-row blocks: out16[m][n] = silu(g)*u
+  EPI_SWIGLU16 = 3,  // weights hold gate/up in alternating 16-row blocks: out16[m][n] = silu(g)*u
+  EPI_PART32 = 4     // split-K: part[split][m][n] = partial product (no bias); folded in by the consumer
+};
+constexpr int kMaxSplits = 8;
+
+// Pending split-K partial sums of a residual projection: the next kernel that reads the
+// residual stream first performs x32[m][n] += bias[n] + sum_s part[s][m][n] (s ascending).
+struct Fold {
+  const float* part = nullptr;   // [nsplit][T][h]
+  int nsplit = 0;
+  const void* bias = nullptr;    // 16-bit [h] or null
 };
 
 // Per-iteration index arrays (device int32), built on the host by sn_step.
@@ -38,17 +48,24 @@ struct StepIndex {
 
 hipError_t launch_cast_in(int dtype, const void* in16, float* x32, size_t n, hipStream_t st);
 hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, hipStream_t st);
+// Same after folding pending partial sums into x32 (written back); bias_dtype: type of fold.bias.
+hipError_t launch_cast_out_fold(int dtype, int bias_dtype, float* x32, void* out16, int T, int h, const Fold& fold,
+                                hipStream_t st);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 hipError_t launch_fill_hash(int dtype, void* out16, size_t n, uint32_t seed, hipStream_t st);
 
 // u16[t][:] = norm(x32[t][:]) * gain (+ shift); shift == nullptr for RMSNorm.
 hipError_t launch_norm(int dtype, int is_ln, const float* x32, const void* gain, const void* shift,
                        void* u16, int T, int h, float eps, hipStream_t st);
+// Same, after folding pending partial sums into x32 (x32 is updated in place).
+hipError_t launch_norm_fold(int dtype, int is_ln, float* x32, const void* gain, const void* shift, void* u16, int T,
+                            int h, float eps, const Fold& fold, hipStream_t st);
 
 // out = epilogue(X[M][K] * W^T), W tiled [N/16][K/32][64][8].  N counts weight rows
 // (2*ffn for EPI_SWIGLU16, whose output has N/2 columns).  Decode path: M <= 64.
 hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, const void* bias,
-                              void* out, int M, int N, int K, hipStream_t st);
+                              void* out, int M, int N, int K, hipStream_t st, int splits = 1);
+int gemm_skinny_splits(int M, int N, int K);
 // Prefill path: any M.
 hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, const void* bias,
                             void* out, int M, int N, int K, hipStream_t st);

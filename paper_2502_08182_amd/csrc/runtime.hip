@@ -78,6 +78,7 @@ struct sn_ctx {
   float* x32 = nullptr;
   uint16_t *u16 = nullptr, *qkv16 = nullptr, *attn16 = nullptr, *act16 = nullptr;
   float* part = nullptr;
+  float* part32 = nullptr;       // split-K partial sums of the decode residual projections
   float* inv_freq = nullptr;
   int32_t* meta_dev = nullptr;
   size_t meta_ints = 0;
@@ -231,7 +232,7 @@ extern "C" void sn_destroy(sn_ctx* c) {
   }
   for (auto& s : c->slot)
     if (s) (void)hipFree(s);
-  void* dev[] = {c->x32, c->u16, c->qkv16, c->attn16, c->act16, c->part, c->inv_freq, c->meta_dev};
+  void* dev[] = {c->x32, c->u16, c->qkv16, c->attn16, c->act16, c->part, c->part32, c->inv_freq, c->meta_dev};
   for (void* p : dev)
     if (p) (void)hipFree(p);
   for (int i = 0; i < kMetaRing; ++i) {
@@ -281,7 +282,8 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   c->meta_ints = (size_t)(5 * (uint64_t)s.max_batch + 2 * T + 2 * n_tiles_max);
   const uint64_t b_meta = align_up(c->meta_ints * 4);
   const uint64_t b_freq = align_up((uint64_t)s.head_dim / 2 * 4);
-  c->ws_bytes = b_x32 + b_u + b_qkv + b_attn + b_act + b_part + b_meta + b_freq;
+  const uint64_t b_part32 = align_up((uint64_t)kMaxSplits * std::min(s.max_batch, 64) * s.hidden * 4);
+  c->ws_bytes = b_x32 + b_u + b_qkv + b_attn + b_act + b_part + b_part32 + b_meta + b_freq;
 
   SN_HIP(c, hipStreamCreateWithFlags(&c->h2d, hipStreamNonBlocking));
   SN_HIP(c, hipStreamCreateWithFlags(&c->d2h, hipStreamNonBlocking));
@@ -291,6 +293,7 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   SN_HIP(c, hipMalloc(&c->attn16, b_attn));
   SN_HIP(c, hipMalloc(&c->act16, b_act));
   SN_HIP(c, hipMalloc(&c->part, b_part));
+  SN_HIP(c, hipMalloc(&c->part32, b_part32));
   SN_HIP(c, hipMalloc(&c->meta_dev, b_meta));
   SN_HIP(c, hipMalloc(&c->inv_freq, b_freq));
   {
@@ -497,8 +500,10 @@ struct KTimer {   // optional per-kernel event pairs (timing level 2)
   }
 };
 
+// `pending`: split-K partial sums of the previous residual projection that the next reader of
+// the residual stream (a norm, or the final cast) folds in.
 int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepIndex& ix, int T, int B,
-              bool prefill, int n_qtiles, int S) {
+              bool prefill, int n_qtiles, int S, Fold& pending) {
   const sn_model_shape& s = c->shape;
   const PackedLayout& p = c->pl;
   const int dt = SN_F16;   // compute and internal storage type (see sn_set_layer_weights)
@@ -513,8 +518,19 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
     return small ? launch_gemm_skinny(dt, epi, W, X, bias, out, T, N, K, st)
                  : launch_gemm_tile(dt, epi, W, X, bias, out, T, N, K, st);
   };
+  // residual projection: decode writes split-K partials (folded in by the next norm / cast),
+  // prefill adds into the residual stream in its epilogue
+  auto resid_gemm = [&](const void* W, const void* X, const void* bias, int K) -> hipError_t {
+    if (!small) return launch_gemm_tile(dt, EPI_RESID32, W, X, bias, c->x32, T, h, K, st);
+    const int sp = gemm_skinny_splits(T, h, K);
+    pending.part = c->part32;
+    pending.nsplit = sp;
+    pending.bias = bias;
+    return launch_gemm_skinny(dt, EPI_PART32, W, X, nullptr, c->part32, T, h, K, st, sp);
+  };
   kt.begin(SN_K_NORM);
-  SN_HIP(c, launch_norm(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, st));
+  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, pending, st));
+  pending = Fold{};
   kt.end(SN_K_NORM);
   kt.begin(SN_K_QKV);
   SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h));
@@ -529,16 +545,17 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
     SN_HIP(c, launch_attn_decode(dt, c->qkv16, kv, ix, c->attn16, c->part, B, Hq, Hkv, d, S, st));
   kt.end(SN_K_ATTN);
   kt.begin(SN_K_OPROJ);
-  SN_HIP(c, gemm(EPI_RESID32, at(p.wo), c->attn16, at(p.bo), c->x32, h, qd));
+  SN_HIP(c, resid_gemm(at(p.wo), c->attn16, at(p.bo), qd));
   kt.end(SN_K_OPROJ);
   kt.begin(SN_K_NORM);
-  SN_HIP(c, launch_norm(dt, s.norm == SN_NORM_LN, c->x32, at(p.n2g), at(p.n2b), c->u16, T, h, s.norm_eps, st));
+  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n2g), at(p.n2b), c->u16, T, h, s.norm_eps, pending, st));
+  pending = Fold{};
   kt.end(SN_K_NORM);
   kt.begin(SN_K_FFN_UP);
   SN_HIP(c, gemm(s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup), c->act16, p.n_up, h));
   kt.end(SN_K_FFN_UP);
   kt.begin(SN_K_FFN_DOWN);
-  SN_HIP(c, gemm(EPI_RESID32, at(p.wd), c->act16, at(p.bd), c->x32, h, F));
+  SN_HIP(c, resid_gemm(at(p.wd), c->act16, at(p.bd), F));
   kt.end(SN_K_FFN_DOWN);
   return SN_OK;
 }
@@ -635,6 +652,7 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
 
   SN_HIP(c, hipEventRecord(c->ev_iter_start, c->compute));
   SN_HIP(c, launch_cast_in(s.dtype, bt->hidden_in, c->x32, (size_t)T * s.hidden, c->compute));
+  Fold pending;
 
   for (int l = 0; l < L; ++l) {
     LayerState& ls = c->layers[l];
@@ -663,7 +681,7 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
       base = c->slot[ls.slot];
       if (!prefill) mirror = ls.host_kv_dev;                                 // decode: rows written through
     }
-    int rc = run_layer(c, l, base, mirror, ix, T, B, prefill, n_qtiles, S);
+    int rc = run_layer(c, l, base, mirror, ix, T, B, prefill, n_qtiles, S, pending);
     if (rc) return rc;
     if (ls.offloaded) {
       if (prefill) {
@@ -682,7 +700,10 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
     }
   }
   SN_HIP(c, hipEventRecord(c->ev_layer[L], c->compute));
-  SN_HIP(c, launch_cast_out(s.dtype, c->x32, hidden_out, (size_t)T * s.hidden, c->compute));
+  if (pending.nsplit > 0)
+    SN_HIP(c, launch_cast_out_fold(s.dtype, SN_F16, c->x32, hidden_out, T, s.hidden, pending, c->compute));
+  else
+    SN_HIP(c, launch_cast_out(s.dtype, c->x32, hidden_out, (size_t)T * s.hidden, c->compute));
   SN_HIP(c, hipEventRecord(c->ev_iter_end, c->compute));
 
   for (int b = 0; b < B; ++b) {
@@ -783,14 +804,16 @@ extern "C" int sn_time_kernel_class(sn_ctx* c, int32_t kernel_class, int32_t bat
           e = launch_gemm_skinny(SN_F16, EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, batch, p.n_qkv, h, c->compute);
           break;
         case SN_K_OPROJ:
-          e = launch_gemm_skinny(SN_F16, EPI_RESID32, at(p.wo), c->attn16, at(p.bo), c->x32, batch, h, qd, c->compute);
+          e = launch_gemm_skinny(SN_F16, EPI_PART32, at(p.wo), c->attn16, nullptr, c->part32, batch, h, qd, c->compute,
+                                 gemm_skinny_splits(batch, h, qd));
           break;
         case SN_K_FFN_UP:
           e = launch_gemm_skinny(SN_F16, s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup),
                                  c->act16, batch, p.n_up, h, c->compute);
           break;
         case SN_K_FFN_DOWN:
-          e = launch_gemm_skinny(SN_F16, EPI_RESID32, at(p.wd), c->act16, at(p.bd), c->x32, batch, h, F, c->compute);
+          e = launch_gemm_skinny(SN_F16, EPI_PART32, at(p.wd), c->act16, nullptr, c->part32, batch, h, F, c->compute,
+                                 gemm_skinny_splits(batch, h, F));
           break;
         default:
           return fail(c, SN_E_INVAL, "sn_time_kernel_class: only the four projection classes can be timed alone");

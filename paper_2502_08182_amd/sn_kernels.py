@@ -9,7 +9,7 @@ import numpy as np
 from . import sn as _sn
 
 EXPORTS = ("sn_k_tile_weights", "sn_k_norm", "sn_k_gemm", "sn_k_rope_append", "sn_k_attn_decode",
-           "sn_k_attn_prefill", "sn_k_cast_in", "sn_k_cast_out", "sn_k_copy")
+           "sn_k_attn_prefill", "sn_k_cast_in", "sn_k_cast_out", "sn_k_copy", "sn_k_gemm_splitk", "sn_k_norm_fold", "sn_k_cast_out_fold")
 
 EPI_STORE16, EPI_GELU16, EPI_RESID32, EPI_SWIGLU16 = 0, 1, 2, 3
 PATH_SKINNY, PATH_TILE = 0, 1
@@ -32,6 +32,9 @@ def _lib():
             "sn_k_cast_in": [i32, v, v, u64, v],
             "sn_k_cast_out": [i32, v, v, u64, v],
             "sn_k_copy": [v, v, u64, v],
+            "sn_k_gemm_splitk": [i32, v, v, v, i32, i32, i32, i32, v],
+            "sn_k_norm_fold": [i32, i32, v, v, v, v, i32, i32, C.c_float, v, i32, v, v],
+            "sn_k_cast_out_fold": [i32, v, v, i32, i32, v, i32, v, v],
         }
         for name, args in sig.items():
             f = getattr(L, name)
@@ -95,3 +98,19 @@ def sn_k_cast_out(dtype, x32, out16, n, stream=0):
 
 def sn_k_copy(src, dst, nbytes, stream=0):
     _chk(_lib().sn_k_copy(_p(src), _p(dst), nbytes, stream))
+
+
+def sn_k_gemm_splitk(dtype, W, X, part, M, N, K, splits=0, stream=0) -> int:
+    rc = _lib().sn_k_gemm_splitk(dtype, _p(W), _p(X), _p(part), M, N, K, splits, stream)
+    if rc <= 0:
+        _chk(rc if rc < 0 else -1)
+    return rc
+
+
+def sn_k_norm_fold(dtype, is_ln, x32, gain, shift, out16, T, h, eps, part, splits, bias, stream=0):
+    _chk(_lib().sn_k_norm_fold(dtype, int(is_ln), _p(x32), _p(gain), _p(shift), _p(out16), T, h, eps, _p(part), splits,
+                               _p(bias), stream))
+
+
+def sn_k_cast_out_fold(dtype, x32, out16, T, h, part, splits, bias, stream=0):
+    _chk(_lib().sn_k_cast_out_fold(dtype, _p(x32), _p(out16), T, h, _p(part), splits, _p(bias), stream))

@@ -242,3 +242,38 @@ def test_casts_are_exact(dtype):
     K.sn_k_cast_out(DT[dtype], torch.from_numpy(f).cuda(), back, 5000)
     torch.cuda.synchronize()
     assert np.array_equal(synth.widen(host16(back), dtype), ofw.round_to_storage(f.astype(np.float64), dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("splits", [0, 1, 3, 8])
+def test_splitk_projection_folded_into_norm_and_cast(dtype, splits):
+    """Residual projection as split-K partials, folded into the residual stream by the next
+    norm (and by the final cast): x + bias + X W^T, then LayerNorm / 16-bit rounding."""
+    rng = np.random.default_rng(6)
+    for M, N, Kd in [(8, 256, 1024), (33, 192, 416), (64, 512, 2048)]:
+        xb = synth.to_bits(rng.standard_normal((M, Kd)), dtype)
+        wb = synth.to_bits(rng.standard_normal((N, Kd)) * 0.05, dtype)
+        bb = synth.to_bits(rng.standard_normal(N) * 0.3, dtype)
+        g = synth.to_bits(1 + 0.1 * rng.standard_normal(N), dtype)
+        sh = synth.to_bits(0.1 * rng.standard_normal(N), dtype)
+        r0 = rng.standard_normal((M, N)).astype(np.float32)
+        tiled = K.sn_k_tile_weights(wb, N, Kd)
+        part = torch.full((8, M, N), float("nan"), dtype=torch.float32, device="cuda")
+        used = K.sn_k_gemm_splitk(DT[dtype], dev16(tiled), dev16(xb), part, M, N, Kd, splits)
+        assert used == splits or (splits == 0 and 1 <= used <= 8)
+        want_x = r0.astype(np.float64) + synth.widen(bb, dtype) + synth.widen(xb, dtype) @ synth.widen(wb, dtype).T
+        # folded into a LayerNorm
+        x = torch.from_numpy(r0.copy()).cuda()
+        out = torch.zeros(M, N, dtype=torch.int16, device="cuda")
+        K.sn_k_norm_fold(DT[dtype], True, x, dev16(g), dev16(sh), out, M, N, 1e-5, part, used, dev16(bb))
+        torch.cuda.synchronize()
+        got_x = x.cpu().numpy().astype(np.float64)
+        assert np.abs(got_x - want_x).max() <= 2e-5 * np.abs(want_x).max(), (M, N, Kd)
+        want_u = ofw.layer_norm(want_x, synth.widen(g, dtype), synth.widen(sh, dtype), 1e-5)
+        check(synth.widen(host16(out), dtype), want_u, dtype, f"norm_fold M={M} N={N} K={Kd} splits={used}")
+        # folded into the final cast
+        x2 = torch.from_numpy(r0.copy()).cuda()
+        K.sn_k_cast_out_fold(DT[dtype], x2, out, M, N, part, used, dev16(bb))
+        torch.cuda.synchronize()
+        assert np.array_equal(x2.cpu().numpy(), x.cpu().numpy())               # same fixed-order sum
+        assert np.array_equal(synth.widen(host16(out), dtype), ofw.round_to_storage(got_x, dtype))
