@@ -179,8 +179,9 @@ int sn_get_layer_times(sn_ctx* ctx, int64_t* compute_ns, int64_t* stall_ns, int6
  * Runs `reps` iterations of the given kind (prefill of `seq` tokens per sequence, or
  * one decode step on `seq` cached tokens) on generated inputs under the current
  * placement and reports per layer the median compute time tc_ns[l] (fence waits
- * excluded) and the time tx_ns[l] of a solo host-to-device transfer of that layer's
- * state (weights; plus its KV prefix for decode).  Host arrays [n_layers]; either
+ * excluded) and the time tx_ns[l] of a host-to-device transfer of that layer's state
+ * (weights; plus its KV prefix for decode), taken while the compute stream runs such
+ * iterations -- the condition under which prefetches run.  Host arrays [n_layers]; either
  * may be NULL.  Discards any live KV contents (lengths return to 0). */
 int sn_profile_layers(sn_ctx* ctx, int32_t is_prefill, int32_t batch, int32_t seq, int32_t reps,
                       int64_t* tc_ns, int64_t* tx_ns);

@@ -28,6 +28,14 @@ int64_t sn_k_tile_weights(const void* host_src, void* host_dst, int32_t N, int32
                           int32_t dst_row_block_stride, int32_t dst_row_block_offset,
                           int32_t bf16_to_f16);
 
+/* Row-tile packed activations (decode path).  An [M][K] 16-bit activation matrix can be
+ * stored in 16-row x 32-column tiles in matrix-core operand order, so that the decode
+ * projections read it in 1 KiB pieces: element (m, k) sits at element offset
+ *   (((m/16)*(K/32) + k/32)*64 + (m%16) + 16*((k%32)/8))*8 + k%8      (K % 32 == 0),
+ * and a buffer holds 16*ceil(M/16) rows.  sn_k_packed_offset returns that offset (host
+ * only).  Kernels take a flag where they can read or write this layout. */
+uint64_t sn_k_packed_offset(int32_t m, int32_t k, int32_t K);
+
 /* out16[t][:] = normalise(x32[t][:]) * gain (+ shift).  is_ln: LayerNorm (biased
  * variance) else RMSNorm (shift ignored).  x32 fp32 [T][h]; gain/shift 16-bit [h]. */
 int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, const void* shift,
@@ -37,9 +45,12 @@ int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, c
  * epilogue 0: 16-bit store; 1: GELU (erf) then 16-bit store; 2: out is the fp32 residual
  * stream [M][N], updated in place (+=); 3: SwiGLU -- W holds gate and up in alternating
  * 16-row blocks (N = 2*ffn rows), bias = [gate | up], out16[M][N/2] = silu(g)*u.
- * path 0: weight-streaming decode kernel (M <= 64); path 1: tiled prefill kernel. */
+ * path 0: weight-streaming decode kernel (M <= 64); path 1: tiled prefill kernel.
+ * flags (path 0 only): 1 = X is row-tile packed; 2 = the 16-bit output (epilogues 0, 1, 3)
+ * is written row-tile packed. */
 int sn_k_gemm(int32_t dtype, int32_t epilogue, int32_t path, const void* W, const void* X,
-              const void* bias, void* out, int32_t M, int32_t N, int32_t K, void* stream);
+              const void* bias, void* out, int32_t M, int32_t N, int32_t K, int32_t flags,
+              void* stream);
 
 /* Decode-phase residual projection with the K dimension split over `splits` workgroup
  * ranges (1..8; 0: the library's choice): part[s][M][N] (fp32, device) receives the
@@ -50,10 +61,11 @@ int sn_k_gemm_splitk(int32_t dtype, const void* W, const void* X, void* part, in
                      int32_t K, int32_t splits, void* stream);
 
 /* sn_k_norm preceded by x32[t][:] += bias + sum_s part[s][t][:] (x32 is updated in place;
- * bias 16-bit [h] or NULL; splits == 0: plain sn_k_norm). */
+ * bias 16-bit [h] or NULL; splits == 0: plain sn_k_norm).  packed_out != 0: out16 is
+ * written row-tile packed. */
 int sn_k_norm_fold(int32_t dtype, int32_t is_ln, void* x32, const void* gain, const void* shift,
                    void* out16, int32_t T, int32_t h, float eps, const void* part, int32_t splits,
-                   const void* bias, void* stream);
+                   const void* bias, int32_t packed_out, void* stream);
 
 /* The same fold followed by the fp32 -> 16-bit output cast (x32 updated in place). */
 int sn_k_cast_out_fold(int32_t dtype, void* x32, void* out16, int32_t T, int32_t h, const void* part,
@@ -79,10 +91,12 @@ int sn_k_rope_append(int32_t dtype, int32_t kv_value_dtype, void* qkv16, const i
 /* One query per sequence (row b of qkv16) over keys 0..len_before[b] (the new row was
  * appended first).  out16 [B][Hq*d].  splits S >= 1 key ranges; part: fp32 scratch
  * [B][Hq][S][d+2] (may be NULL when S == 1).  S == 0: the library's own choice for
- * max_len = max_b(len_before[b]) + 1, which must then be given. */
+ * max_len = max_b(len_before[b]) + 1, which must then be given.  packed_out != 0: out16
+ * is written row-tile packed (K = Hq*d). */
 int sn_k_attn_decode(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
                      const int32_t* kv_off, const int32_t* cap, void* out16, float* part, int32_t B,
-                     int32_t Hq, int32_t Hkv, int32_t d, int32_t S, int32_t max_len, void* stream);
+                     int32_t Hq, int32_t Hkv, int32_t d, int32_t S, int32_t max_len,
+                     int32_t packed_out, void* stream);
 
 /* Causal attention of each sequence's n_new tokens over len_before+n_new keys.
  * out16 [T][Hq*d]. */

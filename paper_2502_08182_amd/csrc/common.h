@@ -53,6 +53,15 @@ template <> __device__ __forceinline__ f32x4 mma16x16x32<BF16>(u16x8 a, u16x8 b,
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// ---- row-tile packed activations (decode path) ---------------------------------------
+// Element (m, k) of an [M][K] activation matrix stored as 16-row x 32-k tiles in
+// B-operand lane order: tile (m/16, k/32) at ((m/16)*(K/32) + k/32) KiB, inside it lane
+// (m%16) + 16*((k%32)/8) holds 8 consecutive k.  A wavefront then reads one tile as 64
+// consecutive 16-byte pieces instead of 16 row segments a power of two apart.
+__device__ __forceinline__ size_t packed_off(int m, int k, int KB) {
+  return ((((size_t)(m >> 4) * KB + (k >> 5)) * 64) + (m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+}
+
 // ---- wave64 reductions ----------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

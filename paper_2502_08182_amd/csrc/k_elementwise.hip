@@ -108,7 +108,7 @@ __global__ __launch_bounds__(BLOCK) void norm_kernel(float* __restrict__ x,
                                                      const uint16_t* __restrict__ shift,
                                                      uint16_t* __restrict__ u, int h, float eps,
                                                      const float* __restrict__ part, int nsplit,
-                                                     const uint16_t* __restrict__ fbias) {
+                                                     const uint16_t* __restrict__ fbias, int packed) {
   __shared__ float red[BLOCK / 64];
   f32x4* row = reinterpret_cast<f32x4*>(x + (size_t)blockIdx.x * h);
   uint16_t* out = u + (size_t)blockIdx.x * h;
@@ -158,43 +158,46 @@ __global__ __launch_bounds__(BLOCK) void norm_kernel(float* __restrict__ x,
         if (LN) r += to_f32<T>(b[e]);
         o[e] = from_f32<T>(r);
       }
-      *reinterpret_cast<u16x4*>(out + idx * 4) = o;
+      if (packed)
+        *reinterpret_cast<u16x4*>(u + packed_off(blockIdx.x, idx * 4, h >> 5)) = o;
+      else
+        *reinterpret_cast<u16x4*>(out + idx * 4) = o;
     }
   }
 }
 
 template <class T, bool LN, bool FOLD>
 static void launch_norm_t(float* x32, const uint16_t* gain, const uint16_t* shift, uint16_t* u16, int Tn, int h,
-                          float eps, const Fold& f, hipStream_t st) {
+                          float eps, const Fold& f, int packed, hipStream_t st) {
   const uint16_t* fb = (const uint16_t*)f.bias;
   if (Tn <= 64)
     SN_LAUNCH((norm_kernel<T, LN, 1024, 4, FOLD>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps, f.part,
-              f.nsplit, fb);
+              f.nsplit, fb, packed);
   else
     SN_LAUNCH((norm_kernel<T, LN, 256, 16, FOLD>), dim3(Tn), dim3(256), 0, st, x32, gain, shift, u16, h, eps, f.part,
-              f.nsplit, fb);
+              f.nsplit, fb, packed);
 }
 
 hipError_t launch_norm_fold(int dtype, int is_ln, float* x32, const void* gain, const void* shift, void* u16, int Tn,
-                            int h, float eps, const Fold& fold, hipStream_t st) {
+                            int h, float eps, const Fold& fold, hipStream_t st, int packed) {
   if (Tn == 0) return hipSuccess;
-  if (h % 4 || h > 16384) return hipErrorInvalidValue;
+  if (h % 4 || h > 16384 || (packed && h % 32)) return hipErrorInvalidValue;
   const bool f = fold.nsplit > 0;
   SN_DISPATCH_T(dtype, {
     const uint16_t* g = (const uint16_t*)gain;
     const uint16_t* b = is_ln ? (const uint16_t*)shift : nullptr;
     uint16_t* o = (uint16_t*)u16;
-    if (is_ln && f) launch_norm_t<T, true, true>(x32, g, b, o, Tn, h, eps, fold, st);
-    else if (is_ln) launch_norm_t<T, true, false>(x32, g, b, o, Tn, h, eps, fold, st);
-    else if (f) launch_norm_t<T, false, true>(x32, g, b, o, Tn, h, eps, fold, st);
-    else launch_norm_t<T, false, false>(x32, g, b, o, Tn, h, eps, fold, st);
+    if (is_ln && f) launch_norm_t<T, true, true>(x32, g, b, o, Tn, h, eps, fold, packed, st);
+    else if (is_ln) launch_norm_t<T, true, false>(x32, g, b, o, Tn, h, eps, fold, packed, st);
+    else if (f) launch_norm_t<T, false, true>(x32, g, b, o, Tn, h, eps, fold, packed, st);
+    else launch_norm_t<T, false, false>(x32, g, b, o, Tn, h, eps, fold, packed, st);
   });
   return hipGetLastError();
 }
 
 hipError_t launch_norm(int dtype, int is_ln, const float* x32, const void* gain, const void* shift,
                        void* u16, int Tn, int h, float eps, hipStream_t st) {
-  return launch_norm_fold(dtype, is_ln, const_cast<float*>(x32), gain, shift, u16, Tn, h, eps, Fold{}, st);
+  return launch_norm_fold(dtype, is_ln, const_cast<float*>(x32), gain, shift, u16, Tn, h, eps, Fold{}, st, 0);
 }
 
 // Fold pending partials into the residual stream, write it back and emit the 16-bit output.

@@ -20,7 +20,7 @@ namespace sn {
 template <class T, int MT, int C, int EPI>
 __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
-    void* __restrict__ out, int M, int N, int K) {
+    void* __restrict__ out, int M, int N, int K, int xpacked, int opacked) {
   constexpr bool DUAL = EPI == EPI_SWIGLU16;
   static_assert(!DUAL || C % 2 == 0, "SwiGLU needs gate/up pairs");
   constexpr int U = C >= 4 ? 1 : (C == 2 ? 2 : 4);     // k-blocks in flight per column block
@@ -48,8 +48,9 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
   for (int mt = 0; mt < MT; ++mt) {
     const int m = mt * 16 + (lane & 15);
     xok[mt] = m < M;
-    xrow[mt] = X + (size_t)(xok[mt] ? m : 0) * K + (lane >> 4) * 8;
+    xrow[mt] = xpacked ? X + ((size_t)mt * KB * 64 + lane) * 8 : X + (size_t)(xok[mt] ? m : 0) * K + (lane >> 4) * 8;
   }
+  const int xstep = xpacked ? 512 : 32;                // elements from one k-block to the next
 
   f32x4 acc[MT][C];
   f32x4 acc_b = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           b[u][mt] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-          if (xok[mt]) b[u][mt] = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)(kb + u) * 32);
+          if (xok[mt]) b[u][mt] = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)(kb + u) * xstep);
         }
 #pragma unroll
       for (int u = 0; u < U; ++u)
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         u16x8 b = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-        if (xok[mt]) b = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)kb * 32);
+        if (xok[mt]) b = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)kb * xstep);
 #pragma unroll
         for (int c = 0; c < C; ++c) {
           const u16x8 a = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(wp + c * wstride + (size_t)kb * 512));
@@ -140,7 +141,8 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
           }
           o[i] = from_f32<T>(silu(g) * u);
         }
-        *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + (size_t)m * F + n) = o;
+        const size_t at = opacked ? packed_off(m, n, F >> 5) : (size_t)m * F + n;
+        *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + at) = o;
       } else {
         const int n = (cb + c0) * 16 + nl;
         if (EPI == EPI_PART32) {
@@ -159,7 +161,8 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
             if (EPI == EPI_GELU16) v = gelu_erf(v);
             o[i] = from_f32<T>(v);
           }
-          *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + (size_t)m * N + n) = o;
+          const size_t at = opacked ? packed_off(m, n, N >> 5) : (size_t)m * N + n;
+          *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + at) = o;
         }
       }
     }
@@ -178,7 +181,7 @@ static int pick_ks(int groups, int KB) {
 
 template <class T, int MT, int C>
 static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
-                            int M, int N, int K, int splits, hipStream_t st) {
+                            int M, int N, int K, int splits, int xpacked, int opacked, hipStream_t st) {
   const int KB = K / 32;
   const int groups = N / (16 * C);
   const int ks = epi == EPI_PART32 ? 4 : pick_ks(groups, KB);
@@ -186,20 +189,20 @@ static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const
   dim3 grid(groups, epi == EPI_PART32 ? splits : 1), block(ks * 64);
   switch (epi) {
     case EPI_PART32:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_PART32>), grid, block, lds, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_PART32>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
       break;
     case EPI_STORE16:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_STORE16>), grid, block, lds, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_STORE16>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
       break;
     case EPI_GELU16:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_GELU16>), grid, block, lds, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_GELU16>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
       break;
     case EPI_RESID32:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_RESID32>), grid, block, lds, st, W, X, bias, out, M, N, K);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_RESID32>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
       break;
     case EPI_SWIGLU16:
       if constexpr (C % 2 == 0) {
-        SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_SWIGLU16>), grid, block, lds, st, W, X, bias, out, M, N, K);
+        SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_SWIGLU16>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
         break;
       }
       return hipErrorInvalidValue;
@@ -214,35 +217,38 @@ static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const
 // an even count (gate/up pairs).
 template <class T>
 static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out, int M,
-                           int N, int K, int splits, hipStream_t st) {
+                           int N, int K, int splits, int xpacked, int opacked, hipStream_t st) {
   const int nb = N / 16;
   const bool dual = epi == EPI_SWIGLU16;
   if (M <= 16) {
-    if (dual) return launch_mc<T, 1, 2>(epi, W, X, bias, out, M, N, K, splits, st);
-    return launch_mc<T, 1, 1>(epi, W, X, bias, out, M, N, K, splits, st);
+    if (dual) return launch_mc<T, 1, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    return launch_mc<T, 1, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
   }
   if (M <= 32) {
-    if (nb % 2 == 0) return launch_mc<T, 2, 2>(epi, W, X, bias, out, M, N, K, splits, st);
-    return launch_mc<T, 2, 1>(epi, W, X, bias, out, M, N, K, splits, st);
+    if (nb % 2 == 0) return launch_mc<T, 2, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    return launch_mc<T, 2, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
   }
   if (M <= 48) {
-    if (nb % 4 == 0) return launch_mc<T, 3, 4>(epi, W, X, bias, out, M, N, K, splits, st);
-    if (nb % 2 == 0) return launch_mc<T, 3, 2>(epi, W, X, bias, out, M, N, K, splits, st);
-    return launch_mc<T, 3, 1>(epi, W, X, bias, out, M, N, K, splits, st);
+    if (nb % 4 == 0) return launch_mc<T, 3, 4>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    if (nb % 2 == 0) return launch_mc<T, 3, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    return launch_mc<T, 3, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
   }
-  if (nb % 4 == 0) return launch_mc<T, 4, 4>(epi, W, X, bias, out, M, N, K, splits, st);
-  if (nb % 2 == 0) return launch_mc<T, 4, 2>(epi, W, X, bias, out, M, N, K, splits, st);
-  return launch_mc<T, 4, 1>(epi, W, X, bias, out, M, N, K, splits, st);
+  if (nb % 4 == 0) return launch_mc<T, 4, 4>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+  if (nb % 2 == 0) return launch_mc<T, 4, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+  return launch_mc<T, 4, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
 }
 
 hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, const void* bias, void* out,
-                              int M, int N, int K, hipStream_t st, int splits) {
+                              int M, int N, int K, hipStream_t st, int splits, int flags) {
+  const int xpacked = flags & kXPacked ? 1 : 0, opacked = flags & kOutPacked ? 1 : 0;
+  if (opacked && (epi == EPI_RESID32 || epi == EPI_PART32)) return hipErrorInvalidValue;
+  if (opacked && (epi == EPI_SWIGLU16 ? (N / 2) % 32 : N % 32)) return hipErrorInvalidValue;
   if (M <= 0) return hipSuccess;
   if (M > 64 || N % 16 || K % 32 || (epi == EPI_SWIGLU16 && N % 32)) return hipErrorInvalidValue;
   if (epi == EPI_PART32 ? (splits < 1 || splits > kMaxSplits) : splits != 1) return hipErrorInvalidValue;
   if (dtype == 0)
-    return launch_t<F16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, splits, st);
-  return launch_t<BF16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, splits, st);
+    return launch_t<F16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, splits, xpacked, opacked, st);
+  return launch_t<BF16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, splits, xpacked, opacked, st);
 }
 
 // Split count for the residual projections of a decode step (few output features, long

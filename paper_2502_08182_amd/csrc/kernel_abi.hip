@@ -12,6 +12,11 @@ using namespace sn;
 static int rc_of(hipError_t e) { return e == hipSuccess ? SN_OK : (e == hipErrorInvalidValue ? SN_E_INVAL : SN_E_HIP); }
 static bool bad_dtype(int d) { return d != SN_F16 && d != SN_BF16; }
 
+extern "C" uint64_t sn_k_packed_offset(int32_t m, int32_t k, int32_t K) {
+  const int KB = K / 32;
+  return ((((uint64_t)(m >> 4) * KB + (k >> 5)) * 64) + (m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+}
+
 extern "C" int64_t sn_k_tile_weights(const void* src, void* dst, int32_t N, int32_t K, int32_t stride, int32_t offset,
                                      int32_t bf16_to_f16) {
   if (!src || !dst || N < 16 || K < 32 || N % 16 || K % 32 || stride < 1 || offset < 0 || offset >= stride)
@@ -27,10 +32,11 @@ extern "C" int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const vo
 }
 
 extern "C" int sn_k_gemm(int32_t dtype, int32_t epi, int32_t path, const void* W, const void* X, const void* bias,
-                         void* out, int32_t M, int32_t N, int32_t K, void* stream) {
-  if (bad_dtype(dtype) || !W || !X || !out || M < 0 || N < 16 || K < 32 || epi < 0 || epi > 3) return SN_E_INVAL;
-  if (path == 0) return rc_of(launch_gemm_skinny(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream));
-  if (path == 1) return rc_of(launch_gemm_tile(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream));
+                         void* out, int32_t M, int32_t N, int32_t K, int32_t flags, void* stream) {
+  if (bad_dtype(dtype) || !W || !X || !out || M < 0 || N < 16 || K < 32 || epi < 0 || epi > 3 || flags < 0 || flags > 3)
+    return SN_E_INVAL;
+  if (path == 0) return rc_of(launch_gemm_skinny(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream, 1, flags));
+  if (path == 1 && flags == 0) return rc_of(launch_gemm_tile(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream));
   return SN_E_INVAL;
 }
 
@@ -51,7 +57,8 @@ extern "C" int sn_k_rope_append(int32_t dtype, int32_t kv_value_dtype, void* qkv
 
 extern "C" int sn_k_attn_decode(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
                                 const int32_t* kv_off, const int32_t* cap, void* out16, float* part, int32_t B,
-                                int32_t Hq, int32_t Hkv, int32_t d, int32_t S, int32_t max_len, void* stream) {
+                                int32_t Hq, int32_t Hkv, int32_t d, int32_t S, int32_t max_len, int32_t packed_out,
+                                void* stream) {
   if (bad_dtype(dtype) || !qkv16 || !kv || !len_before || !kv_off || !cap || !out16 || B < 0 || Hq < 1 || Hkv < 1 ||
       Hq % Hkv || (d != 64 && d != 128) || S < 0 || S > 16)
     return SN_E_INVAL;
@@ -64,7 +71,7 @@ extern "C" int sn_k_attn_decode(int32_t dtype, const void* qkv16, const void* kv
   ix.len_before = len_before;
   ix.kv_off = kv_off;
   ix.cap = cap;
-  return rc_of(launch_attn_decode(dtype, qkv16, kv, ix, out16, part, B, Hq, Hkv, d, S, (hipStream_t)stream));
+  return rc_of(launch_attn_decode(dtype, qkv16, kv, ix, out16, part, B, Hq, Hkv, d, S, (hipStream_t)stream, packed_out != 0));
 }
 
 extern "C" int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
@@ -110,7 +117,7 @@ extern "C" int sn_k_gemm_splitk(int32_t dtype, const void* W, const void* X, voi
 
 extern "C" int sn_k_norm_fold(int32_t dtype, int32_t is_ln, void* x32, const void* gain, const void* shift, void* out16,
                               int32_t T, int32_t h, float eps, const void* part, int32_t splits, const void* bias,
-                              void* stream) {
+                              int32_t packed_out, void* stream) {
   if (bad_dtype(dtype) || !x32 || !gain || !out16 || T < 0 || h < 1 || (is_ln && !shift) || splits < 0 ||
       splits > kMaxSplits || (splits > 0 && !part))
     return SN_E_INVAL;
@@ -118,7 +125,7 @@ extern "C" int sn_k_norm_fold(int32_t dtype, int32_t is_ln, void* x32, const voi
   f.part = (const float*)part;
   f.nsplit = splits;
   f.bias = bias;
-  return rc_of(launch_norm_fold(dtype, is_ln, (float*)x32, gain, shift, out16, T, h, eps, f, (hipStream_t)stream));
+  return rc_of(launch_norm_fold(dtype, is_ln, (float*)x32, gain, shift, out16, T, h, eps, f, (hipStream_t)stream, packed_out != 0));
 }
 
 extern "C" int sn_k_cast_out_fold(int32_t dtype, void* x32, void* out16, int32_t T, int32_t h, const void* part,

@@ -59,12 +59,15 @@ hipError_t launch_norm(int dtype, int is_ln, const float* x32, const void* gain,
                        void* u16, int T, int h, float eps, hipStream_t st);
 // Same, after folding pending partial sums into x32 (x32 is updated in place).
 hipError_t launch_norm_fold(int dtype, int is_ln, float* x32, const void* gain, const void* shift, void* u16, int T,
-                            int h, float eps, const Fold& fold, hipStream_t st);
+                            int h, float eps, const Fold& fold, hipStream_t st, int packed_out = 0);
 
 // out = epilogue(X[M][K] * W^T), W tiled [N/16][K/32][64][8].  N counts weight rows
 // (2*ffn for EPI_SWIGLU16, whose output has N/2 columns).  Decode path: M <= 64.
+// flags: kXPacked -- X is row-tile packed (common.h packed_off); kOutPacked -- the 16-bit
+// output is written row-tile packed (it feeds the next decode projection).
+constexpr int kXPacked = 1, kOutPacked = 2;
 hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, const void* bias,
-                              void* out, int M, int N, int K, hipStream_t st, int splits = 1);
+                              void* out, int M, int N, int K, hipStream_t st, int splits = 1, int flags = 0);
 int gemm_skinny_splits(int M, int N, int K);
 // Prefill path: any M.
 hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, const void* bias,
@@ -84,7 +87,7 @@ hipError_t launch_rope_append(int dtype, int kv_value_dtype, void* qkv16, const 
 int attn_decode_splits(int B, int Hkv, int max_len);
 hipError_t launch_attn_decode(int dtype, const void* qkv16, const void* kv, const StepIndex& ix,
                               void* out16, float* part, int B, int Hq, int Hkv, int d, int S,
-                              hipStream_t st);
+                              hipStream_t st, int packed_out = 0);
 // Causal attention of each sequence's new tokens over its cached + new keys.
 hipError_t launch_attn_prefill(int dtype, const void* qkv16, const void* kv, const StepIndex& ix,
                                void* out16, int n_qtiles, int Hq, int Hkv, int d, hipStream_t st);

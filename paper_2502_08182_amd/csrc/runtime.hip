@@ -271,7 +271,8 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   if (c->max_tokens < s.max_batch) c->max_tokens = s.max_batch;
   if (c->max_tokens > (int64_t)1 << 24) return fail(c, SN_E_INVAL, "max_tokens too large");
   const int L = s.n_layers;
-  const uint64_t T = (uint64_t)c->max_tokens;
+  // decode activations are stored in 16-row tiles: keep room for whole tiles
+  const uint64_t T = std::max<uint64_t>((uint64_t)c->max_tokens, (uint64_t)((std::min(s.max_batch, 64) + 15) / 16 * 16));
   const uint64_t qkv_ld = (uint64_t)c->pl.n_qkv, qd = (uint64_t)s.n_q_heads * s.head_dim;
 
   const uint64_t b_x32 = align_up(T * s.hidden * 4), b_u = align_up(T * s.hidden * 2);
@@ -514,8 +515,12 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
   hipStream_t st = c->compute;
   const bool small = !prefill;   // decode path: T == B <= 64
   KTimer kt{c, l, 0, c->timing >= 2};
-  auto gemm = [&](int epi, const void* W, const void* X, const void* bias, void* out, int N, int K) {
-    return small ? launch_gemm_skinny(dt, epi, W, X, bias, out, T, N, K, st)
+  // decode: activations between kernels are row-tile packed (inputs of the skinny GEMMs);
+  // the QKV output stays row-major for the attention kernels
+  const int pk = small ? 1 : 0;
+  auto gemm = [&](int epi, const void* W, const void* X, const void* bias, void* out, int N, int K, bool out_feeds_gemm) {
+    return small ? launch_gemm_skinny(dt, epi, W, X, bias, out, T, N, K, st, 1,
+                                      kXPacked | (out_feeds_gemm ? kOutPacked : 0))
                  : launch_gemm_tile(dt, epi, W, X, bias, out, T, N, K, st);
   };
   // residual projection: decode writes split-K partials (folded in by the next norm / cast),
@@ -526,14 +531,14 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
     pending.part = c->part32;
     pending.nsplit = sp;
     pending.bias = bias;
-    return launch_gemm_skinny(dt, EPI_PART32, W, X, nullptr, c->part32, T, h, K, st, sp);
+    return launch_gemm_skinny(dt, EPI_PART32, W, X, nullptr, c->part32, T, h, K, st, sp, kXPacked);
   };
   kt.begin(SN_K_NORM);
-  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, pending, st));
+  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, pending, st, pk));
   pending = Fold{};
   kt.end(SN_K_NORM);
   kt.begin(SN_K_QKV);
-  SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h));
+  SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h, false));
   kt.end(SN_K_QKV);
   kt.begin(SN_K_ROPE_APPEND);
   SN_HIP(c, launch_rope_append(dt, dt, c->qkv16, ix, kv, mirror_kv, c->inv_freq, T, Hq, Hkv, d, s.rope, st));
@@ -542,17 +547,17 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
   if (prefill)
     SN_HIP(c, launch_attn_prefill(dt, c->qkv16, kv, ix, c->attn16, n_qtiles, Hq, Hkv, d, st));
   else
-    SN_HIP(c, launch_attn_decode(dt, c->qkv16, kv, ix, c->attn16, c->part, B, Hq, Hkv, d, S, st));
+    SN_HIP(c, launch_attn_decode(dt, c->qkv16, kv, ix, c->attn16, c->part, B, Hq, Hkv, d, S, st, 1));
   kt.end(SN_K_ATTN);
   kt.begin(SN_K_OPROJ);
   SN_HIP(c, resid_gemm(at(p.wo), c->attn16, at(p.bo), qd));
   kt.end(SN_K_OPROJ);
   kt.begin(SN_K_NORM);
-  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n2g), at(p.n2b), c->u16, T, h, s.norm_eps, pending, st));
+  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n2g), at(p.n2b), c->u16, T, h, s.norm_eps, pending, st, pk));
   pending = Fold{};
   kt.end(SN_K_NORM);
   kt.begin(SN_K_FFN_UP);
-  SN_HIP(c, gemm(s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup), c->act16, p.n_up, h));
+  SN_HIP(c, gemm(s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup), c->act16, p.n_up, h, true));
   kt.end(SN_K_FFN_UP);
   kt.begin(SN_K_FFN_DOWN);
   SN_HIP(c, resid_gemm(at(p.wd), c->act16, at(p.bd), F));
@@ -801,19 +806,19 @@ extern "C" int sn_time_kernel_class(sn_ctx* c, int32_t kernel_class, int32_t bat
       hipError_t e;
       switch (kernel_class) {
         case SN_K_QKV:
-          e = launch_gemm_skinny(SN_F16, EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, batch, p.n_qkv, h, c->compute);
+          e = launch_gemm_skinny(SN_F16, EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, batch, p.n_qkv, h, c->compute, 1, kXPacked);
           break;
         case SN_K_OPROJ:
           e = launch_gemm_skinny(SN_F16, EPI_PART32, at(p.wo), c->attn16, nullptr, c->part32, batch, h, qd, c->compute,
-                                 gemm_skinny_splits(batch, h, qd));
+                                 gemm_skinny_splits(batch, h, qd), kXPacked);
           break;
         case SN_K_FFN_UP:
           e = launch_gemm_skinny(SN_F16, s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup),
-                                 c->act16, batch, p.n_up, h, c->compute);
+                                 c->act16, batch, p.n_up, h, c->compute, 1, kXPacked | kOutPacked);
           break;
         case SN_K_FFN_DOWN:
           e = launch_gemm_skinny(SN_F16, EPI_PART32, at(p.wd), c->act16, nullptr, c->part32, batch, h, F, c->compute,
-                                 gemm_skinny_splits(batch, h, F));
+                                 gemm_skinny_splits(batch, h, F), kXPacked);
           break;
         default:
           return fail(c, SN_E_INVAL, "sn_time_kernel_class: only the four projection classes can be timed alone");
@@ -900,20 +905,34 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
       for (int l = 0; l < L; ++l) samples[l].push_back(tcur[l]);
   }
   c->timing = saved_timing;
-  (void)hipFree(hin);
-  (void)hipFree(hout);
-  if (rc) return rc;
-  for (int l = 0; l < L; ++l) c->prof_tc[l] = median_of(samples[l]);
+  if (rc) {
+    (void)hipFree(hin);
+    (void)hipFree(hout);
+    return rc;
+  }
+  int64_t iter_est = 0;
+  for (int l = 0; l < L; ++l) {
+    c->prof_tc[l] = median_of(samples[l]);
+    iter_est += c->prof_tc[l];
+  }
 
-  // solo transfer of each layer's state (weights; + KV prefix when decoding)
+  // Transfer of each layer's state (weights; + KV prefix when decoding), timed while the
+  // compute stream runs iterations of the same kind: that is the condition under which
+  // prefetches run, and copies are a little slower then than on an idle GPU.
   uint8_t* dst = c->slot[0];
   bool temp = false;
   if (!dst) {
-    SN_HIP(c, hipMalloc((void**)&dst, c->state_bytes));
+    if (hipMalloc((void**)&dst, c->state_bytes) != hipSuccess) {
+      (void)hipFree(hin);
+      (void)hipFree(hout);
+      return fail(c, SN_E_NOMEM, "sn_profile_layers: device allocation failed");
+    }
     temp = true;
   }
   const uint64_t kv_used = is_prefill ? 0 : (uint64_t)c->kv_used_tokens * kv_token_bytes(s);
   uint8_t* kv_src_tmp = nullptr;
+  int64_t tx_est = 0;
+  const int tx_reps = std::min(reps, 3);
   for (int l = 0; l < L && rc == SN_OK; ++l) {
     LayerState& ls = c->layers[l];
     const uint8_t* kv_src = ls.host_kv;
@@ -928,20 +947,34 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
       kv_src = kv_src_tmp;
     }
     std::vector<int64_t> v;
-    for (int r = 0; r < reps + 1; ++r) {
+    for (int r = 0; r < tx_reps + (l == 0 ? 1 : 0) && rc == SN_OK; ++r) {
+      // keep compute busy for longer than the copy is expected to take (first pass: idle GPU, gives the estimate)
+      int busy = 0;
+      if (tx_est > 0 && iter_est > 0) busy = (int)std::min<int64_t>(64, tx_est / iter_est + 2);
+      for (int k = 0; k < busy && rc == SN_OK; ++k) {
+        for (int b = 0; b < batch; ++b) c->len[b] = lens[b] = is_prefill ? 0 : seq;
+        rc = sn_step(c, &bt, &kvh, hout);
+      }
+      if (rc) break;
       hipError_t e = hipEventRecord(c->ev_copy_start[l], c->h2d);
       if (e == hipSuccess) e = hipMemcpyAsync(dst, ls.host_w, c->w_bytes, hipMemcpyHostToDevice, c->h2d);
       if (e == hipSuccess && kv_used) e = hipMemcpyAsync(dst + c->w_bytes, kv_src, kv_used, hipMemcpyHostToDevice, c->h2d);
       if (e == hipSuccess) e = hipEventRecord(c->ev_ready[l], c->h2d);
       if (e == hipSuccess) e = hipStreamSynchronize(c->h2d);
+      if (e == hipSuccess) e = hipStreamSynchronize(c->compute);
+      if (e == hipSuccess) e = hipStreamSynchronize(c->d2h);
       if (e != hipSuccess) {
         rc = fail(c, SN_E_HIP, "sn_profile_layers: transfer timing: %s", hipGetErrorString(e));
         break;
       }
-      if (r > 0) v.push_back(elapsed_ns(c->ev_copy_start[l], c->ev_ready[l]));
+      const int64_t t = elapsed_ns(c->ev_copy_start[l], c->ev_ready[l]);
+      if (l == 0 && r == 0) tx_est = t;      // idle-GPU warm-up pass, not a sample
+      else v.push_back(t);
     }
     if (rc == SN_OK) c->prof_tx[l] = median_of(v);
   }
+  (void)hipFree(hin);
+  (void)hipFree(hout);
   if (kv_src_tmp) (void)hipHostFree(kv_src_tmp);
   if (temp) (void)hipFree(dst);
   if (rc) return rc;

@@ -9,7 +9,7 @@ import numpy as np
 from . import sn as _sn
 
 EXPORTS = ("sn_k_tile_weights", "sn_k_norm", "sn_k_gemm", "sn_k_rope_append", "sn_k_attn_decode",
-           "sn_k_attn_prefill", "sn_k_cast_in", "sn_k_cast_out", "sn_k_copy", "sn_k_gemm_splitk", "sn_k_norm_fold", "sn_k_cast_out_fold")
+           "sn_k_attn_prefill", "sn_k_cast_in", "sn_k_cast_out", "sn_k_copy", "sn_k_gemm_splitk", "sn_k_norm_fold", "sn_k_cast_out_fold", "sn_k_packed_offset")
 
 EPI_STORE16, EPI_GELU16, EPI_RESID32, EPI_SWIGLU16 = 0, 1, 2, 3
 PATH_SKINNY, PATH_TILE = 0, 1
@@ -25,20 +25,22 @@ def _lib():
         sig = {
             "sn_k_tile_weights": [v, v, i32, i32, i32, i32, i32],
             "sn_k_norm": [i32, i32, v, v, v, v, i32, i32, C.c_float, v],
-            "sn_k_gemm": [i32, i32, i32, v, v, v, v, i32, i32, i32, v],
+            "sn_k_gemm": [i32, i32, i32, v, v, v, v, i32, i32, i32, i32, v],
+            "sn_k_packed_offset": [i32, i32, i32],
             "sn_k_rope_append": [i32, i32, v, v, v, v, v, v, v, v, i32, i32, i32, i32, i32, v],
-            "sn_k_attn_decode": [i32, v, v, v, v, v, v, v, i32, i32, i32, i32, i32, i32, v],
+            "sn_k_attn_decode": [i32, v, v, v, v, v, v, v, i32, i32, i32, i32, i32, i32, i32, v],
             "sn_k_attn_prefill": [i32, v, v, v, v, v, v, v, v, v, v, i32, i32, i32, i32, v],
             "sn_k_cast_in": [i32, v, v, u64, v],
             "sn_k_cast_out": [i32, v, v, u64, v],
             "sn_k_copy": [v, v, u64, v],
             "sn_k_gemm_splitk": [i32, v, v, v, i32, i32, i32, i32, v],
-            "sn_k_norm_fold": [i32, i32, v, v, v, v, i32, i32, C.c_float, v, i32, v, v],
+            "sn_k_norm_fold": [i32, i32, v, v, v, v, i32, i32, C.c_float, v, i32, v, i32, v],
             "sn_k_cast_out_fold": [i32, v, v, i32, i32, v, i32, v, v],
         }
         for name, args in sig.items():
             f = getattr(L, name)
-            f.restype = C.c_int64 if name == "sn_k_tile_weights" else C.c_int
+            f.restype = (C.c_int64 if name == "sn_k_tile_weights" else
+                         C.c_uint64 if name == "sn_k_packed_offset" else C.c_int)
             f.argtypes = args
         _ready = True
     return L
@@ -67,8 +69,26 @@ def sn_k_norm(dtype, is_ln, x32, gain, shift, out16, T, h, eps, stream=0):
     _chk(_lib().sn_k_norm(dtype, int(is_ln), _p(x32), _p(gain), _p(shift), _p(out16), T, h, eps, stream))
 
 
-def sn_k_gemm(dtype, epilogue, path, W, X, bias, out, M, N, K, stream=0):
-    _chk(_lib().sn_k_gemm(dtype, epilogue, path, _p(W), _p(X), _p(bias), _p(out), M, N, K, stream))
+def sn_k_gemm(dtype, epilogue, path, W, X, bias, out, M, N, K, flags=0, stream=0):
+    _chk(_lib().sn_k_gemm(dtype, epilogue, path, _p(W), _p(X), _p(bias), _p(out), M, N, K, flags, stream))
+
+
+def sn_k_packed_offset(m, k, K) -> int:
+    return int(_lib().sn_k_packed_offset(m, k, K))
+
+
+def pack_rows(x: np.ndarray) -> np.ndarray:
+    """Host helper (marshalling only): row-major [M][K] -> the row-tile packed layout."""
+    M, K = x.shape
+    Mp = (M + 15) // 16 * 16
+    xp = np.zeros((Mp, K), dtype=x.dtype)
+    xp[:M] = x
+    return np.ascontiguousarray(xp.reshape(Mp // 16, 16, K // 32, 4, 8).transpose(0, 2, 3, 1, 4)).reshape(-1)
+
+
+def unpack_rows(p: np.ndarray, M: int, K: int) -> np.ndarray:
+    Mp = (M + 15) // 16 * 16
+    return np.ascontiguousarray(p.reshape(Mp // 16, K // 32, 4, 16, 8).transpose(0, 3, 1, 2, 4)).reshape(Mp, K)[:M]
 
 
 def sn_k_rope_append(dtype, kv_value_dtype, qkv16, tok_seq, tok_pos, kv_off, cap, kv, mirror, inv_freq, T, Hq, Hkv,
@@ -77,9 +97,10 @@ def sn_k_rope_append(dtype, kv_value_dtype, qkv16, tok_seq, tok_pos, kv_off, cap
                                  _p(mirror), _p(inv_freq), T, Hq, Hkv, d, int(rope), stream))
 
 
-def sn_k_attn_decode(dtype, qkv16, kv, len_before, kv_off, cap, out16, part, B, Hq, Hkv, d, S, max_len, stream=0):
+def sn_k_attn_decode(dtype, qkv16, kv, len_before, kv_off, cap, out16, part, B, Hq, Hkv, d, S, max_len,
+                     packed_out=0, stream=0):
     _chk(_lib().sn_k_attn_decode(dtype, _p(qkv16), _p(kv), _p(len_before), _p(kv_off), _p(cap), _p(out16),
-                                 _p(part), B, Hq, Hkv, d, S, max_len, stream))
+                                 _p(part), B, Hq, Hkv, d, S, max_len, packed_out, stream))
 
 
 def sn_k_attn_prefill(dtype, qkv16, kv, len_before, n_new, tok_start, kv_off, cap, tile_seq, tile_q0, out16,
@@ -107,9 +128,9 @@ def sn_k_gemm_splitk(dtype, W, X, part, M, N, K, splits=0, stream=0) -> int:
     return rc
 
 
-def sn_k_norm_fold(dtype, is_ln, x32, gain, shift, out16, T, h, eps, part, splits, bias, stream=0):
+def sn_k_norm_fold(dtype, is_ln, x32, gain, shift, out16, T, h, eps, part, splits, bias, packed_out=0, stream=0):
     _chk(_lib().sn_k_norm_fold(dtype, int(is_ln), _p(x32), _p(gain), _p(shift), _p(out16), T, h, eps, _p(part), splits,
-                               _p(bias), stream))
+                               _p(bias), packed_out, stream))
 
 
 def sn_k_cast_out_fold(dtype, x32, out16, T, h, part, splits, bias, stream=0):

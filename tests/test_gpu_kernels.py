@@ -265,7 +265,7 @@ def test_splitk_projection_folded_into_norm_and_cast(dtype, splits):
         # folded into a LayerNorm
         x = torch.from_numpy(r0.copy()).cuda()
         out = torch.zeros(M, N, dtype=torch.int16, device="cuda")
-        K.sn_k_norm_fold(DT[dtype], True, x, dev16(g), dev16(sh), out, M, N, 1e-5, part, used, dev16(bb))
+        K.sn_k_norm_fold(DT[dtype], True, x, dev16(g), dev16(sh), out, M, N, 1e-5, part, used, dev16(bb), 0)
         torch.cuda.synchronize()
         got_x = x.cpu().numpy().astype(np.float64)
         assert np.abs(got_x - want_x).max() <= 2e-5 * np.abs(want_x).max(), (M, N, Kd)
@@ -277,3 +277,53 @@ def test_splitk_projection_folded_into_norm_and_cast(dtype, splits):
         torch.cuda.synchronize()
         assert np.array_equal(x2.cpu().numpy(), x.cpu().numpy())               # same fixed-order sum
         assert np.array_equal(synth.widen(host16(out), dtype), ofw.round_to_storage(got_x, dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_packed_activation_layout_through_norm_gemm_and_attention(dtype):
+    """The row-tile packed layout is only a permutation: every kernel that can read or write
+    it must produce exactly the bits of its row-major form."""
+    rng = np.random.default_rng(7)
+    for M in (1, 8, 17, 64):
+        h, N = 416, 192
+        Mp = (M + 15) // 16 * 16
+        x = (rng.standard_normal((M, h)) * 2).astype(np.float32)
+        g = synth.to_bits(1 + 0.1 * rng.standard_normal(h), dtype)
+        sh = synth.to_bits(0.1 * rng.standard_normal(h), dtype)
+        u_row = torch.zeros(M, h, dtype=torch.int16, device="cuda")
+        u_pk = torch.zeros(Mp * h, dtype=torch.int16, device="cuda")
+        xd = torch.from_numpy(x).cuda()
+        K.sn_k_norm_fold(DT[dtype], True, xd, dev16(g), dev16(sh), u_row, M, h, 1e-5, None, 0, None, 0)
+        K.sn_k_norm_fold(DT[dtype], True, xd, dev16(g), dev16(sh), u_pk, M, h, 1e-5, None, 0, None, 1)
+        torch.cuda.synchronize()
+        u = host16(u_row)
+        assert np.array_equal(K.unpack_rows(host16(u_pk), M, h), u)
+        assert np.array_equal(K.pack_rows(u)[K.sn_k_packed_offset(M - 1, h - 1, h)], u[M - 1, h - 1])
+        wb = synth.to_bits(rng.standard_normal((N, h)) * 0.05, dtype)
+        tiled = dev16(K.sn_k_tile_weights(wb, N, h))
+        for epi in (K.EPI_STORE16, K.EPI_GELU16):
+            ref = torch.zeros(M, N, dtype=torch.int16, device="cuda")
+            K.sn_k_gemm(DT[dtype], epi, K.PATH_SKINNY, tiled, u_row, None, ref, M, N, h, 0)
+            a = torch.zeros(M, N, dtype=torch.int16, device="cuda")
+            K.sn_k_gemm(DT[dtype], epi, K.PATH_SKINNY, tiled, u_pk, None, a, M, N, h, 1)            # packed in
+            b = torch.zeros(Mp * N, dtype=torch.int16, device="cuda")
+            K.sn_k_gemm(DT[dtype], epi, K.PATH_SKINNY, tiled, u_pk, None, b, M, N, h, 3)            # packed in and out
+            torch.cuda.synchronize()
+            assert np.array_equal(host16(a), host16(ref))
+            assert np.array_equal(K.unpack_rows(host16(b), M, N), host16(ref))
+    # decode attention writing packed output
+    Hq, Hkv, d = 8, 2, 128
+    lens_before = [5, 300, 0]
+    B = len(lens_before)
+    caps = [l + 2 for l in lens_before]
+    qkv, Kc, Vc, kv_off, tok_start, dv = _kv_setup(rng, dtype, lens_before, [1] * B, caps, Hq, Hkv, d, True)
+    K.sn_k_rope_append(DT[dtype], DT[dtype], dv["qkv"], dv["tok_seq"], dv["tok_pos"], dv["kv_off"], dv["cap"], dv["kv"], None,
+                       dv["inv_freq"], B, Hq, Hkv, d, True)
+    part = torch.zeros(B * Hq * 16 * (d + 2), dtype=torch.float32, device="cuda")
+    for S in (1, 2):
+        ref = torch.zeros(B, Hq * d, dtype=torch.int16, device="cuda")
+        pk = torch.zeros(16 * Hq * d, dtype=torch.int16, device="cuda")
+        K.sn_k_attn_decode(DT[dtype], dv["qkv"], dv["kv"], dv["len_before"], dv["kv_off"], dv["cap"], ref, part, B, Hq, Hkv, d, S, 301, 0)
+        K.sn_k_attn_decode(DT[dtype], dv["qkv"], dv["kv"], dv["len_before"], dv["kv_off"], dv["cap"], pk, part, B, Hq, Hkv, d, S, 301, 1)
+        torch.cuda.synchronize()
+        assert np.array_equal(K.unpack_rows(host16(pk), B, Hq * d), host16(ref))
