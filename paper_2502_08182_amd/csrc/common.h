@@ -62,6 +62,15 @@ __device__ __forceinline__ size_t packed_off(int m, int k, int KB) {
   return ((((size_t)(m >> 4) * KB + (k >> 5)) * 64) + (m & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
 }
 
+// Rotate the 8 halfwords of v left by 2*g elements (g in 0..3) with selects only, so that
+// element e0 of the result is element (e0 + 2g) % 8 of v and can be indexed statically.
+__device__ __forceinline__ u16x8 rot_pairs(u16x8 v, int g) {
+  u32x4 w = __builtin_bit_cast(u32x4, v);
+  if (g & 1) w = u32x4{w[1], w[2], w[3], w[0]};
+  if (g & 2) w = u32x4{w[2], w[3], w[0], w[1]};
+  return __builtin_bit_cast(u16x8, w);
+}
+
 // ---- wave64 reductions ----------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -167,6 +167,177 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------
+// Grouped-query decode attention on the matrix cores.  With G >= 4 query heads per KV
+// head the per-key dot products of the kernel above cost G times the vector work and
+// it stops being memory-bound; here the G heads of a group form the (padded) 16
+// columns of one MFMA tile, so a KV head's keys and values are read once for the whole
+// group and the arithmetic moves to the matrix cores:
+//   S^T = K Q^T    A = 16 key rows x 32 of d straight from the KV slice (rows chosen as
+//                  keys 8*(r/4) + 4*t + r%4 so a lane ends up with 8 consecutive keys),
+//                  B = Q^T of the group;
+//   O^T = V^T P^T  A = V^T read from a per-wavefront LDS tile transposed while staged,
+//                  B = P^T from registers; the head index stays on lane%16 for both.
+// One workgroup = 4 wavefronts per (sequence, KV head, key range); each wavefront takes
+// every 4th 32-key tile with its own online softmax; the four are merged lane-locally
+// through LDS in fixed order.  Output format identical to the kernel above.
+template <class T, int D, int G>
+__global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
+    const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
+    const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ out,
+    float* __restrict__ part, int Hq, int Hkv, int S, int packed) {
+  constexpr int LD = 40, DK = D / 32, DT = D / 16;
+  constexpr int kVtWave = D * LD;                        // uint16 elements of one wavefront's V^T tile
+  constexpr int kMrgLane = 2 + DT * 4;                   // floats a lane contributes to the merge
+  static_assert(64 * kMrgLane * 4 <= kVtWave * 2, "merge buffer must fit the V^T tile");
+  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * kVtWave];
+
+  const int b = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, split = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int len = len_before[b] + 1;
+  const int chunk = (len + S - 1) / S;
+  const int j0 = split * chunk, j1 = min(len, j0 + chunk);
+  const int qkv_ld = (Hq + 2 * Hkv) * D;
+  const bool qok = r < G;
+
+  u16x8 qf[DK];
+#pragma unroll
+  for (int kk = 0; kk < DK; ++kk) {
+    qf[kk] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    if (qok) qf[kk] = *reinterpret_cast<const u16x8*>(qkv + (size_t)b * qkv_ld + (size_t)(hk * G + r) * D + kk * 32 + g * 8);
+  }
+  const int cp = cap[b];
+  const uint16_t* Kb = kv + (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D;
+  const uint16_t* Vb = Kb + (size_t)cp * D;
+  const float scale = rsqrtf((float)D);
+  uint16_t* vt = smem + wave * kVtWave;
+
+  float m = kNegBig, l = 0.f;
+  f32x4 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int jt = j0 + wave * 32; jt < j1; jt += 4 * 32) {
+    // stage V[jt..jt+32) transposed into this wavefront's LDS tile (wavefront-private: no workgroup barrier)
+    // each lane takes (key pair, 8 d-values) items: two 16-byte loads, later eight 4-byte LDS writes
+    constexpr int CH = 16 * (D / 8) / 64;                // items per lane
+    u16x8 va[CH], vb[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int id = lane + 64 * c, key = 2 * (id & 15), dc = id >> 4;
+      va[c] = vb[c] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      if (jt + key < j1) va[c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vb + (size_t)(jt + key) * D + dc * 8));
+      if (jt + key + 1 < j1) vb[c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vb + (size_t)(jt + key + 1) * D + dc * 8));
+    }
+    f32x4 st[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      st[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const int key = min(jt + 8 * (r >> 2) + 4 * t + (r & 3), j1 - 1);     // clamped; masked below
+      const uint16_t* kp = Kb + (size_t)key * D + g * 8;
+#pragma unroll
+      for (int kk = 0; kk < DK; ++kk)
+        st[t] = mma16x16x32<T>(__builtin_nontemporal_load(reinterpret_cast<const u16x8*>(kp + kk * 32)), qf[kk], st[t]);
+    }
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int id = lane + 64 * c, key = 2 * (id & 15), dc = id >> 4;
+      const u16x8 ra = rot_pairs(va[c], g), rb = rot_pairs(vb[c], g);
+#pragma unroll
+      for (int e0 = 0; e0 < 8; ++e0) {
+        const int e = (e0 + 2 * g) & 7;                  // the four 16-lane groups write different rows: fewer bank conflicts
+        *reinterpret_cast<uint32_t*>(&vt[(dc * 8 + e) * LD + key]) = (uint32_t)ra[e0] | ((uint32_t)rb[e0] << 16);
+      }
+    }
+    float sc[8], mx = kNegBig;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const bool ok = jt + 8 * g + e < j1;
+      sc[e] = ok ? st[e >> 2][e & 3] * scale : kNegBig;
+      mx = fmaxf(mx, sc[e]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx);
+    const float corr = __expf(m - mn);
+    float rs = 0.f;
+    u16x8 pb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float p = sc[e] > 0.5f * kNegBig ? __expf(sc[e] - mn) : 0.f;
+      rs += p;
+      pb[e] = from_f32<T>(p);
+    }
+    l = l * corr + rs;
+    m = mn;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the tile written above is read by other lanes below
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const u16x8 vf = *reinterpret_cast<const u16x8*>(&vt[(dt * 16 + r) * LD + g * 8]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[dt][i] *= corr;
+      o[dt] = mma16x16x32<T>(vf, pb, o[dt]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // reads done before the next trip overwrites the tile
+    __builtin_amdgcn_wave_barrier();
+  }
+
+  // merge the four wavefronts lane by lane (same lane = same head and same d columns), in order
+  __syncthreads();
+  float* mrg = reinterpret_cast<float*>(smem);
+  {
+    float* mine = mrg + ((size_t)wave * 64 + lane) * kMrgLane;
+    mine[0] = m;
+    mine[1] = l;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mine[2 + dt * 4 + i] = o[dt][i];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  for (int w = 1; w < 4; ++w) {
+    const float* other = mrg + ((size_t)w * 64 + lane) * kMrgLane;
+    const float m2 = other[0], mn = fmaxf(m, m2);
+    const float c1 = __expf(m - mn), c2 = __expf(m2 - mn);
+    l = l * c1 + other[1] * c2;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[dt][i] = o[dt][i] * c1 + other[2 + dt * 4 + i] * c2;
+    m = mn;
+  }
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  if (!qok) return;
+  const int hq = hk * G + r;
+  if (S == 1) {
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      u16x4 w4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w4[i] = from_f32<T>(o[dt][i] * inv);
+      const int k = hq * D + dt * 16 + g * 4;
+      const size_t at = packed ? packed_off(b, k, (Hq * D) >> 5) : (size_t)b * Hq * D + k;
+      *reinterpret_cast<u16x4*>(out + at) = w4;
+    }
+  } else {
+    float* p = part + (((size_t)b * Hq + hq) * S + split) * (D + 2);
+    if (g == 0) {
+      p[0] = m;
+      p[1] = l;
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) p[2 + dt * 16 + g * 4 + i] = o[dt][i];
+  }
+}
+
 // Merge the S key-range partials of one (sequence, query head); thread = output element.
 template <class T, int D>
 __global__ void attn_combine_kernel(const float* __restrict__ part, uint16_t* __restrict__ out, int S, int Hq,
@@ -205,14 +376,18 @@ static hipError_t launch_d(const uint16_t* qkv, const uint16_t* kv, const StepIn
 #define SN_LAUNCH_G(GV, NWV, UKV)                                                                                 \
   SN_LAUNCH((attn_decode_kernel<T, D, GV, NWV, UKV>), dim3(B * Hkv, S), dim3(NWV * 64), 0, st, qkv, kv, ix.len_before, \
             ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed)
+#define SN_LAUNCH_GQA(GV)                                                                                     \
+  SN_LAUNCH((attn_decode_gqa_kernel<T, D, GV>), dim3(B * Hkv, S), dim3(256), 0, st, qkv, kv, ix.len_before, ix.kv_off, \
+            ix.cap, out, part, Hq, Hkv, S, packed)
   switch (G) {
     case 1: SN_LAUNCH_G(1, 16, 2); break;
     case 2: SN_LAUNCH_G(2, 16, 2); break;
-    case 4: SN_LAUNCH_G(4, 8, 4); break;
-    case 8: SN_LAUNCH_G(8, 8, 4); break;
+    case 4: SN_LAUNCH_GQA(4); break;
+    case 8: SN_LAUNCH_GQA(8); break;
     default: return hipErrorInvalidValue;
   }
 #undef SN_LAUNCH_G
+#undef SN_LAUNCH_GQA
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || S == 1) return e;
   SN_LAUNCH((attn_combine_kernel<T, D>), dim3(B * Hq), dim3(D), 0, st, part, out, S, Hq, packed);

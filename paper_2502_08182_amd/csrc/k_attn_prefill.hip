@@ -69,14 +69,20 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
 
   for (int j0 = 0; j0 < kend; j0 += KT) {
     // ---- stage V[j0..j0+32) transposed into LDS: vt[dcol][key] ----
-    constexpr int CHUNKS = KT * D / 8;                   // 16-byte pieces in the tile
+    // item = (key pair, 8 d-values): two 16-byte loads, eight 4-byte LDS writes {v[key][e], v[key+1][e]}
+    constexpr int ITEMS = (KT / 2) * (D / 8);
 #pragma unroll
-    for (int cid = threadIdx.x; cid < CHUNKS; cid += 256) {
-      const int key = cid / (D / 8), dc = cid % (D / 8);
-      u16x8 v = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-      if (j0 + key < total) v = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + key) * D + dc * 8);
+    for (int id = threadIdx.x; id < ITEMS; id += 256) {
+      const int key = 2 * (id & 15), dc = id >> 4;
+      u16x8 va = u16x8{0, 0, 0, 0, 0, 0, 0, 0}, vb = va;
+      if (j0 + key < total) va = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + key) * D + dc * 8);
+      if (j0 + key + 1 < total) vb = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + key + 1) * D + dc * 8);
+      const u16x8 ra = rot_pairs(va, g), rb = rot_pairs(vb, g);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) vt[(dc * 8 + e) * LD + key] = v[e];
+      for (int e0 = 0; e0 < 8; ++e0) {
+        const int e = (e0 + 2 * g) & 7;                  // 16-lane groups write different rows: fewer bank conflicts
+        *reinterpret_cast<uint32_t*>(&vt[(dc * 8 + e) * LD + key]) = (uint32_t)ra[e0] | ((uint32_t)rb[e0] << 16);
+      }
     }
     __syncthreads();
 
