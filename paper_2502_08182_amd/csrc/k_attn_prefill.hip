@@ -67,38 +67,53 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int j0 = 0; j0 < kend; j0 += KT) {
-    // ---- stage V[j0..j0+32) transposed into LDS: vt[dcol][key] ----
-    // item = (key pair, 8 d-values): two 16-byte loads, eight 4-byte LDS writes {v[key][e], v[key+1][e]}
-    constexpr int ITEMS = (KT / 2) * (D / 8);
+  // Operands of the next key tile are fetched into registers while the current tile is being
+  // computed (one tile of software prefetch): V as (key pair, 8 d-values) items, two 16-byte
+  // loads per thread; K as the A-operand fragments of the two 16-key sub-tiles.
+  constexpr int ITEMS = (KT / 2) * (D / 8);              // <= 256: at most one item per thread
+  static_assert(ITEMS <= 256, "one V item per thread");
+  const bool vitem = (int)threadIdx.x < ITEMS;
+  const int vkey = 2 * (threadIdx.x & 15), vdc = threadIdx.x >> 4;
+  u16x8 va, vb, kf[2][DK];
+  auto fetch = [&](int j0) {
+    va = vb = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    if (vitem && j0 + vkey < total) va = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + vkey) * D + vdc * 8);
+    if (vitem && j0 + vkey + 1 < total) vb = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + vkey + 1) * D + vdc * 8);
 #pragma unroll
-    for (int id = threadIdx.x; id < ITEMS; id += 256) {
-      const int key = 2 * (id & 15), dc = id >> 4;
-      u16x8 va = u16x8{0, 0, 0, 0, 0, 0, 0, 0}, vb = va;
-      if (j0 + key < total) va = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + key) * D + dc * 8);
-      if (j0 + key + 1 < total) vb = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + key + 1) * D + dc * 8);
+    for (int t = 0; t < 2; ++t) {
+      const int key = min(j0 + 8 * (r >> 2) + 4 * t + (r & 3), total - 1);   // inside the cached rows; masked later
+      const uint16_t* kp = Kb + (size_t)key * D + g * 8;
+#pragma unroll
+      for (int kk = 0; kk < DK; ++kk) kf[t][kk] = *reinterpret_cast<const u16x8*>(kp + kk * 32);
+    }
+  };
+  if (kend > 0) fetch(0);
+
+  for (int j0 = 0; j0 < kend; j0 += KT) {
+    // ---- stage V[j0..j0+32) transposed into LDS: vt[dcol][key], eight 4-byte writes {v[key][e], v[key+1][e]} ----
+    if (vitem) {
       const u16x8 ra = rot_pairs(va, g), rb = rot_pairs(vb, g);
 #pragma unroll
       for (int e0 = 0; e0 < 8; ++e0) {
         const int e = (e0 + 2 * g) & 7;                  // 16-lane groups write different rows: fewer bank conflicts
-        *reinterpret_cast<uint32_t*>(&vt[(dc * 8 + e) * LD + key]) = (uint32_t)ra[e0] | ((uint32_t)rb[e0] << 16);
+        *reinterpret_cast<uint32_t*>(&vt[(vdc * 8 + e) * LD + vkey]) = (uint32_t)ra[e0] | ((uint32_t)rb[e0] << 16);
       }
     }
+    u16x8 kc[2][DK];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int kk = 0; kk < DK; ++kk) kc[t][kk] = kf[t][kk];
     __syncthreads();
+    if (j0 + KT < kend) fetch(j0 + KT);                  // in flight during this tile's arithmetic
 
     // ---- scores of 32 keys for this wavefront's 16 queries ----
     f32x4 st[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       st[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-      int key = j0 + 8 * (r >> 2) + 4 * t + (r & 3);
-      key = min(key, total - 1);                         // stay inside the cached rows; masked below
-      const uint16_t* kp = Kb + (size_t)key * D + g * 8;
 #pragma unroll
-      for (int kk = 0; kk < DK; ++kk) {
-        const u16x8 kf = *reinterpret_cast<const u16x8*>(kp + kk * 32);
-        st[t] = mma16x16x32<T>(kf, qf[kk], st[t]);
-      }
+      for (int kk = 0; kk < DK; ++kk) st[t] = mma16x16x32<T>(kc[t][kk], qf[kk], st[t]);
     }
     // lane now holds scores of keys j0 + 8g + e (e = 4t + i) for query lane%16
     float s[8];
