@@ -98,6 +98,21 @@ int sn_k_attn_decode(int32_t dtype, const void* qkv16, const void* kv, const int
                      int32_t Hq, int32_t Hkv, int32_t d, int32_t S, int32_t max_len,
                      int32_t packed_out, void* stream);
 
+/* The decode step's rotation, KV append and attention in one kernel (what sn_step runs
+ * when decoding; steps a6 + a7 of a layer).  Row b of qkv16 is the QKV projection's
+ * output as is: q and k not yet rotated, nothing appended.  The kernel rotates q and k at
+ * position len_before[b] (rope != 0; inv_freq [d/2] device fp32), rounds them to the 16-bit
+ * type, stores k and v as row len_before[b] of the sequence's slice in `kv` (device,
+ * read and written) and in `mirror` (a second slice of identical layout, e.g. mapped
+ * pinned host memory; may be NULL), and attends over keys 0..len_before[b].  qkv16 is not
+ * modified.  Other arguments as sn_k_attn_decode.  Needs cap[b] > len_before[b] (not checked:
+ * the arrays are device memory). */
+int sn_k_attn_decode_append(int32_t dtype, const void* qkv16, void* kv, void* mirror, const float* inv_freq,
+                            int32_t rope, const int32_t* len_before, const int32_t* kv_off,
+                            const int32_t* cap, void* out16, float* part, int32_t B, int32_t Hq,
+                            int32_t Hkv, int32_t d, int32_t S, int32_t max_len, int32_t packed_out,
+                            void* stream);
+
 /* Causal attention of each sequence's n_new tokens over len_before+n_new keys.
  * out16 [T][Hq*d]. */
 int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,

@@ -16,6 +16,50 @@ namespace sn {
 
 constexpr float kNegBig = -1.0e30f;
 
+// Fused append (template flag FA): the decode step's own q, k and v rows are still
+// un-rotated in the QKV projection's output.  The workgroup rotates q and k (RoPE,
+// pairs (i, i + d/2), fp32 angles), rounds them to the 16-bit storage type and parks
+// them in LDS: rows 0..G-1 = the group's query heads, row G = k, row G+1 = v.  The key
+// range that contains the new position stores k and v into the KV slice (and its host
+// mirror, when the layer's KV lives in host memory) and takes that key from LDS instead
+// of from the cache, so no workgroup ever loads the row that is being written.
+template <class T, int D, int G>
+__device__ __forceinline__ void stage_new_token(uint16_t (*stage)[D], const uint16_t* __restrict__ qkv_row, int hk,
+                                                int Hq, int Hkv, int pos, const float* __restrict__ inv_freq,
+                                                int rope) {
+  constexpr int half = D / 2;
+  for (int t = threadIdx.x; t < (G + 2) * half; t += blockDim.x) {
+    const int hs = t / half, i = t % half;
+    const int head = hs < G ? hk * G + hs : hs == G ? Hq + hk : Hq + Hkv + hk;
+    const uint16_t* src = qkv_row + (size_t)head * D;
+    float a = to_f32<T>(src[i]), b = to_f32<T>(src[i + half]);
+    if (rope && hs <= G) {
+      float sn_, cs_;
+      sincosf((float)pos * inv_freq[i], &sn_, &cs_);
+      const float ra = a * cs_ - b * sn_;
+      const float rb = a * sn_ + b * cs_;
+      a = ra;
+      b = rb;
+    }
+    stage[hs][i] = from_f32<T>(a);
+    stage[hs][i + half] = from_f32<T>(b);
+  }
+}
+
+// k and v of the new position: LDS rows G and G+1 -> KV slice row `pos` (16-byte stores).
+template <int D, int G>
+__device__ __forceinline__ void store_new_token(const uint16_t (*stage)[D], uint16_t* __restrict__ kvw,
+                                                uint16_t* __restrict__ mirror, size_t k_row_off, size_t v_row_off) {
+  constexpr int LPK = D / 8;
+  if (threadIdx.x < 2 * LPK) {
+    const int is_v = threadIdx.x / LPK, cc = threadIdx.x % LPK;
+    const u16x8 val = *reinterpret_cast<const u16x8*>(&stage[G + is_v][cc * 8]);
+    const size_t off = (is_v ? v_row_off : k_row_off) + cc * 8;
+    *reinterpret_cast<u16x8*>(kvw + off) = val;
+    if (mirror) *reinterpret_cast<u16x8*>(mirror + off) = val;
+  }
+}
+
 __device__ __forceinline__ void merge_into(float& m, float& l, float (&a)[8], float m2, float l2,
                                            const float (&a2)[8]) {
   const float mn = fmaxf(m, m2);
@@ -30,14 +74,16 @@ __device__ __forceinline__ void merge_into(float& m, float& l, float (&a)[8], fl
 // flight per wavefront.  Measured on MI355X: 16 x 2 is best for multi-head attention at
 // small batch (8 x 32 heads x 530 keys: 14.9 us vs 16.8 us for 8 x 4); with 8 query heads
 // per KV head the per-lane state needs the registers of an 8-wavefront workgroup.
-template <class T, int D, int G, int NW, int UK>
+template <class T, int D, int G, int NW, int UK, bool FA>
 __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
     const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ out,
-    float* __restrict__ part, int Hq, int Hkv, int S, int packed) {
+    float* __restrict__ part, int Hq, int Hkv, int S, int packed, uint16_t* __restrict__ kvw,
+    uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int rope) {
   constexpr int LPK = D / 8;          // lanes per key row
   constexpr int KPW = 64 / LPK;       // keys per wavefront load
   __shared__ float lds[NW][G][LPK][10];
+  __shared__ __attribute__((aligned(16))) uint16_t stage[FA ? G + 2 : 1][D];
 
   const int b = blockIdx.x / Hkv;
   const int hk = blockIdx.x % Hkv;
@@ -52,17 +98,31 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
 
   const int qkv_ld = (Hq + 2 * Hkv) * D;
   const float scale = rsqrtf((float)D);
+  const int cp = cap[b];
+  const size_t k_base = (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D;
+  const int pos = len - 1;            // position of this step's token
+  u16x8 knew = {0, 0, 0, 0, 0, 0, 0, 0}, vnew = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (FA) {
+    stage_new_token<T, D, G>(stage, qkv + (size_t)b * qkv_ld, hk, Hq, Hkv, pos, inv_freq, rope);
+    __syncthreads();
+    if (pos >= j0 && pos < j1)
+      store_new_token<D, G>(stage, kvw, mirror, k_base + (size_t)pos * D, k_base + ((size_t)cp + pos) * D);
+    knew = *reinterpret_cast<const u16x8*>(&stage[G][c * 8]);
+    vnew = *reinterpret_cast<const u16x8*>(&stage[G + 1][c * 8]);
+  }
   float q[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const u16x8 v = *reinterpret_cast<const u16x8*>(qkv + (size_t)b * qkv_ld + (size_t)(hk * G + g) * D + c * 8);
+    const u16x8 v = FA ? *reinterpret_cast<const u16x8*>(&stage[g][c * 8])
+                       : *reinterpret_cast<const u16x8*>(qkv + (size_t)b * qkv_ld + (size_t)(hk * G + g) * D + c * 8);
 #pragma unroll
     for (int e = 0; e < 8; ++e) q[g][e] = to_f32<T>(v[e]) * scale;
   }
 
-  const int cp = cap[b];
-  const uint16_t* Kb = kv + (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D + c * 8;
+  const uint16_t* Kb = kv + k_base + c * 8;
   const uint16_t* Vb = Kb + (size_t)cp * D;
+  // last cached row a load may touch: with the fused append the new row is never loaded
+  const int jlast = FA ? max(min(j1 - 1, pos - 1), 0) : j1 - 1;
 
   float m[G], l[G], acc[G][8];
 #pragma unroll
@@ -82,9 +142,13 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
     for (int u = 0; u < UK; ++u) {
       const int j = jb + u * NW * KPW + slot;
       ok[u] = j < j1;
-      const int jc = ok[u] ? j : j1 - 1;               // clamped: loads stay inside the cached rows
+      const int jc = min(j, jlast);                    // clamped: loads stay inside the cached rows
       kr[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Kb + (size_t)jc * D));
       vr[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vb + (size_t)jc * D));
+      if (FA && j == pos) {
+        kr[u] = knew;
+        vr[u] = vnew;
+      }
     }
 #pragma unroll
     for (int u = 0; u < UK; ++u) {
@@ -181,16 +245,18 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
 // One workgroup = 4 wavefronts per (sequence, KV head, key range); each wavefront takes
 // every 4th 32-key tile with its own online softmax; the four are merged lane-locally
 // through LDS in fixed order.  Output format identical to the kernel above.
-template <class T, int D, int G>
+template <class T, int D, int G, bool FA>
 __global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
     const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ out,
-    float* __restrict__ part, int Hq, int Hkv, int S, int packed) {
+    float* __restrict__ part, int Hq, int Hkv, int S, int packed, uint16_t* __restrict__ kvw,
+    uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int rope) {
   constexpr int LD = 40, DK = D / 32, DT = D / 16;
   constexpr int kVtWave = D * LD;                        // uint16 elements of one wavefront's V^T tile
   constexpr int kMrgLane = 2 + DT * 4;                   // floats a lane contributes to the merge
   static_assert(64 * kMrgLane * 4 <= kVtWave * 2, "merge buffer must fit the V^T tile");
   __shared__ __attribute__((aligned(16))) uint16_t smem[4 * kVtWave];
+  __shared__ __attribute__((aligned(16))) uint16_t stage[FA ? G + 2 : 1][D];
 
   const int b = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, split = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -201,15 +267,27 @@ __global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
   const int qkv_ld = (Hq + 2 * Hkv) * D;
   const bool qok = r < G;
 
+  const int cp = cap[b];
+  const size_t k_base = (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D;
+  const int pos = len - 1;            // position of this step's token
+  if (FA) {
+    stage_new_token<T, D, G>(stage, qkv + (size_t)b * qkv_ld, hk, Hq, Hkv, pos, inv_freq, rope);
+    __syncthreads();
+    if (pos >= j0 && pos < j1)
+      store_new_token<D, G>(stage, kvw, mirror, k_base + (size_t)pos * D, k_base + ((size_t)cp + pos) * D);
+  }
   u16x8 qf[DK];
 #pragma unroll
   for (int kk = 0; kk < DK; ++kk) {
     qf[kk] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-    if (qok) qf[kk] = *reinterpret_cast<const u16x8*>(qkv + (size_t)b * qkv_ld + (size_t)(hk * G + r) * D + kk * 32 + g * 8);
+    if (qok)
+      qf[kk] = FA ? *reinterpret_cast<const u16x8*>(&stage[r][kk * 32 + g * 8])
+                  : *reinterpret_cast<const u16x8*>(qkv + (size_t)b * qkv_ld + (size_t)(hk * G + r) * D + kk * 32 + g * 8);
   }
-  const int cp = cap[b];
-  const uint16_t* Kb = kv + (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D;
+  const uint16_t* Kb = kv + k_base;
   const uint16_t* Vb = Kb + (size_t)cp * D;
+  // last cached row a load may touch: with the fused append the new row is never loaded
+  const int jlast = FA ? max(min(j1 - 1, pos - 1), 0) : j1 - 1;
   const float scale = rsqrtf((float)D);
   uint16_t* vt = smem + wave * kVtWave;
 
@@ -227,18 +305,25 @@ __global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
     for (int c = 0; c < CH; ++c) {
       const int id = lane + 64 * c, key = 2 * (id & 15), dc = id >> 4;
       va[c] = vb[c] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-      if (jt + key < j1) va[c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vb + (size_t)(jt + key) * D + dc * 8));
-      if (jt + key + 1 < j1) vb[c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vb + (size_t)(jt + key + 1) * D + dc * 8));
+      const int ka = jt + key, kb = ka + 1;
+      if (FA && ka == pos) va[c] = *reinterpret_cast<const u16x8*>(&stage[G + 1][dc * 8]);
+      else if (ka < j1) va[c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vb + (size_t)ka * D + dc * 8));
+      if (FA && kb == pos) vb[c] = *reinterpret_cast<const u16x8*>(&stage[G + 1][dc * 8]);
+      else if (kb < j1) vb[c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vb + (size_t)kb * D + dc * 8));
     }
     f32x4 st[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       st[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-      const int key = min(jt + 8 * (r >> 2) + 4 * t + (r & 3), j1 - 1);     // clamped; masked below
-      const uint16_t* kp = Kb + (size_t)key * D + g * 8;
+      const int key = jt + 8 * (r >> 2) + 4 * t + (r & 3);
+      const uint16_t* kp = Kb + (size_t)min(key, jlast) * D + g * 8;        // clamped; masked below
+      const bool fresh = FA && key == pos;
 #pragma unroll
-      for (int kk = 0; kk < DK; ++kk)
-        st[t] = mma16x16x32<T>(__builtin_nontemporal_load(reinterpret_cast<const u16x8*>(kp + kk * 32)), qf[kk], st[t]);
+      for (int kk = 0; kk < DK; ++kk) {
+        u16x8 kf = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(kp + kk * 32));
+        if (fresh) kf = *reinterpret_cast<const u16x8*>(&stage[G][kk * 32 + g * 8]);
+        st[t] = mma16x16x32<T>(kf, qf[kk], st[t]);
+      }
     }
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
@@ -369,16 +454,17 @@ int attn_decode_splits(int B, int Hkv, int max_len) {
   return S;
 }
 
-template <class T, int D>
+template <class T, int D, bool FA>
 static hipError_t launch_d(const uint16_t* qkv, const uint16_t* kv, const StepIndex& ix, uint16_t* out,
-                           float* part, int B, int Hq, int Hkv, int S, int packed, hipStream_t st) {
+                           float* part, int B, int Hq, int Hkv, int S, int packed, const AttnAppend& ap,
+                           hipStream_t st) {
   const int G = Hq / Hkv;
 #define SN_LAUNCH_G(GV, NWV, UKV)                                                                                 \
-  SN_LAUNCH((attn_decode_kernel<T, D, GV, NWV, UKV>), dim3(B * Hkv, S), dim3(NWV * 64), 0, st, qkv, kv, ix.len_before, \
-            ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed)
-#define SN_LAUNCH_GQA(GV)                                                                                     \
-  SN_LAUNCH((attn_decode_gqa_kernel<T, D, GV>), dim3(B * Hkv, S), dim3(256), 0, st, qkv, kv, ix.len_before, ix.kv_off, \
-            ix.cap, out, part, Hq, Hkv, S, packed)
+  SN_LAUNCH((attn_decode_kernel<T, D, GV, NWV, UKV, FA>), dim3(B * Hkv, S), dim3(NWV * 64), 0, st, qkv, kv,       \
+            ix.len_before, ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope)
+#define SN_LAUNCH_GQA(GV)                                                                                         \
+  SN_LAUNCH((attn_decode_gqa_kernel<T, D, GV, FA>), dim3(B * Hkv, S), dim3(256), 0, st, qkv, kv, ix.len_before,   \
+            ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope)
   switch (G) {
     case 1: SN_LAUNCH_G(1, 16, 2); break;
     case 2: SN_LAUNCH_G(2, 16, 2); break;
@@ -395,18 +481,25 @@ static hipError_t launch_d(const uint16_t* qkv, const uint16_t* kv, const StepIn
 }
 
 hipError_t launch_attn_decode(int dtype, const void* qkv16, const void* kv, const StepIndex& ix, void* out16,
-                              float* part, int B, int Hq, int Hkv, int d, int S, hipStream_t st, int packed) {
+                              float* part, int B, int Hq, int Hkv, int d, int S, hipStream_t st, int packed,
+                              const AttnAppend* append) {
   if (B <= 0) return hipSuccess;
   const uint16_t* q = (const uint16_t*)qkv16;
   const uint16_t* k = (const uint16_t*)kv;
   uint16_t* o = (uint16_t*)out16;
+  if (append && (!append->kv || (append->rope && !append->inv_freq))) return hipErrorInvalidValue;
+  const AttnAppend ap = append ? *append : AttnAppend{};
+#define SN_DISPATCH(TT, DD)                                                                        \
+  return append ? launch_d<TT, DD, true>(q, k, ix, o, part, B, Hq, Hkv, S, packed, ap, st)         \
+                : launch_d<TT, DD, false>(q, k, ix, o, part, B, Hq, Hkv, S, packed, ap, st)
   if (dtype == 0) {
-    if (d == 64) return launch_d<F16, 64>(q, k, ix, o, part, B, Hq, Hkv, S, packed, st);
-    if (d == 128) return launch_d<F16, 128>(q, k, ix, o, part, B, Hq, Hkv, S, packed, st);
+    if (d == 64) SN_DISPATCH(F16, 64);
+    if (d == 128) SN_DISPATCH(F16, 128);
   } else {
-    if (d == 64) return launch_d<BF16, 64>(q, k, ix, o, part, B, Hq, Hkv, S, packed, st);
-    if (d == 128) return launch_d<BF16, 128>(q, k, ix, o, part, B, Hq, Hkv, S, packed, st);
+    if (d == 64) SN_DISPATCH(BF16, 64);
+    if (d == 128) SN_DISPATCH(BF16, 128);
   }
+#undef SN_DISPATCH
   return hipErrorInvalidValue;
 }
 

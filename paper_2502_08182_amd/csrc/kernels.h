@@ -83,11 +83,20 @@ hipError_t launch_rope_append(int dtype, int kv_value_dtype, void* qkv16, const 
                               hipStream_t st);
 
 // One query per sequence over len_before+1 cached keys.  part: fp32 scratch for
-// split partials, [B][Hq][S][d+2].
+// split partials, [B][Hq][S][d+2].  append == nullptr: the new row is already in the KV
+// slice and q, k are already rotated.  Otherwise the kernel does that itself: it rotates
+// q and k of row b of qkv16 (when rope != 0), stores k, v at position len_before[b] of
+// the slice `kv` (and of `mirror`, if not null) and attends over them from registers.
+struct AttnAppend {
+  uint16_t* kv = nullptr;
+  uint16_t* mirror = nullptr;
+  const float* inv_freq = nullptr;
+  int rope = 0;
+};
 int attn_decode_splits(int B, int Hkv, int max_len);
 hipError_t launch_attn_decode(int dtype, const void* qkv16, const void* kv, const StepIndex& ix,
                               void* out16, float* part, int B, int Hq, int Hkv, int d, int S,
-                              hipStream_t st, int packed_out = 0);
+                              hipStream_t st, int packed_out = 0, const AttnAppend* append = nullptr);
 // Causal attention of each sequence's new tokens over its cached + new keys.
 hipError_t launch_attn_prefill(int dtype, const void* qkv16, const void* kv, const StepIndex& ix,
                                void* out16, int n_qtiles, int Hq, int Hkv, int d, hipStream_t st);

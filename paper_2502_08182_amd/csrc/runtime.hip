@@ -540,15 +540,20 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
   kt.begin(SN_K_QKV);
   SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h, false));
   kt.end(SN_K_QKV);
-  kt.begin(SN_K_ROPE_APPEND);
-  SN_HIP(c, launch_rope_append(dt, dt, c->qkv16, ix, kv, mirror_kv, c->inv_freq, T, Hq, Hkv, d, s.rope, st));
-  kt.end(SN_K_ROPE_APPEND);
-  kt.begin(SN_K_ATTN);
-  if (prefill)
+  if (prefill) {
+    kt.begin(SN_K_ROPE_APPEND);
+    SN_HIP(c, launch_rope_append(dt, dt, c->qkv16, ix, kv, mirror_kv, c->inv_freq, T, Hq, Hkv, d, s.rope, st));
+    kt.end(SN_K_ROPE_APPEND);
+    kt.begin(SN_K_ATTN);
     SN_HIP(c, launch_attn_prefill(dt, c->qkv16, kv, ix, c->attn16, n_qtiles, Hq, Hkv, d, st));
-  else
-    SN_HIP(c, launch_attn_decode(dt, c->qkv16, kv, ix, c->attn16, c->part, B, Hq, Hkv, d, S, st, 1));
-  kt.end(SN_K_ATTN);
+    kt.end(SN_K_ATTN);
+  } else {
+    // decode: rotation and KV append are done by the attention kernel itself
+    const AttnAppend ap{(uint16_t*)kv, (uint16_t*)mirror_kv, c->inv_freq, s.rope};
+    kt.begin(SN_K_ATTN);
+    SN_HIP(c, launch_attn_decode(dt, c->qkv16, kv, ix, c->attn16, c->part, B, Hq, Hkv, d, S, st, 1, &ap));
+    kt.end(SN_K_ATTN);
+  }
   kt.begin(SN_K_OPROJ);
   SN_HIP(c, resid_gemm(at(p.wo), c->attn16, at(p.bo), qd));
   kt.end(SN_K_OPROJ);

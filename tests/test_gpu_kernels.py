@@ -201,6 +201,50 @@ def test_rope_append_and_attn_decode(dtype, Hq, Hkv, d, rope):
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,rope", [("f16", 4, 4, 64, False), ("bf16", 8, 8, 128, True),
+                                                 ("bf16", 16, 2, 128, True), ("f16", 6, 3, 64, True),
+                                                 ("f16", 8, 2, 64, True), ("f16", 32, 32, 128, False)])
+def test_attn_decode_with_fused_append(dtype, Hq, Hkv, d, rope):
+    """The decode kernel that rotates, appends and attends in one launch: against the oracle,
+    and bit for bit against rope_append followed by attn_decode (outputs, cache rows, mirror);
+    the QKV buffer must be left as it was."""
+    rng = np.random.default_rng(13)
+    lens_before = [0, 1, 130, 517, 63, 31, 32]
+    B = len(lens_before)
+    caps = [l + 2 for l in lens_before]
+    n_new = [1] * B
+    qkv, Kc, Vc, kv_off, tok_start, dv = _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope)
+    want, k_new, v_new, _ = _oracle_attention(dtype, qkv, Kc, Vc, lens_before, n_new, tok_start, Hq, Hkv, d, rope)
+    kv0 = dv["kv"].clone()
+    qkv0 = dv["qkv"].clone()
+    part = torch.zeros(B * Hq * 16 * (d + 2), dtype=torch.float32, device="cuda")
+    # reference pair of kernels on its own copies
+    kv_two, qkv_two, mir_two = kv0.clone(), qkv0.clone(), torch.zeros_like(kv0)
+    K.sn_k_rope_append(DT[dtype], DT[dtype], qkv_two, dv["tok_seq"], dv["tok_pos"], dv["kv_off"], dv["cap"], kv_two, mir_two,
+                       dv["inv_freq"], B, Hq, Hkv, d, rope)
+    for S in (0, 1, 3, 16):
+        out_two = torch.zeros(B, Hq * d, dtype=torch.int16, device="cuda")
+        K.sn_k_attn_decode(DT[dtype], qkv_two, kv_two, dv["len_before"], dv["kv_off"], dv["cap"], out_two, part, B, Hq,
+                           Hkv, d, S, max(lens_before) + 1)
+        kv_f, mir_f = kv0.clone(), torch.zeros_like(kv0)
+        out_f = torch.zeros(B, Hq * d, dtype=torch.int16, device="cuda")
+        K.sn_k_attn_decode_append(DT[dtype], dv["qkv"], kv_f, mir_f, dv["inv_freq"], rope, dv["len_before"], dv["kv_off"],
+                                  dv["cap"], out_f, part, B, Hq, Hkv, d, S, max(lens_before) + 1)
+        torch.cuda.synchronize()
+        check(synth.widen(host16(out_f), dtype), want, dtype, f"fused attn_decode S={S}", factor=2.0)
+        assert torch.equal(dv["qkv"], qkv0), "the fused kernel must not modify the QKV buffer"
+        assert torch.equal(kv_f, kv_two), f"cache after the fused kernel differs from rope_append's (S={S})"
+        assert torch.equal(mir_f, mir_two), f"mirror differs (S={S})"
+        assert torch.equal(out_f, out_two), f"fused output differs from the two-kernel path (S={S})"
+    kv_host = host16(kv_f)
+    for b in range(B):
+        base = int(kv_off[b]) * 2 * Hkv * d
+        blk = kv_host[base: base + caps[b] * 2 * Hkv * d].reshape(Hkv, 2, caps[b], d)
+        p = lens_before[b]
+        check(synth.widen(blk[:, 0, p], dtype), k_new[b][0], dtype, f"appended k seq {b}")
+        assert np.array_equal(synth.widen(blk[:, 1, p], dtype), v_new[b][0])
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,rope", [("f16", 4, 4, 64, False), ("bf16", 8, 8, 128, True),
                                                  ("bf16", 8, 2, 128, True)])
 def test_attn_prefill(dtype, Hq, Hkv, d, rope):
     rng = np.random.default_rng(4)
