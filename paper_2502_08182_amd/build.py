@@ -24,11 +24,32 @@ def _compile(src: str) -> str:
     cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     if src.endswith(".cpp"):
         cmd[1:1] = ["-x", "hip"]
+    if src.endswith(".hip"):
+        cmd.append("-Rpass-analysis=kernel-resource-usage")
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
+    lines, spills, name = [], [], "?"
+    for l in r.stderr.splitlines():
+        if noise in l:
+            continue
+        if "[-Rpass-analysis=kernel-resource-usage]" in l:
+            # keep only what matters: a kernel that spills registers to scratch memory is a
+            # performance bug here (every kernel is written to fit its register budget)
+            if "Function Name:" in l:
+                name = l.split("Function Name:")[1].split()[0]
+            elif "ScratchSize [bytes/lane]:" in l and int(l.split("ScratchSize [bytes/lane]:")[1].split()[0]) > 0:
+                spills.append(f"{src}: kernel {name} uses "
+                              f"{l.split('ScratchSize [bytes/lane]:')[1].split()[0]} bytes/lane of scratch (register spills)")
+            continue
+        if l.startswith("      |") or l.strip() == "^" or (lines == [] and l[:1].isspace()):
+            continue
+        lines.append(l)
+    err = "\n".join(l for l in lines if not l.lstrip()[:4].strip().isdigit())
     if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed for {src}:\n{err}")
+        raise RuntimeError(f"hipcc failed for {src}:\n" + "\n".join(
+            l for l in r.stderr.splitlines() if noise not in l and "kernel-resource-usage" not in l))
+    if spills:
+        sys.stderr.write("WARNING: register spills\n  " + "\n  ".join(spills) + "\n")
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj

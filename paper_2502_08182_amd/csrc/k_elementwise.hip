@@ -98,7 +98,20 @@ __device__ __forceinline__ f32x4 folded(f32x4 v, const float* __restrict__ part,
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] += to_f32<T>(b[e]);
   }
-  for (int s = 0; s < nsplit; ++s) v += *reinterpret_cast<const f32x4*>(part + (size_t)s * split_stride + off);
+  // partials are requested four at a time before the first of them is added (one memory latency
+  // per group, not per partial); the additions keep their fixed order
+  static_assert(kMaxSplits % 4 == 0, "groups of four");
+#pragma unroll
+  for (int s0 = 0; s0 < kMaxSplits; s0 += 4) {
+    if (s0 >= nsplit) break;
+    f32x4 p[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (s0 + s < nsplit) p[s] = *reinterpret_cast<const f32x4*>(part + (size_t)(s0 + s) * split_stride + off);
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (s0 + s < nsplit) v += p[s];
+  }
   return v;
 }
 
@@ -115,7 +128,19 @@ __global__ __launch_bounds__(BLOCK) void norm_kernel(float* __restrict__ x,
   const int nv = h >> 2;
   const float inv_h = 1.0f / (float)h;
   f32x4 v[MAXV];
+  u16x4 gv[MAXV], bv[MAXV];
   float s = 0.f;
+  // gains and shifts come from the layer's weight record (HBM, cold): fetch them together with
+  // the row so that their latency does not follow the two reductions
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int idx = threadIdx.x + i * BLOCK;
+    gv[i] = bv[i] = u16x4{0, 0, 0, 0};
+    if (idx < nv) {
+      gv[i] = *reinterpret_cast<const u16x4*>(gain + idx * 4);
+      if (LN) bv[i] = *reinterpret_cast<const u16x4*>(shift + idx * 4);
+    }
+  }
 #pragma unroll
   for (int i = 0; i < MAXV; ++i) {
     const int idx = threadIdx.x + i * BLOCK;
@@ -148,9 +173,7 @@ __global__ __launch_bounds__(BLOCK) void norm_kernel(float* __restrict__ x,
   for (int i = 0; i < MAXV; ++i) {
     const int idx = threadIdx.x + i * BLOCK;
     if (idx < nv) {
-      const u16x4 g = *reinterpret_cast<const u16x4*>(gain + idx * 4);
-      u16x4 b = u16x4{0, 0, 0, 0};
-      if (LN) b = *reinterpret_cast<const u16x4*>(shift + idx * 4);
+      const u16x4 g = gv[i], b = bv[i];
       u16x4 o;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -170,7 +193,13 @@ template <class T, bool LN, bool FOLD>
 static void launch_norm_t(float* x32, const uint16_t* gain, const uint16_t* shift, uint16_t* u16, int Tn, int h,
                           float eps, const Fold& f, int packed, hipStream_t st) {
   const uint16_t* fb = (const uint16_t*)f.bias;
-  if (Tn <= 64)
+  if (Tn <= 64 && h <= 4096)
+    SN_LAUNCH((norm_kernel<T, LN, 1024, 1, FOLD>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps, f.part,
+              f.nsplit, fb, packed);
+  else if (Tn <= 64 && h <= 8192)
+    SN_LAUNCH((norm_kernel<T, LN, 1024, 2, FOLD>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps, f.part,
+              f.nsplit, fb, packed);
+  else if (Tn <= 64)
     SN_LAUNCH((norm_kernel<T, LN, 1024, 4, FOLD>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps, f.part,
               f.nsplit, fb, packed);
   else
