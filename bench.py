@@ -26,6 +26,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
 LINK_NOMINAL = 64.0e9      # bytes/s per direction, PCIe Gen5 x16 host link
+MFMA_PEAK = 2.5e15         # flop/s, dense fp16/bf16 matrix cores
+FAMILY = {"c2": "OPT-6.7B", "c3": "Llama-2-13B", "c4": "OPT-30B", "c5": "Llama-2-70B (GQA)"}
 
 
 def parse():
@@ -34,14 +36,17 @@ def parse():
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
-    ap.add_argument("--slo-factor", type=float, default=2.0)
+    ap.add_argument("--slo-factor", type=float, default=None,
+                    help="TPOT SLO as a multiple of the all-resident step (default: the workload's own, 2.0 for c2)")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (the c4 batch sweep)")
     ap.add_argument("--guard", type=float, default=0.03,
                     help="fraction of the SLO kept as a guard band when picking (measured iterations run ~1-2%% "
                          "over the timeline's prediction: copies slow down slightly under concurrent compute)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB copy kernel (known HBM traffic) for counter calibration")
-    ap.add_argument("--slo-points", default="3,5,10",
-                    help="extra SLO factors (x all-resident TPOT) at which the picker is exercised and verified")
+    ap.add_argument("--slo-points", default=None,
+                    help="extra SLO factors (x all-resident TPOT) at which the picker is exercised and verified "
+                         "(default: 3,5,10 for c2, the workload's other SLO factors otherwise)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the interval sweep report")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--distinct-layers", type=int, default=0,
@@ -104,7 +109,7 @@ def cpu_baseline(w, seconds_target=12.0):
         cores = os.cpu_count() or 1
     layer = synth.widen_layer(s, synth.make_layer(s, 0, 0))
     rng = np.random.default_rng(7)
-    B, P = w.batch, w.prompt_lens[0]
+    B, P = w.batch, int(round(float(np.mean(w.prompt_lens))))
     kv = [{"k": ofw.round_to_storage(rng.standard_normal((P, s.n_kv_heads, s.head_dim)), s.dtype),
            "v": ofw.round_to_storage(rng.standard_normal((P, s.n_kv_heads, s.head_dim)), s.dtype)} for _ in range(B)]
     x = rng.standard_normal((B, s.hidden))
@@ -138,16 +143,25 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
-    w = synth.workload(a.workload)
+    w = synth.workload(a.workload, **({"batch": a.batch} if a.batch and a.workload == "c4" else {}))
+    if a.batch and a.workload != "c4":
+        from dataclasses import replace
+        w = replace(w, batch=a.batch, prompt_lens=(w.prompt_lens[0],) * a.batch)
     s = w.shape
     L, B = s.n_layers, w.batch
     K, W = a.steps, a.warmup
+    if a.slo_factor is None:
+        a.slo_factor = max(w.slo_factors) if w.slo_factors else 2.0
+    if a.slo_points is None:
+        a.slo_points = "3,5,10" if w.name == "c2" else ",".join(str(f) for f in w.slo_factors if f != a.slo_factor)
+    p_mean = int(round(float(np.mean(w.prompt_lens))))      # ragged prompts: profile at the mean length
     max_seq = max(w.prompt_lens) + K + W + 2
     t_start = time.time()
     se = Session(s, B, max_seq, hbm_budget=w.hbm_budget)
     sn.sn_set_budget_enforce(se.ctx, False)     # over-cap intervals are run and labelled, not refused
     log(f"[bench] {w.name}: L={L} h={s.hidden} heads={s.n_q_heads}/{s.n_kv_heads} ffn={s.ffn} {s.dtype} "
-        f"B={B} P={w.prompt_lens[0]} budget={w.hbm_budget / 1e9:.1f} GB")
+        f"B={B} P={min(w.prompt_lens)}..{max(w.prompt_lens)} (mean {p_mean}) budget={w.hbm_budget / 1e9:.1f} GB")
+    se.place(0)       # weights go straight to the device; host masters only for layers that get offloaded
     se.load_device_generated_weights(seed=0, distinct=a.distinct_layers)
     log(f"[bench] weights loaded in {time.time() - t_start:.1f} s")
 
@@ -174,7 +188,7 @@ def main():
         f"prefill {pre0['iter_ns'] / 1e6:.2f} ms; SLO = {a.slo_factor} x = {slo_ns / 1e6:.3f} ms")
 
     # ---- profile and pick ------------------------------------------------------------------
-    seq_prof = w.prompt_lens[0] + W + K // 2
+    seq_prof = p_mean + W + K // 2
     tc, tx = sn.sn_profile_layers(se.ctx, L, False, B, seq_prof, reps=5)
     n_max_cap = sn.sn_max_interval(se.ctx)
     rho = float(np.median(tx) / np.median(tc))
@@ -217,12 +231,17 @@ def main():
     achieved = alg_bytes / (k_avg_ns * 1e-9) if k_avg_ns > 0 else 0.0
     roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel (FFN up-projection, decode)", "achieved": achieved / 1e9,
                 "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": achieved / HBM_PEAK,
-                "traffic": read_traffic_note("gemm_skinny_ffn_up_c2_pmc.txt"),
+                "traffic": read_traffic_note("gemm_skinny_ffn_up_c2_pmc.txt") if w.name == "c2" and B == 8 else None,
                 "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": k_avg_ns / 1e3, "launches_timed": k_calls}
     # whole-step HBM roofline: every weight and every cached K/V element is read once per step
     kvtok = s.kv_bytes_per_token
-    len_mid = w.prompt_lens[0] + W + K // 2
+    len_mid = p_mean + W + K // 2
     step_bytes = L * (sn.sn_layer_blob_bytes(se.cshape) + len_mid * B * kvtok)
+    # prefill: dense contractions.  2 flop per weight element per token, plus causal attention
+    # (QK^T and PV: 4 * Hq * d flop per (query, visible key) pair)
+    w_elems = s.hidden * (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim + s.n_q_heads * s.head_dim * s.hidden \
+        + s.hidden * s.ffn * (3 if s.act == "swiglu" else 2)
+    pre_flops = L * (2.0 * w_elems * T + 4.0 * s.n_q_heads * s.head_dim * sum(p * (p + 1) / 2 for p in w.prompt_lens))
     log(f"[bench] N={n_run}: TPOT median {np.median(it) / 1e6:.3f} ms max {it.max() / 1e6:.3f} ms (SLO {slo_ns / 1e6:.3f}), "
         f"wall {wall_ms:.3f} ms/step -> {value:.1f} tok/s; ffn_up {k_avg_ns / 1e3:.1f} us = {achieved / 1e9:.0f} GB/s")
 
@@ -231,9 +250,11 @@ def main():
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if s.dtype == "f16" else "f16 (bf16 storage)",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: OPT-6.7B-shaped decoder, {L} layers, hidden {s.hidden}, {s.n_q_heads} heads, "
-                               f"GELU FFN {s.ffn}, fp16 random weights N(0,0.02), batch {B}, prompt {w.prompt_lens[0]}, "
-                               f"teacher-forced decode; HBM budget {w.hbm_budget / 1e9:.0f} GB; TPOT SLO {a.slo_factor}x all-resident",
+        "config": {"workload": f"{w.name}: {FAMILY.get(w.name, w.name)}-shaped decoder, {L} layers, hidden {s.hidden}, "
+                               f"{s.n_q_heads} query / {s.n_kv_heads} KV heads, {'SwiGLU' if s.act == 'swiglu' else 'GELU'} FFN "
+                               f"{s.ffn}, {'fp16' if s.dtype == 'f16' else 'bf16'} random weights N(0,0.02), batch {B}, prompt "
+                               f"{w.prompt_lens[0] if min(w.prompt_lens) == max(w.prompt_lens) else f'{min(w.prompt_lens)}..{max(w.prompt_lens)}'}"
+                               f", teacher-forced decode; HBM budget {w.hbm_budget / 1e9:.0f} GB; TPOT SLO {a.slo_factor}x all-resident",
                    "interval": int(n_run), "n_offloaded": int(st[-1]["n_offloaded"]),
                    "interval_over_cap": bool(sn.sn_resident_bytes(se.ctx, n_run) > w.hbm_budget > 0)},
         "roofline": roofline,
@@ -252,7 +273,9 @@ def main():
                      "frac_of_peak": step_bytes / (tpot0_ns * 1e-9) / HBM_PEAK,
                      "roofline_tokens_per_s": B * HBM_PEAK / step_bytes},
         "prefill": {"iter_ms_all_resident": pre0["iter_ns"] / 1e6, "iter_ms_at_interval": pre["iter_ns"] / 1e6,
-                    "tokens": T},
+                    "tokens": T, "algorithmic_tflop": pre_flops / 1e12,
+                    "all_resident_TFLOPs": pre_flops / (pre0["iter_ns"] * 1e-9) / 1e12,
+                    "frac_of_mfma_peak": pre_flops / (pre0["iter_ns"] * 1e-9) / MFMA_PEAK},
     }
 
     if a.calibrate_copy:

@@ -112,9 +112,15 @@ const char* sn_last_error(const sn_ctx* ctx);
  *   wo [hidden, Hq*d], bo, wg [ffn, hidden] (SwiGLU gate), bg, wu [ffn, hidden], bu,
  *   wd [hidden, ffn], bd, n1g [hidden], n1b (LayerNorm only), n2g, n2b.
  * sn_layer_blob_bytes gives the total size.  sn_set_layer_weights copies (and
- * re-tiles for the matrix cores) into the context's pinned master; host_blob is a
- * host pointer and may be freed afterwards.  If the layer is GPU resident at the
- * time, its device copy is refreshed too. */
+ * re-tiles for the matrix cores); host_blob is a host pointer and may be freed
+ * afterwards.  It may be called before or after sn_place.  Where the copy goes: a
+ * layer that is host-resident, or that has not been placed yet, gets a pinned host
+ * master; a layer that is GPU resident is written to its device copy (and to its
+ * master, if it has one).  Masters are created when a layer first needs one and
+ * then kept; when pinned memory runs out, masters of GPU-resident layers are given
+ * up (a later sn_place copies such a layer back from the device).  For a model
+ * whose weights exceed the host's pinned memory, call sn_place first.
+ * SN_E_NOMEM if a master cannot be allocated even so. */
 uint64_t sn_layer_blob_bytes(const sn_model_shape* shape);
 int sn_set_layer_weights(sn_ctx* ctx, int32_t layer, const void* host_blob, uint64_t bytes);
 

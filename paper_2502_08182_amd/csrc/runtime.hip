@@ -46,7 +46,9 @@ constexpr int kMetaRing = 8;
 constexpr int kKernelsPerLayer = 9;
 
 struct LayerState {
-  uint8_t* host_w = nullptr;    // pinned, tiled weights record (always present)
+  uint8_t* host_w = nullptr;    // pinned, tiled weights record: the host master.  Present while the layer is
+                                // host-resident and kept afterwards as long as pinned memory lasts
+  bool has_w = false;           // weights have been set (they live in host_w, in dev, or in both)
   uint8_t* host_kv = nullptr;   // pinned KV slice (present once the layer has been offloaded)
   uint8_t* host_kv_dev = nullptr;   // the same slice as the GPU addresses it (for write-through)
   uint8_t* dev = nullptr;       // device [weights | KV] when GPU resident
@@ -73,6 +75,7 @@ struct sn_ctx {
   int64_t max_tokens = 0;
   std::vector<LayerState> layers;
   uint8_t* slot[2] = {nullptr, nullptr};
+  uint8_t* stage_w = nullptr;    // pinned staging record for layers that have no host master
 
   // workspace (device)
   float* x32 = nullptr;
@@ -232,6 +235,7 @@ extern "C" void sn_destroy(sn_ctx* c) {
   }
   for (auto& s : c->slot)
     if (s) (void)hipFree(s);
+  if (c->stage_w) (void)hipHostFree(c->stage_w);
   void* dev[] = {c->x32, c->u16, c->qkv16, c->attn16, c->act16, c->part, c->part32, c->inv_freq, c->meta_dev};
   for (void* p : dev)
     if (p) (void)hipFree(p);
@@ -308,7 +312,6 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
     SN_HIP(c, hipEventCreateWithFlags(&c->ev_meta[i], hipEventDisableTiming));
   }
   c->layers.resize(L);
-  for (int l = 0; l < L; ++l) SN_HIP(c, hipHostMalloc((void**)&c->layers[l].host_w, c->w_bytes, hipHostMallocDefault));
 
   int rc;
   if ((rc = make_events(c, c->ev_layer, L + 1, true))) return rc;
@@ -348,6 +351,45 @@ extern "C" int sn_init(sn_ctx** out, const sn_model_shape* shape, uint64_t hbm_b
 // =================================================================================
 // weights, capacity accounting, placement
 // =================================================================================
+// A layer's host master is pinned memory.  Masters are created on demand (when a layer is
+// host-resident, or when weights arrive before any placement) and then kept, so that a later
+// re-placement needs no device-to-host copy; if pinned memory runs out, the masters of layers
+// that currently live on the GPU are given up (their weights stay on the device) and the
+// allocation is tried once more.
+// N_keep: the placement that is in effect, or being established, when the call returns; only
+// layers that are GPU-resident under it (and hold their weights on the device) may lose a master.
+static int ensure_master(sn_ctx* c, int l, int N_keep) {
+  LayerState& ls = c->layers[l];
+  if (ls.host_w) return SN_OK;
+  const int L = c->shape.n_layers;
+  hipError_t e = hipHostMalloc((void**)&ls.host_w, c->w_bytes, hipHostMallocDefault);
+  if (e == hipErrorOutOfMemory) {
+    (void)hipGetLastError();
+    ls.host_w = nullptr;
+    for (int o = 0; o < L; ++o) {
+      LayerState& os = c->layers[o];
+      if (os.dev && os.host_w && !is_offloaded(L, N_keep, o)) {
+        (void)hipHostFree(os.host_w);
+        os.host_w = nullptr;
+      }
+    }
+    e = hipHostMalloc((void**)&ls.host_w, c->w_bytes, hipHostMallocDefault);
+  }
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    ls.host_w = nullptr;
+    return fail(c, e == hipErrorOutOfMemory ? SN_E_NOMEM : SN_E_HIP,
+                "pinned host master of layer %d (%llu bytes): %s", l, (unsigned long long)c->w_bytes, hipGetErrorString(e));
+  }
+  return SN_OK;
+}
+
+static int ensure_stage(sn_ctx* c) {
+  if (c->stage_w) return SN_OK;
+  SN_HIP(c, hipHostMalloc((void**)&c->stage_w, c->w_bytes, hipHostMallocDefault));
+  return SN_OK;
+}
+
 extern "C" int sn_set_layer_weights(sn_ctx* c, int32_t layer, const void* host_blob, uint64_t bytes) {
   if (!c) return fail(nullptr, SN_E_INVAL, "sn_set_layer_weights: null context");
   if (!host_blob || layer < 0 || layer >= c->shape.n_layers) return fail(c, SN_E_INVAL, "sn_set_layer_weights: bad layer or blob");
@@ -357,15 +399,28 @@ extern "C" int sn_set_layer_weights(sn_ctx* c, int32_t layer, const void* host_b
   int rc = sync_all(c);
   if (rc) return rc;
   LayerState& ls = c->layers[layer];
+  // Destination of the tiled record: the layer's host master if it has one; a layer that lives
+  // on the GPU and has no master is packed into the staging record and uploaded from there.
+  uint8_t* dst = ls.host_w;
+  if (!dst) {
+    if (ls.dev) {
+      if ((rc = ensure_stage(c))) return rc;
+      dst = c->stage_w;
+    } else {
+      if ((rc = ensure_master(c, layer, c->placed ? c->N : c->shape.n_layers + 1))) return rc;
+      dst = ls.host_w;
+    }
+  }
   // All arithmetic runs in float16 with fp32 accumulation.  bfloat16 weights are stored as
   // the equal float16 value (exact for 2^-17 <= |w| <= 65504): activations kept in
   // bfloat16 between kernels would lose 3 mantissa bits per hand-off, which at the
   // 13B/70B layer shapes is already ~3e-2 x RMS after a single layer.
-  const uint64_t bad = pack_layer(c->shape, static_cast<const uint8_t*>(host_blob), ls.host_w);
+  const uint64_t bad = pack_layer(c->shape, static_cast<const uint8_t*>(host_blob), dst);
   if (bad)
     return fail(c, SN_E_INVAL, "sn_set_layer_weights: %llu weights are not representable in float16 (|w| > 65504, inf or NaN)",
                 (unsigned long long)bad);
-  if (ls.dev) SN_HIP(c, hipMemcpy(ls.dev, ls.host_w, c->w_bytes, hipMemcpyHostToDevice));
+  if (ls.dev) SN_HIP(c, hipMemcpy(ls.dev, dst, c->w_bytes, hipMemcpyHostToDevice));
+  ls.has_w = true;
   return SN_OK;
 }
 
@@ -402,6 +457,10 @@ extern "C" int sn_place(sn_ctx* c, int32_t N) {
   for (int l = 0; l < L; ++l) {
     LayerState& ls = c->layers[l];
     if (!is_offloaded(L, N, l)) continue;
+    if (!ls.host_w) {     // the layer moves to (or starts in) host memory: it needs its master
+      if ((rc = ensure_master(c, l, N))) return rc;
+      if (ls.dev && ls.has_w) SN_HIP(c, hipMemcpy(ls.host_w, ls.dev, c->w_bytes, hipMemcpyDeviceToHost));
+    }
     if (!ls.host_kv) {
       SN_HIP(c, hipHostMalloc((void**)&ls.host_kv, c->kv_bytes, hipHostMallocDefault));
       std::memset(ls.host_kv, 0, c->kv_bytes);
@@ -425,7 +484,7 @@ extern "C" int sn_place(sn_ctx* c, int32_t N) {
     LayerState& ls = c->layers[l];
     if (is_offloaded(L, N, l) || ls.dev) continue;
     SN_HIP(c, hipMalloc((void**)&ls.dev, c->state_bytes));
-    SN_HIP(c, hipMemcpy(ls.dev, ls.host_w, c->w_bytes, hipMemcpyHostToDevice));
+    if (ls.host_w) SN_HIP(c, hipMemcpy(ls.dev, ls.host_w, c->w_bytes, hipMemcpyHostToDevice));
     if (ls.host_kv && ls.offloaded && kv_used)
       SN_HIP(c, hipMemcpy(kv_of(ls.dev, c), ls.host_kv, kv_used, hipMemcpyHostToDevice));
     else
@@ -951,6 +1010,14 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
       }
       kv_src = kv_src_tmp;
     }
+    const uint8_t* w_src = ls.host_w;
+    if (!w_src) {               // no host master (the layer lives on the GPU): same bytes from the staging record
+      if (ensure_stage(c)) {
+        rc = SN_E_NOMEM;
+        break;
+      }
+      w_src = c->stage_w;
+    }
     std::vector<int64_t> v;
     for (int r = 0; r < tx_reps + (l == 0 ? 1 : 0) && rc == SN_OK; ++r) {
       // keep compute busy for longer than the copy is expected to take (first pass: idle GPU, gives the estimate)
@@ -962,7 +1029,7 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
       }
       if (rc) break;
       hipError_t e = hipEventRecord(c->ev_copy_start[l], c->h2d);
-      if (e == hipSuccess) e = hipMemcpyAsync(dst, ls.host_w, c->w_bytes, hipMemcpyHostToDevice, c->h2d);
+      if (e == hipSuccess) e = hipMemcpyAsync(dst, w_src, c->w_bytes, hipMemcpyHostToDevice, c->h2d);
       if (e == hipSuccess && kv_used) e = hipMemcpyAsync(dst + c->w_bytes, kv_src, kv_used, hipMemcpyHostToDevice, c->h2d);
       if (e == hipSuccess) e = hipEventRecord(c->ev_ready[l], c->h2d);
       if (e == hipSuccess) e = hipStreamSynchronize(c->h2d);

@@ -115,6 +115,29 @@ def test_replacing_between_iterations_keeps_the_cache(c1):
     assert np.array_equal(np.stack(outs), ref[1])
 
 
+def test_weights_may_arrive_after_placement(c1):
+    """A model larger than the host's pinned memory is loaded after sn_place: GPU-resident
+    layers then have no host master until they are first offloaded (the master is copied
+    back from the device).  Whatever the order, and whatever intervals follow, the output
+    is the one of the ordinary order, bit for bit."""
+    w, layers, prompt, table, *_ = c1
+    ref = gpu_run(w, layers, prompt, table, 0)
+    for first in (0, 2):
+        with Session(w.shape, w.batch, w.max_seq) as se:
+            se.place(first)
+            se.load_synthetic_weights(layers=layers)
+            se.kv_reset([p + w.decode_steps for p in w.prompt_lens])
+            pre = se.step(list(w.prompt_lens), True, prompt)
+            outs = []
+            for t, N in enumerate([3, 1, 0, 4, 2, 0, 1, 3]):
+                se.place(N)
+                if t == 4:      # weights replaced in place while some layers live on the host
+                    se.load_synthetic_weights(layers=layers)
+                outs.append(se.step([1] * w.batch, False, table[t]))
+        assert np.array_equal(pre, ref[0]), f"prefill differs (first placement {first})"
+        assert np.array_equal(np.stack(outs), ref[1]), f"decode differs (first placement {first})"
+
+
 @pytest.mark.parametrize("name", ["c2t", "c3t", "c4t", "c5t"])
 def test_truncated_real_shapes_match_oracle(name):
     w = synth.workload(name)
