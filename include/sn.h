@@ -103,6 +103,7 @@ int sn_init(sn_ctx** out, const sn_model_shape* shape, uint64_t hbm_budget_bytes
             void* hip_compute_stream);
 void sn_destroy(sn_ctx* ctx);
 const char* sn_last_error(const sn_ctx* ctx);
+int32_t sn_layers(const sn_ctx* ctx);        /* the model's layer count; 0 for a null context */
 
 /* --- weights -------------------------------------------------------------------
  * Caller-side layer blob: the tensors below in this order, 16-bit (shape.dtype),

@@ -216,6 +216,8 @@ extern "C" uint64_t sn_layer_blob_bytes(const sn_model_shape* shape) {
   return blob_layout(*shape).total;
 }
 
+extern "C" int32_t sn_layers(const sn_ctx* ctx) { return ctx ? ctx->shape.n_layers : 0; }
+
 extern "C" const char* sn_last_error(const sn_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
 
 // =================================================================================

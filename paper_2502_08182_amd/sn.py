@@ -23,7 +23,7 @@ ERROR_NAMES = {-1: "SN_E_INVAL", -2: "SN_E_STATE", -3: "SN_E_BUDGET", -4: "SN_E_
                -5: "SN_E_NOMEM", -6: "SN_E_HIP"}
 
 EXPORTS = (
-    "sn_init", "sn_destroy", "sn_last_error", "sn_layer_blob_bytes", "sn_set_layer_weights", "sn_place",
+    "sn_init", "sn_destroy", "sn_last_error", "sn_layers", "sn_layer_blob_bytes", "sn_set_layer_weights", "sn_place",
     "sn_set_budget_enforce", "sn_resident_bytes", "sn_max_interval", "sn_placement", "sn_kv_reset", "sn_step",
     "sn_read_hidden_f32",
     "sn_set_timing", "sn_set_kernel_timing_class", "sn_time_kernel_class", "sn_get_stats", "sn_get_layer_times", "sn_profile_layers", "sn_timeline",
@@ -85,6 +85,7 @@ def lib() -> C.CDLL:
         "sn_init": (C.c_int, [C.POINTER(ctx), C.POINTER(sn_model_shape), u64, C.c_void_p]),
         "sn_destroy": (None, [ctx]),
         "sn_last_error": (C.c_char_p, [ctx]),
+        "sn_layers": (i32, [ctx]),
         "sn_layer_blob_bytes": (u64, [C.POINTER(sn_model_shape)]),
         "sn_set_layer_weights": (C.c_int, [ctx, i32, C.c_void_p, u64]),
         "sn_place": (C.c_int, [ctx, i32]),
@@ -188,6 +189,10 @@ def sn_resident_bytes(ctx, N: int) -> int:
 
 def sn_max_interval(ctx) -> int:
     return int(lib().sn_max_interval(ctx))
+
+
+def sn_layers(ctx) -> int:
+    return int(lib().sn_layers(ctx))
 
 
 def sn_placement(L: int, N: int):

@@ -212,6 +212,64 @@ def test_profiler_and_picker_agree_with_oracle(c1):
                     assert sn.sn_timeline(tc, tx, want)[0] <= slo_ns
 
 
+def test_performance_record_profiled_on_the_gpu(c1, tmp_path):
+    """The analyzer (Sec. 4.4): profile a small grid of sizes for both phases into a record, then
+    every lookup must equal the oracle's record fed with the same measured times; after a
+    save / load round trip too.  The picked interval is then run and its output is still the
+    all-resident one."""
+    from oracle import record as orec
+    from paper_2502_08182_amd import sn_record as R
+    w, layers, prompt, table, *_ = c1
+    L = w.shape.n_layers
+    ref = gpu_run(w, layers, prompt, table, 0)
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        se.load_synthetic_weights(layers=layers)
+        se.place(2)
+        rec = R.sn_record_create(L, 0)
+        o = orec.Record(L, 0)
+        try:
+            wrong = R.sn_record_create(L + 1, 0)
+            with pytest.raises(sn.SnError) as e:
+                R.sn_record_profile(wrong, se.ctx, R.SN_PHASE_DECODE, 1, 16, 2)
+            assert e.value.code == sn.SN_E_INVAL                    # layer counts differ
+            R.sn_record_destroy(wrong)
+            for phase in (R.SN_PHASE_DECODE, R.SN_PHASE_PREFILL):
+                for b in (1, 2):
+                    for s in (16, 32):
+                        R.sn_record_profile(rec, se.ctx, phase, b, s, 2)
+                        tc, tx, n_max = R.sn_record_get(rec, phase, b, s)
+                        assert (tc > 0).all() and (tx > 0).all() and n_max == sn.sn_max_interval(se.ctx) == L + 1
+                        o.put(phase, b, s, tc.tolist(), tx.tolist(), n_max)
+            assert R.sn_record_cells(rec) == 8
+            path = str(tmp_path / "record.json")
+            R.sn_record_save(rec, path)
+            rec2 = R.sn_record_load(path)
+            for r in (rec, rec2):
+                for phase in (R.SN_PHASE_DECODE, R.SN_PHASE_PREFILL):
+                    for b, s in [(1, 16), (2, 32), (2, 20), (1, 1), (2, 24)]:
+                        for permille in (1000, 1100, 1500, 3000, 20000, 900):
+                            want = o.lookup(phase, b, s, orec.SLO_REL_PERMILLE, permille)
+                            try:
+                                got = R.sn_record_lookup(r, phase, b, s, R.SN_SLO_REL_PERMILLE, permille)
+                            except sn.SnError as e:
+                                assert e.code == sn.SN_E_INFEASIBLE
+                                got = None
+                            assert got == want, (phase, b, s, permille)
+            R.sn_record_destroy(rec2)
+            # separate intervals per phase (Sec. 4.4): place what each phase's record says, run, compare
+            n_pre = R.sn_record_lookup(rec, R.SN_PHASE_PREFILL, 2, 32, R.SN_SLO_REL_PERMILLE, 3000)
+            n_dec = R.sn_record_lookup(rec, R.SN_PHASE_DECODE, 2, 32, R.SN_SLO_REL_PERMILLE, 3000)
+            print("record: prefill interval", n_pre, "decode interval", n_dec, flush=True)
+            se.place(n_pre)
+            se.kv_reset([p + w.decode_steps for p in w.prompt_lens])
+            pre = se.step(list(w.prompt_lens), True, prompt)
+            se.place(n_dec)
+            outs = [se.step([1] * w.batch, False, table[t]) for t in range(w.decode_steps)]
+            assert np.array_equal(pre, ref[0]) and np.array_equal(np.stack(outs), ref[1])
+        finally:
+            R.sn_record_destroy(rec)
+
+
 def test_budget_and_call_order_errors():
     w = synth.workload("c1")
     cs = sn.make_shape(w.shape, w.batch, w.max_seq)

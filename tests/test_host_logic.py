@@ -33,6 +33,12 @@ def test_library_exports_every_declared_symbol():
     for n in knames:
         assert hasattr(L, n), n
     assert sorted(sn_kernels.EXPORTS) == knames
+    from paper_2502_08182_amd import sn_record
+    rnames = [n for n in _declared_functions("sn_record.h") if n.startswith("sn_record_")]
+    assert len(rnames) == 12
+    for n in rnames:
+        assert hasattr(L, n), n
+    assert sorted(sn_record.EXPORTS) == rnames
 
 
 def test_weight_tiling_is_a_permutation_with_the_documented_index():
