@@ -47,7 +47,9 @@ def parse():
     ap.add_argument("--slo-points", default=None,
                     help="extra SLO factors (x all-resident TPOT) at which the picker is exercised and verified "
                          "(default: 3,5,10 for c2, the workload's other SLO factors otherwise)")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the interval sweep report")
+    ap.add_argument("--prefill-slo-points", default="1.2,1.5,2",
+                    help="TTFT SLO factors (x all-resident prefill) at which the prefill phase picks its own interval")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the interval sweep and SLO-point reports")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="draw only this many different random layer blobs (0: every layer its own)")
@@ -95,6 +97,17 @@ def run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, n_steps, warmup, ti
     wall_ms = (time.perf_counter() - t0) * 1e3 / n_steps
     sn.sn_set_timing(se.ctx, 0)
     return [s.as_dict() for s in stats], wall_ms, pre
+
+
+def run_prefill(se, sn, w, x_pre, y_pre, reps=2):
+    """reps prefill iterations from empty caches, each synchronised; returns their stats."""
+    out = []
+    sn.sn_set_timing(se.ctx, 0)
+    for _ in range(reps):
+        se.kv_reset([p + 1 for p in w.prompt_lens])
+        se.step_device(list(w.prompt_lens), True, x_pre, y_pre)
+        out.append(sn.sn_get_stats(se.ctx).as_dict())
+    return out
 
 
 def cpu_baseline(w, seconds_target=12.0):
@@ -316,6 +329,45 @@ def main():
                 f"{pts[-1]['tpot_median_ms']:.3f} max {pts[-1]['tpot_max_ms']:.3f} (predicted {pred / 1e6:.3f}) "
                 f"within={pts[-1]['every_iteration_within_slo']} hidden {pts[-1]['hidden_fraction']:.3f}")
         out["slo_points"] = pts
+
+    # ---- the prefill phase has its own profile and its own interval (Sec. 4.4, separation of
+    # prefill and decoding): TTFT SLOs relative to the all-resident prefill iteration ------------
+    if not a.no_sweep and a.prefill_slo_points:
+        se.place(0)
+        ttft0 = float(min(d["iter_ns"] for d in run_prefill(se, sn, w, x_pre, y_pre, 2)))
+        tcp, txp = sn.sn_profile_layers(se.ctx, L, True, B, p_mean, reps=3)
+        rho_p = float(np.median(txp) / np.median(tcp))
+        pts = []
+        for f in [float(v) for v in a.prefill_slo_points.split(",") if v]:
+            slo_f = int(f * ttft0)
+            try:
+                n_f = sn.sn_pick_interval_from_times(tcp, txp, int(slo_f * (1.0 - a.guard)), L + 1)
+            except sn.SnError:
+                n_f = L + 1
+            se.place(n_f)
+            pst = run_prefill(se, sn, w, x_pre, y_pre, 3)[1:]
+            pit = np.array([d["iter_ns"] for d in pst], dtype=np.float64)
+            ph = sum(d["h2d_ns"] for d in pst)
+            pb = sum(d["h2d_bytes"] for d in pst)
+            ps = sum(d["stall_ns"] for d in pst)
+            pred, _ = sn.sn_timeline(tcp, txp, n_f)
+            pts.append({"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f),
+                        "n_offloaded": int(pst[-1]["n_offloaded"]), "ttft_ms": float(np.median(pit)) / 1e6,
+                        "ttft_max_ms": float(pit.max()) / 1e6, "predicted_ms": pred / 1e6,
+                        "every_iteration_within_slo": bool((pit <= slo_f).all()),
+                        "hidden_fraction": (1 - ps / ph) if ph else 1.0,
+                        "h2d_GBps": pb / (ph * 1e-9) / 1e9 if ph else None,
+                        "host_resident_weight_GB": int(pst[-1]["n_offloaded"]) * sn.sn_layer_blob_bytes(se.cshape) / 1e9,
+                        "resident_GB": sn.sn_resident_bytes(se.ctx, n_f) / 1e9,
+                        "over_cap": bool(sn.sn_resident_bytes(se.ctx, n_f) > w.hbm_budget > 0),
+                        "prefill_tokens_per_s": T / (float(np.median(pit)) * 1e-9)})
+            log(f"[bench] prefill SLO {f}x = {slo_f / 1e6:.2f} ms: picked N={n_f} (K={pts[-1]['n_offloaded']}), TTFT "
+                f"{pts[-1]['ttft_ms']:.2f} max {pts[-1]['ttft_max_ms']:.2f} (predicted {pred / 1e6:.2f}) "
+                f"within={pts[-1]['every_iteration_within_slo']} hidden {pts[-1]['hidden_fraction']:.3f} "
+                f"h2d {pts[-1]['h2d_GBps']}")
+        out["prefill_phase"] = {"ttft_all_resident_ms": ttft0 / 1e6, "rho_transfer_over_compute": rho_p,
+                                "layer_compute_us_median": float(np.median(tcp)) / 1e3,
+                                "layer_transfer_us_median": float(np.median(txp)) / 1e3, "slo_points": pts}
 
     # ---- interval sweep (reported, over-cap points labelled) ------------------------------------
     if not a.no_sweep:

@@ -1,6 +1,7 @@
 // Small bandwidth-trivial kernels of the layer: casts between the 16-bit boundary
 // type and the fp32 residual stream, the two normalisations, rotary embedding with
 // the KV-cache append, and a hash fill used by the profiler for generated inputs.
+#include <algorithm>
 #include "kernels.h"
 #include "common.h"
 
@@ -42,7 +43,9 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
   if (bytes == 0) return hipSuccess;
   if (bytes % 16) return hipErrorInvalidValue;
-  SN_LAUNCH(copy_kernel, dim3(2048), dim3(256), 0, st, (const u32x4*)src, (u32x4*)dst, bytes / 16);
+  const size_t n16 = bytes / 16;
+  const unsigned grid = (unsigned)std::min<size_t>(2048, (n16 + 255) / 256);
+  SN_LAUNCH(copy_kernel, dim3(grid), dim3(256), 0, st, (const u32x4*)src, (u32x4*)dst, n16);
   return hipGetLastError();
 }
 

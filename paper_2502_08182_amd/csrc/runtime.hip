@@ -86,6 +86,7 @@ struct sn_ctx {
   int32_t* meta_dev = nullptr;
   size_t meta_ints = 0;
   int32_t* meta_host[kMetaRing] = {};
+  int32_t* meta_host_dev[kMetaRing] = {};   // the same pinned buffers as the GPU addresses them
   hipEvent_t ev_meta[kMetaRing] = {};
   bool meta_used[kMetaRing] = {};
   int meta_next = 0;
@@ -311,6 +312,7 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   }
   for (int i = 0; i < kMetaRing; ++i) {
     SN_HIP(c, hipHostMalloc((void**)&c->meta_host[i], b_meta, hipHostMallocDefault));
+    SN_HIP(c, hipHostGetDevicePointer((void**)&c->meta_host_dev[i], c->meta_host[i], 0));
     SN_HIP(c, hipEventCreateWithFlags(&c->ev_meta[i], hipEventDisableTiming));
   }
   c->layers.resize(L);
@@ -695,7 +697,10 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
   }
   const size_t used_ints = (size_t)5 * B + 2 * (size_t)T + 2 * (size_t)n_qtiles;
   if (used_ints > c->meta_ints) return fail(c, SN_E_INVAL, "sn_step: index arrays overflow");
-  SN_HIP(c, hipMemcpyAsync(c->meta_dev, mh, used_ints * 4, hipMemcpyHostToDevice, c->compute));
+  // The index arrays are pulled from the pinned ring by a kernel, not by an asynchronous copy: a
+  // copy engine serves its requests in order, so a copy that has to wait for the previous
+  // iteration (stream order) would hold up every prefetch queued behind it on that engine.
+  SN_HIP(c, launch_copy(c->meta_host_dev[ring], c->meta_dev, (used_ints * 4 + 15) / 16 * 16, c->compute));
   SN_HIP(c, hipEventRecord(c->ev_meta[ring], c->compute));
   c->meta_used[ring] = true;
   int32_t* md = c->meta_dev;
