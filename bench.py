@@ -50,6 +50,10 @@ def parse():
     ap.add_argument("--prefill-slo-points", default="1.2,1.5,2",
                     help="TTFT SLO factors (x all-resident prefill) at which the prefill phase picks its own interval")
     ap.add_argument("--no-sweep", action="store_true", help="skip the interval sweep and SLO-point reports")
+    ap.add_argument("--repick", type=int, default=0, metavar="CELLS",
+                    help="also run the decode steps with the interval re-selected before every iteration from a "
+                         "performance record of CELLS sequence lengths spanning the run (the KV cache grows, the "
+                         "TPOT SLO stays fixed); 0: off")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="draw only this many different random layer blobs (0: every layer its own)")
@@ -368,6 +372,66 @@ def main():
         out["prefill_phase"] = {"ttft_all_resident_ms": ttft0 / 1e6, "rho_transfer_over_compute": rho_p,
                                 "layer_compute_us_median": float(np.median(tcp)) / 1e3,
                                 "layer_transfer_us_median": float(np.median(txp)) / 1e3, "slo_points": pts}
+
+    # ---- fixed TPOT SLO while the KV cache grows: the interval is looked up in a performance record
+    # before every iteration and the placement is changed when the answer changes (Sec. 4.2, 4.4) ----
+    if a.repick > 1:
+        from paper_2502_08182_amd import sn_record as R
+        rec = R.sn_record_create(L, 0)
+        se.place(0)
+        lens = sorted({int(round(p_mean + W + i * K / (a.repick - 1))) for i in range(a.repick)})
+        t_rec = time.time()
+        for sq in lens:      # as sn_record_profile, but without the capacity bound: over-cap points are run and labelled
+            tcr, txr = sn.sn_profile_layers(se.ctx, L, False, B, sq, reps=1)
+            R.sn_record_put(rec, R.SN_PHASE_DECODE, B, sq, tcr, txr, L + 1)
+        t_rec = time.time() - t_rec
+        slo_abs = int(slo_ns * (1.0 - a.guard))
+
+        def look(cur_len):
+            try:
+                return R.sn_record_lookup(rec, R.SN_PHASE_DECODE, B, cur_len, R.SN_SLO_ABS_NS, slo_abs)
+            except sn.SnError as e:
+                if e.code == sn.SN_E_INFEASIBLE:
+                    return L + 1
+                raise
+        se.kv_reset([p + W + K + 1 for p in w.prompt_lens])
+        n_cur = look(p_mean)
+        se.place(n_cur)
+        sn.sn_set_timing(se.ctx, 0)
+        se.step_device(list(w.prompt_lens), True, x_pre, y_pre)
+        ones = [1] * B
+        for i in range(W):
+            se.step_device(ones, False, x_dec[i % len(x_dec)], y_dec)
+        se.stream.synchronize()
+        its, picks, mig_ms = [], [], 0.0
+        for i in range(K):
+            n_i = look(p_mean + W + i)
+            if n_i != n_cur:
+                t0 = time.perf_counter()
+                se.place(n_i)                 # synchronous; moves weights and the live KV of the layers that change side
+                mig_ms += (time.perf_counter() - t0) * 1e3
+                n_cur = n_i
+            se.step_device(ones, False, x_dec[i % len(x_dec)], y_dec)
+            its.append(sn.sn_get_stats(se.ctx).as_dict()["iter_ns"])
+            picks.append(n_cur)
+        runs = []
+        for i, n in enumerate(picks):
+            if not runs or runs[-1][1] != n:
+                runs.append([i, n, 1])
+            else:
+                runs[-1][2] += 1
+        its = np.array(its, dtype=np.float64)
+        out["repick"] = {"slo_ms": slo_ns / 1e6, "record_seq_lens": lens, "record_build_s": t_rec,
+                         "cell_intervals": [look(sq) for sq in lens],
+                         "interval_runs": [{"first_step": r[0], "interval": r[1], "steps": r[2]} for r in runs],
+                         "placements_changed": len(runs) - 1, "migration_ms_total": mig_ms,
+                         "tpot_median_ms": float(np.median(its)) / 1e6, "tpot_max_ms": float(its.max()) / 1e6,
+                         "every_iteration_within_slo": bool((its <= slo_ns).all())}
+        log(f"[bench] repick: record of {len(lens)} lengths built in {t_rec:.1f} s, cell intervals "
+            f"{out['repick']['cell_intervals']}; runs {[(r[1], r[2]) for r in runs]}; TPOT median "
+            f"{out['repick']['tpot_median_ms']:.3f} max {out['repick']['tpot_max_ms']:.3f} (SLO {slo_ns / 1e6:.3f}) "
+            f"within={out['repick']['every_iteration_within_slo']} migration {mig_ms:.1f} ms")
+        R.sn_record_destroy(rec)
 
     # ---- interval sweep (reported, over-cap points labelled) ------------------------------------
     if not a.no_sweep:
