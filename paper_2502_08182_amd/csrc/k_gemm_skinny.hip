@@ -146,6 +146,12 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
       } else {
         const int n = (cb + c0) * 16 + nl;
         if (EPI == EPI_PART32) {
+          // the bias goes into plane 0 here, not into the later fold: the fold runs inside the NEXT layer,
+          // when this layer's weight record (a staging slot, if the layer is host-resident) may already
+          // be receiving another layer
+          if (bias && blockIdx.y == 0)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s0[i] += to_f32<T>(bias[n + i]);
           *reinterpret_cast<f32x4*>(static_cast<float*>(out) + ((size_t)blockIdx.y * M + m) * N + n) = s0;
         } else if (EPI == EPI_RESID32) {
           float* xr = static_cast<float*>(out) + (size_t)m * N + n;

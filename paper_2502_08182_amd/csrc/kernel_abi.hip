@@ -128,12 +128,12 @@ extern "C" int sn_k_copy(const void* src, void* dst, uint64_t bytes, void* strea
   return rc_of(launch_copy(src, dst, bytes, (hipStream_t)stream));
 }
 
-extern "C" int sn_k_gemm_splitk(int32_t dtype, const void* W, const void* X, void* part, int32_t M, int32_t N, int32_t K,
-                                int32_t splits, void* stream) {
+extern "C" int sn_k_gemm_splitk(int32_t dtype, const void* W, const void* X, const void* bias, void* part, int32_t M,
+                                int32_t N, int32_t K, int32_t splits, void* stream) {
   if (bad_dtype(dtype) || !W || !X || !part || M < 0 || M > 64 || N < 16 || K < 32) return SN_E_INVAL;
   if (splits == 0) splits = gemm_skinny_splits(M, N, K);
   if (splits < 1 || splits > kMaxSplits) return SN_E_INVAL;
-  const hipError_t e = launch_gemm_skinny(dtype, EPI_PART32, W, X, nullptr, part, M, N, K, (hipStream_t)stream, splits);
+  const hipError_t e = launch_gemm_skinny(dtype, EPI_PART32, W, X, bias, part, M, N, K, (hipStream_t)stream, splits);
   return e == hipSuccess ? splits : rc_of(e);
 }
 

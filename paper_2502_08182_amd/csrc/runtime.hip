@@ -593,8 +593,8 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
     const int sp = gemm_skinny_splits(T, h, K);
     pending.part = c->part32;
     pending.nsplit = sp;
-    pending.bias = bias;
-    return launch_gemm_skinny(dt, EPI_PART32, W, X, nullptr, c->part32, T, h, K, st, sp, kXPacked);
+    pending.bias = nullptr;     // added by the GEMM into plane 0: the fold must not touch this layer's record
+    return launch_gemm_skinny(dt, EPI_PART32, W, X, bias, c->part32, T, h, K, st, sp, kXPacked);
   };
   kt.begin(SN_K_NORM);
   SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, pending, st, pk));

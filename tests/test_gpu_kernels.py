@@ -112,6 +112,18 @@ def test_gemm_tile(dtype, epi):
     _gemm_case(dtype, K.PATH_TILE, epi, 130, 384, 64, bias=True, seed=40)
 
 
+@pytest.mark.parametrize("dtype,epi", [("f16", 0), ("f16", 1), ("bf16", 2), ("bf16", 3), ("f16", 3)])
+def test_gemm_tile_large_m(dtype, epi):
+    """From 1024 token rows on (and K a multiple of 256) the prefill GEMM uses its 192-token x 256-feature
+    workgroup tile with direct-to-LDS activation loads and an 8-deep operand ring: one, two and three trips
+    of the unrolled k loop, a ragged last token tile, one and several feature tiles, the XCD-banded
+    numbering (8 feature tiles); other K fall back to the 128 x 256 kernel."""
+    wide = 2 if epi == K.EPI_SWIGLU16 else 1      # SwiGLU: N counts output features, the weight has 2 N rows
+    for i, (M, Nw, Kd) in enumerate([(1100, 256, 256), (1024, 512, 512), (1153, 256, 768), (1030, 2048, 256),
+                                     (1250, 256, 224), (1030, 256, 64)]):
+        _gemm_case(dtype, K.PATH_TILE, epi, M, Nw // wide, Kd, bias=(i % 2 == 0), seed=50 + i)
+
+
 def _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope):
     """Random qkv rows for the new tokens and a random cache prefix; returns device index
     arrays, device buffers and float64 views for the oracle."""
@@ -303,13 +315,17 @@ def test_splitk_projection_folded_into_norm_and_cast(dtype, splits):
         r0 = rng.standard_normal((M, N)).astype(np.float32)
         tiled = K.sn_k_tile_weights(wb, N, Kd)
         part = torch.full((8, M, N), float("nan"), dtype=torch.float32, device="cuda")
-        used = K.sn_k_gemm_splitk(DT[dtype], dev16(tiled), dev16(xb), part, M, N, Kd, splits)
+        # the bias may be added by the projection itself (plane 0; what an iteration does) or by the fold
+        bias_in_gemm = (M != 33)
+        used = K.sn_k_gemm_splitk(DT[dtype], dev16(tiled), dev16(xb), dev16(bb) if bias_in_gemm else None, part,
+                                  M, N, Kd, splits)
+        fold_bias = None if bias_in_gemm else dev16(bb)
         assert used == splits or (splits == 0 and 1 <= used <= 8)
         want_x = r0.astype(np.float64) + synth.widen(bb, dtype) + synth.widen(xb, dtype) @ synth.widen(wb, dtype).T
         # folded into a LayerNorm
         x = torch.from_numpy(r0.copy()).cuda()
         out = torch.zeros(M, N, dtype=torch.int16, device="cuda")
-        K.sn_k_norm_fold(DT[dtype], True, x, dev16(g), dev16(sh), out, M, N, 1e-5, part, used, dev16(bb), 0)
+        K.sn_k_norm_fold(DT[dtype], True, x, dev16(g), dev16(sh), out, M, N, 1e-5, part, used, fold_bias, 0)
         torch.cuda.synchronize()
         got_x = x.cpu().numpy().astype(np.float64)
         assert np.abs(got_x - want_x).max() <= 2e-5 * np.abs(want_x).max(), (M, N, Kd)
@@ -317,7 +333,7 @@ def test_splitk_projection_folded_into_norm_and_cast(dtype, splits):
         check(synth.widen(host16(out), dtype), want_u, dtype, f"norm_fold M={M} N={N} K={Kd} splits={used}")
         # folded into the final cast
         x2 = torch.from_numpy(r0.copy()).cuda()
-        K.sn_k_cast_out_fold(DT[dtype], x2, out, M, N, part, used, dev16(bb))
+        K.sn_k_cast_out_fold(DT[dtype], x2, out, M, N, part, used, fold_bias)
         torch.cuda.synchronize()
         assert np.array_equal(x2.cpu().numpy(), x.cpu().numpy())               # same fixed-order sum
         assert np.array_equal(synth.widen(host16(out), dtype), ofw.round_to_storage(got_x, dtype))
