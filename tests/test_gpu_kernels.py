@@ -114,10 +114,9 @@ def test_gemm_tile(dtype, epi):
 
 @pytest.mark.parametrize("dtype,epi", [("f16", 0), ("f16", 1), ("bf16", 2), ("bf16", 3), ("f16", 3)])
 def test_gemm_tile_large_m(dtype, epi):
-    """From 1024 token rows on (and K a multiple of 256) the prefill GEMM uses its 192-token x 256-feature
-    workgroup tile with direct-to-LDS activation loads and an 8-deep operand ring: one, two and three trips
-    of the unrolled k loop, a ragged last token tile, one and several feature tiles, the XCD-banded
-    numbering (8 feature tiles); other K fall back to the 128 x 256 kernel."""
+    """The prefill GEMM at more than a thousand token rows: several token tiles with a ragged last one,
+    one and several feature tiles, the XCD-banded numbering (8 feature tiles), K with and without the
+    64-wide staging step of the LDS kernel."""
     wide = 2 if epi == K.EPI_SWIGLU16 else 1      # SwiGLU: N counts output features, the weight has 2 N rows
     for i, (M, Nw, Kd) in enumerate([(1100, 256, 256), (1024, 512, 512), (1153, 256, 768), (1030, 2048, 256),
                                      (1250, 256, 224), (1030, 256, 64)]):
