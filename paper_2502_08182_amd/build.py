@@ -12,7 +12,7 @@ LIB_DIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIB_DIR, "libsn.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["schedule.cpp", "layout.cpp", "record.cpp", "k_elementwise.hip", "k_gemm_skinny.hip", "k_gemm_tile.hip",
+SOURCES = ["schedule.cpp", "layout.cpp", "record.cpp", "coord.cpp", "k_elementwise.hip", "k_gemm_skinny.hip", "k_gemm_tile.hip",
            "k_attn_decode.hip", "k_attn_prefill.hip", "runtime.hip", "kernel_abi.hip"]
 
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",

@@ -39,6 +39,12 @@ def test_library_exports_every_declared_symbol():
     for n in rnames:
         assert hasattr(L, n), n
     assert sorted(sn_record.EXPORTS) == rnames
+    from paper_2502_08182_amd import sn_coord
+    cnames = [n for n in _declared_functions("sn_coord.h") if n.startswith("sn_coord_")]
+    assert len(cnames) == 4
+    for n in cnames:
+        assert hasattr(L, n), n
+    assert sorted(sn_coord.EXPORTS) == cnames
 
 
 def test_weight_tiling_is_a_permutation_with_the_documented_index():
