@@ -50,6 +50,10 @@ def parse():
     ap.add_argument("--prefill-slo-points", default="1.2,1.5,2",
                     help="TTFT SLO factors (x all-resident prefill) at which the prefill phase picks its own interval")
     ap.add_argument("--no-sweep", action="store_true", help="skip the interval sweep and SLO-point reports")
+    ap.add_argument("--contention", type=float, default=0.0, metavar="FRACTION",
+                    help="also run the prefill phase while a competing host-to-device copy stream takes this fraction "
+                         "of the link (0: off): at the interval picked without contention, then at the interval the "
+                         "bandwidth coordinator assigns (Sec. 4.5)")
     ap.add_argument("--repick", type=int, default=0, metavar="CELLS",
                     help="also run the decode steps with the interval re-selected before every iteration from a "
                          "performance record of CELLS sequence lengths spanning the run (the KV cache grows, the "
@@ -372,6 +376,89 @@ def main():
         out["prefill_phase"] = {"ttft_all_resident_ms": ttft0 / 1e6, "rho_transfer_over_compute": rho_p,
                                 "layer_compute_us_median": float(np.median(tcp)) / 1e3,
                                 "layer_transfer_us_median": float(np.median(txp)) / 1e3, "slo_points": pts}
+
+    # ---- bandwidth contention on the host link (Sec. 4.5): a competing copy stream stands in for a second
+    # GPU instance on the same bus; the coordinator widens this instance's interval until the two fit -------
+    if a.contention > 0:
+        import threading
+        from paper_2502_08182_amd import sn_coord as CO
+        se.place(0)
+        ttft0c = float(min(d["iter_ns"] for d in run_prefill(se, sn, w, x_pre, y_pre, 2)))
+        tcp2, txp2 = sn.sn_profile_layers(se.ctx, L, True, B, p_mean, reps=3)
+        w_bytes = sn.sn_layer_blob_bytes(se.cshape)
+        link_bps = int(w_bytes / (float(np.median(txp2)) * 1e-9))          # measured, this phase's transfers
+        f_c = 1.5
+        slo_c = int(f_c * ttft0c)
+        try:
+            n_solo = sn.sn_pick_interval_from_times(tcp2, txp2, int(slo_c * (1.0 - a.guard)), L + 1)
+        except sn.SnError:
+            n_solo = L + 1
+        other_bps = int(a.contention * link_bps)
+        chunk = 32 << 20
+        src = torch.empty(chunk, dtype=torch.uint8, pin_memory=True)
+        dst = torch.empty(chunk, dtype=torch.uint8, device="cuda")
+        side = torch.cuda.Stream()
+        stop = threading.Event()
+        moved = [0, 0.0]
+
+        def competitor():
+            period = chunk / other_bps
+            t_begin = time.perf_counter()
+            nxt = t_begin
+            while not stop.is_set():
+                with torch.cuda.stream(side):
+                    dst.copy_(src, non_blocking=True)
+                side.synchronize()
+                moved[0] += chunk
+                nxt += period
+                lag = nxt - time.perf_counter()
+                if lag > 0:
+                    time.sleep(lag)
+                else:
+                    nxt = time.perf_counter()      # cannot keep up: do not accumulate debt
+            moved[1] = time.perf_counter() - t_begin
+
+        def measure(n, contended):
+            se.place(n)
+            if contended:
+                stop.clear()
+                moved[0], moved[1] = 0, 0.0
+                th = threading.Thread(target=competitor)
+                th.start()
+                time.sleep(0.05)
+            st_ = run_prefill(se, sn, w, x_pre, y_pre, 4)[1:]
+            if contended:
+                stop.set()
+                th.join()
+            it_ = np.array([d["iter_ns"] for d in st_], dtype=np.float64)
+            hh = sum(d["h2d_ns"] for d in st_)
+            hb = sum(d["h2d_bytes"] for d in st_)
+            hs = sum(d["stall_ns"] for d in st_)
+            return {"interval": int(n), "n_offloaded": int(st_[-1]["n_offloaded"]), "ttft_ms": float(np.median(it_)) / 1e6,
+                    "ttft_max_ms": float(it_.max()) / 1e6, "within_slo": bool((it_ <= slo_c).all()),
+                    "hidden_fraction": (1 - hs / hh) if hh else 1.0, "h2d_GBps": hb / (hh * 1e-9) / 1e9 if hh else None,
+                    "competitor_GBps": (moved[0] / moved[1] / 1e9) if contended and moved[1] > 0 else 0.0}
+
+        me = CO.make_instance(L, w_bytes, int(ttft0c), n_solo, L + 1)
+        # the competitor as an instance with a single legal interval: one "layer" of other_bps bytes per second
+        other = CO.make_instance(1, other_bps, 1_000_000_000, 1, 1)
+        try:
+            (n_adj, _), host_b, rate_b = CO.sn_coord_adjust([me, other], link_bps)
+        except sn.SnError:
+            n_adj, host_b, rate_b = L + 1, 0, other_bps
+        res = {"slo_factor": f_c, "slo_ms": slo_c / 1e6, "link_GBps": link_bps / 1e9, "competitor_target_GBps": other_bps / 1e9,
+               "interval_without_contention": int(n_solo), "interval_from_coordinator": int(n_adj),
+               "coordinator_rate_GBps": rate_b / 1e9, "coordinator_host_GB": host_b / 1e9,
+               "alone": measure(n_solo, False), "contended_at_solo_interval": measure(n_solo, True),
+               "contended_at_coordinator_interval": measure(n_adj, True)}
+        out["contention"] = res
+        log(f"[bench] contention: link {link_bps / 1e9:.1f} GB/s, competitor {other_bps / 1e9:.1f} GB/s, TTFT SLO {slo_c / 1e6:.1f} ms; "
+            f"alone N={n_solo}: {res['alone']['ttft_ms']:.1f} ms; contended N={n_solo}: "
+            f"{res['contended_at_solo_interval']['ttft_ms']:.1f} ms (within={res['contended_at_solo_interval']['within_slo']}, "
+            f"competitor got {res['contended_at_solo_interval']['competitor_GBps']:.1f} GB/s); coordinator N={n_adj}: "
+            f"{res['contended_at_coordinator_interval']['ttft_ms']:.1f} ms (within={res['contended_at_coordinator_interval']['within_slo']}, "
+            f"competitor got {res['contended_at_coordinator_interval']['competitor_GBps']:.1f} GB/s)")
+        del src, dst
 
     # ---- fixed TPOT SLO while the KV cache grows: the interval is looked up in a performance record
     # before every iteration and the placement is changed when the answer changes (Sec. 4.2, 4.4) ----
