@@ -170,6 +170,47 @@ def test_decode_batches_spanning_row_tiles(batch):
         assert_close(gdec[t], dec[t], shape.dtype, f"B={batch} decode {t}")
 
 
+@pytest.mark.parametrize("family", ["opt", "llama_gqa"])
+def test_long_context_decode_splits_keys_across_workgroups(family):
+    """With few (sequence, KV head) pairs and more than 512 cached keys an iteration splits each
+    sequence's keys over several workgroups and merges the partial softmaxes in a second kernel
+    (with the rotation / append fused into the split that owns the new position).  One sequence is
+    long, one is short, one has an empty slot in the prefill batch (joins at the second chunk)."""
+    if family == "opt":
+        shape = synth.ModelShape(2, 256, 4, 4, 64, 512, act="gelu", norm="ln", rope=False, has_bias=True, dtype="f16")
+    else:
+        shape = synth.ModelShape(2, 512, 8, 2, 64, 512, act="swiglu", norm="rms", rope=True, has_bias=False, dtype="bf16")
+    lens = (700, 37, 513)
+    w = synth.Workload("long", shape, 3, lens, 3)
+    layers, prompt, table = _inputs(w)
+    pre, dec = oracle_run(w, layers, prompt, table)
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        se.load_synthetic_weights(layers=layers)
+        se.place(2)
+        se.kv_reset([p + w.decode_steps for p in lens])
+        # two prefill chunks; the third sequence contributes nothing to the first one
+        o0, o1, o2 = 0, lens[0], lens[0] + lens[1]
+        a = np.concatenate([prompt[o0:o0 + 400], prompt[o1:o1 + 37]])
+        b = np.concatenate([prompt[o0 + 400:o0 + 700], prompt[o2:o2 + 513]])
+        ga, fa = se.step([400, 37, 0], True, a, want_f32=True)
+        gb, fb = se.step([300, 0, 513], True, b, want_f32=True)
+        outs = [se.step([1, 1, 1], False, table[t], want_f32=True) for t in range(w.decode_steps)]
+        with Session(w.shape, w.batch, w.max_seq) as ref:      # everything resident, same chunks: bit for bit
+            ref.load_synthetic_weights(layers=layers)
+            ref.place(0)
+            ref.kv_reset([p + w.decode_steps for p in lens])
+            ra = ref.step([400, 37, 0], True, a)
+            rb = ref.step([300, 0, 513], True, b)
+            routs = [ref.step([1, 1, 1], False, table[t]) for t in range(w.decode_steps)]
+    assert np.array_equal(ga, ra) and np.array_equal(gb, rb)
+    got_f = np.concatenate([fa[:400], fb[:300], fa[400:], fb[300:]])
+    got_b = np.concatenate([ga[:400], gb[:300], ga[400:], gb[300:]])
+    assert_close_f32(got_b, got_f, pre, shape.dtype, f"{family} long prefill")
+    for t in range(w.decode_steps):
+        assert np.array_equal(outs[t][0], routs[t])
+        assert_close_f32(outs[t][0], outs[t][1], dec[t], shape.dtype, f"{family} long decode {t}")
+
+
 def test_chunked_prefill_equals_oracle(c1):
     w, layers, prompt, table, pre, dec = c1
     with Session(w.shape, w.batch, w.max_seq) as se:
