@@ -299,6 +299,16 @@ def main():
                     "frac_of_mfma_peak": pre_flops / (pre0["iter_ns"] * 1e-9) / MFMA_PEAK},
     }
 
+    # Sec. 5.6 / Fig. 14: tokens ("max length" = batch x (sequence + output)) the HBM budget can hold per interval
+    if w.hbm_budget > 0:
+        wl = sn.sn_layer_blob_bytes(se.cshape)
+        base_tok = sn.sn_max_tokens(L, 0, wl, kvtok, 0, w.hbm_budget)
+        out["max_length_vs_interval"] = {
+            "hbm_budget_GB": w.hbm_budget / 1e9, "workspace": "excluded",
+            "rows": [{"interval": int(N), "max_tokens": int(sn.sn_max_tokens(L, N, wl, kvtok, 0, w.hbm_budget))}
+                     for N in sorted({1, 2, 3, 4, 6, 8, 16, L, L + 1}) if N <= L + 1],
+            "no_offloading_tokens": int(base_tok)}
+
     if a.calibrate_copy:
         from paper_2502_08182_amd import sn_kernels
         src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")

@@ -140,6 +140,14 @@ uint64_t sn_resident_bytes(const sn_ctx* ctx, int32_t N);
  * (infinite maximum, Sec. 4.5); 0 = not even N = 1 fits. */
 int32_t sn_max_interval(const sn_ctx* ctx);
 
+/* "Max length" of Sec. 5.6 (batch size x (sequence + output length)): the largest number of
+ * cached tokens for which interval N (0 or > L: nothing offloaded) fits budget_bytes, when a
+ * layer's state is weight_bytes_per_layer + tokens * kv_bytes_per_token_per_layer, the GPU holds
+ * one state per resident layer plus two staging slots if anything is offloaded, and fixed_bytes
+ * of workspace.  0 if not even the weights fit (or if a token costs nothing).  Pure, host only. */
+uint64_t sn_max_tokens(int32_t L, int32_t N, uint64_t weight_bytes_per_layer, uint64_t kv_bytes_per_token_per_layer,
+                       uint64_t fixed_bytes, uint64_t budget_bytes);
+
 /* Pure helpers (host only, no GPU): the placement map and prefetch triggers for
  * (L, N).  offloaded[l] in {0,1}; trigger[l] = layer at whose start the load of
  * layer l is issued, or -1 for resident layers.  Both host arrays of length L. */

@@ -9,6 +9,7 @@ Contents (all exact integer arithmetic; times are nanoseconds):
   timeline                           iteration time under that placement (Sec. 4.3, Fig. 7)
   pick_interval                      smallest N that meets the SLO       (Sec. 4.3 last par., 4.4)
   resident_bytes / max_interval      GPU-capacity bound on N             (Sec. 4.5)
+  max_tokens                         "max length" a GPU can hold at N    (Sec. 5.6, Fig. 14)
   paper_rule                         the analyzer's closed form          (Sec. 4.4)
 
 Layers are 0-indexed here; the paper counts from 1.
@@ -113,6 +114,31 @@ def max_interval(L: int, budget: int, state_bytes: int, slot_bytes: int, fixed_b
         if resident_bytes(L, N, state_bytes, slot_bytes, fixed_bytes) <= budget:
             best = N
     return best
+
+
+def max_tokens(L: int, N: int, weight_bytes: int, kv_token_bytes: int, fixed_bytes: int, budget: int) -> int:
+    """Sec. 5.6's "max length" (batch size x (sequence + output length)): the largest number of
+    cached tokens for which interval N still fits the budget.  A layer's state is its weights plus
+    its KV slice of that many tokens; GPU-resident layers and the two staging slots (when anything
+    is offloaded) each hold one such state.  Plain search from the definition."""
+    def fits(t: int) -> bool:
+        state = weight_bytes + t * kv_token_bytes
+        return resident_bytes(L, N, state, state, fixed_bytes) <= budget
+    if not fits(0):
+        return 0
+    if kv_token_bytes == 0:
+        raise ValueError("unbounded")
+    hi = 1
+    while fits(hi):
+        hi *= 2
+    lo = hi // 2                      # fits(lo), not fits(hi)
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if fits(mid):
+            lo = mid
+        else:
+            hi = mid
+    return lo
 
 
 # ---------------------------------------------------------------------------

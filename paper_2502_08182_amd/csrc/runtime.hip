@@ -208,6 +208,12 @@ extern "C" int sn_pick_interval_from_times(int32_t L, const int64_t* tc, const i
   return SN_OK;
 }
 
+extern "C" uint64_t sn_max_tokens(int32_t L, int32_t N, uint64_t weight_bytes_per_layer, uint64_t kv_bytes_per_token_per_layer,
+                                  uint64_t fixed_bytes, uint64_t budget_bytes) {
+  if (L < 1 || N < 0) return 0;
+  return max_tokens(L, N == 0 ? L + 1 : N, weight_bytes_per_layer, kv_bytes_per_token_per_layer, fixed_bytes, budget_bytes);
+}
+
 extern "C" int32_t sn_paper_rule(int32_t L, int64_t t_trans_ns, int64_t slo_ns) {
   return paper_rule(L, t_trans_ns, slo_ns);
 }

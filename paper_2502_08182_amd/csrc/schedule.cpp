@@ -70,6 +70,17 @@ uint64_t resident_bytes(int L, int N, uint64_t state, uint64_t slot, uint64_t fi
   return (uint64_t)(L - K) * state + (K ? 2 * slot : 0) + fixed;
 }
 
+uint64_t max_tokens(int L, int N, uint64_t weight_bytes, uint64_t kv_token_bytes, uint64_t fixed, uint64_t budget) {
+  // states held on the GPU: resident layers, plus two staging slots when anything is offloaded;
+  // each is weights + tokens * kv_token_bytes
+  const int K = offloaded_count(L, N);
+  const unsigned __int128 states = (unsigned __int128)(L - K) + (K ? 2 : 0);
+  const unsigned __int128 base = states * weight_bytes + fixed;
+  if (kv_token_bytes == 0 || base > budget) return 0;
+  const unsigned __int128 t = ((unsigned __int128)budget - base) / (states * kv_token_bytes);
+  return t > (unsigned __int128)UINT64_MAX ? UINT64_MAX : (uint64_t)t;
+}
+
 int max_interval(int L, uint64_t budget, uint64_t state, uint64_t slot, uint64_t fixed) {
   if (budget == 0) return L + 1;
   int best = 0;

@@ -24,7 +24,7 @@ ERROR_NAMES = {-1: "SN_E_INVAL", -2: "SN_E_STATE", -3: "SN_E_BUDGET", -4: "SN_E_
 
 EXPORTS = (
     "sn_init", "sn_destroy", "sn_last_error", "sn_layers", "sn_layer_blob_bytes", "sn_set_layer_weights", "sn_place",
-    "sn_set_budget_enforce", "sn_resident_bytes", "sn_max_interval", "sn_placement", "sn_kv_reset", "sn_step",
+    "sn_set_budget_enforce", "sn_resident_bytes", "sn_max_interval", "sn_max_tokens", "sn_placement", "sn_kv_reset", "sn_step",
     "sn_read_hidden_f32",
     "sn_set_timing", "sn_set_kernel_timing_class", "sn_time_kernel_class", "sn_get_stats", "sn_get_layer_times", "sn_profile_layers", "sn_timeline",
     "sn_pick_interval_from_times", "sn_pick_interval", "sn_paper_rule",
@@ -92,6 +92,7 @@ def lib() -> C.CDLL:
         "sn_set_budget_enforce": (C.c_int, [ctx, i32]),
         "sn_resident_bytes": (u64, [ctx, i32]),
         "sn_max_interval": (i32, [ctx]),
+        "sn_max_tokens": (u64, [i32, i32, u64, u64, u64, u64]),
         "sn_placement": (C.c_int, [i32, i32, C.POINTER(C.c_uint8), pi32]),
         "sn_kv_reset": (C.c_int, [ctx, i32, pi32]),
         "sn_step": (C.c_int, [ctx, C.POINTER(sn_batch), C.POINTER(sn_kv), C.c_void_p]),
@@ -189,6 +190,10 @@ def sn_resident_bytes(ctx, N: int) -> int:
 
 def sn_max_interval(ctx) -> int:
     return int(lib().sn_max_interval(ctx))
+
+
+def sn_max_tokens(L: int, N: int, weight_bytes: int, kv_token_bytes: int, fixed_bytes: int, budget: int) -> int:
+    return int(lib().sn_max_tokens(L, N, weight_bytes, kv_token_bytes, fixed_bytes, budget))
 
 
 def sn_layers(ctx) -> int:

@@ -169,3 +169,14 @@ def test_init_without_gpu_fails_loudly():
     with pytest.raises(sn.SnError) as e:
         sn.sn_init(sn.make_shape(synth.workload("c1").shape, 2, 40))
     assert e.value.code == sn.SN_E_HIP
+
+
+def test_max_tokens_agrees_with_the_oracle():
+    """Sec. 5.6's max length: the library's closed form against the oracle's search from the definition."""
+    assert sn.sn_max_tokens(8, 2, 100, 2, 50, 2050) == 116 and sn.sn_max_tokens(8, 0, 100, 2, 50, 2050) == 75
+    rnd = random.Random(12)
+    for _ in range(2000):
+        L, N = rnd.randint(1, 80), rnd.randint(1, 82)
+        wb, kt, fx = rnd.randint(1, 3 * 10**9), rnd.randint(1, 10**6), rnd.randint(0, 10**10)
+        budget = rnd.choice([0, rnd.randint(0, 300 * 10**9)])
+        assert sn.sn_max_tokens(L, N, wb, kt, fx, budget) == osch.max_tokens(L, N, wb, kt, fx, budget)

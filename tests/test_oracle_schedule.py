@@ -193,6 +193,38 @@ def test_capacity_bound():
         prev = r
 
 
+def test_max_tokens_hand_worked():
+    """Sec. 5.6 / Fig. 14: a smaller interval frees GPU memory for tokens.  L = 8 layers of 100 B of
+    weights, 2 B of KV per token per layer, 50 B of workspace, 2050 B of GPU memory.
+    Nothing offloaded: 8 states -> 8 (100 + 2t) + 50 <= 2050 -> t <= 75.
+    N = 2: 4 resident + 2 slots = 6 states -> 6 (100 + 2t) <= 2000 -> t <= 116 (2t <= 233.3).
+    N = 1: 2 slots only -> 2 (100 + 2t) <= 2000 -> t <= 450.
+    N = 8: 7 resident + 2 slots = 9 states -> 9 (100 + 2t) <= 2000 -> t <= 61 (2t <= 122.2)."""
+    args = dict(weight_bytes=100, kv_token_bytes=2, fixed_bytes=50, budget=2050)
+    assert osch.max_tokens(8, 9, **args) == 75
+    assert osch.max_tokens(8, 2, **args) == 116
+    assert osch.max_tokens(8, 1, **args) == 450
+    assert osch.max_tokens(8, 8, **args) == 61
+    assert osch.max_tokens(8, 9, weight_bytes=100, kv_token_bytes=2, fixed_bytes=50, budget=849) == 0   # weights alone do not fit
+    assert osch.max_tokens(8, 9, weight_bytes=100, kv_token_bytes=2, fixed_bytes=50, budget=850) == 0
+    assert osch.max_tokens(8, 9, weight_bytes=100, kv_token_bytes=2, fixed_bytes=50, budget=866) == 1
+    # consistent with the capacity bound: at that many tokens the interval fits, with one more it does not
+    rnd = random.Random(9)
+    for _ in range(300):
+        L, N = rnd.randint(1, 40), rnd.randint(1, 41)
+        wb, kt, fx = rnd.randint(1, 10**9), rnd.randint(1, 10**5), rnd.randint(0, 10**9)
+        budget = rnd.randint(0, 60 * 10**9)
+        t = osch.max_tokens(L, N, wb, kt, fx, budget)
+        st = wb + t * kt
+        if t > 0:
+            assert osch.resident_bytes(L, N, st, st, fx) <= budget
+        if osch.resident_bytes(L, N, wb, wb, fx) <= budget:
+            assert osch.resident_bytes(L, N, st + kt, st + kt, fx) > budget
+    # fewer resident layers never hold fewer tokens (K is non-increasing in N; the slots cost two states)
+    for N in range(2, 9):
+        assert osch.max_tokens(8, N, **args) >= osch.max_tokens(8, N + 1, **args) or N == 8
+
+
 def test_paper_rule_never_exceeds_timeline_pick():
     rnd = random.Random(4)
     for _ in range(5000):
