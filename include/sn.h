@@ -133,6 +133,18 @@ int sn_set_layer_weights(sn_ctx* ctx, int32_t layer, const void* host_blob, uint
  * enforcement was switched off with sn_set_budget_enforce(ctx, 0). */
 int sn_place(sn_ctx* ctx, int32_t N);
 int sn_set_budget_enforce(sn_ctx* ctx, int32_t on);
+/* When the load of an offloaded layer is issued.
+ *   SN_SCHED_PAPER (default): when compute reaches the first layer of the offloaded layer's own
+ *     group (Sec. 4.3, Fig. 7; the previous layer when N = 1).
+ *   SN_SCHED_EAGER: one group earlier -- as early as the two staging slots allow: the slot of
+ *     the k-th offloaded layer is free once the (k-2)-th has been computed, so its load is
+ *     issued at the layer after that one (at the start of the iteration for the first two).
+ *     The copy stream then runs back to back, the regime the analyzer's closed form (Sec. 4.4)
+ *     describes; the iteration is never longer than with SN_SCHED_PAPER, the output identical.
+ * Takes effect at once (also for the placement in force); sn_pick_interval and the timeline it
+ * uses follow the context's schedule. */
+enum { SN_SCHED_PAPER = 0, SN_SCHED_EAGER = 1 };
+int sn_set_schedule(sn_ctx* ctx, int32_t schedule);
 /* Device bytes interval N needs: resident layers' state + two staging slots (if any
  * layer is offloaded) + workspace. */
 uint64_t sn_resident_bytes(const sn_ctx* ctx, int32_t N);
@@ -152,6 +164,7 @@ uint64_t sn_max_tokens(int32_t L, int32_t N, uint64_t weight_bytes_per_layer, ui
  * (L, N).  offloaded[l] in {0,1}; trigger[l] = layer at whose start the load of
  * layer l is issued, or -1 for resident layers.  Both host arrays of length L. */
 int sn_placement(int32_t L, int32_t N, uint8_t* offloaded, int32_t* trigger);
+int sn_placement_sched(int32_t L, int32_t N, int32_t schedule, uint8_t* offloaded, int32_t* trigger);
 
 /* --- KV cache ------------------------------------------------------------------
  * Start a new set of sequences: per-sequence capacities in tokens (host, [batch]);
@@ -210,7 +223,13 @@ int sn_timeline(int32_t L, const int64_t* tc_ns, const int64_t* tx_ns, int32_t N
  * Pure, host only. */
 int sn_pick_interval_from_times(int32_t L, const int64_t* tc_ns, const int64_t* tx_ns,
                                 int64_t slo_ns, int32_t N_max, int32_t* N_out);
-/* Same, using the last sn_profile_layers result and the context's budget. */
+/* The two above for a given schedule (SN_SCHED_*); sn_timeline and
+ * sn_pick_interval_from_times are the SN_SCHED_PAPER case. */
+int sn_timeline_sched(int32_t L, const int64_t* tc_ns, const int64_t* tx_ns, int32_t N, int32_t schedule,
+                      int64_t* iter_ns, int64_t* stall_total_ns);
+int sn_pick_interval_from_times_sched(int32_t L, const int64_t* tc_ns, const int64_t* tx_ns, int64_t slo_ns,
+                                      int32_t N_max, int32_t schedule, int32_t* N_out);
+/* Same, using the last sn_profile_layers result, the context's budget and its schedule. */
 int sn_pick_interval(sn_ctx* ctx, double slo_ms, int32_t* N_out);
 
 /* The analyzer's closed form (Sec. 4.4) for uniform times, reported beside the pick:

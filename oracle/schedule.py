@@ -50,9 +50,19 @@ def offloaded_layers(L: int, N: int) -> List[int]:
     return [l for l in range(L) if (l + 1) % N == 0]
 
 
-def trigger_layers(L: int, N: int) -> List[int]:
-    """For each offloaded layer (same order), the layer at whose start its load is issued."""
-    back = max(N - 1, 1)
+PAPER, EAGER = 0, 1     # when the load of an offloaded layer is issued
+
+
+def trigger_layers(L: int, N: int, schedule: int = PAPER) -> List[int]:
+    """For each offloaded layer (same order), the layer at whose start its load is issued.
+
+    PAPER: the first layer of the offloaded layer's own group (Sec. 4.3, Fig. 7).
+    EAGER: one group earlier -- as early as two staging slots allow: the slot of the k-th
+    offloaded layer is free as soon as the (k-2)-th has been computed, so its load is issued at
+    the layer after that one (at the start of the iteration for the first two).  This keeps
+    the copy stream busy back to back, the regime the analyzer's closed form (Sec. 4.4)
+    describes."""
+    back = max(N - 1, 1) if schedule == PAPER else 2 * N - 1
     return [max(0, o - back) for o in offloaded_layers(L, N)]
 
 
@@ -61,14 +71,14 @@ def trigger_layers(L: int, N: int) -> List[int]:
 # point before each offloaded layer)
 # ---------------------------------------------------------------------------
 
-def timeline(tc: Sequence[int], tx: Sequence[int], N: int) -> Tuple[int, List[int]]:
+def timeline(tc: Sequence[int], tx: Sequence[int], N: int, schedule: int = PAPER) -> Tuple[int, List[int]]:
     """Iteration time and the stall before each offloaded layer.
 
     tc[l]: compute time of layer l; tx[l]: host-to-GPU transfer time of layer l's state.
     """
     L = len(tc)
     off = offloaded_layers(L, N)
-    trig = trigger_layers(L, N)
+    trig = trigger_layers(L, N, schedule)
     t = 0                 # compute-stream clock
     copy_free = 0         # time the copy stream finishes what it has been given
     ready = {}            # offloaded layer -> time its state is on the GPU
@@ -146,19 +156,19 @@ def max_tokens(L: int, N: int, weight_bytes: int, kv_token_bytes: int, fixed_byt
 # 4.4); the request is rejected when minimum > maximum (Sec. 4.5, Fig. 8)
 # ---------------------------------------------------------------------------
 
-def min_interval(tc: Sequence[int], tx: Sequence[int], slo: int) -> Optional[int]:
+def min_interval(tc: Sequence[int], tx: Sequence[int], slo: int, schedule: int = PAPER) -> Optional[int]:
     """Smallest N in 1..L with iteration time <= slo; L+1 if only the un-offloaded
     iteration meets it; None if even that does not."""
     L = len(tc)
     for N in range(1, L + 1):
-        if timeline(tc, tx, N)[0] <= slo:
+        if timeline(tc, tx, N, schedule)[0] <= slo:
             return N
     return L + 1 if sum(tc) <= slo else None
 
 
-def pick_interval(tc: Sequence[int], tx: Sequence[int], slo: int, n_max: int) -> Optional[int]:
+def pick_interval(tc: Sequence[int], tx: Sequence[int], slo: int, n_max: int, schedule: int = PAPER) -> Optional[int]:
     """The interval to run with, or None when the SLO cannot be met within capacity."""
-    n_min = min_interval(tc, tx, slo)
+    n_min = min_interval(tc, tx, slo, schedule)
     if n_min is None or n_min > n_max:
         return None
     return n_min

@@ -67,6 +67,7 @@ struct sn_ctx {
   bool enforce = true;
   hipStream_t compute = nullptr, h2d = nullptr, d2h = nullptr;
   int N = 0;                     // interval in effect (L+1: nothing offloaded)
+  int sched = kSchedPaper;       // when prefetches are issued (sn_set_schedule)
   bool placed = false;
   int timing = 0;
   int timing_class = -1;          // kernel class whose launches are bracketed at level 2 (-1: all)
@@ -183,6 +184,40 @@ extern "C" int sn_placement(int32_t L, int32_t N, uint8_t* offloaded, int32_t* t
     offloaded[l] = is_offloaded(L, N, l) ? 1 : 0;
     trigger[l] = offloaded[l] ? trigger_of(N, l) : -1;
   }
+  return SN_OK;
+}
+
+static bool bad_sched(int32_t s) { return s != kSchedPaper && s != kSchedEager; }
+
+extern "C" int sn_placement_sched(int32_t L, int32_t N, int32_t schedule, uint8_t* offloaded, int32_t* trigger) {
+  if (L < 1 || !offloaded || !trigger || bad_sched(schedule)) return fail(nullptr, SN_E_INVAL, "sn_placement_sched: bad argument");
+  for (int l = 0; l < L; ++l) {
+    offloaded[l] = is_offloaded(L, N, l) ? 1 : 0;
+    trigger[l] = offloaded[l] ? trigger_of(N, l, schedule) : -1;
+  }
+  return SN_OK;
+}
+
+extern "C" int sn_timeline_sched(int32_t L, const int64_t* tc, const int64_t* tx, int32_t N, int32_t schedule,
+                                 int64_t* iter_ns, int64_t* stall_total_ns) {
+  if (L < 1 || !tc || !tx || !iter_ns || bad_sched(schedule)) return fail(nullptr, SN_E_INVAL, "sn_timeline_sched: bad argument");
+  for (int l = 0; l < L; ++l)
+    if (tc[l] < 0 || tx[l] < 0) return fail(nullptr, SN_E_INVAL, "sn_timeline_sched: negative time");
+  *iter_ns = iteration_time(L, tc, tx, N, stall_total_ns, schedule);
+  return SN_OK;
+}
+
+extern "C" int sn_pick_interval_from_times_sched(int32_t L, const int64_t* tc, const int64_t* tx, int64_t slo_ns,
+                                                 int32_t N_max, int32_t schedule, int32_t* N_out) {
+  if (L < 1 || !tc || !tx || !N_out || bad_sched(schedule))
+    return fail(nullptr, SN_E_INVAL, "sn_pick_interval_from_times_sched: bad argument");
+  for (int l = 0; l < L; ++l)
+    if (tc[l] < 0 || tx[l] < 0) return fail(nullptr, SN_E_INVAL, "sn_pick_interval_from_times_sched: negative time");
+  const int n = min_interval(L, tc, tx, slo_ns, schedule);
+  if (n < 0) return fail(nullptr, SN_E_INFEASIBLE, "SLO %lld ns is below the un-offloaded iteration time", (long long)slo_ns);
+  if (n > N_max)
+    return fail(nullptr, SN_E_INFEASIBLE, "minimum interval %d exceeds the maximum %d allowed by GPU capacity", n, N_max);
+  *N_out = n;
   return SN_OK;
 }
 
@@ -444,6 +479,21 @@ extern "C" int32_t sn_max_interval(const sn_ctx* c) {
   return max_interval(c->shape.n_layers, c->budget, c->state_bytes, c->state_bytes, fixed_bytes(c));
 }
 
+extern "C" int sn_set_schedule(sn_ctx* c, int32_t schedule) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "null context");
+  if (bad_sched(schedule)) return fail(c, SN_E_INVAL, "sn_set_schedule: unknown schedule %d", schedule);
+  int rc = sync_all(c);
+  if (rc) return rc;
+  c->sched = schedule;
+  if (c->placed)
+    for (int l = 0; l < c->shape.n_layers; ++l) {
+      LayerState& ls = c->layers[l];
+      ls.trigger = ls.offloaded ? trigger_of(c->N, l, c->sched) : -1;
+    }
+  c->last_valid = false;
+  return SN_OK;
+}
+
 extern "C" int sn_set_budget_enforce(sn_ctx* c, int32_t on) {
   if (!c) return fail(nullptr, SN_E_INVAL, "null context");
   c->enforce = on != 0;
@@ -507,7 +557,7 @@ extern "C" int sn_place(sn_ctx* c, int32_t N) {
   for (int l = 0; l < L; ++l) {
     LayerState& ls = c->layers[l];
     ls.offloaded = is_offloaded(L, N, l);
-    ls.trigger = ls.offloaded ? trigger_of(N, l) : -1;
+    ls.trigger = ls.offloaded ? trigger_of(N, l, c->sched) : -1;
     ls.slot = ls.offloaded ? (k++ & 1) : 0;
   }
   c->slot_free_valid[0] = c->slot_free_valid[1] = false;
@@ -739,8 +789,9 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
   for (int l = 0; l < L; ++l) {
     LayerState& ls = c->layers[l];
     if (c->timing >= 1 || ls.offloaded) SN_HIP(c, hipEventRecord(c->ev_layer[l], c->compute));
-    // prefetches triggered by reaching this layer (paper Sec. 4.3: first layer of the group)
-    for (int o = l; o < L && o <= l + std::max(c->N - 1, 1); ++o) {
+    // prefetches triggered by reaching this layer (paper Sec. 4.3: first layer of the group; eager
+    // schedule: one group earlier, as soon as the staging slot is free)
+    for (int o = l; o < L && o <= l + trigger_lead(c->N, c->sched); ++o) {
       LayerState& os = c->layers[o];
       if (!os.offloaded || os.trigger != l) continue;
       SN_HIP(c, hipEventRecord(c->ev_trig[o], c->compute));
@@ -1078,7 +1129,8 @@ extern "C" int sn_pick_interval(sn_ctx* c, double slo_ms, int32_t* N_out) {
   if (!(slo_ms > 0)) return fail(c, SN_E_INVAL, "sn_pick_interval: SLO must be positive");
   const int64_t slo_ns = (int64_t)std::llround(slo_ms * 1.0e6);
   const int L = c->shape.n_layers;
-  const int rc = sn_pick_interval_from_times(L, c->prof_tc.data(), c->prof_tx.data(), slo_ns, sn_max_interval(c), N_out);
+  const int rc = sn_pick_interval_from_times_sched(L, c->prof_tc.data(), c->prof_tx.data(), slo_ns, sn_max_interval(c),
+                                                   c->sched, N_out);
   if (rc) {
     c->err = g_err;
     return rc;

@@ -17,13 +17,19 @@ int offloaded_count(int L, int N) { return (N >= 1 && N <= L) ? L / N : 0; }
 
 bool is_offloaded(int L, int N, int l) { return N >= 1 && N <= L && (l + 1) % N == 0; }
 
-int trigger_of(int N, int o) {
-  // first layer of the group; one layer ahead when every layer is offloaded (N == 1)
-  const int lead = N > 1 ? N - 1 : 1;
+int trigger_lead(int N, int sched) {
+  // paper: first layer of the group; one layer ahead when every layer is offloaded (N == 1).
+  // eager: one group earlier -- the staging slot of the k-th offloaded layer is free once the
+  // (k-2)-th has been computed, so its load can be issued at the layer after that one.
+  return sched == kSchedEager ? 2 * N - 1 : (N > 1 ? N - 1 : 1);
+}
+
+int trigger_of(int N, int o, int sched) {
+  const int lead = trigger_lead(N, sched);
   return o >= lead ? o - lead : 0;
 }
 
-int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total) {
+int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total, int sched) {
   // Walk the offloaded layers in order.  `now` is the compute stream's clock at the
   // start of the layer under consideration, `copy_idle` the time the (single, FIFO)
   // copy stream runs dry.  Prefix sums give the clock at any trigger layer without
@@ -35,14 +41,15 @@ int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64
   int64_t stalls = 0;
   const int K = offloaded_count(L, N);
   // Stalls at offloaded layers strictly before a trigger layer delay that trigger.
-  // Offloaded layers are visited in increasing order; a trigger g_k may precede the
-  // previous offloaded layer only when N == 1, where g_k = o_k - 1 = o_{k-1}: the
-  // trigger fires at the *start* of o_{k-1}, i.e. before that layer's own stall.
+  // Offloaded layers are visited in increasing order.  A trigger g_k never lies beyond the
+  // previous offloaded layer o_{k-1}; when it coincides with it (N == 1) it fires at the
+  // *start* of o_{k-1}, i.e. before that layer's own stall; with the eager schedule it is the
+  // layer right after o_{k-2}, whose stall is already part of the shift recorded for it.
   std::vector<int64_t> shift_before(L + 1, 0);   // stall accumulated before layer l starts waiting
   int next_fill = 0;
   for (int k = 1; k <= K; ++k) {
     const int o = k * N - 1;
-    const int g = trigger_of(N, o);
+    const int g = trigger_of(N, o, sched);
     for (; next_fill <= o; ++next_fill) shift_before[next_fill] = shift;
     const int64_t issue = pre[g] + shift_before[g];
     const int64_t begin = std::max(copy_idle, issue);
@@ -56,10 +63,10 @@ int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64
   return pre[L] + shift;
 }
 
-int min_interval(int L, const int64_t* tc, const int64_t* tx, int64_t slo) {
+int min_interval(int L, const int64_t* tc, const int64_t* tx, int64_t slo, int sched) {
   // Measured layer times need not make T(N) monotone in N, so every N is tried.
   for (int N = 1; N <= L; ++N)
-    if (iteration_time(L, tc, tx, N, nullptr) <= slo) return N;
+    if (iteration_time(L, tc, tx, N, nullptr, sched) <= slo) return N;
   int64_t all = 0;
   for (int l = 0; l < L; ++l) all += tc[l];
   return all <= slo ? L + 1 : -1;

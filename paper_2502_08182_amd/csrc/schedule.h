@@ -5,9 +5,11 @@
 namespace sn {
 int offloaded_count(int L, int N);
 bool is_offloaded(int L, int N, int l);
-int trigger_of(int N, int offloaded_layer);
-int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total);
-int min_interval(int L, const int64_t* tc, const int64_t* tx, int64_t slo);   // -1: none
+constexpr int kSchedPaper = 0, kSchedEager = 1;   // when the load of an offloaded layer is issued
+int trigger_lead(int N, int sched);               // layers between the trigger and the offloaded layer
+int trigger_of(int N, int offloaded_layer, int sched = kSchedPaper);
+int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total, int sched = kSchedPaper);
+int min_interval(int L, const int64_t* tc, const int64_t* tx, int64_t slo, int sched = kSchedPaper);   // -1: none
 uint64_t resident_bytes(int L, int N, uint64_t state, uint64_t slot, uint64_t fixed);
 int max_interval(int L, uint64_t budget, uint64_t state, uint64_t slot, uint64_t fixed);
 uint64_t max_tokens(int L, int N, uint64_t weight_bytes, uint64_t kv_token_bytes, uint64_t fixed, uint64_t budget);

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libsn.so")
 SN_F16, SN_BF16 = 0, 1
 SN_ACT_GELU, SN_ACT_SWIGLU = 0, 1
 SN_NORM_LN, SN_NORM_RMS = 0, 1
+SN_SCHED_PAPER, SN_SCHED_EAGER = 0, 1
 SN_OK, SN_E_INVAL, SN_E_STATE, SN_E_BUDGET, SN_E_INFEASIBLE, SN_E_NOMEM, SN_E_HIP = 0, -1, -2, -3, -4, -5, -6
 SN_K_NAMES = ("norm", "qkv", "rope_append", "attn", "oproj", "ffn_up", "ffn_down", "other")
 ERROR_NAMES = {-1: "SN_E_INVAL", -2: "SN_E_STATE", -3: "SN_E_BUDGET", -4: "SN_E_INFEASIBLE",
@@ -28,6 +29,7 @@ EXPORTS = (
     "sn_read_hidden_f32",
     "sn_set_timing", "sn_set_kernel_timing_class", "sn_time_kernel_class", "sn_get_stats", "sn_get_layer_times", "sn_profile_layers", "sn_timeline",
     "sn_pick_interval_from_times", "sn_pick_interval", "sn_paper_rule",
+    "sn_set_schedule", "sn_placement_sched", "sn_timeline_sched", "sn_pick_interval_from_times_sched",
 )
 
 
@@ -107,6 +109,10 @@ def lib() -> C.CDLL:
         "sn_pick_interval_from_times": (C.c_int, [i32, pi64, pi64, i64, i32, pi32]),
         "sn_pick_interval": (C.c_int, [ctx, C.c_double, pi32]),
         "sn_paper_rule": (i32, [i32, i64, i64]),
+        "sn_set_schedule": (C.c_int, [ctx, i32]),
+        "sn_placement_sched": (C.c_int, [i32, i32, i32, C.POINTER(C.c_uint8), pi32]),
+        "sn_timeline_sched": (C.c_int, [i32, pi64, pi64, i32, i32, pi64, pi64]),
+        "sn_pick_interval_from_times_sched": (C.c_int, [i32, pi64, pi64, i64, i32, i32, pi32]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -208,6 +214,18 @@ def sn_placement(L: int, N: int):
     return off, trig
 
 
+def sn_placement_sched(L: int, N: int, schedule: int):
+    off = np.zeros(L, dtype=np.uint8)
+    trig = np.zeros(L, dtype=np.int32)
+    _check(lib().sn_placement_sched(L, N, schedule, off.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                    trig.ctypes.data_as(C.POINTER(C.c_int32))))
+    return off, trig
+
+
+def sn_set_schedule(ctx, schedule: int) -> None:
+    _check(lib().sn_set_schedule(ctx, schedule), ctx)
+
+
 def sn_kv_reset(ctx, capacity: Sequence[int]) -> None:
     cap = np.ascontiguousarray(capacity, dtype=np.int32)
     _check(lib().sn_kv_reset(ctx, cap.size, cap.ctypes.data_as(C.POINTER(C.c_int32))), ctx)
@@ -269,6 +287,22 @@ def sn_timeline(tc: Sequence[int], tx: Sequence[int], N: int):
     it, st = C.c_int64(), C.c_int64()
     _check(lib().sn_timeline(a.size, pa, pb, N, C.byref(it), C.byref(st)))
     return it.value, st.value
+
+
+def sn_timeline_sched(tc: Sequence[int], tx: Sequence[int], N: int, schedule: int):
+    a, pa = _i64(tc)
+    b, pb = _i64(tx)
+    it, st = C.c_int64(), C.c_int64()
+    _check(lib().sn_timeline_sched(a.size, pa, pb, N, schedule, C.byref(it), C.byref(st)))
+    return it.value, st.value
+
+
+def sn_pick_interval_from_times_sched(tc: Sequence[int], tx: Sequence[int], slo_ns: int, n_max: int, schedule: int) -> int:
+    a, pa = _i64(tc)
+    b, pb = _i64(tx)
+    out = C.c_int32()
+    _check(lib().sn_pick_interval_from_times_sched(a.size, pa, pb, int(slo_ns), int(n_max), schedule, C.byref(out)))
+    return out.value
 
 
 def sn_pick_interval_from_times(tc: Sequence[int], tx: Sequence[int], slo_ns: int, n_max: int) -> int:

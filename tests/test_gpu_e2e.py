@@ -98,6 +98,30 @@ def test_output_is_bit_identical_for_every_interval(c1):
         assert np.array_equal(got[1], ref[1]), f"decode differs at N={N}"
 
 
+def test_eager_schedule_changes_timing_only(c1):
+    """Loads issued one group earlier (as soon as a staging slot is free) move the same bytes and give
+    the same bits for every interval, also when the schedule is switched under a live placement."""
+    w, layers, prompt, table, *_ = c1
+    ref = gpu_run(w, layers, prompt, table, 0)
+    for N in (1, 2, 3, 4):
+        with Session(w.shape, w.batch, w.max_seq) as se:
+            se.load_synthetic_weights(layers=layers)
+            sn.sn_set_schedule(se.ctx, sn.SN_SCHED_EAGER)
+            se.place(N)
+            pre, dec = se.run_workload(w, prompt, table)
+            st = se.stats()
+            assert st["n_offloaded"] == w.shape.n_layers // N and st["h2d_bytes"] > 0
+            assert np.array_equal(pre, ref[0]) and np.array_equal(dec, ref[1]), f"eager differs at N={N}"
+            sn.sn_set_schedule(se.ctx, sn.SN_SCHED_PAPER)          # switched back without re-placing
+            pre2, dec2 = se.run_workload(w, prompt, table)
+            assert se.stats()["h2d_bytes"] == st["h2d_bytes"]
+            assert np.array_equal(pre2, ref[0]) and np.array_equal(dec2, ref[1])
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        with pytest.raises(sn.SnError) as e:
+            sn.sn_set_schedule(se.ctx, 7)
+        assert e.value.code == sn.SN_E_INVAL
+
+
 def test_replacing_between_iterations_keeps_the_cache(c1):
     """Sec. 4.2: a new interval is applied before the next iteration; live KV must move with it."""
     w, layers, prompt, table, *_ = c1

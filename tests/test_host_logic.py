@@ -180,3 +180,31 @@ def test_max_tokens_agrees_with_the_oracle():
         wb, kt, fx = rnd.randint(1, 3 * 10**9), rnd.randint(1, 10**6), rnd.randint(0, 10**10)
         budget = rnd.choice([0, rnd.randint(0, 300 * 10**9)])
         assert sn.sn_max_tokens(L, N, wb, kt, fx, budget) == osch.max_tokens(L, N, wb, kt, fx, budget)
+
+
+def test_eager_schedule_agrees_with_the_oracle():
+    """Triggers, timeline and picker of the eager schedule (loads issued as early as the two staging
+    slots allow) against the oracle, exactly; and never slower than the paper's schedule."""
+    rnd = random.Random(31)
+    for _ in range(1500):
+        L = rnd.randint(1, 40)
+        tc = [rnd.randint(1, 400) for _ in range(L)]
+        tx = [rnd.randint(0, 3000) for _ in range(L)]
+        N = rnd.randint(1, L + 1)
+        off, trig = sn.sn_placement_sched(L, N, sn.SN_SCHED_EAGER)
+        want = dict(zip(osch.offloaded_layers(L, N), osch.trigger_layers(L, N, osch.EAGER)))
+        assert {l: int(trig[l]) for l in range(L) if off[l]} == want
+        t_o, stalls = osch.timeline(tc, tx, N, osch.EAGER)
+        assert sn.sn_timeline_sched(tc, tx, N, sn.SN_SCHED_EAGER) == (t_o, sum(stalls))
+        assert sn.sn_timeline_sched(tc, tx, N, sn.SN_SCHED_PAPER) == sn.sn_timeline(tc, tx, N)
+        assert t_o <= sn.sn_timeline(tc, tx, N)[0]
+        slo = rnd.randint(1, 3 * sum(tc))
+        want_n = osch.pick_interval(tc, tx, slo, L + 1, osch.EAGER)
+        try:
+            got_n = sn.sn_pick_interval_from_times_sched(tc, tx, slo, L + 1, sn.SN_SCHED_EAGER)
+        except sn.SnError as e:
+            assert e.code == sn.SN_E_INFEASIBLE
+            got_n = None
+        assert got_n == want_n
+    with pytest.raises(sn.SnError):
+        sn.sn_timeline_sched([1], [1], 1, 2)

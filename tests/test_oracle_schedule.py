@@ -140,6 +140,71 @@ def test_timeline_equals_independent_event_simulation():
         assert osch.timeline(tc, tx, N)[0] == _two_queue_simulation(tc, tx, N), (tc, tx, N)
 
 
+def _slot_simulation(tc, tx, N):
+    """The eager schedule from its own definition, without trigger layers: two staging slots; the
+    k-th offloaded layer uses slot k % 2; its load starts as soon as the copy stream is free and the
+    slot is (i.e. the layer that last used it has been computed); loads are served in layer order."""
+    L = len(tc)
+    off = [l for l in range(L) if 1 <= N <= L and (l + 1) % N == 0]
+    load_end = {}
+    layer_end = {}
+    t = 0
+    copy_free = 0
+    k_next = 0                      # next load to hand to the copy stream
+
+    def issue_ready_loads(now):
+        nonlocal k_next, copy_free
+        while k_next < len(off):
+            user = off[k_next - 2] if k_next >= 2 else None       # previous user of this slot
+            if user is not None and user not in layer_end:
+                break
+            slot_free = 0 if user is None else layer_end[user]
+            if slot_free > now:
+                break
+            start = max(copy_free, slot_free)
+            copy_free = start + tx[off[k_next]]
+            load_end[off[k_next]] = copy_free
+            k_next += 1
+
+    issue_ready_loads(0)
+    for l in range(L):
+        if l in off:
+            t = max(t, load_end[l])
+        t += tc[l]
+        layer_end[l] = t
+        issue_ready_loads(t)
+    return t
+
+
+def test_eager_schedule_hand_worked_and_independent_simulation():
+    # L = 4, N = 2, compute 10 per layer, transfer 25: layers 1 and 3 are on the host.
+    # Paper's schedule: load(1) 0-25; layer 0 0-10; stall to 25; layer 1 25-35; load(3) issued at 35, 35-60;
+    #   layer 2 35-45; stall to 60; layer 3 60-70.
+    # Eager: both slots are free at the start: load(1) 0-25, load(3) 25-50; layer 1 25-35; layer 2 35-45;
+    #   stall to 50; layer 3 50-60.
+    tc, tx = [10] * 4, [25] * 4
+    assert osch.timeline(tc, tx, 2) == (70, [15, 15])
+    assert osch.timeline(tc, tx, 2, osch.EAGER) == (60, [15, 5])
+    assert osch.trigger_layers(8, 2, osch.EAGER) == [0, 0, 2, 4] and osch.trigger_layers(8, 2) == [0, 2, 4, 6]
+    assert osch.trigger_layers(6, 1, osch.EAGER) == osch.trigger_layers(6, 1)         # N = 1: already one layer ahead
+    rnd = random.Random(21)
+    for _ in range(3000):
+        L = rnd.randint(1, 24)
+        tc = [rnd.randint(1, 100) for _ in range(L)]
+        tx = [rnd.randint(0, 500) for _ in range(L)]
+        N = rnd.randint(1, L + 1)
+        eager = osch.timeline(tc, tx, N, osch.EAGER)[0]
+        assert eager == _slot_simulation(tc, tx, N), (tc, tx, N)
+        paper = osch.timeline(tc, tx, N)[0]
+        assert eager <= paper                                   # issuing earlier never hurts
+        if L // N <= 1 or N == 1 or N > L:
+            assert eager == paper                               # nothing to issue earlier
+    # saturated copy stream, uniform times, N | L, x >= N c: the loads run back to back from t = 0 and
+    # the last layer computes after the last load: T = K x + c  (the regime of the analyzer's closed form)
+    for L, N, c, x in [(8, 2, 10, 25), (12, 3, 7, 40), (32, 4, 5, 21), (6, 2, 3, 6)]:
+        assert osch.timeline([c] * L, [x] * L, N, osch.EAGER)[0] == (L // N) * x + c
+
+
 def test_picker_is_min_feasible_and_monotone_in_slo():
     rnd = random.Random(3)
     for _ in range(400):
