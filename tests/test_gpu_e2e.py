@@ -445,3 +445,77 @@ def test_full_size_config2_offloaded_equals_resident_and_sampled_rows_match_orac
     cache = ofw.new_cache(1, 1, s.n_kv_heads, s.head_dim)
     want = ofw.step(s.as_dict(), [lw], [synth.widen(prompt[:40], s.dtype)], cache, kv_dtype=KV_STORAGE)[0]
     assert_close(outs[8][0][:40], want, s.dtype, "c2 full size, first layer, sampled rows")
+
+
+def _llama_layer0_rows(s, layer0, x_seq, rows):
+    """Oracle value of the first layer's output for selected token rows of ONE sequence (RMSNorm / RoPE /
+    SwiGLU family).  Keys and values are needed for every earlier position, everything else only for the
+    selected rows, so the pieces of the oracle are applied to exactly those."""
+    Hq, Hkv, d, eps = s.n_q_heads, s.n_kv_heads, s.head_dim, s.norm_eps
+    P = x_seq.shape[0]
+    wd = lambda name: synth.widen(layer0[name], s.dtype)
+    u = ofw.rms_norm(x_seq, wd("n1g"), eps)
+    wqkv = wd("wqkv")
+    kv = u @ wqkv[Hq * d:].T
+    pos = np.arange(P)
+    k = ofw.rope(kv[:, :Hkv * d].reshape(P, Hkv, d), pos[:, None], s.rope_theta)
+    v = kv[:, Hkv * d:].reshape(P, Hkv, d)
+    K, V = ofw.round_to_storage(k, KV_STORAGE), ofw.round_to_storage(v, KV_STORAGE)
+    wq, wo, wg, wu, wdn, n2g = wqkv[:Hq * d], wd("wo"), wd("wg"), wd("wu"), wd("wd"), wd("n2g")
+    out = []
+    for r in rows:
+        q = ofw.rope((u[r] @ wq.T).reshape(1, Hq, d), np.array([[r]]), s.rope_theta)
+        a = ofw.causal_attention(q, K[:r + 1], V[:r + 1], r).reshape(1, Hq * d)
+        x1 = x_seq[r:r + 1] + a @ wo.T
+        u2 = ofw.rms_norm(x1, n2g, eps)
+        out.append(x1 + (ofw.silu(u2 @ wg.T) * (u2 @ wu.T)) @ wdn.T)
+    return np.concatenate(out, axis=0)
+
+
+def test_full_size_config5_layer_shape_and_batch():
+    """The Llama-2-70B-shaped configuration at its real per-layer shape and full batch: 64 sequences x 2048
+    prompt tokens = 131072 rows per prefill launch, GQA 64/8 heads, SwiGLU 28672, bf16 -- the launch
+    configuration of that workload -- with 3 layers instead of 80 (the 80-layer model is 137 GB; the
+    kernels do not depend on the layer count).  (i) offloaded (N = 2) and all-resident runs are
+    bit-identical for the prefill and two decode steps; (ii) with the output projections of layers 1, 2
+    zeroed the model is its first layer, which the oracle computes for sampled rows of sequence 0: early,
+    tile-boundary and last prompt positions (attention over up to 2048 keys) and both decode steps."""
+    import dataclasses
+    w = synth.workload("c5")
+    s = dataclasses.replace(w.shape, n_layers=3)
+    B, P = w.batch, 2048
+    rng = np.random.default_rng(51)
+    layer0 = synth.make_layer(s, 0, 0)
+    blob0 = synth.pack_blob(s, layer0)
+    dead = dict(layer0)
+    for name in ("wo", "wd"):
+        dead[name] = np.zeros_like(layer0[name])
+    blob_dead = synth.pack_blob(s, dead)
+    del dead
+    prompt = synth.to_bits(rng.standard_normal((B * P, s.hidden), dtype=np.float32), s.dtype)
+    table = synth.to_bits(rng.standard_normal((2, B, s.hidden), dtype=np.float32), s.dtype)
+    outs = {}
+    for N in (0, 2):
+        with Session(s, B, P + 4) as se:
+            for l in range(3):
+                sn.sn_set_layer_weights(se.ctx, l, blob0 if l == 0 else blob_dead)
+            se.place(N)
+            se.kv_reset([P + 4] * B)
+            pre, fpre = se.step([P] * B, True, prompt, want_f32=True)
+            d0, f0 = se.step([1] * B, False, table[0], want_f32=True)
+            d1, f1 = se.step([1] * B, False, table[1], want_f32=True)
+            st = se.stats()
+        assert st["n_offloaded"] == (1 if N else 0)
+        outs[N] = (pre, d0, d1, fpre[:P].copy(), f0[0:1].copy(), f1[0:1].copy())
+        del fpre
+    for a, b in zip(outs[0][:3], outs[2][:3]):
+        assert np.array_equal(a, b)
+    del blob0, blob_dead
+    # oracle: sequence 0 = rows 0..P-1 of the prompt, then its two decode tokens at positions P, P+1
+    x_seq = np.concatenate([synth.widen(prompt[:P], s.dtype), synth.widen(table[0, 0:1], s.dtype),
+                            synth.widen(table[1, 0:1], s.dtype)], axis=0)
+    rows = [0, 1, 63, 64, 1023, 2047, P, P + 1]
+    want = _llama_layer0_rows(s, layer0, x_seq, rows)
+    got_f = np.concatenate([outs[2][3][rows[:6]], outs[2][4], outs[2][5]], axis=0)
+    got_b = np.concatenate([outs[2][0][rows[:6]], outs[2][1][0:1], outs[2][2][0:1]], axis=0)
+    assert_close_f32(got_b, got_f, want, s.dtype, "c5 shape, full batch, first layer, sampled rows of sequence 0")
