@@ -277,9 +277,337 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
   }
 }
 
+
+// ---------------------------------------------------------------------------------
+// many-tile path: 192 tokens x 256 features per workgroup, 192 x 64 per wavefront
+// ---------------------------------------------------------------------------------
+// One workgroup (4 wavefronts, one per SIMD, 512 registers each) per CU; a wavefront keeps 4 x 12
+// accumulator tiles: 64 features x all 192 tokens, 48 MFMAs per 32-wide k step for 4 weight fragments of
+// its own and 12 activation fragments from LDS (112 flop per byte fetched, against 87 for 128 x 256).
+//   * weights of step t: global -> register set t % NB, requested NB - 1 steps ahead (no weight is
+//     fetched twice by a workgroup, none passes through LDS);
+//   * activations of step t: global -> LDS buffer t % NB directly (global_load_lds_dwordx4: lane l's
+//     16 bytes land at M0 + 16 l, which is exactly the B-operand tile order when lane l asks for
+//     token l % 16, k chunk l / 16), requested NB - 1 steps ahead, no registers involved; each fragment
+//     is re-read from LDS for the next step right after the four MFMAs that used it.
+// What makes a lone wavefront per SIMD work (each found by measurement):
+//   * memory requests are spread over the step -- one request, four MFMAs, one LDS read, twelve times --
+//     because a wavefront that queues its seven requests at once stalls behind them and nothing else
+//     feeds its matrix core (1450 -> 1150 clocks per step);
+//   * the direct-to-LDS loads are inline assembly, so that the compiler does not serialise every LDS
+//     read behind the newest of them; their completion is awaited by hand: loads complete in issue
+//     order, each step issues 3 of them followed by 4 weight loads per wavefront, so "the activations
+//     of step t + 2 have landed" is s_waitcnt vmcnt(4 + 7 * (NB - 3)) at the end of step t (every
+//     step issues its 7 requests, the last ones redundantly, so the count always holds).  The waits the
+//     compiler inserts for the weight registers count only its own loads and therefore wait for more
+//     than necessary -- never for less;
+//   * a bare s_barrier per step (no fence): it publishes the loads just awaited, and the buffer the
+//     next step overwrites was read two steps ago;
+//   * the epilogue fetches its bias values once per feature block (not per element: 20 -> 4 us per
+//     tile), transposes the tile through the idle operand ring and stores whole cache lines, and for
+//     the fp32 residual stream requests all its reads before using the first;
+//   * all tiles take the same time, so the first workgroup of each CU starts up to 3/4 of a tile late
+//     (see below), which spreads the epilogues' memory bursts over the other CUs' k loops.
+// Ring indices must be compile-time constants, hence the k loop is unrolled by the ring depth, which
+// must divide the number of k steps.  Token rows past M fetch row 0 and are never stored.
+// Measured at 32768 rows (MI355X): 0.97-1.11 PFLOP/s against 0.86-0.99 for the kernel above.
+// The 192 x 256 kernel runs one workgroup per CU, so it needs several rounds of tiles to amortise the
+// unevenness of the last round and its start-up stagger: measured break-even against the 128 x 256 kernel
+// (two workgroups per CU) in isolation is around four rounds of 256 tiles; inside an iteration, between
+// other kernels, it only pays from about eight.
+constexpr int kBigTileMinTiles = 2048;
+constexpr int kBigTileRing = 8;          // LDS buffers / weight register sets of the 192 x 256 kernel (look-ahead 7 k steps)
+constexpr int kBigTileFirstWave = 256;   // workgroups that start at once: one per CU
+constexpr int kBigTileTokenTiles = 12;  // 16-token tiles per workgroup (192 tokens): 4 x 12 accumulator tiles per wavefront
+
+template <int V>
+struct IC {
+  static constexpr int value = V;
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <class T, int EPI, int TI>   // TI: 16-token tiles per workgroup
+__global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
+    void* __restrict__ out, int M, int N, int K, int NT, int TT) {
+  constexpr int BM = TI * 16;             // tokens per workgroup
+  constexpr int XT = TI / 4;              // token tiles each wavefront stages per k step
+  constexpr int FJ = 4;                   // 16-feature blocks per wavefront
+  constexpr int NB = kBigTileRing;        // ring depth: LDS buffers and weight register sets
+  constexpr int D = NB - 1;               // look-ahead in k steps
+  constexpr int kTile = 64 * 8;           // elements of one 16 x 32 operand tile
+  static_assert(XT == 3 && FJ == 4 && D >= 3 && D <= 7, "the hand-written wait counts 3 + 4 loads per step");
+  __shared__ __attribute__((aligned(16))) uint16_t xs[NB][TI][kTile];   // 8 x 12 KiB
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int S = K >> 5;                      // k steps
+
+  int tn, tt;                                // XCD-aware numbering, as in gemm_tile_lds_kernel
+  {
+    const int id = blockIdx.x;
+    if (NT % 8 == 0) {
+      const int xcd = id & 7, j = id >> 3, band = NT >> 3;
+      tn = xcd * band + j % band;
+      tt = j / band;
+    } else {
+      tn = id % NT;
+      tt = id / NT;
+    }
+  }
+  // All tiles take the same time, so without help every CU would reach its epilogue (a burst of stores, for the
+  // residual epilogue a read-modify-write of 384 KiB) at the same moment, again and again, and the memory system
+  // would alternate between idle and overrun.  The first workgroup of each CU therefore starts up to three
+  // quarters of a tile late; later workgroups inherit the offset because a CU holds one workgroup at a time.
+  if (blockIdx.x < kBigTileFirstWave) {
+    const int quarters = (blockIdx.x >> 3) & 3;          // consecutive ids go to different XCDs: vary within an XCD
+    const int naps = quarters * (S / 28 + 1);            // one nap = 127 * 64 clocks; a tile is ~1150 clocks per k step + epilogue
+    for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
+  }
+  const int t0 = tt * BM;
+  const int nb0 = tn * 16 + wave * FJ;       // first of this wavefront's feature blocks
+  const uint16_t* wp = W + ((size_t)nb0 * S) * 512 + lane * 8;
+  const size_t wstride = (size_t)S * 512;
+
+  // activation staging: wavefront w fetches token tiles XT*w .. XT*w + XT - 1 of the workgroup's TI
+  const uint16_t* xg[XT];
+#pragma unroll
+  for (int i = 0; i < XT; ++i) {
+    const int row = t0 + (wave * XT + i) * 16 + (lane & 15);
+    xg[i] = X + (size_t)(row < M ? row : 0) * K + (lane >> 4) * 8;
+  }
+  // LDS byte address of this wavefront's first staging tile in buffer 0 (wave-uniform)
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&xs[0][wave * XT][0]);
+
+  f32x4 acc[FJ][TI];                         // [feature block][token tile]
+#pragma unroll
+  for (int j = 0; j < FJ; ++j)
+#pragma unroll
+    for (int i = 0; i < TI; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  u16x8 a[NB][FJ], bf[TI];
+  auto load_w = [&](auto set, int st) __attribute__((always_inline)) {
+    constexpr int R = decltype(set)::value;
+#pragma unroll
+    for (int j = 0; j < FJ; ++j) a[R][j] = *reinterpret_cast<const u16x8*>(wp + j * wstride + (size_t)st * 512);
+  };
+  auto dma_x = [&](auto buf, int st) __attribute__((always_inline)) {
+    constexpr int B = decltype(buf)::value;
+#pragma unroll
+    for (int i = 0; i < XT; ++i) {
+      const uint16_t* g = xg[i] + (size_t)st * 32;
+      const uint32_t m0 = lds0 + (uint32_t)((B * TI + i) * kTile * 2);
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory");
+    }
+  };
+  // k step st (st % NB == U)
+  auto step = [&](auto uc, auto, int st) __attribute__((always_inline)) {
+    constexpr int U = decltype(uc)::value;
+    constexpr int R = (U + D) % NB;           // ring slot being refilled
+    constexpr int BN = (U + 1) % NB;          // LDS buffer of the next step
+    const int ahead = st + D < S ? st + D : S - 1;
+    // One memory request, four MFMAs, one LDS read, twelve times over: a wavefront alone on its SIMD
+    // must never sit in a queue of its own requests while the matrix core runs dry.
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+      if (i < XT) {
+        const uint16_t* g = xg[i] + (size_t)ahead * 32;
+        const uint32_t m0 = lds0 + (uint32_t)((R * TI + i) * kTile * 2);
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory");
+      } else if (i < XT + FJ) {
+        a[R][i - XT] = *reinterpret_cast<const u16x8*>(wp + (i - XT) * wstride + (size_t)ahead * 512);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < FJ; ++j) acc[j][i] = mma16x16x32<T>(a[U][j], bf[i], acc[j][i]);
+      __builtin_amdgcn_sched_barrier(0);
+      bf[i] = *reinterpret_cast<const u16x8*>(&xs[BN][i][lane * 8]);   // next step's fragment; after the last step: stale, unused
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_vmcnt<4 + 7 * (D - 2)>();         // this wavefront's share of the activations of step st + 2 has landed
+    // Bare barrier (no fence): what it publishes are the direct-to-LDS loads just awaited, and the buffer
+    // the next step overwrites was read into registers two steps ago.  A fence would also wait for the
+    // fragment reads issued a moment ago, which are not needed before the next step.
+    asm volatile("s_barrier" ::: "memory");
+  };
+
+  // prologue: the first seven steps' operands, all awaited (one exposed latency per tile)
+  auto prologue = [&](auto uc) __attribute__((always_inline)) {
+    constexpr int U = decltype(uc)::value;
+    if (U < D) {
+      dma_x(IC<U>{}, U);
+      load_w(IC<U>{}, U);
+    }
+  };
+  prologue(IC<0>{});
+  prologue(IC<1>{});
+  prologue(IC<2>{});
+  if (D > 3) prologue(IC<3 % NB>{});
+  if (D > 4) prologue(IC<4 % NB>{});
+  if (D > 5) prologue(IC<5 % NB>{});
+  if (D > 6) prologue(IC<6 % NB>{});
+  wait_vmcnt<0>();
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TI; ++i) bf[i] = *reinterpret_cast<const u16x8*>(&xs[0][i][lane * 8]);
+
+  // S is a multiple of NB (the launcher sees to it).  Every step requests operands without a condition --
+  // the last D steps re-request the final step's (harmless: those ring slots are free) -- because the
+  // compiler's own waits for the weight registers are only as tight as what it knows was requested since.
+  for (int s = 0; s < S; s += NB) {
+    step(IC<0>{}, IC<1>{}, s);
+    step(IC<1>{}, IC<1>{}, s + 1);
+    step(IC<2>{}, IC<1>{}, s + 2);
+    step(IC<3>{}, IC<1>{}, s + 3);
+    if (NB > 4) step(IC<4 % NB>{}, IC<1>{}, s + 4);
+    if (NB > 5) step(IC<5 % NB>{}, IC<1>{}, s + 5);
+    if (NB > 6) step(IC<6 % NB>{}, IC<1>{}, s + 6);
+    if (NB > 7) step(IC<7 % NB>{}, IC<1>{}, s + 7);
+  }
+  wait_vmcnt<0>();   // the redundant requests of the last steps
+
+  const int nl = (lane >> 4) * 4;
+  if (EPI == EPI_RESID32) {
+    // fp32 read-modify-write of the residual stream, through the idle operand ring as well (see below):
+    // two halves of 96 tokens x 256 features x 4 bytes; 16-byte chunks swizzled by chunk ^ (token % 16);
+    // afterwards every thread adds 16 contiguous bytes into the stream, a token's 1 KiB row as whole lines.
+    static_assert(TI % 2 == 0 && (TI / 2) * 16 * 256 * 4 <= NB * TI * kTile * 2, "half the fp32 tile must fit the ring");
+    float* fb = reinterpret_cast<float*>(&xs[0][0][0]);
+    float bvr[FJ][4];
+#pragma unroll
+    for (int j = 0; j < FJ; ++j) {
+      u16x4 b4 = u16x4{0, 0, 0, 0};
+      if (bias) b4 = *reinterpret_cast<const u16x4*>(bias + (nb0 + j) * 16 + nl);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) bvr[j][r] = bias ? to_f32<T>(b4[r]) : 0.f;
+    }
+    const int q = threadIdx.x & 63, r0 = threadIdx.x >> 6;       // 16-byte chunk of the row, first row of this thread
+    float* xg0 = static_cast<float*>(out) + (size_t)tn * 256 + q * 4;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      __syncthreads();                                            // ring (or the previous half) no longer read
+#pragma unroll
+      for (int ii = 0; ii < TI / 2; ++ii) {
+        const int i = h * (TI / 2) + ii;
+        const int tok = ii * 16 + (lane & 15);
+#pragma unroll
+        for (int j = 0; j < FJ; ++j) {
+          f32x4 v = acc[j][i];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] += bvr[j][r];
+          const int c = wave * 16 + j * 4 + (lane >> 4);
+          *reinterpret_cast<f32x4*>(fb + (size_t)tok * 256 + ((c ^ (lane & 15)) << 2)) = v;
+        }
+      }
+      __syncthreads();
+      // all of this thread's stream reads are requested before the first is used (one latency, not 24)
+      constexpr int ROWS = (TI / 2) * 16 / 4;
+      f32x4 r[ROWS];
+#pragma unroll
+      for (int k = 0; k < ROWS; ++k) {
+        const int t = t0 + h * (TI / 2) * 16 + r0 + 4 * k;
+        r[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (t < M) r[k] = *reinterpret_cast<const f32x4*>(xg0 + (size_t)t * N);
+      }
+#pragma unroll
+      for (int k = 0; k < ROWS; ++k) {
+        const int tok = r0 + 4 * k;
+        const int t = t0 + h * (TI / 2) * 16 + tok;
+        r[k] += *reinterpret_cast<const f32x4*>(fb + (size_t)tok * 256 + ((q ^ (tok & 15)) << 2));
+        if (t < M) *reinterpret_cast<f32x4*>(xg0 + (size_t)t * N) = r[k];
+      }
+    }
+    return;
+  }
+  // 16-bit outputs.  A lane holds 4 consecutive features of one token per accumulator tile, so a direct
+  // store writes 32-byte pieces of cache lines (measured: ~20 us per tile, a quarter of the kernel).  The
+  // tile is therefore transposed through the now idle operand ring: [192 tokens][OW features], 8-byte chunks
+  // swizzled by chunk ^ (token % 16) so that the 16 tokens a store instruction covers hit 16 different
+  // bank pairs; then every thread moves 16 contiguous bytes and a token's row leaves as whole lines.
+  constexpr bool DUAL = EPI == EPI_SWIGLU16;
+  constexpr int OW = DUAL ? 128 : 256;                 // output features of this workgroup
+  static_assert(TI * 16 * OW * 2 <= NB * TI * kTile * 2, "output tile must fit the operand ring");
+  uint16_t* ob = &xs[0][0][0];
+  // this lane's bias values, fetched once (they depend on the feature block only, not on the token tile)
+  float bv[FJ][4];
+#pragma unroll
+  for (int j = 0; j < FJ; ++j) {
+    const int F = N >> 1;
+    const int n = DUAL ? ((nb0 + (j & ~1)) >> 1) * 16 + nl + ((j & 1) ? F : 0) : (nb0 + j) * 16 + nl;
+    u16x4 b4 = u16x4{0, 0, 0, 0};
+    if (bias) b4 = *reinterpret_cast<const u16x4*>(bias + n);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) bv[j][r] = bias ? to_f32<T>(b4[r]) : 0.f;
+  }
+  __syncthreads();                                     // every wavefront is done with the ring
+#pragma unroll
+  for (int i = 0; i < TI; ++i) {
+    const int tok = i * 16 + (lane & 15);
+#pragma unroll
+    for (int j = 0; j < FJ; j += (DUAL ? 2 : 1)) {
+      u16x4 o;
+      if (DUAL) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[r] = from_f32<T>(silu(acc[j][i][r] + bv[j][r]) * (acc[j + 1][i][r] + bv[j + 1][r]));
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float v = acc[j][i][r] + bv[j][r];
+          if (EPI == EPI_GELU16) v = gelu_erf(v);
+          o[r] = from_f32<T>(v);
+        }
+      }
+      const int c = DUAL ? wave * 8 + (j >> 1) * 4 + (lane >> 4) : wave * 16 + j * 4 + (lane >> 4);   // 8-byte chunk in the row
+      *reinterpret_cast<u16x4*>(ob + (size_t)tok * OW + ((c ^ (lane & 15)) << 2)) = o;
+    }
+  }
+  __syncthreads();
+  constexpr int PIECES = OW / 8;                       // 16-byte pieces per token row
+  constexpr int RPP = 256 / PIECES;                    // token rows per pass of the workgroup
+  const int q = threadIdx.x % PIECES, r0 = threadIdx.x / PIECES;
+  const int ON = DUAL ? N >> 1 : N;
+  uint16_t* og = static_cast<uint16_t*>(out) + (size_t)tn * OW + q * 8;
+#pragma unroll 4
+  for (int tok = r0; tok < BM; tok += RPP) {
+    const int t = tok & 15;
+    u16x8 v = *reinterpret_cast<const u16x8*>(ob + (size_t)tok * OW + ((q ^ (t >> 1)) << 3));
+    if (t & 1) v = u16x8{v[4], v[5], v[6], v[7], v[0], v[1], v[2], v[3]};
+    if (t0 + tok < M) *reinterpret_cast<u16x8*>(og + (size_t)(t0 + tok) * ON) = v;
+  }
+}
+
 template <class T>
 static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out, int M,
                            int N, int K, hipStream_t st) {
+  constexpr int TI = kBigTileTokenTiles;
+  if (N % 256 == 0 && K % (32 * kBigTileRing) == 0 &&
+      (int64_t)(N / 256) * ((M + TI * 16 - 1) / (TI * 16)) >= kBigTileMinTiles) {
+    const int NT = N / 256, TT = (M + TI * 16 - 1) / (TI * 16);
+    dim3 grid(NT * TT), block(256);
+    switch (epi) {
+      case EPI_STORE16:
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_STORE16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        break;
+      case EPI_GELU16:
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_GELU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        break;
+      case EPI_RESID32:
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_RESID32, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        break;
+      case EPI_SWIGLU16:
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_SWIGLU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        break;
+      default:
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   if (N % 256 == 0 && K % 64 == 0) {
     const int NT = N / 256, TT = (M + 127) / 128;
     dim3 grid(NT * TT), block(256);

@@ -114,12 +114,12 @@ def test_gemm_tile(dtype, epi):
 
 @pytest.mark.parametrize("dtype,epi", [("f16", 0), ("f16", 1), ("bf16", 2), ("bf16", 3), ("f16", 3)])
 def test_gemm_tile_large_m(dtype, epi):
-    """The prefill GEMM at more than a thousand token rows: several token tiles with a ragged last one,
-    one and several feature tiles, the XCD-banded numbering (8 feature tiles), K with and without the
-    64-wide staging step of the LDS kernel."""
+    """With at least 2048 tiles (and K a multiple of 256) the prefill GEMM uses its 192-token x 256-feature
+    workgroup tile: direct-to-LDS activation loads, an 8-deep operand ring (one, two and three trips of the
+    unrolled k loop), outputs transposed through LDS, a ragged last token tile, the XCD-banded numbering
+    (32 feature tiles) and the plain one (33).  The last case stays below the threshold (128 x 256 kernel)."""
     wide = 2 if epi == K.EPI_SWIGLU16 else 1      # SwiGLU: N counts output features, the weight has 2 N rows
-    for i, (M, Nw, Kd) in enumerate([(1100, 256, 256), (1024, 512, 512), (1153, 256, 768), (1030, 2048, 256),
-                                     (1250, 256, 224), (1030, 256, 64)]):
+    for i, (M, Nw, Kd) in enumerate([(12400, 8192, 256), (12300, 8448, 512), (12481, 8192, 768), (1250, 256, 224)]):
         _gemm_case(dtype, K.PATH_TILE, epi, M, Nw // wide, Kd, bias=(i % 2 == 0), seed=50 + i)
 
 
