@@ -231,6 +231,40 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
   }
 
   const int nl = (lane >> 4) * 4;
+  // this lane's bias values depend on the feature block only: fetched once, not once per element
+  // (128 two-byte loads per lane in the epilogue cost more than the stores)
+  float bv[4][4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int n = EPI == EPI_SWIGLU16 ? ((nb0 + (j & ~1)) >> 1) * 16 + nl + ((j & 1) ? (N >> 1) : 0) : (nb0 + j) * 16 + nl;
+    u16x4 b4 = u16x4{0, 0, 0, 0};
+    if (bias) b4 = *reinterpret_cast<const u16x4*>(bias + n);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) bv[j][r] = bias ? to_f32<T>(b4[r]) : 0.f;
+  }
+  if (EPI == EPI_RESID32) {
+    // fp32 read-modify-write of the residual stream: all reads of a feature block are requested before
+    // the first is used
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = (nb0 + j) * 16 + nl;
+      f32x4 r[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int t = t0 + i * 16 + (lane & 15);
+        r[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (t < M) r[i] = *reinterpret_cast<const f32x4*>(static_cast<float*>(out) + (size_t)t * N + n);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int t = t0 + i * 16 + (lane & 15);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) r[i][q] += acc[j][i][q] + bv[j][q];
+        if (t < M) *reinterpret_cast<f32x4*>(static_cast<float*>(out) + (size_t)t * N + n) = r[i];
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int t = t0 + i * 16 + (lane & 15);
@@ -242,36 +276,21 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
         const int n = ((nb0 + j) >> 1) * 16 + nl;
         u16x4 o;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float g = acc[j][i][r], u = acc[j + 1][i][r];
-          if (bias) {
-            g += to_f32<T>(bias[n + r]);
-            u += to_f32<T>(bias[F + n + r]);
-          }
-          o[r] = from_f32<T>(silu(g) * u);
-        }
+        for (int r = 0; r < 4; ++r) o[r] = from_f32<T>(silu(acc[j][i][r] + bv[j][r]) * (acc[j + 1][i][r] + bv[j + 1][r]));
         *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + (size_t)t * F + n) = o;
       }
     } else {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int n = (nb0 + j) * 16 + nl;
-        if (EPI == EPI_RESID32) {
-          float* xr = static_cast<float*>(out) + (size_t)t * N + n;
-          f32x4 r = *reinterpret_cast<const f32x4*>(xr);
+        u16x4 o;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) r[q] += acc[j][i][q] + (bias ? to_f32<T>(bias[n + q]) : 0.f);
-          *reinterpret_cast<f32x4*>(xr) = r;
-        } else {
-          u16x4 o;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            float v = acc[j][i][q] + (bias ? to_f32<T>(bias[n + q]) : 0.f);
-            if (EPI == EPI_GELU16) v = gelu_erf(v);
-            o[q] = from_f32<T>(v);
-          }
-          *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + (size_t)t * N + n) = o;
+        for (int q = 0; q < 4; ++q) {
+          float v = acc[j][i][q] + bv[j][q];
+          if (EPI == EPI_GELU16) v = gelu_erf(v);
+          o[q] = from_f32<T>(v);
         }
+        *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + (size_t)t * N + n) = o;
       }
     }
   }
