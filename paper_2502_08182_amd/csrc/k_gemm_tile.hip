@@ -303,7 +303,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
 // One workgroup (4 wavefronts, one per SIMD, 512 registers each) per CU; a wavefront keeps 4 x 12
 // accumulator tiles: 64 features x all 192 tokens, 48 MFMAs per 32-wide k step for 4 weight fragments of
 // its own and 12 activation fragments from LDS (112 flop per byte fetched, against 87 for 128 x 256).
-//   * weights of step t: global -> register set t % NB, requested NB - 1 steps ahead (no weight is
+//   * weights of step t: global -> register set t % 4, requested three steps ahead (no weight is
 //     fetched twice by a workgroup, none passes through LDS);
 //   * activations of step t: global -> LDS buffer t % NB directly (global_load_lds_dwordx4: lane l's
 //     16 bytes land at M0 + 16 l, which is exactly the B-operand tile order when lane l asks for
@@ -315,11 +315,12 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
 //     feeds its matrix core (1450 -> 1150 clocks per step);
 //   * the direct-to-LDS loads are inline assembly, so that the compiler does not serialise every LDS
 //     read behind the newest of them; their completion is awaited by hand: loads complete in issue
-//     order, each step issues 3 of them followed by 4 weight loads per wavefront, so "the activations
+//     order, each step issues 3 of them and 4 weight loads per wavefront, so "the activations
 //     of step t + 2 have landed" is s_waitcnt vmcnt(4 + 7 * (NB - 3)) at the end of step t (every
 //     step issues its 7 requests, the last ones redundantly, so the count always holds).  The waits the
 //     compiler inserts for the weight registers count only its own loads and therefore wait for more
 //     than necessary -- never for less;
+//   * the MFMAs are inline assembly with the accumulator tied to its registers (see mma_inplace);
 //   * a bare s_barrier per step (no fence): it publishes the loads just awaited, and the buffer the
 //     next step overwrites was read two steps ago;
 //   * the epilogue fetches its bias values once per feature block (not per element: 20 -> 4 us per
@@ -336,6 +337,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
 // other kernels, it only pays from about eight.
 constexpr int kBigTileMinTiles = 2048;
 constexpr int kBigTileRing = 8;          // LDS buffers / weight register sets of the 192 x 256 kernel (look-ahead 7 k steps)
+constexpr int kBigTileWeightRing = 4;    // weight register sets of the 192 x 256 kernel (look-ahead 3 k steps)
 constexpr int kBigTileFirstWave = 256;   // workgroups that start at once: one per CU
 constexpr int kBigTileTokenTiles = 12;  // 16-token tiles per workgroup (192 tokens): 4 x 12 accumulator tiles per wavefront
 
@@ -343,6 +345,23 @@ template <int V>
 struct IC {
   static constexpr int value = V;
 };
+
+// In-place MFMA (accumulator tied to its registers).  With the builtin, the register allocator gives a
+// loop-carried accumulator different registers at the top and at the bottom of the unrolled k loop and
+// repairs that with ~190 accumulator moves per trip; a tied operand leaves it no such freedom.  The compiler
+// cannot see inside: operands come from loads (it still inserts their waits), an accumulator is touched once
+// per k step (48 MFMAs apart), and the accumulators are first read long after the last MFMA (a counter
+// wait, a barrier and the bias loads come first), so no matrix-core hazard needs a hand-placed wait state.
+template <class T>
+__device__ __forceinline__ void mma_inplace(f32x4& c, const u16x8& a, const u16x8& b);
+template <>
+__device__ __forceinline__ void mma_inplace<F16>(f32x4& c, const u16x8& a, const u16x8& b) {
+  asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+template <>
+__device__ __forceinline__ void mma_inplace<BF16>(f32x4& c, const u16x8& a, const u16x8& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -410,7 +429,9 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
 #pragma unroll
     for (int i = 0; i < TI; ++i) acc[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  u16x8 a[NB][FJ], bf[TI];
+  constexpr int NW = kBigTileWeightRing;   // weight register sets (look-ahead NW - 1 steps)
+  static_assert(NB % NW == 0, "the unrolled loop must bring both rings back to slot 0");
+  u16x8 a[NW][FJ], bf[TI];
   auto load_w = [&](auto set, int st) __attribute__((always_inline)) {
     constexpr int R = decltype(set)::value;
 #pragma unroll
@@ -428,9 +449,11 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
   // k step st (st % NB == U)
   auto step = [&](auto uc, auto, int st) __attribute__((always_inline)) {
     constexpr int U = decltype(uc)::value;
-    constexpr int R = (U + D) % NB;           // ring slot being refilled
+    constexpr int R = (U + D) % NB;           // LDS ring slot being refilled
+    constexpr int RW = (U + NW - 1) % NW;     // weight register set being refilled
     constexpr int BN = (U + 1) % NB;          // LDS buffer of the next step
     const int ahead = st + D < S ? st + D : S - 1;
+    const int ahead_w = st + NW - 1 < S ? st + NW - 1 : S - 1;
     // One memory request, four MFMAs, one LDS read, twelve times over: a wavefront alone on its SIMD
     // must never sit in a queue of its own requests while the matrix core runs dry.
 #pragma unroll
@@ -440,11 +463,11 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
         const uint32_t m0 = lds0 + (uint32_t)((R * TI + i) * kTile * 2);
         asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory");
       } else if (i < XT + FJ) {
-        a[R][i - XT] = *reinterpret_cast<const u16x8*>(wp + (i - XT) * wstride + (size_t)ahead * 512);
+        a[RW][i - XT] = *reinterpret_cast<const u16x8*>(wp + (i - XT) * wstride + (size_t)ahead_w * 512);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int j = 0; j < FJ; ++j) acc[j][i] = mma16x16x32<T>(a[U][j], bf[i], acc[j][i]);
+      for (int j = 0; j < FJ; ++j) mma_inplace<T>(acc[j][i], a[U % NW][j], bf[i]);
       __builtin_amdgcn_sched_barrier(0);
       bf[i] = *reinterpret_cast<const u16x8*>(&xs[BN][i][lane * 8]);   // next step's fragment; after the last step: stale, unused
       __builtin_amdgcn_sched_barrier(0);
@@ -459,10 +482,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
   // prologue: the first seven steps' operands, all awaited (one exposed latency per tile)
   auto prologue = [&](auto uc) __attribute__((always_inline)) {
     constexpr int U = decltype(uc)::value;
-    if (U < D) {
-      dma_x(IC<U>{}, U);
-      load_w(IC<U>{}, U);
-    }
+    if (U < D) dma_x(IC<U>{}, U);
+    if (U < NW - 1) load_w(IC<U % NW>{}, U);
   };
   prologue(IC<0>{});
   prologue(IC<1>{});
