@@ -269,7 +269,7 @@ hipError_t launch_cast_out_fold(int dtype, int bias_dtype, float* x32, void* out
 
 // ---------------------------------------------------------------------------------
 // Rotary embedding (pairs i, i + d/2; angle = position * inv_freq[i]) on q and k, and
-// append of the new k, v rows to the KV slice.  One thread per (token, head slot, pair).
+// append of the new k, v rows to the KV slice.  One thread per (token, head slot, 8 pairs).
 // KVR is the value type of the cache: k and v are rounded to KVR and then stored in the
 // container type T (a bfloat16-valued cache lives in float16 containers, which hold
 // every bfloat16 value of moderate magnitude exactly).
@@ -279,35 +279,44 @@ __global__ __launch_bounds__(256) void rope_append_kernel(
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ kv,
     uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int Tn, int Hq, int Hkv, int d,
     int rope) {
+  // one thread per (token, head slot, 8 pairs): 16 bytes from each half of the head
   const int half = d >> 1;
+  const int chunks = half >> 3;
   const int slots = Hq + 2 * Hkv;
-  const size_t total = (size_t)Tn * slots * half;
+  const size_t total = (size_t)Tn * slots * chunks;
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
-  const int i = (int)(idx % half);
-  const int hs = (int)((idx / half) % slots);
-  const int t = (int)(idx / ((size_t)half * slots));
+  const int i0 = (int)(idx % chunks) * 8;
+  const int hs = (int)((idx / chunks) % slots);
+  const int t = (int)(idx / ((size_t)chunks * slots));
   uint16_t* row = qkv + ((size_t)t * slots + hs) * d;
-  float a = to_f32<T>(row[i]), b = to_f32<T>(row[i + half]);
+  const u16x8 va = *reinterpret_cast<const u16x8*>(row + i0);
+  const u16x8 vb = *reinterpret_cast<const u16x8*>(row + i0 + half);
   const int pos = tok_pos[t];
-  if (rope && hs < Hq + Hkv) {
-    float sn_, cs_;
-    sincosf((float)pos * inv_freq[i], &sn_, &cs_);
-    const float ra = a * cs_ - b * sn_;
-    const float rb = a * sn_ + b * cs_;
-    a = ra;
-    b = rb;
-  }
-  if (hs >= Hq) {
-    a = to_f32<KVR>(from_f32<KVR>(a));
-    b = to_f32<KVR>(from_f32<KVR>(b));
-  }
-  const uint16_t oa = from_f32<T>(a), ob = from_f32<T>(b);
-  if (hs < Hq) {
-    if (rope) {
-      row[i] = oa;
-      row[i + half] = ob;
+  const bool is_q = hs < Hq;
+  if (is_q && !rope) return;                       // q stays as the projection wrote it
+  u16x8 oa, ob;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float a = to_f32<T>(va[e]), b = to_f32<T>(vb[e]);
+    if (rope && hs < Hq + Hkv) {
+      float sn_, cs_;
+      sincosf((float)pos * inv_freq[i0 + e], &sn_, &cs_);
+      const float ra = a * cs_ - b * sn_;
+      const float rb = a * sn_ + b * cs_;
+      a = ra;
+      b = rb;
     }
+    if (!is_q) {
+      a = to_f32<KVR>(from_f32<KVR>(a));
+      b = to_f32<KVR>(from_f32<KVR>(b));
+    }
+    oa[e] = from_f32<T>(a);
+    ob[e] = from_f32<T>(b);
+  }
+  if (is_q) {
+    *reinterpret_cast<u16x8*>(row + i0) = oa;
+    *reinterpret_cast<u16x8*>(row + i0 + half) = ob;
     return;
   }
   const int s = tok_seq[t];
@@ -315,18 +324,19 @@ __global__ __launch_bounds__(256) void rope_append_kernel(
   const bool is_v = hs >= Hq + Hkv;
   const int g = is_v ? hs - Hq - Hkv : hs - Hq;
   const size_t off = (size_t)kv_off[s] * 2 * Hkv * d + ((size_t)(g * 2 + (is_v ? 1 : 0)) * c + pos) * d;
-  kv[off + i] = oa;
-  kv[off + i + half] = ob;
+  *reinterpret_cast<u16x8*>(kv + off + i0) = oa;
+  *reinterpret_cast<u16x8*>(kv + off + i0 + half) = ob;
   if (mirror) {
-    mirror[off + i] = oa;
-    mirror[off + i + half] = ob;
+    *reinterpret_cast<u16x8*>(mirror + off + i0) = oa;
+    *reinterpret_cast<u16x8*>(mirror + off + i0 + half) = ob;
   }
 }
 
 hipError_t launch_rope_append(int dtype, int kv_value_dtype, void* qkv16, const StepIndex& ix, void* kv,
                               void* mirror, const float* inv_freq, int Tn, int Hq, int Hkv, int d, int rope,
                               hipStream_t st) {
-  const size_t total = (size_t)Tn * (Hq + 2 * Hkv) * (d / 2);
+  if (d % 16) return hipErrorInvalidValue;          // 8 pairs (16 bytes of each half) per thread
+  const size_t total = (size_t)Tn * (Hq + 2 * Hkv) * (d / 16);
   if (total == 0) return hipSuccess;
   const unsigned grid = (unsigned)((total + 255) / 256);
 #define SN_ROPE(TT, RR)                                                                                     \
