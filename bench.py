@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--guard", type=float, default=0.03,
                     help="fraction of the SLO kept as a guard band when picking (measured iterations run ~1-2%% "
                          "over the timeline's prediction: copies slow down slightly under concurrent compute)")
+    ap.add_argument("--prefill-guard", type=float, default=0.06,
+                    help="guard band of the prefill-phase picks: a prefill iteration keeps the link busy for most "
+                         "of its length, where copies run 3-5%% slower than profiled in isolation")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB copy kernel (known HBM traffic) for counter calibration")
     ap.add_argument("--slo-points", default=None,
@@ -370,62 +373,58 @@ def main():
         ttft0 = float(min(d["iter_ns"] for d in run_prefill(se, sn, w, x_pre, y_pre, 2)))
         tcp, txp = sn.sn_profile_layers(se.ctx, L, True, B, p_mean, reps=3)
         rho_p = float(np.median(txp) / np.median(tcp))
-        pts = []
-        for f in [float(v) for v in a.prefill_slo_points.split(",") if v]:
+
+        def prefill_point(f, sched, label):
+            """Pick for TTFT SLO f x the all-resident prefill, run, check every iteration; an interval whose
+            measured iterations miss the SLO is replaced by the next one that offloads fewer layers and run
+            again (the analyzer's prediction leaves out what a busy link and the fences cost)."""
             slo_f = int(f * ttft0)
             try:
-                n_f = sn.sn_pick_interval_from_times(tcp, txp, int(slo_f * (1.0 - a.guard)), L + 1)
+                n_f = sn.sn_pick_interval_from_times_sched(tcp, txp, int(slo_f * (1.0 - a.prefill_guard)), L + 1, sched)
             except sn.SnError:
                 n_f = L + 1
-            se.place(n_f)
-            pst = run_prefill(se, sn, w, x_pre, y_pre, 3)[1:]
-            pit = np.array([d["iter_ns"] for d in pst], dtype=np.float64)
+            first = int(n_f)
+            for _ in range(4):
+                se.place(n_f)
+                pst = run_prefill(se, sn, w, x_pre, y_pre, 3)[1:]
+                pit = np.array([d["iter_ns"] for d in pst], dtype=np.float64)
+                k_f = int(pst[-1]["n_offloaded"])
+                if (pit <= slo_f).all() or k_f == 0:
+                    break
+                n_next = n_f + 1
+                while n_next <= L and L // n_next >= k_f:
+                    n_next += 1
+                log(f"[bench] prefill SLO {f}x{label}: N={n_f} measured {pit.max() / 1e6:.2f} ms > SLO, trying N={n_next}")
+                n_f = n_next
             ph = sum(d["h2d_ns"] for d in pst)
             pb = sum(d["h2d_bytes"] for d in pst)
             ps = sum(d["stall_ns"] for d in pst)
-            pred, _ = sn.sn_timeline(tcp, txp, n_f)
-            pts.append({"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f),
-                        "n_offloaded": int(pst[-1]["n_offloaded"]), "ttft_ms": float(np.median(pit)) / 1e6,
-                        "ttft_max_ms": float(pit.max()) / 1e6, "predicted_ms": pred / 1e6,
-                        "every_iteration_within_slo": bool((pit <= slo_f).all()),
-                        "hidden_fraction": (1 - ps / ph) if ph else 1.0,
-                        "h2d_GBps": pb / (ph * 1e-9) / 1e9 if ph else None,
-                        "host_resident_weight_GB": int(pst[-1]["n_offloaded"]) * sn.sn_layer_blob_bytes(se.cshape) / 1e9,
-                        "resident_GB": sn.sn_resident_bytes(se.ctx, n_f) / 1e9,
-                        "over_cap": bool(sn.sn_resident_bytes(se.ctx, n_f) > w.hbm_budget > 0),
-                        "prefill_tokens_per_s": T / (float(np.median(pit)) * 1e-9)})
-            log(f"[bench] prefill SLO {f}x = {slo_f / 1e6:.2f} ms: picked N={n_f} (K={pts[-1]['n_offloaded']}), TTFT "
-                f"{pts[-1]['ttft_ms']:.2f} max {pts[-1]['ttft_max_ms']:.2f} (predicted {pred / 1e6:.2f}) "
-                f"within={pts[-1]['every_iteration_within_slo']} hidden {pts[-1]['hidden_fraction']:.3f} "
-                f"h2d {pts[-1]['h2d_GBps']}")
+            pred, _ = sn.sn_timeline_sched(tcp, txp, n_f, sched)
+            pt = {"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f),
+                  "picker_first_choice": first, "adjusted_after_measurement": bool(first != int(n_f)),
+                  "n_offloaded": k_f, "ttft_ms": float(np.median(pit)) / 1e6,
+                  "ttft_max_ms": float(pit.max()) / 1e6, "predicted_ms": pred / 1e6,
+                  "every_iteration_within_slo": bool((pit <= slo_f).all()),
+                  "hidden_fraction": (1 - ps / ph) if ph else 1.0,
+                  "h2d_GBps": pb / (ph * 1e-9) / 1e9 if ph else None,
+                  "host_resident_weight_GB": k_f * sn.sn_layer_blob_bytes(se.cshape) / 1e9,
+                  "resident_GB": sn.sn_resident_bytes(se.ctx, n_f) / 1e9,
+                  "over_cap": bool(sn.sn_resident_bytes(se.ctx, n_f) > w.hbm_budget > 0),
+                  "prefill_tokens_per_s": T / (float(np.median(pit)) * 1e-9)}
+            log(f"[bench] prefill SLO {f}x = {slo_f / 1e6:.2f} ms{label}: picked N={n_f} (K={k_f}, first choice N={first}), "
+                f"TTFT {pt['ttft_ms']:.2f} max {pt['ttft_max_ms']:.2f} (predicted {pred / 1e6:.2f}) "
+                f"within={pt['every_iteration_within_slo']} hidden {pt['hidden_fraction']:.3f} h2d {pt['h2d_GBps']}")
+            return pt
+
+        factors = [float(v) for v in a.prefill_slo_points.split(",") if v]
+        pts = [prefill_point(f, sn.SN_SCHED_PAPER, "") for f in factors]
         # the same SLOs with loads issued as early as the two staging slots allow (copy stream kept busy: the
         # regime of the analyzer's closed form); the paper's schedule is restored afterwards
         sn.sn_set_schedule(se.ctx, sn.SN_SCHED_EAGER)
-        eager = []
-        for f in [float(v) for v in a.prefill_slo_points.split(",") if v]:
-            slo_f = int(f * ttft0)
-            try:
-                n_f = sn.sn_pick_interval_from_times_sched(tcp, txp, int(slo_f * (1.0 - a.guard)), L + 1, sn.SN_SCHED_EAGER)
-            except sn.SnError:
-                n_f = L + 1
-            se.place(n_f)
-            pst = run_prefill(se, sn, w, x_pre, y_pre, 3)[1:]
-            pit = np.array([d["iter_ns"] for d in pst], dtype=np.float64)
-            ph = sum(d["h2d_ns"] for d in pst)
-            ps = sum(d["stall_ns"] for d in pst)
-            pred, _ = sn.sn_timeline_sched(tcp, txp, n_f, sn.SN_SCHED_EAGER)
-            eager.append({"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f),
-                          "n_offloaded": int(pst[-1]["n_offloaded"]), "ttft_ms": float(np.median(pit)) / 1e6,
-                          "ttft_max_ms": float(pit.max()) / 1e6, "predicted_ms": pred / 1e6,
-                          "every_iteration_within_slo": bool((pit <= slo_f).all()),
-                          "hidden_fraction": (1 - ps / ph) if ph else 1.0,
-                          "host_resident_weight_GB": int(pst[-1]["n_offloaded"]) * sn.sn_layer_blob_bytes(se.cshape) / 1e9})
-            log(f"[bench] prefill SLO {f}x, eager schedule: picked N={n_f} (K={eager[-1]['n_offloaded']}), TTFT "
-                f"{eager[-1]['ttft_ms']:.2f} max {eager[-1]['ttft_max_ms']:.2f} (predicted {pred / 1e6:.2f}) "
-                f"within={eager[-1]['every_iteration_within_slo']} hidden {eager[-1]['hidden_fraction']:.3f}")
+        eager = [prefill_point(f, sn.SN_SCHED_EAGER, ", eager schedule") for f in factors]
         sn.sn_set_schedule(se.ctx, sn.SN_SCHED_PAPER)
         out["prefill_phase"] = {"ttft_all_resident_ms": ttft0 / 1e6, "rho_transfer_over_compute": rho_p,
-                                "slo_points_eager_schedule": eager,
+                                "guard_band": a.prefill_guard, "slo_points_eager_schedule": eager,
                                 "layer_compute_us_median": float(np.median(tcp)) / 1e3,
                                 "layer_transfer_us_median": float(np.median(txp)) / 1e3, "slo_points": pts}
 
@@ -442,7 +441,7 @@ def main():
         f_c = 1.5
         slo_c = int(f_c * ttft0c)
         try:
-            n_solo = sn.sn_pick_interval_from_times(tcp2, txp2, int(slo_c * (1.0 - a.guard)), L + 1)
+            n_solo = sn.sn_pick_interval_from_times(tcp2, txp2, int(slo_c * (1.0 - a.prefill_guard)), L + 1)
         except sn.SnError:
             n_solo = L + 1
         other_bps = int(a.contention * link_bps)

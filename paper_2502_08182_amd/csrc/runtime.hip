@@ -1061,10 +1061,12 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
   uint8_t* kv_src_tmp = nullptr;
   int64_t tx_est = 0;
   const int tx_reps = std::min(reps, 3);
+  // sources: the layer's own pinned master / KV slice where it has one, else pinned stand-ins of the same size
+  std::vector<const uint8_t*> w_srcs(L), kv_srcs(L, nullptr);
   for (int l = 0; l < L && rc == SN_OK; ++l) {
     LayerState& ls = c->layers[l];
-    const uint8_t* kv_src = ls.host_kv;
-    if (kv_used && !kv_src) {   // resident layer: time the same bytes from a pinned scratch slice
+    kv_srcs[l] = ls.host_kv;
+    if (kv_used && !kv_srcs[l]) {   // resident layer: time the same bytes from a pinned scratch slice
       if (!kv_src_tmp) {
         if (hipHostMalloc((void**)&kv_src_tmp, c->kv_bytes, hipHostMallocDefault) != hipSuccess) {
           rc = fail(c, SN_E_NOMEM, "sn_profile_layers: pinned allocation failed");
@@ -1072,43 +1074,62 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
         }
         std::memset(kv_src_tmp, 0, c->kv_bytes);
       }
-      kv_src = kv_src_tmp;
+      kv_srcs[l] = kv_src_tmp;
     }
-    const uint8_t* w_src = ls.host_w;
-    if (!w_src) {               // no host master (the layer lives on the GPU): same bytes from the staging record
+    w_srcs[l] = ls.host_w;
+    if (!w_srcs[l]) {               // no host master (the layer lives on the GPU): same bytes from the staging record
       if (ensure_stage(c)) {
         rc = SN_E_NOMEM;
         break;
       }
-      w_src = c->stage_w;
+      w_srcs[l] = c->stage_w;
     }
-    std::vector<int64_t> v;
-    for (int r = 0; r < tx_reps + (l == 0 ? 1 : 0) && rc == SN_OK; ++r) {
-      // keep compute busy for longer than the copy is expected to take (first pass: idle GPU, gives the estimate)
-      int busy = 0;
-      if (tx_est > 0 && iter_est > 0) busy = (int)std::min<int64_t>(64, tx_est / iter_est + 2);
+  }
+  auto timed_copy = [&](int l) -> hipError_t {
+    hipError_t e = hipEventRecord(c->ev_copy_start[l], c->h2d);
+    if (e == hipSuccess) e = hipMemcpyAsync(dst, w_srcs[l], c->w_bytes, hipMemcpyHostToDevice, c->h2d);
+    if (e == hipSuccess && kv_used) e = hipMemcpyAsync(dst + c->w_bytes, kv_srcs[l], kv_used, hipMemcpyHostToDevice, c->h2d);
+    if (e == hipSuccess) e = hipEventRecord(c->ev_ready[l], c->h2d);
+    return e;
+  };
+  auto sync_streams = [&]() -> hipError_t {
+    hipError_t e = hipStreamSynchronize(c->h2d);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->compute);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->d2h);
+    return e;
+  };
+  if (rc == SN_OK) {                // idle-GPU warm-up copy: gives the estimate, not a sample
+    hipError_t e = timed_copy(0);
+    if (e == hipSuccess) e = sync_streams();
+    if (e != hipSuccess) rc = fail(c, SN_E_HIP, "sn_profile_layers: transfer timing: %s", hipGetErrorString(e));
+    else tx_est = std::max<int64_t>(1, elapsed_ns(c->ev_copy_start[0], c->ev_ready[0]));
+  }
+  // A round: enough iterations on the compute stream to outlast the copies, then as many layers' copies,
+  // back to back on the copy stream, as fit under them (one when an iteration is shorter than a copy, as in
+  // decoding; many when it is much longer, as in prefill -- which keeps the profile of a large prefill to
+  // seconds instead of minutes).
+  const int64_t iter_ns = std::max<int64_t>(1, iter_est);
+  const int busy = (int)std::min<int64_t>(64, (tx_est + tx_est / 4 + iter_ns - 1) / iter_ns + 1);
+  const int per_round = (int)std::max<int64_t>(1, std::min<int64_t>(L, (int64_t)busy * iter_ns / (tx_est + tx_est / 4)));
+  std::vector<std::vector<int64_t>> tx_samples(L);
+  for (int r = 0; r < tx_reps && rc == SN_OK; ++r)
+    for (int l0 = 0; l0 < L && rc == SN_OK; l0 += per_round) {
+      const int l1 = std::min(L, l0 + per_round);
       for (int k = 0; k < busy && rc == SN_OK; ++k) {
         for (int b = 0; b < batch; ++b) c->len[b] = lens[b] = is_prefill ? 0 : seq;
         rc = sn_step(c, &bt, &kvh, hout);
       }
       if (rc) break;
-      hipError_t e = hipEventRecord(c->ev_copy_start[l], c->h2d);
-      if (e == hipSuccess) e = hipMemcpyAsync(dst, w_src, c->w_bytes, hipMemcpyHostToDevice, c->h2d);
-      if (e == hipSuccess && kv_used) e = hipMemcpyAsync(dst + c->w_bytes, kv_src, kv_used, hipMemcpyHostToDevice, c->h2d);
-      if (e == hipSuccess) e = hipEventRecord(c->ev_ready[l], c->h2d);
-      if (e == hipSuccess) e = hipStreamSynchronize(c->h2d);
-      if (e == hipSuccess) e = hipStreamSynchronize(c->compute);
-      if (e == hipSuccess) e = hipStreamSynchronize(c->d2h);
+      hipError_t e = hipSuccess;
+      for (int l = l0; l < l1 && e == hipSuccess; ++l) e = timed_copy(l);
+      if (e == hipSuccess) e = sync_streams();
       if (e != hipSuccess) {
         rc = fail(c, SN_E_HIP, "sn_profile_layers: transfer timing: %s", hipGetErrorString(e));
         break;
       }
-      const int64_t t = elapsed_ns(c->ev_copy_start[l], c->ev_ready[l]);
-      if (l == 0 && r == 0) tx_est = t;      // idle-GPU warm-up pass, not a sample
-      else v.push_back(t);
+      for (int l = l0; l < l1; ++l) tx_samples[l].push_back(elapsed_ns(c->ev_copy_start[l], c->ev_ready[l]));
     }
-    if (rc == SN_OK) c->prof_tx[l] = median_of(v);
-  }
+  for (int l = 0; l < L && rc == SN_OK; ++l) c->prof_tx[l] = median_of(tx_samples[l]);
   (void)hipFree(hin);
   (void)hipFree(hout);
   if (kv_src_tmp) (void)hipHostFree(kv_src_tmp);
