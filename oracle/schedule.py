@@ -50,7 +50,9 @@ def offloaded_layers(L: int, N: int) -> List[int]:
     return [l for l in range(L) if (l + 1) % N == 0]
 
 
-PAPER, EAGER = 0, 1     # when the load of an offloaded layer is issued
+PAPER, EAGER, CONTINUOUS = 0, 1, 2     # when the load of an offloaded layer is issued
+
+CONTINUOUS_ITERATIONS = 16              # iterations walked to reach the continuous schedule's steady state
 
 
 def trigger_layers(L: int, N: int, schedule: int = PAPER) -> List[int]:
@@ -61,7 +63,9 @@ def trigger_layers(L: int, N: int, schedule: int = PAPER) -> List[int]:
     offloaded layer is free as soon as the (k-2)-th has been computed, so its load is issued at
     the layer after that one (at the start of the iteration for the first two).  This keeps
     the copy stream busy back to back, the regime the analyzer's closed form (Sec. 4.4)
-    describes."""
+    describes.
+    CONTINUOUS: within an iteration the same as EAGER; in addition the loads do not stop at the
+    iteration boundary (see timeline_continuous)."""
     back = max(N - 1, 1) if schedule == PAPER else 2 * N - 1
     return [max(0, o - back) for o in offloaded_layers(L, N)]
 
@@ -76,6 +80,9 @@ def timeline(tc: Sequence[int], tx: Sequence[int], N: int, schedule: int = PAPER
 
     tc[l]: compute time of layer l; tx[l]: host-to-GPU transfer time of layer l's state.
     """
+    if schedule == CONTINUOUS:
+        times, stalls = timeline_continuous(tc, tx, N, CONTINUOUS_ITERATIONS)
+        return max(times[-2:]), stalls
     L = len(tc)
     off = offloaded_layers(L, N)
     trig = trigger_layers(L, N, schedule)
@@ -95,6 +102,61 @@ def timeline(tc: Sequence[int], tx: Sequence[int], N: int, schedule: int = PAPER
             t += stall
         t += tc[l]
     return t, stalls
+
+
+def timeline_continuous(tc: Sequence[int], tx: Sequence[int], N: int, iterations: int) -> Tuple[List[int], List[int]]:
+    """Back-to-back iterations of the same kind with loads that run on across the iteration
+    boundary (the paper is silent on what happens there; its closed form in Sec. 4.4 counts
+    how many layer transfers fit into one iteration, which presumes exactly this).
+
+    All loads of all iterations form one sequence g = 0, 1, 2, ...: iteration g // K, the
+    (g % K)-th offloaded layer.  Load g goes into staging slot g % 2.  It is issued when the
+    layer of load g - m has been computed, m = min(2, K): for K >= 2 that is when its slot
+    is given back; for K = 1 the other slot is free all along, but the layer's KV rows of the
+    previous iteration must have been written before they are fetched again.  The first m
+    loads are issued at time 0.  One copy stream, served in issue order.
+
+    Returns the duration of each iteration and the stalls of the last one.  The first
+    iteration starts cold; `timeline` reports the larger of the last two durations."""
+    L = len(tc)
+    off = offloaded_layers(L, N)
+    K = len(off)
+    if K == 0:
+        return [sum(tc)] * iterations, []
+    m = min(2, K)
+    computed = {}         # load number -> time its layer finished computing
+    ready = {}            # load number -> time its state is on the GPU
+    copy_free = 0
+    issued = 0            # loads handed to the copy stream so far
+
+    def issue_what_is_due(now: int):
+        nonlocal issued, copy_free
+        while issued < iterations * K and (issued < m or (issued - m) in computed):
+            at = 0 if issued < m else computed[issued - m]
+            assert at <= now
+            start = max(copy_free, at)
+            copy_free = start + tx[off[issued % K]]
+            ready[issued] = copy_free
+            issued += 1
+
+    t = 0
+    times, stalls = [], []
+    for it in range(iterations):
+        begin = t
+        stalls = []
+        for l in range(L):
+            issue_what_is_due(t)
+            if l in off:
+                g = it * K + off.index(l)
+                stall = max(0, ready[g] - t)
+                stalls.append(stall)
+                t += stall
+                t += tc[l]
+                computed[g] = t
+            else:
+                t += tc[l]
+        times.append(t - begin)
+    return times, stalls
 
 
 def hidden_fraction(tx: Sequence[int], N: int, stalls: Sequence[int]) -> float:

@@ -205,6 +205,104 @@ def test_eager_schedule_hand_worked_and_independent_simulation():
         assert osch.timeline([c] * L, [x] * L, N, osch.EAGER)[0] == (L // N) * x + c
 
 
+
+def _dependency_graph_times(tc, tx, N, iterations):
+    """The continuous schedule as a dependency graph, solved by longest paths: compute task (i, l)
+    follows the previous compute task and, if layer l is on the host, its load; load g follows load
+    g - 1 (one copy stream) and the compute task of load g - min(2, K) (staging slot / KV rows)."""
+    L = len(tc)
+    off = [l for l in range(L) if 1 <= N <= L and (l + 1) % N == 0]
+    K = len(off)
+    m = min(2, K)
+    load_done, layer_done = {}, {}
+
+    def load(g):
+        if g not in load_done:
+            after = [0]
+            if g >= 1:
+                after.append(load(g - 1))
+            if g >= m:
+                after.append(layer(*divmod(g - m, K)))
+            load_done[g] = max(after) + tx[off[g % K]]
+        return load_done[g]
+
+    def layer(i, k_or_l, by_layer=False):
+        l = k_or_l if by_layer else off[k_or_l]
+        if (i, l) not in layer_done:
+            after = [0]
+            if l > 0:
+                after.append(layer(i, l - 1, True))
+            elif i > 0:
+                after.append(layer(i - 1, L - 1, True))
+            if l in off:
+                after.append(load(i * K + off.index(l)))
+            layer_done[(i, l)] = max(after) + tc[l]
+        return layer_done[(i, l)]
+
+    import sys
+    sys.setrecursionlimit(100000)
+    ends = [0]
+    for i in range(iterations):
+        for l in range(L):
+            layer(i, l, True)                 # in order, so the recursion stays shallow
+        ends.append(layer_done[(i, L - 1)])
+    return [b - a for a, b in zip(ends, ends[1:])]
+
+
+def test_continuous_schedule_hand_worked_closed_forms_and_dependency_graph():
+    # L = 4, N = 2, compute 10, transfer 25 (layers 1 and 3 on the host), loads numbered across iterations:
+    # load0 0-25, load1 25-50; iteration 0: layer0 0-10, layer1 25-35 (-> load2 50-75), layer2 35-45,
+    #   layer3 50-60 (-> load3 75-100): 60, as the eager schedule from a cold start.
+    # iteration 1: layer0 60-70, layer1 75-85 (-> load4 100-125), layer2 85-95, layer3 100-110 (-> load5 125-150): 50
+    # iteration 2: layer0 110-120, layer1 125-135, layer2 135-145, layer3 150-160: 50 = 2 transfers.
+    tc, tx = [10] * 4, [25] * 4
+    times, stalls = osch.timeline_continuous(tc, tx, 2, 3)
+    assert times == [60, 50, 50] and stalls == [5, 5]
+    assert osch.timeline(tc, tx, 2, osch.CONTINUOUS) == (50, [5, 5])
+    assert osch.trigger_layers(8, 2, osch.CONTINUOUS) == osch.trigger_layers(8, 2, osch.EAGER)
+    # one offloaded layer (K = 1): its next load starts when it has been computed, so an iteration is
+    # the longer of the compute chain and one transfer plus that layer: max(L c, x + c)
+    assert osch.timeline([10] * 6, [100] * 6, 4, osch.CONTINUOUS)[0] == 110
+    assert osch.timeline([10] * 6, [30] * 6, 4, osch.CONTINUOUS)[0] == 60
+    rnd = random.Random(11)
+    checked = {"one": 0, "copy": 0, "compute": 0}
+    for _ in range(3000):
+        L = rnd.randint(2, 24)
+        N = rnd.randint(1, L)
+        c, x = rnd.randint(1, 20), rnd.randint(0, 200)
+        K, r = L // N, L % N
+        T = osch.timeline([c] * L, [x] * L, N, osch.CONTINUOUS)[0]
+        if K == 1:
+            assert T == max(L * c, x + c)
+            checked["one"] += 1
+        elif x >= (2 * N + r) * c:                   # copy stream never idles: the analyzer's regime (Sec. 4.4)
+            assert T == K * x
+            checked["copy"] += 1
+        elif x + c <= 2 * N * c and K * x <= L * c:  # every load is back before its layer is reached
+            assert T == L * c
+            checked["compute"] += 1
+    assert min(checked.values()) > 100
+    for _ in range(300):
+        L = rnd.randint(1, 12)
+        N = rnd.randint(1, L + 1)
+        tc = [rnd.randint(1, 100) for _ in range(L)]
+        tx = [rnd.randint(0, 600) for _ in range(L)]
+        times, _ = osch.timeline_continuous(tc, tx, N, 6)
+        assert times == _dependency_graph_times(tc, tx, N, 6), (tc, tx, N)
+        assert times[0] == osch.timeline(tc, tx, N, osch.EAGER)[0]          # a cold start is the eager schedule
+        steady = osch.timeline(tc, tx, N, osch.CONTINUOUS)[0]
+        assert max(sum(tc), sum(tx[o] for o in osch.offloaded_layers(L, N))) <= steady <= times[0]
+        assert steady == max(osch.timeline_continuous(tc, tx, N, 40)[0][-2:])   # 16 iterations reach the steady state
+    # the repaired closed form of Sec. 4.4 is this schedule's answer whenever the copy stream is the
+    # bottleneck: the SLO admits floor(SLO / x) transfers per iteration
+    L, c, x = 32, 10, 830
+    for slo in (2 * L * c, 3 * L * c, 5 * L * c, 10 * L * c):
+        n = osch.min_interval([c] * L, [x] * L, slo, osch.CONTINUOUS)
+        k_allowed = slo // x
+        assert (L // n if n <= L else 0) <= k_allowed
+        assert n == osch.paper_rule(L, c, x, slo) or x + c > slo   # K = 1 costs x + c, not x
+
+
 def test_picker_is_min_feasible_and_monotone_in_slo():
     rnd = random.Random(3)
     for _ in range(400):
