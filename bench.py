@@ -61,6 +61,8 @@ def parse():
                     help="also run the decode steps with the interval re-selected before every iteration from a "
                          "performance record of CELLS sequence lengths spanning the run (the KV cache grows, the "
                          "TPOT SLO stays fixed); 0: off")
+    ap.add_argument("--no-continuous", action="store_true",
+                    help="skip the decode runs with loads issued across the iteration boundary")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="draw only this many different random layer blobs (0: every layer its own)")
@@ -365,6 +367,48 @@ def main():
                 f"{pts[-1]['tpot_median_ms']:.3f} max {pts[-1]['tpot_max_ms']:.3f} (predicted {pred / 1e6:.3f}) "
                 f"within={pts[-1]['every_iteration_within_slo']} hidden {pts[-1]['hidden_fraction']:.3f}")
         out["slo_points"] = pts
+
+    # ---- decode with loads that run on across the iteration boundary (continuous schedule): the steady
+    # state the analyzer's closed form describes -- floor(SLO / transfer) layers fit one iteration -----------
+    if not a.no_continuous:
+        factors = [a.slo_factor] + ([float(v) for v in a.slo_points.split(",") if v] if (a.slo_points and not a.no_sweep) else [])
+        sn.sn_set_schedule(se.ctx, sn.SN_SCHED_CONTINUOUS)
+        cont = []
+        for f in factors:
+            slo_f = int(f * tpot0_ns)
+            try:
+                n_f = sn.sn_pick_interval_from_times_sched(tc, tx, int(slo_f * (1.0 - a.guard)), L + 1, sn.SN_SCHED_CONTINUOUS)
+            except sn.SnError:
+                n_f = L + 1
+            try:
+                n_paper_sched = sn.sn_pick_interval_from_times(tc, tx, int(slo_f * (1.0 - a.guard)), L + 1)
+            except sn.SnError:
+                n_paper_sched = L + 1
+            se.place(n_f)
+            n_c = max(4, min(K, 16))
+            cst, cwall, _ = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, n_c, W)
+            cit = np.array([d["iter_ns"] for d in cst], dtype=np.float64)
+            ch = sum(d["h2d_ns"] for d in cst)
+            cs = sum(d["stall_ns"] for d in cst)
+            cb = sum(d["h2d_bytes"] for d in cst)
+            pred, _ = sn.sn_timeline_sched(tc, tx, n_f, sn.SN_SCHED_CONTINUOUS)
+            pred_paper, _ = sn.sn_timeline(tc, tx, n_f)
+            cont.append({"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f),
+                         "interval_picked_for_the_papers_schedule": int(n_paper_sched),
+                         "n_offloaded": int(cst[-1]["n_offloaded"]), "loads_issued_ahead_per_step": int(cst[-1]["n_preissued"]),
+                         "tpot_median_ms": float(np.median(cit)) / 1e6, "tpot_max_ms": float(cit.max()) / 1e6,
+                         "predicted_steady_state_ms": pred / 1e6, "predicted_papers_schedule_ms": pred_paper / 1e6,
+                         "every_iteration_within_slo": bool((cit <= slo_f).all()),
+                         "hidden_fraction": (1 - cs / ch) if ch else 1.0,
+                         "h2d_GBps": cb / (ch * 1e-9) / 1e9 if ch else None,
+                         "host_resident_GB": int(cst[-1]["n_offloaded"]) * (sn.sn_layer_blob_bytes(se.cshape) + seq_prof * B * kvtok) / 1e9,
+                         "tokens_per_s": B * 1e3 / cwall, "tokens_per_s_at_median_tpot": B / (float(np.median(cit)) * 1e-9)})
+            log(f"[bench] continuous schedule, SLO {f}x = {slo_f / 1e6:.2f} ms: picked N={n_f} (K={cont[-1]['n_offloaded']}; paper's schedule "
+                f"needs N={n_paper_sched}), TPOT median {cont[-1]['tpot_median_ms']:.3f} max {cont[-1]['tpot_max_ms']:.3f} "
+                f"(predicted {pred / 1e6:.3f}; paper's schedule at this N {pred_paper / 1e6:.3f}) within={cont[-1]['every_iteration_within_slo']} "
+                f"hidden {cont[-1]['hidden_fraction']:.3f} issued ahead {cont[-1]['loads_issued_ahead_per_step']} -> {cont[-1]['tokens_per_s']:.1f} tok/s")
+        sn.sn_set_schedule(se.ctx, sn.SN_SCHED_PAPER)
+        out["decode_continuous_schedule"] = cont
 
     # ---- the prefill phase has its own profile and its own interval (Sec. 4.4, separation of
     # prefill and decoding): TTFT SLOs relative to the all-resident prefill iteration ------------

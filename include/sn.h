@@ -87,6 +87,8 @@ typedef struct {
   uint64_t resident_bytes;  /* device bytes held for this placement                         */
   int64_t kernel_ns[8];     /* per kernel class, summed over layers, when kernel timing on  */
   int32_t kernel_calls[8];
+  int32_t n_preissued;      /* of this iteration's loads, how many had been issued during the
+                               previous iteration (SN_SCHED_CONTINUOUS)                      */
 } sn_step_stats;
 
 /* Kernel classes for sn_step_stats.kernel_ns / sn_set_timing(level 2). */
@@ -141,9 +143,20 @@ int sn_set_budget_enforce(sn_ctx* ctx, int32_t on);
  *     issued at the layer after that one (at the start of the iteration for the first two).
  *     The copy stream then runs back to back, the regime the analyzer's closed form (Sec. 4.4)
  *     describes; the iteration is never longer than with SN_SCHED_PAPER, the output identical.
+ *   SN_SCHED_CONTINUOUS: as SN_SCHED_EAGER within an iteration, and the loads do not stop at the
+ *     iteration boundary (the paper is silent on the boundary; Sec. 4.4's closed form counts the
+ *     transfers that fit into one iteration, which presumes this).  With K layers on the host,
+ *     a decode iteration issues, as soon as its k-th host-resident layer has been computed, the
+ *     load that the next iteration needs (number k + min(2, K) - K, if positive), weights and
+ *     the whole KV slice, into the staging slot that has just become free.  The next sn_step
+ *     finds those loads issued, whatever its kind; sn_place, sn_kv_reset, sn_set_schedule,
+ *     sn_set_layer_weights and sn_profile_layers wait for them and discard them.  Prefill
+ *     iterations run as SN_SCHED_EAGER (what follows a prefill needs the KV it writes back).
+ *     sn_timeline_sched reports the steady state: the longer of the last two of 16 back-to-back
+ *     iterations; the first iteration after a placement starts cold, as SN_SCHED_EAGER.
  * Takes effect at once (also for the placement in force); sn_pick_interval and the timeline it
  * uses follow the context's schedule. */
-enum { SN_SCHED_PAPER = 0, SN_SCHED_EAGER = 1 };
+enum { SN_SCHED_PAPER = 0, SN_SCHED_EAGER = 1, SN_SCHED_CONTINUOUS = 2 };
 int sn_set_schedule(sn_ctx* ctx, int32_t schedule);
 /* Device bytes interval N needs: resident layers' state + two staging slots (if any
  * layer is offloaded) + workspace. */

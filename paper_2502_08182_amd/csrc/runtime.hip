@@ -53,8 +53,9 @@ struct LayerState {
   uint8_t* host_kv_dev = nullptr;   // the same slice as the GPU addresses it (for write-through)
   uint8_t* dev = nullptr;       // device [weights | KV] when GPU resident
   bool offloaded = false;
-  int slot = 0;
+  int slot = 0;                 // staging slot of the load in flight or last used (set when the load is issued)
   int trigger = -1;
+  bool preissued = false;       // the load for the next iteration was issued during the previous one
 };
 
 }  // namespace
@@ -100,8 +101,12 @@ struct sn_ctx {
   // events
   std::vector<hipEvent_t> ev_layer, ev_after_wait, ev_trig, ev_copy_start, ev_ready, ev_done, ev_d2h_start,
       ev_d2h_end;
+  // ev_trig, ev_copy_start and ev_ready hold two sets of n_layers events, one per iteration parity:
+  // a load issued ahead for the next iteration must not re-record what this iteration's statistics read
   hipEvent_t ev_slot_free[2] = {};
   bool slot_free_valid[2] = {false, false};
+  int par = 0, last_par = 0;     // event set of the iteration being enqueued / of the last one enqueued
+  uint32_t load_seq = 0;         // loads issued so far; a load goes to staging slot load_seq % 2
   hipEvent_t ev_iter_start = nullptr, ev_iter_end = nullptr;
   std::vector<hipEvent_t> kev;   // [L][kKernelsPerLayer][2], created on demand
 
@@ -111,6 +116,7 @@ struct sn_ctx {
   int last_tokens = 0;
   int last_timing = 0;
   int64_t last_h2d_bytes = 0, last_d2h_bytes = 0;
+  int last_preissued = 0;        // loads of the last iteration that had been issued during the one before
   std::vector<uint8_t> last_kernel_class;   // [kKernelsPerLayer] class of each per-layer kernel slot
 
   // profile
@@ -164,6 +170,15 @@ void free_events(std::vector<hipEvent_t>& v) {
 
 uint64_t fixed_bytes(const sn_ctx* c) { return c->ws_bytes; }
 
+// What the last iteration's statistics need: its kernels and write-backs.  Every load it used has
+// been waited for by the compute stream; the copy stream may already be busy with loads issued
+// ahead for the next iteration, which must not be waited for here.
+int sync_step(sn_ctx* c) {
+  SN_HIP(c, hipStreamSynchronize(c->compute));
+  SN_HIP(c, hipStreamSynchronize(c->d2h));
+  return SN_OK;
+}
+
 int sync_all(sn_ctx* c) {
   SN_HIP(c, hipStreamSynchronize(c->compute));
   SN_HIP(c, hipStreamSynchronize(c->h2d));
@@ -172,6 +187,41 @@ int sync_all(sn_ctx* c) {
 }
 
 uint8_t* kv_of(uint8_t* state_base, const sn_ctx* c) { return state_base + c->w_bytes; }
+
+// Loads issued ahead for an iteration that will not run as foreseen (placement, schedule, KV
+// layout or weights are about to change): wait for the copy stream and forget them.  The staging
+// slots then hold nothing anyone waits for.
+int drop_preissued(sn_ctx* c) {
+  bool any = false;
+  for (auto& ls : c->layers) {
+    any |= ls.preissued;
+    ls.preissued = false;
+  }
+  if (any) SN_HIP(c, hipStreamSynchronize(c->h2d));
+  return SN_OK;
+}
+
+// Hand the load of host-resident layer o to the copy stream: it starts once compute has reached
+// this point (trigger) and the staging slot's previous user has been computed, fills the slot
+// with the layer's weights (and its KV slice), and signals ev_ready of event set `set`.
+int issue_load(sn_ctx* c, int o, int set, bool with_kv, uint64_t kv_used, int64_t* bytes) {
+  LayerState& os = c->layers[o];
+  const int L = c->shape.n_layers;
+  const int e = set * L + o;
+  os.slot = (int)(c->load_seq++ & 1u);
+  SN_HIP(c, hipEventRecord(c->ev_trig[e], c->compute));
+  SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_trig[e], 0));
+  if (c->slot_free_valid[os.slot]) SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_slot_free[os.slot], 0));
+  SN_HIP(c, hipEventRecord(c->ev_copy_start[e], c->h2d));
+  SN_HIP(c, hipMemcpyAsync(c->slot[os.slot], os.host_w, c->w_bytes, hipMemcpyHostToDevice, c->h2d));
+  *bytes = (int64_t)c->w_bytes;
+  if (with_kv && kv_used) {
+    SN_HIP(c, hipMemcpyAsync(kv_of(c->slot[os.slot], c), os.host_kv, kv_used, hipMemcpyHostToDevice, c->h2d));
+    *bytes += (int64_t)kv_used;
+  }
+  SN_HIP(c, hipEventRecord(c->ev_ready[e], c->h2d));
+  return SN_OK;
+}
 
 }  // namespace
 
@@ -187,7 +237,7 @@ extern "C" int sn_placement(int32_t L, int32_t N, uint8_t* offloaded, int32_t* t
   return SN_OK;
 }
 
-static bool bad_sched(int32_t s) { return s != kSchedPaper && s != kSchedEager; }
+static bool bad_sched(int32_t s) { return s != kSchedPaper && s != kSchedEager && s != kSchedContinuous; }
 
 extern "C" int sn_placement_sched(int32_t L, int32_t N, int32_t schedule, uint8_t* offloaded, int32_t* trigger) {
   if (L < 1 || !offloaded || !trigger || bad_sched(schedule)) return fail(nullptr, SN_E_INVAL, "sn_placement_sched: bad argument");
@@ -361,9 +411,9 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   int rc;
   if ((rc = make_events(c, c->ev_layer, L + 1, true))) return rc;
   if ((rc = make_events(c, c->ev_after_wait, L, true))) return rc;
-  if ((rc = make_events(c, c->ev_trig, L, false))) return rc;
-  if ((rc = make_events(c, c->ev_copy_start, L, true))) return rc;
-  if ((rc = make_events(c, c->ev_ready, L, true))) return rc;
+  if ((rc = make_events(c, c->ev_trig, 2 * L, false))) return rc;
+  if ((rc = make_events(c, c->ev_copy_start, 2 * L, true))) return rc;
+  if ((rc = make_events(c, c->ev_ready, 2 * L, true))) return rc;
   if ((rc = make_events(c, c->ev_done, L, false))) return rc;
   if ((rc = make_events(c, c->ev_d2h_start, L, true))) return rc;
   if ((rc = make_events(c, c->ev_d2h_end, L, true))) return rc;
@@ -443,6 +493,7 @@ extern "C" int sn_set_layer_weights(sn_ctx* c, int32_t layer, const void* host_b
                 (unsigned long long)c->bl.total);
   int rc = sync_all(c);
   if (rc) return rc;
+  for (auto& other : c->layers) other.preissued = false;     // a load issued ahead may carry the old weights
   LayerState& ls = c->layers[layer];
   // Destination of the tiled record: the layer's host master if it has one; a layer that lives
   // on the GPU and has no master is packed into the staging record and uploaded from there.
@@ -484,6 +535,7 @@ extern "C" int sn_set_schedule(sn_ctx* c, int32_t schedule) {
   if (bad_sched(schedule)) return fail(c, SN_E_INVAL, "sn_set_schedule: unknown schedule %d", schedule);
   int rc = sync_all(c);
   if (rc) return rc;
+  for (auto& ls : c->layers) ls.preissued = false;
   c->sched = schedule;
   if (c->placed)
     for (int l = 0; l < c->shape.n_layers; ++l) {
@@ -511,6 +563,7 @@ extern "C" int sn_place(sn_ctx* c, int32_t N) {
                 (unsigned long long)c->budget);
   int rc = sync_all(c);
   if (rc) return rc;
+  for (auto& ls : c->layers) ls.preissued = false;      // loads issued ahead have landed; nobody will use them
   const uint64_t kv_used = (uint64_t)c->kv_used_tokens * kv_token_bytes(c->shape);
 
   // first release what leaves the GPU, then allocate what enters it
@@ -553,12 +606,11 @@ extern "C" int sn_place(sn_ctx* c, int32_t N) {
   if (K > 0)
     for (auto& s : c->slot)
       if (!s) SN_HIP(c, hipMalloc((void**)&s, c->state_bytes));
-  int k = 0;
   for (int l = 0; l < L; ++l) {
     LayerState& ls = c->layers[l];
     ls.offloaded = is_offloaded(L, N, l);
     ls.trigger = ls.offloaded ? trigger_of(N, l, c->sched) : -1;
-    ls.slot = ls.offloaded ? (k++ & 1) : 0;
+    ls.slot = 0;
   }
   c->slot_free_valid[0] = c->slot_free_valid[1] = false;
   c->N = N;
@@ -581,6 +633,8 @@ extern "C" int sn_kv_reset(sn_ctx* c, int32_t batch, const int32_t* capacity) {
   if (tot > (int64_t)c->shape.max_batch * c->shape.max_seq)
     return fail(c, SN_E_INVAL, "sn_kv_reset: capacities sum to %lld tokens, context holds %lld", (long long)tot,
                 (long long)c->shape.max_batch * c->shape.max_seq);
+  int rc = drop_preissued(c);      // a load issued ahead carries the old layout's KV bytes
+  if (rc) return rc;
   c->batch = batch;
   c->cap.assign(capacity, capacity + batch);
   c->kv_off.assign(batch, 0);
@@ -781,6 +835,8 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
   const uint64_t kv_used = (uint64_t)c->kv_used_tokens * kv_token_bytes(s);
   const bool fetch_kv = any_cached;             // prefill from empty caches produces the KV itself
   c->last_h2d_bytes = c->last_d2h_bytes = 0;
+  c->last_preissued = 0;
+  const int par = c->par;
 
   SN_HIP(c, hipEventRecord(c->ev_iter_start, c->compute));
   SN_HIP(c, launch_cast_in(s.dtype, bt->hidden_in, c->x32, (size_t)T * s.hidden, c->compute));
@@ -794,22 +850,21 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
     for (int o = l; o < L && o <= l + trigger_lead(c->N, c->sched); ++o) {
       LayerState& os = c->layers[o];
       if (!os.offloaded || os.trigger != l) continue;
-      SN_HIP(c, hipEventRecord(c->ev_trig[o], c->compute));
-      SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_trig[o], 0));
-      if (c->slot_free_valid[os.slot]) SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_slot_free[os.slot], 0));
-      SN_HIP(c, hipEventRecord(c->ev_copy_start[o], c->h2d));
-      SN_HIP(c, hipMemcpyAsync(c->slot[os.slot], os.host_w, c->w_bytes, hipMemcpyHostToDevice, c->h2d));
-      c->last_h2d_bytes += (int64_t)c->w_bytes;
-      if (fetch_kv && kv_used) {
-        SN_HIP(c, hipMemcpyAsync(kv_of(c->slot[os.slot], c), os.host_kv, kv_used, hipMemcpyHostToDevice, c->h2d));
-        c->last_h2d_bytes += (int64_t)kv_used;
+      if (os.preissued) {            // already on its way (or here): issued during the previous iteration
+        os.preissued = false;
+        c->last_h2d_bytes += (int64_t)(c->w_bytes + kv_used);
+        ++c->last_preissued;
+        continue;
       }
-      SN_HIP(c, hipEventRecord(c->ev_ready[o], c->h2d));
+      int64_t bytes = 0;
+      int rc = issue_load(c, o, par, fetch_kv, kv_used, &bytes);
+      if (rc) return rc;
+      c->last_h2d_bytes += bytes;
     }
     uint8_t* base = ls.dev;
     uint8_t* mirror = nullptr;
     if (ls.offloaded) {
-      SN_HIP(c, hipStreamWaitEvent(c->compute, c->ev_ready[l], 0));     // the fence "S" of Fig. 7
+      SN_HIP(c, hipStreamWaitEvent(c->compute, c->ev_ready[par * L + l], 0));     // the fence "S" of Fig. 7
       SN_HIP(c, hipEventRecord(c->ev_after_wait[l], c->compute));
       base = c->slot[ls.slot];
       if (!prefill) mirror = ls.host_kv_dev;                                 // decode: rows written through
@@ -830,6 +885,21 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
         c->last_d2h_bytes += (int64_t)B * (int64_t)kv_token_bytes(s);
       }
       c->slot_free_valid[ls.slot] = true;
+      // Continuous schedule, decode: the loads do not stop at the iteration boundary.  With K layers
+      // on the host, the k-th one's completion releases what load k + min(2, K) waits for; when that
+      // load belongs to the next iteration it is issued here, into the other event set.  It carries the
+      // layer's weights and its whole KV slice (the rows this iteration wrote through included), which
+      // is what any next iteration under the same placement and KV layout needs.
+      if (c->sched == kSchedContinuous && !prefill) {
+        const int K = offloaded_count(L, c->N), k = (l + 1) / c->N, ahead = std::min(2, K);
+        if (k + ahead > K) {
+          const int on = (k + ahead - K) * c->N - 1;
+          int64_t bytes = 0;
+          rc = issue_load(c, on, par ^ 1, true, kv_used, &bytes);
+          if (rc) return rc;
+          c->layers[on].preissued = true;
+        }
+      }
     }
   }
   SN_HIP(c, hipEventRecord(c->ev_layer[L], c->compute));
@@ -844,6 +914,8 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
     kv->len[b] = c->len[b];
   }
   c->last_valid = true;
+  c->last_par = par;
+  c->par = par ^ 1;
   c->last_tokens = T;
   c->last_prefill = prefill;
   c->last_timing = c->timing;
@@ -880,7 +952,7 @@ extern "C" int sn_set_kernel_timing_class(sn_ctx* c, int32_t kernel_class) {
 extern "C" int sn_get_stats(sn_ctx* c, sn_step_stats* out) {
   if (!c || !out) return fail(c, SN_E_INVAL, "sn_get_stats: null argument");
   if (!c->last_valid) return fail(c, SN_E_STATE, "sn_get_stats: no iteration has run under this placement");
-  int rc = sync_all(c);
+  int rc = sync_step(c);
   if (rc) return rc;
   std::memset(out, 0, sizeof *out);
   const int L = c->shape.n_layers;
@@ -888,12 +960,13 @@ extern "C" int sn_get_stats(sn_ctx* c, sn_step_stats* out) {
   out->interval = c->N;
   out->resident_bytes = sn_resident_bytes(c, c->N);
   out->h2d_bytes = c->last_h2d_bytes;
+  out->n_preissued = c->last_preissued;
   out->d2h_bytes = c->last_d2h_bytes;
   for (int l = 0; l < L; ++l) {
     const LayerState& ls = c->layers[l];
     if (!ls.offloaded) continue;
     ++out->n_offloaded;
-    out->h2d_ns += std::max<int64_t>(0, elapsed_ns(c->ev_copy_start[l], c->ev_ready[l]));
+    out->h2d_ns += std::max<int64_t>(0, elapsed_ns(c->ev_copy_start[c->last_par * L + l], c->ev_ready[c->last_par * L + l]));
     out->stall_ns += std::max<int64_t>(0, elapsed_ns(c->ev_layer[l], c->ev_after_wait[l]));
     if (c->last_prefill) out->d2h_ns += std::max<int64_t>(0, elapsed_ns(c->ev_d2h_start[l], c->ev_d2h_end[l]));
   }
@@ -967,14 +1040,14 @@ extern "C" int sn_get_layer_times(sn_ctx* c, int64_t* compute_ns, int64_t* stall
   if (!c) return fail(nullptr, SN_E_INVAL, "null context");
   if (!c->last_valid) return fail(c, SN_E_STATE, "sn_get_layer_times: no iteration has run under this placement");
   if (c->last_timing < 1) return fail(c, SN_E_STATE, "sn_get_layer_times: needs timing level >= 1 during the step");
-  int rc = sync_all(c);
+  int rc = sync_step(c);
   if (rc) return rc;
   const int L = c->shape.n_layers;
   for (int l = 0; l < L; ++l) {
     const LayerState& ls = c->layers[l];
     if (compute_ns) compute_ns[l] = elapsed_ns(ls.offloaded ? c->ev_after_wait[l] : c->ev_layer[l], c->ev_layer[l + 1]);
     if (stall_ns) stall_ns[l] = ls.offloaded ? std::max<int64_t>(0, elapsed_ns(c->ev_layer[l], c->ev_after_wait[l])) : 0;
-    if (h2d_ns) h2d_ns[l] = ls.offloaded ? elapsed_ns(c->ev_copy_start[l], c->ev_ready[l]) : 0;
+    if (h2d_ns) h2d_ns[l] = ls.offloaded ? elapsed_ns(c->ev_copy_start[c->last_par * L + l], c->ev_ready[c->last_par * L + l]) : 0;
   }
   return SN_OK;
 }
@@ -1004,6 +1077,13 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
 
   int rc = sync_all(c);
   if (rc) return rc;
+  // The iterations run here are measurements, each followed by a reset: nothing is issued ahead.
+  struct SchedGuard {
+    sn_ctx* c;
+    int saved;
+    ~SchedGuard() { c->sched = saved; }
+  } guard{c, c->sched};
+  if (c->sched == kSchedContinuous) c->sched = kSchedEager;
   std::vector<int32_t> caps(batch, cap1), n_new(batch, is_prefill ? seq : 1), lens(batch, 0);
   if ((rc = sn_kv_reset(c, batch, caps.data()))) return rc;
 

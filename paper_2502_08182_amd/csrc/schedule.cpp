@@ -21,7 +21,8 @@ int trigger_lead(int N, int sched) {
   // paper: first layer of the group; one layer ahead when every layer is offloaded (N == 1).
   // eager: one group earlier -- the staging slot of the k-th offloaded layer is free once the
   // (k-2)-th has been computed, so its load can be issued at the layer after that one.
-  return sched == kSchedEager ? 2 * N - 1 : (N > 1 ? N - 1 : 1);
+  // continuous: within an iteration as eager (what it adds happens at the iteration boundary).
+  return sched != kSchedPaper ? 2 * N - 1 : (N > 1 ? N - 1 : 1);
 }
 
 int trigger_of(int N, int o, int sched) {
@@ -29,7 +30,44 @@ int trigger_of(int N, int o, int sched) {
   return o >= lead ? o - lead : 0;
 }
 
+// Steady state of back-to-back iterations whose loads run on across the iteration boundary.
+// Loads are numbered through all iterations; load g (iteration g / K, g % K-th offloaded layer) is
+// handed to the copy stream when the layer of load g - min(2, K) has been computed (its staging slot
+// is free then; with a single offloaded layer, its KV rows of the previous iteration are written
+// then), the first min(2, K) at time zero.  The copy stream is FIFO in that order, so each load's
+// arrival follows from the previous load's arrival and that one compute-finish time, both of
+// which are known by the time compute reaches the load's own layer.  Reports the longer of the
+// last two of kContinuousIterations iterations and the stalls of the last one.
+static int64_t continuous_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total) {
+  const int K = offloaded_count(L, N);
+  const int m = std::min(2, K);
+  const int total = kContinuousIterations * K;
+  std::vector<int64_t> arrive(total), finish(total);
+  int64_t now = 0, last = 0, before_last = 0, stalls = 0;
+  for (int it = 0, g = 0; it < kContinuousIterations; ++it) {
+    const int64_t begin = now;
+    stalls = 0;
+    for (int l = 0; l < L; ++l) {
+      if (is_offloaded(L, N, l)) {
+        const int64_t handed_over = g < m ? 0 : finish[g - m];
+        arrive[g] = std::max(g ? arrive[g - 1] : 0, handed_over) + tx[l];
+        const int64_t wait = std::max<int64_t>(0, arrive[g] - now);
+        stalls += wait;
+        now += wait + tc[l];
+        finish[g++] = now;
+      } else {
+        now += tc[l];
+      }
+    }
+    before_last = last;
+    last = now - begin;
+  }
+  if (stall_total) *stall_total = stalls;
+  return std::max(last, before_last);
+}
+
 int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total, int sched) {
+  if (sched == kSchedContinuous && offloaded_count(L, N) > 0) return continuous_time(L, tc, tx, N, stall_total);
   // Walk the offloaded layers in order.  `now` is the compute stream's clock at the
   // start of the layer under consideration, `copy_idle` the time the (single, FIFO)
   // copy stream runs dry.  Prefix sums give the clock at any trigger layer without

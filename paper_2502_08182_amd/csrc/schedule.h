@@ -5,7 +5,8 @@
 namespace sn {
 int offloaded_count(int L, int N);
 bool is_offloaded(int L, int N, int l);
-constexpr int kSchedPaper = 0, kSchedEager = 1;   // when the load of an offloaded layer is issued
+constexpr int kSchedPaper = 0, kSchedEager = 1, kSchedContinuous = 2;   // when the load of an offloaded layer is issued
+constexpr int kContinuousIterations = 16;         // iterations walked to the continuous schedule's steady state
 int trigger_lead(int N, int sched);               // layers between the trigger and the offloaded layer
 int trigger_of(int N, int offloaded_layer, int sched = kSchedPaper);
 int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total, int sched = kSchedPaper);

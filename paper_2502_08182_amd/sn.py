@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libsn.so")
 SN_F16, SN_BF16 = 0, 1
 SN_ACT_GELU, SN_ACT_SWIGLU = 0, 1
 SN_NORM_LN, SN_NORM_RMS = 0, 1
-SN_SCHED_PAPER, SN_SCHED_EAGER = 0, 1
+SN_SCHED_PAPER, SN_SCHED_EAGER, SN_SCHED_CONTINUOUS = 0, 1, 2
 SN_OK, SN_E_INVAL, SN_E_STATE, SN_E_BUDGET, SN_E_INFEASIBLE, SN_E_NOMEM, SN_E_HIP = 0, -1, -2, -3, -4, -5, -6
 SN_K_NAMES = ("norm", "qkv", "rope_append", "attn", "oproj", "ffn_up", "ffn_down", "other")
 ERROR_NAMES = {-1: "SN_E_INVAL", -2: "SN_E_STATE", -3: "SN_E_BUDGET", -4: "SN_E_INFEASIBLE",
@@ -53,7 +53,7 @@ class sn_step_stats(C.Structure):
     _fields_ = [("iter_ns", C.c_int64), ("stall_ns", C.c_int64), ("h2d_ns", C.c_int64), ("h2d_bytes", C.c_int64),
                 ("d2h_ns", C.c_int64), ("d2h_bytes", C.c_int64), ("hidden_fraction", C.c_double),
                 ("interval", C.c_int32), ("n_offloaded", C.c_int32), ("resident_bytes", C.c_uint64),
-                ("kernel_ns", C.c_int64 * 8), ("kernel_calls", C.c_int32 * 8)]
+                ("kernel_ns", C.c_int64 * 8), ("kernel_calls", C.c_int32 * 8), ("n_preissued", C.c_int32)]
 
     def as_dict(self) -> dict:
         d = {n: getattr(self, n) for n, _ in self._fields_ if n not in ("kernel_ns", "kernel_calls")}

@@ -122,6 +122,53 @@ def test_eager_schedule_changes_timing_only(c1):
         assert e.value.code == sn.SN_E_INVAL
 
 
+def test_continuous_schedule_changes_timing_only(c1):
+    """Loads issued across the iteration boundary (during decode, for the next iteration): same bits
+    for every interval; from the second decode step on min(2, K) of an iteration's loads were issued
+    during the one before; a placement change, a KV reset, a schedule change or new weights while such
+    loads are in flight discard them without harm."""
+    w, layers, prompt, table, *_ = c1
+    L = w.shape.n_layers
+    ref = gpu_run(w, layers, prompt, table, 0)
+    for N in (1, 2, 3, 4):
+        K = L // N
+        with Session(w.shape, w.batch, w.max_seq) as se:
+            se.load_synthetic_weights(layers=layers)
+            sn.sn_set_schedule(se.ctx, sn.SN_SCHED_CONTINUOUS)
+            se.place(N)
+            se.kv_reset([p + w.decode_steps for p in w.prompt_lens])
+            pre = se.step(list(w.prompt_lens), True, prompt)
+            assert se.stats()["n_preissued"] == 0
+            outs = []
+            for t in range(w.decode_steps):
+                outs.append(se.step([1] * w.batch, False, table[t]))
+                st = se.stats()
+                assert st["n_preissued"] == (0 if t == 0 else min(2, K)), (N, t, st["n_preissued"])
+                assert st["n_offloaded"] == K and st["h2d_bytes"] > 0
+            assert np.array_equal(pre, ref[0]) and np.array_equal(np.stack(outs), ref[1]), f"continuous differs at N={N}"
+            # loads for a ninth decode step are in flight now; a new request (KV reset) must not see them
+            pre2, dec2 = se.run_workload(w, prompt, table)
+            assert np.array_equal(pre2, ref[0]) and np.array_equal(dec2, ref[1])
+            sn.sn_set_schedule(se.ctx, sn.SN_SCHED_PAPER)
+            pre3, dec3 = se.run_workload(w, prompt, table)
+            assert se.stats()["n_preissued"] == 0
+            assert np.array_equal(pre3, ref[0]) and np.array_equal(dec3, ref[1])
+    # the interval changes before every iteration, and the weights are set again in the middle
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        se.load_synthetic_weights(layers=layers)
+        sn.sn_set_schedule(se.ctx, sn.SN_SCHED_CONTINUOUS)
+        se.place(2)
+        se.kv_reset([p + w.decode_steps for p in w.prompt_lens])
+        pre = se.step(list(w.prompt_lens), True, prompt)
+        outs = []
+        for t, N in enumerate([1, 1, 3, 0, 2, 2, 4, 1]):
+            se.place(N)
+            if t == 5:
+                se.load_synthetic_weights(layers=layers)
+            outs.append(se.step([1] * w.batch, False, table[t]))
+        assert np.array_equal(pre, ref[0]) and np.array_equal(np.stack(outs), ref[1])
+
+
 def test_replacing_between_iterations_keeps_the_cache(c1):
     """Sec. 4.2: a new interval is applied before the next iteration; live KV must move with it."""
     w, layers, prompt, table, *_ = c1

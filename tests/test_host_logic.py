@@ -85,7 +85,7 @@ def test_bf16_weights_become_equal_float16_values():
 
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(sn.sn_model_shape) == 16 * 4
-    assert ctypes.sizeof(sn.sn_step_stats) == 6 * 8 + 8 + 2 * 4 + 8 + 8 * 8 + 8 * 4
+    assert ctypes.sizeof(sn.sn_step_stats) == 6 * 8 + 8 + 2 * 4 + 8 + 8 * 8 + 8 * 4 + 8     # n_preissued and tail padding
 
 
 def test_placement_matches_oracle_and_fig7():
@@ -207,4 +207,29 @@ def test_eager_schedule_agrees_with_the_oracle():
             got_n = None
         assert got_n == want_n
     with pytest.raises(sn.SnError):
-        sn.sn_timeline_sched([1], [1], 1, 2)
+        sn.sn_timeline_sched([1], [1], 1, 3)
+
+
+def test_continuous_schedule_agrees_with_the_oracle():
+    """Loads that run on across the iteration boundary: steady-state iteration time, the stalls of the
+    last iteration and the picker against the oracle, exactly; triggers inside an iteration are the
+    eager schedule's; the steady state is never slower than a cold start."""
+    rnd = random.Random(37)
+    for _ in range(1200):
+        L = rnd.randint(1, 40)
+        tc = [rnd.randint(1, 400) for _ in range(L)]
+        tx = [rnd.randint(0, 3000) for _ in range(L)]
+        N = rnd.randint(1, L + 1)
+        assert [list(v) for v in sn.sn_placement_sched(L, N, sn.SN_SCHED_CONTINUOUS)] == \
+               [list(v) for v in sn.sn_placement_sched(L, N, sn.SN_SCHED_EAGER)]
+        t_o, stalls = osch.timeline(tc, tx, N, osch.CONTINUOUS)
+        assert sn.sn_timeline_sched(tc, tx, N, sn.SN_SCHED_CONTINUOUS) == (t_o, sum(stalls))
+        assert t_o <= sn.sn_timeline_sched(tc, tx, N, sn.SN_SCHED_EAGER)[0]
+        slo = rnd.randint(1, 3 * sum(tc))
+        want_n = osch.pick_interval(tc, tx, slo, L + 1, osch.CONTINUOUS)
+        try:
+            got_n = sn.sn_pick_interval_from_times_sched(tc, tx, slo, L + 1, sn.SN_SCHED_CONTINUOUS)
+        except sn.SnError as e:
+            assert e.code == sn.SN_E_INFEASIBLE
+            got_n = None
+        assert got_n == want_n
