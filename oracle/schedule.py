@@ -176,6 +176,20 @@ def resident_bytes(L: int, N: int, state_bytes: int, slot_bytes: int, fixed_byte
     return (L - K) * state_bytes + (2 * slot_bytes if K else 0) + fixed_bytes
 
 
+STATE, WEIGHTS, KV = 0, 1, 2      # which part of a host-resident layer's state lives on the host
+
+
+def resident_bytes_of(L: int, N: int, weight_bytes: int, kv_bytes: int, fixed_bytes: int, what: int = STATE) -> int:
+    """GPU bytes held for interval N when a host-resident layer keeps on the host its whole state
+    (weights and KV slice; Sec. 1 and 2.3 speak of "LLM state"), only its weights, or only its KV
+    slice.  The part that stays behind lives on the GPU; a staging slot holds only the part that
+    travels."""
+    K = len(offloaded_layers(L, N))
+    stays = {STATE: 0, WEIGHTS: kv_bytes, KV: weight_bytes}[what]
+    travels = weight_bytes + kv_bytes - stays
+    return (L - K) * (weight_bytes + kv_bytes) + K * stays + (2 * travels if K else 0) + fixed_bytes
+
+
 def max_interval(L: int, budget: int, state_bytes: int, slot_bytes: int, fixed_bytes: int) -> int:
     """Largest interval whose footprint fits the budget; L+1 stands for "no offloading"
     (infinite maximum, Sec. 4.5); 0 when not even N = 1 fits.  budget <= 0: no cap."""
@@ -188,14 +202,26 @@ def max_interval(L: int, budget: int, state_bytes: int, slot_bytes: int, fixed_b
     return best
 
 
-def max_tokens(L: int, N: int, weight_bytes: int, kv_token_bytes: int, fixed_bytes: int, budget: int) -> int:
+def max_interval_of(L: int, budget: int, weight_bytes: int, kv_bytes: int, fixed_bytes: int, what: int = STATE) -> int:
+    """max_interval for a given choice of what is kept on the host."""
+    if budget <= 0:
+        return L + 1
+    best = 0
+    for N in range(1, L + 2):
+        if resident_bytes_of(L, N, weight_bytes, kv_bytes, fixed_bytes, what) <= budget:
+            best = N
+    return best
+
+
+def max_tokens(L: int, N: int, weight_bytes: int, kv_token_bytes: int, fixed_bytes: int, budget: int,
+               what: int = STATE) -> int:
     """Sec. 5.6's "max length" (batch size x (sequence + output length)): the largest number of
     cached tokens for which interval N still fits the budget.  A layer's state is its weights plus
-    its KV slice of that many tokens; GPU-resident layers and the two staging slots (when anything
-    is offloaded) each hold one such state.  Plain search from the definition."""
+    its KV slice of that many tokens; GPU-resident layers hold one such state, and so does each of
+    the two staging slots (when anything is offloaded) -- or only the part of it that travels, when
+    host-resident layers keep the other part on the GPU.  Plain search from the definition."""
     def fits(t: int) -> bool:
-        state = weight_bytes + t * kv_token_bytes
-        return resident_bytes(L, N, state, state, fixed_bytes) <= budget
+        return resident_bytes_of(L, N, weight_bytes, t * kv_token_bytes, fixed_bytes, what) <= budget
     if not fits(0):
         return 0
     if kv_token_bytes == 0:
@@ -211,6 +237,12 @@ def max_tokens(L: int, N: int, weight_bytes: int, kv_token_bytes: int, fixed_byt
         else:
             hi = mid
     return lo
+
+
+def load_bytes(weight_bytes: int, kv_prefix_bytes: int, what: int = STATE) -> int:
+    """Bytes one host-resident layer's load moves host-to-GPU: the part of its state that lives on
+    the host (kv_prefix_bytes: its cached K/V so far; 0 in a prefill from empty caches)."""
+    return {STATE: weight_bytes + kv_prefix_bytes, WEIGHTS: weight_bytes, KV: kv_prefix_bytes}[what]
 
 
 # ---------------------------------------------------------------------------

@@ -388,6 +388,73 @@ def test_max_tokens_hand_worked():
         assert osch.max_tokens(8, N, **args) >= osch.max_tokens(8, N + 1, **args) or N == 8
 
 
+def _inventory(L, N, w, kv, fixed, what):
+    """What the GPU holds, item by item: each layer's weights and KV slice if they live there, the
+    two staging slots' parts if any layer is host-resident, the workspace."""
+    items = [fixed]
+    any_host = False
+    for l in range(L):
+        host = 1 <= N <= L and (l + 1) % N == 0
+        any_host |= host
+        if not host or what == osch.KV:
+            items.append(w)                 # weights on the GPU
+        if not host or what == osch.WEIGHTS:
+            items.append(kv)                # KV slice on the GPU
+    if any_host:
+        for _slot in range(2):
+            if what != osch.KV:
+                items.append(w)
+            if what != osch.WEIGHTS:
+                items.append(kv)
+    return sum(items)
+
+
+def test_what_is_offloaded_hand_worked_and_inventory():
+    """Host-resident layers may keep their whole state, only their weights or only their KV slice on the
+    host.  L = 8, N = 2 (4 layers on the host), weights 100 B, KV slice 30 B, workspace 50 B:
+    whole state: 4 x 130 resident + 2 slots x 130 + 50 = 830
+    weights only: 4 x 130 + 4 x 30 (their KV stays) + 2 x 100 + 50 = 890
+    KV only:      4 x 130 + 4 x 100 (their weights stay) + 2 x 30 + 50 = 1030;   nothing offloaded: 8 x 130 + 50 = 1090."""
+    assert osch.resident_bytes_of(8, 2, 100, 30, 50, osch.STATE) == 830
+    assert osch.resident_bytes_of(8, 2, 100, 30, 50, osch.WEIGHTS) == 890
+    assert osch.resident_bytes_of(8, 2, 100, 30, 50, osch.KV) == 1030
+    assert osch.resident_bytes_of(8, 9, 100, 30, 50, osch.KV) == 1090
+    assert osch.load_bytes(100, 12, osch.STATE) == 112 and osch.load_bytes(100, 12, osch.WEIGHTS) == 100
+    assert osch.load_bytes(100, 12, osch.KV) == 12 and osch.load_bytes(100, 0, osch.KV) == 0
+    # max length, same numbers as the whole-state case above (2 B per token, budget 2050, workspace 50), N = 2:
+    # weights only: 4 (100 + 2t) + 4 (2t) + 2 x 100 <= 2000 -> 16 t <= 1400 -> t <= 87
+    # KV only:      4 (100 + 2t) + 4 x 100 + 2 (2t) <= 2000 -> 12 t <= 1200 -> t <= 100
+    args = dict(weight_bytes=100, kv_token_bytes=2, fixed_bytes=50, budget=2050)
+    assert osch.max_tokens(8, 2, what=osch.WEIGHTS, **args) == 87
+    assert osch.max_tokens(8, 2, what=osch.KV, **args) == 100
+    assert osch.max_tokens(8, 2, what=osch.STATE, **args) == osch.max_tokens(8, 2, **args) == 116
+    rnd = random.Random(13)
+    for _ in range(600):
+        L, N = rnd.randint(1, 40), rnd.randint(0, 42)
+        w, kv, fx = rnd.randint(0, 10**6), rnd.randint(0, 10**6), rnd.randint(0, 10**6)
+        r = {what: osch.resident_bytes_of(L, N, w, kv, fx, what) for what in (osch.STATE, osch.WEIGHTS, osch.KV)}
+        for what in r:
+            assert r[what] == _inventory(L, N, w, kv, fx, what)
+        assert r[osch.STATE] == osch.resident_bytes(L, N, w + kv, w + kv, fx)
+        none = osch.resident_bytes_of(L, L + 1, w, kv, fx)
+        assert r[osch.WEIGHTS] + r[osch.KV] == r[osch.STATE] + none          # the two halves add up
+        budget = rnd.randint(0, 50 * 10**6)
+        for what in r:
+            n_max = osch.max_interval_of(L, budget, w, kv, fx, what)
+            fits = [n for n in range(1, L + 2) if _inventory(L, n, w, kv, fx, what) <= budget]
+            assert n_max == (max(fits) if fits else 0)
+    for _ in range(200):                       # max length against a linear scan on small numbers
+        L, N = rnd.randint(1, 12), rnd.randint(1, 13)
+        w, kt, fx, budget = rnd.randint(1, 60), rnd.randint(1, 9), rnd.randint(0, 40), rnd.randint(0, 3000)
+        for what in (osch.STATE, osch.WEIGHTS, osch.KV):
+            t = 0
+            while _inventory(L, N, w, (t + 1) * kt, fx, what) <= budget:
+                t += 1
+            if _inventory(L, N, w, 0, fx, what) > budget:
+                t = 0
+            assert osch.max_tokens(L, N, w, kt, fx, budget, what) == t
+
+
 def test_paper_rule_never_exceeds_timeline_pick():
     rnd = random.Random(4)
     for _ in range(5000):
