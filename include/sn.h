@@ -158,8 +158,24 @@ int sn_set_budget_enforce(sn_ctx* ctx, int32_t on);
  * uses follow the context's schedule. */
 enum { SN_SCHED_PAPER = 0, SN_SCHED_EAGER = 1, SN_SCHED_CONTINUOUS = 2 };
 int sn_set_schedule(sn_ctx* ctx, int32_t schedule);
-/* Device bytes interval N needs: resident layers' state + two staging slots (if any
- * layer is offloaded) + workspace. */
+/* Which part of a host-resident layer's state is kept on the host (the paper speaks of "LLM state",
+ * Sec. 1, 2.3; both parts is the default).
+ *   SN_OFFLOAD_STATE:   weights and KV slice; a load moves both (weights only in a prefill from
+ *                       empty caches), new KV rows return to the host.
+ *   SN_OFFLOAD_WEIGHTS: the weights; the layer's KV slice stays on the GPU, loads move weights
+ *                       only, nothing returns to the host.
+ *   SN_OFFLOAD_KV:      the KV slice; the weights stay on the GPU, a load moves the cached K/V
+ *                       (nothing in a prefill from empty caches), new rows return to the host.
+ * The part left behind stays on the GPU and a staging slot holds only the part that travels,
+ * which sn_resident_bytes, sn_max_interval and the budget check follow.  Under a placement in
+ * force the layers' parts are moved at once (synchronously, like sn_place; SN_E_BUDGET and no
+ * change if the new footprint exceeds the budget).  The output does not depend on it.  A profile
+ * taken before the change is dropped (its transfer times were for the other part). */
+enum { SN_OFFLOAD_STATE = 0, SN_OFFLOAD_WEIGHTS = 1, SN_OFFLOAD_KV = 2 };
+int sn_set_offload_part(sn_ctx* ctx, int32_t what);
+int32_t sn_offload_part(const sn_ctx* ctx);      /* -1 for a null context */
+/* Device bytes interval N needs: resident layers' state + what host-resident layers leave on the
+ * GPU + two staging slots (if any layer is offloaded) + workspace. */
 uint64_t sn_resident_bytes(const sn_ctx* ctx, int32_t N);
 /* Largest N whose footprint fits the budget; n_layers+1 = "no offloading fits"
  * (infinite maximum, Sec. 4.5); 0 = not even N = 1 fits. */
@@ -172,6 +188,12 @@ int32_t sn_max_interval(const sn_ctx* ctx);
  * of workspace.  0 if not even the weights fit (or if a token costs nothing).  Pure, host only. */
 uint64_t sn_max_tokens(int32_t L, int32_t N, uint64_t weight_bytes_per_layer, uint64_t kv_bytes_per_token_per_layer,
                        uint64_t fixed_bytes, uint64_t budget_bytes);
+/* The same for a given part kept on the host (SN_OFFLOAD_*), and the footprint itself for a KV
+ * slice of kv_bytes_per_layer.  0 for an unknown part.  Pure, host only. */
+uint64_t sn_max_tokens_part(int32_t L, int32_t N, uint64_t weight_bytes_per_layer, uint64_t kv_bytes_per_token_per_layer,
+                            uint64_t fixed_bytes, uint64_t budget_bytes, int32_t what);
+uint64_t sn_resident_bytes_part(int32_t L, int32_t N, uint64_t weight_bytes_per_layer, uint64_t kv_bytes_per_layer,
+                                uint64_t fixed_bytes, int32_t what);
 
 /* Pure helpers (host only, no GPU): the placement map and prefetch triggers for
  * (L, N).  offloaded[l] in {0,1}; trigger[l] = layer at whose start the load of

@@ -51,8 +51,10 @@ struct LayerState {
   bool has_w = false;           // weights have been set (they live in host_w, in dev, or in both)
   uint8_t* host_kv = nullptr;   // pinned KV slice (present once the layer has been offloaded)
   uint8_t* host_kv_dev = nullptr;   // the same slice as the GPU addresses it (for write-through)
-  uint8_t* dev = nullptr;       // device [weights | KV] when GPU resident
-  bool offloaded = false;
+  uint8_t* dev_w = nullptr;     // device weights record, when the weights live on the GPU
+  uint8_t* dev_kv = nullptr;    // device KV slice, when it lives on the GPU
+  bool offloaded = false;       // some part of the layer's state lives on the host (it needs a load and a fence)
+  bool w_host = false, kv_host = false;   // which part
   int slot = 0;                 // staging slot of the load in flight or last used (set when the load is issued)
   int trigger = -1;
   bool preissued = false;       // the load for the next iteration was issued during the previous one
@@ -76,7 +78,9 @@ struct sn_ctx {
   uint64_t w_bytes = 0, kv_bytes = 0, state_bytes = 0, ws_bytes = 0;
   int64_t max_tokens = 0;
   std::vector<LayerState> layers;
-  uint8_t* slot[2] = {nullptr, nullptr};
+  int what = SN_OFFLOAD_STATE;   // which part of a host-resident layer's state is kept on the host
+  uint8_t* slot_w[2] = {nullptr, nullptr};    // staging slots: the weights part and the KV part, present
+  uint8_t* slot_kv[2] = {nullptr, nullptr};   // when that part travels
   uint8_t* stage_w = nullptr;    // pinned staging record for layers that have no host master
 
   // workspace (device)
@@ -186,7 +190,8 @@ int sync_all(sn_ctx* c) {
   return SN_OK;
 }
 
-uint8_t* kv_of(uint8_t* state_base, const sn_ctx* c) { return state_base + c->w_bytes; }
+bool weights_travel(int what) { return what != SN_OFFLOAD_KV; }
+bool kv_travels(int what) { return what != SN_OFFLOAD_WEIGHTS; }
 
 // Loads issued ahead for an iteration that will not run as foreseen (placement, schedule, KV
 // layout or weights are about to change): wait for the copy stream and forget them.  The staging
@@ -203,7 +208,7 @@ int drop_preissued(sn_ctx* c) {
 
 // Hand the load of host-resident layer o to the copy stream: it starts once compute has reached
 // this point (trigger) and the staging slot's previous user has been computed, fills the slot
-// with the layer's weights (and its KV slice), and signals ev_ready of event set `set`.
+// with the part of the layer's state that lives on the host, and signals ev_ready of event set `set`.
 int issue_load(sn_ctx* c, int o, int set, bool with_kv, uint64_t kv_used, int64_t* bytes) {
   LayerState& os = c->layers[o];
   const int L = c->shape.n_layers;
@@ -213,10 +218,13 @@ int issue_load(sn_ctx* c, int o, int set, bool with_kv, uint64_t kv_used, int64_
   SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_trig[e], 0));
   if (c->slot_free_valid[os.slot]) SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_slot_free[os.slot], 0));
   SN_HIP(c, hipEventRecord(c->ev_copy_start[e], c->h2d));
-  SN_HIP(c, hipMemcpyAsync(c->slot[os.slot], os.host_w, c->w_bytes, hipMemcpyHostToDevice, c->h2d));
-  *bytes = (int64_t)c->w_bytes;
-  if (with_kv && kv_used) {
-    SN_HIP(c, hipMemcpyAsync(kv_of(c->slot[os.slot], c), os.host_kv, kv_used, hipMemcpyHostToDevice, c->h2d));
+  *bytes = 0;
+  if (os.w_host) {
+    SN_HIP(c, hipMemcpyAsync(c->slot_w[os.slot], os.host_w, c->w_bytes, hipMemcpyHostToDevice, c->h2d));
+    *bytes += (int64_t)c->w_bytes;
+  }
+  if (os.kv_host && with_kv && kv_used) {
+    SN_HIP(c, hipMemcpyAsync(c->slot_kv[os.slot], os.host_kv, kv_used, hipMemcpyHostToDevice, c->h2d));
     *bytes += (int64_t)kv_used;
   }
   SN_HIP(c, hipEventRecord(c->ev_ready[e], c->h2d));
@@ -299,6 +307,20 @@ extern "C" uint64_t sn_max_tokens(int32_t L, int32_t N, uint64_t weight_bytes_pe
   return max_tokens(L, N == 0 ? L + 1 : N, weight_bytes_per_layer, kv_bytes_per_token_per_layer, fixed_bytes, budget_bytes);
 }
 
+static bool bad_part(int32_t what) { return what != SN_OFFLOAD_STATE && what != SN_OFFLOAD_WEIGHTS && what != SN_OFFLOAD_KV; }
+
+extern "C" uint64_t sn_max_tokens_part(int32_t L, int32_t N, uint64_t weight_bytes_per_layer, uint64_t kv_bytes_per_token_per_layer,
+                                       uint64_t fixed_bytes, uint64_t budget_bytes, int32_t what) {
+  if (L < 1 || N < 0 || bad_part(what)) return 0;
+  return max_tokens(L, N == 0 ? L + 1 : N, weight_bytes_per_layer, kv_bytes_per_token_per_layer, fixed_bytes, budget_bytes, what);
+}
+
+extern "C" uint64_t sn_resident_bytes_part(int32_t L, int32_t N, uint64_t weight_bytes_per_layer, uint64_t kv_bytes_per_layer,
+                                           uint64_t fixed_bytes, int32_t what) {
+  if (L < 1 || N < 0 || bad_part(what)) return 0;
+  return resident_bytes_of(L, N, weight_bytes_per_layer, kv_bytes_per_layer, fixed_bytes, what);
+}
+
 extern "C" int32_t sn_paper_rule(int32_t L, int64_t t_trans_ns, int64_t slo_ns) {
   return paper_rule(L, t_trans_ns, slo_ns);
 }
@@ -325,9 +347,12 @@ extern "C" void sn_destroy(sn_ctx* c) {
   for (auto& ls : c->layers) {
     if (ls.host_w) (void)hipHostFree(ls.host_w);
     if (ls.host_kv) (void)hipHostFree(ls.host_kv);
-    if (ls.dev) (void)hipFree(ls.dev);
+    if (ls.dev_w) (void)hipFree(ls.dev_w);
+    if (ls.dev_kv) (void)hipFree(ls.dev_kv);
   }
-  for (auto& s : c->slot)
+  for (auto& s : c->slot_w)
+    if (s) (void)hipFree(s);
+  for (auto& s : c->slot_kv)
     if (s) (void)hipFree(s);
   if (c->stage_w) (void)hipHostFree(c->stage_w);
   void* dev[] = {c->x32, c->u16, c->qkv16, c->attn16, c->act16, c->part, c->part32, c->inv_freq, c->meta_dev};
@@ -463,7 +488,7 @@ static int ensure_master(sn_ctx* c, int l, int N_keep) {
     ls.host_w = nullptr;
     for (int o = 0; o < L; ++o) {
       LayerState& os = c->layers[o];
-      if (os.dev && os.host_w && !is_offloaded(L, N_keep, o)) {
+      if (os.dev_w && os.host_w && (!is_offloaded(L, N_keep, o) || !weights_travel(c->what))) {
         (void)hipHostFree(os.host_w);
         os.host_w = nullptr;
       }
@@ -499,7 +524,7 @@ extern "C" int sn_set_layer_weights(sn_ctx* c, int32_t layer, const void* host_b
   // on the GPU and has no master is packed into the staging record and uploaded from there.
   uint8_t* dst = ls.host_w;
   if (!dst) {
-    if (ls.dev) {
+    if (ls.dev_w) {
       if ((rc = ensure_stage(c))) return rc;
       dst = c->stage_w;
     } else {
@@ -515,19 +540,19 @@ extern "C" int sn_set_layer_weights(sn_ctx* c, int32_t layer, const void* host_b
   if (bad)
     return fail(c, SN_E_INVAL, "sn_set_layer_weights: %llu weights are not representable in float16 (|w| > 65504, inf or NaN)",
                 (unsigned long long)bad);
-  if (ls.dev) SN_HIP(c, hipMemcpy(ls.dev, dst, c->w_bytes, hipMemcpyHostToDevice));
+  if (ls.dev_w) SN_HIP(c, hipMemcpy(ls.dev_w, dst, c->w_bytes, hipMemcpyHostToDevice));
   ls.has_w = true;
   return SN_OK;
 }
 
 extern "C" uint64_t sn_resident_bytes(const sn_ctx* c, int32_t N) {
   if (!c) return 0;
-  return resident_bytes(c->shape.n_layers, N, c->state_bytes, c->state_bytes, fixed_bytes(c));
+  return resident_bytes_of(c->shape.n_layers, N, c->w_bytes, c->kv_bytes, fixed_bytes(c), c->what);
 }
 
 extern "C" int32_t sn_max_interval(const sn_ctx* c) {
   if (!c) return 0;
-  return max_interval(c->shape.n_layers, c->budget, c->state_bytes, c->state_bytes, fixed_bytes(c));
+  return max_interval_of(c->shape.n_layers, c->budget, c->w_bytes, c->kv_bytes, fixed_bytes(c), c->what);
 }
 
 extern "C" int sn_set_schedule(sn_ctx* c, int32_t schedule) {
@@ -545,6 +570,21 @@ extern "C" int sn_set_schedule(sn_ctx* c, int32_t schedule) {
   c->last_valid = false;
   return SN_OK;
 }
+
+extern "C" int sn_set_offload_part(sn_ctx* c, int32_t what) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "null context");
+  if (bad_part(what)) return fail(c, SN_E_INVAL, "sn_set_offload_part: unknown part %d", what);
+  if (what == c->what) return SN_OK;
+  const int before = c->what;
+  c->what = what;
+  c->has_profile = false;          // transfer times were measured for the other part
+  if (!c->placed) return SN_OK;
+  const int rc = sn_place(c, c->N);  // moves what has to move; checks the budget first and changes nothing if it fails
+  if (rc) c->what = before;
+  return rc;
+}
+
+extern "C" int32_t sn_offload_part(const sn_ctx* c) { return c ? c->what : -1; }
 
 extern "C" int sn_set_budget_enforce(sn_ctx* c, int32_t on) {
   if (!c) return fail(nullptr, SN_E_INVAL, "null context");
@@ -567,48 +607,68 @@ extern "C" int sn_place(sn_ctx* c, int32_t N) {
   const uint64_t kv_used = (uint64_t)c->kv_used_tokens * kv_token_bytes(c->shape);
 
   // first release what leaves the GPU, then allocate what enters it
+  auto w_goes_host = [&](int l) { return is_offloaded(L, N, l) && weights_travel(c->what); };
+  auto kv_goes_host = [&](int l) { return is_offloaded(L, N, l) && kv_travels(c->what); };
   for (int l = 0; l < L; ++l) {
     LayerState& ls = c->layers[l];
-    if (!is_offloaded(L, N, l)) continue;
-    if (!ls.host_w) {     // the layer moves to (or starts in) host memory: it needs its master
-      if ((rc = ensure_master(c, l, N))) return rc;
-      if (ls.dev && ls.has_w) SN_HIP(c, hipMemcpy(ls.host_w, ls.dev, c->w_bytes, hipMemcpyDeviceToHost));
+    if (w_goes_host(l)) {
+      if (!ls.host_w) {     // the weights move to (or start in) host memory: they need their master
+        if ((rc = ensure_master(c, l, N))) return rc;
+        if (ls.dev_w && ls.has_w) SN_HIP(c, hipMemcpy(ls.host_w, ls.dev_w, c->w_bytes, hipMemcpyDeviceToHost));
+      }
+      if (ls.dev_w) {
+        SN_HIP(c, hipFree(ls.dev_w));
+        ls.dev_w = nullptr;
+      }
     }
-    if (!ls.host_kv) {
-      SN_HIP(c, hipHostMalloc((void**)&ls.host_kv, c->kv_bytes, hipHostMallocDefault));
-      std::memset(ls.host_kv, 0, c->kv_bytes);
-      SN_HIP(c, hipHostGetDevicePointer((void**)&ls.host_kv_dev, ls.host_kv, 0));
-    }
-    if (ls.dev) {
-      if (kv_used) SN_HIP(c, hipMemcpy(ls.host_kv, kv_of(ls.dev, c), kv_used, hipMemcpyDeviceToHost));
-      SN_HIP(c, hipFree(ls.dev));
-      ls.dev = nullptr;
+    if (kv_goes_host(l)) {
+      if (!ls.host_kv) {
+        SN_HIP(c, hipHostMalloc((void**)&ls.host_kv, c->kv_bytes, hipHostMallocDefault));
+        std::memset(ls.host_kv, 0, c->kv_bytes);
+        SN_HIP(c, hipHostGetDevicePointer((void**)&ls.host_kv_dev, ls.host_kv, 0));
+      }
+      if (ls.dev_kv) {
+        if (kv_used) SN_HIP(c, hipMemcpy(ls.host_kv, ls.dev_kv, kv_used, hipMemcpyDeviceToHost));
+        SN_HIP(c, hipFree(ls.dev_kv));
+        ls.dev_kv = nullptr;
+      }
     }
   }
   const int K = offloaded_count(L, N);
-  if (K == 0) {
-    for (auto& s : c->slot)
-      if (s) {
-        SN_HIP(c, hipFree(s));
-        s = nullptr;
-      }
+  for (int i = 0; i < 2; ++i) {
+    if ((K == 0 || !weights_travel(c->what)) && c->slot_w[i]) {
+      SN_HIP(c, hipFree(c->slot_w[i]));
+      c->slot_w[i] = nullptr;
+    }
+    if ((K == 0 || !kv_travels(c->what)) && c->slot_kv[i]) {
+      SN_HIP(c, hipFree(c->slot_kv[i]));
+      c->slot_kv[i] = nullptr;
+    }
   }
   for (int l = 0; l < L; ++l) {
     LayerState& ls = c->layers[l];
-    if (is_offloaded(L, N, l) || ls.dev) continue;
-    SN_HIP(c, hipMalloc((void**)&ls.dev, c->state_bytes));
-    if (ls.host_w) SN_HIP(c, hipMemcpy(ls.dev, ls.host_w, c->w_bytes, hipMemcpyHostToDevice));
-    if (ls.host_kv && ls.offloaded && kv_used)
-      SN_HIP(c, hipMemcpy(kv_of(ls.dev, c), ls.host_kv, kv_used, hipMemcpyHostToDevice));
-    else
-      SN_HIP(c, hipMemset(kv_of(ls.dev, c), 0, c->kv_bytes));
+    if (!w_goes_host(l) && !ls.dev_w) {
+      SN_HIP(c, hipMalloc((void**)&ls.dev_w, c->w_bytes));
+      if (ls.host_w) SN_HIP(c, hipMemcpy(ls.dev_w, ls.host_w, c->w_bytes, hipMemcpyHostToDevice));
+    }
+    if (!kv_goes_host(l) && !ls.dev_kv) {
+      SN_HIP(c, hipMalloc((void**)&ls.dev_kv, c->kv_bytes));
+      if (ls.host_kv && ls.kv_host && kv_used)      // the slice was live on the host until now
+        SN_HIP(c, hipMemcpy(ls.dev_kv, ls.host_kv, kv_used, hipMemcpyHostToDevice));
+      else
+        SN_HIP(c, hipMemset(ls.dev_kv, 0, c->kv_bytes));
+    }
   }
   if (K > 0)
-    for (auto& s : c->slot)
-      if (!s) SN_HIP(c, hipMalloc((void**)&s, c->state_bytes));
+    for (int i = 0; i < 2; ++i) {
+      if (weights_travel(c->what) && !c->slot_w[i]) SN_HIP(c, hipMalloc((void**)&c->slot_w[i], c->w_bytes));
+      if (kv_travels(c->what) && !c->slot_kv[i]) SN_HIP(c, hipMalloc((void**)&c->slot_kv[i], c->kv_bytes));
+    }
   for (int l = 0; l < L; ++l) {
     LayerState& ls = c->layers[l];
     ls.offloaded = is_offloaded(L, N, l);
+    ls.w_host = w_goes_host(l);
+    ls.kv_host = kv_goes_host(l);
     ls.trigger = ls.offloaded ? trigger_of(N, l, c->sched) : -1;
     ls.slot = 0;
   }
@@ -676,7 +736,7 @@ struct KTimer {   // optional per-kernel event pairs (timing level 2)
 
 // `pending`: split-K partial sums of the previous residual projection that the next reader of
 // the residual stream (a norm, or the final cast) folds in.
-int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepIndex& ix, int T, int B,
+int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, const StepIndex& ix, int T, int B,
               bool prefill, int n_qtiles, int S, Fold& pending) {
   const sn_model_shape& s = c->shape;
   const PackedLayout& p = c->pl;
@@ -684,7 +744,6 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* mirror_kv, const StepInd
   const int h = s.hidden, F = s.ffn, Hq = s.n_q_heads, Hkv = s.n_kv_heads, d = s.head_dim;
   const int qd = Hq * d;
   auto at = [&](uint64_t off) -> const void* { return off == kNone ? nullptr : base + off; };
-  uint8_t* kv = kv_of(base, c);
   hipStream_t st = c->compute;
   const bool small = !prefill;   // decode path: T == B <= 64
   KTimer kt{c, l, 0, c->timing >= 2};
@@ -852,7 +911,7 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
       if (!os.offloaded || os.trigger != l) continue;
       if (os.preissued) {            // already on its way (or here): issued during the previous iteration
         os.preissued = false;
-        c->last_h2d_bytes += (int64_t)(c->w_bytes + kv_used);
+        c->last_h2d_bytes += (int64_t)((os.w_host ? c->w_bytes : 0) + (os.kv_host ? kv_used : 0));
         ++c->last_preissued;
         continue;
       }
@@ -861,28 +920,30 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
       if (rc) return rc;
       c->last_h2d_bytes += bytes;
     }
-    uint8_t* base = ls.dev;
+    uint8_t* base = ls.dev_w;
+    uint8_t* kvbase = ls.dev_kv;
     uint8_t* mirror = nullptr;
     if (ls.offloaded) {
       SN_HIP(c, hipStreamWaitEvent(c->compute, c->ev_ready[par * L + l], 0));     // the fence "S" of Fig. 7
       SN_HIP(c, hipEventRecord(c->ev_after_wait[l], c->compute));
-      base = c->slot[ls.slot];
-      if (!prefill) mirror = ls.host_kv_dev;                                 // decode: rows written through
+      if (ls.w_host) base = c->slot_w[ls.slot];
+      if (ls.kv_host) kvbase = c->slot_kv[ls.slot];
+      if (ls.kv_host && !prefill) mirror = ls.host_kv_dev;                   // decode: rows written through
     }
-    int rc = run_layer(c, l, base, mirror, ix, T, B, prefill, n_qtiles, S, pending);
+    int rc = run_layer(c, l, base, kvbase, mirror, ix, T, B, prefill, n_qtiles, S, pending);
     if (rc) return rc;
     if (ls.offloaded) {
-      if (prefill) {
+      if (prefill && ls.kv_host) {
         SN_HIP(c, hipEventRecord(c->ev_done[l], c->compute));
         SN_HIP(c, hipStreamWaitEvent(c->d2h, c->ev_done[l], 0));
         SN_HIP(c, hipEventRecord(c->ev_d2h_start[l], c->d2h));
-        SN_HIP(c, hipMemcpyAsync(ls.host_kv, kv_of(base, c), kv_used, hipMemcpyDeviceToHost, c->d2h));
+        SN_HIP(c, hipMemcpyAsync(ls.host_kv, kvbase, kv_used, hipMemcpyDeviceToHost, c->d2h));
         SN_HIP(c, hipEventRecord(c->ev_d2h_end[l], c->d2h));
         SN_HIP(c, hipEventRecord(c->ev_slot_free[ls.slot], c->d2h));
         c->last_d2h_bytes += (int64_t)kv_used;
       } else {
         SN_HIP(c, hipEventRecord(c->ev_slot_free[ls.slot], c->compute));
-        c->last_d2h_bytes += (int64_t)B * (int64_t)kv_token_bytes(s);
+        if (ls.kv_host) c->last_d2h_bytes += (int64_t)B * (int64_t)kv_token_bytes(s);
       }
       c->slot_free_valid[ls.slot] = true;
       // Continuous schedule, decode: the loads do not stop at the iteration boundary.  With K layers
@@ -968,7 +1029,7 @@ extern "C" int sn_get_stats(sn_ctx* c, sn_step_stats* out) {
     ++out->n_offloaded;
     out->h2d_ns += std::max<int64_t>(0, elapsed_ns(c->ev_copy_start[c->last_par * L + l], c->ev_ready[c->last_par * L + l]));
     out->stall_ns += std::max<int64_t>(0, elapsed_ns(c->ev_layer[l], c->ev_after_wait[l]));
-    if (c->last_prefill) out->d2h_ns += std::max<int64_t>(0, elapsed_ns(c->ev_d2h_start[l], c->ev_d2h_end[l]));
+    if (c->last_prefill && ls.kv_host) out->d2h_ns += std::max<int64_t>(0, elapsed_ns(c->ev_d2h_start[l], c->ev_d2h_end[l]));
   }
   out->hidden_fraction = out->h2d_ns > 0 ? 1.0 - (double)std::min(out->stall_ns, out->h2d_ns) / (double)out->h2d_ns : 1.0;
   if (c->last_timing >= 2 && !c->kev.empty()) {
@@ -1002,8 +1063,8 @@ extern "C" int sn_time_kernel_class(sn_ctx* c, int32_t kernel_class, int32_t bat
   SN_HIP(c, hipEventRecord(c->ev_iter_start, c->compute));
   for (int r = 0; r < reps; ++r)
     for (const LayerState& ls : c->layers) {
-      if (!ls.dev) continue;
-      auto at = [&](uint64_t off) -> const void* { return off == kNone ? nullptr : ls.dev + off; };
+      if (!ls.dev_w) continue;
+      auto at = [&](uint64_t off) -> const void* { return off == kNone ? nullptr : ls.dev_w + off; };
       hipError_t e;
       switch (kernel_class) {
         case SN_K_QKV:
@@ -1124,20 +1185,20 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
     iter_est += c->prof_tc[l];
   }
 
-  // Transfer of each layer's state (weights; + KV prefix when decoding), timed while the
+  // Transfer of each layer's state -- the part of it that is kept on the host when the layer is
+  // host-resident (weights; + KV prefix when decoding) -- timed while the
   // compute stream runs iterations of the same kind: that is the condition under which
   // prefetches run, and copies are a little slower then than on an idle GPU.
-  uint8_t* dst = c->slot[0];
-  bool temp = false;
-  if (!dst) {
-    if (hipMalloc((void**)&dst, c->state_bytes) != hipSuccess) {
-      (void)hipFree(hin);
-      (void)hipFree(hout);
-      return fail(c, SN_E_NOMEM, "sn_profile_layers: device allocation failed");
-    }
-    temp = true;
+  // Destination: a scratch state of its own (the staging slots hold only the part that travels).
+  uint8_t* dst = nullptr;
+  const bool temp = true;
+  if (hipMalloc((void**)&dst, c->state_bytes) != hipSuccess) {
+    (void)hipFree(hin);
+    (void)hipFree(hout);
+    return fail(c, SN_E_NOMEM, "sn_profile_layers: device allocation failed");
   }
-  const uint64_t kv_used = is_prefill ? 0 : (uint64_t)c->kv_used_tokens * kv_token_bytes(s);
+  const bool copy_w = weights_travel(c->what);
+  const uint64_t kv_used = (is_prefill || !kv_travels(c->what)) ? 0 : (uint64_t)c->kv_used_tokens * kv_token_bytes(s);
   uint8_t* kv_src_tmp = nullptr;
   int64_t tx_est = 0;
   const int tx_reps = std::min(reps, 3);
@@ -1167,7 +1228,7 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
   }
   auto timed_copy = [&](int l) -> hipError_t {
     hipError_t e = hipEventRecord(c->ev_copy_start[l], c->h2d);
-    if (e == hipSuccess) e = hipMemcpyAsync(dst, w_srcs[l], c->w_bytes, hipMemcpyHostToDevice, c->h2d);
+    if (e == hipSuccess && copy_w) e = hipMemcpyAsync(dst, w_srcs[l], c->w_bytes, hipMemcpyHostToDevice, c->h2d);
     if (e == hipSuccess && kv_used) e = hipMemcpyAsync(dst + c->w_bytes, kv_srcs[l], kv_used, hipMemcpyHostToDevice, c->h2d);
     if (e == hipSuccess) e = hipEventRecord(c->ev_ready[l], c->h2d);
     return e;

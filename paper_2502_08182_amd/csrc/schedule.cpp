@@ -115,14 +115,41 @@ uint64_t resident_bytes(int L, int N, uint64_t state, uint64_t slot, uint64_t fi
   return (uint64_t)(L - K) * state + (K ? 2 * slot : 0) + fixed;
 }
 
-uint64_t max_tokens(int L, int N, uint64_t weight_bytes, uint64_t kv_token_bytes, uint64_t fixed, uint64_t budget) {
-  // states held on the GPU: resident layers, plus two staging slots when anything is offloaded;
-  // each is weights + tokens * kv_token_bytes
+// What a host-resident layer leaves on the GPU, and what a staging slot holds, when the layer keeps on
+// the host its whole state (0), only its weights (1) or only its KV slice (2).
+static uint64_t part_left_behind(uint64_t weight_bytes, uint64_t kv_bytes, int what) {
+  return what == 1 ? kv_bytes : what == 2 ? weight_bytes : 0;
+}
+
+uint64_t resident_bytes_of(int L, int N, uint64_t weight_bytes, uint64_t kv_bytes, uint64_t fixed, int what) {
   const int K = offloaded_count(L, N);
-  const unsigned __int128 states = (unsigned __int128)(L - K) + (K ? 2 : 0);
-  const unsigned __int128 base = states * weight_bytes + fixed;
-  if (kv_token_bytes == 0 || base > budget) return 0;
-  const unsigned __int128 t = ((unsigned __int128)budget - base) / (states * kv_token_bytes);
+  const uint64_t stays = part_left_behind(weight_bytes, kv_bytes, what);
+  const uint64_t travels = weight_bytes + kv_bytes - stays;
+  return (uint64_t)(L - K) * (weight_bytes + kv_bytes) + (uint64_t)K * stays + (K ? 2 * travels : 0) + fixed;
+}
+
+int max_interval_of(int L, uint64_t budget, uint64_t weight_bytes, uint64_t kv_bytes, uint64_t fixed, int what) {
+  if (budget == 0) return L + 1;
+  int best = 0;
+  for (int N = 1; N <= L + 1; ++N)
+    if (resident_bytes_of(L, N, weight_bytes, kv_bytes, fixed, what) <= budget) best = N;
+  return best;
+}
+
+uint64_t max_tokens(int L, int N, uint64_t weight_bytes, uint64_t kv_token_bytes, uint64_t fixed, uint64_t budget, int what) {
+  // The footprint is linear in the token count t: copies of the weights and copies of the KV slice
+  // (t * kv_token_bytes each).  GPU-resident layers hold both; a host-resident layer holds the part it
+  // leaves behind; the two staging slots (when anything is offloaded) hold the part that travels.
+  const int K = offloaded_count(L, N);
+  unsigned __int128 w_copies = (unsigned __int128)(L - K), kv_copies = w_copies;
+  if (K) {
+    if (what == 1) { kv_copies += K; w_copies += 2; }
+    else if (what == 2) { w_copies += K; kv_copies += 2; }
+    else { w_copies += 2; kv_copies += 2; }
+  }
+  const unsigned __int128 base = w_copies * weight_bytes + fixed;
+  if (kv_token_bytes == 0 || kv_copies == 0 || base > budget) return 0;
+  const unsigned __int128 t = ((unsigned __int128)budget - base) / (kv_copies * kv_token_bytes);
   return t > (unsigned __int128)UINT64_MAX ? UINT64_MAX : (uint64_t)t;
 }
 

@@ -13,6 +13,9 @@ int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64
 int min_interval(int L, const int64_t* tc, const int64_t* tx, int64_t slo, int sched = kSchedPaper);   // -1: none
 uint64_t resident_bytes(int L, int N, uint64_t state, uint64_t slot, uint64_t fixed);
 int max_interval(int L, uint64_t budget, uint64_t state, uint64_t slot, uint64_t fixed);
-uint64_t max_tokens(int L, int N, uint64_t weight_bytes, uint64_t kv_token_bytes, uint64_t fixed, uint64_t budget);
+// `what`: the part of a host-resident layer's state kept on the host -- 0 whole state, 1 weights, 2 KV slice
+uint64_t resident_bytes_of(int L, int N, uint64_t weight_bytes, uint64_t kv_bytes, uint64_t fixed, int what);
+int max_interval_of(int L, uint64_t budget, uint64_t weight_bytes, uint64_t kv_bytes, uint64_t fixed, int what);
+uint64_t max_tokens(int L, int N, uint64_t weight_bytes, uint64_t kv_token_bytes, uint64_t fixed, uint64_t budget, int what = 0);
 int32_t paper_rule(int L, int64_t t_trans, int64_t slo);
 }  // namespace sn

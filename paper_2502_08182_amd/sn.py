@@ -18,6 +18,7 @@ SN_F16, SN_BF16 = 0, 1
 SN_ACT_GELU, SN_ACT_SWIGLU = 0, 1
 SN_NORM_LN, SN_NORM_RMS = 0, 1
 SN_SCHED_PAPER, SN_SCHED_EAGER, SN_SCHED_CONTINUOUS = 0, 1, 2
+SN_OFFLOAD_STATE, SN_OFFLOAD_WEIGHTS, SN_OFFLOAD_KV = 0, 1, 2
 SN_OK, SN_E_INVAL, SN_E_STATE, SN_E_BUDGET, SN_E_INFEASIBLE, SN_E_NOMEM, SN_E_HIP = 0, -1, -2, -3, -4, -5, -6
 SN_K_NAMES = ("norm", "qkv", "rope_append", "attn", "oproj", "ffn_up", "ffn_down", "other")
 ERROR_NAMES = {-1: "SN_E_INVAL", -2: "SN_E_STATE", -3: "SN_E_BUDGET", -4: "SN_E_INFEASIBLE",
@@ -30,6 +31,7 @@ EXPORTS = (
     "sn_set_timing", "sn_set_kernel_timing_class", "sn_time_kernel_class", "sn_get_stats", "sn_get_layer_times", "sn_profile_layers", "sn_timeline",
     "sn_pick_interval_from_times", "sn_pick_interval", "sn_paper_rule",
     "sn_set_schedule", "sn_placement_sched", "sn_timeline_sched", "sn_pick_interval_from_times_sched",
+    "sn_set_offload_part", "sn_offload_part", "sn_max_tokens_part", "sn_resident_bytes_part",
 )
 
 
@@ -95,6 +97,10 @@ def lib() -> C.CDLL:
         "sn_resident_bytes": (u64, [ctx, i32]),
         "sn_max_interval": (i32, [ctx]),
         "sn_max_tokens": (u64, [i32, i32, u64, u64, u64, u64]),
+        "sn_max_tokens_part": (u64, [i32, i32, u64, u64, u64, u64, i32]),
+        "sn_resident_bytes_part": (u64, [i32, i32, u64, u64, u64, i32]),
+        "sn_set_offload_part": (C.c_int, [ctx, i32]),
+        "sn_offload_part": (i32, [ctx]),
         "sn_placement": (C.c_int, [i32, i32, C.POINTER(C.c_uint8), pi32]),
         "sn_kv_reset": (C.c_int, [ctx, i32, pi32]),
         "sn_step": (C.c_int, [ctx, C.POINTER(sn_batch), C.POINTER(sn_kv), C.c_void_p]),
@@ -200,6 +206,22 @@ def sn_max_interval(ctx) -> int:
 
 def sn_max_tokens(L: int, N: int, weight_bytes: int, kv_token_bytes: int, fixed_bytes: int, budget: int) -> int:
     return int(lib().sn_max_tokens(L, N, weight_bytes, kv_token_bytes, fixed_bytes, budget))
+
+
+def sn_max_tokens_part(L: int, N: int, weight_bytes: int, kv_token_bytes: int, fixed_bytes: int, budget: int, what: int) -> int:
+    return int(lib().sn_max_tokens_part(L, N, weight_bytes, kv_token_bytes, fixed_bytes, budget, what))
+
+
+def sn_resident_bytes_part(L: int, N: int, weight_bytes: int, kv_bytes: int, fixed_bytes: int, what: int) -> int:
+    return int(lib().sn_resident_bytes_part(L, N, weight_bytes, kv_bytes, fixed_bytes, what))
+
+
+def sn_set_offload_part(ctx, what: int) -> None:
+    _check(lib().sn_set_offload_part(ctx, what), ctx)
+
+
+def sn_offload_part(ctx) -> int:
+    return int(lib().sn_offload_part(ctx))
 
 
 def sn_layers(ctx) -> int:

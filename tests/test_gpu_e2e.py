@@ -169,6 +169,60 @@ def test_continuous_schedule_changes_timing_only(c1):
         assert np.array_equal(pre, ref[0]) and np.array_equal(np.stack(outs), ref[1])
 
 
+def test_weights_only_and_kv_only_offloading(c1):
+    """Host-resident layers may keep only their weights or only their KV slice on the host: same bits
+    for every interval and schedule; a decode step then loads exactly the part that lives on the host
+    (the two parts add up to the whole state's load); the footprints add up the same way; switching
+    the part between decode steps keeps the cache."""
+    w, layers, prompt, table, *_ = c1
+    L = w.shape.n_layers
+    ref = gpu_run(w, layers, prompt, table, 0)
+    parts = (sn.SN_OFFLOAD_STATE, sn.SN_OFFLOAD_WEIGHTS, sn.SN_OFFLOAD_KV)
+    for N in (1, 2, 3, 4):
+        moved, held = {}, {}
+        for what in parts:
+            with Session(w.shape, w.batch, w.max_seq) as se:
+                se.load_synthetic_weights(layers=layers)
+                sn.sn_set_offload_part(se.ctx, what)
+                assert sn.sn_offload_part(se.ctx) == what
+                se.place(N)
+                for sched in (sn.SN_SCHED_PAPER, sn.SN_SCHED_CONTINUOUS):
+                    sn.sn_set_schedule(se.ctx, sched)
+                    pre, dec = se.run_workload(w, prompt, table)
+                    assert np.array_equal(pre, ref[0]) and np.array_equal(dec, ref[1]), (N, what, sched)
+                st = se.stats()
+                moved[what], held[what] = st["h2d_bytes"], st["resident_bytes"]
+                assert st["n_offloaded"] == L // N
+                none = sn.sn_resident_bytes(se.ctx, 0)
+        assert moved[sn.SN_OFFLOAD_WEIGHTS] > 0 and moved[sn.SN_OFFLOAD_KV] > 0
+        assert moved[sn.SN_OFFLOAD_WEIGHTS] + moved[sn.SN_OFFLOAD_KV] == moved[sn.SN_OFFLOAD_STATE]
+        assert held[sn.SN_OFFLOAD_WEIGHTS] + held[sn.SN_OFFLOAD_KV] == held[sn.SN_OFFLOAD_STATE] + none
+    # prefill from empty caches: nothing to load when only the KV slice is on the host, weights otherwise
+    with Session(w.shape, w.batch, w.max_seq) as se:
+        se.load_synthetic_weights(layers=layers)
+        sn.sn_set_offload_part(se.ctx, sn.SN_OFFLOAD_KV)
+        se.place(2)
+        se.kv_reset([p + w.decode_steps for p in w.prompt_lens])
+        se.step(list(w.prompt_lens), True, prompt)
+        st = se.stats()
+        assert st["h2d_bytes"] == 0 and st["d2h_bytes"] > 0
+        # the part changes under a live cache, before every decode step
+        outs = []
+        order = [sn.SN_OFFLOAD_WEIGHTS, sn.SN_OFFLOAD_STATE, sn.SN_OFFLOAD_KV, sn.SN_OFFLOAD_KV,
+                 sn.SN_OFFLOAD_WEIGHTS, sn.SN_OFFLOAD_KV, sn.SN_OFFLOAD_STATE, sn.SN_OFFLOAD_WEIGHTS]
+        for t, what in enumerate(order):
+            sn.sn_set_offload_part(se.ctx, what)
+            if t == 3:
+                se.place(1)
+            outs.append(se.step([1] * w.batch, False, table[t]))
+            if what == sn.SN_OFFLOAD_WEIGHTS:
+                assert se.stats()["d2h_bytes"] == 0
+        assert np.array_equal(np.stack(outs), ref[1])
+        with pytest.raises(sn.SnError) as e:
+            sn.sn_set_offload_part(se.ctx, 5)
+        assert e.value.code == sn.SN_E_INVAL
+
+
 def test_replacing_between_iterations_keeps_the_cache(c1):
     """Sec. 4.2: a new interval is applied before the next iteration; live KV must move with it."""
     w, layers, prompt, table, *_ = c1

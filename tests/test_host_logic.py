@@ -233,3 +233,20 @@ def test_continuous_schedule_agrees_with_the_oracle():
             assert e.code == sn.SN_E_INFEASIBLE
             got_n = None
         assert got_n == want_n
+
+
+def test_capacity_accounting_by_offloaded_part_agrees_with_the_oracle():
+    """Footprint and max length when host-resident layers keep their whole state, only their weights or
+    only their KV slice on the host: library = oracle, exactly."""
+    rnd = random.Random(41)
+    parts = {sn.SN_OFFLOAD_STATE: osch.STATE, sn.SN_OFFLOAD_WEIGHTS: osch.WEIGHTS, sn.SN_OFFLOAD_KV: osch.KV}
+    for _ in range(1500):
+        L, N = rnd.randint(1, 96), rnd.randint(0, 98)
+        wb, kvb, fx = rnd.randint(0, 3 * 10**9), rnd.randint(0, 3 * 10**9), rnd.randint(0, 10**10)
+        kt = rnd.randint(1, 10**6)
+        budget = rnd.choice([0, rnd.randint(0, 300 * 10**9)])
+        for what, o_what in parts.items():
+            assert sn.sn_resident_bytes_part(L, N, wb, kvb, fx, what) == osch.resident_bytes_of(L, N, wb, kvb, fx, o_what)
+            assert sn.sn_max_tokens_part(L, N, wb, kt, fx, budget, what) == osch.max_tokens(L, N if N else L + 1, wb, kt, fx, budget, o_what)
+        assert sn.sn_max_tokens_part(L, N, wb, kt, fx, budget, sn.SN_OFFLOAD_STATE) == sn.sn_max_tokens(L, N, wb, kt, fx, budget)
+    assert sn.sn_resident_bytes_part(4, 2, 1, 1, 1, 3) == 0 and sn.sn_max_tokens_part(4, 2, 1, 1, 1, 100, -1) == 0
