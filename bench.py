@@ -63,6 +63,8 @@ def parse():
                          "TPOT SLO stays fixed); 0: off")
     ap.add_argument("--no-continuous", action="store_true",
                     help="skip the decode runs with loads issued across the iteration boundary")
+    ap.add_argument("--no-parts", action="store_true",
+                    help="skip the decode runs with only the weights / only the KV slices of host-resident layers on the host")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="draw only this many different random layer blobs (0: every layer its own)")
@@ -325,7 +327,9 @@ def main():
         base_tok = sn.sn_max_tokens(L, 0, wl, kvtok, 0, w.hbm_budget)
         out["max_length_vs_interval"] = {
             "hbm_budget_GB": w.hbm_budget / 1e9, "workspace": "excluded",
-            "rows": [{"interval": int(N), "max_tokens": int(sn.sn_max_tokens(L, N, wl, kvtok, 0, w.hbm_budget))}
+            "rows": [{"interval": int(N), "max_tokens": int(sn.sn_max_tokens(L, N, wl, kvtok, 0, w.hbm_budget)),
+                      "max_tokens_weights_only": int(sn.sn_max_tokens_part(L, N, wl, kvtok, 0, w.hbm_budget, sn.SN_OFFLOAD_WEIGHTS)),
+                      "max_tokens_kv_only": int(sn.sn_max_tokens_part(L, N, wl, kvtok, 0, w.hbm_budget, sn.SN_OFFLOAD_KV))}
                      for N in sorted({1, 2, 3, 4, 6, 8, 16, L, L + 1}) if N <= L + 1],
             "no_offloading_tokens": int(base_tok)}
 
@@ -409,6 +413,46 @@ def main():
                 f"hidden {cont[-1]['hidden_fraction']:.3f} issued ahead {cont[-1]['loads_issued_ahead_per_step']} -> {cont[-1]['tokens_per_s']:.1f} tok/s")
         sn.sn_set_schedule(se.ctx, sn.SN_SCHED_PAPER)
         out["decode_continuous_schedule"] = cont
+
+    # ---- host-resident layers that keep only their weights, or only their KV slice, on the host: smaller
+    # loads, so the same SLO admits more layers (at the price of the part that stays on the GPU) ---------------
+    if not a.no_parts:
+        parts = []
+        for what, name in ((sn.SN_OFFLOAD_WEIGHTS, "weights"), (sn.SN_OFFLOAD_KV, "kv")):
+            se.place(0)
+            sn.sn_set_offload_part(se.ctx, what)
+            tcw, txw = sn.sn_profile_layers(se.ctx, L, False, B, seq_prof, reps=3)
+            row = {"part_on_host": name, "layer_transfer_us_median": float(np.median(txw)) / 1e3,
+                   "rho_transfer_over_compute": float(np.median(txw) / np.median(tcw)), "points": []}
+            for sched, sname in ((sn.SN_SCHED_PAPER, "paper"), (sn.SN_SCHED_CONTINUOUS, "continuous")):
+                sn.sn_set_schedule(se.ctx, sched)
+                slo_f = int(a.slo_factor * tpot0_ns)
+                try:
+                    n_f = sn.sn_pick_interval_from_times_sched(tcw, txw, int(slo_f * (1.0 - a.guard)), L + 1, sched)
+                except sn.SnError:
+                    n_f = L + 1
+                se.place(n_f)
+                n_c = max(4, min(K, 8))
+                pst, pwall, _ = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, n_c, W)
+                pit = np.array([d["iter_ns"] for d in pst], dtype=np.float64)
+                k_f = int(pst[-1]["n_offloaded"])
+                pred, _ = sn.sn_timeline_sched(tcw, txw, n_f, sched)
+                host_gb = k_f * (sn.sn_layer_blob_bytes(se.cshape) if name == "weights" else seq_prof * B * kvtok) / 1e9
+                row["points"].append({"schedule": sname, "slo_factor": a.slo_factor, "picked_interval": int(n_f), "n_offloaded": k_f,
+                                      "tpot_median_ms": float(np.median(pit)) / 1e6, "tpot_max_ms": float(pit.max()) / 1e6,
+                                      "predicted_ms": pred / 1e6, "every_iteration_within_slo": bool((pit <= slo_f).all()),
+                                      "h2d_bytes_per_step": pst[-1]["h2d_bytes"], "host_resident_GB": host_gb,
+                                      "resident_GB": sn.sn_resident_bytes(se.ctx, n_f) / 1e9,
+                                      "tokens_per_s_at_median_tpot": B / (float(np.median(pit)) * 1e-9)})
+                log(f"[bench] {name} only on the host, {sname} schedule, SLO {a.slo_factor}x: tx {row['layer_transfer_us_median']:.0f} us "
+                    f"(rho {row['rho_transfer_over_compute']:.1f}); picked N={n_f} (K={k_f}, {host_gb:.2f} GB on the host), TPOT median "
+                    f"{np.median(pit) / 1e6:.3f} max {pit.max() / 1e6:.3f} (predicted {pred / 1e6:.3f}) "
+                    f"within={row['points'][-1]['every_iteration_within_slo']}")
+            sn.sn_set_schedule(se.ctx, sn.SN_SCHED_PAPER)
+            parts.append(row)
+        se.place(0)
+        sn.sn_set_offload_part(se.ctx, sn.SN_OFFLOAD_STATE)
+        out["decode_by_offloaded_part"] = parts
 
     # ---- the prefill phase has its own profile and its own interval (Sec. 4.4, separation of
     # prefill and decoding): TTFT SLOs relative to the all-resident prefill iteration ------------
