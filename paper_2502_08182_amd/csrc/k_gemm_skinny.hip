@@ -6,9 +6,13 @@
 // ((nb * K/32) + kb) * 1 KiB, so a wavefront reads each tile as one fully coalesced
 // 1 KiB request and feeds it straight to v_mfma_f32_16x16x32 as the A operand
 // (16 output features x 32 inputs); the B operand is the activation tile
-// (32 inputs x 16 token rows).  One workgroup owns 16*C output features; its KS
-// wavefronts split K into contiguous ranges and their fp32 partial tiles are summed
-// through LDS in a fixed order (deterministic).
+// (32 inputs x 16 token rows).  A wavefront owns 16*C output features.  The KS
+// wavefronts of a workgroup form NWN columns of KS/NWN: wavefronts side by side cover
+// adjacent feature groups over the SAME K range, so the activation fragments they
+// read are the same ones at about the same time and come from the L1 cache instead of
+// L2 (at 64 token rows the activation reads cost a fifth of the weight stream's rate
+// otherwise); wavefronts of one column split K into contiguous ranges and their fp32
+// partial tiles are summed through LDS in a fixed order (deterministic).
 #include "kernels.h"
 #include "common.h"
 
@@ -17,10 +21,17 @@ namespace sn {
 // MT: 16-row tiles of token rows; C: adjacent 16-column blocks per wavefront (each
 // activation fragment read from L2 is reused for C weight tiles, keeping activation
 // traffic at or below weight traffic for every M <= 64).
-template <class T, int MT, int C, int EPI>
-__global__ __launch_bounds__(1024) void gemm_skinny_kernel(
+// WMAX: most wavefronts a workgroup of this instance may have (bounds the register budget:
+// 16 -> 128 registers, 8 or fewer -> 256, which the 4-row-tile variants need to stay out of
+// scratch memory).
+// SHARE: the instance supports more than one column of wavefronts (NWN_ > 1); without it the
+// column count is the constant 1, which saves the registers the 4-row-tile split-K variants need
+// to keep four wavefronts per SIMD.
+template <class T, int MT, int C, int EPI, int WMAX, bool SHARE>
+__global__ __launch_bounds__(WMAX * 64) void gemm_skinny_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
-    void* __restrict__ out, int M, int N, int K, int xpacked, int opacked) {
+    void* __restrict__ out, int M, int N, int K, int xpacked, int opacked, int NWN_) {
+  const int NWN = SHARE ? NWN_ : 1;
   constexpr bool DUAL = EPI == EPI_SWIGLU16;
   static_assert(!DUAL || C % 2 == 0, "SwiGLU needs gate/up pairs");
   constexpr int U = C >= 4 ? 1 : (C == 2 ? 2 : 4);     // k-blocks in flight per column block
@@ -34,10 +45,11 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
   const int per_wg = (KB + gridDim.y - 1) / gridDim.y;
   const int g0 = blockIdx.y * per_wg;
   const int g1 = min(KB, g0 + per_wg);
-  const int per = (max(g1 - g0, 0) + KS - 1) / KS;
-  const int kb0 = g0 + wave * per;
+  const int wn = wave % NWN, wk = wave / NWN, KSK = KS / NWN;   // column of wavefronts, position in it
+  const int per = (max(g1 - g0, 0) + KSK - 1) / KSK;
+  const int kb0 = g0 + wk * per;
   const int kb1 = min(g1, kb0 + per);
-  const int cb = blockIdx.x * C;                       // first 16-row block of the weight matrix
+  const int cb = (blockIdx.x * NWN + wn) * C;          // first 16-row block of the weight matrix
 
   const uint16_t* wp = W + ((size_t)cb * KB) * 512 + lane * 8;
   const size_t wstride = (size_t)KB * 512;             // next column block
@@ -62,10 +74,11 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
   // Every wavefront walks its K range starting at a different rotation.  Tile rows of the
   // weight matrix lie a power of two apart, so wavefronts that all start at the beginning of
   // their range march over the HBM channels in lock-step (measured: 4.8 vs 6.1 TB/s on a
-  // 4096 x 16384 matrix).  The rotation is a fixed function of (column group, wavefront), so
-  // the summation order, and with it the result, stays reproducible.
+  // 4096 x 16384 matrix).  The rotation is a fixed function of (workgroup, K range), so the
+  // summation order, and with it the result, stays reproducible -- and wavefronts side by side
+  // walk the same k-blocks at the same time.
   const int len = max(kb1 - kb0, 0);
-  const int rot = len > 0 ? ((blockIdx.x + wave * 5 + blockIdx.y * 3) * 4) % len : 0;
+  const int rot = len > 0 ? ((blockIdx.x + wk * 5 + blockIdx.y * 3) * 4) % len : 0;
   for (int seg = 0; seg < 2; ++seg) {
     int kb = seg == 0 ? kb0 + rot : kb0;
     const int kend = seg == 0 ? kb1 : kb0 + rot;
@@ -121,16 +134,20 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
       *reinterpret_cast<f32x4*>(red + ((size_t)(wave * C + c) * 64 + lane) * 4) = acc[mt][c];
     __syncthreads();
     const int m = mt * 16 + (lane & 15);
-    if (wave < ITEMS && m < M) {
-      const int c0 = DUAL ? wave * 2 : wave;
+    // epilogue work items: (column of wavefronts, output block [pair]); dealt round-robin to the wavefronts
+    for (int item = wave; item < NWN * ITEMS; item += SHARE ? KS : ITEMS) {   // one pass at most when !SHARE
+      if (m >= M) break;
+      const int wn_i = item / ITEMS, it = item % ITEMS;
+      const int cb_i = (blockIdx.x * NWN + wn_i) * C;
+      const int c0 = DUAL ? it * 2 : it;
       f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int w = 0; w < KS; ++w) {
-        s0 += *reinterpret_cast<const f32x4*>(red + ((size_t)(w * C + c0) * 64 + lane) * 4);
-        if (DUAL) s1 += *reinterpret_cast<const f32x4*>(red + ((size_t)(w * C + c0 + 1) * 64 + lane) * 4);
+      for (int w = 0; w < KSK; ++w) {
+        s0 += *reinterpret_cast<const f32x4*>(red + ((size_t)((w * NWN + wn_i) * C + c0) * 64 + lane) * 4);
+        if (DUAL) s1 += *reinterpret_cast<const f32x4*>(red + ((size_t)((w * NWN + wn_i) * C + c0 + 1) * 64 + lane) * 4);
       }
       if (EPI == EPI_SWIGLU16) {
         const int F = N >> 1;
-        const int n = ((cb >> 1) + wave) * 16 + nl;
+        const int n = ((cb_i >> 1) + it) * 16 + nl;
         u16x4 o;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -144,7 +161,7 @@ __global__ __launch_bounds__(1024) void gemm_skinny_kernel(
         const size_t at = opacked ? packed_off(m, n, F >> 5) : (size_t)m * F + n;
         *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + at) = o;
       } else {
-        const int n = (cb + c0) * 16 + nl;
+        const int n = (cb_i + c0) * 16 + nl;
         if (EPI == EPI_PART32) {
           // the bias goes into plane 0 here, not into the later fold: the fold runs inside the NEXT layer,
           // when this layer's weight record (a staging slot, if the layer is host-resident) may already
@@ -185,30 +202,44 @@ static int pick_ks(int groups, int KB) {
   return ks;
 }
 
-template <class T, int MT, int C>
-static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
-                            int M, int N, int K, int splits, int xpacked, int opacked, hipStream_t st) {
-  const int KB = K / 32;
-  const int groups = N / (16 * C);
-  const int ks = epi == EPI_PART32 ? 4 : pick_ks(groups, KB);
+// Columns of wavefronts that share their activation reads (see the kernel).  Sharing pays
+// while a workgroup per compute unit is left (>= 200 workgroups) -- measured at 64 rows:
+// 57344 x 8192 4.9 -> 5.9 TB/s, at 32 rows: 27648 x 5120 4.8 -> 5.7 TB/s; with few feature
+// groups (10240 x 8192 at 64 rows: 160) it only starves the chip.  At 16 rows or fewer the
+// wavefronts of a column must also keep a long K run each (>= 128 k-blocks; 28672 x 7168:
+// 6.0 -> 6.4 TB/s), or the shorter kernels lose more at start-up than the reads gain.
+static int pick_columns(int MT, int groups, int KB, int ks) {
+  for (int nwn = MT == 1 ? 8 : 4; nwn > 1; nwn >>= 1) {
+    if (ks % nwn || groups % nwn || groups / nwn < 200) continue;
+    if (MT == 1 && KB * nwn / ks < 128) continue;
+    return nwn;
+  }
+  return 1;
+}
+
+template <class T, int MT, int C, int WMAX, bool SHARE>
+static hipError_t launch_w(int epi, int ks, int nwn, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
+                           int M, int N, int K, int splits, int xpacked, int opacked, hipStream_t st) {
+  const int groups = N / (16 * C * nwn);
   const size_t lds = (size_t)ks * C * 64 * 4 * sizeof(float);     // <= 64 KiB (ks <= 16, C <= 4)
   dim3 grid(groups, epi == EPI_PART32 ? splits : 1), block(ks * 64);
+  if (ks > WMAX || ks % nwn || (N / (16 * C)) % nwn || (!SHARE && nwn != 1)) return hipErrorInvalidValue;
   switch (epi) {
     case EPI_PART32:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_PART32>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_PART32, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
       break;
     case EPI_STORE16:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_STORE16>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_STORE16, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
       break;
     case EPI_GELU16:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_GELU16>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_GELU16, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
       break;
     case EPI_RESID32:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_RESID32>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_RESID32, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
       break;
     case EPI_SWIGLU16:
       if constexpr (C % 2 == 0) {
-        SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_SWIGLU16>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked);
+        SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_SWIGLU16, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
         break;
       }
       return hipErrorInvalidValue;
@@ -216,6 +247,25 @@ static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const
       return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+template <class T, int MT, int C>
+static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
+                            int M, int N, int K, int splits, int xpacked, int opacked, hipStream_t st) {
+  const int KB = K / 32;
+  const int groups = N / (16 * C);
+  if (epi == EPI_PART32)        // 4 wavefronts; the K split across workgroups provides the parallelism
+    return launch_w<T, MT, C, 16, false>(epi, 4, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+  if constexpr (MT >= 3) {      // 8 wavefronts at most: twice the registers, nothing spills
+    const int nwn = pick_columns(MT, groups, KB, 8);
+    if (nwn > 1) return launch_w<T, MT, C, 8, true>(epi, 8, nwn, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    return launch_w<T, MT, C, 8, false>(epi, 8, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+  } else {
+    const int ks = pick_ks(groups, KB);
+    const int nwn = pick_columns(MT, groups, KB, ks);
+    if (nwn > 1) return launch_w<T, MT, C, 16, true>(epi, ks, nwn, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    return launch_w<T, MT, C, 16, false>(epi, ks, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+  }
 }
 
 // Column blocks per wavefront: as many as row tiles (activation traffic <= weight

@@ -104,6 +104,22 @@ def test_gemm_skinny(dtype, epi):
     _gemm_case(dtype, K.PATH_SKINNY, epi, 5, 4096, 1024, bias=True, seed=20)     # 16-way K split
 
 
+@pytest.mark.parametrize("epi", [0, 2, 3])
+def test_gemm_skinny_wide(epi):
+    """Wide weight matrices switch the decode GEMM to workgroups whose wavefronts stand side by side over
+    the features and share their activation reads (2, 4 or 8 columns of wavefronts, chosen from the number
+    of feature groups, the row count and the length of K); every row-tile count, ragged rows."""
+    wide = 2 if epi == K.EPI_SWIGLU16 else 1
+    cases = [(64, 28672, 96),       # 4 row tiles, 448 feature groups of 64: 2 columns
+             (50, 51200, 64),       # 4 row tiles, 800 groups: 4 columns
+             (40, 25600, 96),       # 3 row tiles, 400 groups: 2 columns
+             (20, 25600, 160),      # 2 row tiles, 800 groups of 32: 4 columns
+             (8, 6400, 16384),      # 1 row tile, 400 groups of 16, long K: 2 columns
+             (13, 25600, 4096)]     # 1 row tile, 1600 groups: 8 columns
+    for i, (M, Nw, Kd) in enumerate(cases):
+        _gemm_case("f16", K.PATH_SKINNY, epi, M, Nw // wide, Kd, bias=(i % 2 == 0), seed=70 + i)
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3])
 def test_gemm_tile(dtype, epi):
