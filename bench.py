@@ -230,6 +230,28 @@ def main():
     log(f"[bench] all-resident: TPOT median {tpot0_ns / 1e6:.3f} ms (max {it0.max() / 1e6:.3f}), wall {wall0:.3f} ms/step, "
         f"prefill {pre0['iter_ns'] / 1e6:.2f} ms; SLO = {a.slo_factor} x = {slo_ns / 1e6:.3f} ms")
 
+    # ---- where the all-resident decode step spends its time: every launch bracketed by HIP events,
+    # summed per kernel class; algorithmic bytes per class over that time -------------------------------
+    stk, _, _ = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, 4, W, timing_class=-1)
+    kvtok0 = s.kv_bytes_per_token
+    len_k = p_mean + W + 2
+    n_up0 = s.ffn * (2 if s.act == "swiglu" else 1)
+    qd0 = s.n_q_heads * s.head_dim
+    class_bytes = {"qkv": (qd0 + 2 * s.n_kv_heads * s.head_dim) * s.hidden * 2, "attn": len_k * B * kvtok0,
+                   "oproj": s.hidden * qd0 * 2, "ffn_up": n_up0 * s.hidden * 2, "ffn_down": s.hidden * s.ffn * 2}
+    breakdown = {}
+    for name in ("norm", "qkv", "attn", "oproj", "ffn_up", "ffn_down"):
+        ns = float(np.median([d["kernel_ns"][name] for d in stk]))
+        calls = int(stk[-1]["kernel_calls"][name])
+        row = {"us_per_layer": ns / L / 1e3, "launches_per_layer": calls / L}
+        if name in class_bytes and ns > 0:
+            row["algorithmic_MB_per_layer"] = class_bytes[name] / 1e6
+            row["GBps"] = class_bytes[name] * L / (ns * 1e-9) / 1e9
+            row["frac_of_hbm_peak"] = row["GBps"] * 1e9 / HBM_PEAK
+        breakdown[name] = row
+    log("[bench] decode layer, per kernel class (us per layer, TB/s): " + ", ".join(
+        f"{k} {v['us_per_layer']:.1f}" + (f" ({v['GBps'] / 1e3:.2f})" if "GBps" in v else "") for k, v in breakdown.items()))
+
     # ---- profile and pick ------------------------------------------------------------------
     seq_prof = p_mean + W + K // 2
     tc, tx = sn.sn_profile_layers(se.ctx, L, False, B, seq_prof, reps=5)
@@ -315,6 +337,7 @@ def main():
         "hbm_step": {"algorithmic_bytes_per_step": step_bytes, "all_resident_GBps": step_bytes / (tpot0_ns * 1e-9) / 1e9,
                      "frac_of_peak": step_bytes / (tpot0_ns * 1e-9) / HBM_PEAK,
                      "roofline_tokens_per_s": B * HBM_PEAK / step_bytes},
+        "decode_layer_breakdown": breakdown,
         "prefill": {"iter_ms_all_resident": pre0["iter_ns"] / 1e6, "iter_ms_at_interval": pre["iter_ns"] / 1e6,
                     "tokens": T, "algorithmic_tflop": pre_flops / 1e12,
                     "all_resident_TFLOPs": pre_flops / (pre0["iter_ns"] * 1e-9) / 1e12,
