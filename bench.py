@@ -230,27 +230,28 @@ def main():
     log(f"[bench] all-resident: TPOT median {tpot0_ns / 1e6:.3f} ms (max {it0.max() / 1e6:.3f}), wall {wall0:.3f} ms/step, "
         f"prefill {pre0['iter_ns'] / 1e6:.2f} ms; SLO = {a.slo_factor} x = {slo_ns / 1e6:.3f} ms")
 
-    # ---- where the all-resident decode step spends its time: every launch bracketed by HIP events,
-    # summed per kernel class; algorithmic bytes per class over that time -------------------------------
-    stk, _, _ = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, 4, W, timing_class=-1)
+    # ---- where the all-resident decode step spends its time: each projection class timed alone, back to back
+    # over every layer's own weights (one pair of HIP events around the region: bracketing single launches
+    # would add microseconds to each); attention, the norms and the casts are what remains of the layer time ----
     kvtok0 = s.kv_bytes_per_token
-    len_k = p_mean + W + 2
     n_up0 = s.ffn * (2 if s.act == "swiglu" else 1)
     qd0 = s.n_q_heads * s.head_dim
-    class_bytes = {"qkv": (qd0 + 2 * s.n_kv_heads * s.head_dim) * s.hidden * 2, "attn": len_k * B * kvtok0,
-                   "oproj": s.hidden * qd0 * 2, "ffn_up": n_up0 * s.hidden * 2, "ffn_down": s.hidden * s.ffn * 2}
+    class_bytes = {"qkv": (qd0 + 2 * s.n_kv_heads * s.head_dim) * s.hidden * 2, "oproj": s.hidden * qd0 * 2,
+                   "ffn_up": n_up0 * s.hidden * 2, "ffn_down": s.hidden * s.ffn * 2}
     breakdown = {}
-    for name in ("norm", "qkv", "attn", "oproj", "ffn_up", "ffn_down"):
-        ns = float(np.median([d["kernel_ns"][name] for d in stk]))
-        calls = int(stk[-1]["kernel_calls"][name])
-        row = {"us_per_layer": ns / L / 1e3, "launches_per_layer": calls / L}
-        if name in class_bytes and ns > 0:
-            row["algorithmic_MB_per_layer"] = class_bytes[name] / 1e6
-            row["GBps"] = class_bytes[name] * L / (ns * 1e-9) / 1e9
-            row["frac_of_hbm_peak"] = row["GBps"] * 1e9 / HBM_PEAK
-        breakdown[name] = row
-    log("[bench] decode layer, per kernel class (us per layer, TB/s): " + ", ".join(
-        f"{k} {v['us_per_layer']:.1f}" + (f" ({v['GBps'] / 1e3:.2f})" if "GBps" in v else "") for k, v in breakdown.items()))
+    for name, cls in (("qkv", 1), ("oproj", 4), ("ffn_up", 5), ("ffn_down", 6)):
+        ns, calls = sn.sn_time_kernel_class(se.ctx, cls, B, reps=2)
+        us = ns / max(calls, 1) / 1e3
+        gbps = class_bytes[name] / (us * 1e-6) / 1e9
+        breakdown[name] = {"us_per_launch": us, "weight_MB": class_bytes[name] / 1e6, "GBps": gbps, "frac_of_hbm_peak": gbps * 1e9 / HBM_PEAK}
+    layer_us = tpot0_ns / L / 1e3
+    rest_us = layer_us - sum(v["us_per_launch"] for v in breakdown.values())
+    kv_mb = (p_mean + W + K // 2) * B * kvtok0 / 1e6
+    breakdown["attention_norms_casts"] = {"us_per_layer": rest_us, "kv_MB_per_layer": kv_mb}
+    breakdown["layer_us"] = layer_us
+    log("[bench] decode layer %.1f us: " % layer_us + ", ".join(
+        f"{k} {v['us_per_launch']:.1f} us ({v['GBps'] / 1e3:.2f} TB/s)" for k, v in breakdown.items() if isinstance(v, dict) and "GBps" in v)
+        + f", attention + norms + casts {rest_us:.1f} us (KV {kv_mb:.0f} MB)")
 
     # ---- profile and pick ------------------------------------------------------------------
     seq_prof = p_mean + W + K // 2
