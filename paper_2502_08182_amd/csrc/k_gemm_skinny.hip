@@ -13,6 +13,8 @@
 // L2 (at 64 token rows the activation reads cost a fifth of the weight stream's rate
 // otherwise); wavefronts of one column split K into contiguous ranges and their fp32
 // partial tiles are summed through LDS in a fixed order (deterministic).
+#include <algorithm>
+
 #include "kernels.h"
 #include "common.h"
 
@@ -202,17 +204,23 @@ static int pick_ks(int groups, int KB) {
   return ks;
 }
 
-// Columns of wavefronts that share their activation reads (see the kernel).  Sharing pays
-// while a workgroup per compute unit is left (>= 200 workgroups) -- measured at 64 rows:
-// 57344 x 8192 4.9 -> 5.9 TB/s, at 32 rows: 27648 x 5120 4.8 -> 5.7 TB/s; with few feature
-// groups (10240 x 8192 at 64 rows: 160) it only starves the chip.  At 16 rows or fewer the
-// wavefronts of a column must also keep a long K run each (>= 128 k-blocks; 28672 x 7168:
-// 6.0 -> 6.4 TB/s), or the shorter kernels lose more at start-up than the reads gain.
+// Columns of wavefronts that share their activation reads (see the kernel).  Measured at 64 rows:
+// 57344 x 8192 4.9 -> 5.9 TB/s, at 32 rows: 27648 x 5120 4.8 -> 5.7 TB/s.  More columns mean fewer
+// workgroups, and what decides then is how evenly they fill the 256 compute units: 336 workgroups
+// (one unit in three holds two) ran 21504 x 7168 at 32 rows in 77 us where 672 take 62.  So: the
+// widest sharing among the counts that fill the chip about as evenly as any, never below 128
+// workgroups.  At 16 rows or fewer the wavefronts of a column must also keep a long K run each
+// (>= 128 k-blocks; 28672 x 7168: 6.0 -> 6.4 TB/s), or the shorter kernels lose more at start-up
+// than the reads gain.
 static int pick_columns(int MT, int groups, int KB, int ks) {
+  auto evenness = [](int wgs) { return (double)wgs / (double)((wgs + 255) / 256 * 256); };
+  double best = evenness(groups);
+  for (int nwn = 2; nwn <= (MT == 1 ? 8 : 4); nwn <<= 1)
+    if (ks % nwn == 0 && groups % nwn == 0 && groups / nwn >= 128) best = std::max(best, evenness(groups / nwn));
   for (int nwn = MT == 1 ? 8 : 4; nwn > 1; nwn >>= 1) {
-    if (ks % nwn || groups % nwn || groups / nwn < 200) continue;
+    if (ks % nwn || groups % nwn || groups / nwn < 128) continue;
     if (MT == 1 && KB * nwn / ks < 128) continue;
-    return nwn;
+    if (evenness(groups / nwn) >= best - 0.03) return nwn;
   }
   return 1;
 }

@@ -114,8 +114,9 @@ def test_gemm_skinny_wide(epi):
              (50, 51200, 64),       # 4 row tiles, 800 groups: 4 columns
              (40, 25600, 96),       # 3 row tiles, 400 groups: 2 columns
              (20, 25600, 160),      # 2 row tiles, 800 groups of 32: 4 columns
-             (8, 6400, 16384),      # 1 row tile, 400 groups of 16, long K: 2 columns
-             (13, 25600, 4096)]     # 1 row tile, 1600 groups: 8 columns
+             (8, 8192, 16384),      # 1 row tile, 512 groups of 16, long K: 2 columns
+             (13, 32768, 4096),     # 1 row tile, 2048 groups: 8 columns
+             (32, 21504, 224)]      # 2 row tiles, 672 groups: sharing would leave the chip unevenly filled, none
     for i, (M, Nw, Kd) in enumerate(cases):
         _gemm_case("f16", K.PATH_SKINNY, epi, M, Nw // wide, Kd, bias=(i % 2 == 0), seed=70 + i)
 
