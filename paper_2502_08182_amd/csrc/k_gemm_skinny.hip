@@ -268,8 +268,12 @@ static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const
     if constexpr (MT >= 3 && C == 4)
       if (groups % 4 == 0 && groups / 4 * splits >= 200 && KB / splits >= 64)
         return launch_w<T, MT, C, 8, true>(epi, 8, 4, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
-    // otherwise 4 wavefronts; the K split across workgroups provides the parallelism
-    return launch_w<T, MT, C, 16, false>(epi, 4, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    // 3-4 row tiles otherwise: 8 wavefronts (few splits, see gemm_skinny_splits); up to 2 row tiles:
+    // 4 wavefronts, the K split across workgroups provides the parallelism
+    if constexpr (MT >= 3)
+      return launch_w<T, MT, C, 8, false>(epi, 8, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    else
+      return launch_w<T, MT, C, 16, false>(epi, 4, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
   }
   if constexpr (MT >= 3) {      // 8 wavefronts at most: twice the registers, nothing spills
     const int nwn = pick_columns(MT, groups, KB, 8);
@@ -323,13 +327,21 @@ hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, 
 }
 
 // Split count for the residual projections of a decode step (few output features, long
-// K): enough 256-thread workgroups that every CU holds several, each wavefront still
-// streaming at least 4 KiB of weights.
+// K).  Up to 32 rows: enough 256-thread workgroups that every CU holds several, each
+// wavefront still streaming at least 4 KiB of weights.  Above 32 rows every split costs a
+// plane of 64 x N partial sums, written here and read again by the fold, so: 8 splits where
+// the 4-column instance applies (long K, see launch_mc), else as few as give about one
+// workgroup per CU (64 rows, 8192 x 8192: 2 splits 30.7 us, 8 splits 33.5 us).
 int gemm_skinny_splits(int M, int N, int K) {
   const int C = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
   const int groups = N / (16 * C);
   const int KB = K / 32;
   int sp = 1;
+  if (M > 32) {
+    if (groups % 4 == 0 && groups / 4 * 8 >= 200 && KB / 8 >= 64) return 8;
+    while (sp < kMaxSplits && groups * sp < 200 && KB / (sp * 2) >= 64) sp *= 2;
+    return sp;
+  }
   while (sp < kMaxSplits && groups * 4 * sp < 4096 && KB / (4 * sp * 2) >= 4) sp *= 2;
   return sp;
 }

@@ -473,8 +473,17 @@ def test_budget_and_call_order_errors():
         with pytest.raises(sn.SnError) as e:
             sn.sn_place(ctx, 2)
         assert e.value.code == sn.SN_E_BUDGET
+        # keeping only one part on the host leaves the other on the GPU: over this budget, refused, nothing changes
+        for what in (sn.SN_OFFLOAD_WEIGHTS, sn.SN_OFFLOAD_KV):
+            with pytest.raises(sn.SnError) as e:
+                sn.sn_set_offload_part(ctx, what)
+            assert e.value.code == sn.SN_E_BUDGET
+            assert sn.sn_offload_part(ctx) == sn.SN_OFFLOAD_STATE and sn.sn_resident_bytes(ctx, 1) == r[0]
         sn.sn_set_budget_enforce(ctx, False)
         sn.sn_place(ctx, 2)                                        # over the cap, allowed when enforcement is off
+        sn.sn_set_offload_part(ctx, sn.SN_OFFLOAD_KV)              # and so is this, now
+        assert sn.sn_offload_part(ctx) == sn.SN_OFFLOAD_KV
+        assert sn.sn_resident_bytes(ctx, 1) > r[0] and sn.sn_resident_bytes(ctx, 2) == r[1]    # 4 weights stay; 2 stay + 2 KV slots
     finally:
         sn.sn_destroy(ctx)
     ctx = sn.sn_init(cs, r[0] - 1, 0)
