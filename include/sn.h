@@ -232,7 +232,8 @@ int sn_set_kernel_timing_class(sn_ctx* ctx, int32_t kernel_class);
  * average launch duration (launch gaps included). */
 int sn_time_kernel_class(sn_ctx* ctx, int32_t kernel_class, int32_t batch, int32_t reps,
                          int64_t* total_ns, int32_t* launches);
-/* Waits for the compute and copy streams, then fills *out for the last sn_step. */
+/* Waits for the last sn_step's kernels and write-backs (not for loads already issued for the
+ * next iteration under SN_SCHED_CONTINUOUS), then fills *out for that step. */
 int sn_get_stats(sn_ctx* ctx, sn_step_stats* out);
 /* Per-layer figures of the last sn_step (timing level >= 1): host arrays [n_layers];
  * stall_ns[l] is 0 for resident layers.  Any pointer may be NULL. */
@@ -243,8 +244,9 @@ int sn_get_layer_times(sn_ctx* ctx, int64_t* compute_ns, int64_t* stall_ns, int6
  * one decode step on `seq` cached tokens) on generated inputs under the current
  * placement and reports per layer the median compute time tc_ns[l] (fence waits
  * excluded) and the time tx_ns[l] of a host-to-device transfer of that layer's state
- * (weights; plus its KV prefix for decode), taken while the compute stream runs such
- * iterations -- the condition under which prefetches run.  Host arrays [n_layers]; either
+ * (the part of it that sn_set_offload_part keeps on the host: weights; plus its KV prefix for
+ * decode), taken while the compute stream runs such iterations -- the condition under which
+ * prefetches run.  Host arrays [n_layers]; either
  * may be NULL.  Discards any live KV contents (lengths return to 0). */
 int sn_profile_layers(sn_ctx* ctx, int32_t is_prefill, int32_t batch, int32_t seq, int32_t reps,
                       int64_t* tc_ns, int64_t* tx_ns);
