@@ -1,9 +1,10 @@
 // Prefill attention: causal attention of a sequence's new tokens over its cached and
 // new keys, on the matrix cores (prefill is the computation-intensive phase, paper
 // Sec. 2.1).  One 256-thread workgroup handles 64 query rows of one (sequence, query
-// head); each wavefront owns 16 of them.  Keys are consumed 32 at a time:
+// head); each wavefront owns 16 of them.  Keys are consumed 32 at a time, staged through a
+// three-deep ring of LDS tiles (K row-major, V transposed) shared by the four wavefronts:
 //
-//   S^T = K Q^T   A operand = 16 key rows x 32 of d (read from the KV slice),
+//   S^T = K Q^T   A operand = 16 key rows x 32 of d (read from the LDS K tile),
 //                 B operand = Q^T (this wavefront's 16 queries), result D[key][query].
 //                 The 16 rows of the two key sub-tiles are chosen as keys
 //                 8*(r/4) + 4*t + r%4 so that a lane ends up holding the scores of
@@ -28,9 +29,14 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
     uint16_t* __restrict__ out, int Hq, int Hkv) {
   constexpr int KT = 32;              // keys per step
   constexpr int LD = 40;              // LDS row stride (elements) of the transposed V tile: 80 B, 16 B aligned
+  constexpr int LDK = D + 8;          // LDS row stride (elements) of the K tile: rows 16 B apart modulo 256 B
   constexpr int DK = D / 32;          // k-steps over the head dimension
   constexpr int DT = D / 16;          // 16-wide output tiles over the head dimension
-  __shared__ __attribute__((aligned(16))) uint16_t vt[D * LD];
+  constexpr int RING = 3;             // key tiles in LDS: one being computed, one ready, one being written
+  constexpr int KCH = KT * (D / 8) / 256;   // 16-byte pieces of the K tile per thread (2 at d = 128, 1 at d = 64)
+  static_assert(KCH >= 1 && KT * (D / 8) % 256 == 0, "K tile must split evenly over the workgroup");
+  __shared__ __attribute__((aligned(16))) uint16_t ks[RING][KT * LDK];
+  __shared__ __attribute__((aligned(16))) uint16_t vt[RING][D * LD];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, g = lane >> 4;
@@ -67,53 +73,50 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Operands of the next key tile are fetched into registers while the current tile is being
-  // computed (one tile of software prefetch): V as (key pair, 8 d-values) items, two 16-byte
-  // loads per thread; K as the A-operand fragments of the two 16-key sub-tiles.
-  constexpr int ITEMS = (KT / 2) * (D / 8);              // <= 256: at most one item per thread
+  // A key tile travels global -> registers -> LDS.  Its loads are issued two steps before it is
+  // computed and it is written to LDS one step before (two register sets, a ring of three LDS
+  // tiles, one barrier per step), so a load has two steps of arithmetic to hide behind.  K goes
+  // to LDS row-major, shared by the four wavefronts; V as (key pair, 8 d-values) items that are
+  // transposed on the way in.
+  constexpr int ITEMS = (KT / 2) * (D / 8);              // <= 256: at most one V item per thread
   static_assert(ITEMS <= 256, "one V item per thread");
   const bool vitem = (int)threadIdx.x < ITEMS;
   const int vkey = 2 * (threadIdx.x & 15), vdc = threadIdx.x >> 4;
-  u16x8 va, vb, kf[2][DK];
-  auto fetch = [&](int j0) {
-    va = vb = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-    if (vitem && j0 + vkey < total) va = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + vkey) * D + vdc * 8);
-    if (vitem && j0 + vkey + 1 < total) vb = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + vkey + 1) * D + vdc * 8);
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int key = min(j0 + 8 * (r >> 2) + 4 * t + (r & 3), total - 1);   // inside the cached rows; masked later
-      const uint16_t* kp = Kb + (size_t)key * D + g * 8;
-#pragma unroll
-      for (int kk = 0; kk < DK; ++kk) kf[t][kk] = *reinterpret_cast<const u16x8*>(kp + kk * 32);
-    }
+  const int kkey = (threadIdx.x * KCH) / (D / 8), kch = (threadIdx.x * KCH) % (D / 8);   // K row and first piece
+  struct Stage {
+    u16x8 k[KCH], va, vb;
   };
-  if (kend > 0) fetch(0);
-
-  for (int j0 = 0; j0 < kend; j0 += KT) {
-    // ---- stage V[j0..j0+32) transposed into LDS: vt[dcol][key], eight 4-byte writes {v[key][e], v[key+1][e]} ----
+  auto gload = [&](int j0, Stage& R) {
+    R.va = R.vb = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    if (vitem && j0 + vkey < total) R.va = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + vkey) * D + vdc * 8);
+    if (vitem && j0 + vkey + 1 < total) R.vb = *reinterpret_cast<const u16x8*>(Vb + (size_t)(j0 + vkey + 1) * D + vdc * 8);
+    const int key = min(j0 + kkey, total - 1);           // inside the cached rows; masked later
+#pragma unroll
+    for (int c = 0; c < KCH; ++c) R.k[c] = *reinterpret_cast<const u16x8*>(Kb + (size_t)key * D + (kch + c) * 8);
+  };
+  auto lstore = [&](int buf, const Stage& R) {
+#pragma unroll
+    for (int c = 0; c < KCH; ++c) *reinterpret_cast<u16x8*>(&ks[buf][kkey * LDK + (kch + c) * 8]) = R.k[c];
     if (vitem) {
-      const u16x8 ra = rot_pairs(va, g), rb = rot_pairs(vb, g);
+      // vt[dcol][key], eight 4-byte writes {v[key][e], v[key+1][e]}
+      const u16x8 ra = rot_pairs(R.va, g), rb = rot_pairs(R.vb, g);
 #pragma unroll
       for (int e0 = 0; e0 < 8; ++e0) {
         const int e = (e0 + 2 * g) & 7;                  // 16-lane groups write different rows: fewer bank conflicts
-        *reinterpret_cast<uint32_t*>(&vt[(vdc * 8 + e) * LD + vkey]) = (uint32_t)ra[e0] | ((uint32_t)rb[e0] << 16);
+        *reinterpret_cast<uint32_t*>(&vt[buf][(vdc * 8 + e) * LD + vkey]) = (uint32_t)ra[e0] | ((uint32_t)rb[e0] << 16);
       }
     }
-    u16x8 kc[2][DK];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int kk = 0; kk < DK; ++kk) kc[t][kk] = kf[t][kk];
-    __syncthreads();
-    if (j0 + KT < kend) fetch(j0 + KT);                  // in flight during this tile's arithmetic
-
+  };
+  auto compute = [&](int buf, int j0) {
     // ---- scores of 32 keys for this wavefront's 16 queries ----
     f32x4 st[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       st[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const uint16_t* kp = &ks[buf][(8 * (r >> 2) + 4 * t + (r & 3)) * LDK + g * 8];
 #pragma unroll
-      for (int kk = 0; kk < DK; ++kk) st[t] = mma16x16x32<T>(kc[t][kk], qf[kk], st[t]);
+      for (int kk = 0; kk < DK; ++kk)
+        st[t] = mma16x16x32<T>(*reinterpret_cast<const u16x8*>(kp + kk * 32), qf[kk], st[t]);
     }
     // lane now holds scores of keys j0 + 8g + e (e = 4t + i) for query lane%16
     float s[8];
@@ -139,16 +142,35 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
     }
     l = l * corr + rs;                                   // per-lane partial; lanes of a query are summed at the end
     m = mn;
-
     // ---- O^T += V^T P^T ----
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      const u16x8 vf = *reinterpret_cast<const u16x8*>(&vt[(dt * 16 + r) * LD + g * 8]);
+      const u16x8 vf = *reinterpret_cast<const u16x8*>(&vt[buf][(dt * 16 + r) * LD + g * 8]);
 #pragma unroll
       for (int i = 0; i < 4; ++i) o[dt][i] *= corr;
       o[dt] = mma16x16x32<T>(vf, pb, o[dt]);
     }
+  };
+
+  const int nsteps = (kend + KT - 1) / KT;
+  Stage RA, RB;
+  if (nsteps > 0) {
+    gload(0, RA);
+    if (nsteps > 1) gload(KT, RB);
+    lstore(0, RA);
+  }
+  __syncthreads();
+  // step t: tile t is in LDS slot t % 3, tile t + 1 is arriving in `next`; tile t + 2 is requested into `far`
+  // (which held tile t, already in LDS), tile t is computed, tile t + 1 goes to its LDS slot.
+  auto step = [&](int t, Stage& far, const Stage& next) {
+    if (t + 2 < nsteps) gload((t + 2) * KT, far);
+    compute(t % RING, t * KT);
+    if (t + 1 < nsteps) lstore((t + 1) % RING, next);
     __syncthreads();
+  };
+  for (int t = 0; t < nsteps; t += 2) {
+    step(t, RA, RB);
+    if (t + 1 < nsteps) step(t + 1, RB, RA);
   }
 
   l += __shfl_xor(l, 16, 64);
