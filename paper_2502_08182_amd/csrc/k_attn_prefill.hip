@@ -66,7 +66,9 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
   const int cp = cap[b];
   const uint16_t* Kb = kv + (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D;
   const uint16_t* Vb = Kb + (size_t)cp * D;
-  const float scale = rsqrtf((float)D);
+  const float scale2 = rsqrtf((float)D) * 1.4426950408889634f;   // log2(e) / sqrt(d)
+  const int qlo = lb + q0 + wave * 16;                   // position of this wavefront's first query
+  const bool all_valid = q0 + wave * 16 + 15 < nn;       // all 16 queries of this wavefront exist
 
   float m = kMasked, l = 0.f;
   f32x4 o[DT];
@@ -118,36 +120,55 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
       for (int kk = 0; kk < DK; ++kk)
         st[t] = mma16x16x32<T>(*reinterpret_cast<const u16x8*>(kp + kk * 32), qf[kk], st[t]);
     }
-    // lane now holds scores of keys j0 + 8g + e (e = 4t + i) for query lane%16
+    // lane now holds scores of keys j0 + 8g + e (e = 4t + i) for query lane%16.  The softmax runs in
+    // the base-2 domain (scores times log2 e / sqrt d, v_exp_f32 is 2^x).  Away from the diagonal
+    // and the ragged end of the sequence nothing needs masking (decided per wavefront).
     float s[8];
     float mx = kMasked;
+    if (all_valid && j0 + KT - 1 <= qlo) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int key = j0 + 8 * g + e;
-      const bool ok = qok && key <= qpos;
-      s[e] = ok ? st[e >> 2][e & 3] * scale : kMasked;
-      mx = fmaxf(mx, s[e]);
+      for (int e = 0; e < 8; ++e) {
+        s[e] = st[e >> 2][e & 3] * scale2;
+        mx = fmaxf(mx, s[e]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int key = j0 + 8 * g + e;
+        const bool ok = qok && key <= qpos;
+        s[e] = ok ? st[e >> 2][e & 3] * scale2 : kMasked;
+        mx = fmaxf(mx, s[e]);
+      }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx);
-    const float corr = __expf(m - mn);
+    // the running maximum rarely moves after the first tiles: rescale only when it does for some
+    // query of the wavefront (multiplying by 2^0 would change nothing)
+    if (__any(mx > m)) {
+      const float mn = fmaxf(m, mx);
+      const float corr = __builtin_amdgcn_exp2f(m - mn);
+      l *= corr;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[dt][i] *= corr;
+      m = mn;
+    }
     float rs = 0.f;
     u16x8 pb;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float p = s[e] > 0.5f * kMasked ? __expf(s[e] - mn) : 0.f;
+      // a masked score is -1e30: 2^(-1e30 - m) is 0 once the row has seen a real key, which its
+      // first tile always holds (key 0); rows of queries past the end are never stored
+      const float p = __builtin_amdgcn_exp2f(s[e] - m);
       rs += p;
       pb[e] = from_f32<T>(p);
     }
-    l = l * corr + rs;                                   // per-lane partial; lanes of a query are summed at the end
-    m = mn;
+    l += rs;                                             // per-lane partial; lanes of a query are summed at the end
     // ---- O^T += V^T P^T ----
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       const u16x8 vf = *reinterpret_cast<const u16x8*>(&vt[buf][(dt * 16 + r) * LD + g * 8]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) o[dt][i] *= corr;
       o[dt] = mma16x16x32<T>(vf, pb, o[dt]);
     }
   };
