@@ -76,6 +76,9 @@ int sn_k_cast_out_fold(int32_t dtype, void* x32, void* out16, int32_t T, int32_t
 /* Index arrays shared by the attention-side kernels (device int32):
  *   len_before[B], n_new[B], tok_start[B], kv_off[B] (token offset of the sequence in the
  *   KV slice), cap[B]; tok_seq[T], tok_pos[T]; tile_seq[n_qtiles], tile_q0[n_qtiles].
+ *   A query tile is a run of up to SN_K_PREFILL_QTILE consecutive new tokens of one sequence:
+ *   tile_seq its sequence, tile_q0 the index of its first token among the sequence's new
+ *   tokens (a multiple of SN_K_PREFILL_QTILE); every new token lies in exactly one tile.
  * KV slice layout: for sequence b at element offset kv_off[b]*2*Hkv*d:
  *   [Hkv][2 (K then V)][cap[b]][d], 16-bit. */
 
@@ -115,6 +118,7 @@ int sn_k_attn_decode_append(int32_t dtype, const void* qkv16, void* kv, void* mi
                             int32_t Hkv, int32_t d, int32_t S, int32_t max_len, int32_t packed_out,
                             void* stream);
 
+#define SN_K_PREFILL_QTILE 128
 /* Causal attention of each sequence's n_new tokens over len_before+n_new keys.
  * out16 [T][Hq*d]. */
 int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,

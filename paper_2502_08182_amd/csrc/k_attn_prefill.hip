@@ -1,7 +1,8 @@
 // Prefill attention: causal attention of a sequence's new tokens over its cached and
 // new keys, on the matrix cores (prefill is the computation-intensive phase, paper
-// Sec. 2.1).  One 256-thread workgroup handles 64 query rows of one (sequence, query
-// head); each wavefront owns 16 of them.  Keys are consumed 32 at a time, staged through a
+// Sec. 2.1).  One 256-thread workgroup handles kPrefillQTile = 128 query rows of one
+// (sequence, query head); each wavefront owns 32 of them as two 16-query MFMA column tiles, so
+// every K and V fragment read from LDS feeds two products.  Keys are consumed 32 at a time, staged through a
 // three-deep ring of LDS tiles (K row-major, V transposed) shared by the four wavefronts:
 //
 //   S^T = K Q^T   A operand = 16 key rows x 32 of d (read from the LDS K tile),
@@ -33,6 +34,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
   constexpr int DK = D / 32;          // k-steps over the head dimension
   constexpr int DT = D / 16;          // 16-wide output tiles over the head dimension
   constexpr int RING = 3;             // key tiles in LDS: one being computed, one ready, one being written
+  constexpr int QW = kPrefillQTile / 64;  // 16-query tiles per wavefront
   constexpr int KCH = KT * (D / 8) / 256;   // 16-byte pieces of the K tile per thread (2 at d = 128, 1 at d = 64)
   static_assert(KCH >= 1 && KT * (D / 8) % 256 == 0, "K tile must split evenly over the workgroup");
   __shared__ __attribute__((aligned(16))) uint16_t ks[RING][KT * LDK];
@@ -47,33 +49,42 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
   const int nn = n_new[b];
   const int lb = len_before[b];
   const int total = lb + nn;                             // keys that exist after the append
-  const int kend = lb + min(nn, q0 + 64);                // keys any query of this tile may see
+  const int kend = lb + min(nn, q0 + kPrefillQTile);     // keys any query of this tile may see
 
-  const int qi = q0 + wave * 16 + r;                     // this lane's query (new-token index)
-  const bool qok = qi < nn;
-  const int qpos = lb + qi;
   const int qkv_ld = (Hq + 2 * Hkv) * D;
-
-  u16x8 qf[DK];
+  const int qw0 = q0 + wave * 16 * QW;                   // first query (new-token index) of this wavefront
+  int qi[QW], qpos[QW];                                  // this lane's query in each of its column tiles
+  bool qok[QW];
+  u16x8 qf[QW][DK];
 #pragma unroll
-  for (int kk = 0; kk < DK; ++kk) {
-    qf[kk] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-    if (qok)
-      qf[kk] = *reinterpret_cast<const u16x8*>(qkv + (size_t)(tok_start[b] + qi) * qkv_ld + (size_t)hq * D +
-                                               kk * 32 + g * 8);
+  for (int j = 0; j < QW; ++j) {
+    qi[j] = qw0 + j * 16 + r;
+    qok[j] = qi[j] < nn;
+    qpos[j] = lb + qi[j];
+#pragma unroll
+    for (int kk = 0; kk < DK; ++kk) {
+      qf[j][kk] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      if (qok[j])
+        qf[j][kk] = *reinterpret_cast<const u16x8*>(qkv + (size_t)(tok_start[b] + qi[j]) * qkv_ld + (size_t)hq * D +
+                                                    kk * 32 + g * 8);
+    }
   }
 
   const int cp = cap[b];
   const uint16_t* Kb = kv + (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D;
   const uint16_t* Vb = Kb + (size_t)cp * D;
   const float scale2 = rsqrtf((float)D) * 1.4426950408889634f;   // log2(e) / sqrt(d)
-  const int qlo = lb + q0 + wave * 16;                   // position of this wavefront's first query
-  const bool all_valid = q0 + wave * 16 + 15 < nn;       // all 16 queries of this wavefront exist
+  const int qlo = lb + qw0;                              // position of this wavefront's first query
 
-  float m = kMasked, l = 0.f;
-  f32x4 o[DT];
+  float m[QW], l[QW];
+  f32x4 o[QW][DT];
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < QW; ++j) {
+    m[j] = kMasked;
+    l[j] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[j][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
 
   // A key tile travels global -> registers -> LDS.  Its loads are issued two steps before it is
   // computed and it is written to LDS one step before (two register sets, a ring of three LDS
@@ -110,66 +121,75 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
     }
   };
   auto compute = [&](int buf, int j0) {
-    // ---- scores of 32 keys for this wavefront's 16 queries ----
-    f32x4 st[2];
+    if (j0 > qlo + 16 * QW - 1) return;                  // every key of this tile lies after all of this wavefront's queries
+    // ---- scores of 32 keys for this wavefront's 16 * QW queries ----
+    f32x4 st[QW][2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      st[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < QW; ++j) st[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
       const uint16_t* kp = &ks[buf][(8 * (r >> 2) + 4 * t + (r & 3)) * LDK + g * 8];
 #pragma unroll
-      for (int kk = 0; kk < DK; ++kk)
-        st[t] = mma16x16x32<T>(*reinterpret_cast<const u16x8*>(kp + kk * 32), qf[kk], st[t]);
-    }
-    // lane now holds scores of keys j0 + 8g + e (e = 4t + i) for query lane%16.  The softmax runs in
-    // the base-2 domain (scores times log2 e / sqrt d, v_exp_f32 is 2^x).  Away from the diagonal
-    // and the ragged end of the sequence nothing needs masking (decided per wavefront).
-    float s[8];
-    float mx = kMasked;
-    if (all_valid && j0 + KT - 1 <= qlo) {
+      for (int kk = 0; kk < DK; ++kk) {
+        const u16x8 kfrag = *reinterpret_cast<const u16x8*>(kp + kk * 32);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        s[e] = st[e >> 2][e & 3] * scale2;
-        mx = fmaxf(mx, s[e]);
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int key = j0 + 8 * g + e;
-        const bool ok = qok && key <= qpos;
-        s[e] = ok ? st[e >> 2][e & 3] * scale2 : kMasked;
-        mx = fmaxf(mx, s[e]);
+        for (int j = 0; j < QW; ++j) st[j][t] = mma16x16x32<T>(kfrag, qf[j][kk], st[j][t]);
       }
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    // the running maximum rarely moves after the first tiles: rescale only when it does for some
-    // query of the wavefront (multiplying by 2^0 would change nothing)
-    if (__any(mx > m)) {
-      const float mn = fmaxf(m, mx);
-      const float corr = __builtin_amdgcn_exp2f(m - mn);
-      l *= corr;
+    u16x8 pb[QW];
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+    for (int j = 0; j < QW; ++j) {
+      // lane now holds scores of keys j0 + 8g + e (e = 4t + i) for query lane%16 of column tile j.  The
+      // softmax runs in the base-2 domain (scores times log2 e / sqrt d, v_exp_f32 is 2^x).  Away from
+      // the diagonal and the ragged end of the sequence nothing needs masking (decided per wavefront).
+      float sc[8];
+      float mx = kMasked;
+      if (qw0 + j * 16 + 15 < nn && j0 + KT - 1 <= qlo + j * 16) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[dt][i] *= corr;
-      m = mn;
+        for (int e = 0; e < 8; ++e) {
+          sc[e] = st[j][e >> 2][e & 3] * scale2;
+          mx = fmaxf(mx, sc[e]);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int key = j0 + 8 * g + e;
+          const bool ok = qok[j] && key <= qpos[j];
+          sc[e] = ok ? st[j][e >> 2][e & 3] * scale2 : kMasked;
+          mx = fmaxf(mx, sc[e]);
+        }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      // the running maximum rarely moves after the first tiles: rescale only when it does for some
+      // query of the wavefront (multiplying by 2^0 would change nothing)
+      if (__any(mx > m[j])) {
+        const float mn = fmaxf(m[j], mx);
+        const float corr = __builtin_amdgcn_exp2f(m[j] - mn);
+        l[j] *= corr;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[j][dt][i] *= corr;
+        m[j] = mn;
+      }
+      float rs = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        // a masked score is -1e30: 2^(-1e30 - m) is 0 once the row has seen a real key, which its
+        // first tile always holds (key 0); rows of queries past the end are never stored
+        const float p = __builtin_amdgcn_exp2f(sc[e] - m[j]);
+        rs += p;
+        pb[j][e] = from_f32<T>(p);
+      }
+      l[j] += rs;                                        // per-lane partial; lanes of a query are summed at the end
     }
-    float rs = 0.f;
-    u16x8 pb;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      // a masked score is -1e30: 2^(-1e30 - m) is 0 once the row has seen a real key, which its
-      // first tile always holds (key 0); rows of queries past the end are never stored
-      const float p = __builtin_amdgcn_exp2f(s[e] - m);
-      rs += p;
-      pb[e] = from_f32<T>(p);
-    }
-    l += rs;                                             // per-lane partial; lanes of a query are summed at the end
     // ---- O^T += V^T P^T ----
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       const u16x8 vf = *reinterpret_cast<const u16x8*>(&vt[buf][(dt * 16 + r) * LD + g * 8]);
-      o[dt] = mma16x16x32<T>(vf, pb, o[dt]);
+#pragma unroll
+      for (int j = 0; j < QW; ++j) o[j][dt] = mma16x16x32<T>(vf, pb[j], o[j][dt]);
     }
   };
 
@@ -194,17 +214,21 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
     if (t + 1 < nsteps) step(t + 1, RB, RA);
   }
 
-  l += __shfl_xor(l, 16, 64);
-  l += __shfl_xor(l, 32, 64);
-  if (qok) {
-    const float inv = 1.0f / l;
-    uint16_t* op = out + (size_t)(tok_start[b] + qi) * Hq * D + (size_t)hq * D + g * 4;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      u16x4 w;
+  for (int j = 0; j < QW; ++j) {
+    float lj = l[j];
+    lj += __shfl_xor(lj, 16, 64);
+    lj += __shfl_xor(lj, 32, 64);
+    if (qok[j]) {
+      const float inv = 1.0f / lj;
+      uint16_t* op = out + (size_t)(tok_start[b] + qi[j]) * Hq * D + (size_t)hq * D + g * 4;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) w[i] = from_f32<T>(o[dt][i] * inv);
-      *reinterpret_cast<u16x4*>(op + dt * 16) = w;
+      for (int dt = 0; dt < DT; ++dt) {
+        u16x4 w;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = from_f32<T>(o[j][dt][i] * inv);
+        *reinterpret_cast<u16x4*>(op + dt * 16) = w;
+      }
     }
   }
 }

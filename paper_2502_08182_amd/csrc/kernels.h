@@ -24,6 +24,7 @@ enum Epilogue {
   EPI_PART32 = 4     // split-K: part[split][m][n] = partial product (no bias); folded in by the consumer
 };
 constexpr int kMaxSplits = 8;
+constexpr int kPrefillQTile = 128;   // query rows (new tokens of one sequence) per prefill-attention workgroup
 
 // Pending split-K partial sums of a residual projection: the next kernel that reads the
 // residual stream first performs x32[m][n] += bias[n] + sum_s part[s][m][n] (s ascending).
@@ -42,7 +43,7 @@ struct StepIndex {
   const int32_t* cap;         // [B] KV capacity of the sequence (tokens)
   const int32_t* tok_seq;     // [T] sequence of each token row
   const int32_t* tok_pos;     // [T] absolute position of each token row
-  const int32_t* tile_seq;    // [n_qtiles] prefill attention: sequence of each 64-row query tile
+  const int32_t* tile_seq;    // [n_qtiles] prefill attention: sequence of each kPrefillQTile-row query tile
   const int32_t* tile_q0;     // [n_qtiles] first new-token index of the tile inside its sequence
 };
 

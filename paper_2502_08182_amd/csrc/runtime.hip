@@ -851,7 +851,7 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
         m_seq[t] = b;
         m_pos[t] = c->len[b] + i;
       }
-      if (prefill) n_qtiles += (bt->n_new[b] + 63) / 64;
+      if (prefill) n_qtiles += (bt->n_new[b] + kPrefillQTile - 1) / kPrefillQTile;
       max_len = std::max(max_len, c->len[b] + bt->n_new[b]);
     }
   }
@@ -859,7 +859,7 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
   if (prefill) {
     int q = 0;
     for (int b = 0; b < B; ++b)
-      for (int q0 = 0; q0 < bt->n_new[b]; q0 += 64, ++q) {
+      for (int q0 = 0; q0 < bt->n_new[b]; q0 += kPrefillQTile, ++q) {
         m_tseq[q] = b;
         m_tq0[q] = q0;
       }

@@ -14,6 +14,7 @@ EXPORTS = ("sn_k_tile_weights", "sn_k_norm", "sn_k_gemm", "sn_k_rope_append", "s
 
 EPI_STORE16, EPI_GELU16, EPI_RESID32, EPI_SWIGLU16 = 0, 1, 2, 3
 PATH_SKINNY, PATH_TILE = 0, 1
+SN_K_PREFILL_QTILE = 128    # query rows per prefill-attention tile (include/sn_kernels.h)
 
 _ready = False
 

@@ -277,7 +277,7 @@ def test_attn_decode_with_fused_append(dtype, Hq, Hkv, d, rope):
 def test_attn_prefill(dtype, Hq, Hkv, d, rope):
     rng = np.random.default_rng(4)
     lens_before = [0, 0, 40, 0]
-    n_new = [1, 64, 37, 150]          # single token, exact tile, chunk on top of a cached prefix, ragged multi-tile
+    n_new = [1, 128, 37, 300]         # single token, exact tile, chunk on top of a cached prefix, ragged multi-tile
     B = len(n_new)
     caps = [lens_before[b] + n_new[b] + 2 for b in range(B)]
     qkv, Kc, Vc, kv_off, tok_start, dv = _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope)
@@ -286,7 +286,7 @@ def test_attn_prefill(dtype, Hq, Hkv, d, rope):
                        dv["inv_freq"], T, Hq, Hkv, d, rope)
     tile_seq, tile_q0 = [], []
     for b in range(B):
-        for q0 in range(0, n_new[b], 64):
+        for q0 in range(0, n_new[b], K.SN_K_PREFILL_QTILE):
             tile_seq.append(b)
             tile_q0.append(q0)
     i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
