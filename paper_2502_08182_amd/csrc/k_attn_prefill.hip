@@ -2,8 +2,8 @@
 // new keys, on the matrix cores (prefill is the computation-intensive phase, paper
 // Sec. 2.1).  One 256-thread workgroup handles kPrefillQTile = 128 query rows of one
 // (sequence, query head); each wavefront owns 32 of them as two 16-query MFMA column tiles, so
-// every K and V fragment read from LDS feeds two products.  Keys are consumed 32 at a time, staged through a
-// three-deep ring of LDS tiles (K row-major, V transposed) shared by the four wavefronts:
+// every K and V fragment read from LDS feeds two products.  Keys are consumed 32 at a time,
+// staged through a pair of LDS tiles (K row-major, V transposed) shared by the four wavefronts:
 //
 //   S^T = K Q^T   A operand = 16 key rows x 32 of d (read from the LDS K tile),
 //                 B operand = Q^T (this wavefront's 16 queries), result D[key][query].
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
   constexpr int LDK = D + 8;          // LDS row stride (elements) of the K tile: rows 16 B apart modulo 256 B
   constexpr int DK = D / 32;          // k-steps over the head dimension
   constexpr int DT = D / 16;          // 16-wide output tiles over the head dimension
-  constexpr int RING = 3;             // key tiles in LDS: one being computed, one ready, one being written
+  constexpr int RING = 2;             // key tiles in LDS: the one being computed and the next one, written at the end of the step
   constexpr int QW = kPrefillQTile / 64;  // 16-query tiles per wavefront
   constexpr int KCH = KT * (D / 8) / 256;   // 16-byte pieces of the K tile per thread (2 at d = 128, 1 at d = 64)
   static_assert(KCH >= 1 && KT * (D / 8) % 256 == 0, "K tile must split evenly over the workgroup");
@@ -42,8 +42,11 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, g = lane >> 4;
-  const int b = tile_seq[blockIdx.x];
-  const int q0 = tile_q0[blockIdx.x];
+  // tiles are listed per sequence with the first query rising, i.e. with the causal work rising: take them
+  // from the back so that the longest workgroups start first and the short ones fill the end of the launch
+  const int tile = gridDim.x - 1 - blockIdx.x;
+  const int b = tile_seq[tile];
+  const int q0 = tile_q0[tile];
   const int hq = blockIdx.y;
   const int hk = hq / (Hq / Hkv);
   const int nn = n_new[b];
@@ -87,8 +90,9 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
   }
 
   // A key tile travels global -> registers -> LDS.  Its loads are issued two steps before it is
-  // computed and it is written to LDS one step before (two register sets, a ring of three LDS
-  // tiles, one barrier per step), so a load has two steps of arithmetic to hide behind.  K goes
+  // computed and it is written to LDS at the end of the step before (two register sets, two LDS
+  // tiles, one barrier per step: the tile overwritten was last read one barrier ago), so a load
+  // has two steps of arithmetic to hide behind.  K goes
   // to LDS row-major, shared by the four wavefronts; V as (key pair, 8 d-values) items that are
   // transposed on the way in.
   constexpr int ITEMS = (KT / 2) * (D / 8);              // <= 256: at most one V item per thread
@@ -201,7 +205,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
     lstore(0, RA);
   }
   __syncthreads();
-  // step t: tile t is in LDS slot t % 3, tile t + 1 is arriving in `next`; tile t + 2 is requested into `far`
+  // step t: tile t is in LDS slot t % RING, tile t + 1 is arriving in `next`; tile t + 2 is requested into `far`
   // (which held tile t, already in LDS), tile t is computed, tile t + 1 goes to its LDS slot.
   auto step = [&](int t, Stage& far, const Stage& next) {
     if (t + 2 < nsteps) gload((t + 2) * KT, far);
