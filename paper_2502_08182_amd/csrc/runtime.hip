@@ -4,9 +4,12 @@
 // each offloaded layer is loaded on a copy stream, the load being issued when compute
 // reaches the first layer of the group, and a synchronisation point precedes the
 // offloaded layer; afterwards its mutated state returns to the host.  Here:
-//   * every layer has a pinned host master of its (re-tiled) weights; offloaded layers
-//     also keep their KV slice in pinned host memory;
-//   * two device staging slots, used alternately (offloaded layer k -> slot k mod 2);
+//   * a host-resident layer keeps its (re-tiled) weights, its KV slice or both in pinned host
+//     memory (sn_set_offload_part); what it leaves behind stays in device memory;
+//   * two device staging slots for the part that travels, used alternately (the n-th load
+//     issued goes to slot n mod 2);
+//   * three schedules for issuing the loads (sn_set_schedule): the paper's, one group earlier,
+//     and across the iteration boundary;
 //   * an H2D stream (prefetch) and a D2H stream (write-back after prefill); during
 //     decode the append kernel writes the new K/V rows through to the host slice, so
 //     there is nothing left to copy back;
