@@ -273,7 +273,7 @@ static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const
     if constexpr (MT >= 3)
       return launch_w<T, MT, C, 8, false>(epi, 8, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
     else
-      return launch_w<T, MT, C, 16, false>(epi, 4, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+      return launch_w<T, MT, C, 16, false>(epi, (MT == 1 && splits == 1) ? 8 : 4, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
   }
   if constexpr (MT >= 3) {      // 8 wavefronts at most: twice the registers, nothing spills
     const int nwn = pick_columns(MT, groups, KB, 8);
@@ -342,6 +342,11 @@ int gemm_skinny_splits(int M, int N, int K) {
     while (sp < kMaxSplits && groups * sp < 200 && KB / (sp * 2) >= 64) sp *= 2;
     return sp;
   }
+  // one row tile and the feature groups alone fill the 256 CUs evenly (4096 features: one workgroup each): no
+  // split across workgroups, 8 wavefronts split K inside the workgroup, and the fold reads one plane instead of
+  // four (4096 x 16384 at 8 rows: 22.5 -> 21.7 us, decode step 3.105 -> 3.05 ms).  448 groups (7168 features)
+  // would leave the CUs unevenly loaded and lose 13 %.
+  if (M <= 16 && groups >= 256 && groups % 256 == 0) return 1;
   while (sp < kMaxSplits && groups * 4 * sp < 4096 && KB / (4 * sp * 2) >= 4) sp *= 2;
   return sp;
 }
