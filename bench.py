@@ -14,6 +14,7 @@ checked against the SLO, which is how a serving loop consumes a decode step.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -104,12 +105,16 @@ def run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, n_steps, warmup, ti
         sn.sn_set_kernel_timing_class(se.ctx, timing_class)
     stats = []
     torch.cuda.synchronize()
+    gc_was_on = gc.isenabled()
+    gc.disable()                                       # no collector pauses inside the timed region
     t0 = time.perf_counter()
     for i in range(n_steps):
         se.step_device(ones, False, x_dec[i % len(x_dec)], y_dec)
         stats.append(sn.sn_get_stats(se.ctx))          # synchronises the iteration
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / n_steps
+    if gc_was_on:
+        gc.enable()
     sn.sn_set_timing(se.ctx, 0)
     return [s.as_dict() for s in stats], wall_ms, pre
 
