@@ -586,8 +586,9 @@ def test_full_size_config5_layer_shape_and_batch():
     """The Llama-2-70B-shaped configuration at its real per-layer shape and full batch: 64 sequences x 2048
     prompt tokens = 131072 rows per prefill launch, GQA 64/8 heads, SwiGLU 28672, bf16 -- the launch
     configuration of that workload -- with 3 layers instead of 80 (the 80-layer model is 137 GB; the
-    kernels do not depend on the layer count).  (i) offloaded (N = 2) and all-resident runs are
-    bit-identical for the prefill and two decode steps; (ii) with the output projections of layers 1, 2
+    kernels do not depend on the layer count).  (i) offloaded (N = 2; also with only the KV slice on the
+    host and the continuous schedule) and all-resident runs are bit-identical for the prefill and two
+    decode steps; (ii) with the output projections of layers 1, 2
     zeroed the model is its first layer, which the oracle computes for sampled rows of sequence 0: early,
     tile-boundary and last prompt positions (attention over up to 2048 keys) and both decode steps."""
     import dataclasses
@@ -605,27 +606,32 @@ def test_full_size_config5_layer_shape_and_batch():
     prompt = synth.to_bits(rng.standard_normal((B * P, s.hidden), dtype=np.float32), s.dtype)
     table = synth.to_bits(rng.standard_normal((2, B, s.hidden), dtype=np.float32), s.dtype)
     outs = {}
-    for N in (0, 2):
+    for N in (0, 2, -2):            # -2: interval 2 again, KV slices only on the host, loads across the iteration boundary
         with Session(s, B, P + 4) as se:
             for l in range(3):
                 sn.sn_set_layer_weights(se.ctx, l, blob0 if l == 0 else blob_dead)
-            se.place(N)
+            if N < 0:
+                sn.sn_set_offload_part(se.ctx, sn.SN_OFFLOAD_KV)
+                sn.sn_set_schedule(se.ctx, sn.SN_SCHED_CONTINUOUS)
+            se.place(abs(N))
             se.kv_reset([P + 4] * B)
             pre, fpre = se.step([P] * B, True, prompt, want_f32=True)
             d0, f0 = se.step([1] * B, False, table[0], want_f32=True)
             d1, f1 = se.step([1] * B, False, table[1], want_f32=True)
             st = se.stats()
         assert st["n_offloaded"] == (1 if N else 0)
+        assert st["n_preissued"] == (1 if N < 0 else 0)
         outs[N] = (pre, d0, d1, fpre[:P].copy(), f0[0:1].copy(), f1[0:1].copy())
         del fpre
-    for a, b in zip(outs[0][:3], outs[2][:3]):
-        assert np.array_equal(a, b)
+    for other in (2, -2):
+        for a, b in zip(outs[0][:3], outs[other][:3]):
+            assert np.array_equal(a, b)
     del blob0, blob_dead
     # oracle: sequence 0 = rows 0..P-1 of the prompt, then its two decode tokens at positions P, P+1
     x_seq = np.concatenate([synth.widen(prompt[:P], s.dtype), synth.widen(table[0, 0:1], s.dtype),
                             synth.widen(table[1, 0:1], s.dtype)], axis=0)
-    rows = [0, 1, 63, 64, 1023, 2047, P, P + 1]
+    rows = [0, 1, 63, 64, 127, 128, 1023, 2047, P, P + 1]
     want = _llama_layer0_rows(s, layer0, x_seq, rows)
-    got_f = np.concatenate([outs[2][3][rows[:6]], outs[2][4], outs[2][5]], axis=0)
-    got_b = np.concatenate([outs[2][0][rows[:6]], outs[2][1][0:1], outs[2][2][0:1]], axis=0)
+    got_f = np.concatenate([outs[2][3][rows[:8]], outs[2][4], outs[2][5]], axis=0)
+    got_b = np.concatenate([outs[2][0][rows[:8]], outs[2][1][0:1], outs[2][2][0:1]], axis=0)
     assert_close_f32(got_b, got_f, want, s.dtype, "c5 shape, full batch, first layer, sampled rows of sequence 0")
