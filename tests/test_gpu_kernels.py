@@ -121,6 +121,41 @@ def test_gemm_skinny_wide(epi):
         _gemm_case("f16", K.PATH_SKINNY, epi, M, Nw // wide, Kd, bias=(i % 2 == 0), seed=70 + i)
 
 
+@pytest.mark.parametrize("case", ["c2_ffn_up", "c3_ffn_up", "c5_qkv", "c5_ffn_up"])
+def test_gemm_skinny_full_size_sampled(case):
+    """Decode projections at the benchmark workloads' real shapes and row counts, in the launch configuration a
+    decode step uses (row-tile packed activations in): sampled output features against the oracle's arithmetic
+    (float64 products of the same 16-bit inputs), all rows."""
+    M, Wrows, Kd, epi, bias = {"c2_ffn_up": (8, 16384, 4096, K.EPI_GELU16, True),
+                               "c3_ffn_up": (32, 27648, 5120, K.EPI_SWIGLU16, False),
+                               "c5_qkv": (64, 10240, 8192, K.EPI_STORE16, False),
+                               "c5_ffn_up": (64, 57344, 8192, K.EPI_SWIGLU16, False)}[case]
+    rng = np.random.default_rng(90)
+    dual = epi == K.EPI_SWIGLU16
+    N = Wrows // 2 if dual else Wrows
+    xb = synth.to_bits(rng.standard_normal((M, Kd)), "f16")
+    tiled = np.zeros(Wrows * Kd, dtype=np.uint16)
+    parts = []
+    for i in range(2 if dual else 1):
+        wpart = synth.to_bits(rng.standard_normal((N, Kd), dtype=np.float32) * 0.02, "f16")
+        K.sn_k_tile_weights(wpart, N, Kd, tiled, 2 if dual else 1, i)
+        parts.append(wpart)
+    bb = synth.to_bits(rng.standard_normal(Wrows) * 0.3, "f16") if bias else None
+    out = torch.full((M, N), 0x7e00, dtype=torch.int16, device="cuda")
+    K.sn_k_gemm(DT["f16"], epi, K.PATH_SKINNY, dev16(tiled), dev16(K.pack_rows(xb)), dev16(bb) if bias else None, out,
+                M, Wrows, Kd, 1)
+    torch.cuda.synchronize()
+    cols = np.unique(np.concatenate([[0, 1, 15, 16, 63, 64, N - 65, N - 1], rng.integers(0, N, 400)]))
+    x64 = synth.widen(xb, "f16")
+    lin = [x64 @ synth.widen(wp[cols], "f16").T for wp in parts]
+    if bias:
+        lin[0] = lin[0] + synth.widen(bb, "f16")[cols]
+    want = ofw.silu(lin[0]) * lin[1] if dual else (ofw.gelu(lin[0]) if epi == K.EPI_GELU16 else lin[0])
+    got = synth.widen(host16(out), "f16")
+    assert np.isfinite(got).all()
+    check(got[:, cols], want, "f16", f"gemm_skinny full size {case}")
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3])
 def test_gemm_tile(dtype, epi):
