@@ -1,15 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the offloaded serving iteration on one MI355X.
 
-Workload: the OPT-6.7B-shaped configuration (32 layers, hidden 4096, 32 heads, GELU FFN
-16384, fp16 random weights, batch 8, prompt 512, teacher-forced decode), HBM budget
-8 GB, TPOT SLO = 2 x the all-resident decode step.  One "step" is one decode iteration
-of the whole layer loop (all kernels, prefetches and fences) at the interval the
-picker chooses from the measured per-layer compute and transfer times.
+Default workload: the Llama-2-70B-shaped configuration, the largest one that fits one GPU (80 layers,
+hidden 8192, 64 query / 8 KV heads, SwiGLU FFN 28672, bf16 random weights, 137 GB; batch 64, prompt
+2048, teacher-forced decode), HBM budget 96 GB, TPOT SLO = 2 x the all-resident decode step.  One
+"step" is one decode iteration of the whole layer loop (all kernels, prefetches, fences, write-through)
+at the interval the picker chooses from the measured per-layer compute and transfer times.
 
-Prints ONE JSON line (metric / value / roofline / cpu_baseline ...).  Inputs are
-resident in HBM before the timed region.  Every timed iteration is synchronised and
-checked against the SLO, which is how a serving loop consumes a decode step.
+Order of a run: weights -> profiles (whole state; KV slices only) -> ONE prefill -> all-resident decode
+(defines TPOT and the SLO) -> pick -> decode at the picked interval (the headline) -> dominant kernel
+timed inside iterations -> the same SLO under the continuous schedule and with only the KV slices on
+the host -> CPU oracle.  The decode legs share the one prefill: the cache is cut back to the prompt
+(sn_kv_truncate) and the placement changed (sn_place moves live state) between them.  --full adds
+the looser SLO points, the interval sweep and the prefill phase with its own intervals.
+
+Prints ONE JSON line (metric / value / roofline / cpu_baseline ...).  Inputs are resident in HBM
+before the timed region.  Every timed iteration is synchronised and checked against the SLO, which is
+how a serving loop consumes a decode step.
 """
 from __future__ import annotations
 
@@ -29,6 +36,8 @@ HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
 LINK_NOMINAL = 64.0e9      # bytes/s per direction, PCIe Gen5 x16 host link
 MFMA_PEAK = 2.5e15         # flop/s, dense fp16/bf16 matrix cores
 FAMILY = {"c2": "OPT-6.7B", "c3": "Llama-2-13B", "c4": "OPT-30B", "c5": "Llama-2-70B (GQA)"}
+# rocprofv3 --pmc summaries of the dominant kernel (FETCH_SIZE / WRITE_SIZE), by (workload, batch)
+TRAFFIC_NOTES = {("c2", 8): "gemm_skinny_ffn_up_c2_pmc.txt", ("c5", 64): "gemm_skinny_ffn_up_c5_pmc.txt"}
 
 
 def parse():
@@ -36,9 +45,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c5")
     ap.add_argument("--slo-factor", type=float, default=None,
-                    help="TPOT SLO as a multiple of the all-resident step (default: the workload's own, 2.0 for c2)")
+                    help="TPOT SLO as a multiple of the all-resident step (default: the workload's own, 2.0)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (the c4 batch sweep)")
     ap.add_argument("--guard", type=float, default=0.03,
                     help="fraction of the SLO kept as a guard band when picking (measured iterations run ~1-2%% "
@@ -48,12 +57,14 @@ def parse():
                          "of its length, where copies run 3-5%% slower than profiled in isolation")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB copy kernel (known HBM traffic) for counter calibration")
+    ap.add_argument("--full", action="store_true",
+                    help="also: the picker at looser SLOs, the interval sweep, the prefill phase with its own intervals, "
+                         "weights-only offloading")
     ap.add_argument("--slo-points", default=None,
-                    help="extra SLO factors (x all-resident TPOT) at which the picker is exercised and verified "
-                         "(default: 3,5,10 for c2, the workload's other SLO factors otherwise)")
+                    help="with --full: extra SLO factors (x all-resident TPOT) at which the picker is exercised and "
+                         "verified (default: 3,5,10 for c2, the workload's other SLO factors otherwise)")
     ap.add_argument("--prefill-slo-points", default="1.2,1.5,2",
-                    help="TTFT SLO factors (x all-resident prefill) at which the prefill phase picks its own interval")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the interval sweep and SLO-point reports")
+                    help="with --full: TTFT SLO factors (x all-resident prefill) at which the prefill phase picks its own interval")
     ap.add_argument("--contention", type=float, default=0.0, metavar="FRACTION",
                     help="also run the prefill phase while a competing host-to-device copy stream takes this fraction "
                          "of the link (0: off): at the interval picked without contention, then at the interval the "
@@ -63,9 +74,9 @@ def parse():
                          "performance record of CELLS sequence lengths spanning the run (the KV cache grows, the "
                          "TPOT SLO stays fixed); 0: off")
     ap.add_argument("--no-continuous", action="store_true",
-                    help="skip the decode runs with loads issued across the iteration boundary")
+                    help="skip the decode run with loads issued across the iteration boundary")
     ap.add_argument("--no-parts", action="store_true",
-                    help="skip the decode runs with only the weights / only the KV slices of host-resident layers on the host")
+                    help="skip the decode runs with only the KV slices of host-resident layers on the host")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="draw only this many different random layer blobs (0: every layer its own)")
@@ -88,35 +99,66 @@ def read_traffic_note(name):
     return None
 
 
-def run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, n_steps, warmup, timing_class=None):
-    """kv reset -> prefill -> warmup decode steps -> n_steps timed decode steps, each synchronised.
-    Returns per-step stats, wall ms per step and the prefill iteration time."""
-    B = w.batch
-    se.kv_reset([p + warmup + n_steps + 1 for p in w.prompt_lens])
-    sn.sn_set_timing(se.ctx, 0)
-    se.step_device(list(w.prompt_lens), True, x_pre, y_pre)
-    pre = sn.sn_get_stats(se.ctx).as_dict()
-    ones = [1] * B
-    for i in range(warmup):
-        se.step_device(ones, False, x_dec[i % len(x_dec)], y_dec)
-    se.stream.synchronize()
-    if timing_class is not None:
-        sn.sn_set_timing(se.ctx, 2)
-        sn.sn_set_kernel_timing_class(se.ctx, timing_class)
-    stats = []
-    torch.cuda.synchronize()
-    gc_was_on = gc.isenabled()
-    gc.disable()                                       # no collector pauses inside the timed region
-    t0 = time.perf_counter()
-    for i in range(n_steps):
-        se.step_device(ones, False, x_dec[i % len(x_dec)], y_dec)
-        stats.append(sn.sn_get_stats(se.ctx))          # synchronises the iteration
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / n_steps
-    if gc_was_on:
-        gc.enable()
-    sn.sn_set_timing(se.ctx, 0)
-    return [s.as_dict() for s in stats], wall_ms, pre
+class DecodeRig:
+    """One prefill, then any number of decode legs over the same prompt cache: a leg cuts the cache back to
+    the prompt (sn_kv_truncate), runs warm-up steps and then timed steps, each synchronised."""
+
+    def __init__(self, se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, max_steps):
+        self.se, self.sn, self.torch, self.w = se, sn, torch, w
+        self.x_pre, self.y_pre, self.x_dec, self.y_dec = x_pre, y_pre, x_dec, y_dec
+        self.max_steps = max_steps
+        self.prefilled = False
+
+    def prefill(self):
+        se, sn, w = self.se, self.sn, self.w
+        se.kv_reset([p + self.max_steps + 1 for p in w.prompt_lens])
+        sn.sn_set_timing(se.ctx, 0)
+        se.step_device(list(w.prompt_lens), True, self.x_pre, self.y_pre)
+        self.prefilled = True
+        return sn.sn_get_stats(se.ctx).as_dict()
+
+    def decode(self, n_steps, warmup, timing_class=None):
+        """Returns per-step stats and wall ms per step of n_steps timed decode iterations."""
+        se, sn, torch, w = self.se, self.sn, self.torch, self.w
+        assert warmup + n_steps <= self.max_steps
+        if not self.prefilled:
+            self.prefill()
+        se.kv_truncate(list(w.prompt_lens))
+        sn.sn_set_timing(se.ctx, 0)
+        ones = [1] * w.batch
+        for i in range(warmup):
+            se.step_device(ones, False, self.x_dec[i % len(self.x_dec)], self.y_dec)
+        se.stream.synchronize()
+        if timing_class is not None:
+            sn.sn_set_timing(se.ctx, 2)
+            sn.sn_set_kernel_timing_class(se.ctx, timing_class)
+        stats = []
+        torch.cuda.synchronize()
+        gc_was_on = gc.isenabled()
+        gc.disable()                                       # no collector pauses inside the timed region
+        t0 = time.perf_counter()
+        for i in range(n_steps):
+            se.step_device(ones, False, self.x_dec[i % len(self.x_dec)], self.y_dec)
+            stats.append(sn.sn_get_stats(se.ctx))          # synchronises the iteration
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / n_steps
+        if gc_was_on:
+            gc.enable()
+        sn.sn_set_timing(se.ctx, 0)
+        sn.sn_set_kernel_timing_class(se.ctx, -1)
+        return [s.as_dict() for s in stats], wall_ms
+
+
+def leg_summary(stats, wall_ms, slo_ns, B):
+    it = np.array([d["iter_ns"] for d in stats], dtype=np.float64)
+    h = sum(d["h2d_ns"] for d in stats)
+    hb = sum(d["h2d_bytes"] for d in stats)
+    st = sum(d["stall_ns"] for d in stats)
+    return {"n_offloaded": int(stats[-1]["n_offloaded"]), "tpot_median_ms": float(np.median(it)) / 1e6,
+            "tpot_max_ms": float(it.max()) / 1e6, "every_iteration_within_slo": bool((it <= slo_ns).all()),
+            "hidden_fraction": (1.0 - st / h) if h else 1.0, "h2d_GBps": (hb / (h * 1e-9) / 1e9) if h else None,
+            "h2d_bytes_per_step": hb / len(stats), "stall_ms_per_step": st / len(stats) / 1e6,
+            "tokens_per_s": B * 1e3 / wall_ms, "tokens_per_s_at_median_tpot": B / (float(np.median(it)) * 1e-9)}
 
 
 def run_prefill(se, sn, w, x_pre, y_pre, reps=2):
@@ -178,6 +220,16 @@ def cpu_baseline(w, seconds_target=12.0):
                       f"{', scaled from a partial step' if layer_passes < s.n_layers else ''}); every pass uses layer 0's weights"}
 
 
+def pick_or_none(sn, tc, tx, slo_ns, n_max, sched):
+    """Smallest interval meeting slo_ns under `sched`, L + 1 when only the un-offloaded iteration does."""
+    try:
+        return sn.sn_pick_interval_from_times_sched(tc, tx, int(slo_ns), n_max, sched)
+    except sn.SnError as e:
+        if e.code != sn.SN_E_INFEASIBLE:
+            raise
+        return len(tc) + 1
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -218,17 +270,40 @@ def main():
     g.manual_seed(1)
     T = int(sum(w.prompt_lens))
     with torch.cuda.stream(se.stream):
-        x_pre = torch.randn(T, s.hidden, generator=g, device="cuda", dtype=torch.float32).to(tdt)
+        x_pre = torch.empty(T, s.hidden, device="cuda", dtype=tdt)
+        for r0 in range(0, T, 8192):                           # in pieces: no fp32 copy of the whole prompt
+            r1 = min(T, r0 + 8192)
+            x_pre[r0:r1] = torch.randn(r1 - r0, s.hidden, generator=g, device="cuda", dtype=torch.float32).to(tdt)
         y_pre = torch.empty_like(x_pre)
         g.manual_seed(2)
         x_dec = [torch.randn(B, s.hidden, generator=g, device="cuda", dtype=torch.float32).to(tdt) for _ in range(8)]
         y_dec = torch.empty_like(x_dec[0])
     se.stream.synchronize()
 
-    # ---- all-resident reference: defines the SLO (TPOT without offloading) -------------
-    se.place(0)
-    run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, K, W)      # untimed pass: clocks and caches settle
-    st0, wall0, pre0 = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, K, W)
+    kvtok = s.kv_bytes_per_token
+    w_layer = sn.sn_layer_blob_bytes(se.cshape)
+    seq_prof = p_mean + W + K // 2               # the decode legs' mid-run cache length
+    PAPER, CONT = sn.SN_SCHED_PAPER, sn.SN_SCHED_CONTINUOUS
+
+    # ---- profiles (Sec. 4.4), before the prefill: the profiler runs on generated inputs and leaves the caches empty
+    t_prof = time.time()
+    profiles = {}
+    parts_wanted = ([] if a.no_parts else ["kv"]) + (["weights"] if a.full and not a.no_parts else [])
+    for name in parts_wanted:
+        sn.sn_set_offload_part(se.ctx, sn.SN_OFFLOAD_KV if name == "kv" else sn.SN_OFFLOAD_WEIGHTS)
+        profiles[name] = sn.sn_profile_layers(se.ctx, L, False, B, seq_prof, reps=3)
+    sn.sn_set_offload_part(se.ctx, sn.SN_OFFLOAD_STATE)
+    tc, tx = sn.sn_profile_layers(se.ctx, L, False, B, seq_prof, reps=3)     # last: the one sn_pick_interval uses
+    profiles["state"] = (tc, tx)
+    rho = float(np.median(tx) / np.median(tc))
+    log(f"[bench] profiles ({', '.join(profiles)}) in {time.time() - t_prof:.1f} s: tc median {np.median(tc) / 1e3:.1f} us, "
+        f"tx median {np.median(tx) / 1e3:.1f} us, rho {rho:.1f}, cv(tc) {np.std(tc) / np.mean(tc):.4f}")
+
+    # ---- ONE prefill, then the all-resident reference: defines the SLO (TPOT without offloading) -----
+    rig = DecodeRig(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, K + W)
+    pre0 = rig.prefill()
+    rig.decode(min(K, 8), W)                                  # untimed pass: clocks and caches settle
+    st0, wall0 = rig.decode(K, W)
     it0 = np.array([d["iter_ns"] for d in st0], dtype=np.float64)
     tpot0_ns = float(np.median(it0))
     slo_ns = int(a.slo_factor * tpot0_ns)
@@ -236,13 +311,12 @@ def main():
         f"prefill {pre0['iter_ns'] / 1e6:.2f} ms; SLO = {a.slo_factor} x = {slo_ns / 1e6:.3f} ms")
 
     # ---- where the all-resident decode step spends its time: each projection class timed alone, back to back
-    # over every layer's own weights (one pair of HIP events around the region: bracketing single launches
-    # would add microseconds to each); attention, the norms and the casts are what remains of the layer time ----
-    kvtok0 = s.kv_bytes_per_token
-    n_up0 = s.ffn * (2 if s.act == "swiglu" else 1)
+    # over every layer's own weights (one pair of HIP events around the region); attention, the norms and the
+    # casts are what remains of the layer time ----
+    n_up = s.ffn * (2 if s.act == "swiglu" else 1)
     qd0 = s.n_q_heads * s.head_dim
     class_bytes = {"qkv": (qd0 + 2 * s.n_kv_heads * s.head_dim) * s.hidden * 2, "oproj": s.hidden * qd0 * 2,
-                   "ffn_up": n_up0 * s.hidden * 2, "ffn_down": s.hidden * s.ffn * 2}
+                   "ffn_up": n_up * s.hidden * 2, "ffn_down": s.hidden * s.ffn * 2}
     breakdown = {}
     for name, cls in (("qkv", 1), ("oproj", 4), ("ffn_up", 5), ("ffn_down", 6)):
         ns, calls = sn.sn_time_kernel_class(se.ctx, cls, B, reps=2)
@@ -251,70 +325,71 @@ def main():
         breakdown[name] = {"us_per_launch": us, "weight_MB": class_bytes[name] / 1e6, "GBps": gbps, "frac_of_hbm_peak": gbps * 1e9 / HBM_PEAK}
     layer_us = tpot0_ns / L / 1e3
     rest_us = layer_us - sum(v["us_per_launch"] for v in breakdown.values())
-    kv_mb = (p_mean + W + K // 2) * B * kvtok0 / 1e6
+    kv_mb = seq_prof * B * kvtok / 1e6
     breakdown["attention_norms_casts"] = {"us_per_layer": rest_us, "kv_MB_per_layer": kv_mb}
     breakdown["layer_us"] = layer_us
     log("[bench] decode layer %.1f us: " % layer_us + ", ".join(
         f"{k} {v['us_per_launch']:.1f} us ({v['GBps'] / 1e3:.2f} TB/s)" for k, v in breakdown.items() if isinstance(v, dict) and "GBps" in v)
         + f", attention + norms + casts {rest_us:.1f} us (KV {kv_mb:.0f} MB)")
 
-    # ---- profile and pick ------------------------------------------------------------------
-    seq_prof = p_mean + W + K // 2
-    tc, tx = sn.sn_profile_layers(se.ctx, L, False, B, seq_prof, reps=5)
+    # ---- pick (Sec. 4.3 / 4.4) and the admission check against the capacity bound (Sec. 4.5) -------------
     n_max_cap = sn.sn_max_interval(se.ctx)
-    rho = float(np.median(tx) / np.median(tc))
     pick_slo_ns = int(slo_ns * (1.0 - a.guard))
+    n_min = pick_or_none(sn, tc, tx, pick_slo_ns, L + 1, PAPER)
     try:
-        n_pick_cap = sn.sn_pick_interval(se.ctx, pick_slo_ns / 1e6)
+        n_pick_cap = sn.sn_pick_interval(se.ctx, pick_slo_ns / 1e6)      # the last profile, the budget, the schedule
         feasible_at_cap = True
     except sn.SnError as e:
         if e.code != sn.SN_E_INFEASIBLE:
             raise
         n_pick_cap, feasible_at_cap = None, False
-    try:
-        n_min = sn.sn_pick_interval_from_times(tc, tx, pick_slo_ns, L + 1)
-    except sn.SnError:
-        n_min = L + 1
     pred_ns, _ = sn.sn_timeline(tc, tx, n_min)
     n_paper = sn.sn_paper_rule(L, int(np.median(tx)), slo_ns)
-    log(f"[bench] profile: tc median {np.median(tc) / 1e3:.1f} us, tx median {np.median(tx) / 1e3:.1f} us, rho {rho:.1f}; "
-        f"N_min(SLO)={n_min} N_max(cap)={n_max_cap} feasible_at_cap={feasible_at_cap} paper_rule={n_paper} "
+    log(f"[bench] N_min(SLO)={n_min} N_max(cap)={n_max_cap} feasible_at_cap={feasible_at_cap} paper_rule={n_paper} "
         f"predicted T(N_min)={pred_ns / 1e6:.3f} ms")
     n_run = n_pick_cap if feasible_at_cap else n_min
 
-    # ---- the measured run at the picked interval --------------------------------------------
+    # ---- the measured run at the picked interval: the headline ---------------------------------------------
     se.place(n_run)
-    st, wall_ms, pre = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, K, W)
+    st, wall_ms = rig.decode(K, W)
+    head = leg_summary(st, wall_ms, slo_ns, B)
     it = np.array([d["iter_ns"] for d in st], dtype=np.float64)
-    h2d_ns = sum(d["h2d_ns"] for d in st)
-    h2d_bytes = sum(d["h2d_bytes"] for d in st)
-    stall_ns = sum(d["stall_ns"] for d in st)
     value = B * 1e3 / wall_ms
-    # Dominant kernel, timed live with one pair of HIP events on the compute stream around
-    # a region of its launches: the FFN up-projection of every GPU-resident layer on that
-    # layer's own weights (distinct buffers, far larger than the caches), several rounds.
+    log(f"[bench] N={n_run} (K={head['n_offloaded']}): TPOT median {head['tpot_median_ms']:.3f} ms max {head['tpot_max_ms']:.3f} ms "
+        f"(SLO {slo_ns / 1e6:.3f}), wall {wall_ms:.3f} ms/step -> {value:.1f} tok/s, hidden {head['hidden_fraction']:.3f}")
+
+    # ---- the dominant kernel (FFN up-projection of the decode step), timed live: (i) inside iterations under this
+    # placement, each launch bracketed by its own start/stop timestamps (what a kernel trace shows); (ii) on its own,
+    # back to back over every resident layer's weights between one pair of events (launch gaps included) ----------
+    kst, _ = rig.decode(min(K, 4), 1, timing_class=5)
+    in_ns = sum(d["kernel_ns"]["ffn_up"] for d in kst)
+    in_calls = sum(d["kernel_calls"]["ffn_up"] for d in kst)
     k_ns, k_calls = sn.sn_time_kernel_class(se.ctx, 5, B, reps=4)
-    # dominant kernel: FFN up-projection weight stream.  Algorithmic bytes per launch:
-    # weights ffn*hidden*2 + bias ffn*2 + activations in B*hidden*2 + out B*ffn*2.
-    n_up = s.ffn * (2 if s.act == "swiglu" else 1)
+    # algorithmic bytes per launch: weights + bias + activations in + out
     alg_bytes = n_up * s.hidden * 2 + (n_up * 2 if s.has_bias else 0) + B * s.hidden * 2 + B * s.ffn * 2
-    k_avg_ns = k_ns / max(k_calls, 1)
+    k_avg_ns = in_ns / max(in_calls, 1)
+    iso_avg_ns = k_ns / max(k_calls, 1)
     achieved = alg_bytes / (k_avg_ns * 1e-9) if k_avg_ns > 0 else 0.0
+    note = TRAFFIC_NOTES.get((w.name, B))
+    traffic = read_traffic_note(note) if note else None
     roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel (FFN up-projection, decode)", "achieved": achieved / 1e9,
-                "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": achieved / HBM_PEAK,
-                "traffic": read_traffic_note("gemm_skinny_ffn_up_c2_pmc.txt") if w.name == "c2" and B == 8 else None,
-                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": k_avg_ns / 1e3, "launches_timed": k_calls}
+                "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": traffic,
+                "traffic_source": (f"profiles/{note}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, collected offline "
+                                   "(counters cannot be read from inside the run)") if traffic else None,
+                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": k_avg_ns / 1e3, "launches_timed": in_calls,
+                "timed": "every launch inside decode iterations at the picked interval, own start/stop timestamps",
+                "isolated_back_to_back": {"avg_launch_us": iso_avg_ns / 1e3, "launches": k_calls,
+                                          "GBps": alg_bytes / (iso_avg_ns * 1e-9) / 1e9 if iso_avg_ns > 0 else None}}
+    log(f"[bench] ffn_up inside iterations {k_avg_ns / 1e3:.1f} us = {achieved / 1e9:.0f} GB/s ({in_calls} launches); "
+        f"back to back {iso_avg_ns / 1e3:.1f} us")
     # whole-step HBM roofline: every weight and every cached K/V element is read once per step
-    kvtok = s.kv_bytes_per_token
-    len_mid = p_mean + W + K // 2
-    step_bytes = L * (sn.sn_layer_blob_bytes(se.cshape) + len_mid * B * kvtok)
+    step_bytes = L * (w_layer + seq_prof * B * kvtok)
     # prefill: dense contractions.  2 flop per weight element per token, plus causal attention
     # (QK^T and PV: 4 * Hq * d flop per (query, visible key) pair)
     w_elems = s.hidden * (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim + s.n_q_heads * s.head_dim * s.hidden \
         + s.hidden * s.ffn * (3 if s.act == "swiglu" else 2)
     pre_flops = L * (2.0 * w_elems * T + 4.0 * s.n_q_heads * s.head_dim * sum(p * (p + 1) / 2 for p in w.prompt_lens))
-    log(f"[bench] N={n_run}: TPOT median {np.median(it) / 1e6:.3f} ms max {it.max() / 1e6:.3f} ms (SLO {slo_ns / 1e6:.3f}), "
-        f"wall {wall_ms:.3f} ms/step -> {value:.1f} tok/s; ffn_up {k_avg_ns / 1e3:.1f} us = {achieved / 1e9:.0f} GB/s")
+    over_cap = bool(sn.sn_resident_bytes(se.ctx, n_run) > w.hbm_budget > 0)
 
     out = {
         "metric": "decode tok/s at max-offload interval meeting TPOT SLO; HBM + H2D GB/s",
@@ -326,39 +401,43 @@ def main():
                                f"{s.ffn}, {'fp16' if s.dtype == 'f16' else 'bf16'} random weights N(0,0.02), batch {B}, prompt "
                                f"{w.prompt_lens[0] if min(w.prompt_lens) == max(w.prompt_lens) else f'{min(w.prompt_lens)}..{max(w.prompt_lens)}'}"
                                f", teacher-forced decode; HBM budget {w.hbm_budget / 1e9:.0f} GB; TPOT SLO {a.slo_factor}x all-resident",
-                   "interval": int(n_run), "n_offloaded": int(st[-1]["n_offloaded"]),
-                   "interval_over_cap": bool(sn.sn_resident_bytes(se.ctx, n_run) > w.hbm_budget > 0)},
+                   "interval": int(n_run), "n_offloaded": head["n_offloaded"], "schedule": "paper (Fig. 7)",
+                   "host_resident_GB": head["n_offloaded"] * (w_layer + seq_prof * B * kvtok) / 1e9,
+                   "interval_over_cap": over_cap,
+                   "admission_at_cap": ("feasible" if feasible_at_cap else
+                                        f"SN_E_INFEASIBLE: smallest interval meeting the SLO is {n_min}, largest the {w.hbm_budget / 1e9:.0f} GB "
+                                        f"cap holds is {n_max_cap}; under Sec. 4.5 this request goes back to the scheduler.  Timed with the "
+                                        f"cap lifted (the device holds 288 GB) at the smallest interval that meets the SLO")},
         "roofline": roofline,
-        "slo": {"tpot_all_resident_ms": tpot0_ns / 1e6, "slo_ms": slo_ns / 1e6, "tpot_median_ms": float(np.median(it)) / 1e6,
-                "tpot_max_ms": float(it.max()) / 1e6, "every_iteration_within_slo": bool((it <= slo_ns).all()),
+        "slo": {"tpot_all_resident_ms": tpot0_ns / 1e6, "slo_ms": slo_ns / 1e6, "tpot_median_ms": head["tpot_median_ms"],
+                "tpot_max_ms": head["tpot_max_ms"], "every_iteration_within_slo": head["every_iteration_within_slo"],
                 "guard_band": a.guard, "n_min_slo": int(n_min), "n_max_cap": int(n_max_cap), "feasible_at_cap": feasible_at_cap,
                 "paper_closed_form_interval": int(n_paper), "predicted_iter_ms": pred_ns / 1e6,
                 "rho_transfer_over_compute": rho, "layer_compute_us_median": float(np.median(tc)) / 1e3,
                 "layer_transfer_us_median": float(np.median(tx)) / 1e3,
                 "layer_compute_cv": float(np.std(tc) / np.mean(tc))},
-        "h2d": {"bytes_per_step": h2d_bytes / K, "achieved_GBps": (h2d_bytes / (h2d_ns * 1e-9) / 1e9) if h2d_ns else None,
-                "solo_GBps": float((sn.sn_layer_blob_bytes(se.cshape) + seq_prof * B * kvtok) / (np.median(tx) * 1e-9) / 1e9),
+        "h2d": {"bytes_per_step": head["h2d_bytes_per_step"], "achieved_GBps": head["h2d_GBps"],
+                "solo_GBps": float((w_layer + seq_prof * B * kvtok) / (np.median(tx) * 1e-9) / 1e9),
                 "nominal_link_GBps": LINK_NOMINAL / 1e9,
-                "hidden_fraction": (1.0 - stall_ns / h2d_ns) if h2d_ns else 1.0, "stall_ms_per_step": stall_ns / K / 1e6},
+                "hidden_fraction": head["hidden_fraction"], "stall_ms_per_step": head["stall_ms_per_step"]},
         "hbm_step": {"algorithmic_bytes_per_step": step_bytes, "all_resident_GBps": step_bytes / (tpot0_ns * 1e-9) / 1e9,
                      "frac_of_peak": step_bytes / (tpot0_ns * 1e-9) / HBM_PEAK,
+                     "all_resident_tokens_per_s": B / (tpot0_ns * 1e-9),
                      "roofline_tokens_per_s": B * HBM_PEAK / step_bytes},
         "decode_layer_breakdown": breakdown,
-        "prefill": {"iter_ms_all_resident": pre0["iter_ns"] / 1e6, "iter_ms_at_interval": pre["iter_ns"] / 1e6,
-                    "tokens": T, "algorithmic_tflop": pre_flops / 1e12,
+        "prefill": {"iter_ms_all_resident": pre0["iter_ns"] / 1e6, "tokens": T, "algorithmic_tflop": pre_flops / 1e12,
                     "all_resident_TFLOPs": pre_flops / (pre0["iter_ns"] * 1e-9) / 1e12,
                     "frac_of_mfma_peak": pre_flops / (pre0["iter_ns"] * 1e-9) / MFMA_PEAK},
     }
 
     # Sec. 5.6 / Fig. 14: tokens ("max length" = batch x (sequence + output)) the HBM budget can hold per interval
     if w.hbm_budget > 0:
-        wl = sn.sn_layer_blob_bytes(se.cshape)
-        base_tok = sn.sn_max_tokens(L, 0, wl, kvtok, 0, w.hbm_budget)
+        base_tok = sn.sn_max_tokens(L, 0, w_layer, kvtok, 0, w.hbm_budget)
         out["max_length_vs_interval"] = {
             "hbm_budget_GB": w.hbm_budget / 1e9, "workspace": "excluded",
-            "rows": [{"interval": int(N), "max_tokens": int(sn.sn_max_tokens(L, N, wl, kvtok, 0, w.hbm_budget)),
-                      "max_tokens_weights_only": int(sn.sn_max_tokens_part(L, N, wl, kvtok, 0, w.hbm_budget, sn.SN_OFFLOAD_WEIGHTS)),
-                      "max_tokens_kv_only": int(sn.sn_max_tokens_part(L, N, wl, kvtok, 0, w.hbm_budget, sn.SN_OFFLOAD_KV))}
+            "rows": [{"interval": int(N), "max_tokens": int(sn.sn_max_tokens(L, N, w_layer, kvtok, 0, w.hbm_budget)),
+                      "max_tokens_weights_only": int(sn.sn_max_tokens_part(L, N, w_layer, kvtok, 0, w.hbm_budget, sn.SN_OFFLOAD_WEIGHTS)),
+                      "max_tokens_kv_only": int(sn.sn_max_tokens_part(L, N, w_layer, kvtok, 0, w.hbm_budget, sn.SN_OFFLOAD_KV))}
                      for N in sorted({1, 2, 3, 4, 6, 8, 16, L, L + 1}) if N <= L + 1],
             "no_offloading_tokens": int(base_tok)}
 
@@ -371,121 +450,98 @@ def main():
         se.stream.synchronize()
         del src, dst
 
+    def decode_point(f, tcp_, txp_, sched, steps):
+        """Pick for SLO f x the all-resident TPOT under `sched` from the given profile, place, run, check."""
+        slo_f = int(f * tpot0_ns)
+        n_f = pick_or_none(sn, tcp_, txp_, int(slo_f * (1.0 - a.guard)), L + 1, sched)
+        se.place(n_f)
+        fst, fwall = rig.decode(steps, W)
+        pt = {"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f), **leg_summary(fst, fwall, slo_f, B)}
+        pred, _ = sn.sn_timeline_sched(tcp_, txp_, n_f, sched)
+        pt["predicted_ms"] = pred / 1e6
+        pt["resident_GB"] = sn.sn_resident_bytes(se.ctx, n_f) / 1e9
+        pt["over_cap"] = bool(sn.sn_resident_bytes(se.ctx, n_f) > w.hbm_budget > 0)
+        pt["loads_issued_ahead_per_step"] = int(fst[-1]["n_preissued"])
+        return pt
+
+    k_short = max(4, min(K, 16))
+    extra_factors = [float(v) for v in a.slo_points.split(",") if v] if (a.full and a.slo_points) else []
+
     # ---- the picker at looser SLOs: pick, run, check every iteration (over-cap points labelled) ----
-    if not a.no_sweep and a.slo_points:
+    if extra_factors:
         pts = []
-        for f in [float(v) for v in a.slo_points.split(",") if v]:
-            slo_f = int(f * tpot0_ns)
-            try:
-                n_f = sn.sn_pick_interval_from_times(tc, tx, int(slo_f * (1.0 - a.guard)), L + 1)
-            except sn.SnError:
-                n_f = L + 1
-            se.place(n_f)
-            fst, fwall, _ = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, max(4, min(K, 8)), W)
-            fit = np.array([d["iter_ns"] for d in fst], dtype=np.float64)
-            fh = sum(d["h2d_ns"] for d in fst)
-            fs = sum(d["stall_ns"] for d in fst)
-            fb = sum(d["h2d_bytes"] for d in fst)
-            pred, _ = sn.sn_timeline(tc, tx, n_f)
-            pts.append({"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f),
-                        "n_offloaded": int(fst[-1]["n_offloaded"]), "tpot_median_ms": float(np.median(fit)) / 1e6,
-                        "tpot_max_ms": float(fit.max()) / 1e6, "predicted_ms": pred / 1e6,
-                        "every_iteration_within_slo": bool((fit <= slo_f).all()),
-                        "hidden_fraction": (1 - fs / fh) if fh else 1.0,
-                        "h2d_GBps": fb / (fh * 1e-9) / 1e9 if fh else None,
-                        "resident_GB": sn.sn_resident_bytes(se.ctx, n_f) / 1e9,
-                        "over_cap": bool(sn.sn_resident_bytes(se.ctx, n_f) > w.hbm_budget > 0),
-                        "tokens_per_s": B * 1e3 / fwall})
-            log(f"[bench] SLO {f}x = {slo_f / 1e6:.2f} ms: picked N={n_f} (K={pts[-1]['n_offloaded']}), TPOT median "
-                f"{pts[-1]['tpot_median_ms']:.3f} max {pts[-1]['tpot_max_ms']:.3f} (predicted {pred / 1e6:.3f}) "
+        for f in extra_factors:
+            pts.append(decode_point(f, tc, tx, PAPER, max(4, min(K, 8))))
+            log(f"[bench] SLO {f}x: picked N={pts[-1]['picked_interval']} (K={pts[-1]['n_offloaded']}), TPOT median "
+                f"{pts[-1]['tpot_median_ms']:.3f} max {pts[-1]['tpot_max_ms']:.3f} (predicted {pts[-1]['predicted_ms']:.3f}) "
                 f"within={pts[-1]['every_iteration_within_slo']} hidden {pts[-1]['hidden_fraction']:.3f}")
         out["slo_points"] = pts
 
     # ---- decode with loads that run on across the iteration boundary (continuous schedule): the steady
     # state the analyzer's closed form describes -- floor(SLO / transfer) layers fit one iteration -----------
     if not a.no_continuous:
-        factors = [a.slo_factor] + ([float(v) for v in a.slo_points.split(",") if v] if (a.slo_points and not a.no_sweep) else [])
-        sn.sn_set_schedule(se.ctx, sn.SN_SCHED_CONTINUOUS)
+        sn.sn_set_schedule(se.ctx, CONT)
         cont = []
-        for f in factors:
-            slo_f = int(f * tpot0_ns)
-            try:
-                n_f = sn.sn_pick_interval_from_times_sched(tc, tx, int(slo_f * (1.0 - a.guard)), L + 1, sn.SN_SCHED_CONTINUOUS)
-            except sn.SnError:
-                n_f = L + 1
-            try:
-                n_paper_sched = sn.sn_pick_interval_from_times(tc, tx, int(slo_f * (1.0 - a.guard)), L + 1)
-            except sn.SnError:
-                n_paper_sched = L + 1
-            se.place(n_f)
-            n_c = max(4, min(K, 16))
-            cst, cwall, _ = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, n_c, W)
-            cit = np.array([d["iter_ns"] for d in cst], dtype=np.float64)
-            ch = sum(d["h2d_ns"] for d in cst)
-            cs = sum(d["stall_ns"] for d in cst)
-            cb = sum(d["h2d_bytes"] for d in cst)
-            pred, _ = sn.sn_timeline_sched(tc, tx, n_f, sn.SN_SCHED_CONTINUOUS)
-            pred_paper, _ = sn.sn_timeline(tc, tx, n_f)
-            cont.append({"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f),
-                         "interval_picked_for_the_papers_schedule": int(n_paper_sched),
-                         "n_offloaded": int(cst[-1]["n_offloaded"]), "loads_issued_ahead_per_step": int(cst[-1]["n_preissued"]),
-                         "tpot_median_ms": float(np.median(cit)) / 1e6, "tpot_max_ms": float(cit.max()) / 1e6,
-                         "predicted_steady_state_ms": pred / 1e6, "predicted_papers_schedule_ms": pred_paper / 1e6,
-                         "every_iteration_within_slo": bool((cit <= slo_f).all()),
-                         "hidden_fraction": (1 - cs / ch) if ch else 1.0,
-                         "h2d_GBps": cb / (ch * 1e-9) / 1e9 if ch else None,
-                         "host_resident_GB": int(cst[-1]["n_offloaded"]) * (sn.sn_layer_blob_bytes(se.cshape) + seq_prof * B * kvtok) / 1e9,
-                         "tokens_per_s": B * 1e3 / cwall, "tokens_per_s_at_median_tpot": B / (float(np.median(cit)) * 1e-9)})
-            log(f"[bench] continuous schedule, SLO {f}x = {slo_f / 1e6:.2f} ms: picked N={n_f} (K={cont[-1]['n_offloaded']}; paper's schedule "
-                f"needs N={n_paper_sched}), TPOT median {cont[-1]['tpot_median_ms']:.3f} max {cont[-1]['tpot_max_ms']:.3f} "
-                f"(predicted {pred / 1e6:.3f}; paper's schedule at this N {pred_paper / 1e6:.3f}) within={cont[-1]['every_iteration_within_slo']} "
-                f"hidden {cont[-1]['hidden_fraction']:.3f} issued ahead {cont[-1]['loads_issued_ahead_per_step']} -> {cont[-1]['tokens_per_s']:.1f} tok/s")
-        sn.sn_set_schedule(se.ctx, sn.SN_SCHED_PAPER)
+        for f in [a.slo_factor] + extra_factors:
+            pt = decode_point(f, tc, tx, CONT, k_short)
+            pt["interval_picked_for_the_papers_schedule"] = int(pick_or_none(sn, tc, tx, int(f * tpot0_ns * (1.0 - a.guard)), L + 1, PAPER))
+            pt["predicted_papers_schedule_ms"] = sn.sn_timeline(tc, tx, pt["picked_interval"])[0] / 1e6
+            pt["host_resident_GB"] = pt["n_offloaded"] * (w_layer + seq_prof * B * kvtok) / 1e9
+            cont.append(pt)
+            log(f"[bench] continuous schedule, SLO {f}x: picked N={pt['picked_interval']} (K={pt['n_offloaded']}), TPOT median "
+                f"{pt['tpot_median_ms']:.3f} max {pt['tpot_max_ms']:.3f} (predicted {pt['predicted_ms']:.3f}; paper's schedule at this N "
+                f"{pt['predicted_papers_schedule_ms']:.3f}) within={pt['every_iteration_within_slo']} hidden {pt['hidden_fraction']:.3f} "
+                f"issued ahead {pt['loads_issued_ahead_per_step']} -> {pt['tokens_per_s']:.1f} tok/s")
+        sn.sn_set_schedule(se.ctx, PAPER)
         out["decode_continuous_schedule"] = cont
 
-    # ---- host-resident layers that keep only their weights, or only their KV slice, on the host: smaller
+    # ---- host-resident layers that keep only their KV slice (or only their weights) on the host: smaller
     # loads, so the same SLO admits more layers (at the price of the part that stays on the GPU) ---------------
-    if not a.no_parts:
+    if parts_wanted:
         parts = []
-        for what, name in ((sn.SN_OFFLOAD_WEIGHTS, "weights"), (sn.SN_OFFLOAD_KV, "kv")):
+        for name in parts_wanted:
+            what = sn.SN_OFFLOAD_KV if name == "kv" else sn.SN_OFFLOAD_WEIGHTS
+            tcw, txw = profiles[name]
             se.place(0)
             sn.sn_set_offload_part(se.ctx, what)
-            tcw, txw = sn.sn_profile_layers(se.ctx, L, False, B, seq_prof, reps=3)
             row = {"part_on_host": name, "layer_transfer_us_median": float(np.median(txw)) / 1e3,
                    "rho_transfer_over_compute": float(np.median(txw) / np.median(tcw)), "points": []}
-            for sched, sname in ((sn.SN_SCHED_PAPER, "paper"), (sn.SN_SCHED_CONTINUOUS, "continuous")):
+            for sched, sname in ((PAPER, "paper"), (CONT, "continuous")):
                 sn.sn_set_schedule(se.ctx, sched)
-                slo_f = int(a.slo_factor * tpot0_ns)
-                try:
-                    n_f = sn.sn_pick_interval_from_times_sched(tcw, txw, int(slo_f * (1.0 - a.guard)), L + 1, sched)
-                except sn.SnError:
-                    n_f = L + 1
-                se.place(n_f)
-                n_c = max(4, min(K, 8))
-                pst, pwall, _ = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, n_c, W)
-                pit = np.array([d["iter_ns"] for d in pst], dtype=np.float64)
-                k_f = int(pst[-1]["n_offloaded"])
-                pred, _ = sn.sn_timeline_sched(tcw, txw, n_f, sched)
-                host_gb = k_f * (sn.sn_layer_blob_bytes(se.cshape) if name == "weights" else seq_prof * B * kvtok) / 1e9
-                row["points"].append({"schedule": sname, "slo_factor": a.slo_factor, "picked_interval": int(n_f), "n_offloaded": k_f,
-                                      "tpot_median_ms": float(np.median(pit)) / 1e6, "tpot_max_ms": float(pit.max()) / 1e6,
-                                      "predicted_ms": pred / 1e6, "every_iteration_within_slo": bool((pit <= slo_f).all()),
-                                      "h2d_bytes_per_step": pst[-1]["h2d_bytes"], "host_resident_GB": host_gb,
-                                      "resident_GB": sn.sn_resident_bytes(se.ctx, n_f) / 1e9,
-                                      "tokens_per_s_at_median_tpot": B / (float(np.median(pit)) * 1e-9)})
+                pt = decode_point(a.slo_factor, tcw, txw, sched, k_short)
+                pt["schedule"] = sname
+                pt["host_resident_GB"] = pt["n_offloaded"] * (w_layer if name == "weights" else seq_prof * B * kvtok) / 1e9
+                row["points"].append(pt)
                 log(f"[bench] {name} only on the host, {sname} schedule, SLO {a.slo_factor}x: tx {row['layer_transfer_us_median']:.0f} us "
-                    f"(rho {row['rho_transfer_over_compute']:.1f}); picked N={n_f} (K={k_f}, {host_gb:.2f} GB on the host), TPOT median "
-                    f"{np.median(pit) / 1e6:.3f} max {pit.max() / 1e6:.3f} (predicted {pred / 1e6:.3f}) "
-                    f"within={row['points'][-1]['every_iteration_within_slo']}")
-            sn.sn_set_schedule(se.ctx, sn.SN_SCHED_PAPER)
+                    f"(rho {row['rho_transfer_over_compute']:.1f}); picked N={pt['picked_interval']} (K={pt['n_offloaded']}, "
+                    f"{pt['host_resident_GB']:.2f} GB on the host), TPOT median {pt['tpot_median_ms']:.3f} max {pt['tpot_max_ms']:.3f} "
+                    f"(predicted {pt['predicted_ms']:.3f}) within={pt['every_iteration_within_slo']} hidden {pt['hidden_fraction']:.3f}")
+            sn.sn_set_schedule(se.ctx, PAPER)
             parts.append(row)
         se.place(0)
         sn.sn_set_offload_part(se.ctx, sn.SN_OFFLOAD_STATE)
         out["decode_by_offloaded_part"] = parts
 
+    # ---- interval sweep (reported, over-cap points labelled) ------------------------------------
+    if a.full:
+        sweep = []
+        for N in list(w.intervals) + [L]:
+            se.place(N)
+            sst, swall = rig.decode(max(4, min(K, 8)), 1)
+            row = {"interval": N, **leg_summary(sst, swall, slo_ns, B)}
+            pred, _ = sn.sn_timeline(tc, tx, N)
+            row.update({"x_all_resident": row["tpot_median_ms"] * 1e6 / tpot0_ns, "predicted_ms": pred / 1e6,
+                        "resident_GB": sn.sn_resident_bytes(se.ctx, N) / 1e9,
+                        "over_cap": bool(sn.sn_resident_bytes(se.ctx, N) > w.hbm_budget > 0)})
+            sweep.append(row)
+            log(f"[bench] sweep N={N}: TPOT {row['tpot_median_ms']:.3f} ms ({row['x_all_resident']:.2f}x, predicted "
+                f"{pred / 1e6:.3f}) hidden {row['hidden_fraction']:.3f} h2d {row['h2d_GBps']} GB/s")
+        out["sweep"] = sweep
+    se.place(0)
+
     # ---- the prefill phase has its own profile and its own interval (Sec. 4.4, separation of
     # prefill and decoding): TTFT SLOs relative to the all-resident prefill iteration ------------
-    if not a.no_sweep and a.prefill_slo_points:
+    if a.full and a.prefill_slo_points:
         se.place(0)
         ttft0 = float(min(d["iter_ns"] for d in run_prefill(se, sn, w, x_pre, y_pre, 2)))
         tcp, txp = sn.sn_profile_layers(se.ctx, L, True, B, p_mean, reps=3)
@@ -688,29 +744,6 @@ def main():
             f"within={out['repick']['every_iteration_within_slo']} migration {mig_ms:.1f} ms")
         R.sn_record_destroy(rec)
 
-    # ---- interval sweep (reported, over-cap points labelled) ------------------------------------
-    if not a.no_sweep:
-        sweep = []
-        ks = max(4, min(K, 8))
-        for N in list(w.intervals) + [L]:
-            se.place(N)
-            sst, swall, spre = run_decode(se, sn, torch, w, x_pre, y_pre, x_dec, y_dec, ks, 1)
-            sit = np.array([d["iter_ns"] for d in sst], dtype=np.float64)
-            sh = sum(d["h2d_ns"] for d in sst)
-            sb = sum(d["h2d_bytes"] for d in sst)
-            ss = sum(d["stall_ns"] for d in sst)
-            pred, _ = sn.sn_timeline(tc, tx, N)
-            sweep.append({"interval": N, "n_offloaded": sst[-1]["n_offloaded"], "tpot_ms": float(np.median(sit)) / 1e6,
-                          "x_all_resident": float(np.median(sit)) / tpot0_ns, "predicted_ms": pred / 1e6,
-                          "meets_slo": bool((sit <= slo_ns).all()), "hidden_fraction": (1 - ss / sh) if sh else 1.0,
-                          "h2d_GBps": sb / (sh * 1e-9) / 1e9 if sh else None,
-                          "resident_GB": sn.sn_resident_bytes(se.ctx, N) / 1e9,
-                          "over_cap": bool(sn.sn_resident_bytes(se.ctx, N) > w.hbm_budget > 0),
-                          "prefill_ms": spre["iter_ns"] / 1e6, "prefill_hidden_fraction": spre["hidden_fraction"]})
-            log(f"[bench] sweep N={N}: TPOT {sweep[-1]['tpot_ms']:.3f} ms ({sweep[-1]['x_all_resident']:.2f}x, predicted "
-                f"{pred / 1e6:.3f}) hidden {sweep[-1]['hidden_fraction']:.3f} h2d {sweep[-1]['h2d_GBps']} GB/s "
-                f"prefill {sweep[-1]['prefill_ms']:.2f} ms")
-        out["sweep"] = sweep
     se.close()
 
     if not a.no_cpu:

@@ -206,6 +206,13 @@ int sn_placement_sched(int32_t L, int32_t N, int32_t schedule, uint8_t* offloade
  * sum must fit max_batch*max_seq.  All lengths become 0. */
 int sn_kv_reset(sn_ctx* ctx, int32_t batch, const int32_t* capacity);
 
+/* Shorten the cached sequences: len (host, [batch]) gives the new token counts, none larger than
+ * the current one.  The rows beyond them are dropped (capacities and layout stay), so the next
+ * iteration continues from there -- e.g. a rejected speculative continuation, or a benchmark
+ * that runs the same decode steps under several placements after one prefill.  The caller
+ * sets its own sn_kv.len to the same values.  Bookkeeping only: nothing is copied. */
+int sn_kv_truncate(sn_ctx* ctx, int32_t batch, const int32_t* len);
+
 /* --- one serving iteration (Sec. 4.3, Fig. 7) ----------------------------------
  * Enqueues the whole layer loop and returns without waiting for the GPU.
  * hidden_out: device, [sum n_new, hidden], shape.dtype: hidden states after the last
@@ -238,6 +245,29 @@ int sn_get_stats(sn_ctx* ctx, sn_step_stats* out);
 /* Per-layer figures of the last sn_step (timing level >= 1): host arrays [n_layers];
  * stall_ns[l] is 0 for resident layers.  Any pointer may be NULL. */
 int sn_get_layer_times(sn_ctx* ctx, int64_t* compute_ns, int64_t* stall_ns, int64_t* h2d_ns);
+
+/* Test switches for the ordering that Sec. 4.3 / Fig. 7 requires between the compute stream and
+ * the copy streams.  They change when things happen, never what is computed: with any
+ * combination the output must be bit-identical to a run without them.  Every added kernel ends
+ * by itself (the delays are bounded waits).
+ *   SN_DEBUG_POISON_SLOT:   before each load, once its staging slot has been released, a fill
+ *                           kernel on the copy stream overwrites the bytes the load will bring
+ *                           with 16-bit NaN patterns: whoever still reads the slot's previous
+ *                           layer, or reads the slot before the load has landed, yields NaN.
+ *   SN_DEBUG_DELAY_H2D:     the copy stream waits delay_us before each load (after the poison):
+ *                           compute reaches the host-resident layer first and must stall at the
+ *                           synchronisation point "S"; stall_ns grows by about the delay.
+ *   SN_DEBUG_DELAY_COMPUTE: the compute stream waits delay_us at the start of every layer, after
+ *                           the loads triggered there have been handed over: the copy stream gets
+ *                           ahead, so a kernel of that layer that still read a slot released by the
+ *                           previous layer would find the poison or the next layer's weights.
+ *   SN_DEBUG_DELAY_D2H:     the write-back stream waits delay_us before each prefill write-back of
+ *                           a KV slice: the next iteration's load of that slice, its rows written
+ *                           through while decoding, and the reuse of the staging slot all have to
+ *                           wait for the write-back.
+ * delay_us: 0..20000.  Synchronises all streams; flags == 0 switches everything off. */
+enum { SN_DEBUG_POISON_SLOT = 1, SN_DEBUG_DELAY_H2D = 2, SN_DEBUG_DELAY_COMPUTE = 4, SN_DEBUG_DELAY_D2H = 8 };
+int sn_set_debug(sn_ctx* ctx, int32_t flags, int32_t delay_us);
 
 /* --- profiler and picker (Sec. 4.4) --------------------------------------------
  * Runs `reps` iterations of the given kind (prefill of `seq` tokens per sequence, or

@@ -49,6 +49,38 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
   return hipGetLastError();
 }
 
+// Fill with a 32-bit pattern, 16 bytes per thread per trip (debug: poisoning a released staging slot).
+__global__ __launch_bounds__(256) void fill_kernel(u32x4* __restrict__ dst, size_t n16, uint32_t pattern) {
+  const u32x4 v = u32x4{pattern, pattern, pattern, pattern};
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = v;
+}
+
+hipError_t launch_fill(void* dst, size_t bytes, uint32_t pattern, hipStream_t st) {
+  if (bytes == 0) return hipSuccess;
+  if (bytes % 16) return hipErrorInvalidValue;
+  const size_t n16 = bytes / 16;
+  const unsigned grid = (unsigned)std::min<size_t>(2048, (n16 + 255) / 256);
+  SN_LAUNCH(fill_kernel, dim3(grid), dim3(256), 0, st, (u32x4*)dst, n16, pattern);
+  return hipGetLastError();
+}
+
+// Occupies a stream for about `ticks` periods of the constant-rate wall clock (debug: delaying one of the
+// streams so that an ordering that usually holds by luck has to be enforced by its fence).  One wavefront;
+// it leaves when the time is up or after max_trips sleeps, whichever comes first, so it always ends.
+__global__ void delay_kernel(uint64_t ticks, int max_trips) {
+  const uint64_t t0 = wall_clock64();
+  for (int i = 0; i < max_trips; ++i) {
+    if ((uint64_t)wall_clock64() - t0 >= ticks) break;
+    __builtin_amdgcn_s_sleep(64);
+  }
+}
+
+hipError_t launch_delay(uint64_t ticks, int max_trips, hipStream_t st) {
+  if (ticks == 0 || max_trips < 1) return hipSuccess;
+  SN_LAUNCH(delay_kernel, dim3(1), dim3(64), 0, st, ticks, max_trips);
+  return hipGetLastError();
+}
+
 static inline int grid_for(size_t n, int block) {
   size_t g = (n + block - 1) / block;
   return (int)(g < 1 ? 1 : (g > 4096 ? 4096 : g));

@@ -53,6 +53,10 @@ hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, h
 hipError_t launch_cast_out_fold(int dtype, int bias_dtype, float* x32, void* out16, int T, int h, const Fold& fold,
                                 hipStream_t st);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+// Debug aids: fill `bytes` (multiple of 16) with a 32-bit pattern; keep a stream busy for `ticks` wall-clock
+// periods (bounded by max_trips sleeps of a few microseconds each, so the kernel always ends).
+hipError_t launch_fill(void* dst, size_t bytes, uint32_t pattern, hipStream_t st);
+hipError_t launch_delay(uint64_t ticks, int max_trips, hipStream_t st);
 hipError_t launch_fill_hash(int dtype, void* out16, size_t n, uint32_t seed, hipStream_t st);
 
 // u16[t][:] = norm(x32[t][:]) * gain (+ shift); shift == nullptr for RMSNorm.

@@ -61,6 +61,8 @@ struct LayerState {
   int slot = 0;                 // staging slot of the load in flight or last used (set when the load is issued)
   int trigger = -1;
   bool preissued = false;       // the load for the next iteration was issued during the previous one
+  bool d2h_pending = false;     // a prefill's write-back of the KV slice (ev_d2h_end) has been enqueued and the
+                                // compute stream has not waited for it yet
 };
 
 }  // namespace
@@ -77,6 +79,9 @@ struct sn_ctx {
   bool placed = false;
   int timing = 0;
   int timing_class = -1;          // kernel class whose launches are bracketed at level 2 (-1: all)
+  int debug = 0;                  // SN_DEBUG_* switches (sn_set_debug)
+  uint64_t debug_ticks = 0;       // length of a debug delay in wall-clock periods
+  int debug_trips = 0;            // and the bound on its sleeps
 
   uint64_t w_bytes = 0, kv_bytes = 0, state_bytes = 0, ws_bytes = 0;
   int64_t max_tokens = 0;
@@ -196,6 +201,13 @@ int sync_all(sn_ctx* c) {
 bool weights_travel(int what) { return what != SN_OFFLOAD_KV; }
 bool kv_travels(int what) { return what != SN_OFFLOAD_WEIGHTS; }
 
+// Debug delay on a stream (sn_set_debug): a bounded wait, enqueued like any kernel.
+int debug_delay(sn_ctx* c, int flag, hipStream_t st) {
+  if (!(c->debug & flag) || c->debug_ticks == 0) return SN_OK;
+  SN_HIP(c, launch_delay(c->debug_ticks, c->debug_trips, st));
+  return SN_OK;
+}
+
 // Loads issued ahead for an iteration that will not run as foreseen (placement, schedule, KV
 // layout or weights are about to change): wait for the copy stream and forget them.  The staging
 // slots then hold nothing anyone waits for.
@@ -220,13 +232,24 @@ int issue_load(sn_ctx* c, int o, int set, bool with_kv, uint64_t kv_used, int64_
   SN_HIP(c, hipEventRecord(c->ev_trig[e], c->compute));
   SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_trig[e], 0));
   if (c->slot_free_valid[os.slot]) SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_slot_free[os.slot], 0));
+  // The host slice may still be receiving the KV a prefill produced (write-back on the D2H stream).  That copy
+  // released the OTHER staging slot, so the slot-free event above does not order this load behind it.
+  if (os.kv_host && with_kv && kv_used && os.d2h_pending) SN_HIP(c, hipStreamWaitEvent(c->h2d, c->ev_d2h_end[o], 0));
+  const bool load_kv = os.kv_host && with_kv && kv_used;
+  if (c->debug & SN_DEBUG_POISON_SLOT) {
+    // the slot is free now: overwrite what the load is about to fill with 16-bit NaN patterns, so that anything
+    // that still reads the slot's previous contents, or reads the slot before the load has landed, shows
+    if (os.w_host) SN_HIP(c, launch_fill(c->slot_w[os.slot], c->w_bytes, 0x7e007e00u, c->h2d));
+    if (load_kv) SN_HIP(c, launch_fill(c->slot_kv[os.slot], (kv_used + 15) / 16 * 16, 0x7e007e00u, c->h2d));
+  }
+  if (int rc = debug_delay(c, SN_DEBUG_DELAY_H2D, c->h2d)) return rc;
   SN_HIP(c, hipEventRecord(c->ev_copy_start[e], c->h2d));
   *bytes = 0;
   if (os.w_host) {
     SN_HIP(c, hipMemcpyAsync(c->slot_w[os.slot], os.host_w, c->w_bytes, hipMemcpyHostToDevice, c->h2d));
     *bytes += (int64_t)c->w_bytes;
   }
-  if (os.kv_host && with_kv && kv_used) {
+  if (load_kv) {
     SN_HIP(c, hipMemcpyAsync(c->slot_kv[os.slot], os.host_kv, kv_used, hipMemcpyHostToDevice, c->h2d));
     *bytes += (int64_t)kv_used;
   }
@@ -674,6 +697,7 @@ extern "C" int sn_place(sn_ctx* c, int32_t N) {
     ls.kv_host = kv_goes_host(l);
     ls.trigger = ls.offloaded ? trigger_of(N, l, c->sched) : -1;
     ls.slot = 0;
+    ls.d2h_pending = false;          // every stream was waited for above
   }
   c->slot_free_valid[0] = c->slot_free_valid[1] = false;
   c->N = N;
@@ -708,6 +732,38 @@ extern "C" int sn_kv_reset(sn_ctx* c, int32_t batch, const int32_t* capacity) {
     off += capacity[b];
   }
   c->kv_used_tokens = tot;
+  return SN_OK;
+}
+
+extern "C" int sn_kv_truncate(sn_ctx* c, int32_t batch, const int32_t* len) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "sn_kv_truncate: null context");
+  if (c->batch == 0) return fail(c, SN_E_STATE, "sn_kv_truncate before sn_kv_reset");
+  if (batch != c->batch || !len) return fail(c, SN_E_INVAL, "sn_kv_truncate: batch %d, KV was reset for %d", batch, c->batch);
+  for (int b = 0; b < batch; ++b)
+    if (len[b] < 0 || len[b] > c->len[b])
+      return fail(c, SN_E_INVAL, "sn_kv_truncate: sequence %d holds %d tokens, cannot become %d", b, c->len[b], len[b]);
+  // Rows beyond the new lengths stay where they are and are never read again; a load issued ahead
+  // carries the whole slice and stays valid.  Only the bookkeeping changes.
+  for (int b = 0; b < batch; ++b) c->len[b] = len[b];
+  return SN_OK;
+}
+
+extern "C" int sn_set_debug(sn_ctx* c, int32_t flags, int32_t delay_us) {
+  if (!c) return fail(nullptr, SN_E_INVAL, "sn_set_debug: null context");
+  const int known = SN_DEBUG_POISON_SLOT | SN_DEBUG_DELAY_H2D | SN_DEBUG_DELAY_COMPUTE | SN_DEBUG_DELAY_D2H;
+  if (flags & ~known) return fail(c, SN_E_INVAL, "sn_set_debug: unknown flag in 0x%x", flags);
+  if (delay_us < 0 || delay_us > 20000) return fail(c, SN_E_INVAL, "sn_set_debug: delay must be 0..20000 us");
+  int dev = 0, khz = 0;
+  SN_HIP(c, hipGetDevice(&dev));
+  if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
+    (void)hipGetLastError();
+    khz = 100000;                     // the constant-rate counter of this GPU family runs at 100 MHz
+  }
+  int rc = sync_all(c);
+  if (rc) return rc;
+  c->debug = flags;
+  c->debug_ticks = (uint64_t)delay_us * (uint64_t)khz / 1000u;
+  c->debug_trips = delay_us;          // a sleep lasts a microsecond or more: the time test ends the wait first
   return SN_OK;
 }
 
@@ -923,6 +979,7 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
       if (rc) return rc;
       c->last_h2d_bytes += bytes;
     }
+    if (int rc = debug_delay(c, SN_DEBUG_DELAY_COMPUTE, c->compute)) return rc;
     uint8_t* base = ls.dev_w;
     uint8_t* kvbase = ls.dev_kv;
     uint8_t* mirror = nullptr;
@@ -933,15 +990,25 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
       if (ls.kv_host) kvbase = c->slot_kv[ls.slot];
       if (ls.kv_host && !prefill) mirror = ls.host_kv_dev;                   // decode: rows written through
     }
+    // Whatever this layer's kernels write to the host slice (rows written through now, the slice copied back
+    // after this prefill chunk) must land after an earlier write-back of the same slice has finished, or that
+    // copy would overwrite the new rows with what the staging slot held.  Once the compute stream has waited,
+    // everything enqueued later is ordered behind it (loads start from an event of the compute stream).
+    if (ls.kv_host && ls.d2h_pending) {
+      SN_HIP(c, hipStreamWaitEvent(c->compute, c->ev_d2h_end[l], 0));
+      ls.d2h_pending = false;
+    }
     int rc = run_layer(c, l, base, kvbase, mirror, ix, T, B, prefill, n_qtiles, S, pending);
     if (rc) return rc;
     if (ls.offloaded) {
       if (prefill && ls.kv_host) {
         SN_HIP(c, hipEventRecord(c->ev_done[l], c->compute));
         SN_HIP(c, hipStreamWaitEvent(c->d2h, c->ev_done[l], 0));
+        if ((rc = debug_delay(c, SN_DEBUG_DELAY_D2H, c->d2h))) return rc;
         SN_HIP(c, hipEventRecord(c->ev_d2h_start[l], c->d2h));
         SN_HIP(c, hipMemcpyAsync(ls.host_kv, kvbase, kv_used, hipMemcpyDeviceToHost, c->d2h));
         SN_HIP(c, hipEventRecord(c->ev_d2h_end[l], c->d2h));
+        ls.d2h_pending = true;
         SN_HIP(c, hipEventRecord(c->ev_slot_free[ls.slot], c->d2h));
         c->last_d2h_bytes += (int64_t)kv_used;
       } else {

@@ -82,6 +82,10 @@ class Session:
         sn.sn_kv_reset(self.ctx, capacity)
         self.kv_len = np.zeros(len(capacity), dtype=np.int32)
 
+    def kv_truncate(self, length: Sequence[int]):
+        sn.sn_kv_truncate(self.ctx, length)
+        self.kv_len[:] = np.asarray(length, dtype=np.int32)
+
     # -- iterations ------------------------------------------------------------------
     def step_device(self, n_new: Sequence[int], is_prefill: bool, hidden_in: torch.Tensor,
                     hidden_out: torch.Tensor):

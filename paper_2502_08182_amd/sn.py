@@ -20,6 +20,7 @@ SN_NORM_LN, SN_NORM_RMS = 0, 1
 SN_SCHED_PAPER, SN_SCHED_EAGER, SN_SCHED_CONTINUOUS = 0, 1, 2
 SN_OFFLOAD_STATE, SN_OFFLOAD_WEIGHTS, SN_OFFLOAD_KV = 0, 1, 2
 SN_OK, SN_E_INVAL, SN_E_STATE, SN_E_BUDGET, SN_E_INFEASIBLE, SN_E_NOMEM, SN_E_HIP = 0, -1, -2, -3, -4, -5, -6
+SN_DEBUG_POISON_SLOT, SN_DEBUG_DELAY_H2D, SN_DEBUG_DELAY_COMPUTE, SN_DEBUG_DELAY_D2H = 1, 2, 4, 8
 SN_K_NAMES = ("norm", "qkv", "rope_append", "attn", "oproj", "ffn_up", "ffn_down", "other")
 ERROR_NAMES = {-1: "SN_E_INVAL", -2: "SN_E_STATE", -3: "SN_E_BUDGET", -4: "SN_E_INFEASIBLE",
                -5: "SN_E_NOMEM", -6: "SN_E_HIP"}
@@ -32,6 +33,7 @@ EXPORTS = (
     "sn_pick_interval_from_times", "sn_pick_interval", "sn_paper_rule",
     "sn_set_schedule", "sn_placement_sched", "sn_timeline_sched", "sn_pick_interval_from_times_sched",
     "sn_set_offload_part", "sn_offload_part", "sn_max_tokens_part", "sn_resident_bytes_part",
+    "sn_kv_truncate", "sn_set_debug",
 )
 
 
@@ -103,6 +105,8 @@ def lib() -> C.CDLL:
         "sn_offload_part": (i32, [ctx]),
         "sn_placement": (C.c_int, [i32, i32, C.POINTER(C.c_uint8), pi32]),
         "sn_kv_reset": (C.c_int, [ctx, i32, pi32]),
+        "sn_kv_truncate": (C.c_int, [ctx, i32, pi32]),
+        "sn_set_debug": (C.c_int, [ctx, i32, i32]),
         "sn_step": (C.c_int, [ctx, C.POINTER(sn_batch), C.POINTER(sn_kv), C.c_void_p]),
         "sn_read_hidden_f32": (C.c_int, [ctx, C.c_void_p, u64]),
         "sn_set_timing": (C.c_int, [ctx, i32]),
@@ -251,6 +255,15 @@ def sn_set_schedule(ctx, schedule: int) -> None:
 def sn_kv_reset(ctx, capacity: Sequence[int]) -> None:
     cap = np.ascontiguousarray(capacity, dtype=np.int32)
     _check(lib().sn_kv_reset(ctx, cap.size, cap.ctypes.data_as(C.POINTER(C.c_int32))), ctx)
+
+
+def sn_kv_truncate(ctx, length: Sequence[int]) -> None:
+    ln = np.ascontiguousarray(length, dtype=np.int32)
+    _check(lib().sn_kv_truncate(ctx, ln.size, ln.ctypes.data_as(C.POINTER(C.c_int32))), ctx)
+
+
+def sn_set_debug(ctx, flags: int, delay_us: int = 0) -> None:
+    _check(lib().sn_set_debug(ctx, int(flags), int(delay_us)), ctx)
 
 
 def sn_step(ctx, n_new: Sequence[int], is_prefill: bool, hidden_in, kv_len: np.ndarray, hidden_out) -> None:

@@ -1,0 +1,124 @@
+"""The bandwidth coordinator (paper Sec. 4.5, Fig. 8) on the GPU.  One GPU cannot hold a second model
+instance on the same host link, so a paced host-to-device copy stream stands in for the neighbour:
+it takes half of the link while this instance prefetches.  With the interval the picker chooses for
+an idle link the prefill iteration then misses its TTFT SLO; with the interval the coordinator
+assigns (this instance's bounds, the neighbour as a fixed-rate instance) it meets it; and the
+library's adjustment equals the oracle's on the same measured inputs.  Sizes: the OPT-6.7B layer
+shape (403 MB of weights per layer), 12 layers, 8 x 512 prompt tokens -- transfer about 3.5 layer
+computes long, the regime of the paper's prefill measurements."""
+import dataclasses
+import threading
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import coordinator as ocoord
+from oracle import schedule as osch
+from paper_2502_08182_amd import sn, synth
+from paper_2502_08182_amd import sn_coord as CO
+from paper_2502_08182_amd.runner import Session
+
+pytestmark = pytest.mark.gpu
+
+
+def _prefill_iters(se, w, x, y, reps):
+    out = []
+    for _ in range(reps):
+        se.kv_reset([p + 1 for p in w.prompt_lens])
+        se.step_device(list(w.prompt_lens), True, x, y)
+        out.append(sn.sn_get_stats(se.ctx).as_dict())
+    return out
+
+
+def test_coordinator_interval_meets_the_slo_under_contention_where_the_solo_pick_misses():
+    base = synth.workload("c2")
+    s = dataclasses.replace(base.shape, n_layers=12)
+    L, B, P = s.n_layers, 8, 512
+    w = synth.Workload("c2x12", s, B, (P,) * B, 1)
+    with Session(s, B, P + 2) as se:
+        se.place(0)
+        se.load_device_generated_weights(seed=0, distinct=1)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(1)
+        with torch.cuda.stream(se.stream):
+            x = torch.randn(B * P, s.hidden, generator=g, device="cuda", dtype=torch.float32).to(torch.float16)
+            y = torch.empty_like(x)
+        se.stream.synchronize()
+        ttft0 = float(min(d["iter_ns"] for d in _prefill_iters(se, w, x, y, 3)))
+        tc, tx = sn.sn_profile_layers(se.ctx, L, True, B, P, reps=3)
+        w_bytes = sn.sn_layer_blob_bytes(se.cshape)
+        link_bps = int(w_bytes / (float(np.median(tx)) * 1e-9))
+        slo = int(1.5 * ttft0)
+        guard = 0.06
+        n_solo = sn.sn_pick_interval_from_times(tc, tx, int(slo * (1 - guard)), L + 1)
+        assert n_solo == osch.pick_interval(tc.tolist(), tx.tolist(), int(slo * (1 - guard)), L + 1)
+        print(f"TTFT all-resident {ttft0 / 1e6:.2f} ms, tc {np.median(tc) / 1e3:.0f} us, tx {np.median(tx) / 1e3:.0f} us, "
+              f"link {link_bps / 1e9:.1f} GB/s, SLO {slo / 1e6:.2f} ms, solo pick N={n_solo}", flush=True)
+        assert 2 <= n_solo <= L and L // n_solo >= 2          # the idle link lets several layers live on the host
+
+        # the neighbour: half of the link, as one "layer" of that many bytes per second with a single legal interval
+        other_bps = link_bps // 2
+        me = CO.make_instance(L, w_bytes, int(ttft0), n_solo, L + 1)
+        other = CO.make_instance(1, other_bps, 1_000_000_000, 1, 1)
+        (n_adj, n_other), host_b, rate_b = CO.sn_coord_adjust([me, other], link_bps)
+        want = ocoord.adjust([ocoord.Instance(L, w_bytes, int(ttft0), n_solo, L + 1),
+                              ocoord.Instance(1, other_bps, 1_000_000_000, 1, 1)], link_bps)
+        assert want is not None and (n_adj, n_other) == want[0] and host_b == want[1] and rate_b == want[2]
+        assert n_other == 1 and n_adj > n_solo and rate_b < link_bps
+        print(f"coordinator: N={n_adj} ({L // n_adj if n_adj <= L else 0} layers on the host), {rate_b / 1e9:.1f} of {link_bps / 1e9:.1f} GB/s", flush=True)
+
+        chunk = 32 << 20
+        src = torch.empty(chunk, dtype=torch.uint8, pin_memory=True)
+        dst = torch.empty(chunk, dtype=torch.uint8, device="cuda")
+        side = torch.cuda.Stream()
+        stop = threading.Event()
+        moved = [0, 0.0]
+
+        def neighbour():
+            period = chunk / other_bps
+            t0 = time.perf_counter()
+            nxt = t0
+            while not stop.is_set():
+                with torch.cuda.stream(side):
+                    dst.copy_(src, non_blocking=True)
+                side.synchronize()
+                moved[0] += chunk
+                nxt += period
+                lag = nxt - time.perf_counter()
+                if lag > 0:
+                    time.sleep(lag)
+                else:
+                    nxt = time.perf_counter()
+            moved[1] = time.perf_counter() - t0
+
+        def measure(n, contended):
+            se.place(n)
+            th = None
+            if contended:
+                stop.clear()
+                moved[0], moved[1] = 0, 0.0
+                th = threading.Thread(target=neighbour)
+                th.start()
+                time.sleep(0.05)
+            try:
+                st = _prefill_iters(se, w, x, y, 5)[1:]
+            finally:
+                if th is not None:
+                    stop.set()
+                    th.join()
+            it = np.array([d["iter_ns"] for d in st], dtype=np.float64)
+            got = moved[0] / moved[1] / 1e9 if contended and moved[1] > 0 else 0.0
+            print(f"N={n} contended={contended}: TTFT median {np.median(it) / 1e6:.2f} max {it.max() / 1e6:.2f} ms, "
+                  f"neighbour {got:.1f} GB/s", flush=True)
+            return it, got
+
+        alone, _ = measure(n_solo, False)
+        assert (alone <= slo).all()                            # the pick is right for an idle link
+        hit, got_solo = measure(n_solo, True)
+        assert got_solo >= 0.25 * link_bps / 1e9                # the neighbour really took a sizeable share
+        assert np.median(hit) > slo                            # ... and this instance's iteration no longer fits
+        ok, got_adj = measure(n_adj, True)
+        assert got_adj >= 0.25 * link_bps / 1e9
+        assert (ok <= slo).all()                               # the coordinator's interval does

@@ -378,6 +378,27 @@ def test_profiler_and_picker_agree_with_oracle(c1):
                     assert sn.sn_timeline(tc, tx, want)[0] <= slo_ns
 
 
+def test_layer_compute_time_is_deterministic_at_a_real_layer_shape():
+    """The premise the method rests on (Sec. 4.3, Insight): all layers have the same structure and the same
+    input size, so their compute times agree, within an iteration and from one profile to the next.  Checked
+    where a layer is long enough for event timestamps to resolve it: 8 layers of the OPT-6.7B layer shape,
+    decode at batch 8 over 512 cached tokens and a prefill of 4 x 256 tokens."""
+    import dataclasses
+    s = dataclasses.replace(synth.workload("c2").shape, n_layers=8)
+    L = s.n_layers
+    with Session(s, 8, 520) as se:
+        se.place(0)
+        se.load_device_generated_weights(seed=0, distinct=1)
+        for is_prefill, batch, seq in ((False, 8, 512), (True, 4, 256)):
+            a, _ = sn.sn_profile_layers(se.ctx, L, is_prefill, batch, seq, reps=5)
+            b, _ = sn.sn_profile_layers(se.ctx, L, is_prefill, batch, seq, reps=5)
+            cv = float(np.std(a) / np.mean(a))
+            drift = float(np.abs(a - b).max() / np.mean(a))
+            print("prefill" if is_prefill else "decode", "tc", a.tolist(), f"cv {cv:.4f} drift between profiles {drift:.4f}", flush=True)
+            assert cv < 0.05, (is_prefill, a.tolist())
+            assert drift < 0.05, (is_prefill, a.tolist(), b.tolist())
+
+
 def test_performance_record_profiled_on_the_gpu(c1, tmp_path):
     """The analyzer (Sec. 4.4): profile a small grid of sizes for both phases into a record, then
     every lookup must equal the oracle's record fed with the same measured times; after a

@@ -1,8 +1,19 @@
 """GPU parity of each layer kernel against the matching piece of the CPU oracle, through
-the per-kernel C ABI.  Sizes span several tiles and ragged tails.  Tolerances: the
-kernels accumulate in fp32 and round once to the 16-bit output type, so the bound used
-is a few output ulps relative to the RMS of the expected tensor -- far inside the
-end-to-end bar of 2e-2 x RMS."""
+the per-kernel C ABI.  Sizes span several tiles and ragged tails.
+
+The bar, per element: |got - want| <= C_ARITH x RMS(want) + HALF_ULP x |want|.
+  * HALF_ULP x |want| is the one rounding every kernel must make, to its output type: at most
+    half an ulp of the element, 2^-11 |v| for float16, 2^-8 |v| for bfloat16, nothing for an
+    fp32 output.  It has to be per element: for bfloat16 it alone reaches 1.6e-2 x RMS on an
+    element of 4 x RMS, and activation outputs (GELU, SwiGLU) have heavier tails than that.
+  * C_ARITH x RMS is everything else the kernel may add: fp32 accumulation in another order
+    (~1e-6), and the 16-bit roundings inside the attention kernels (rotated q and the softmax
+    weights are rounded to the storage type before the matrix-core products: relative 2^-12 /
+    2^-9 per term, which over a row of weights comes to about 1e-4 / 1e-3 x RMS typically and
+    four times that at the worst element of a tensor).  2e-3 for float16 and 8e-3 for
+    bfloat16 leave a factor of two over that model and stay 10x / 2.5x inside the
+    end-to-end bar of 2e-2 x RMS, which is asserted as well wherever the output rounding
+    alone cannot exceed it (float16 and fp32 outputs)."""
 import math
 
 import numpy as np
@@ -16,7 +27,9 @@ from paper_2502_08182_amd import sn_kernels as K
 pytestmark = pytest.mark.gpu
 
 DT = {"f16": sn.SN_F16, "bf16": sn.SN_BF16}
-TOL = {"f16": 2.0 ** -10, "bf16": 2.0 ** -8}     # x max|expected|: one ulp of the output type
+C_ARITH = {"f16": 2e-3, "bf16": 8e-3}                      # x RMS(expected)
+HALF_ULP = {"f16": 2.0 ** -11, "bf16": 2.0 ** -8, "f32": 0.0}   # x |expected element|, by output type
+E2E_BAR = 2e-2                                              # x RMS(expected)
 
 
 def dev16(bits):
@@ -31,12 +44,20 @@ def rms(a):
     return math.sqrt(float((np.asarray(a, dtype=np.float64) ** 2).mean()))
 
 
-def check(got, want, dtype, what, factor=1.0):
-    err = float(np.abs(got - want).max())
-    bound = TOL[dtype] * factor * float(np.abs(want).max())
-    print(f"{what}: max|d|={err:.3e} bound={bound:.3e} rms={rms(want):.3e}", flush=True)
+def check(got, want, dtype, what, out="same", want_is_rounded=False):
+    """dtype: the 16-bit type the kernel computes with; out: its output type ("same", or "f32").
+    want_is_rounded: the expected values were themselves rounded to the output type (a cache row), so a value
+    that lands on the other side of a rounding boundary differs by a whole ulp, not half of one."""
+    out = dtype if out == "same" else out
+    r = rms(want)
+    d = np.abs(got - want)
+    arith = float((d - (2.0 if want_is_rounded else 1.0) * HALF_ULP[out] * np.abs(want)).max())   # beyond the output rounding
+    print(f"{what}: max|d| = {d.max() / r:.2e} x RMS, beyond output rounding {max(arith, 0.0) / r:.2e} x RMS "
+          f"(bar {C_ARITH[dtype]:.0e}), max|want| = {np.abs(want).max() / r:.1f} x RMS", flush=True)
     assert np.isfinite(got).all(), what
-    assert err <= bound, (what, err, bound)
+    assert arith <= C_ARITH[dtype] * r, (what, arith / r)
+    if out != "bf16":
+        assert d.max() <= E2E_BAR * r, (what, d.max() / r)
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
@@ -93,7 +114,8 @@ def _gemm_case(dtype, path, epi, M, N, Kd, bias, seed):
         else:
             want = lin
     got = out.cpu().numpy().astype(np.float64) if epi == K.EPI_RESID32 else synth.widen(host16(out), dtype)
-    check(got, want, dtype, f"gemm path={path} epi={epi} M={M} N={N} K={Kd} bias={bias}")
+    check(got, want, dtype, f"gemm path={path} epi={epi} M={M} N={N} K={Kd} bias={bias}",
+          out="f32" if epi == K.EPI_RESID32 else "same")
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
@@ -247,7 +269,7 @@ def test_rope_append_and_attn_decode(dtype, Hq, Hkv, d, rope):
         blk = kv_host[base: base + caps[b] * 2 * Hkv * d].reshape(Hkv, 2, caps[b], d)
         mblk = mir_host[base: base + caps[b] * 2 * Hkv * d].reshape(Hkv, 2, caps[b], d)
         p = lens_before[b]
-        check(synth.widen(blk[:, 0, p], dtype), k_new[b][0], dtype, f"appended k seq {b}")
+        check(synth.widen(blk[:, 0, p], dtype), k_new[b][0], dtype, f"appended k seq {b}", want_is_rounded=True)
         assert np.array_equal(synth.widen(blk[:, 1, p], dtype), v_new[b][0])          # v is copied bit for bit
         assert np.array_equal(blk[:, :, p], mblk[:, :, p])                              # mirror gets the same rows
         assert np.array_equal(blk[:, 0, :p], Kc[b].transpose(1, 0, 2))                  # the prefix is untouched
@@ -260,7 +282,7 @@ def test_rope_append_and_attn_decode(dtype, Hq, Hkv, d, rope):
         K.sn_k_attn_decode(DT[dtype], dv["qkv"], dv["kv"], dv["len_before"], dv["kv_off"], dv["cap"], out, part, B, Hq,
                            Hkv, d, S, max(lens_before) + 1)
         torch.cuda.synchronize()
-        check(synth.widen(host16(out), dtype), want, dtype, f"attn_decode S={S}", factor=2.0)
+        check(synth.widen(host16(out), dtype), want, dtype, f"attn_decode S={S}")
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,rope", [("f16", 4, 4, 64, False), ("bf16", 8, 8, 128, True),
@@ -293,7 +315,7 @@ def test_attn_decode_with_fused_append(dtype, Hq, Hkv, d, rope):
         K.sn_k_attn_decode_append(DT[dtype], dv["qkv"], kv_f, mir_f, dv["inv_freq"], rope, dv["len_before"], dv["kv_off"],
                                   dv["cap"], out_f, part, B, Hq, Hkv, d, S, max(lens_before) + 1)
         torch.cuda.synchronize()
-        check(synth.widen(host16(out_f), dtype), want, dtype, f"fused attn_decode S={S}", factor=2.0)
+        check(synth.widen(host16(out_f), dtype), want, dtype, f"fused attn_decode S={S}")
         assert torch.equal(dv["qkv"], qkv0), "the fused kernel must not modify the QKV buffer"
         assert torch.equal(kv_f, kv_two), f"cache after the fused kernel differs from rope_append's (S={S})"
         assert torch.equal(mir_f, mir_two), f"mirror differs (S={S})"
@@ -303,7 +325,7 @@ def test_attn_decode_with_fused_append(dtype, Hq, Hkv, d, rope):
         base = int(kv_off[b]) * 2 * Hkv * d
         blk = kv_host[base: base + caps[b] * 2 * Hkv * d].reshape(Hkv, 2, caps[b], d)
         p = lens_before[b]
-        check(synth.widen(blk[:, 0, p], dtype), k_new[b][0], dtype, f"appended k seq {b}")
+        check(synth.widen(blk[:, 0, p], dtype), k_new[b][0], dtype, f"appended k seq {b}", want_is_rounded=True)
         assert np.array_equal(synth.widen(blk[:, 1, p], dtype), v_new[b][0])
 
 
@@ -330,7 +352,7 @@ def test_attn_prefill(dtype, Hq, Hkv, d, rope):
                         dv["cap"], i32(tile_seq), i32(tile_q0), out, len(tile_seq), Hq, Hkv, d)
     torch.cuda.synchronize()
     want, *_ = _oracle_attention(dtype, qkv, Kc, Vc, lens_before, n_new, tok_start, Hq, Hkv, d, rope)
-    check(synth.widen(host16(out), dtype), want, dtype, "attn_prefill", factor=2.0)
+    check(synth.widen(host16(out), dtype), want, dtype, "attn_prefill")
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])

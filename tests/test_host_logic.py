@@ -83,6 +83,53 @@ def test_bf16_weights_become_equal_float16_values():
     assert np.isnan(got[np.isnan(src)]).all() and np.isinf(got[~fin & ~np.isnan(src)]).all()
 
 
+def test_tiny_bf16_weights_round_to_float16_subnormals_far_below_the_bar():
+    """bfloat16 weights below 2^-17 have no equal float16 value; the library rounds them to the nearest
+    float16 subnormal (absolute error below 2^-25 each) instead of refusing them.  With a tenth of a
+    layer's weights pushed into that range, the oracle's layer output with the converted weights differs
+    from the one with the original weights by far less than the parity bar of 2e-2 x RMS."""
+    from oracle import forward as ofw
+    from paper_2502_08182_amd import sn_kernels
+    s = synth.ModelShape(1, 256, 4, 2, 64, 512, act="swiglu", norm="rms", rope=True, has_bias=False, dtype="bf16")
+    rng = np.random.default_rng(17)
+    layer = synth.make_layer(s, 0, 0)
+    conv, worst = {}, 0.0
+    for name, bits in layer.items():
+        if bits.ndim == 2:
+            v = synth.widen(bits, "bf16")
+            tiny = rng.random(v.shape) < 0.1
+            v = np.where(tiny, v * 2.0 ** -14, v)                      # N(0, 0.02) * 2^-14: mostly below 2^-17
+            bits = synth.to_bits(v, "bf16")
+            layer[name] = bits
+            n, k = bits.shape
+            tiled, bad = sn_kernels.sn_k_tile_weights(bits, n, k, bf16_to_f16=True, return_bad=True)
+            assert bad == 0
+            # undo the tiling: tile the element indices with the same routine (32-bit indices via two 16-bit halves)
+            idx = np.arange(n * k, dtype=np.uint32).reshape(n, k)
+            lo = sn_kernels.sn_k_tile_weights((idx & 0xffff).astype(np.uint16), n, k).astype(np.uint32)
+            hi = sn_kernels.sn_k_tile_weights((idx >> 16).astype(np.uint16), n, k).astype(np.uint32)
+            back = np.empty(n * k, dtype=np.float64)
+            back[(hi << 16) | lo] = tiled.view(np.float16).astype(np.float64)
+            conv[name] = back.reshape(n, k)
+            src = synth.widen(bits, "bf16")
+            assert (np.abs(src) < 2.0 ** -17).mean() > 0.05            # the case is really exercised
+            worst = max(worst, float(np.abs(conv[name] - src).max()))
+            big = np.abs(src) >= 2.0 ** -17
+            assert np.array_equal(conv[name][big], src[big])
+        else:
+            conv[name] = synth.widen(bits, "bf16")
+    assert 0.0 < worst <= 2.0 ** -25
+    x = rng.standard_normal((24, s.hidden))
+    outs = []
+    for wts in (synth.widen_layer(s, layer), conv):
+        cache = ofw.new_cache(1, 1, s.n_kv_heads, s.head_dim)
+        outs.append(ofw.step(s.as_dict(), [wts], [x], cache, kv_dtype="f16")[0])
+    rms = float(np.sqrt((outs[0] ** 2).mean()))
+    diff = float(np.abs(outs[0] - outs[1]).max())
+    print(f"tiny weights: max|d| = {diff / rms:.2e} x RMS", flush=True)
+    assert diff <= 1e-5 * rms
+
+
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(sn.sn_model_shape) == 16 * 4
     assert ctypes.sizeof(sn.sn_step_stats) == 6 * 8 + 8 + 2 * 4 + 8 + 8 * 8 + 8 * 4 + 8     # n_preissued and tail padding
