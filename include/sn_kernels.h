@@ -57,10 +57,10 @@ int sn_k_gemm(int32_t dtype, int32_t epilogue, int32_t path, const void* W, cons
  * partial product of range s; plane 0 also receives the bias (16-bit [N], may be NULL),
  * so that whoever folds the planes later needs nothing from this layer's weight record.
  * The consumer folds them into the residual stream in ascending s (sn_k_norm_fold,
- * sn_k_cast_out_fold), which keeps the sum order fixed.  Returns the number of splits
- * used (> 0) or a negative SN_E_* code. */
+ * sn_k_cast_out_fold), which keeps the sum order fixed.  flags: 1 = X is row-tile packed (what
+ * a decode step passes).  Returns the number of splits used (> 0) or a negative SN_E_* code. */
 int sn_k_gemm_splitk(int32_t dtype, const void* W, const void* X, const void* bias, void* part, int32_t M,
-                     int32_t N, int32_t K, int32_t splits, void* stream);
+                     int32_t N, int32_t K, int32_t splits, int32_t flags, void* stream);
 
 /* sn_k_norm preceded by x32[t][:] += bias + sum_s part[s][t][:] (x32 is updated in place;
  * bias 16-bit [h] or NULL; splits == 0: plain sn_k_norm).  packed_out != 0: out16 is

@@ -20,111 +20,15 @@
 
 namespace sn {
 
-// MT: 16-row tiles of token rows; C: adjacent 16-column blocks per wavefront (each
-// activation fragment read from L2 is reused for C weight tiles, keeping activation
-// traffic at or below weight traffic for every M <= 64).
-// WMAX: most wavefronts a workgroup of this instance may have (bounds the register budget:
-// 16 -> 128 registers, 8 or fewer -> 256, which the 4-row-tile variants need to stay out of
-// scratch memory).
-// SHARE: the instance supports more than one column of wavefronts (NWN_ > 1); without it the
-// column count is the constant 1, which saves the registers the 4-row-tile split-K variants need
-// to keep four wavefronts per SIMD.
-template <class T, int MT, int C, int EPI, int WMAX, bool SHARE>
-__global__ __launch_bounds__(WMAX * 64) void gemm_skinny_kernel(
-    const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
-    void* __restrict__ out, int M, int N, int K, int xpacked, int opacked, int NWN_) {
-  const int NWN = SHARE ? NWN_ : 1;
+// Fixed-order reduction of the KS partial tiles through LDS (one row tile at a time) and the fused epilogue.
+// red: [KS][C][64][4] floats.  Wavefront (wk, wn) = (wave / NWN, wave % NWN) holds the partial sums of
+// column blocks (blockIdx.x * NWN + wn) * C .. + C over the wk-th part of the workgroup's K range.
+template <class T, int MT, int C, int EPI>
+__device__ __forceinline__ void reduce_and_store(float* red, const f32x4 (&acc)[MT][C], int lane, int wave, int KS, int NWN,
+                                                 const uint16_t* __restrict__ bias, void* __restrict__ out, int M, int N,
+                                                 int opacked) {
   constexpr bool DUAL = EPI == EPI_SWIGLU16;
-  static_assert(!DUAL || C % 2 == 0, "SwiGLU needs gate/up pairs");
-  constexpr int U = C >= 4 ? 1 : (C == 2 ? 2 : 4);     // k-blocks in flight per column block
-  constexpr bool SPLIT_ACC = MT * C == 1;              // lone accumulator: alternate two to hide MFMA latency
-  extern __shared__ float red[];                       // [KS][C][64][4], reused for each row tile
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int KS = blockDim.x >> 6;
-  const int KB = K >> 5;
-  // K range of this workgroup (gridDim.y > 1 only for EPI_PART32), then of this wavefront
-  const int per_wg = (KB + gridDim.y - 1) / gridDim.y;
-  const int g0 = blockIdx.y * per_wg;
-  const int g1 = min(KB, g0 + per_wg);
-  const int wn = wave % NWN, wk = wave / NWN, KSK = KS / NWN;   // column of wavefronts, position in it
-  const int per = (max(g1 - g0, 0) + KSK - 1) / KSK;
-  const int kb0 = g0 + wk * per;
-  const int kb1 = min(g1, kb0 + per);
-  const int cb = (blockIdx.x * NWN + wn) * C;          // first 16-row block of the weight matrix
-
-  const uint16_t* wp = W + ((size_t)cb * KB) * 512 + lane * 8;
-  const size_t wstride = (size_t)KB * 512;             // next column block
-
-  const uint16_t* xrow[MT];
-  bool xok[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int m = mt * 16 + (lane & 15);
-    xok[mt] = m < M;
-    xrow[mt] = xpacked ? X + ((size_t)mt * KB * 64 + lane) * 8 : X + (size_t)(xok[mt] ? m : 0) * K + (lane >> 4) * 8;
-  }
-  const int xstep = xpacked ? 512 : 32;                // elements from one k-block to the next
-
-  f32x4 acc[MT][C];
-  f32x4 acc_b = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int c = 0; c < C; ++c) acc[mt][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // Every wavefront walks its K range starting at a different rotation.  Tile rows of the
-  // weight matrix lie a power of two apart, so wavefronts that all start at the beginning of
-  // their range march over the HBM channels in lock-step (measured: 4.8 vs 6.1 TB/s on a
-  // 4096 x 16384 matrix).  The rotation is a fixed function of (workgroup, K range), so the
-  // summation order, and with it the result, stays reproducible -- and wavefronts side by side
-  // walk the same k-blocks at the same time.
-  const int len = max(kb1 - kb0, 0);
-  const int rot = len > 0 ? ((blockIdx.x + wk * 5 + blockIdx.y * 3) * 4) % len : 0;
-  for (int seg = 0; seg < 2; ++seg) {
-    int kb = seg == 0 ? kb0 + rot : kb0;
-    const int kend = seg == 0 ? kb1 : kb0 + rot;
-    for (; kb + U <= kend; kb += U) {
-      u16x8 a[U][C], b[U][MT];
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int c = 0; c < C; ++c)
-          a[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(wp + c * wstride + (size_t)(kb + u) * 512));
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          b[u][mt] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-          if (xok[mt]) b[u][mt] = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)(kb + u) * xstep);
-        }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int c = 0; c < C; ++c) {
-            if (SPLIT_ACC && (u & 1))
-              acc_b = mma16x16x32<T>(a[u][c], b[u][mt], acc_b);
-            else
-              acc[mt][c] = mma16x16x32<T>(a[u][c], b[u][mt], acc[mt][c]);
-          }
-    }
-    for (; kb < kend; ++kb) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        u16x8 b = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
-        if (xok[mt]) b = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)kb * xstep);
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-          const u16x8 a = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(wp + c * wstride + (size_t)kb * 512));
-          acc[mt][c] = mma16x16x32<T>(a, b, acc[mt][c]);
-        }
-      }
-    }
-  }
-  if (SPLIT_ACC) acc[0][0] += acc_b;
-
+  const int KSK = KS / NWN;
   // fixed-order reduction of the KS partial tiles, one row tile at a time
   constexpr int ITEMS = DUAL ? C / 2 : C;              // epilogue work items per row tile
   const int nl = (lane >> 4) * 4;                      // first of this lane's 4 columns in a block
@@ -137,7 +41,7 @@ __global__ __launch_bounds__(WMAX * 64) void gemm_skinny_kernel(
     __syncthreads();
     const int m = mt * 16 + (lane & 15);
     // epilogue work items: (column of wavefronts, output block [pair]); dealt round-robin to the wavefronts
-    for (int item = wave; item < NWN * ITEMS; item += SHARE ? KS : ITEMS) {   // one pass at most when !SHARE
+    for (int item = wave; item < NWN * ITEMS; item += KS) {
       if (m >= M) break;
       const int wn_i = item / ITEMS, it = item % ITEMS;
       const int cb_i = (blockIdx.x * NWN + wn_i) * C;
@@ -194,6 +98,306 @@ __global__ __launch_bounds__(WMAX * 64) void gemm_skinny_kernel(
   }
 }
 
+// MT: 16-row tiles of token rows; C: adjacent 16-column blocks per wavefront (each
+// activation fragment read from L2 is reused for C weight tiles, keeping activation
+// traffic at or below weight traffic for every M <= 64).
+// WMAX: most wavefronts a workgroup of this instance may have (bounds the register budget:
+// 16 -> 128 registers, 8 or fewer -> 256, which the 4-row-tile variants need to stay out of
+// scratch memory).
+// SHARE: the instance supports more than one column of wavefronts (NWN_ > 1); without it the
+// column count is the constant 1, which saves the registers the 4-row-tile split-K variants need
+// to keep four wavefronts per SIMD.
+// k-blocks a wavefront keeps in flight (depth of its register ring): the deepest of 8, 4, 3, 2 whose ring of
+// C weight and MT activation fragments fits the register budget beside the MT*C accumulators, up to 8 KiB of
+// weights per wavefront where a compute unit holds 16 wavefronts and 12 KiB where it holds 8.
+constexpr int ring_depth(int MT, int C, int WMAX) {
+  const int budget = (WMAX > 8 ? 128 : 256) - 40 - MT * C * 4;
+  const int most = (WMAX > 8 ? 8 : 12) / C;
+  for (int pd : {8, 4, 3, 2})
+    if (pd <= most && pd * (C + MT) * 4 <= budget) return pd;
+  return 2;
+}
+
+template <class T, int MT, int C, int EPI, int WMAX, bool SHARE>
+__global__ __launch_bounds__(WMAX * 64) void gemm_skinny_kernel(
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
+    void* __restrict__ out, int M, int N, int K, int xpacked, int opacked, int NWN_) {
+  const int NWN = SHARE ? NWN_ : 1;
+  constexpr bool DUAL = EPI == EPI_SWIGLU16;
+  static_assert(!DUAL || C % 2 == 0, "SwiGLU needs gate/up pairs");
+  constexpr int PD = ring_depth(MT, C, WMAX);
+  constexpr bool SPLIT_ACC = MT * C == 1;              // lone accumulator: alternate two to hide MFMA latency
+  extern __shared__ float red[];                       // [KS][C][64][4], reused for each row tile
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int KS = blockDim.x >> 6;
+  const int KB = K >> 5;
+  // K range of this workgroup (gridDim.y > 1 only for EPI_PART32), then of this wavefront
+  const int per_wg = (KB + gridDim.y - 1) / gridDim.y;
+  const int g0 = blockIdx.y * per_wg;
+  const int g1 = min(KB, g0 + per_wg);
+  const int wn = wave % NWN, wk = wave / NWN, KSK = KS / NWN;   // column of wavefronts, position in it
+  const int per = (max(g1 - g0, 0) + KSK - 1) / KSK;
+  const int kb0 = g0 + wk * per;
+  const int kb1 = min(g1, kb0 + per);
+  const int cb = (blockIdx.x * NWN + wn) * C;          // first 16-row block of the weight matrix
+
+  const uint16_t* wp = W + ((size_t)cb * KB) * 512 + lane * 8;
+  const size_t wstride = (size_t)KB * 512;             // next column block
+
+  const uint16_t* xrow[MT];
+  bool xok[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = mt * 16 + (lane & 15);
+    xok[mt] = m < M;
+    xrow[mt] = xpacked ? X + ((size_t)mt * KB * 64 + lane) * 8 : X + (size_t)(xok[mt] ? m : 0) * K + (lane >> 4) * 8;
+  }
+  const int xstep = xpacked ? 512 : 32;                // elements from one k-block to the next
+
+  f32x4 acc[MT][C];
+  f32x4 acc_b = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int c = 0; c < C; ++c) acc[mt][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // Every wavefront walks its K range starting at a different rotation.  Tile rows of the
+  // weight matrix lie a power of two apart, so wavefronts that all start at the beginning of
+  // their range march over the HBM channels in lock-step (measured: 4.8 vs 6.1 TB/s on a
+  // 4096 x 16384 matrix).  The rotation is a fixed function of (workgroup, K range), so the
+  // summation order, and with it the result, stays reproducible -- and wavefronts side by side
+  // walk the same k-blocks at the same time.
+  //
+  // From two row tiles on the walk is software-pipelined over a ring of PD k-blocks: the loads of
+  // k-block i + PD are issued right after the products of k-block i, so a wavefront always has
+  // PD - 1 .. PD k-blocks (C KiB of weights each) on their way while it computes.
+  const int len = max(kb1 - kb0, 0);
+  const int rot = len > 0 ? ((blockIdx.x + wk * 5 + blockIdx.y * 3) * 4) % len : 0;
+  if constexpr (MT == 1) {
+    // One row tile: the wavefront requests U k-blocks (U KiB of consecutive weights per column block) in one
+    // burst, then multiplies them; 16 wavefronts per compute unit overlap each other's bursts.  (Keeping the
+    // requests of single k-blocks in flight across the products, as below, measured 10-25 % slower here.)
+    constexpr int U = C == 2 ? 2 : 4;
+    for (int seg = 0; seg < 2; ++seg) {
+      int kb = seg == 0 ? kb0 + rot : kb0;
+      const int kend = seg == 0 ? kb1 : kb0 + rot;
+      for (; kb + U <= kend; kb += U) {
+        u16x8 a[U][C], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int c = 0; c < C; ++c)
+            a[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(wp + c * wstride + (size_t)(kb + u) * 512));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          b[u] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+          if (xok[0]) b[u] = *reinterpret_cast<const u16x8*>(xrow[0] + (size_t)(kb + u) * xstep);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int c = 0; c < C; ++c) {
+            if (SPLIT_ACC && (u & 1))
+              acc_b = mma16x16x32<T>(a[u][c], b[u], acc_b);
+            else
+              acc[0][c] = mma16x16x32<T>(a[u][c], b[u], acc[0][c]);
+          }
+      }
+      for (; kb < kend; ++kb) {
+        u16x8 b = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        if (xok[0]) b = *reinterpret_cast<const u16x8*>(xrow[0] + (size_t)kb * xstep);
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+          const u16x8 a = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(wp + c * wstride + (size_t)kb * 512));
+          acc[0][c] = mma16x16x32<T>(a, b, acc[0][c]);
+        }
+      }
+    }
+  } else {
+    u16x8 a[PD][C], b[PD][MT];
+    // Token rows beyond M are loaded like the others (from row 0 of a row-major X; from the padding rows a
+    // packed X always has): a token row only ever reaches its own output row, and those are not stored.  So the
+    // loop body has no branches, and the loads of later k-blocks stay in flight across the products.
+    auto load = [&](int slot, int i) {       // k-block number i of the rotated walk into ring slot `slot`
+      int kb = kb0 + rot + i;
+      if (kb >= kb1) kb -= len;
+  #pragma unroll
+      for (int c = 0; c < C; ++c)
+        a[slot][c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(wp + c * wstride + (size_t)kb * 512));
+  #pragma unroll
+      for (int mt = 0; mt < MT; ++mt) b[slot][mt] = *reinterpret_cast<const u16x8*>(xrow[mt] + (size_t)kb * xstep);
+    };
+    auto products = [&](int slot) {
+  #pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+  #pragma unroll
+        for (int c = 0; c < C; ++c) {
+          if (SPLIT_ACC && (slot & 1))
+            acc_b = mma16x16x32<T>(a[slot][c], b[slot][mt], acc_b);
+          else
+            acc[mt][c] = mma16x16x32<T>(a[slot][c], b[slot][mt], acc[mt][c]);
+        }
+    };
+    if (len >= PD) {
+  #pragma unroll
+      for (int sl = 0; sl < PD; ++sl) load(sl, sl);
+      int i = 0;
+      for (; i + 2 * PD <= len; i += PD) {   // the ring is full and stays full: no conditions in here
+  #pragma unroll
+        for (int sl = 0; sl < PD; ++sl) {
+          products(sl);
+          load(sl, i + PD + sl);
+          __builtin_amdgcn_sched_barrier(0);   // keep this order: the compiler would otherwise gather all products
+                                               // first and all loads last, which empties the ring every round
+        }
+      }
+      // the ring holds k-blocks i .. i + PD - 1; fewer than PD are left to request
+  #pragma unroll
+      for (int sl = 0; sl < PD; ++sl) {
+        products(sl);
+        if (i + PD + sl < len) load(sl, i + PD + sl);
+      }
+      i += PD;
+  #pragma unroll
+      for (int sl = 0; sl < PD; ++sl)
+        if (i + sl < len) products(sl);
+    } else {
+      for (int i = 0; i < len; ++i) {        // a K range shorter than the ring
+        load(0, i);
+        products(0);
+      }
+    }
+  }
+  if (SPLIT_ACC) acc[0][0] += acc_b;
+
+  reduce_and_store<T, MT, C, EPI>(red, acc, lane, wave, KS, NWN, bias, out, M, N, opacked);
+}
+
+// ---------------------------------------------------------------------------------------------
+// 3-4 row tiles (33..64 token rows), activations shared through LDS.
+//
+// With that many rows a wavefront of the kernel above issues as many activation loads as weight
+// loads, and although they hit the L1 cache they cost: doubling them (two column blocks per
+// wavefront instead of four) took the 57344 x 8192 projection from 164 to 191 us, i.e. the
+// weight stream alone would take ~137 us (6.85 TB/s) and every "weights' worth" of activation
+// loads adds 27 us.  Here the wavefronts of a workgroup that walk the same K range (NWN side by
+// side, each with its own C column blocks) fetch each activation tile ONCE, together, into LDS
+// -- 16-byte pieces dealt round-robin over their lanes, two k-blocks per step, double-buffered,
+// one barrier per step -- and every wavefront reads its B operands from there.  Weights go
+// global -> registers as before, two steps ahead.  X must be row-tile packed.
+template <class T, int MT, int C, int EPI>
+__global__ __launch_bounds__(512) void gemm_wide_kernel(
+    const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
+    void* __restrict__ out, int M, int N, int K, int opacked, int NWN) {
+  constexpr int KC = 2;                                // k-blocks per step
+  constexpr int TILES = KC * MT;                       // activation tiles (1 KiB) per step and K range
+  constexpr int R = (TILES + 3) / 4;                   // 16-byte pieces per lane and step (NWN >= 4)
+  extern __shared__ __attribute__((aligned(16))) float red[];   // stages during the walk, partial tiles afterwards
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int KS = blockDim.x >> 6;
+  const int KB = K >> 5;
+  const int per_wg = (KB + gridDim.y - 1) / gridDim.y;
+  const int g0 = blockIdx.y * per_wg;
+  const int g1 = min(KB, g0 + per_wg);
+  const int wn = wave % NWN, wk = wave / NWN, KSK = KS / NWN;
+  const int per = (max(g1 - g0, 0) + KSK - 1) / KSK;   // longest K range of the workgroup: its step count is everyone's
+  const int kb0 = g0 + wk * per;
+  const int kb1 = min(g1, kb0 + per);
+  const int len = max(kb1 - kb0, 0);
+  const int nsteps = (per + KC - 1) / KC;
+  const int rot = len > 0 ? ((blockIdx.x + wk * 5 + blockIdx.y * 3) * 4) % len : 0;
+  // k-block at position i of this wavefront's rotated walk; positions past the end give some valid block
+  // (their loads are harmless, their products are skipped)
+  auto kb_at = [&](int i) {
+    int kb = kb0 + rot + min(i, max(len - 1, 0));
+    if (kb >= kb1) kb -= len;
+    return min(max(kb, 0), KB - 1);
+  };
+  const int cb = (blockIdx.x * NWN + wn) * C;
+  const uint16_t* wp = W + ((size_t)cb * KB) * 512 + lane * 8;
+  const size_t wstride = (size_t)KB * 512;
+  uint16_t* stage = reinterpret_cast<uint16_t*>(red) + (size_t)wk * (2 * TILES * 512);   // this K range's two stages
+
+  // this lane's pieces of a step: piece p = tile (p / 64) = (kc, mt), 16 bytes number p % 64 of it
+  int ptile[R], poff[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int p = min((wn + r * NWN) * 64 + lane, TILES * 64 - 1);   // surplus lanes repeat the last piece
+    ptile[r] = p >> 6;
+    poff[r] = (p & 63) * 8;
+  }
+
+  f32x4 acc[MT][C];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int c = 0; c < C; ++c) acc[mt][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  u16x8 a[2][KC][C], sreg[R];
+
+  auto wload = [&](int slot, int step) {
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      const size_t kb = (size_t)kb_at(step * KC + kc);
+#pragma unroll
+      for (int c = 0; c < C; ++c)
+        a[slot][kc][c] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(wp + c * wstride + kb * 512));
+    }
+  };
+  auto sload = [&](int step) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int kc = ptile[r] / MT, mt = ptile[r] % MT;
+      sreg[r] = *reinterpret_cast<const u16x8*>(X + ((size_t)mt * KB + kb_at(step * KC + kc)) * 512 + poff[r]);
+    }
+  };
+  auto sstore = [&](int s) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) *reinterpret_cast<u16x8*>(stage + (size_t)(s * TILES + ptile[r]) * 512 + poff[r]) = sreg[r];
+  };
+  auto products = [&](int slot, int s, int step) {
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      if (step * KC + kc < len) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const u16x8 bf = *reinterpret_cast<const u16x8*>(stage + (size_t)(s * TILES + kc * MT + mt) * 512 + lane * 8);
+#pragma unroll
+          for (int c = 0; c < C; ++c) acc[mt][c] = mma16x16x32<T>(a[slot][kc][c], bf, acc[mt][c]);
+        }
+      }
+    }
+  };
+  // LDS writes of this wavefront done, then everyone's: a bare barrier (a fence would also wait for the loads in flight)
+  auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+  sload(0);
+  wload(0, 0);
+  sstore(0);
+  sload(1);
+  wload(1, 1);
+  lds_barrier();
+  for (int j = 0; j < nsteps; j += 2) {
+    products(0, 0, j);
+    __builtin_amdgcn_sched_barrier(0);
+    sstore(1);                 // activations of step j + 1, requested one half-trip ago
+    sload(j + 2);
+    wload(0, j + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_barrier();
+    products(1, 1, j + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    sstore(0);
+    sload(j + 3);
+    wload(1, j + 3);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_barrier();
+  }
+  // the last barrier also says: nobody reads the stages any more
+  reduce_and_store<T, MT, C, EPI>(red, acc, lane, wave, KS, NWN, bias, out, M, N, opacked);
+}
+
 // K-split per workgroup (wavefronts per workgroup).  Measured on MI355X with M = 8:
 // 8 wavefronts reach 6.0-6.2 TB/s on [12288|16384] x 4096 and 5.2 TB/s on 4096 x 4096;
 // 16 are better (5.35 vs 5.0 TB/s) only when few column groups meet a long K
@@ -223,6 +427,66 @@ static int pick_columns(int MT, int groups, int KB, int ks) {
     if (evenness(groups / nwn) >= best - 0.03) return nwn;
   }
   return 1;
+}
+
+// Shape of the launch for 3-4 row tiles (8 wavefronts per compute unit at most): C column blocks per
+// wavefront, nwn wavefronts side by side, ksk wavefronts splitting K below each.  A compute unit streams
+// weights at a rate that hardly depends on how the work is cut, so what counts is how many 16-column blocks
+// the busiest unit gets: workgroups are dealt out over the 256 units, each bringing nwn * C blocks.
+// 57344 rows in blocks of 64 make 896 groups -- 224 workgroups of 4 columns leave 32 units idle -- but as
+// 1792 groups of 32 in workgroups of 7 columns they are exactly one workgroup per unit.  Ties: more column
+// blocks per wavefront (fewer operand reads per weight), then wider workgroups.  nwn >= 4 selects the kernel
+// that shares activations through LDS; nwn == 1 means "no such shape" (too few feature groups).
+struct WidePlan {
+  int C, nwn, ks;
+};
+static WidePlan plan_wide(int nb, int KB) {
+  WidePlan best{nb % 4 == 0 ? 4 : (nb % 2 == 0 ? 2 : 1), 1, 8};
+  long best_cost = -1;
+  for (int C : {4, 2}) {
+    if (nb % C) continue;
+    const int groups = nb / C;
+    for (int nwn = 4; nwn <= 8; ++nwn) {
+      if (groups % nwn) continue;
+      const int wgs = groups / nwn;
+      if (wgs < 128) continue;
+      int ksk = 8 / nwn;
+      while (ksk > 1 && KB / ksk < 16) --ksk;
+      const long cost = (long)((wgs + 255) / 256) * nwn * C;
+      if (best_cost < 0 || cost < best_cost || (cost == best_cost && (C > best.C || (C == best.C && nwn > best.nwn)))) {
+        best = WidePlan{C, nwn, nwn * ksk};
+        best_cost = cost;
+      }
+    }
+  }
+  return best;
+}
+
+template <class T, int MT, int C>
+static hipError_t launch_wide(int epi, int ks, int nwn, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
+                              int M, int N, int K, int splits, int opacked, hipStream_t st) {
+  const int groups = N / (16 * C * nwn);
+  const int ksk = ks / nwn;
+  const size_t lds = std::max((size_t)ks * C * 64 * 4 * sizeof(float), (size_t)ksk * 2 * 2 * MT * 1024);
+  dim3 grid(groups, epi == EPI_PART32 ? splits : 1), block(ks * 64);
+  if (nwn < 4 || ks > 8 || ks % nwn || (N / (16 * C)) % nwn) return hipErrorInvalidValue;
+  switch (epi) {
+    case EPI_PART32:
+      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_PART32>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn);
+      break;
+    case EPI_STORE16:
+      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_STORE16>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn);
+      break;
+    case EPI_GELU16:
+      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_GELU16>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn);
+      break;
+    case EPI_SWIGLU16:
+      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_SWIGLU16>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn);
+      break;
+    default:
+      return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 template <class T, int MT, int C, int WMAX, bool SHARE>
@@ -302,6 +566,34 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
   if (M <= 32) {
     if (nb % 2 == 0) return launch_mc<T, 2, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
     return launch_mc<T, 2, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+  }
+  if (M > 16 && xpacked && epi != EPI_RESID32) {
+    // 2-4 row tiles, packed activations: the kernel that shares them through LDS, where a launch shape exists
+    WidePlan pl{0, 1, 8};
+    bool ok;
+    if (epi == EPI_PART32) {
+      // split-K planes: 4 columns of 2 wavefronts, 4 column blocks each, where the feature groups times the
+      // splits fill the chip and every split keeps a long K (64 rows, 8192 x 28672, 8 splits: 87 -> 84 us; other
+      // cuts of this shape -- 2 column blocks, 8 columns, 4 splits -- measured 83..103 us)
+      const int groups = nb / 4;
+      ok = nb % 4 == 0 && groups % 4 == 0 && groups / 4 * splits >= 200 && (K / 32) / splits >= 64;
+      pl = WidePlan{4, 4, 8};
+    } else {
+      pl = plan_wide(nb, K / 32);
+      ok = pl.nwn >= 4;
+    }
+    if (ok && !(dual && pl.C % 2)) {
+      if (M <= 32) {
+        if (pl.C == 4) return launch_wide<T, 2, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
+        return launch_wide<T, 2, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
+      }
+      if (M <= 48) {
+        if (pl.C == 4) return launch_wide<T, 3, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
+        return launch_wide<T, 3, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
+      }
+      if (pl.C == 4) return launch_wide<T, 4, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
+      return launch_wide<T, 4, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
+    }
   }
   if (M <= 48) {
     if (nb % 4 == 0) return launch_mc<T, 3, 4>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);

@@ -1374,3 +1374,4 @@ extern "C" int sn_pick_interval(sn_ctx* c, double slo_ms, int32_t* N_out) {
   if (c->budget && sn_resident_bytes(c, *N_out) > c->budget) *N_out = L + 1;
   return SN_OK;
 }
+

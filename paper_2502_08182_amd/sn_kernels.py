@@ -36,7 +36,7 @@ def _lib():
             "sn_k_cast_in": [i32, v, v, u64, v],
             "sn_k_cast_out": [i32, v, v, u64, v],
             "sn_k_copy": [v, v, u64, v],
-            "sn_k_gemm_splitk": [i32, v, v, v, v, i32, i32, i32, i32, v],
+            "sn_k_gemm_splitk": [i32, v, v, v, v, i32, i32, i32, i32, i32, v],
             "sn_k_norm_fold": [i32, i32, v, v, v, v, i32, i32, C.c_float, v, i32, v, i32, v],
             "sn_k_cast_out_fold": [i32, v, v, i32, i32, v, i32, v, v],
         }
@@ -131,8 +131,8 @@ def sn_k_copy(src, dst, nbytes, stream=0):
     _chk(_lib().sn_k_copy(_p(src), _p(dst), nbytes, stream))
 
 
-def sn_k_gemm_splitk(dtype, W, X, bias, part, M, N, K, splits=0, stream=0) -> int:
-    rc = _lib().sn_k_gemm_splitk(dtype, _p(W), _p(X), _p(bias), _p(part), M, N, K, splits, stream)
+def sn_k_gemm_splitk(dtype, W, X, bias, part, M, N, K, splits=0, flags=0, stream=0) -> int:
+    rc = _lib().sn_k_gemm_splitk(dtype, _p(W), _p(X), _p(bias), _p(part), M, N, K, splits, flags, stream)
     if rc <= 0:
         _chk(rc if rc < 0 else -1)
     return rc

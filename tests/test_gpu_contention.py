@@ -77,20 +77,27 @@ def test_coordinator_interval_meets_the_slo_under_contention_where_the_solo_pick
         moved = [0, 0.0]
 
         def neighbour():
+            """Copies `chunk` bytes at a time, never more than other_bps on average; when the shared link
+            makes it fall behind it copies back to back until it has caught up (two copies in flight)."""
             period = chunk / other_bps
             t0 = time.perf_counter()
-            nxt = t0
+            due = t0
+            ev = [torch.cuda.Event(), torch.cuda.Event()]
+            n = 0
             while not stop.is_set():
+                if n >= 2:
+                    ev[n % 2].synchronize()                       # the copy before the previous one has landed
+                    moved[0] += chunk
                 with torch.cuda.stream(side):
                     dst.copy_(src, non_blocking=True)
-                side.synchronize()
-                moved[0] += chunk
-                nxt += period
-                lag = nxt - time.perf_counter()
+                    ev[n % 2].record(side)
+                n += 1
+                due = max(due + period, time.perf_counter() - 8 * period)   # bounded debt
+                lag = due - time.perf_counter()
                 if lag > 0:
                     time.sleep(lag)
-                else:
-                    nxt = time.perf_counter()
+            side.synchronize()
+            moved[0] += chunk * min(n, 2)
             moved[1] = time.perf_counter() - t0
 
         def measure(n, contended):
