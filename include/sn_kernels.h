@@ -103,6 +103,23 @@ int sn_k_attn_decode(int32_t dtype, const void* qkv16, const void* kv, const int
                      int32_t Hq, int32_t Hkv, int32_t d, int32_t S, int32_t max_len,
                      int32_t packed_out, void* stream);
 
+/* sn_k_attn_decode for callers that cannot allocate device memory -- code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc: the partial results of the S key ranges go to a
+ * buffer of SN_K_STATIC_SCRATCH_BYTES that is part of the library's code object, so there is no `part`
+ * argument and the call allocates nothing (no hipMalloc / hipFree, no allocating library routine).  Inputs
+ * and outputs are the caller's, as in sn_k_attn_decode, and the result is the same bit for bit.
+ * Limit: B*Hq*S*(d+2)*4 bytes <= SN_K_STATIC_SCRATCH_BYTES when S > 1 (S == 0: the library's choice for
+ * max_len, as in sn_k_attn_decode); beyond it SN_E_INVAL, with the sizes in sn_last_error(NULL).
+ * Every call on one GPU uses that GPU's single buffer: calls that overlap on one GPU (different streams
+ * or threads) race; calls on one stream are ordered.  Nothing in it needs clearing between calls (every
+ * partial is written before it is read).  Each GPU the library has run on keeps its buffer until the
+ * process ends; its address is looked up at sn_init or at the first call on that GPU. */
+#define SN_K_STATIC_SCRATCH_BYTES (16u << 20)
+int sn_k_attn_decode_static(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
+                            const int32_t* kv_off, const int32_t* cap, void* out16, int32_t B, int32_t Hq,
+                            int32_t Hkv, int32_t d, int32_t S, int32_t max_len, int32_t packed_out,
+                            void* stream);
+
 /* The decode step's rotation, KV append and attention in one kernel (what sn_step runs
  * when decoding; steps a6 + a7 of a layer).  Row b of qkv16 is the QKV projection's
  * output as is: q and k not yet rotated, nothing appended.  The kernel rotates q and k at

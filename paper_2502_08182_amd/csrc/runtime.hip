@@ -24,10 +24,12 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
 #include "../../include/sn.h"
+#include "../../include/sn_kernels.h"
 #include "kernels.h"
 #include "layout.h"
 #include "schedule.h"
@@ -65,6 +67,37 @@ struct LayerState {
                                 // compute stream has not waited for it yet
 };
 
+}  // namespace
+
+// Scratch memory that belongs to the library's code object, for the entry point that may not allocate
+// (sn_k_attn_decode_static).  Each GPU the library runs on holds its own copy until the process ends; in
+// host code the array's name is only a handle, so its device address is looked up once per device, with
+// that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[SN_K_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+// Device address of `scratch` on the current device (nullptr and a HIP error code on failure).
+hipError_t static_scratch(void** out) {
+  *out = nullptr;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 }  // namespace
 
 struct sn_ctx {
@@ -483,6 +516,13 @@ extern "C" int sn_init(sn_ctx** out, const sn_model_shape* shape, uint64_t hbm_b
   int ndev = 0;
   if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1)
     return fail(nullptr, SN_E_HIP, "sn_init: no HIP device available");
+  {
+    // set-up of the library's own scratch memory on this device, so that the entry point that must not
+    // allocate finds it ready (it would otherwise do this on its first call)
+    void* p = nullptr;
+    const hipError_t e = static_scratch(&p);
+    if (e != hipSuccess) return fail(nullptr, SN_E_HIP, "sn_init: address of the static scratch buffer: %s", hipGetErrorString(e));
+  }
   sn_ctx* c = new sn_ctx();
   const int rc = init_impl(c, shape, hbm_budget_bytes, stream);
   if (rc != SN_OK) {
@@ -1375,3 +1415,37 @@ extern "C" int sn_pick_interval(sn_ctx* c, double slo_ms, int32_t* N_out) {
   return SN_OK;
 }
 
+// =================================================================================
+// entry point for callers that cannot allocate
+// =================================================================================
+extern "C" int sn_k_attn_decode_static(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
+                                       const int32_t* kv_off, const int32_t* cap, void* out16, int32_t B, int32_t Hq,
+                                       int32_t Hkv, int32_t d, int32_t S, int32_t max_len, int32_t packed_out,
+                                       void* stream) {
+  if ((dtype != SN_F16 && dtype != SN_BF16) || !qkv16 || !kv || !len_before || !kv_off || !cap || !out16 || B < 0 ||
+      Hq < 1 || Hkv < 1 || Hq % Hkv || (d != 64 && d != 128) || S < 0 || S > 16)
+    return fail(nullptr, SN_E_INVAL, "sn_k_attn_decode_static: bad argument");
+  if (S == 0) {
+    if (max_len < 1) return fail(nullptr, SN_E_INVAL, "sn_k_attn_decode_static: S == 0 needs max_len");
+    S = attn_decode_splits(B, Hkv, max_len);
+  }
+  // the partial results of the key ranges: [B][Hq][S][d+2] fp32, every element written before it is read
+  const uint64_t need = S > 1 ? (uint64_t)B * Hq * S * (d + 2) * sizeof(float) : 0;
+  if (need > SN_K_STATIC_SCRATCH_BYTES)
+    return fail(nullptr, SN_E_INVAL,
+                "sn_k_attn_decode_static: %d sequences x %d heads x %d key ranges need %llu bytes of partial results, the "
+                "static buffer holds %llu; use sn_k_attn_decode with a buffer of your own",
+                B, Hq, S, (unsigned long long)need, (unsigned long long)SN_K_STATIC_SCRATCH_BYTES);
+  void* part = nullptr;
+  const hipError_t es = static_scratch(&part);
+  if (es != hipSuccess) return fail(nullptr, SN_E_HIP, "sn_k_attn_decode_static: static scratch buffer: %s", hipGetErrorString(es));
+  StepIndex ix{};
+  ix.len_before = len_before;
+  ix.kv_off = kv_off;
+  ix.cap = cap;
+  const hipError_t e = launch_attn_decode(dtype, qkv16, kv, ix, out16, static_cast<float*>(part), B, Hq, Hkv, d, S,
+                                          (hipStream_t)stream, packed_out != 0);
+  if (e != hipSuccess)
+    return fail(nullptr, e == hipErrorInvalidValue ? SN_E_INVAL : SN_E_HIP, "sn_k_attn_decode_static: %s", hipGetErrorString(e));
+  return SN_OK;
+}
