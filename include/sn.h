@@ -64,7 +64,7 @@ typedef struct {
  * hidden_in, sequences in order. */
 typedef struct {
   int32_t batch;
-  int32_t is_prefill;       /* 0: decode (every n_new[b] == 1); 1: prefill / chunk          */
+  int32_t is_prefill;       /* 0: decode (every n_new[b] == 1, batch <= 128); 1: prefill / chunk */
   const int32_t* n_new;     /* host, [batch]                                                */
   const void* hidden_in;    /* device, [sum n_new, hidden], shape.dtype                     */
 } sn_batch;

@@ -45,7 +45,7 @@ int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, c
  * epilogue 0: 16-bit store; 1: GELU (erf) then 16-bit store; 2: out is the fp32 residual
  * stream [M][N], updated in place (+=); 3: SwiGLU -- W holds gate and up in alternating
  * 16-row blocks (N = 2*ffn rows), bias = [gate | up], out16[M][N/2] = silu(g)*u.
- * path 0: weight-streaming decode kernel (M <= 64); path 1: tiled prefill kernel.
+ * path 0: weight-streaming decode kernel (M <= 128; a packed X holds 16*ceil(M/16) rows); path 1: tiled prefill kernel.
  * flags (path 0 only): 1 = X is row-tile packed; 2 = the 16-bit output (epilogues 0, 1, 3)
  * is written row-tile packed. */
 int sn_k_gemm(int32_t dtype, int32_t epilogue, int32_t path, const void* W, const void* X,

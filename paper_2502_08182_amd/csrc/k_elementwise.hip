@@ -228,13 +228,13 @@ template <class T, bool LN, bool FOLD>
 static void launch_norm_t(float* x32, const uint16_t* gain, const uint16_t* shift, uint16_t* u16, int Tn, int h,
                           float eps, const Fold& f, int packed, hipStream_t st) {
   const uint16_t* fb = (const uint16_t*)f.bias;
-  if (Tn <= 64 && h <= 4096)
+  if (Tn <= 128 && h <= 4096)
     SN_LAUNCH((norm_kernel<T, LN, 1024, 1, FOLD>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps, f.part,
               f.nsplit, fb, packed);
-  else if (Tn <= 64 && h <= 8192)
+  else if (Tn <= 128 && h <= 8192)
     SN_LAUNCH((norm_kernel<T, LN, 1024, 2, FOLD>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps, f.part,
               f.nsplit, fb, packed);
-  else if (Tn <= 64)
+  else if (Tn <= 128)
     SN_LAUNCH((norm_kernel<T, LN, 1024, 4, FOLD>), dim3(Tn), dim3(1024), 0, st, x32, gain, shift, u16, h, eps, f.part,
               f.nsplit, fb, packed);
   else

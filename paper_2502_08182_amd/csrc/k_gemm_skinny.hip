@@ -26,7 +26,7 @@ namespace sn {
 template <class T, int MT, int C, int EPI>
 __device__ __forceinline__ void reduce_and_store(float* red, const f32x4 (&acc)[MT][C], int lane, int wave, int KS, int NWN,
                                                  const uint16_t* __restrict__ bias, void* __restrict__ out, int M, int N,
-                                                 int opacked) {
+                                                 int opacked, int plane_rows) {
   constexpr bool DUAL = EPI == EPI_SWIGLU16;
   const int KSK = KS / NWN;
   // fixed-order reduction of the KS partial tiles, one row tile at a time
@@ -75,7 +75,7 @@ __device__ __forceinline__ void reduce_and_store(float* red, const f32x4 (&acc)[
           if (bias && blockIdx.y == 0)
 #pragma unroll
             for (int i = 0; i < 4; ++i) s0[i] += to_f32<T>(bias[n + i]);
-          *reinterpret_cast<f32x4*>(static_cast<float*>(out) + ((size_t)blockIdx.y * M + m) * N + n) = s0;
+          *reinterpret_cast<f32x4*>(static_cast<float*>(out) + ((size_t)blockIdx.y * plane_rows + m) * N + n) = s0;
         } else if (EPI == EPI_RESID32) {
           float* xr = static_cast<float*>(out) + (size_t)m * N + n;
           f32x4 r = *reinterpret_cast<const f32x4*>(xr);
@@ -121,7 +121,7 @@ constexpr int ring_depth(int MT, int C, int WMAX) {
 template <class T, int MT, int C, int EPI, int WMAX, bool SHARE>
 __global__ __launch_bounds__(WMAX * 64) void gemm_skinny_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
-    void* __restrict__ out, int M, int N, int K, int xpacked, int opacked, int NWN_) {
+    void* __restrict__ out, int M, int N, int K, int xpacked, int opacked, int NWN_, int plane_rows) {
   const int NWN = SHARE ? NWN_ : 1;
   constexpr bool DUAL = EPI == EPI_SWIGLU16;
   static_assert(!DUAL || C % 2 == 0, "SwiGLU needs gate/up pairs");
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(WMAX * 64) void gemm_skinny_kernel(
   }
   if (SPLIT_ACC) acc[0][0] += acc_b;
 
-  reduce_and_store<T, MT, C, EPI>(red, acc, lane, wave, KS, NWN, bias, out, M, N, opacked);
+  reduce_and_store<T, MT, C, EPI>(red, acc, lane, wave, KS, NWN, bias, out, M, N, opacked, plane_rows);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(WMAX * 64) void gemm_skinny_kernel(
 template <class T, int MT, int C, int EPI>
 __global__ __launch_bounds__(512) void gemm_wide_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
-    void* __restrict__ out, int M, int N, int K, int opacked, int NWN) {
+    void* __restrict__ out, int M, int N, int K, int opacked, int NWN, int plane_rows) {
   constexpr int KC = 2;                                // k-blocks per step
   constexpr int TILES = KC * MT;                       // activation tiles (1 KiB) per step and K range
   constexpr int R = (TILES + 3) / 4;                   // 16-byte pieces per lane and step (NWN >= 4)
@@ -318,6 +318,7 @@ __global__ __launch_bounds__(512) void gemm_wide_kernel(
   const int cb = (blockIdx.x * NWN + wn) * C;
   const uint16_t* wp = W + ((size_t)cb * KB) * 512 + lane * 8;
   const size_t wstride = (size_t)KB * 512;
+  const int mtiles = (M + 15) >> 4;
   uint16_t* stage = reinterpret_cast<uint16_t*>(red) + (size_t)wk * (2 * TILES * 512);   // this K range's two stages
 
   // this lane's pieces of a step: piece p = tile (p / 64) = (kc, mt), 16 bytes number p % 64 of it
@@ -348,7 +349,8 @@ __global__ __launch_bounds__(512) void gemm_wide_kernel(
   auto sload = [&](int step) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const int kc = ptile[r] / MT, mt = ptile[r] % MT;
+      // row tiles past the last one X holds (MT may exceed ceil(M / 16)) read the last real tile: never stored
+      const int kc = ptile[r] / MT, mt = min(ptile[r] % MT, mtiles - 1);
       sreg[r] = *reinterpret_cast<const u16x8*>(X + ((size_t)mt * KB + kb_at(step * KC + kc)) * 512 + poff[r]);
     }
   };
@@ -395,7 +397,7 @@ __global__ __launch_bounds__(512) void gemm_wide_kernel(
     lds_barrier();
   }
   // the last barrier also says: nobody reads the stages any more
-  reduce_and_store<T, MT, C, EPI>(red, acc, lane, wave, KS, NWN, bias, out, M, N, opacked);
+  reduce_and_store<T, MT, C, EPI>(red, acc, lane, wave, KS, NWN, bias, out, M, N, opacked, plane_rows);
 }
 
 // K-split per workgroup (wavefronts per workgroup).  Measured on MI355X with M = 8:
@@ -440,11 +442,11 @@ static int pick_columns(int MT, int groups, int KB, int ks) {
 struct WidePlan {
   int C, nwn, ks;
 };
-static WidePlan plan_wide(int nb, int KB) {
+static WidePlan plan_wide(int nb, int KB, int only_c = 0) {
   WidePlan best{nb % 4 == 0 ? 4 : (nb % 2 == 0 ? 2 : 1), 1, 8};
   long best_cost = -1;
   for (int C : {4, 2}) {
-    if (nb % C) continue;
+    if (nb % C || (only_c && C != only_c)) continue;
     const int groups = nb / C;
     for (int nwn = 4; nwn <= 8; ++nwn) {
       if (groups % nwn) continue;
@@ -464,7 +466,7 @@ static WidePlan plan_wide(int nb, int KB) {
 
 template <class T, int MT, int C>
 static hipError_t launch_wide(int epi, int ks, int nwn, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
-                              int M, int N, int K, int splits, int opacked, hipStream_t st) {
+                              int M, int N, int K, int splits, int opacked, int plane_rows, hipStream_t st) {
   const int groups = N / (16 * C * nwn);
   const int ksk = ks / nwn;
   const size_t lds = std::max((size_t)ks * C * 64 * 4 * sizeof(float), (size_t)ksk * 2 * 2 * MT * 1024);
@@ -472,16 +474,16 @@ static hipError_t launch_wide(int epi, int ks, int nwn, const uint16_t* W, const
   if (nwn < 4 || ks > 8 || ks % nwn || (N / (16 * C)) % nwn) return hipErrorInvalidValue;
   switch (epi) {
     case EPI_PART32:
-      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_PART32>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn);
+      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_PART32>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn, plane_rows);
       break;
     case EPI_STORE16:
-      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_STORE16>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn);
+      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_STORE16>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn, plane_rows);
       break;
     case EPI_GELU16:
-      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_GELU16>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn);
+      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_GELU16>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn, plane_rows);
       break;
     case EPI_SWIGLU16:
-      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_SWIGLU16>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn);
+      SN_LAUNCH((gemm_wide_kernel<T, MT, C, EPI_SWIGLU16>), grid, block, lds, st, W, X, bias, out, M, N, K, opacked, nwn, plane_rows);
       break;
     default:
       return hipErrorInvalidValue;
@@ -491,27 +493,27 @@ static hipError_t launch_wide(int epi, int ks, int nwn, const uint16_t* W, const
 
 template <class T, int MT, int C, int WMAX, bool SHARE>
 static hipError_t launch_w(int epi, int ks, int nwn, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
-                           int M, int N, int K, int splits, int xpacked, int opacked, hipStream_t st) {
+                           int M, int N, int K, int splits, int xpacked, int opacked, int plane_rows, hipStream_t st) {
   const int groups = N / (16 * C * nwn);
   const size_t lds = (size_t)ks * C * 64 * 4 * sizeof(float);     // <= 64 KiB (ks <= 16, C <= 4)
   dim3 grid(groups, epi == EPI_PART32 ? splits : 1), block(ks * 64);
   if (ks > WMAX || ks % nwn || (N / (16 * C)) % nwn || (!SHARE && nwn != 1)) return hipErrorInvalidValue;
   switch (epi) {
     case EPI_PART32:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_PART32, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_PART32, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn, plane_rows);
       break;
     case EPI_STORE16:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_STORE16, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_STORE16, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn, plane_rows);
       break;
     case EPI_GELU16:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_GELU16, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_GELU16, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn, plane_rows);
       break;
     case EPI_RESID32:
-      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_RESID32, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
+      SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_RESID32, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn, plane_rows);
       break;
     case EPI_SWIGLU16:
       if constexpr (C % 2 == 0) {
-        SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_SWIGLU16, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn);
+        SN_LAUNCH((gemm_skinny_kernel<T, MT, C, EPI_SWIGLU16, WMAX, SHARE>), grid, block, lds, st, W, X, bias, out, M, N, K, xpacked, opacked, nwn, plane_rows);
         break;
       }
       return hipErrorInvalidValue;
@@ -523,7 +525,7 @@ static hipError_t launch_w(int epi, int ks, int nwn, const uint16_t* W, const ui
 
 template <class T, int MT, int C>
 static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
-                            int M, int N, int K, int splits, int xpacked, int opacked, hipStream_t st) {
+                            int M, int N, int K, int splits, int xpacked, int opacked, int plane_rows, hipStream_t st) {
   const int KB = K / 32;
   const int groups = N / (16 * C);
   if (epi == EPI_PART32) {
@@ -531,23 +533,23 @@ static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const
     // (64 rows, 8192 x 28672, 8 splits: 96 -> 87 us)
     if constexpr (MT >= 3 && C == 4)
       if (groups % 4 == 0 && groups / 4 * splits >= 200 && KB / splits >= 64)
-        return launch_w<T, MT, C, 8, true>(epi, 8, 4, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+        return launch_w<T, MT, C, 8, true>(epi, 8, 4, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
     // 3-4 row tiles otherwise: 8 wavefronts (few splits, see gemm_skinny_splits); up to 2 row tiles:
     // 4 wavefronts, the K split across workgroups provides the parallelism
     if constexpr (MT >= 3)
-      return launch_w<T, MT, C, 8, false>(epi, 8, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+      return launch_w<T, MT, C, 8, false>(epi, 8, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
     else
-      return launch_w<T, MT, C, 16, false>(epi, (MT == 1 && splits == 1) ? 8 : 4, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+      return launch_w<T, MT, C, 16, false>(epi, (MT == 1 && splits == 1) ? 8 : 4, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
   }
   if constexpr (MT >= 3) {      // 8 wavefronts at most: twice the registers, nothing spills
     const int nwn = pick_columns(MT, groups, KB, 8);
-    if (nwn > 1) return launch_w<T, MT, C, 8, true>(epi, 8, nwn, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
-    return launch_w<T, MT, C, 8, false>(epi, 8, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    if (nwn > 1) return launch_w<T, MT, C, 8, true>(epi, 8, nwn, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+    return launch_w<T, MT, C, 8, false>(epi, 8, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
   } else {
     const int ks = pick_ks(groups, KB);
     const int nwn = pick_columns(MT, groups, KB, ks);
-    if (nwn > 1) return launch_w<T, MT, C, 16, true>(epi, ks, nwn, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
-    return launch_w<T, MT, C, 16, false>(epi, ks, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    if (nwn > 1) return launch_w<T, MT, C, 16, true>(epi, ks, nwn, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+    return launch_w<T, MT, C, 16, false>(epi, ks, 1, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
   }
 }
 
@@ -556,16 +558,43 @@ static hipError_t launch_mc(int epi, const uint16_t* W, const uint16_t* X, const
 // an even count (gate/up pairs).
 template <class T>
 static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out, int M,
-                           int N, int K, int splits, int xpacked, int opacked, hipStream_t st) {
+                           int N, int K, int splits, int xpacked, int opacked, int plane_rows, hipStream_t st) {
   const int nb = N / 16;
   const bool dual = epi == EPI_SWIGLU16;
+  if (M > 64) {
+    // 65..128 rows.  Packed activations and enough feature groups: the LDS-sharing kernel with 6 or 8 row tiles and
+    // two column blocks per wavefront (the weights still cross the chip once).  Otherwise two passes of up to 64 rows
+    // (the weights are read twice: only shapes with few feature groups or row-major activations get here).
+    if (xpacked && epi != EPI_RESID32 && nb % 2 == 0) {
+      WidePlan pl{2, 4, 8};
+      bool ok;
+      if (epi == EPI_PART32) {
+        const int groups = nb / 2;
+        ok = groups % 4 == 0 && groups / 4 * splits >= 200 && (K / 32) / splits >= 64;
+      } else {
+        pl = plan_wide(nb, K / 32, 2);
+        ok = pl.nwn >= 4;
+      }
+      if (ok) {
+        if (M <= 96) return launch_wide<T, 6, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
+        return launch_wide<T, 8, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
+      }
+    }
+    const hipError_t e = launch_t<T>(epi, W, X, bias, out, 64, N, K, splits, xpacked, opacked, plane_rows, st);
+    if (e != hipSuccess) return e;
+    const int ncols = dual ? N / 2 : N;
+    const uint16_t* X2 = X + (size_t)64 * K;                    // 4 row tiles further on, packed or row-major
+    void* out2 = (epi == EPI_PART32 || epi == EPI_RESID32) ? static_cast<void*>(static_cast<float*>(out) + (size_t)64 * ncols)
+                                                           : static_cast<void*>(static_cast<uint16_t*>(out) + (size_t)64 * ncols);
+    return launch_t<T>(epi, W, X2, bias, out2, M - 64, N, K, splits, xpacked, opacked, plane_rows, st);
+  }
   if (M <= 16) {
-    if (dual) return launch_mc<T, 1, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
-    return launch_mc<T, 1, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    if (dual) return launch_mc<T, 1, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+    return launch_mc<T, 1, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
   }
   if (M <= 32) {
-    if (nb % 2 == 0) return launch_mc<T, 2, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
-    return launch_mc<T, 2, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    if (nb % 2 == 0) return launch_mc<T, 2, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+    return launch_mc<T, 2, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
   }
   if (M > 16 && xpacked && epi != EPI_RESID32) {
     // 2-4 row tiles, packed activations: the kernel that shares them through LDS, where a launch shape exists
@@ -584,25 +613,25 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
     }
     if (ok && !(dual && pl.C % 2)) {
       if (M <= 32) {
-        if (pl.C == 4) return launch_wide<T, 2, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
-        return launch_wide<T, 2, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
+        if (pl.C == 4) return launch_wide<T, 2, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
+        return launch_wide<T, 2, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
       }
       if (M <= 48) {
-        if (pl.C == 4) return launch_wide<T, 3, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
-        return launch_wide<T, 3, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
+        if (pl.C == 4) return launch_wide<T, 3, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
+        return launch_wide<T, 3, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
       }
-      if (pl.C == 4) return launch_wide<T, 4, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
-      return launch_wide<T, 4, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, st);
+      if (pl.C == 4) return launch_wide<T, 4, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
+      return launch_wide<T, 4, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
     }
   }
   if (M <= 48) {
-    if (nb % 4 == 0) return launch_mc<T, 3, 4>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
-    if (nb % 2 == 0) return launch_mc<T, 3, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
-    return launch_mc<T, 3, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+    if (nb % 4 == 0) return launch_mc<T, 3, 4>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+    if (nb % 2 == 0) return launch_mc<T, 3, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+    return launch_mc<T, 3, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
   }
-  if (nb % 4 == 0) return launch_mc<T, 4, 4>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
-  if (nb % 2 == 0) return launch_mc<T, 4, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
-  return launch_mc<T, 4, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, st);
+  if (nb % 4 == 0) return launch_mc<T, 4, 4>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+  if (nb % 2 == 0) return launch_mc<T, 4, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+  return launch_mc<T, 4, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
 }
 
 hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, const void* bias, void* out,
@@ -611,11 +640,12 @@ hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, 
   if (opacked && (epi == EPI_RESID32 || epi == EPI_PART32)) return hipErrorInvalidValue;
   if (opacked && (epi == EPI_SWIGLU16 ? (N / 2) % 32 : N % 32)) return hipErrorInvalidValue;
   if (M <= 0) return hipSuccess;
-  if (M > 64 || N % 16 || K % 32 || (epi == EPI_SWIGLU16 && N % 32)) return hipErrorInvalidValue;
+  if (M > kMaxDecodeRows || N % 16 || K % 32 || (epi == EPI_SWIGLU16 && N % 32)) return hipErrorInvalidValue;
   if (epi == EPI_PART32 ? (splits < 1 || splits > kMaxSplits) : splits != 1) return hipErrorInvalidValue;
+  const int plane_rows = M;                                    // rows of one plane of partial sums
   if (dtype == 0)
-    return launch_t<F16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, splits, xpacked, opacked, st);
-  return launch_t<BF16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, splits, xpacked, opacked, st);
+    return launch_t<F16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+  return launch_t<BF16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
 }
 
 // Split count for the residual projections of a decode step (few output features, long
@@ -625,7 +655,7 @@ hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, 
 // the 4-column instance applies (long K, see launch_mc), else as few as give about one
 // workgroup per CU (64 rows, 8192 x 8192: 2 splits 30.7 us, 8 splits 33.5 us).
 int gemm_skinny_splits(int M, int N, int K) {
-  const int C = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+  const int C = M <= 16 ? 1 : (M <= 32 || M > 64 ? 2 : 4);
   const int groups = N / (16 * C);
   const int KB = K / 32;
   int sp = 1;

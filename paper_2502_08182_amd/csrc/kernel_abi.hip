@@ -130,7 +130,7 @@ extern "C" int sn_k_copy(const void* src, void* dst, uint64_t bytes, void* strea
 
 extern "C" int sn_k_gemm_splitk(int32_t dtype, const void* W, const void* X, const void* bias, void* part, int32_t M,
                                 int32_t N, int32_t K, int32_t splits, int32_t flags, void* stream) {
-  if (bad_dtype(dtype) || !W || !X || !part || M < 0 || M > 64 || N < 16 || K < 32 || (flags & ~1)) return SN_E_INVAL;
+  if (bad_dtype(dtype) || !W || !X || !part || M < 0 || M > kMaxDecodeRows || N < 16 || K < 32 || (flags & ~1)) return SN_E_INVAL;
   if (splits == 0) splits = gemm_skinny_splits(M, N, K);
   if (splits < 1 || splits > kMaxSplits) return SN_E_INVAL;
   const hipError_t e = launch_gemm_skinny(dtype, EPI_PART32, W, X, bias, part, M, N, K, (hipStream_t)stream, splits, flags & 1 ? kXPacked : 0);

@@ -24,6 +24,7 @@ enum Epilogue {
   EPI_PART32 = 4     // split-K: part[split][m][n] = partial product (no bias); folded in by the consumer
 };
 constexpr int kMaxSplits = 8;
+constexpr int kMaxDecodeRows = 128;  // most token rows of a decode step (the weight-streaming projections)
 constexpr int kPrefillQTile = 128;   // query rows (new tokens of one sequence) per prefill-attention workgroup
 
 // Pending split-K partial sums of a residual projection: the next kernel that reads the
@@ -67,7 +68,7 @@ hipError_t launch_norm_fold(int dtype, int is_ln, float* x32, const void* gain, 
                             int h, float eps, const Fold& fold, hipStream_t st, int packed_out = 0);
 
 // out = epilogue(X[M][K] * W^T), W tiled [N/16][K/32][64][8].  N counts weight rows
-// (2*ffn for EPI_SWIGLU16, whose output has N/2 columns).  Decode path: M <= 64.
+// (2*ffn for EPI_SWIGLU16, whose output has N/2 columns).  Decode path: M <= kMaxDecodeRows.
 // flags: kXPacked -- X is row-tile packed (common.h packed_off); kOutPacked -- the 16-bit
 // output is written row-tile packed (it feeds the next decode projection).
 constexpr int kXPacked = 1, kOutPacked = 2;

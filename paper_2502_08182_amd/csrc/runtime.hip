@@ -454,7 +454,7 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   if (c->max_tokens > (int64_t)1 << 24) return fail(c, SN_E_INVAL, "max_tokens too large");
   const int L = s.n_layers;
   // decode activations are stored in 16-row tiles: keep room for whole tiles
-  const uint64_t T = std::max<uint64_t>((uint64_t)c->max_tokens, (uint64_t)((std::min(s.max_batch, 64) + 15) / 16 * 16));
+  const uint64_t T = std::max<uint64_t>((uint64_t)c->max_tokens, (uint64_t)((std::min(s.max_batch, kMaxDecodeRows) + 15) / 16 * 16));
   const uint64_t qkv_ld = (uint64_t)c->pl.n_qkv, qd = (uint64_t)s.n_q_heads * s.head_dim;
 
   const uint64_t b_x32 = align_up(T * s.hidden * 4), b_u = align_up(T * s.hidden * 2);
@@ -465,7 +465,7 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   c->meta_ints = (size_t)(5 * (uint64_t)s.max_batch + 2 * T + 2 * n_tiles_max);
   const uint64_t b_meta = align_up(c->meta_ints * 4);
   const uint64_t b_freq = align_up((uint64_t)s.head_dim / 2 * 4);
-  const uint64_t b_part32 = align_up((uint64_t)kMaxSplits * std::min(s.max_batch, 64) * s.hidden * 4);
+  const uint64_t b_part32 = align_up((uint64_t)kMaxSplits * std::min(s.max_batch, kMaxDecodeRows) * s.hidden * 4);
   c->ws_bytes = b_x32 + b_u + b_qkv + b_attn + b_act + b_part + b_part32 + b_meta + b_freq;
 
   SN_HIP(c, hipStreamCreateWithFlags(&c->h2d, hipStreamNonBlocking));
@@ -844,7 +844,7 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, 
   const int qd = Hq * d;
   auto at = [&](uint64_t off) -> const void* { return off == kNone ? nullptr : base + off; };
   hipStream_t st = c->compute;
-  const bool small = !prefill;   // decode path: T == B <= 64
+  const bool small = !prefill;   // decode path: T == B <= kMaxDecodeRows
   KTimer kt{c, l, 0, c->timing >= 2};
   // decode: activations between kernels are row-tile packed (inputs of the skinny GEMMs);
   // the QKV output stays row-major for the attention kernels
@@ -927,7 +927,7 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
   }
   if (T64 == 0) return fail(c, SN_E_INVAL, "sn_step: no tokens");
   if (T64 > c->max_tokens) return fail(c, SN_E_INVAL, "sn_step: %lld tokens exceed max_tokens %lld", (long long)T64, (long long)c->max_tokens);
-  if (!prefill && B > 64) return fail(c, SN_E_INVAL, "sn_step: decode batch above 64");
+  if (!prefill && B > kMaxDecodeRows) return fail(c, SN_E_INVAL, "sn_step: decode batch above %d", kMaxDecodeRows);
   const int T = (int)T64;
 
   // ---- index arrays: host ring buffer -> device ----
@@ -1162,7 +1162,7 @@ extern "C" int sn_time_kernel_class(sn_ctx* c, int32_t kernel_class, int32_t bat
                                     int32_t* launches) {
   if (!c || !total_ns || !launches) return fail(c, SN_E_INVAL, "sn_time_kernel_class: null argument");
   if (!c->placed) return fail(c, SN_E_STATE, "sn_time_kernel_class before sn_place");
-  if (batch < 1 || batch > 64 || batch > c->shape.max_batch || reps < 1 || reps > 1000)
+  if (batch < 1 || batch > kMaxDecodeRows || batch > c->shape.max_batch || reps < 1 || reps > 1000)
     return fail(c, SN_E_INVAL, "sn_time_kernel_class: bad batch or reps");
   const sn_model_shape& s = c->shape;
   const PackedLayout& p = c->pl;
@@ -1239,7 +1239,7 @@ extern "C" int sn_profile_layers(sn_ctx* c, int32_t is_prefill, int32_t batch, i
   const int L = s.n_layers;
   if (batch < 1 || batch > s.max_batch || seq < 1 || reps < 1 || reps > 1000)
     return fail(c, SN_E_INVAL, "sn_profile_layers: bad batch/seq/reps");
-  if (!is_prefill && batch > 64) return fail(c, SN_E_INVAL, "sn_profile_layers: decode batch above 64");
+  if (!is_prefill && batch > kMaxDecodeRows) return fail(c, SN_E_INVAL, "sn_profile_layers: decode batch above %d", kMaxDecodeRows);
   const int cap1 = is_prefill ? seq : seq + 1;
   if ((int64_t)cap1 * batch > (int64_t)s.max_batch * s.max_seq)
     return fail(c, SN_E_INVAL, "sn_profile_layers: batch*seq exceeds the context's KV capacity");

@@ -206,6 +206,65 @@ def test_gemm_wide_shares_activations_through_lds(dtype):
         assert np.abs(planes.sum(axis=0) - want).max() <= 2e-5 * np.abs(want).max(), (M, N, Kd)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_gemm_skinny_65_to_128_rows(dtype):
+    """Decode projections at 65..128 token rows: the LDS-sharing kernel with 6 or 8 row tiles where the launch
+    shape allows it (packed activations, enough feature groups), two passes of up to 64 rows otherwise (few
+    feature groups, or row-major activations); every epilogue; split-K planes on both paths."""
+    cases = [(K.EPI_STORE16, 65, 16384, 96, True, True),      # 6 row tiles, 5 of them real
+             (K.EPI_SWIGLU16, 96, 16384, 160, False, True),
+             (K.EPI_GELU16, 128, 28672, 1056, True, True),    # 8 row tiles, 7 wavefronts side by side, odd k-block count
+             (K.EPI_STORE16, 100, 192, 416, True, True),      # few feature groups: two passes, packed
+             (K.EPI_SWIGLU16, 128, 320, 96, False, False),    # two passes, row-major
+             (K.EPI_RESID32, 77, 192, 416, True, False)]
+    for i, (epi, M, N, Kd, bias, packed) in enumerate(cases):
+        rng = np.random.default_rng(400 + i)
+        dual = epi == K.EPI_SWIGLU16
+        Wrows = 2 * N if dual else N
+        xb = synth.to_bits(rng.standard_normal((M, Kd)), dtype)
+        tiled = np.zeros(Wrows * Kd, dtype=np.uint16)
+        parts = []
+        for j in range(2 if dual else 1):
+            wp = synth.to_bits(rng.standard_normal((N, Kd), dtype=np.float32) * 0.05, dtype)
+            K.sn_k_tile_weights(wp, N, Kd, tiled, 2 if dual else 1, j)
+            parts.append(wp)
+        bb = synth.to_bits(rng.standard_normal(Wrows) * 0.3, dtype) if bias else None
+        x64 = synth.widen(xb, dtype)
+        lin = [x64 @ synth.widen(wp, dtype).T for wp in parts]
+        if bias:
+            b64 = synth.widen(bb, dtype)
+            lin[0] = lin[0] + b64[:N]
+            if dual:
+                lin[1] = lin[1] + b64[N:]
+        xdev = dev16(K.pack_rows(xb) if packed else xb)
+        if epi == K.EPI_RESID32:
+            r0 = rng.standard_normal((M, N)).astype(np.float32)
+            out = torch.from_numpy(r0.copy()).cuda()
+            want = r0.astype(np.float64) + lin[0]
+        else:
+            out = torch.full((M, N), 0x7e00 if dtype == "f16" else 0x7fc0, dtype=torch.int16, device="cuda")
+            want = ofw.silu(lin[0]) * lin[1] if dual else (ofw.gelu(lin[0]) if epi == K.EPI_GELU16 else lin[0])
+        K.sn_k_gemm(DT[dtype], epi, K.PATH_SKINNY, dev16(tiled), xdev, dev16(bb) if bias else None, out, M, Wrows, Kd,
+                    1 if packed else 0)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64) if epi == K.EPI_RESID32 else synth.widen(host16(out), dtype)
+        check(got, want, dtype, f"gemm {M} rows epi={epi} N={N} K={Kd} packed={packed}", out="f32" if epi == K.EPI_RESID32 else "same")
+    rng = np.random.default_rng(420)
+    for M, N, Kd, splits, packed in [(128, 8192, 16384, 8, True), (70, 256, 1024, 3, True), (90, 192, 416, 2, False)]:
+        xb = synth.to_bits(rng.standard_normal((M, Kd)), dtype)
+        wb = synth.to_bits(rng.standard_normal((N, Kd), dtype=np.float32) * 0.05, dtype)
+        bb = synth.to_bits(rng.standard_normal(N) * 0.3, dtype)
+        part = torch.full((splits, M, N), float("nan"), dtype=torch.float32, device="cuda")
+        used = K.sn_k_gemm_splitk(DT[dtype], dev16(K.sn_k_tile_weights(wb, N, Kd)), dev16(K.pack_rows(xb) if packed else xb), dev16(bb),
+                                  part, M, N, Kd, splits, 1 if packed else 0)
+        torch.cuda.synchronize()
+        assert used == splits
+        planes = part.cpu().numpy().astype(np.float64)
+        want = synth.widen(xb, dtype) @ synth.widen(wb, dtype).T + synth.widen(bb, dtype)
+        assert np.isfinite(planes).all(), (M, N, Kd)
+        assert np.abs(planes.sum(axis=0) - want).max() <= 2e-5 * np.abs(want).max(), (M, N, Kd)
+
+
 @pytest.mark.parametrize("case", ["c2_ffn_up", "c3_ffn_up", "c5_qkv", "c5_ffn_up"])
 def test_gemm_skinny_full_size_sampled(case):
     """Decode projections at the benchmark workloads' real shapes and row counts, in the launch configuration a
