@@ -537,24 +537,22 @@ def test_stall_and_hidden_fraction_are_reported(c1):
 
 
 def test_full_size_config2_offloaded_equals_resident_and_sampled_rows_match_oracle():
-    """The benchmark's configuration at full size (32 layers, batch 8, prompt 512), in the launch
+    """The OPT-6.7B-shaped configuration at full size (32 layers, batch 8, prompt 512), in the launch
     configuration bench.py times.  The whole forward is ~1e14 flop, out of the oracle's reach,
     so: (i) offloaded (N=8) and all-resident runs are bit-identical and finite for the prefill
     and two decode steps; (ii) a property that holds at any size pins the numbers to the oracle:
-    with every layer's output projections (wo, wd) and their biases zeroed only in layers
-    1..L-1, the model reduces to its first layer, which the oracle computes for sampled rows
-    of the full-size batch (whole sequence 0, the first 40 tokens of it)."""
-    import dataclasses
+    with the output projections (wo, wd) and their biases zeroed in layers 2..L-1, the model
+    reduces to its first TWO layers, which the oracle computes for sampled rows of the full-size
+    batch (the first 40 tokens of sequence 0: causal, so they depend on nothing later)."""
     w = synth.workload("c2")
     s = w.shape
     L, B, P = s.n_layers, w.batch, 512
     rng = np.random.default_rng(21)
-    layer0 = synth.make_layer(s, 0, 0)
-    lay, total = synth.blob_layout(s)
-    blob0 = synth.pack_blob(s, layer0)
-    dead = dict(layer0)
+    live = [synth.make_layer(s, l, 0) for l in range(2)]
+    blobs = [synth.pack_blob(s, t) for t in live]
+    dead = dict(live[0])
     for name in ("wo", "wd", "bo", "bd"):
-        dead[name] = np.zeros_like(layer0[name])
+        dead[name] = np.zeros_like(live[0][name])
     blob_dead = synth.pack_blob(s, dead)
     prompt = synth.to_bits(rng.standard_normal((B * P, s.hidden)), s.dtype)
     table = synth.to_bits(rng.standard_normal((2, B, s.hidden)), s.dtype)
@@ -562,7 +560,7 @@ def test_full_size_config2_offloaded_equals_resident_and_sampled_rows_match_orac
     for N in (0, 8):
         with Session(s, B, P + 4) as se:
             for l in range(L):
-                sn.sn_set_layer_weights(se.ctx, l, blob0 if l == 0 else blob_dead)
+                sn.sn_set_layer_weights(se.ctx, l, blobs[l] if l < 2 else blob_dead)
             se.place(N)
             se.kv_reset([P + 4] * B)
             pre = se.step([P] * B, True, prompt)
@@ -574,58 +572,69 @@ def test_full_size_config2_offloaded_equals_resident_and_sampled_rows_match_orac
     for a, b in zip(outs[0], outs[8]):
         assert np.array_equal(a, b)
         assert np.isfinite(synth.widen(a, s.dtype)).all()
-    # oracle: layer 0 only, sequence 0, first 40 prompt tokens (causal: they do not depend on later ones)
-    lw = synth.widen_layer(s, layer0)
-    cache = ofw.new_cache(1, 1, s.n_kv_heads, s.head_dim)
-    want = ofw.step(s.as_dict(), [lw], [synth.widen(prompt[:40], s.dtype)], cache, kv_dtype=KV_STORAGE)[0]
-    assert_close(outs[8][0][:40], want, s.dtype, "c2 full size, first layer, sampled rows")
+    lws = [synth.widen_layer(s, t) for t in live]
+    cache = ofw.new_cache(2, 1, s.n_kv_heads, s.head_dim)
+    want = ofw.step(s.as_dict(), lws, [synth.widen(prompt[:40], s.dtype)], cache, kv_dtype=KV_STORAGE)[0]
+    assert_close(outs[8][0][:40], want, s.dtype, "c2 full size, two live layers, sampled rows")
 
 
-def _llama_layer0_rows(s, layer0, x_seq, rows):
-    """Oracle value of the first layer's output for selected token rows of ONE sequence (RMSNorm / RoPE /
-    SwiGLU family).  Keys and values are needed for every earlier position, everything else only for the
-    selected rows, so the pieces of the oracle are applied to exactly those."""
+def _layer_rows(s, layer, x_seq, rows):
+    """Oracle value of ONE layer's output for selected token rows of one sequence whose inputs to that layer are
+    x_seq [P, hidden] (positions 0..P-1).  Keys and values are needed for every earlier position, everything else
+    only for the selected rows, so the pieces of the oracle are applied to exactly those.  Both layer families."""
     Hq, Hkv, d, eps = s.n_q_heads, s.n_kv_heads, s.head_dim, s.norm_eps
     P = x_seq.shape[0]
-    wd = lambda name: synth.widen(layer0[name], s.dtype)
-    u = ofw.rms_norm(x_seq, wd("n1g"), eps)
+    wd = lambda name: synth.widen(layer[name], s.dtype)
+    norm = (lambda x, i: ofw.layer_norm(x, wd(f"n{i}g"), wd(f"n{i}b"), eps)) if s.norm == "ln" else \
+           (lambda x, i: ofw.rms_norm(x, wd(f"n{i}g"), eps))
+    bias = (lambda name: wd(name)) if s.has_bias else (lambda name: 0.0)
+    u = norm(x_seq, 1)
     wqkv = wd("wqkv")
-    kv = u @ wqkv[Hq * d:].T
+    bqkv = bias("bqkv")
+    kv = u @ wqkv[Hq * d:].T + (bqkv[Hq * d:] if s.has_bias else 0.0)
     pos = np.arange(P)
-    k = ofw.rope(kv[:, :Hkv * d].reshape(P, Hkv, d), pos[:, None], s.rope_theta)
+    k = kv[:, :Hkv * d].reshape(P, Hkv, d)
+    if s.rope:
+        k = ofw.rope(k, pos[:, None], s.rope_theta)
     v = kv[:, Hkv * d:].reshape(P, Hkv, d)
     K, V = ofw.round_to_storage(k, KV_STORAGE), ofw.round_to_storage(v, KV_STORAGE)
-    wq, wo, wg, wu, wdn, n2g = wqkv[:Hq * d], wd("wo"), wd("wg"), wd("wu"), wd("wd"), wd("n2g")
+    wq, wo, wdn = wqkv[:Hq * d], wd("wo"), wd("wd")
+    wg = wd("wg") if s.act == "swiglu" else None
+    wu = wd("wu")
     out = []
     for r in rows:
-        q = ofw.rope((u[r] @ wq.T).reshape(1, Hq, d), np.array([[r]]), s.rope_theta)
+        q = (u[r] @ wq.T + (bqkv[:Hq * d] if s.has_bias else 0.0)).reshape(1, Hq, d)
+        if s.rope:
+            q = ofw.rope(q, np.array([[r]]), s.rope_theta)
         a = ofw.causal_attention(q, K[:r + 1], V[:r + 1], r).reshape(1, Hq * d)
-        x1 = x_seq[r:r + 1] + a @ wo.T
-        u2 = ofw.rms_norm(x1, n2g, eps)
-        out.append(x1 + (ofw.silu(u2 @ wg.T) * (u2 @ wu.T)) @ wdn.T)
+        x1 = x_seq[r:r + 1] + a @ wo.T + bias("bo")
+        u2 = norm(x1, 2)
+        if s.act == "swiglu":
+            m = ofw.silu(u2 @ wg.T + bias("bg")) * (u2 @ wu.T + bias("bu"))
+        else:
+            m = ofw.gelu(u2 @ wu.T + bias("bu"))
+        out.append(x1 + m @ wdn.T + bias("bd"))
     return np.concatenate(out, axis=0)
 
 
-def test_full_size_config5_layer_shape_and_batch():
-    """The Llama-2-70B-shaped configuration at its real per-layer shape and full batch: 64 sequences x 2048
-    prompt tokens = 131072 rows per prefill launch, GQA 64/8 heads, SwiGLU 28672, bf16 -- the launch
-    configuration of that workload -- with 3 layers instead of 80 (the 80-layer model is 137 GB; the
-    kernels do not depend on the layer count).  (i) offloaded (N = 2; also with only the KV slice on the
-    host and the continuous schedule) and all-resident runs are bit-identical for the prefill and two
-    decode steps; (ii) with the output projections of layers 1, 2
-    zeroed the model is its first layer, which the oracle computes for sampled rows of sequence 0: early,
-    tile-boundary and last prompt positions (attention over up to 2048 keys) and both decode steps."""
+def _two_live_layers_at_full_batch(name, P, rows_prompt, seed):
+    """A workload's real per-layer shape and full batch with 3 layers, the first two live and the third with its
+    output projections zeroed (so the model IS its first two layers): offloaded runs -- interval 2; and interval 2
+    with only the KV slices on the host under the continuous schedule -- are bit-identical to the all-resident one
+    for the prefill and two decode steps, and the oracle reproduces sampled rows of sequence 0 through BOTH layers:
+    layer 0 for every position of that sequence (layer 1's keys and values need them all), layer 1 for the sampled
+    prompt positions and both decode steps."""
     import dataclasses
-    w = synth.workload("c5")
+    w = synth.workload(name)
     s = dataclasses.replace(w.shape, n_layers=3)
-    B, P = w.batch, 2048
-    rng = np.random.default_rng(51)
-    layer0 = synth.make_layer(s, 0, 0)
-    blob0 = synth.pack_blob(s, layer0)
-    dead = dict(layer0)
-    for name in ("wo", "wd"):
-        dead[name] = np.zeros_like(layer0[name])
-    blob_dead = synth.pack_blob(s, dead)
+    B = w.batch
+    rng = np.random.default_rng(seed)
+    live = [synth.make_layer(s, l, 0) for l in range(2)]
+    blobs = [synth.pack_blob(s, t) for t in live]
+    dead = dict(live[0])
+    for nm in ("wo", "wd") + (("bo", "bd") if s.has_bias else ()):
+        dead[nm] = np.zeros_like(live[0][nm])
+    blobs.append(synth.pack_blob(s, dead))
     del dead
     prompt = synth.to_bits(rng.standard_normal((B * P, s.hidden), dtype=np.float32), s.dtype)
     table = synth.to_bits(rng.standard_normal((2, B, s.hidden), dtype=np.float32), s.dtype)
@@ -633,7 +642,7 @@ def test_full_size_config5_layer_shape_and_batch():
     for N in (0, 2, -2):            # -2: interval 2 again, KV slices only on the host, loads across the iteration boundary
         with Session(s, B, P + 4) as se:
             for l in range(3):
-                sn.sn_set_layer_weights(se.ctx, l, blob0 if l == 0 else blob_dead)
+                sn.sn_set_layer_weights(se.ctx, l, blobs[l])
             if N < 0:
                 sn.sn_set_offload_part(se.ctx, sn.SN_OFFLOAD_KV)
                 sn.sn_set_schedule(se.ctx, sn.SN_SCHED_CONTINUOUS)
@@ -650,12 +659,31 @@ def test_full_size_config5_layer_shape_and_batch():
     for other in (2, -2):
         for a, b in zip(outs[0][:3], outs[other][:3]):
             assert np.array_equal(a, b)
-    del blob0, blob_dead
+    del blobs
     # oracle: sequence 0 = rows 0..P-1 of the prompt, then its two decode tokens at positions P, P+1
     x_seq = np.concatenate([synth.widen(prompt[:P], s.dtype), synth.widen(table[0, 0:1], s.dtype),
                             synth.widen(table[1, 0:1], s.dtype)], axis=0)
-    rows = [0, 1, 63, 64, 127, 128, 1023, 2047, P, P + 1]
-    want = _llama_layer0_rows(s, layer0, x_seq, rows)
-    got_f = np.concatenate([outs[2][3][rows[:8]], outs[2][4], outs[2][5]], axis=0)
-    got_b = np.concatenate([outs[2][0][rows[:8]], outs[2][1][0:1], outs[2][2][0:1]], axis=0)
-    assert_close_f32(got_b, got_f, want, s.dtype, "c5 shape, full batch, first layer, sampled rows of sequence 0")
+    y0 = ofw.layer_forward(s.as_dict(), synth.widen_layer(s, live[0]), x_seq,
+                           {"k": np.zeros((0, s.n_kv_heads, s.head_dim)), "v": np.zeros((0, s.n_kv_heads, s.head_dim))},
+                           KV_STORAGE)
+    rows = list(rows_prompt) + [P, P + 1]
+    want = _layer_rows(s, live[1], y0, rows)
+    got_f = np.concatenate([outs[2][3][list(rows_prompt)], outs[2][4], outs[2][5]], axis=0)
+    got_b = np.concatenate([outs[2][0][list(rows_prompt)], outs[2][1][0:1], outs[2][2][0:1]], axis=0)
+    assert_close_f32(got_b, got_f, want, s.dtype, f"{name} shape, full batch, two live layers, sampled rows of sequence 0")
+
+
+def test_full_size_config5_layer_shape_and_batch():
+    """The Llama-2-70B-shaped configuration at its real per-layer shape and full batch: 64 sequences x 2048 prompt
+    tokens = 131072 rows per prefill launch, GQA 64/8 heads, SwiGLU 28672, bf16 -- the launch configuration of that
+    workload -- with 3 layers instead of 80 (the 80-layer model is 137 GB; the kernels do not depend on the layer
+    count).  Sampled: early, tile-boundary and last prompt positions (attention over up to 2048 keys) and both
+    decode steps (decode attention over 2049 / 2050 keys of layer 1's cache)."""
+    _two_live_layers_at_full_batch("c5", 2048, [0, 1, 63, 64, 127, 128, 1023, 2047], 51)
+
+
+def test_full_size_config3_layer_shape_and_batch():
+    """The Llama-2-13B-shaped configuration at its real per-layer shape, full batch and context: 32 sequences x 1024
+    prompt tokens, 40 MHA heads (the vector decode-attention path, the largest kernel of that workload's decode
+    step), SwiGLU 13824, bf16; 3 layers instead of 40."""
+    _two_live_layers_at_full_batch("c3", 1024, [0, 1, 31, 32, 127, 128, 511, 1023], 31)
