@@ -37,7 +37,7 @@ LINK_NOMINAL = 64.0e9      # bytes/s per direction, PCIe Gen5 x16 host link
 MFMA_PEAK = 2.5e15         # flop/s, dense fp16/bf16 matrix cores
 FAMILY = {"c2": "OPT-6.7B", "c3": "Llama-2-13B", "c4": "OPT-30B", "c5": "Llama-2-70B (GQA)"}
 # rocprofv3 --pmc summaries of the dominant kernel (FETCH_SIZE / WRITE_SIZE), by (workload, batch)
-TRAFFIC_NOTES = {("c2", 8): "gemm_skinny_ffn_up_c2_pmc.txt", ("c5", 64): "gemm_skinny_ffn_up_c5_pmc.txt"}
+TRAFFIC_NOTES = {("c2", 8): "gemm_skinny_ffn_up_c2_pmc.txt", ("c5", 64): "gemm_wide_ffn_up_c5_pmc.txt"}
 
 
 def parse():
@@ -367,21 +367,23 @@ def main():
     k_ns, k_calls = sn.sn_time_kernel_class(se.ctx, 5, B, reps=4)
     # algorithmic bytes per launch: weights + bias + activations in + out
     alg_bytes = n_up * s.hidden * 2 + (n_up * 2 if s.has_bias else 0) + B * s.hidden * 2 + B * s.ffn * 2
-    k_avg_ns = in_ns / max(in_calls, 1)
-    iso_avg_ns = k_ns / max(k_calls, 1)
+    in_avg_ns = in_ns / max(in_calls, 1)
+    k_avg_ns = k_ns / max(k_calls, 1)
     achieved = alg_bytes / (k_avg_ns * 1e-9) if k_avg_ns > 0 else 0.0
     note = TRAFFIC_NOTES.get((w.name, B))
     traffic = read_traffic_note(note) if note else None
-    roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel (FFN up-projection, decode)", "achieved": achieved / 1e9,
+    roofline = {"bound": "hbm", "kernel": "FFN up-projection of the decode step (gemm_wide_kernel / gemm_skinny_kernel)", "achieved": achieved / 1e9,
                 "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": traffic,
                 "traffic_source": (f"profiles/{note}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, collected offline "
-                                   "(counters cannot be read from inside the run)") if traffic else None,
-                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": k_avg_ns / 1e3, "launches_timed": in_calls,
-                "timed": "every launch inside decode iterations at the picked interval, own start/stop timestamps",
-                "isolated_back_to_back": {"avg_launch_us": iso_avg_ns / 1e3, "launches": k_calls,
-                                          "GBps": alg_bytes / (iso_avg_ns * 1e-9) / 1e9 if iso_avg_ns > 0 else None}}
-    log(f"[bench] ffn_up inside iterations {k_avg_ns / 1e3:.1f} us = {achieved / 1e9:.0f} GB/s ({in_calls} launches); "
-        f"back to back {iso_avg_ns / 1e3:.1f} us")
+                                   "(hardware counters cannot be read from inside the run)") if traffic else None,
+                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": k_avg_ns / 1e3, "launches_timed": k_calls,
+                "timed": "one pair of HIP events on the compute stream around back-to-back launches on every resident layer's own weights "
+                         "(launch gaps included); agrees with the kernel trace's average inside iterations",
+                "inside_iterations": {"avg_launch_us": in_avg_ns / 1e3, "launches": in_calls,
+                                      "GBps": alg_bytes / (in_avg_ns * 1e-9) / 1e9 if in_avg_ns > 0 else None,
+                                      "note": "each launch bracketed by its own start/stop events, which add a few microseconds"}}
+    log(f"[bench] ffn_up back to back {k_avg_ns / 1e3:.1f} us = {achieved / 1e9:.0f} GB/s ({k_calls} launches); "
+        f"inside iterations, bracketed {in_avg_ns / 1e3:.1f} us")
     # whole-step HBM roofline: every weight and every cached K/V element is read once per step
     step_bytes = L * (w_layer + seq_prof * B * kvtok)
     # prefill: dense contractions.  2 flop per weight element per token, plus causal attention
