@@ -18,6 +18,8 @@
 //    and token rows in that XCD's L2.
 //  * gemm_tile_kernel -- any N % 16 == 0, K % 32 == 0: 128 x 128 per workgroup, both
 //    operands read directly from global memory.
+#include <algorithm>
+
 #include "kernels.h"
 #include "common.h"
 
@@ -124,10 +126,44 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
 // ---------------------------------------------------------------------------------
 // fast path
 // ---------------------------------------------------------------------------------
+// Workgroup id -> output tile, XCD-aware.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs, each
+// with its own L2.  An XCD gets a contiguous band of NT/8 feature tiles and walks it in groups of CB feature tiles:
+// inside a group, token tile by token tile.  The ~32-64 workgroups an XCD runs at once are then about 32/CB token
+// tiles x CB feature tiles: the CB workgroups of a token tile share its activations in that L2, and the weights of
+// the 8 groups in progress (8 x CB x 256 x K x 2 bytes, chosen to be at most half of the 256 MB memory-side cache)
+// stay in that cache for all the token tiles, instead of being streamed from HBM once per token tile (what a group as
+// wide as the whole band does when the band's weights exceed the cache: 57344 x 8192 re-read 683 times at 131072 rows).
+__device__ __forceinline__ void tile_of(int id, int NT, int TT, int CB, int& tn, int& tt) {
+  if (NT % 8 == 0) {
+    const int xcd = id & 7, j = id >> 3, band = NT >> 3;
+    const int per_group = TT * CB;               // CB divides band
+    const int gi = j / per_group, r = j % per_group;
+    tt = r / CB;
+    tn = xcd * band + gi * CB + r % CB;
+  } else {
+    tn = id % NT;
+    tt = id / NT;
+  }
+}
+
+// Feature tiles per group for tile_of: the largest divisor of the band whose 8 groups' weights fit half the memory-side
+// cache, but two where the band allows it (two feature tiles per token tile halve the activation reads, which pays even
+// when the weights overflow: 8192 x 28672 at 65536 rows, 1.04 -> 1.10 PFLOP/s).  Measured at 65536 rows, 57344 x 8192
+// (band 28): whole band 0.905, groups of 7 1.08, of 4 1.14, of 2 1.12, of 1 1.09 PFLOP/s.
+static int tile_group(int NT, int K) {
+  if (NT % 8) return 1;
+  const int band = NT / 8;
+  const long most = std::max(2l, (128l << 20) / (8l * 256 * K * 2));
+  int cb = 1;
+  for (int d = 1; d <= band; ++d)
+    if (band % d == 0 && d <= most) cb = d;
+  return cb;
+}
+
 template <class T, int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
-    void* __restrict__ out, int M, int N, int K, int NT, int TT) {
+    void* __restrict__ out, int M, int N, int K, int NT, int TT, int CB) {
   constexpr int BM = 128, BK = 64;
   __shared__ __attribute__((aligned(16))) uint16_t xs[2][BM / 16][BK / 32][64][8];   // 2 x 16 KiB
 
@@ -141,17 +177,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
   // tiles for that band, so that the ~32-64 workgroups it runs at once share weights
   // (same band) and activations (same token tile) in its L2.
   int tn, tt;
-  {
-    const int id = blockIdx.x;
-    if (NT % 8 == 0) {
-      const int xcd = id & 7, j = id >> 3, band = NT >> 3;
-      tn = xcd * band + j % band;
-      tt = j / band;
-    } else {
-      tn = id % NT;
-      tt = id / NT;
-    }
-  }
+  tile_of(blockIdx.x, NT, TT, CB, tn, tt);
   const int t0 = tt * BM;
   const int nb0 = tn * 16 + wave * 4;                      // first of this wavefront's 4 feature blocks
 
@@ -372,7 +398,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <class T, int EPI, int TI>   // TI: 16-token tiles per workgroup
 __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
-    void* __restrict__ out, int M, int N, int K, int NT, int TT) {
+    void* __restrict__ out, int M, int N, int K, int NT, int TT, int CB) {
   constexpr int BM = TI * 16;             // tokens per workgroup
   constexpr int XT = TI / 4;              // token tiles each wavefront stages per k step
   constexpr int FJ = 4;                   // 16-feature blocks per wavefront
@@ -387,23 +413,14 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
   const int S = K >> 5;                      // k steps
 
   int tn, tt;                                // XCD-aware numbering, as in gemm_tile_lds_kernel
-  {
-    const int id = blockIdx.x;
-    if (NT % 8 == 0) {
-      const int xcd = id & 7, j = id >> 3, band = NT >> 3;
-      tn = xcd * band + j % band;
-      tt = j / band;
-    } else {
-      tn = id % NT;
-      tt = id / NT;
-    }
-  }
+  tile_of(blockIdx.x, NT, TT, CB, tn, tt);
   // All tiles take the same time, so without help every CU would reach its epilogue (a burst of stores, for the
   // residual epilogue a read-modify-write of 384 KiB) at the same moment, again and again, and the memory system
   // would alternate between idle and overrun.  The first workgroup of each CU therefore starts up to three
   // quarters of a tile late; later workgroups inherit the offset because a CU holds one workgroup at a time.
   if (blockIdx.x < kBigTileFirstWave) {
-    const int quarters = (blockIdx.x >> 3) & 3;          // consecutive ids go to different XCDs: vary within an XCD
+    const int quarters = ((blockIdx.x >> 3) / CB) & 3;   // consecutive ids go to different XCDs: vary within an XCD, by
+                                                         // token tile, so that the CB workgroups sharing one start together
     const int naps = quarters * (S / 28 + 1);            // one nap = 127 * 64 clocks; a tile is ~1150 clocks per k step + epilogue
     for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
   }
@@ -628,20 +645,20 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
   constexpr int TI = kBigTileTokenTiles;
   if (N % 256 == 0 && K % (32 * kBigTileRing) == 0 &&
       (int64_t)(N / 256) * ((M + TI * 16 - 1) / (TI * 16)) >= kBigTileMinTiles) {
-    const int NT = N / 256, TT = (M + TI * 16 - 1) / (TI * 16);
+    const int NT = N / 256, TT = (M + TI * 16 - 1) / (TI * 16), CB = tile_group(NT, K);
     dim3 grid(NT * TT), block(256);
     switch (epi) {
       case EPI_STORE16:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_STORE16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_STORE16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
         break;
       case EPI_GELU16:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_GELU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_GELU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
         break;
       case EPI_RESID32:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_RESID32, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_RESID32, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
         break;
       case EPI_SWIGLU16:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_SWIGLU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_SWIGLU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
         break;
       default:
         return hipErrorInvalidValue;
@@ -649,20 +666,20 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
     return hipGetLastError();
   }
   if (N % 256 == 0 && K % 64 == 0) {
-    const int NT = N / 256, TT = (M + 127) / 128;
+    const int NT = N / 256, TT = (M + 127) / 128, CB = tile_group(NT, K);
     dim3 grid(NT * TT), block(256);
     switch (epi) {
       case EPI_STORE16:
-        SN_LAUNCH((gemm_tile_lds_kernel<T, EPI_STORE16>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        SN_LAUNCH((gemm_tile_lds_kernel<T, EPI_STORE16>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
         break;
       case EPI_GELU16:
-        SN_LAUNCH((gemm_tile_lds_kernel<T, EPI_GELU16>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        SN_LAUNCH((gemm_tile_lds_kernel<T, EPI_GELU16>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
         break;
       case EPI_RESID32:
-        SN_LAUNCH((gemm_tile_lds_kernel<T, EPI_RESID32>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        SN_LAUNCH((gemm_tile_lds_kernel<T, EPI_RESID32>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
         break;
       case EPI_SWIGLU16:
-        SN_LAUNCH((gemm_tile_lds_kernel<T, EPI_SWIGLU16>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT);
+        SN_LAUNCH((gemm_tile_lds_kernel<T, EPI_SWIGLU16>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
         break;
       default:
         return hipErrorInvalidValue;
