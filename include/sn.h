@@ -52,7 +52,9 @@ typedef struct {
   int32_t norm;       /* SN_NORM_* : LayerNorm (gain, shift) or RMSNorm (gain)            */
   int32_t rope;       /* 1: rotary embedding on q,k (pairs i, i+head_dim/2)               */
   int32_t has_bias;   /* 1: every projection has a bias vector                            */
-  int32_t dtype;      /* SN_F16 / SN_BF16: storage of weights, KV cache, hidden in/out    */
+  int32_t dtype;      /* SN_F16 / SN_BF16: type of the caller's weights and hidden in/out.  The library
+                         computes in float16 either way (bfloat16 weights are stored as the equal
+                         float16 value; the KV cache and all hand-offs are float16)          */
   float norm_eps, rope_theta;
   int32_t max_batch;  /* most sequences in one iteration                                   */
   int32_t max_seq;    /* sum of per-sequence KV capacities may not exceed max_batch*max_seq*/
@@ -89,6 +91,12 @@ typedef struct {
   int32_t kernel_calls[8];
   int32_t n_preissued;      /* of this iteration's loads, how many had been issued during the
                                previous iteration (SN_SCHED_CONTINUOUS)                      */
+  int32_t nonfinite;        /* 1: some hidden state of this iteration's output is inf or NaN.
+                               All arithmetic runs in float16 with fp32 accumulation (bfloat16
+                               models too: their weights are converted at load), activations
+                               pass between kernels in float16, so a value beyond +-65504
+                               overflows there; it then reaches the fp32 residual stream and
+                               this flag.  0 for a healthy model.                            */
 } sn_step_stats;
 
 /* Kernel classes for sn_step_stats.kernel_ns / sn_set_timing(level 2). */

@@ -14,15 +14,24 @@ namespace sn {
   } while (0)
 
 // ---------------------------------------------------------------------------------
+// flag (may be null): cleared here at the start of an iteration, set by the cast at its end when a hidden state is
+// not finite -- a 16-bit hand-off that overflowed (|v| > 65504 in float16) reaches the fp32 residual stream as
+// inf or NaN and stays there, so this one check at the end covers every hand-off of the iteration.
 template <class T>
-__global__ void cast_in_kernel(const uint16_t* __restrict__ in, float* __restrict__ x, size_t n) {
+__global__ void cast_in_kernel(const uint16_t* __restrict__ in, float* __restrict__ x, size_t n, int32_t* __restrict__ flag) {
+  if (flag && blockIdx.x == 0 && threadIdx.x == 0) *flag = 0;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
     x[i] = to_f32<T>(in[i]);
 }
 template <class T>
-__global__ void cast_out_kernel(const float* __restrict__ x, uint16_t* __restrict__ out, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
-    out[i] = from_f32<T>(x[i]);
+__global__ void cast_out_kernel(const float* __restrict__ x, uint16_t* __restrict__ out, size_t n, int32_t* __restrict__ flag) {
+  bool bad = false;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    const float v = x[i];
+    bad |= !(fabsf(v) <= 3.0e38f);
+    out[i] = from_f32<T>(v);
+  }
+  if (flag && bad) *flag = 1;
 }
 // Values in [-1, 1) from an integer hash of the element index (generated profiler inputs).
 template <class T>
@@ -86,16 +95,16 @@ static inline int grid_for(size_t n, int block) {
   return (int)(g < 1 ? 1 : (g > 4096 ? 4096 : g));
 }
 
-hipError_t launch_cast_in(int dtype, const void* in16, float* x32, size_t n, hipStream_t st) {
+hipError_t launch_cast_in(int dtype, const void* in16, float* x32, size_t n, hipStream_t st, int32_t* flag) {
   if (n == 0) return hipSuccess;
   SN_DISPATCH_T(dtype, SN_LAUNCH(cast_in_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
-                                          (const uint16_t*)in16, x32, n));
+                                          (const uint16_t*)in16, x32, n, flag));
   return hipGetLastError();
 }
-hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, hipStream_t st) {
+hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, hipStream_t st, int32_t* flag) {
   if (n == 0) return hipSuccess;
   SN_DISPATCH_T(dtype, SN_LAUNCH(cast_out_kernel<T>, dim3(grid_for(n, 256)), dim3(256), 0, st,
-                                          x32, (uint16_t*)out16, n));
+                                          x32, (uint16_t*)out16, n, flag));
   return hipGetLastError();
 }
 hipError_t launch_fill_hash(int dtype, void* out16, size_t n, uint32_t seed, hipStream_t st) {
@@ -268,28 +277,33 @@ hipError_t launch_norm(int dtype, int is_ln, const float* x32, const void* gain,
 template <class T, class TB>
 __global__ __launch_bounds__(256) void cast_out_fold_kernel(float* __restrict__ x, uint16_t* __restrict__ out, int Tn,
                                                             int h, const float* __restrict__ part, int nsplit,
-                                                            const uint16_t* __restrict__ fbias) {
+                                                            const uint16_t* __restrict__ fbias, int32_t* __restrict__ flag) {
   const size_t nv = (size_t)Tn * h / 4;
+  bool bad = false;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
     f32x4 v = reinterpret_cast<f32x4*>(x)[i];
     v = folded<TB>(v, part, nsplit, (size_t)Tn * h, i * 4, fbias, (int)((i * 4) % h));
     reinterpret_cast<f32x4*>(x)[i] = v;
     u16x4 o;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = from_f32<T>(v[e]);
+    for (int e = 0; e < 4; ++e) {
+      bad |= !(fabsf(v[e]) <= 3.0e38f);
+      o[e] = from_f32<T>(v[e]);
+    }
     reinterpret_cast<u16x4*>(out)[i] = o;
   }
+  if (flag && bad) *flag = 1;
 }
 
 hipError_t launch_cast_out_fold(int dtype, int bias_dtype, float* x32, void* out16, int Tn, int h, const Fold& fold,
-                                hipStream_t st) {
+                                hipStream_t st, int32_t* flag) {
   if (Tn == 0) return hipSuccess;
   if (h % 4) return hipErrorInvalidValue;
   const size_t nv = (size_t)Tn * h / 4;
   const dim3 grid(grid_for(nv, 256)), block(256);
   const uint16_t* fb = (const uint16_t*)fold.bias;
 #define SN_COF(TT, TB) \
-  SN_LAUNCH((cast_out_fold_kernel<TT, TB>), grid, block, 0, st, x32, (uint16_t*)out16, Tn, h, fold.part, fold.nsplit, fb)
+  SN_LAUNCH((cast_out_fold_kernel<TT, TB>), grid, block, 0, st, x32, (uint16_t*)out16, Tn, h, fold.part, fold.nsplit, fb, flag)
   if (dtype == 0 && bias_dtype == 0) SN_COF(F16, F16);
   else if (dtype == 1 && bias_dtype == 0) SN_COF(BF16, F16);
   else if (dtype == 1 && bias_dtype == 1) SN_COF(BF16, BF16);

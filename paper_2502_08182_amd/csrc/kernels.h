@@ -48,11 +48,12 @@ struct StepIndex {
   const int32_t* tile_q0;     // [n_qtiles] first new-token index of the tile inside its sequence
 };
 
-hipError_t launch_cast_in(int dtype, const void* in16, float* x32, size_t n, hipStream_t st);
-hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, hipStream_t st);
+// flag (device int32, may be null): launch_cast_in clears it, the output casts set it to 1 when a hidden state is inf or NaN.
+hipError_t launch_cast_in(int dtype, const void* in16, float* x32, size_t n, hipStream_t st, int32_t* flag = nullptr);
+hipError_t launch_cast_out(int dtype, const float* x32, void* out16, size_t n, hipStream_t st, int32_t* flag = nullptr);
 // Same after folding pending partial sums into x32 (written back); bias_dtype: type of fold.bias.
 hipError_t launch_cast_out_fold(int dtype, int bias_dtype, float* x32, void* out16, int T, int h, const Fold& fold,
-                                hipStream_t st);
+                                hipStream_t st, int32_t* flag = nullptr);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 // Debug aids: fill `bytes` (multiple of 16) with a 32-bit pattern; keep a stream busy for `ticks` wall-clock
 // periods (bounded by max_trips sleeps of a few microseconds each, so the kernel always ends).

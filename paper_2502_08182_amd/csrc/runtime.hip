@@ -130,6 +130,7 @@ struct sn_ctx {
   float* part = nullptr;
   float* part32 = nullptr;       // split-K partial sums of the decode residual projections
   float* inv_freq = nullptr;
+  int32_t* flag_dev = nullptr;   // set by the final cast of an iteration when a hidden state is not finite
   int32_t* meta_dev = nullptr;
   size_t meta_ints = 0;
   int32_t* meta_host[kMetaRing] = {};
@@ -414,7 +415,7 @@ extern "C" void sn_destroy(sn_ctx* c) {
   for (auto& s : c->slot_kv)
     if (s) (void)hipFree(s);
   if (c->stage_w) (void)hipHostFree(c->stage_w);
-  void* dev[] = {c->x32, c->u16, c->qkv16, c->attn16, c->act16, c->part, c->part32, c->inv_freq, c->meta_dev};
+  void* dev[] = {c->x32, c->u16, c->qkv16, c->attn16, c->act16, c->part, c->part32, c->inv_freq, c->meta_dev, c->flag_dev};
   for (void* p : dev)
     if (p) (void)hipFree(p);
   for (int i = 0; i < kMetaRing; ++i) {
@@ -479,6 +480,8 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   SN_HIP(c, hipMalloc(&c->part32, b_part32));
   SN_HIP(c, hipMalloc(&c->meta_dev, b_meta));
   SN_HIP(c, hipMalloc(&c->inv_freq, b_freq));
+  SN_HIP(c, hipMalloc(&c->flag_dev, 256));
+  SN_HIP(c, hipMemset(c->flag_dev, 0, 256));
   {
     std::vector<float> f(s.head_dim / 2);
     for (int i = 0; i < s.head_dim / 2; ++i)
@@ -997,7 +1000,7 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
   const int par = c->par;
 
   SN_HIP(c, hipEventRecord(c->ev_iter_start, c->compute));
-  SN_HIP(c, launch_cast_in(s.dtype, bt->hidden_in, c->x32, (size_t)T * s.hidden, c->compute));
+  SN_HIP(c, launch_cast_in(s.dtype, bt->hidden_in, c->x32, (size_t)T * s.hidden, c->compute, c->flag_dev));
   Fold pending;
 
   for (int l = 0; l < L; ++l) {
@@ -1075,9 +1078,9 @@ extern "C" int sn_step(sn_ctx* c, const sn_batch* bt, sn_kv* kv, void* hidden_ou
   }
   SN_HIP(c, hipEventRecord(c->ev_layer[L], c->compute));
   if (pending.nsplit > 0)
-    SN_HIP(c, launch_cast_out_fold(s.dtype, SN_F16, c->x32, hidden_out, T, s.hidden, pending, c->compute));
+    SN_HIP(c, launch_cast_out_fold(s.dtype, SN_F16, c->x32, hidden_out, T, s.hidden, pending, c->compute, c->flag_dev));
   else
-    SN_HIP(c, launch_cast_out(s.dtype, c->x32, hidden_out, (size_t)T * s.hidden, c->compute));
+    SN_HIP(c, launch_cast_out(s.dtype, c->x32, hidden_out, (size_t)T * s.hidden, c->compute, c->flag_dev));
   SN_HIP(c, hipEventRecord(c->ev_iter_end, c->compute));
 
   for (int b = 0; b < B; ++b) {
@@ -1133,6 +1136,7 @@ extern "C" int sn_get_stats(sn_ctx* c, sn_step_stats* out) {
   out->h2d_bytes = c->last_h2d_bytes;
   out->n_preissued = c->last_preissued;
   out->d2h_bytes = c->last_d2h_bytes;
+  SN_HIP(c, hipMemcpy(&out->nonfinite, c->flag_dev, sizeof(int32_t), hipMemcpyDeviceToHost));
   for (int l = 0; l < L; ++l) {
     const LayerState& ls = c->layers[l];
     if (!ls.offloaded) continue;

@@ -57,7 +57,8 @@ class sn_step_stats(C.Structure):
     _fields_ = [("iter_ns", C.c_int64), ("stall_ns", C.c_int64), ("h2d_ns", C.c_int64), ("h2d_bytes", C.c_int64),
                 ("d2h_ns", C.c_int64), ("d2h_bytes", C.c_int64), ("hidden_fraction", C.c_double),
                 ("interval", C.c_int32), ("n_offloaded", C.c_int32), ("resident_bytes", C.c_uint64),
-                ("kernel_ns", C.c_int64 * 8), ("kernel_calls", C.c_int32 * 8), ("n_preissued", C.c_int32)]
+                ("kernel_ns", C.c_int64 * 8), ("kernel_calls", C.c_int32 * 8), ("n_preissued", C.c_int32),
+                ("nonfinite", C.c_int32)]
 
     def as_dict(self) -> dict:
         d = {n: getattr(self, n) for n, _ in self._fields_ if n not in ("kernel_ns", "kernel_calls")}

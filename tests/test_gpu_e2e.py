@@ -520,6 +520,26 @@ def test_budget_and_call_order_errors():
         sn.sn_destroy(ctx)
 
 
+def test_float16_overflow_of_a_hand_off_is_reported(c1):
+    """Activations pass between the kernels in float16: a value beyond 65504 overflows there.  The iteration's
+    statistics say so (it reaches the fp32 residual stream as inf / NaN, which the final cast checks); a healthy
+    model reports nothing."""
+    w, layers, prompt, table, *_ = c1
+    hot = [dict(t) for t in layers]
+    big = synth.widen(layers[0]["wu"], "f16") * 2.0 ** 16          # |w| ~ 1300: representable, products are not
+    hot[0]["wu"] = synth.to_bits(big, "f16")
+    for tensors, want in ((layers, 0), (hot, 1)):
+        with Session(w.shape, w.batch, w.max_seq) as se:
+            se.load_synthetic_weights(layers=tensors)
+            se.place(2)
+            se.kv_reset([p + 2 for p in w.prompt_lens])
+            out = se.step(list(w.prompt_lens), True, prompt)
+            assert se.stats()["nonfinite"] == want
+            assert np.isfinite(synth.widen(out, "f16")).all() == (want == 0)
+            se.step([1] * w.batch, False, table[0])
+            assert se.stats()["nonfinite"] == want
+
+
 def test_stall_and_hidden_fraction_are_reported(c1):
     w, layers, prompt, table, *_ = c1
     with Session(w.shape, w.batch, w.max_seq) as se:

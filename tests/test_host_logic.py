@@ -132,7 +132,7 @@ def test_tiny_bf16_weights_round_to_float16_subnormals_far_below_the_bar():
 
 def test_struct_sizes_match_header():
     assert ctypes.sizeof(sn.sn_model_shape) == 16 * 4
-    assert ctypes.sizeof(sn.sn_step_stats) == 6 * 8 + 8 + 2 * 4 + 8 + 8 * 8 + 8 * 4 + 8     # n_preissued and tail padding
+    assert ctypes.sizeof(sn.sn_step_stats) == 6 * 8 + 8 + 2 * 4 + 8 + 8 * 8 + 8 * 4 + 8     # n_preissued, nonfinite
 
 
 def test_placement_matches_oracle_and_fig7():
