@@ -255,7 +255,8 @@ def main():
     if a.slo_points is None:
         a.slo_points = "3,5,10" if w.name == "c2" else ",".join(str(f) for f in w.slo_factors if f != a.slo_factor)
     p_mean = int(round(float(np.mean(w.prompt_lens))))      # ragged prompts: profile at the mean length
-    max_seq = max(w.prompt_lens) + K + W + 2
+    # KV capacity: the context holds max_batch * max_seq tokens per layer in all; ragged prompts need their sum, not B x the longest
+    max_seq = -(-sum(p + K + W + 2 for p in w.prompt_lens) // B)
     t_start = time.time()
     se = Session(s, B, max_seq, hbm_budget=w.hbm_budget)
     sn.sn_set_budget_enforce(se.ctx, False)     # over-cap intervals are run and labelled, not refused
