@@ -65,6 +65,9 @@ def parse():
                          "verified (default: 3,5,10 for c2, the workload's other SLO factors otherwise)")
     ap.add_argument("--prefill-slo-points", default="1.2,1.5,2",
                     help="with --full: TTFT SLO factors (x all-resident prefill) at which the prefill phase picks its own interval")
+    ap.add_argument("--host-limit-gb", type=float, default=24.0,
+                    help="--full legs keep at most this much pinned host memory: sweep points beyond it are skipped, "
+                         "prefill picks are moved to the first interval within it")
     ap.add_argument("--contention", type=float, default=0.0, metavar="FRACTION",
                     help="also run the prefill phase while a competing host-to-device copy stream takes this fraction "
                          "of the link (0: off): at the interval picked without contention, then at the interval the "
@@ -528,7 +531,12 @@ def main():
     # ---- interval sweep (reported, over-cap points labelled) ------------------------------------
     if a.full:
         sweep = []
+        state_bytes = w_layer + seq_prof * B * kvtok
         for N in list(w.intervals) + [L]:
+            if (L // N) * state_bytes > a.host_limit_gb * 1e9:
+                log(f"[bench] sweep N={N}: skipped, {(L // N) * state_bytes / 1e9:.0f} GB of pinned host memory (--host-limit-gb)")
+                continue
+            log(f"[bench] sweep N={N}: placing {L // N} layers on the host")
             se.place(N)
             sst, swall = rig.decode(max(4, min(K, 8)), 1)
             row = {"interval": N, **leg_summary(sst, swall, slo_ns, B)}
@@ -559,8 +567,12 @@ def main():
                 n_f = sn.sn_pick_interval_from_times_sched(tcp, txp, int(slo_f * (1.0 - a.prefill_guard)), L + 1, sched)
             except sn.SnError:
                 n_f = L + 1
+            # no more pinned host memory than --host-limit-gb (weights of the offloaded layers)
+            while n_f <= L and (L // n_f) * sn.sn_layer_blob_bytes(se.cshape) > a.host_limit_gb * 1e9:
+                n_f += 1
             first = int(n_f)
             for _ in range(4):
+                log(f"[bench] prefill SLO {f}x{label}: running N={n_f}")
                 se.place(n_f)
                 pst = run_prefill(se, sn, w, x_pre, y_pre, 3)[1:]
                 pit = np.array([d["iter_ns"] for d in pst], dtype=np.float64)

@@ -135,6 +135,18 @@ int sn_k_attn_decode_append(int32_t dtype, const void* qkv16, void* kv, void* mi
                             int32_t Hkv, int32_t d, int32_t S, int32_t max_len, int32_t packed_out,
                             void* stream);
 
+/* sn_k_attn_decode_append with the step's q, k and v given as split-K partial planes of the QKV
+ * projection (what sn_step runs at 9..64 rows, where that projection is split over K like the residual
+ * projections; steps a5-a7): qkv_part [splits][plane_rows][(Hq + 2 Hkv) d] device fp32, 1 <= splits <= 8,
+ * plane_rows >= B, the projection's bias already in plane 0 (sn_k_gemm_splitk writes exactly this).  The
+ * kernel adds the planes in ascending order, rounds the sum to the 16-bit type -- the value the unsplit
+ * projection stores -- and proceeds as sn_k_attn_decode_append.  qkv_part is not modified. */
+int sn_k_attn_decode_append_planes(int32_t dtype, const float* qkv_part, int32_t splits, int32_t plane_rows,
+                                   void* kv, void* mirror, const float* inv_freq, int32_t rope,
+                                   const int32_t* len_before, const int32_t* kv_off, const int32_t* cap,
+                                   void* out16, float* part, int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
+                                   int32_t S, int32_t max_len, int32_t packed_out, void* stream);
+
 #define SN_K_PREFILL_QTILE 128
 /* Causal attention of each sequence's n_new tokens over len_before+n_new keys.
  * out16 [T][Hq*d]. */

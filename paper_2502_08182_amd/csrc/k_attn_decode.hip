@@ -23,16 +23,51 @@ constexpr float kNegBig = -1.0e30f;
 // range that contains the new position stores k and v into the KV slice (and its host
 // mirror, when the layer's KV lives in host memory) and takes that key from LDS instead
 // of from the cache, so no workgroup ever loads the row that is being written.
+//
+// When the QKV projection ran split over K (few output features: the only way to give every
+// compute unit a workgroup), its output arrives as fp32 partial planes instead: qpart
+// [nsplit][rows][(Hq + 2 Hkv) d], bias already in plane 0.  The planes are summed here in
+// ascending order and the sum is rounded to the 16-bit type first -- exactly the value the
+// unsplit projection would have stored -- so everything after this point is unchanged.
+struct QkvPlanes {
+  const float* part;     // null: read the 16-bit row
+  int nsplit;
+  int rows;              // rows of one plane
+};
 template <class T, int D, int G>
-__device__ __forceinline__ void stage_new_token(uint16_t (*stage)[D], const uint16_t* __restrict__ qkv_row, int hk,
-                                                int Hq, int Hkv, int pos, const float* __restrict__ inv_freq,
-                                                int rope) {
+__device__ __forceinline__ void stage_new_token(uint16_t (*stage)[D], const uint16_t* __restrict__ qkv_row,
+                                                const QkvPlanes qp, int seq, int hk, int Hq, int Hkv, int pos,
+                                                const float* __restrict__ inv_freq, int rope) {
   constexpr int half = D / 2;
+  const int ld = (Hq + 2 * Hkv) * D;
   for (int t = threadIdx.x; t < (G + 2) * half; t += blockDim.x) {
     const int hs = t / half, i = t % half;
     const int head = hs < G ? hk * G + hs : hs == G ? Hq + hk : Hq + Hkv + hk;
-    const uint16_t* src = qkv_row + (size_t)head * D;
-    float a = to_f32<T>(src[i]), b = to_f32<T>(src[i + half]);
+    float a, b;
+    if (qp.part) {
+      const float* src = qp.part + (size_t)seq * ld + (size_t)head * D;
+      const size_t plane = (size_t)qp.rows * ld;
+      // all planes requested at once (absent ones read as zero), then added in ascending order
+      float va[kMaxSplits], vb[kMaxSplits];
+#pragma unroll
+      for (int sp = 0; sp < kMaxSplits; ++sp) {
+        const bool on = sp < qp.nsplit;
+        va[sp] = on ? src[sp * plane + i] : 0.f;
+        vb[sp] = on ? src[sp * plane + i + half] : 0.f;
+      }
+      float sa = va[0], sb = vb[0];
+#pragma unroll
+      for (int sp = 1; sp < kMaxSplits; ++sp) {
+        sa += va[sp];
+        sb += vb[sp];
+      }
+      a = to_f32<T>(from_f32<T>(sa));
+      b = to_f32<T>(from_f32<T>(sb));
+    } else {
+      const uint16_t* src = qkv_row + (size_t)head * D;
+      a = to_f32<T>(src[i]);
+      b = to_f32<T>(src[i + half]);
+    }
     if (rope && hs <= G) {
       float sn_, cs_;
       sincosf((float)pos * inv_freq[i], &sn_, &cs_);
@@ -79,7 +114,7 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
     const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ out,
     float* __restrict__ part, int Hq, int Hkv, int S, int packed, uint16_t* __restrict__ kvw,
-    uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int rope) {
+    uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int rope, QkvPlanes qp) {
   constexpr int LPK = D / 8;          // lanes per key row
   constexpr int KPW = 64 / LPK;       // keys per wavefront load
   __shared__ float lds[NW][G][LPK][10];
@@ -103,7 +138,7 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_kernel(
   const int pos = len - 1;            // position of this step's token
   u16x8 knew = {0, 0, 0, 0, 0, 0, 0, 0}, vnew = {0, 0, 0, 0, 0, 0, 0, 0};
   if (FA) {
-    stage_new_token<T, D, G>(stage, qkv + (size_t)b * qkv_ld, hk, Hq, Hkv, pos, inv_freq, rope);
+    stage_new_token<T, D, G>(stage, qkv + (size_t)b * qkv_ld, qp, b, hk, Hq, Hkv, pos, inv_freq, rope);
     __syncthreads();
     if (pos >= j0 && pos < j1)
       store_new_token<D, G>(stage, kvw, mirror, k_base + (size_t)pos * D, k_base + ((size_t)cp + pos) * D);
@@ -250,7 +285,7 @@ __global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
     const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
     const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ out,
     float* __restrict__ part, int Hq, int Hkv, int S, int packed, uint16_t* __restrict__ kvw,
-    uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int rope) {
+    uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int rope, QkvPlanes qp) {
   constexpr int LD = 40, DK = D / 32, DT = D / 16;
   constexpr int kVtWave = D * LD;                        // uint16 elements of one wavefront's V^T tile
   constexpr int kMrgLane = 2 + DT * 4;                   // floats a lane contributes to the merge
@@ -271,7 +306,7 @@ __global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
   const size_t k_base = (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D;
   const int pos = len - 1;            // position of this step's token
   if (FA) {
-    stage_new_token<T, D, G>(stage, qkv + (size_t)b * qkv_ld, hk, Hq, Hkv, pos, inv_freq, rope);
+    stage_new_token<T, D, G>(stage, qkv + (size_t)b * qkv_ld, qp, b, hk, Hq, Hkv, pos, inv_freq, rope);
     __syncthreads();
     if (pos >= j0 && pos < j1)
       store_new_token<D, G>(stage, kvw, mirror, k_base + (size_t)pos * D, k_base + ((size_t)cp + pos) * D);
@@ -459,12 +494,13 @@ static hipError_t launch_d(const uint16_t* qkv, const uint16_t* kv, const StepIn
                            float* part, int B, int Hq, int Hkv, int S, int packed, const AttnAppend& ap,
                            hipStream_t st) {
   const int G = Hq / Hkv;
+  const QkvPlanes qp{FA ? ap.qkv_part : nullptr, ap.qkv_nsplit, ap.qkv_rows};
 #define SN_LAUNCH_G(GV, NWV, UKV)                                                                                 \
   SN_LAUNCH((attn_decode_kernel<T, D, GV, NWV, UKV, FA>), dim3(B * Hkv, S), dim3(NWV * 64), 0, st, qkv, kv,       \
-            ix.len_before, ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope)
+            ix.len_before, ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope, qp)
 #define SN_LAUNCH_GQA(GV)                                                                                         \
   SN_LAUNCH((attn_decode_gqa_kernel<T, D, GV, FA>), dim3(B * Hkv, S), dim3(256), 0, st, qkv, kv, ix.len_before,   \
-            ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope)
+            ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope, qp)
   switch (G) {
     case 1: SN_LAUNCH_G(1, 16, 2); break;
     case 2: SN_LAUNCH_G(2, 16, 2); break;
@@ -488,6 +524,9 @@ hipError_t launch_attn_decode(int dtype, const void* qkv16, const void* kv, cons
   const uint16_t* k = (const uint16_t*)kv;
   uint16_t* o = (uint16_t*)out16;
   if (append && (!append->kv || (append->rope && !append->inv_freq))) return hipErrorInvalidValue;
+  if (append && append->qkv_part && (append->qkv_nsplit < 1 || append->qkv_nsplit > kMaxSplits || append->qkv_rows < B))
+    return hipErrorInvalidValue;
+  if (!q && !(append && append->qkv_part)) return hipErrorInvalidValue;
   const AttnAppend ap = append ? *append : AttnAppend{};
 #define SN_DISPATCH(TT, DD)                                                                        \
   return append ? launch_d<TT, DD, true>(q, k, ix, o, part, B, Hq, Hkv, S, packed, ap, st)         \

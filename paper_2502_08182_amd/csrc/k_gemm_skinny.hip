@@ -290,7 +290,7 @@ template <class T, int MT, int C, int EPI>
 __global__ __launch_bounds__(512) void gemm_wide_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
     void* __restrict__ out, int M, int N, int K, int opacked, int NWN, int plane_rows) {
-  constexpr int KC = 2;                                // k-blocks per step
+  constexpr int KC = 2;                                // k-blocks per step (4 and 8 measured no better at one row tile)
   constexpr int TILES = KC * MT;                       // activation tiles (1 KiB) per step and K range
   constexpr int R = (TILES + 3) / 4;                   // 16-byte pieces per lane and step (NWN >= 4)
   extern __shared__ __attribute__((aligned(16))) float red[];   // stages during the walk, partial tiles afterwards
@@ -464,6 +464,51 @@ static WidePlan plan_wide(int nb, int KB, int only_c = 0) {
   return best;
 }
 
+// Launch shape of a split-K projection (fp32 partial planes) at 9..64 rows, from timings of every legal
+// shape on MI355X (the residual and QKV shapes of the 13B-, 30B- and 70B-shaped layers at 32 and 64 rows): one
+// wavefront per column (no K split inside the workgroup), the splits across workgroups provide the
+// parallelism, at most 256 workgroups -- one per compute unit; a second round costs more than anything else --
+// and at least 8 feature blocks per workgroup (activations fetched once per 8 weight tiles).
+//  * K up to 16384 (start-up and drain are a large share of a 12-50 us launch): as many workgroups as
+//    possible, then as few planes as possible (64 rows, 10240 x 8192: 5 columns x 2 blocks, 4 splits, 256
+//    workgroups 30 us where 160 workgroups of the unsplit kernel took 46; 8192 x 8192: 26 us against 28;
+//    32 rows, 5120 x 13824: 25 us against 28.5).
+//  * longer K: the stream is chip-bound from ~190 workgroups on; 16 feature blocks per workgroup and the
+//    fewest planes that reach 190 (64 rows, 8192 x 28672: 6 splits, 192 workgroups 81 us; 8 splits, 256
+//    workgroups 86 us; 32 rows, 7168 x 28672: 66 us against 82).
+// splits == 0: no such shape (odd block counts, too few features); the caller falls back to the other kernel.
+struct SplitPlan {
+  int C, nwn, splits;
+};
+static SplitPlan plan_split(int M, int nb, int KB) {
+  SplitPlan best{0, 0, 0};
+  if (M <= 8 || M > 64) return best;
+  const bool long_k = KB > 512;
+  long best_key = -1;
+  for (int C : {4, 2}) {      // equal keys: four blocks per wavefront
+    if (nb % C) continue;
+    const int groups = nb / C;
+    for (int nwn = 4; nwn <= 8; ++nwn) {
+      if (groups % nwn || nwn * C < 8 || nwn * C > 20) continue;
+      for (int sp = 1; sp <= kMaxSplits; ++sp) {
+        const int wgs = groups / nwn * sp;
+        if (wgs > 256 || (sp > 1 && KB / sp < 32)) continue;
+        long key;
+        if (long_k)      // reach 190 workgroups; then 16 blocks per workgroup, few planes, more workgroups
+          key = wgs >= 190 ? 1000000L + (nwn * C == 16 ? 100000L : 0) + (kMaxSplits - sp) * 1000L + wgs : wgs;
+        else             // most workgroups, then fewest planes, then more blocks per workgroup
+          key = wgs * 10000L + (kMaxSplits - sp) * 100L + nwn * C;
+        if (key > best_key) {
+          best_key = key;
+          best = SplitPlan{C, nwn, sp};
+        }
+      }
+    }
+  }
+  if (best.splits && nb / (best.C * best.nwn) * best.splits < 120) return SplitPlan{0, 0, 0};
+  return best;
+}
+
 template <class T, int MT, int C>
 static hipError_t launch_wide(int epi, int ks, int nwn, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out,
                               int M, int N, int K, int splits, int opacked, int plane_rows, hipStream_t st) {
@@ -588,30 +633,39 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
                                                            : static_cast<void*>(static_cast<uint16_t*>(out) + (size_t)64 * ncols);
     return launch_t<T>(epi, W, X2, bias, out2, M - 64, N, K, splits, xpacked, opacked, plane_rows, st);
   }
-  if (M <= 16) {
+  // Up to 8 rows: the burst kernel (the LDS-sharing one measured 5 % slower at K = 4096 and 1-6 % faster at
+  // K = 7168).  9..16 rows: it loads all 16 rows of a tile and slows down (21504 x 7168: 50 -> 57 us), the
+  // LDS-sharing kernel does not (48 us).
+  if (M <= 8 || (M <= 16 && !(xpacked && epi != EPI_RESID32))) {
     if (dual) return launch_mc<T, 1, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
     return launch_mc<T, 1, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
   }
-  if (M <= 32) {
-    if (nb % 2 == 0) return launch_mc<T, 2, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
-    return launch_mc<T, 2, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
-  }
-  if (M > 16 && xpacked && epi != EPI_RESID32) {
-    // 2-4 row tiles, packed activations: the kernel that shares them through LDS, where a launch shape exists
+  if (xpacked && epi != EPI_RESID32) {
+    // 9..64 rows, packed activations: the kernel that shares them through LDS, where a launch shape exists
     WidePlan pl{0, 1, 8};
     bool ok;
     if (epi == EPI_PART32) {
-      // split-K planes: 4 columns of 2 wavefronts, 4 column blocks each, where the feature groups times the
-      // splits fill the chip and every split keeps a long K (64 rows, 8192 x 28672, 8 splits: 87 -> 84 us; other
-      // cuts of this shape -- 2 column blocks, 8 columns, 4 splits -- measured 83..103 us)
+      // split-K planes: the planned shape when the caller asks for the planned number of planes
+      // (gemm_skinny_splits); for any other number, 4 columns of 2 wavefronts, 4 column blocks each, where
+      // the feature groups times the splits fill the chip and every split keeps a long K
+      const SplitPlan sp = plan_split(M, nb, K / 32);
       const int groups = nb / 4;
-      ok = nb % 4 == 0 && groups % 4 == 0 && groups / 4 * splits >= 200 && (K / 32) / splits >= 64;
-      pl = WidePlan{4, 4, 8};
+      if (sp.splits == splits) {
+        ok = true;
+        pl = WidePlan{sp.C, sp.nwn, sp.nwn};
+      } else {
+        ok = nb % 4 == 0 && groups % 4 == 0 && groups / 4 * splits >= 200 && (K / 32) / splits >= 64;
+        pl = WidePlan{4, 4, 8};
+      }
     } else {
       pl = plan_wide(nb, K / 32);
       ok = pl.nwn >= 4;
     }
     if (ok && !(dual && pl.C % 2)) {
+      if (M <= 16) {
+        if (pl.C == 4) return launch_wide<T, 1, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
+        return launch_wide<T, 1, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
+      }
       if (M <= 32) {
         if (pl.C == 4) return launch_wide<T, 2, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
         return launch_wide<T, 2, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
@@ -623,6 +677,14 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
       if (pl.C == 4) return launch_wide<T, 4, 4>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
       return launch_wide<T, 4, 2>(epi, pl.ks, pl.nwn, W, X, bias, out, M, N, K, splits, opacked, plane_rows, st);
     }
+  }
+  if (M <= 16) {
+    if (dual) return launch_mc<T, 1, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+    return launch_mc<T, 1, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+  }
+  if (M <= 32) {
+    if (nb % 2 == 0) return launch_mc<T, 2, 2>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
+    return launch_mc<T, 2, 1>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
   }
   if (M <= 48) {
     if (nb % 4 == 0) return launch_mc<T, 3, 4>(epi, W, X, bias, out, M, N, K, splits, xpacked, opacked, plane_rows, st);
@@ -655,9 +717,21 @@ hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, 
 // the 4-column instance applies (long K, see launch_mc), else as few as give about one
 // workgroup per CU (64 rows, 8192 x 8192: 2 splits 30.7 us, 8 splits 33.5 us).
 int gemm_skinny_splits(int M, int N, int K) {
-  const int C = M <= 16 ? 1 : (M <= 32 || M > 64 ? 2 : 4);
-  const int groups = N / (16 * C);
   const int KB = K / 32;
+  if (M > 64) {
+    // 6 or 8 row tiles: the two-column-block instance with 8 splits where launch_t takes it; every other shape runs
+    // as two passes of up to 64 rows and wants the split of 64 rows (7168 x 7168 at 128 rows: one plane left each
+    // pass with 112 workgroups, 75 us; two planes: 224 workgroups)
+    const int g2 = N / 32;
+    if (N % 32 == 0 && g2 % 4 == 0 && g2 / 4 * 8 >= 200 && KB / 8 >= 64) return 8;
+    return gemm_skinny_splits(64, N, K);
+  }
+  if (M > 8 && N % 16 == 0) {
+    const SplitPlan pl = plan_split(M, N / 16, KB);
+    if (pl.splits) return pl.splits;
+  }
+  const int C = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+  const int groups = N / (16 * C);
   int sp = 1;
   if (M > 32) {
     if (groups % 4 == 0 && groups / 4 * 8 >= 200 && KB / 8 >= 64) return 8;
@@ -671,6 +745,15 @@ int gemm_skinny_splits(int M, int N, int K) {
   if (M <= 16 && groups >= 256 && groups % 256 == 0) return 1;
   while (sp < kMaxSplits && groups * 4 * sp < 4096 && KB / (4 * sp * 2) >= 4) sp *= 2;
   return sp;
+}
+
+// The QKV projection of a decode step at 9..64 rows: N = (Hq + 2 Hkv) d features are 160-1344 blocks, so the
+// 16-bit-epilogue kernels run 120-170 workgroups (64 rows, 10240 x 8192: 46 us = 3.6 TB/s; 21504 x 7168: 78 us;
+// 32 rows, 15360 x 5120: 30 us); split over K with the planned shape they fill the chip (30, 52, 28 us).
+int gemm_qkv_splits(int M, int N, int K) {
+  if (M <= 8 || M > 64 || N % 16 || K % 32) return 0;
+  const SplitPlan pl = plan_split(M, N / 16, K / 32);
+  return pl.splits >= 2 ? pl.splits : 0;
 }
 
 }  // namespace sn

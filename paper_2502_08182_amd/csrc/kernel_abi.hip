@@ -96,6 +96,32 @@ extern "C" int sn_k_attn_decode_append(int32_t dtype, const void* qkv16, void* k
                                   packed_out != 0, &ap));
 }
 
+extern "C" int sn_k_attn_decode_append_planes(int32_t dtype, const float* qkv_part, int32_t splits, int32_t plane_rows,
+                                              void* kv, void* mirror, const float* inv_freq, int32_t rope,
+                                              const int32_t* len_before, const int32_t* kv_off, const int32_t* cap,
+                                              void* out16, float* part, int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
+                                              int32_t S, int32_t max_len, int32_t packed_out, void* stream) {
+  if (bad_dtype(dtype) || !qkv_part || splits < 1 || splits > kMaxSplits || plane_rows < B || !kv || !len_before ||
+      !kv_off || !cap || !out16 || B < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv || (d != 64 && d != 128) || S < 0 || S > 16 ||
+      (rope && !inv_freq))
+    return SN_E_INVAL;
+  if (S == 0) {
+    if (max_len < 1) return SN_E_INVAL;
+    S = attn_decode_splits(B, Hkv, max_len);
+  }
+  if (S > 1 && !part) return SN_E_INVAL;
+  StepIndex ix{};
+  ix.len_before = len_before;
+  ix.kv_off = kv_off;
+  ix.cap = cap;
+  AttnAppend ap{(uint16_t*)kv, (uint16_t*)mirror, inv_freq, rope ? 1 : 0};
+  ap.qkv_part = qkv_part;
+  ap.qkv_nsplit = splits;
+  ap.qkv_rows = plane_rows;
+  return rc_of(launch_attn_decode(dtype, nullptr, kv, ix, out16, part, B, Hq, Hkv, d, S, (hipStream_t)stream,
+                                  packed_out != 0, &ap));
+}
+
 extern "C" int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
                                  const int32_t* n_new, const int32_t* tok_start, const int32_t* kv_off,
                                  const int32_t* cap, const int32_t* tile_seq, const int32_t* tile_q0, void* out16,

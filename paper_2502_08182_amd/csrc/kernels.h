@@ -76,6 +76,9 @@ constexpr int kXPacked = 1, kOutPacked = 2;
 hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, const void* bias,
                               void* out, int M, int N, int K, hipStream_t st, int splits = 1, int flags = 0);
 int gemm_skinny_splits(int M, int N, int K);
+// Planes for a QKV projection run as EPI_PART32 (summed by the attention kernel, AttnAppend::qkv_part), or 0:
+// keep the 16-bit epilogue.  Non-zero only at 9..64 rows, where the split shape is the faster one.
+int gemm_qkv_splits(int M, int N, int K);
 // Prefill path: any M.
 hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, const void* bias,
                             void* out, int M, int N, int K, hipStream_t st);
@@ -99,6 +102,11 @@ struct AttnAppend {
   uint16_t* mirror = nullptr;
   const float* inv_freq = nullptr;
   int rope = 0;
+  // the step's q, k, v as split-K partial planes [qkv_nsplit][qkv_rows][(Hq + 2 Hkv) d] (bias in plane 0)
+  // instead of the 16-bit qkv rows; null: read qkv16
+  const float* qkv_part = nullptr;
+  int qkv_nsplit = 0;
+  int qkv_rows = 0;
 };
 int attn_decode_splits(int B, int Hkv, int max_len);
 hipError_t launch_attn_decode(int dtype, const void* qkv16, const void* kv, const StepIndex& ix,

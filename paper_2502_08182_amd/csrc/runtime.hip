@@ -129,6 +129,7 @@ struct sn_ctx {
   uint16_t *u16 = nullptr, *qkv16 = nullptr, *attn16 = nullptr, *act16 = nullptr;
   float* part = nullptr;
   float* part32 = nullptr;       // split-K partial sums of the decode residual projections
+  float* qkv_part32 = nullptr;   // split-K partial sums of the decode QKV projection (9..64 rows), see run_layer
   float* inv_freq = nullptr;
   int32_t* flag_dev = nullptr;   // set by the final cast of an iteration when a hidden state is not finite
   int32_t* meta_dev = nullptr;
@@ -415,7 +416,7 @@ extern "C" void sn_destroy(sn_ctx* c) {
   for (auto& s : c->slot_kv)
     if (s) (void)hipFree(s);
   if (c->stage_w) (void)hipHostFree(c->stage_w);
-  void* dev[] = {c->x32, c->u16, c->qkv16, c->attn16, c->act16, c->part, c->part32, c->inv_freq, c->meta_dev, c->flag_dev};
+  void* dev[] = {c->x32, c->u16, c->qkv16, c->attn16, c->act16, c->part, c->part32, c->qkv_part32, c->inv_freq, c->meta_dev, c->flag_dev};
   for (void* p : dev)
     if (p) (void)hipFree(p);
   for (int i = 0; i < kMetaRing; ++i) {
@@ -467,7 +468,9 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   const uint64_t b_meta = align_up(c->meta_ints * 4);
   const uint64_t b_freq = align_up((uint64_t)s.head_dim / 2 * 4);
   const uint64_t b_part32 = align_up((uint64_t)kMaxSplits * std::min(s.max_batch, kMaxDecodeRows) * s.hidden * 4);
-  c->ws_bytes = b_x32 + b_u + b_qkv + b_attn + b_act + b_part + b_part32 + b_meta + b_freq;
+  // a decode step of 9..64 rows may run its QKV projection split over K (gemm_qkv_splits)
+  const uint64_t b_qkv_part = s.max_batch > 8 ? align_up((uint64_t)kMaxSplits * 64 * qkv_ld * 4) : 0;
+  c->ws_bytes = b_x32 + b_u + b_qkv + b_attn + b_act + b_part + b_part32 + b_qkv_part + b_meta + b_freq;
 
   SN_HIP(c, hipStreamCreateWithFlags(&c->h2d, hipStreamNonBlocking));
   SN_HIP(c, hipStreamCreateWithFlags(&c->d2h, hipStreamNonBlocking));
@@ -478,6 +481,7 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   SN_HIP(c, hipMalloc(&c->act16, b_act));
   SN_HIP(c, hipMalloc(&c->part, b_part));
   SN_HIP(c, hipMalloc(&c->part32, b_part32));
+  if (b_qkv_part) SN_HIP(c, hipMalloc(&c->qkv_part32, b_qkv_part));
   SN_HIP(c, hipMalloc(&c->meta_dev, b_meta));
   SN_HIP(c, hipMalloc(&c->inv_freq, b_freq));
   SN_HIP(c, hipMalloc(&c->flag_dev, 256));
@@ -871,8 +875,15 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, 
   SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, pending, st, pk));
   pending = Fold{};
   kt.end(SN_K_NORM);
+  // decode, 9..64 rows: the QKV projection has too few output features to give every compute unit a
+  // workgroup, so it is split over K like the residual projections; its fp32 planes are summed by the
+  // attention kernel where it picks up the step's q, k and v
+  const int qkv_splits = small && c->qkv_part32 ? gemm_qkv_splits(T, p.n_qkv, h) : 0;
   kt.begin(SN_K_QKV);
-  SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h, false));
+  if (qkv_splits)
+    SN_HIP(c, launch_gemm_skinny(dt, EPI_PART32, at(p.wqkv), c->u16, at(p.bqkv), c->qkv_part32, T, p.n_qkv, h, st, qkv_splits, kXPacked));
+  else
+    SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h, false));
   kt.end(SN_K_QKV);
   if (prefill) {
     kt.begin(SN_K_ROPE_APPEND);
@@ -883,7 +894,12 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, 
     kt.end(SN_K_ATTN);
   } else {
     // decode: rotation and KV append are done by the attention kernel itself
-    const AttnAppend ap{(uint16_t*)kv, (uint16_t*)mirror_kv, c->inv_freq, s.rope};
+    AttnAppend ap{(uint16_t*)kv, (uint16_t*)mirror_kv, c->inv_freq, s.rope};
+    if (qkv_splits) {
+      ap.qkv_part = c->qkv_part32;
+      ap.qkv_nsplit = qkv_splits;
+      ap.qkv_rows = T;
+    }
     kt.begin(SN_K_ATTN);
     SN_HIP(c, launch_attn_decode(dt, c->qkv16, kv, ix, c->attn16, c->part, B, Hq, Hkv, d, S, st, 1, &ap));
     kt.end(SN_K_ATTN);
@@ -1182,7 +1198,10 @@ extern "C" int sn_time_kernel_class(sn_ctx* c, int32_t kernel_class, int32_t bat
       hipError_t e;
       switch (kernel_class) {
         case SN_K_QKV:
-          e = launch_gemm_skinny(SN_F16, EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, batch, p.n_qkv, h, c->compute, 1, kXPacked);
+          if (const int qs = c->qkv_part32 ? gemm_qkv_splits(batch, p.n_qkv, h) : 0)
+            e = launch_gemm_skinny(SN_F16, EPI_PART32, at(p.wqkv), c->u16, at(p.bqkv), c->qkv_part32, batch, p.n_qkv, h, c->compute, qs, kXPacked);
+          else
+            e = launch_gemm_skinny(SN_F16, EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, batch, p.n_qkv, h, c->compute, 1, kXPacked);
           break;
         case SN_K_OPROJ:
           e = launch_gemm_skinny(SN_F16, EPI_PART32, at(p.wo), c->attn16, nullptr, c->part32, batch, h, qd, c->compute,

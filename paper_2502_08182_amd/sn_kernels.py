@@ -9,7 +9,7 @@ import numpy as np
 from . import sn as _sn
 
 EXPORTS = ("sn_k_tile_weights", "sn_k_norm", "sn_k_gemm", "sn_k_rope_append", "sn_k_attn_decode",
-           "sn_k_attn_decode_append", "sn_k_attn_decode_static",
+           "sn_k_attn_decode_append", "sn_k_attn_decode_append_planes", "sn_k_attn_decode_static",
            "sn_k_attn_prefill", "sn_k_cast_in", "sn_k_cast_out", "sn_k_copy", "sn_k_gemm_splitk", "sn_k_norm_fold", "sn_k_cast_out_fold", "sn_k_packed_offset")
 
 EPI_STORE16, EPI_GELU16, EPI_RESID32, EPI_SWIGLU16 = 0, 1, 2, 3
@@ -33,6 +33,7 @@ def _lib():
             "sn_k_attn_decode": [i32, v, v, v, v, v, v, v, i32, i32, i32, i32, i32, i32, i32, v],
             "sn_k_attn_decode_static": [i32, v, v, v, v, v, v, i32, i32, i32, i32, i32, i32, i32, v],
             "sn_k_attn_decode_append": [i32, v, v, v, v, i32, v, v, v, v, v, i32, i32, i32, i32, i32, i32, i32, v],
+            "sn_k_attn_decode_append_planes": [i32, v, i32, i32, v, v, v, i32, v, v, v, v, v, i32, i32, i32, i32, i32, i32, i32, v],
             "sn_k_attn_prefill": [i32, v, v, v, v, v, v, v, v, v, v, i32, i32, i32, i32, v],
             "sn_k_cast_in": [i32, v, v, u64, v],
             "sn_k_cast_out": [i32, v, v, u64, v],
@@ -123,6 +124,13 @@ def sn_k_attn_decode_append(dtype, qkv16, kv, mirror, inv_freq, rope, len_before
     _chk(_lib().sn_k_attn_decode_append(dtype, _p(qkv16), _p(kv), _p(mirror), _p(inv_freq), int(rope), _p(len_before),
                                         _p(kv_off), _p(cap), _p(out16), _p(part), B, Hq, Hkv, d, S, max_len,
                                         packed_out, stream))
+
+
+def sn_k_attn_decode_append_planes(dtype, qkv_part, splits, plane_rows, kv, mirror, inv_freq, rope, len_before, kv_off,
+                                   cap, out16, part, B, Hq, Hkv, d, S, max_len, packed_out=0, stream=0):
+    _chk(_lib().sn_k_attn_decode_append_planes(dtype, _p(qkv_part), splits, plane_rows, _p(kv), _p(mirror), _p(inv_freq),
+                                               int(rope), _p(len_before), _p(kv_off), _p(cap), _p(out16), _p(part),
+                                               B, Hq, Hkv, d, S, max_len, packed_out, stream))
 
 
 def sn_k_attn_prefill(dtype, qkv16, kv, len_before, n_new, tok_start, kv_off, cap, tile_seq, tile_q0, out16,

@@ -85,8 +85,13 @@ def test_forced_hazards_leave_the_output_bit_identical(c1, mode):
                     assert np.array_equal(a, ref_pre), f"prefill differs: {tag}"
                     assert np.array_equal(b, ref_dec), f"decode differs: {tag}"
                 if mode == "sync_point" and sched == sn.SN_SCHED_PAPER:
-                    # every load of the last decode step started DELAY_US late and compute had to wait for it
-                    assert st["stall_ns"] >= plain["stall_ns"] + 0.5 * DELAY_US * 1e3 * (L // N), (tag, st["stall_ns"], plain["stall_ns"])
+                    # every load of the last decode step started DELAY_US late and the layer that needs it could not
+                    # run before it landed: the iteration is longer by about the delays.  (Usually all of it shows as
+                    # waiting at the fence, stall_ns; but the runtime maps streams onto a few hardware queues, and when
+                    # the copy stream shares one with the compute stream the delay holds up the kernels queued behind
+                    # it instead -- so the check is on the iteration's length.)
+                    assert st["iter_ns"] >= plain["iter_ns"] + 0.5 * DELAY_US * 1e3 * (L // N), \
+                        (tag, st["iter_ns"], plain["iter_ns"], st["stall_ns"], plain["stall_ns"])
 
 
 def test_debug_switch_rejects_bad_arguments(c1):

@@ -442,6 +442,18 @@ def test_attn_decode_with_fused_append(dtype, Hq, Hkv, d, rope):
         assert torch.equal(kv_f, kv_two), f"cache after the fused kernel differs from rope_append's (S={S})"
         assert torch.equal(mir_f, mir_two), f"mirror differs (S={S})"
         assert torch.equal(out_f, out_two), f"fused output differs from the two-kernel path (S={S})"
+        # the same step with q, k, v handed over as split-K partial planes (what a 9..64-row decode step
+        # does): three planes that add up, in fp32 and in this order, to exactly the 16-bit values -- so
+        # the result must not differ in a single bit; rows and planes the kernel must not read hold NaN
+        q32 = torch.from_numpy(synth.widen(host16(qkv0), dtype).astype(np.float32)).cuda().reshape(B, -1)
+        planes = torch.full((5, B + 3, q32.shape[1]), float("nan"), dtype=torch.float32, device="cuda")
+        planes[0, :B], planes[1, :B], planes[2, :B] = 0.5 * q32, 0.25 * q32, 0.25 * q32
+        kv_p, mir_p = kv0.clone(), torch.zeros_like(kv0)
+        out_p = torch.zeros(B, Hq * d, dtype=torch.int16, device="cuda")
+        K.sn_k_attn_decode_append_planes(DT[dtype], planes, 3, B + 3, kv_p, mir_p, dv["inv_freq"], rope, dv["len_before"],
+                                         dv["kv_off"], dv["cap"], out_p, part, B, Hq, Hkv, d, S, max(lens_before) + 1)
+        torch.cuda.synchronize()
+        assert torch.equal(out_p, out_f) and torch.equal(kv_p, kv_f) and torch.equal(mir_p, mir_f), f"planes path differs (S={S})"
     kv_host = host16(kv_f)
     for b in range(B):
         base = int(kv_off[b]) * 2 * Hkv * d
@@ -559,6 +571,32 @@ def test_splitk_projection_wide_and_long():
             kr = Kd // used
             want1 = synth.widen(xb, "f16")[:, kr:2 * kr] @ synth.widen(wb, "f16")[:, kr:2 * kr].T
             assert np.abs(planes[1] - want1).max() <= 2e-5 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("case", ["c5_qkv", "c5_oproj", "c5_ffn_down", "c4_qkv", "c3_ffn_down"])
+def test_splitk_projection_planned_shapes_full_size(case):
+    """Split-K projections at the real shapes and row counts of the 13B-, 30B- and 70B-shaped decode steps, with
+    the number of planes and the launch shape the library plans itself (packed activations in, as in a decode
+    step): the planes add up to X W^T + bias on sampled features, all rows."""
+    M, N, Kd = {"c5_qkv": (64, 10240, 8192), "c5_oproj": (64, 8192, 8192), "c5_ffn_down": (64, 8192, 28672),
+                "c4_qkv": (64, 21504, 7168), "c3_ffn_down": (32, 5120, 13824)}[case]
+    rng = np.random.default_rng(91)
+    xb = synth.to_bits(rng.standard_normal((M, Kd)), "f16")
+    wb = synth.to_bits(rng.standard_normal((N, Kd), dtype=np.float32) * 0.02, "f16")
+    bb = synth.to_bits(rng.standard_normal(N) * 0.3, "f16")
+    part = torch.full((8, M, N), float("nan"), dtype=torch.float32, device="cuda")
+    used = K.sn_k_gemm_splitk(DT["f16"], dev16(K.sn_k_tile_weights(wb, N, Kd)), dev16(K.pack_rows(xb)), dev16(bb), part,
+                              M, N, Kd, 0, 1)
+    torch.cuda.synchronize()
+    assert 2 <= used <= 8, used
+    planes = part[:used].cpu().numpy().astype(np.float64)
+    assert np.isfinite(planes).all() and bool(torch.isnan(part[used:]).all())
+    cols = np.unique(np.concatenate([[0, 1, 15, 16, 63, 64, N - 65, N - 1], rng.integers(0, N, 400)]))
+    want = synth.widen(xb, "f16") @ synth.widen(wb[cols], "f16").T + synth.widen(bb, "f16")[cols]
+    got = planes.sum(axis=0)[:, cols]
+    assert np.abs(got - want).max() <= 2e-5 * np.abs(want).max() + 1e-6, case
+    # every plane carries a share: a launch shape that dropped a K range would leave one at zero
+    assert all(np.abs(planes[i]).max() > 0 for i in range(used))
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
