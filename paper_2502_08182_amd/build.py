@@ -22,7 +22,10 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-u
 # Per-file additions.  Prefill attention: its accumulators are rescaled by vector code between matrix-core
 # products; with the accumulators in the AGPR half of the register file the compiler moves all of them to
 # VGPRs and back every step (a quarter of the kernel's instructions), so its MFMAs take the VGPR form.
-EXTRA_FLAGS = {"k_attn_prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+EXTRA_FLAGS = {"k_attn_prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+               # grouped-query decode attention: the same rescale between products, and with its two tiles of K / V
+               # in registers it only fits two wavefronts per SIMD without the AGPR copies
+               "k_attn_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src: str) -> str:

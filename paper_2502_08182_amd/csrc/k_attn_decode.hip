@@ -458,6 +458,230 @@ __global__ __launch_bounds__(256) void attn_decode_gqa_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------
+// The same for head dimension 128, with every load instruction reading whole cache lines.
+//
+// In the kernel above a load instruction fetches the MFMA operand of 16 keys: 64 bytes from each of 16 rows.
+// Half-line requests cost a fifth of the bandwidth (pure reads of this layout: 5.6 TB/s with that lane mapping,
+// 7.1 TB/s with 4 whole 256-byte rows per instruction).  Here all loads are whole rows or whole lines and the
+// operands are formed without LDS:
+//   V: lane (x = lane % 16, y = lane / 16) loads, for i = 0..7, the 16 bytes d = 8x..8x+7 of key 8y+i -- four whole
+//      rows per instruction.  It then holds an 8 x 8 block (keys x d); transposed in registers, row e of the block
+//      is the B operand of product e of  O = P V:  B_e[key 8y+i][column x] = V[8y+i][8x+e], A = P[head][key] --
+//      column x of product e is d = 8x + e, so the 8 products cover d = 0..127 and a lane ends up with 8 consecutive
+//      d-values per head: one 16-byte store.
+//   K: eight lanes share a key row (128 bytes = one line per instruction).  Lane x carries key x/2 of a set of 8
+//      and the 64-byte half x%2 of a 128-byte part u of the row, so as an MFMA A operand "row x" is (key, half):
+//      one product against Q's d-chunks of half 0 is right for the even rows, one against half 1 for the odd rows,
+//      and a key's score is the sum of its even row of the first and its odd row of the second (the same lane
+//      holds both).  Twice the matrix-core work for S, which has room to spare.  The keys of set s are
+//      8y' + 2s + {0, 1} (y' = 0..3), so lane group y' ends up with scores of keys 8y'..8y'+7 -- the layout of
+//      P as A operand and of V's rows as B operand.
+// The rescale factor of the running softmax lives with the head on lane x; the accumulators hold heads 4y + j,
+// so it is fetched across lanes (4 per tile).  Loads for the next tile are issued as soon as the registers of
+// this one have been consumed: K after the score products, V after the output products.
+template <class T, int G, bool FA>
+__global__ __launch_bounds__(256, 2) void attn_decode_gqa128_kernel(
+    const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
+    const int32_t* __restrict__ kv_off, const int32_t* __restrict__ cap, uint16_t* __restrict__ out,
+    float* __restrict__ part, int Hq, int Hkv, int S, int packed, uint16_t* __restrict__ kvw,
+    uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int rope, QkvPlanes qp) {
+  constexpr int D = 128;
+  constexpr int kMrgWave = 32 + 16 * D;                  // floats per wavefront in the merge: m[16], l[16], O[16][D]
+  __shared__ __attribute__((aligned(16))) float mrg[4 * kMrgWave];
+  __shared__ __attribute__((aligned(16))) uint16_t stage[FA ? G + 2 : 1][D];
+
+  const int b = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, split = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int len = len_before[b] + 1;
+  const int chunk = (len + S - 1) / S;
+  const int j0 = split * chunk, j1 = min(len, j0 + chunk);
+  const int qkv_ld = (Hq + 2 * Hkv) * D;
+  const bool qok = r < G;
+
+  const int cp = cap[b];
+  const size_t k_base = (size_t)kv_off[b] * 2 * Hkv * D + (size_t)(hk * 2) * cp * D;
+  const int pos = len - 1;            // position of this step's token
+  if (FA) {
+    stage_new_token<T, D, G>(stage, qkv + (size_t)b * qkv_ld, qp, b, hk, Hq, Hkv, pos, inv_freq, rope);
+    __syncthreads();
+    if (pos >= j0 && pos < j1)
+      store_new_token<D, G>(stage, kvw, mirror, k_base + (size_t)pos * D, k_base + ((size_t)cp + pos) * D);
+  }
+  // B operands of the score products: Q[head r][32 kk + 8 g ..], zero for the padding heads
+  u16x8 qf[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    qf[kk] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    if (qok)
+      qf[kk] = FA ? *reinterpret_cast<const u16x8*>(&stage[r][kk * 32 + g * 8])
+                  : *reinterpret_cast<const u16x8*>(qkv + (size_t)b * qkv_ld + (size_t)(hk * G + r) * D + kk * 32 + g * 8);
+  }
+  const uint16_t* Kb = kv + k_base;
+  const uint16_t* Vb = Kb + (size_t)cp * D;
+  // last cached row a load may touch: with the fused append the new row is never loaded (the workgroup of the
+  // range that owns it is writing it); rows past the end of the range are clamped to it and their scores masked
+  const int jlast = FA ? max(min(j1 - 1, pos - 1), 0) : j1 - 1;
+  const float scale = rsqrtf((float)D);
+
+  // this lane's K rows: set s -> key offset 8 (r / 4) + 2 s + (r / 2) % 2, bytes 128 u + 64 (r % 2) + 16 g
+  const int kkey = 8 * (r >> 2) + ((r >> 1) & 1);
+  const int kcol = 32 * (r & 1) + 8 * g;
+  u16x8 kreg[4][2], vreg[8];
+  auto issue_k = [&](int jt) {
+#pragma unroll
+    for (int s2 = 0; s2 < 4; ++s2) {
+      const uint16_t* kp = Kb + (size_t)min(jt + kkey + 2 * s2, jlast) * D + kcol;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) kreg[s2][u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(kp + 64 * u));
+    }
+  };
+  auto issue_v = [&](int jt) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vb + (size_t)min(jt + 8 * g + i, jlast) * D + 8 * r));
+  };
+
+  float m = kNegBig, l = 0.f;
+  f32x4 o[8];                         // o[e][j] = O[head 4 g + j][d = 8 r + e]
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  int jt = j0 + wave * 32;
+  if (jt < j1) {
+    issue_k(jt);
+    issue_v(jt);
+  }
+  for (; jt < j1; jt += 4 * 32) {
+    const bool own = FA && pos >= jt && pos < jt + 32;   // the tile with this step's own token (wavefront-uniform)
+    if (own) {
+#pragma unroll
+      for (int s2 = 0; s2 < 4; ++s2)
+        if (jt + kkey + 2 * s2 == pos)
+#pragma unroll
+          for (int u = 0; u < 2; ++u) kreg[s2][u] = *reinterpret_cast<const u16x8*>(&stage[G][64 * u + kcol]);
+    }
+    // scores: keys jt + 8 g + e of head r
+    float sc[8];
+#pragma unroll
+    for (int s2 = 0; s2 < 4; ++s2) {
+      f32x4 d0 = f32x4{0.f, 0.f, 0.f, 0.f}, d1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        d0 = mma16x16x32<T>(kreg[s2][u], qf[2 * u], d0);
+        d1 = mma16x16x32<T>(kreg[s2][u], qf[2 * u + 1], d1);
+      }
+      sc[2 * s2] = d0[0] + d1[1];
+      sc[2 * s2 + 1] = d0[2] + d1[3];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    issue_k(jt + 4 * 32);                                 // past the end: clamped rows, never used
+    __builtin_amdgcn_sched_barrier(0);
+    float mx = kNegBig;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sc[e] = jt + 8 * g + e < j1 ? sc[e] * scale : kNegBig;
+      mx = fmaxf(mx, sc[e]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx);
+    const float corr = __expf(m - mn);
+    float rs = 0.f;
+    u16x8 pb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float p = sc[e] > 0.5f * kNegBig ? __expf(sc[e] - mn) : 0.f;
+      rs += p;
+      pb[e] = from_f32<T>(p);
+    }
+    l = l * corr + rs;
+    m = mn;
+    float cj[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) cj[j] = __shfl(corr, 4 * g + j, 64);
+    if (own) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (jt + 8 * g + i == pos) vreg[i] = *reinterpret_cast<const u16x8*>(&stage[G + 1][8 * r]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      // row e of the transposed 8 x 8 block: d = 8 r + e of keys 8 g .. 8 g + 7
+      u32x4 bw;
+#pragma unroll
+      for (int i2 = 0; i2 < 4; ++i2) {
+        const uint32_t lo = __builtin_bit_cast(u32x4, vreg[2 * i2])[e >> 1], hi = __builtin_bit_cast(u32x4, vreg[2 * i2 + 1])[e >> 1];
+        bw[i2] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[e][j] *= cj[j];
+      o[e] = mma16x16x32<T>(pb, __builtin_bit_cast(u16x8, bw), o[e]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    issue_v(jt + 4 * 32);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+
+  // merge the four wavefronts through LDS, in order: per head m, l; per (head, d) the accumulators
+  float* mine = mrg + (size_t)wave * kMrgWave;
+  if (g == 0) {
+    mine[r] = m;
+    mine[16 + r] = l;
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float* row = mine + 32 + (size_t)(4 * g + j) * D + 8 * r;
+    *reinterpret_cast<f32x4*>(row) = f32x4{o[0][j], o[1][j], o[2][j], o[3][j]};
+    *reinterpret_cast<f32x4*>(row + 4) = f32x4{o[4][j], o[5][j], o[6][j], o[7][j]};
+  }
+  __syncthreads();
+  if (wave != 0) return;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int h = 4 * g + j;
+    if (h >= G) continue;
+    float mm = mrg[h], ll = mrg[16 + h];
+    float acc[8];
+    {
+      const float* row = mrg + 32 + (size_t)h * D + 8 * r;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = row[e];
+    }
+    for (int w = 1; w < 4; ++w) {
+      const float* other = mrg + (size_t)w * kMrgWave;
+      const float m2 = other[h], mn = fmaxf(mm, m2);
+      const float c1 = __expf(mm - mn), c2 = __expf(m2 - mn);
+      ll = ll * c1 + other[16 + h] * c2;
+      const float* row = other + 32 + (size_t)h * D + 8 * r;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = acc[e] * c1 + row[e] * c2;
+      mm = mn;
+    }
+    const int hq = hk * G + h;
+    if (S == 1) {
+      const float inv = 1.0f / ll;
+      u16x8 w8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) w8[e] = from_f32<T>(acc[e] * inv);
+      const int k = hq * D + 8 * r;
+      const size_t at = packed ? packed_off(b, k, (Hq * D) >> 5) : (size_t)b * Hq * D + k;
+      *reinterpret_cast<u16x8*>(out + at) = w8;
+    } else {
+      float* p = part + (((size_t)b * Hq + hq) * S + split) * (D + 2);
+      if (r == 0) {
+        p[0] = mm;
+        p[1] = ll;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p[2 + 8 * r + e] = acc[e];
+    }
+  }
+}
+
 // Merge the S key-range partials of one (sequence, query head); thread = output element.
 template <class T, int D>
 __global__ void attn_combine_kernel(const float* __restrict__ part, uint16_t* __restrict__ out, int S, int Hq,
@@ -499,8 +723,12 @@ static hipError_t launch_d(const uint16_t* qkv, const uint16_t* kv, const StepIn
   SN_LAUNCH((attn_decode_kernel<T, D, GV, NWV, UKV, FA>), dim3(B * Hkv, S), dim3(NWV * 64), 0, st, qkv, kv,       \
             ix.len_before, ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope, qp)
 #define SN_LAUNCH_GQA(GV)                                                                                         \
-  SN_LAUNCH((attn_decode_gqa_kernel<T, D, GV, FA>), dim3(B * Hkv, S), dim3(256), 0, st, qkv, kv, ix.len_before,   \
-            ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope, qp)
+  if constexpr (D == 128)                                                                                         \
+    SN_LAUNCH((attn_decode_gqa128_kernel<T, GV, FA>), dim3(B * Hkv, S), dim3(256), 0, st, qkv, kv, ix.len_before, \
+              ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope, qp);      \
+  else                                                                                                            \
+    SN_LAUNCH((attn_decode_gqa_kernel<T, D, GV, FA>), dim3(B * Hkv, S), dim3(256), 0, st, qkv, kv, ix.len_before, \
+              ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope, qp)
   switch (G) {
     case 1: SN_LAUNCH_G(1, 16, 2); break;
     case 2: SN_LAUNCH_G(2, 16, 2); break;

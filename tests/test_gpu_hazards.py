@@ -73,6 +73,9 @@ def test_forced_hazards_leave_the_output_bit_identical(c1, mode):
                     sn.sn_set_offload_part(se.ctx, what)
                     sn.sn_set_schedule(se.ctx, sched)
                     se.place(N)
+                    # baseline without switches: the second of two requests (the first one after a placement
+                    # also pays for first-use effects of the pinned buffers and the copy engines)
+                    run_back_to_back(se, w, prompt, table)
                     plain = run_back_to_back(se, w, prompt, table)[2]
                     sn.sn_set_debug(se.ctx, MODES[mode], DELAY_US)
                     pre, dec, st = run_back_to_back(se, w, prompt, table)

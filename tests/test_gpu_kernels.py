@@ -371,7 +371,9 @@ def _oracle_attention(dtype, qkv, Kc, Vc, lens_before, n_new, tok_start, Hq, Hkv
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,rope", [("f16", 4, 4, 64, False), ("bf16", 8, 8, 128, True),
-                                                 ("bf16", 16, 2, 128, True), ("f16", 6, 3, 64, True)])
+                                                 ("bf16", 16, 2, 128, True), ("f16", 6, 3, 64, True),
+                                                 ("f16", 8, 2, 128, True), ("f16", 16, 2, 128, False),
+                                                 ("f16", 8, 2, 64, True)])
 def test_rope_append_and_attn_decode(dtype, Hq, Hkv, d, rope):
     rng = np.random.default_rng(3)
     lens_before = [0, 1, 130, 517, 63]
@@ -409,7 +411,8 @@ def test_rope_append_and_attn_decode(dtype, Hq, Hkv, d, rope):
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,rope", [("f16", 4, 4, 64, False), ("bf16", 8, 8, 128, True),
                                                  ("bf16", 16, 2, 128, True), ("f16", 6, 3, 64, True),
-                                                 ("f16", 8, 2, 64, True), ("f16", 32, 32, 128, False)])
+                                                 ("f16", 8, 2, 64, True), ("f16", 32, 32, 128, False),
+                                                 ("f16", 8, 2, 128, True), ("f16", 16, 2, 128, False)])
 def test_attn_decode_with_fused_append(dtype, Hq, Hkv, d, rope):
     """The decode kernel that rotates, appends and attends in one launch: against the oracle,
     and bit for bit against rope_append followed by attn_decode (outputs, cache rows, mirror);
