@@ -398,7 +398,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <class T, int EPI, int TI>   // TI: 16-token tiles per workgroup
 __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
-    void* __restrict__ out, int M, int N, int K, int NT, int TT, int CB) {
+    void* __restrict__ out, int M, int N, int K, int NT, int TT, int CB, int xpacked) {
   constexpr int BM = TI * 16;             // tokens per workgroup
   constexpr int XT = TI / 4;              // token tiles each wavefront stages per k step
   constexpr int FJ = 4;                   // 16-feature blocks per wavefront
@@ -430,11 +430,20 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
   const size_t wstride = (size_t)S * 512;
 
   // activation staging: wavefront w fetches token tiles XT*w .. XT*w + XT - 1 of the workgroup's TI
+  // Row-major X: a lane's 16 bytes are k-chunk lane / 16 of token row lane % 16, 64 bytes per row and request.
+  // Row-tile packed X (common.h packed_off): the tile of a k step is one contiguous KiB in exactly the order
+  // the LDS stage wants, so a request reads 8 whole cache lines instead of 16 half ones.
   const uint16_t* xg[XT];
+  const int xstep = xpacked ? kTile : 32;    // elements from one k step to the next
 #pragma unroll
   for (int i = 0; i < XT; ++i) {
     const int row = t0 + (wave * XT + i) * 16 + (lane & 15);
-    xg[i] = X + (size_t)(row < M ? row : 0) * K + (lane >> 4) * 8;
+    if (xpacked) {
+      const int tile = (t0 >> 4) + wave * XT + i;
+      xg[i] = X + (size_t)(tile * 16 < M ? tile : 0) * S * kTile + lane * 8;
+    } else {
+      xg[i] = X + (size_t)(row < M ? row : 0) * K + (lane >> 4) * 8;
+    }
   }
   // LDS byte address of this wavefront's first staging tile in buffer 0 (wave-uniform)
   const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
@@ -458,7 +467,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
     constexpr int B = decltype(buf)::value;
 #pragma unroll
     for (int i = 0; i < XT; ++i) {
-      const uint16_t* g = xg[i] + (size_t)st * 32;
+      const uint16_t* g = xg[i] + (size_t)st * xstep;
       const uint32_t m0 = lds0 + (uint32_t)((B * TI + i) * kTile * 2);
       asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory");
     }
@@ -476,7 +485,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
 #pragma unroll
     for (int i = 0; i < TI; ++i) {
       if (i < XT) {
-        const uint16_t* g = xg[i] + (size_t)ahead * 32;
+        const uint16_t* g = xg[i] + (size_t)ahead * xstep;
         const uint32_t m0 = lds0 + (uint32_t)((R * TI + i) * kTile * 2);
         asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory");
       } else if (i < XT + FJ) {
@@ -641,7 +650,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
 
 template <class T>
 static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out, int M,
-                           int N, int K, hipStream_t st) {
+                           int N, int K, int xpacked, hipStream_t st) {
   constexpr int TI = kBigTileTokenTiles;
   if (N % 256 == 0 && K % (32 * kBigTileRing) == 0 &&
       (int64_t)(N / 256) * ((M + TI * 16 - 1) / (TI * 16)) >= kBigTileMinTiles) {
@@ -649,22 +658,23 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
     dim3 grid(NT * TT), block(256);
     switch (epi) {
       case EPI_STORE16:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_STORE16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_STORE16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked);
         break;
       case EPI_GELU16:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_GELU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_GELU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked);
         break;
       case EPI_RESID32:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_RESID32, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_RESID32, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked);
         break;
       case EPI_SWIGLU16:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_SWIGLU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_SWIGLU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked);
         break;
       default:
         return hipErrorInvalidValue;
     }
     return hipGetLastError();
   }
+  if (xpacked) return hipErrorInvalidValue;
   if (N % 256 == 0 && K % 64 == 0) {
     const int NT = N / 256, TT = (M + 127) / 128, CB = tile_group(NT, K);
     dim3 grid(NT * TT), block(256);
@@ -707,12 +717,13 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
 }
 
 hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, const void* bias, void* out, int M,
-                            int N, int K, hipStream_t st) {
+                            int N, int K, hipStream_t st, int flags) {
   if (M <= 0) return hipSuccess;
   if (N % 16 || K % 32 || (epi == EPI_SWIGLU16 && N % 32)) return hipErrorInvalidValue;
+  const int xpacked = flags & kXPacked ? 1 : 0;
   if (dtype == 0)
-    return launch_t<F16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, st);
-  return launch_t<BF16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, st);
+    return launch_t<F16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, xpacked, st);
+  return launch_t<BF16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, xpacked, st);
 }
 
 }  // namespace sn

@@ -36,7 +36,7 @@ extern "C" int sn_k_gemm(int32_t dtype, int32_t epi, int32_t path, const void* W
   if (bad_dtype(dtype) || !W || !X || !out || M < 0 || N < 16 || K < 32 || epi < 0 || epi > 3 || flags < 0 || flags > 3)
     return SN_E_INVAL;
   if (path == 0) return rc_of(launch_gemm_skinny(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream, 1, flags));
-  if (path == 1 && flags == 0) return rc_of(launch_gemm_tile(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream));
+  if (path == 1 && (flags & ~1) == 0) return rc_of(launch_gemm_tile(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream, flags));
   return SN_E_INVAL;
 }
 

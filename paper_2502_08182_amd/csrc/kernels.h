@@ -81,7 +81,7 @@ int gemm_skinny_splits(int M, int N, int K);
 int gemm_qkv_splits(int M, int N, int K);
 // Prefill path: any M.
 hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, const void* bias,
-                            void* out, int M, int N, int K, hipStream_t st);
+                            void* out, int M, int N, int K, hipStream_t st, int flags = 0);
 
 // Rotates q (in place) and k, and appends k, v rows to the layer's KV slice
 // ([seq][Hkv][K|V][cap][d]); mirror (may be null) is a second copy of the slice that
