@@ -46,8 +46,10 @@ int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, c
  * stream [M][N], updated in place (+=); 3: SwiGLU -- W holds gate and up in alternating
  * 16-row blocks (N = 2*ffn rows), bias = [gate | up], out16[M][N/2] = silu(g)*u.
  * path 0: weight-streaming decode kernel (M <= 128; a packed X holds 16*ceil(M/16) rows); path 1: tiled prefill kernel.
- * flags (path 0 only): 1 = X is row-tile packed; 2 = the 16-bit output (epilogues 0, 1, 3)
- * is written row-tile packed. */
+ * flags: 1 = X is row-tile packed; 2 = the 16-bit output (epilogues 0, 1, 3) is written row-tile packed
+ * (path 0 only).  Path 1 takes flag 1 only where its 192 x 256 kernel applies (N % 256 == 0, K % 256 == 0, at
+ * least 2048 tiles of 192 rows x 256 features) and returns SN_E_INVAL otherwise: same result bit for bit,
+ * whole cache lines per activation request instead of half ones. */
 int sn_k_gemm(int32_t dtype, int32_t epilogue, int32_t path, const void* W, const void* X,
               const void* bias, void* out, int32_t M, int32_t N, int32_t K, int32_t flags,
               void* stream);

@@ -319,6 +319,34 @@ def test_gemm_tile_large_m(dtype, epi):
         _gemm_case(dtype, K.PATH_TILE, epi, M, Nw // wide, Kd, bias=(i % 2 == 0), seed=50 + i)
 
 
+@pytest.mark.parametrize("epi", [0, 2, 3])
+def test_gemm_tile_large_m_packed_activations(epi):
+    """The 192 x 256 prefill GEMM reading row-tile packed activations (one contiguous KiB per 16-token x 32-k tile,
+    whole cache lines per request): the layout is a permutation of the operand fetch only, so the output must equal,
+    bit for bit, that of the same launch on the row-major matrix -- which test_gemm_tile_large_m checks against the
+    oracle.  Ragged last token tile; shapes the smaller kernels would take refuse the flag."""
+    rng = np.random.default_rng(77)
+    wide = 2 if epi == K.EPI_SWIGLU16 else 1
+    M, N, Kd = 12481, 8192 // wide, 512
+    xb = synth.to_bits(rng.standard_normal((M, Kd)), "f16")
+    tiled = np.zeros(N * wide * Kd, dtype=np.uint16)
+    for j in range(wide):
+        K.sn_k_tile_weights(synth.to_bits(rng.standard_normal((N, Kd), dtype=np.float32) * 0.05, "f16"), N, Kd, tiled, wide, j)
+    outs = []
+    for flags, xdev in ((0, dev16(xb)), (1, dev16(K.pack_rows(xb)))):
+        if epi == K.EPI_RESID32:
+            out = torch.ones(M, N, dtype=torch.float32, device="cuda")
+        else:
+            out = torch.full((M, N), 0x7e00, dtype=torch.int16, device="cuda")
+        K.sn_k_gemm(DT["f16"], epi, K.PATH_TILE, dev16(tiled), xdev, None, out, M, N * wide, Kd, flags)
+        torch.cuda.synchronize()
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1])
+    assert bool(torch.isfinite(outs[1].float()).all()) if epi == K.EPI_RESID32 else bool((outs[1] != 0x7e00).any())
+    with pytest.raises(sn.SnError):     # 128 x 256 kernel (fewer than 2048 tiles): row-major only
+        K.sn_k_gemm(DT["f16"], epi, K.PATH_TILE, dev16(tiled), dev16(K.pack_rows(xb[:640])), None, outs[1], 640, N * wide, Kd, 1)
+
+
 def _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope):
     """Random qkv rows for the new tokens and a random cache prefix; returns device index
     arrays, device buffers and float64 views for the oracle."""
