@@ -20,18 +20,90 @@
 
 namespace sn {
 
+// The fused epilogue of one (row tile, output block [pair]) item: s0 (and, SwiGLU, s1) hold the finished sums of
+// this lane's 4 features nl .. nl + 3 of block c0 (c0 + 1) of column wn_i, for token row m.
+template <class T, int C, int EPI>
+__device__ __forceinline__ void epilogue_item(f32x4 s0, f32x4 s1, int m, int wn_i, int it, int nl, int NWN,
+                                              const uint16_t* __restrict__ bias, void* __restrict__ out, int N,
+                                              int opacked, int plane_rows) {
+  constexpr bool DUAL = EPI == EPI_SWIGLU16;
+  const int cb_i = (blockIdx.x * NWN + wn_i) * C;
+  const int c0 = DUAL ? it * 2 : it;
+  if (EPI == EPI_SWIGLU16) {
+    const int F = N >> 1;
+    const int n = ((cb_i >> 1) + it) * 16 + nl;
+    u16x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float g = s0[i], u = s1[i];
+      if (bias) {
+        g += to_f32<T>(bias[n + i]);
+        u += to_f32<T>(bias[F + n + i]);
+      }
+      o[i] = from_f32<T>(silu(g) * u);
+    }
+    const size_t at = opacked ? packed_off(m, n, F >> 5) : (size_t)m * F + n;
+    *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + at) = o;
+  } else {
+    const int n = (cb_i + c0) * 16 + nl;
+    if (EPI == EPI_PART32) {
+      // the bias goes into plane 0 here, not into the later fold: the fold runs inside the NEXT layer,
+      // when this layer's weight record (a staging slot, if the layer is host-resident) may already
+      // be receiving another layer
+      if (bias && blockIdx.y == 0)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s0[i] += to_f32<T>(bias[n + i]);
+      *reinterpret_cast<f32x4*>(static_cast<float*>(out) + ((size_t)blockIdx.y * plane_rows + m) * N + n) = s0;
+    } else if (EPI == EPI_RESID32) {
+      float* xr = static_cast<float*>(out) + (size_t)m * N + n;
+      f32x4 r = *reinterpret_cast<const f32x4*>(xr);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r[i] += s0[i] + (bias ? to_f32<T>(bias[n + i]) : 0.f);
+      *reinterpret_cast<f32x4*>(xr) = r;
+    } else {
+      u16x4 o;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float v = s0[i] + (bias ? to_f32<T>(bias[n + i]) : 0.f);
+        if (EPI == EPI_GELU16) v = gelu_erf(v);
+        o[i] = from_f32<T>(v);
+      }
+      const size_t at = opacked ? packed_off(m, n, N >> 5) : (size_t)m * N + n;
+      *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + at) = o;
+    }
+  }
+}
+
 // Fixed-order reduction of the KS partial tiles through LDS (one row tile at a time) and the fused epilogue.
 // red: [KS][C][64][4] floats.  Wavefront (wk, wn) = (wave / NWN, wave % NWN) holds the partial sums of
 // column blocks (blockIdx.x * NWN + wn) * C .. + C over the wk-th part of the workgroup's K range.
+// With one wavefront per column (KS == NWN) there is nothing to reduce: every wavefront finishes its own
+// blocks from registers (the same sums, 0 + x, so the bits do not depend on which way a launch went).
 template <class T, int MT, int C, int EPI>
 __device__ __forceinline__ void reduce_and_store(float* red, const f32x4 (&acc)[MT][C], int lane, int wave, int KS, int NWN,
                                                  const uint16_t* __restrict__ bias, void* __restrict__ out, int M, int N,
                                                  int opacked, int plane_rows) {
   constexpr bool DUAL = EPI == EPI_SWIGLU16;
   const int KSK = KS / NWN;
-  // fixed-order reduction of the KS partial tiles, one row tile at a time
   constexpr int ITEMS = DUAL ? C / 2 : C;              // epilogue work items per row tile
   const int nl = (lane >> 4) * 4;                      // first of this lane's 4 columns in a block
+  if (KS == NWN) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 16 + (lane & 15);
+      if (m >= M) continue;
+#pragma unroll
+      for (int it = 0; it < ITEMS; ++it) {
+        const int c0 = DUAL ? it * 2 : it;
+        f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+        s0 += acc[mt][c0];
+        if (DUAL) s1 += acc[mt][DUAL ? c0 + 1 : c0];
+        epilogue_item<T, C, EPI>(s0, s1, m, wave, it, nl, NWN, bias, out, N, opacked, plane_rows);
+      }
+    }
+    return;
+  }
+  // fixed-order reduction of the KS partial tiles, one row tile at a time
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     if (mt) __syncthreads();
@@ -44,56 +116,13 @@ __device__ __forceinline__ void reduce_and_store(float* red, const f32x4 (&acc)[
     for (int item = wave; item < NWN * ITEMS; item += KS) {
       if (m >= M) break;
       const int wn_i = item / ITEMS, it = item % ITEMS;
-      const int cb_i = (blockIdx.x * NWN + wn_i) * C;
       const int c0 = DUAL ? it * 2 : it;
       f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
       for (int w = 0; w < KSK; ++w) {
         s0 += *reinterpret_cast<const f32x4*>(red + ((size_t)((w * NWN + wn_i) * C + c0) * 64 + lane) * 4);
         if (DUAL) s1 += *reinterpret_cast<const f32x4*>(red + ((size_t)((w * NWN + wn_i) * C + c0 + 1) * 64 + lane) * 4);
       }
-      if (EPI == EPI_SWIGLU16) {
-        const int F = N >> 1;
-        const int n = ((cb_i >> 1) + it) * 16 + nl;
-        u16x4 o;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float g = s0[i], u = s1[i];
-          if (bias) {
-            g += to_f32<T>(bias[n + i]);
-            u += to_f32<T>(bias[F + n + i]);
-          }
-          o[i] = from_f32<T>(silu(g) * u);
-        }
-        const size_t at = opacked ? packed_off(m, n, F >> 5) : (size_t)m * F + n;
-        *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + at) = o;
-      } else {
-        const int n = (cb_i + c0) * 16 + nl;
-        if (EPI == EPI_PART32) {
-          // the bias goes into plane 0 here, not into the later fold: the fold runs inside the NEXT layer,
-          // when this layer's weight record (a staging slot, if the layer is host-resident) may already
-          // be receiving another layer
-          if (bias && blockIdx.y == 0)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) s0[i] += to_f32<T>(bias[n + i]);
-          *reinterpret_cast<f32x4*>(static_cast<float*>(out) + ((size_t)blockIdx.y * plane_rows + m) * N + n) = s0;
-        } else if (EPI == EPI_RESID32) {
-          float* xr = static_cast<float*>(out) + (size_t)m * N + n;
-          f32x4 r = *reinterpret_cast<const f32x4*>(xr);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) r[i] += s0[i] + (bias ? to_f32<T>(bias[n + i]) : 0.f);
-          *reinterpret_cast<f32x4*>(xr) = r;
-        } else {
-          u16x4 o;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            float v = s0[i] + (bias ? to_f32<T>(bias[n + i]) : 0.f);
-            if (EPI == EPI_GELU16) v = gelu_erf(v);
-            o[i] = from_f32<T>(v);
-          }
-          const size_t at = opacked ? packed_off(m, n, N >> 5) : (size_t)m * N + n;
-          *reinterpret_cast<u16x4*>(static_cast<uint16_t*>(out) + at) = o;
-        }
-      }
+      epilogue_item<T, C, EPI>(s0, s1, m, wn_i, it, nl, NWN, bias, out, N, opacked, plane_rows);
     }
   }
 }
