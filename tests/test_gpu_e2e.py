@@ -281,7 +281,7 @@ def test_truncated_real_shapes_match_oracle(name):
     assert np.array_equal(gpre, ref[0]) and np.array_equal(gdec, ref[1])
 
 
-@pytest.mark.parametrize("batch", [17, 33, 64, 65, 96, 128])
+@pytest.mark.parametrize("batch", [9, 16, 17, 33, 64, 65, 96, 128])
 def test_decode_batches_spanning_row_tiles(batch):
     base = synth.workload("c1")
     shape = synth.ModelShape(2, 256, 8, 2, 64, 512, act="swiglu", norm="rms", rope=True, has_bias=False, dtype="bf16")

@@ -154,16 +154,20 @@ def test_gemm_skinny_wide(epi):
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_gemm_wide_shares_activations_through_lds(dtype):
-    """33..64 token rows, row-tile packed activations and enough feature groups: the decode GEMM whose
+    """9..64 token rows, row-tile packed activations and enough feature groups: the decode GEMM whose
     wavefronts fetch each activation tile once per workgroup into LDS (two k-blocks per step, double
-    buffered).  Every epilogue, 3 and 4 row tiles, ragged rows, 2 and 4 column blocks per wavefront, 4 / 7 / 8
+    buffered).  Every epilogue, 1 to 4 row tiles, ragged rows, 2 and 4 column blocks per wavefront, 4 / 7 / 8
     wavefronts side by side, K ranges of odd length, K shorter than one step, K split inside the workgroup
     (from 32 k-blocks on) and across workgroups (split-K planes)."""
     cases = [(K.EPI_STORE16, 64, 32768, 96, True),        # 4 column blocks, 4 columns x 1; 3 k-blocks: odd
              (K.EPI_GELU16, 50, 28672, 160, False),       # 1792 groups of 32: 7 wavefronts side by side
              (K.EPI_SWIGLU16, 33, 16384, 32, True),       # 3 row tiles, ragged; a single k-block (shorter than a step)
              (K.EPI_SWIGLU16, 64, 28672, 1120, False),    # 35 k-blocks: split in two inside the workgroup, odd halves
-             (K.EPI_STORE16, 48, 16384, 2048, True)]      # 3 full row tiles, 64 k-blocks: 32 per wavefront
+             (K.EPI_STORE16, 48, 16384, 2048, True),      # 3 full row tiles, 64 k-blocks: 32 per wavefront
+             (K.EPI_STORE16, 12, 32768, 96, True),        # one row tile (9..16 rows also take this kernel), ragged
+             (K.EPI_GELU16, 16, 28672, 160, False),       # one full row tile, 7 wavefronts side by side
+             (K.EPI_SWIGLU16, 24, 16384, 1120, True),     # two row tiles, ragged; K split inside the workgroup
+             (K.EPI_STORE16, 32, 16384, 2048, False)]     # two full row tiles
     for i, (epi, M, N, Kd, bias) in enumerate(cases):
         rng = np.random.default_rng(300 + i)
         dual = epi == K.EPI_SWIGLU16
@@ -604,13 +608,14 @@ def test_splitk_projection_wide_and_long():
             assert np.abs(planes[1] - want1).max() <= 2e-5 * np.abs(want).max()
 
 
-@pytest.mark.parametrize("case", ["c5_qkv", "c5_oproj", "c5_ffn_down", "c4_qkv", "c3_ffn_down"])
+@pytest.mark.parametrize("case", ["c5_qkv", "c5_oproj", "c5_ffn_down", "c4_qkv", "c3_ffn_down", "c3_qkv", "c4_qkv_12"])
 def test_splitk_projection_planned_shapes_full_size(case):
     """Split-K projections at the real shapes and row counts of the 13B-, 30B- and 70B-shaped decode steps, with
     the number of planes and the launch shape the library plans itself (packed activations in, as in a decode
     step): the planes add up to X W^T + bias on sampled features, all rows."""
     M, N, Kd = {"c5_qkv": (64, 10240, 8192), "c5_oproj": (64, 8192, 8192), "c5_ffn_down": (64, 8192, 28672),
-                "c4_qkv": (64, 21504, 7168), "c3_ffn_down": (32, 5120, 13824)}[case]
+                "c4_qkv": (64, 21504, 7168), "c3_ffn_down": (32, 5120, 13824), "c3_qkv": (32, 15360, 5120),
+                "c4_qkv_12": (12, 21504, 7168)}[case]
     rng = np.random.default_rng(91)
     xb = synth.to_bits(rng.standard_normal((M, Kd)), "f16")
     wb = synth.to_bits(rng.standard_normal((N, Kd), dtype=np.float32) * 0.02, "f16")
