@@ -637,7 +637,7 @@ def _layer_rows(s, layer, x_seq, rows):
     return np.concatenate(out, axis=0)
 
 
-def _two_live_layers_at_full_batch(name, P, rows_prompt, seed):
+def _two_live_layers_at_full_batch(name, P, rows_prompt, seed, **over):
     """A workload's real per-layer shape and full batch with 3 layers, the first two live and the third with its
     output projections zeroed (so the model IS its first two layers): offloaded runs -- interval 2; and interval 2
     with only the KV slices on the host under the continuous schedule -- are bit-identical to the all-resident one
@@ -645,9 +645,12 @@ def _two_live_layers_at_full_batch(name, P, rows_prompt, seed):
     layer 0 for every position of that sequence (layer 1's keys and values need them all), layer 1 for the sampled
     prompt positions and both decode steps."""
     import dataclasses
-    w = synth.workload(name)
+    w = synth.workload(name, **over)
     s = dataclasses.replace(w.shape, n_layers=3)
     B = w.batch
+    lens = list(w.prompt_lens)          # ragged workloads: sequence 0 has P = lens[0] prompt tokens
+    assert lens[0] == P and max(rows_prompt) < P
+    T = sum(lens)
     rng = np.random.default_rng(seed)
     live = [synth.make_layer(s, l, 0) for l in range(2)]
     blobs = [synth.pack_blob(s, t) for t in live]
@@ -656,19 +659,19 @@ def _two_live_layers_at_full_batch(name, P, rows_prompt, seed):
         dead[nm] = np.zeros_like(live[0][nm])
     blobs.append(synth.pack_blob(s, dead))
     del dead
-    prompt = synth.to_bits(rng.standard_normal((B * P, s.hidden), dtype=np.float32), s.dtype)
+    prompt = synth.to_bits(rng.standard_normal((T, s.hidden), dtype=np.float32), s.dtype)
     table = synth.to_bits(rng.standard_normal((2, B, s.hidden), dtype=np.float32), s.dtype)
     outs = {}
     for N in (0, 2, -2):            # -2: interval 2 again, KV slices only on the host, loads across the iteration boundary
-        with Session(s, B, P + 4) as se:
+        with Session(s, B, -(-(T + 4 * B) // B)) as se:
             for l in range(3):
                 sn.sn_set_layer_weights(se.ctx, l, blobs[l])
             if N < 0:
                 sn.sn_set_offload_part(se.ctx, sn.SN_OFFLOAD_KV)
                 sn.sn_set_schedule(se.ctx, sn.SN_SCHED_CONTINUOUS)
             se.place(abs(N))
-            se.kv_reset([P + 4] * B)
-            pre, fpre = se.step([P] * B, True, prompt, want_f32=True)
+            se.kv_reset([p + 4 for p in lens])
+            pre, fpre = se.step(lens, True, prompt, want_f32=True)
             d0, f0 = se.step([1] * B, False, table[0], want_f32=True)
             d1, f1 = se.step([1] * B, False, table[1], want_f32=True)
             st = se.stats()
@@ -700,6 +703,15 @@ def test_full_size_config5_layer_shape_and_batch():
     count).  Sampled: early, tile-boundary and last prompt positions (attention over up to 2048 keys) and both
     decode steps (decode attention over 2049 / 2050 keys of layer 1's cache)."""
     _two_live_layers_at_full_batch("c5", 2048, [0, 1, 63, 64, 127, 128, 1023, 2047], 51)
+
+
+def test_full_size_config4_layer_shape_ragged_batch_16():
+    """The OPT-30B-shaped configuration at its real per-layer shape with its ragged prompts (256..2048 tokens, drawn as the
+    benchmark draws them) at batch 16: LayerNorm, GELU, biases, 56 MHA heads x 128, FFN 28672; a prefill of ~15000 rows
+    whose sequences end inside token tiles, and decode steps of 16 rows -- the one-row-tile instance of the LDS-sharing
+    projection kernel and the split-K QKV projection summed by the attention kernel; 3 layers instead of 48."""
+    P = synth.workload("c4", batch=16).prompt_lens[0]
+    _two_live_layers_at_full_batch("c4", P, [0, 1, 15, 16, P // 2, P - 2, P - 1], 41, batch=16)
 
 
 def test_full_size_config3_layer_shape_and_batch():
