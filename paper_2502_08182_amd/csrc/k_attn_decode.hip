@@ -9,6 +9,12 @@
 // (wavefront, key slot) keeps its own running softmax (max, sum, weighted V), merged
 // at the end by shuffles, then across the wavefronts through LDS, then across key
 // ranges by a second small kernel.  All merges run in a fixed order.
+//
+// Three kernels: attn_decode_gqa128_kernel (head dimension 128, 1 to 8 query heads per KV
+// head: matrix cores, whole-line loads -- what every configuration measured here runs),
+// attn_decode_gqa_kernel (head dimension 64, 4 or 8 query heads per KV head: matrix cores,
+// V^T staged through LDS) and attn_decode_kernel (head dimension 64, 1 or 2 query heads per
+// KV head: the vector kernel described above).
 #include "kernels.h"
 #include "common.h"
 
@@ -487,8 +493,9 @@ __global__ __launch_bounds__(256, 2) void attn_decode_gqa128_kernel(
     float* __restrict__ part, int Hq, int Hkv, int S, int packed, uint16_t* __restrict__ kvw,
     uint16_t* __restrict__ mirror, const float* __restrict__ inv_freq, int rope, QkvPlanes qp) {
   constexpr int D = 128;
+  constexpr int NW = 4;                                  // wavefronts per workgroup (8 measured no better, even at one workgroup per CU)
   constexpr int kMrgWave = 32 + 16 * D;                  // floats per wavefront in the merge: m[16], l[16], O[16][D]
-  __shared__ __attribute__((aligned(16))) float mrg[4 * kMrgWave];
+  __shared__ __attribute__((aligned(16))) float mrg[NW * kMrgWave];
   __shared__ __attribute__((aligned(16))) uint16_t stage[FA ? G + 2 : 1][D];
 
   const int b = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, split = blockIdx.y;
@@ -548,12 +555,25 @@ __global__ __launch_bounds__(256, 2) void attn_decode_gqa128_kernel(
 #pragma unroll
   for (int e = 0; e < 8; ++e) o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  int jt = j0 + wave * 32;
-  if (jt < j1) {
-    issue_k(jt);
-    issue_v(jt);
+  // The range is walked in rounds of NW tiles, one per wavefront (so the workgroup reads NW * 8 KiB of K and of V
+  // side by side); every workgroup starts at a different round and wraps around.  All workgroups stream regions of
+  // the same size at the same pace, and when the stride between regions maps them onto few memory channels they
+  // would hit those channels in lock-step (8 x 32 heads with room for 1032 keys each, stride 516 KiB: 2.3 TB/s without the
+  // rotation, 5.2 with; other sizes lose 1-3 % to it).
+  // A wavefront's tile of the last round may lie past the end: clamped loads, every score masked.
+  const int nrounds = j1 > j0 ? (j1 - j0 + NW * 32 - 1) / (NW * 32) : 0;
+  const int rot = nrounds > 0 ? (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)nrounds) : 0;
+  auto tile_at = [&](int i) {         // this wavefront's tile of the i-th round of the walk; past the last round: that one again
+    int k = min(i, nrounds - 1) + rot;
+    if (k >= nrounds) k -= nrounds;
+    return j0 + (wave + NW * k) * 32;
+  };
+  if (nrounds > 0) {
+    issue_k(tile_at(0));
+    issue_v(tile_at(0));
   }
-  for (; jt < j1; jt += 4 * 32) {
+  for (int ti = 0; ti < nrounds; ++ti) {
+    const int jt = tile_at(ti), jnext = tile_at(ti + 1);
     const bool own = FA && pos >= jt && pos < jt + 32;   // the tile with this step's own token (wavefront-uniform)
     if (own) {
 #pragma unroll
@@ -576,7 +596,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_gqa128_kernel(
       sc[2 * s2 + 1] = d0[2] + d1[3];
     }
     __builtin_amdgcn_sched_barrier(0);
-    issue_k(jt + 4 * 32);                                 // past the end: clamped rows, never used
+    issue_k(jnext);
     __builtin_amdgcn_sched_barrier(0);
     float mx = kNegBig;
 #pragma unroll
@@ -620,13 +640,13 @@ __global__ __launch_bounds__(256, 2) void attn_decode_gqa128_kernel(
       o[e] = mma16x16x32<T>(pb, __builtin_bit_cast(u16x8, bw), o[e]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    issue_v(jt + 4 * 32);
+    issue_v(jnext);
     __builtin_amdgcn_sched_barrier(0);
   }
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
 
-  // merge the four wavefronts through LDS, in order: per head m, l; per (head, d) the accumulators
+  // merge the NW wavefronts through LDS, in order: per head m, l; per (head, d) the accumulators
   float* mine = mrg + (size_t)wave * kMrgWave;
   if (g == 0) {
     mine[r] = m;
@@ -651,7 +671,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_gqa128_kernel(
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] = row[e];
     }
-    for (int w = 1; w < 4; ++w) {
+    for (int w = 1; w < NW; ++w) {
       const float* other = mrg + (size_t)w * kMrgWave;
       const float m2 = other[h], mn = fmaxf(mm, m2);
       const float c1 = __expf(mm - mn), c2 = __expf(m2 - mn);
@@ -730,8 +750,15 @@ static hipError_t launch_d(const uint16_t* qkv, const uint16_t* kv, const StepIn
     SN_LAUNCH((attn_decode_gqa_kernel<T, D, GV, FA>), dim3(B * Hkv, S), dim3(256), 0, st, qkv, kv, ix.len_before, \
               ix.kv_off, ix.cap, out, part, Hq, Hkv, S, packed, ap.kv, ap.mirror, ap.inv_freq, ap.rope, qp)
   switch (G) {
-    case 1: SN_LAUNCH_G(1, 16, 2); break;
-    case 2: SN_LAUNCH_G(2, 16, 2); break;
+    // head dimension 128: the whole-line matrix-core kernel also for one or two query heads per KV head (15 of its
+    // 16 columns idle, but the bound is the memory system: 32 x 40 heads x 1030 keys 113 -> 103 us, 8 x 32 x 530
+    // 16.2 -> 13.8 us against the vector kernel)
+    case 1:
+      if constexpr (D == 128) { SN_LAUNCH_GQA(1); } else { SN_LAUNCH_G(1, 16, 2); }
+      break;
+    case 2:
+      if constexpr (D == 128) { SN_LAUNCH_GQA(2); } else { SN_LAUNCH_G(2, 16, 2); }
+      break;
     case 4: SN_LAUNCH_GQA(4); break;
     case 8: SN_LAUNCH_GQA(8); break;
     default: return hipErrorInvalidValue;
