@@ -138,7 +138,7 @@ int sn_k_attn_decode_append(int32_t dtype, const void* qkv16, void* kv, void* mi
                             void* stream);
 
 /* sn_k_attn_decode_append with the step's q, k and v given as split-K partial planes of the QKV
- * projection (what sn_step runs at 9..64 rows, where that projection is split over K like the residual
+ * projection (what sn_step runs at 9..128 rows, where that projection is split over K like the residual
  * projections; steps a5-a7): qkv_part [splits][plane_rows][(Hq + 2 Hkv) d] device fp32, 1 <= splits <= 8,
  * plane_rows >= B, the projection's bias already in plane 0 (sn_k_gemm_splitk writes exactly this).  The
  * kernel adds the planes in ascending order, rounds the sum to the 16-bit type -- the value the unsplit

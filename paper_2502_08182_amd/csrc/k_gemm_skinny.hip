@@ -493,7 +493,7 @@ static WidePlan plan_wide(int nb, int KB, int only_c = 0) {
   return best;
 }
 
-// Launch shape of a split-K projection (fp32 partial planes) at 9..64 rows, from timings of every legal
+// Launch shape of a split-K projection (fp32 partial planes) at 9..128 rows, from timings of every legal
 // shape on MI355X (the residual and QKV shapes of the 13B-, 30B- and 70B-shaped layers at 32 and 64 rows): one
 // wavefront per column (no K split inside the workgroup), the splits across workgroups provide the
 // parallelism, at most 256 workgroups -- one per compute unit; a second round costs more than anything else --
@@ -511,11 +511,11 @@ struct SplitPlan {
 };
 static SplitPlan plan_split(int M, int nb, int KB) {
   SplitPlan best{0, 0, 0};
-  if (M <= 8 || M > 64) return best;
+  if (M <= 8 || M > kMaxDecodeRows) return best;
   const bool long_k = KB > 512;
   long best_key = -1;
   for (int C : {4, 2}) {      // equal keys: four blocks per wavefront
-    if (nb % C) continue;
+    if (nb % C || (M > 64 && C != 2)) continue;     // 6 and 8 row tiles exist with two blocks per wavefront only
     const int groups = nb / C;
     for (int nwn = 4; nwn <= 8; ++nwn) {
       if (groups % nwn || nwn * C < 8 || nwn * C > 20) continue;
@@ -643,8 +643,14 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
       WidePlan pl{2, 4, 8};
       bool ok;
       if (epi == EPI_PART32) {
+        const SplitPlan sp = plan_split(M, nb, K / 32);
         const int groups = nb / 2;
-        ok = groups % 4 == 0 && groups / 4 * splits >= 200 && (K / 32) / splits >= 64;
+        if (sp.splits == splits) {       // the planned number of planes: the planned shape
+          ok = true;
+          pl = WidePlan{2, sp.nwn, sp.nwn};
+        } else {
+          ok = groups % 4 == 0 && groups / 4 * splits >= 200 && (K / 32) / splits >= 64;
+        }
       } else {
         pl = plan_wide(nb, K / 32, 2);
         ok = pl.nwn >= 4;
@@ -748,11 +754,12 @@ hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, 
 int gemm_skinny_splits(int M, int N, int K) {
   const int KB = K / 32;
   if (M > 64) {
-    // 6 or 8 row tiles: the two-column-block instance with 8 splits where launch_t takes it; every other shape runs
-    // as two passes of up to 64 rows and wants the split of 64 rows (7168 x 7168 at 128 rows: one plane left each
-    // pass with 112 workgroups, 75 us; two planes: 224 workgroups)
-    const int g2 = N / 32;
-    if (N % 32 == 0 && g2 % 4 == 0 && g2 / 4 * 8 >= 200 && KB / 8 >= 64) return 8;
+    // 6 or 8 row tiles: the planned shape where one exists; every other shape runs as two passes of up to 64 rows
+    // and wants the split of 64 rows
+    if (N % 16 == 0) {
+      const SplitPlan pl = plan_split(M, N / 16, KB);
+      if (pl.splits) return pl.splits;
+    }
     return gemm_skinny_splits(64, N, K);
   }
   if (M > 8 && N % 16 == 0) {
@@ -776,11 +783,11 @@ int gemm_skinny_splits(int M, int N, int K) {
   return sp;
 }
 
-// The QKV projection of a decode step at 9..64 rows: N = (Hq + 2 Hkv) d features are 160-1344 blocks, so the
+// The QKV projection of a decode step at 9..128 rows: N = (Hq + 2 Hkv) d features are 160-1344 blocks, so the
 // 16-bit-epilogue kernels run 120-170 workgroups (64 rows, 10240 x 8192: 46 us = 3.6 TB/s; 21504 x 7168: 78 us;
 // 32 rows, 15360 x 5120: 30 us); split over K with the planned shape they fill the chip (30, 52, 28 us).
 int gemm_qkv_splits(int M, int N, int K) {
-  if (M <= 8 || M > 64 || N % 16 || K % 32) return 0;
+  if (M <= 8 || M > kMaxDecodeRows || N % 16 || K % 32) return 0;
   const SplitPlan pl = plan_split(M, N / 16, K / 32);
   return pl.splits >= 2 ? pl.splits : 0;
 }

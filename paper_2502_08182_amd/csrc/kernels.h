@@ -77,7 +77,7 @@ hipError_t launch_gemm_skinny(int dtype, int epi, const void* W, const void* X, 
                               void* out, int M, int N, int K, hipStream_t st, int splits = 1, int flags = 0);
 int gemm_skinny_splits(int M, int N, int K);
 // Planes for a QKV projection run as EPI_PART32 (summed by the attention kernel, AttnAppend::qkv_part), or 0:
-// keep the 16-bit epilogue.  Non-zero only at 9..64 rows, where the split shape is the faster one.
+// keep the 16-bit epilogue.  Non-zero only at 9..128 rows, where the split shape is the faster one.
 int gemm_qkv_splits(int M, int N, int K);
 // Prefill path: any M.
 hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, const void* bias,

@@ -129,7 +129,7 @@ struct sn_ctx {
   uint16_t *u16 = nullptr, *qkv16 = nullptr, *attn16 = nullptr, *act16 = nullptr;
   float* part = nullptr;
   float* part32 = nullptr;       // split-K partial sums of the decode residual projections
-  float* qkv_part32 = nullptr;   // split-K partial sums of the decode QKV projection (9..64 rows), see run_layer
+  float* qkv_part32 = nullptr;   // split-K partial sums of the decode QKV projection (9..128 rows), see run_layer
   float* inv_freq = nullptr;
   int32_t* flag_dev = nullptr;   // set by the final cast of an iteration when a hidden state is not finite
   int32_t* meta_dev = nullptr;
@@ -468,8 +468,8 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   const uint64_t b_meta = align_up(c->meta_ints * 4);
   const uint64_t b_freq = align_up((uint64_t)s.head_dim / 2 * 4);
   const uint64_t b_part32 = align_up((uint64_t)kMaxSplits * std::min(s.max_batch, kMaxDecodeRows) * s.hidden * 4);
-  // a decode step of 9..64 rows may run its QKV projection split over K (gemm_qkv_splits)
-  const uint64_t b_qkv_part = s.max_batch > 8 ? align_up((uint64_t)kMaxSplits * 64 * qkv_ld * 4) : 0;
+  // a decode step of 9..128 rows may run its QKV projection split over K (gemm_qkv_splits)
+  const uint64_t b_qkv_part = s.max_batch > 8 ? align_up((uint64_t)kMaxSplits * std::min(s.max_batch, kMaxDecodeRows) * qkv_ld * 4) : 0;
   c->ws_bytes = b_x32 + b_u + b_qkv + b_attn + b_act + b_part + b_part32 + b_qkv_part + b_meta + b_freq;
 
   SN_HIP(c, hipStreamCreateWithFlags(&c->h2d, hipStreamNonBlocking));
@@ -875,7 +875,7 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, 
   SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, pending, st, pk));
   pending = Fold{};
   kt.end(SN_K_NORM);
-  // decode, 9..64 rows: the QKV projection has too few output features to give every compute unit a
+  // decode, 9..128 rows: the QKV projection has too few output features to give every compute unit a
   // workgroup, so it is split over K like the residual projections; its fp32 planes are summed by the
   // attention kernel where it picks up the step's q, k and v
   const int qkv_splits = small && c->qkv_part32 ? gemm_qkv_splits(T, p.n_qkv, h) : 0;

@@ -477,7 +477,7 @@ def test_attn_decode_with_fused_append(dtype, Hq, Hkv, d, rope):
         assert torch.equal(kv_f, kv_two), f"cache after the fused kernel differs from rope_append's (S={S})"
         assert torch.equal(mir_f, mir_two), f"mirror differs (S={S})"
         assert torch.equal(out_f, out_two), f"fused output differs from the two-kernel path (S={S})"
-        # the same step with q, k, v handed over as split-K partial planes (what a 9..64-row decode step
+        # the same step with q, k, v handed over as split-K partial planes (what a 9..128-row decode step
         # does): three planes that add up, in fp32 and in this order, to exactly the 16-bit values -- so
         # the result must not differ in a single bit; rows and planes the kernel must not read hold NaN
         q32 = torch.from_numpy(synth.widen(host16(qkv0), dtype).astype(np.float32)).cuda().reshape(B, -1)
