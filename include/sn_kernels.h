@@ -46,10 +46,10 @@ int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, c
  * stream [M][N], updated in place (+=); 3: SwiGLU -- W holds gate and up in alternating
  * 16-row blocks (N = 2*ffn rows), bias = [gate | up], out16[M][N/2] = silu(g)*u.
  * path 0: weight-streaming decode kernel (M <= 128; a packed X holds 16*ceil(M/16) rows); path 1: tiled prefill kernel.
- * flags: 1 = X is row-tile packed; 2 = the 16-bit output (epilogues 0, 1, 3) is written row-tile packed
- * (path 0 only).  Path 1 takes flag 1 only where its 192 x 256 kernel applies (N % 256 == 0, K % 256 == 0, at
- * least 2048 tiles of 192 rows x 256 features) and returns SN_E_INVAL otherwise: same result bit for bit,
- * whole cache lines per activation request instead of half ones. */
+ * flags: 1 = X is row-tile packed; 2 = the 16-bit output (epilogues 0, 1, 3) is written row-tile packed.
+ * Path 1 takes them only where its 192 x 256 kernel applies (N % 256 == 0, K % 256 == 0, at least 2048 tiles
+ * of 192 rows x 256 features) and returns SN_E_INVAL otherwise: same values bit for bit, whole cache lines per
+ * activation request instead of half ones. */
 int sn_k_gemm(int32_t dtype, int32_t epilogue, int32_t path, const void* W, const void* X,
               const void* bias, void* out, int32_t M, int32_t N, int32_t K, int32_t flags,
               void* stream);
@@ -151,11 +151,12 @@ int sn_k_attn_decode_append_planes(int32_t dtype, const float* qkv_part, int32_t
 
 #define SN_K_PREFILL_QTILE 128
 /* Causal attention of each sequence's n_new tokens over len_before+n_new keys.
- * out16 [T][Hq*d]. */
+ * out16 [T][Hq*d]; packed_out != 0: written row-tile packed (16*ceil(T/16) rows; needs Hq*d % 32 == 0). */
 int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
                       const int32_t* n_new, const int32_t* tok_start, const int32_t* kv_off,
                       const int32_t* cap, const int32_t* tile_seq, const int32_t* tile_q0,
-                      void* out16, int32_t n_qtiles, int32_t Hq, int32_t Hkv, int32_t d, void* stream);
+                      void* out16, int32_t n_qtiles, int32_t Hq, int32_t Hkv, int32_t d, int32_t packed_out,
+                      void* stream);
 
 /* 16-bit <-> fp32 residual stream conversions at the boundary of an iteration. */
 int sn_k_cast_in(int32_t dtype, const void* in16, void* x32, uint64_t n, void* stream);

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
     const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
     const int32_t* __restrict__ n_new, const int32_t* __restrict__ tok_start, const int32_t* __restrict__ kv_off,
     const int32_t* __restrict__ cap, const int32_t* __restrict__ tile_seq, const int32_t* __restrict__ tile_q0,
-    uint16_t* __restrict__ out, int Hq, int Hkv) {
+    uint16_t* __restrict__ out, int Hq, int Hkv, int packed) {
   constexpr int KT = 32;              // keys per step
   constexpr int LD = 40;              // LDS row stride (elements) of the transposed V tile: 80 B, 16 B aligned
   constexpr int LDK = D + 8;          // LDS row stride (elements) of the K tile: rows 16 B apart modulo 256 B
@@ -225,26 +225,31 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
     lj += __shfl_xor(lj, 32, 64);
     if (qok[j]) {
       const float inv = 1.0f / lj;
-      uint16_t* op = out + (size_t)(tok_start[b] + qi[j]) * Hq * D + (size_t)hq * D + g * 4;
+      const int tok = tok_start[b] + qi[j];
+      uint16_t* op = out + (size_t)tok * Hq * D + (size_t)hq * D + g * 4;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         u16x4 w;
 #pragma unroll
         for (int i = 0; i < 4; ++i) w[i] = from_f32<T>(o[j][dt][i] * inv);
-        *reinterpret_cast<u16x4*>(op + dt * 16) = w;
+        if (packed)       // row-tile packed (feeds the output projection): 16 tokens x 16 bytes are contiguous
+          *reinterpret_cast<u16x4*>(out + packed_off(tok, hq * D + dt * 16 + g * 4, (Hq * D) >> 5)) = w;
+        else
+          *reinterpret_cast<u16x4*>(op + dt * 16) = w;
       }
     }
   }
 }
 
 hipError_t launch_attn_prefill(int dtype, const void* qkv16, const void* kv, const StepIndex& ix, void* out16,
-                               int n_qtiles, int Hq, int Hkv, int d, hipStream_t st) {
+                               int n_qtiles, int Hq, int Hkv, int d, hipStream_t st, int packed) {
   if (n_qtiles <= 0) return hipSuccess;
+  if (packed && (Hq * d) % 32) return hipErrorInvalidValue;
   dim3 grid(n_qtiles, Hq), block(256);
 #define SN_PREFILL(TT, DD)                                                                                    \
   SN_LAUNCH((attn_prefill_kernel<TT, DD>), grid, block, 0, st, (const uint16_t*)qkv16,               \
                      (const uint16_t*)kv, ix.len_before, ix.n_new, ix.tok_start, ix.kv_off, ix.cap, ix.tile_seq, \
-                     ix.tile_q0, (uint16_t*)out16, Hq, Hkv)
+                     ix.tile_q0, (uint16_t*)out16, Hq, Hkv, packed)
   if (dtype == 0 && d == 64) SN_PREFILL(F16, 64);
   else if (dtype == 0 && d == 128) SN_PREFILL(F16, 128);
   else if (dtype == 1 && d == 64) SN_PREFILL(BF16, 64);

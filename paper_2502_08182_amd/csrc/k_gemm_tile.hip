@@ -398,7 +398,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <class T, int EPI, int TI>   // TI: 16-token tiles per workgroup
 __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
     const uint16_t* __restrict__ W, const uint16_t* __restrict__ X, const uint16_t* __restrict__ bias,
-    void* __restrict__ out, int M, int N, int K, int NT, int TT, int CB, int xpacked) {
+    void* __restrict__ out, int M, int N, int K, int NT, int TT, int CB, int xpacked, int opacked) {
   constexpr int BM = TI * 16;             // tokens per workgroup
   constexpr int XT = TI / 4;              // token tiles each wavefront stages per k step
   constexpr int FJ = 4;                   // 16-feature blocks per wavefront
@@ -636,8 +636,23 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
   __syncthreads();
   constexpr int PIECES = OW / 8;                       // 16-byte pieces per token row
   constexpr int RPP = 256 / PIECES;                    // token rows per pass of the workgroup
-  const int q = threadIdx.x % PIECES, r0 = threadIdx.x / PIECES;
   const int ON = DUAL ? N >> 1 : N;
+  if (opacked) {
+    // row-tile packed output (it feeds another projection): a wavefront writes one 16-token x 32-feature tile,
+    // 1 KiB contiguous, per pass -- lane = token % 16 + 16 * (16-byte piece of the tile)
+    constexpr int PT = PIECES / 4;                     // 32-feature tiles across the workgroup's features
+    uint16_t* og = static_cast<uint16_t*>(out);
+    const int tk = lane & 15, pc = lane >> 4;
+#pragma unroll 4
+    for (int tix = wave; tix < TI * PT; tix += 4) {
+      const int tok = (tix / PT) * 16 + tk, q = (tix % PT) * 4 + pc;
+      u16x8 v = *reinterpret_cast<const u16x8*>(ob + (size_t)tok * OW + ((q ^ (tk >> 1)) << 3));
+      if (tk & 1) v = u16x8{v[4], v[5], v[6], v[7], v[0], v[1], v[2], v[3]};
+      if (t0 + tok < M) *reinterpret_cast<u16x8*>(og + packed_off(t0 + tok, tn * OW + q * 8, ON >> 5)) = v;
+    }
+    return;
+  }
+  const int q = threadIdx.x % PIECES, r0 = threadIdx.x / PIECES;
   uint16_t* og = static_cast<uint16_t*>(out) + (size_t)tn * OW + q * 8;
 #pragma unroll 4
   for (int tok = r0; tok < BM; tok += RPP) {
@@ -650,7 +665,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
 
 template <class T>
 static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out, int M,
-                           int N, int K, int xpacked, hipStream_t st) {
+                           int N, int K, int xpacked, int opacked, hipStream_t st) {
   constexpr int TI = kBigTileTokenTiles;
   if (N % 256 == 0 && K % (32 * kBigTileRing) == 0 &&
       (int64_t)(N / 256) * ((M + TI * 16 - 1) / (TI * 16)) >= kBigTileMinTiles) {
@@ -658,23 +673,23 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
     dim3 grid(NT * TT), block(256);
     switch (epi) {
       case EPI_STORE16:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_STORE16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_STORE16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked, opacked);
         break;
       case EPI_GELU16:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_GELU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_GELU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked, opacked);
         break;
       case EPI_RESID32:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_RESID32, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_RESID32, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked, opacked);
         break;
       case EPI_SWIGLU16:
-        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_SWIGLU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked);
+        SN_LAUNCH((gemm_tile_big_kernel<T, EPI_SWIGLU16, TI>), grid, block, 0, st, W, X, bias, out, M, N, K, NT, TT, CB, xpacked, opacked);
         break;
       default:
         return hipErrorInvalidValue;
     }
     return hipGetLastError();
   }
-  if (xpacked) return hipErrorInvalidValue;
+  if (xpacked || opacked) return hipErrorInvalidValue;
   if (N % 256 == 0 && K % 64 == 0) {
     const int NT = N / 256, TT = (M + 127) / 128, CB = tile_group(NT, K);
     dim3 grid(NT * TT), block(256);
@@ -720,10 +735,19 @@ hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, co
                             int N, int K, hipStream_t st, int flags) {
   if (M <= 0) return hipSuccess;
   if (N % 16 || K % 32 || (epi == EPI_SWIGLU16 && N % 32)) return hipErrorInvalidValue;
-  const int xpacked = flags & kXPacked ? 1 : 0;
+  const int xpacked = flags & kXPacked ? 1 : 0, opacked = flags & kOutPacked ? 1 : 0;
+  if (opacked && (epi == EPI_RESID32 || (epi == EPI_SWIGLU16 ? (N / 2) % 32 : N % 32))) return hipErrorInvalidValue;
   if (dtype == 0)
-    return launch_t<F16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, xpacked, st);
-  return launch_t<BF16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, xpacked, st);
+    return launch_t<F16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, xpacked, opacked, st);
+  return launch_t<BF16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, xpacked, opacked, st);
+}
+
+// Whether launch_gemm_tile would run this shape on the 192 x 256 kernel, the one that reads and writes row-tile
+// packed activations.
+bool gemm_tile_takes_packed(int M, int N, int K) {
+  constexpr int TI = kBigTileTokenTiles;
+  return M > 0 && N % 256 == 0 && K % (32 * kBigTileRing) == 0 &&
+         (int64_t)(N / 256) * ((M + TI * 16 - 1) / (TI * 16)) >= kBigTileMinTiles;
 }
 
 }  // namespace sn

@@ -36,7 +36,7 @@ extern "C" int sn_k_gemm(int32_t dtype, int32_t epi, int32_t path, const void* W
   if (bad_dtype(dtype) || !W || !X || !out || M < 0 || N < 16 || K < 32 || epi < 0 || epi > 3 || flags < 0 || flags > 3)
     return SN_E_INVAL;
   if (path == 0) return rc_of(launch_gemm_skinny(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream, 1, flags));
-  if (path == 1 && (flags & ~1) == 0) return rc_of(launch_gemm_tile(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream, flags));
+  if (path == 1) return rc_of(launch_gemm_tile(dtype, epi, W, X, bias, out, M, N, K, (hipStream_t)stream, flags));
   return SN_E_INVAL;
 }
 
@@ -125,7 +125,7 @@ extern "C" int sn_k_attn_decode_append_planes(int32_t dtype, const float* qkv_pa
 extern "C" int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
                                  const int32_t* n_new, const int32_t* tok_start, const int32_t* kv_off,
                                  const int32_t* cap, const int32_t* tile_seq, const int32_t* tile_q0, void* out16,
-                                 int32_t n_qtiles, int32_t Hq, int32_t Hkv, int32_t d, void* stream) {
+                                 int32_t n_qtiles, int32_t Hq, int32_t Hkv, int32_t d, int32_t packed_out, void* stream) {
   if (bad_dtype(dtype) || !qkv16 || !kv || !len_before || !n_new || !tok_start || !kv_off || !cap || !tile_seq ||
       !tile_q0 || !out16 || n_qtiles < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv || (d != 64 && d != 128))
     return SN_E_INVAL;
@@ -137,7 +137,7 @@ extern "C" int sn_k_attn_prefill(int32_t dtype, const void* qkv16, const void* k
   ix.cap = cap;
   ix.tile_seq = tile_seq;
   ix.tile_q0 = tile_q0;
-  return rc_of(launch_attn_prefill(dtype, qkv16, kv, ix, out16, n_qtiles, Hq, Hkv, d, (hipStream_t)stream));
+  return rc_of(launch_attn_prefill(dtype, qkv16, kv, ix, out16, n_qtiles, Hq, Hkv, d, (hipStream_t)stream, packed_out != 0));
 }
 
 extern "C" int sn_k_cast_in(int32_t dtype, const void* in16, void* x32, uint64_t n, void* stream) {

@@ -82,6 +82,7 @@ int gemm_qkv_splits(int M, int N, int K);
 // Prefill path: any M.
 hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, const void* bias,
                             void* out, int M, int N, int K, hipStream_t st, int flags = 0);
+bool gemm_tile_takes_packed(int M, int N, int K);   // the 192 x 256 kernel applies: flags kXPacked / kOutPacked allowed
 
 // Rotates q (in place) and k, and appends k, v rows to the layer's KV slice
 // ([seq][Hkv][K|V][cap][d]); mirror (may be null) is a second copy of the slice that
@@ -114,6 +115,6 @@ hipError_t launch_attn_decode(int dtype, const void* qkv16, const void* kv, cons
                               hipStream_t st, int packed_out = 0, const AttnAppend* append = nullptr);
 // Causal attention of each sequence's new tokens over its cached + new keys.
 hipError_t launch_attn_prefill(int dtype, const void* qkv16, const void* kv, const StepIndex& ix,
-                               void* out16, int n_qtiles, int Hq, int Hkv, int d, hipStream_t st);
+                               void* out16, int n_qtiles, int Hq, int Hkv, int d, hipStream_t st, int packed = 0);
 
 }  // namespace sn

@@ -856,15 +856,21 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, 
   // decode: activations between kernels are row-tile packed (inputs of the skinny GEMMs);
   // the QKV output stays row-major for the attention kernels
   const int pk = small ? 1 : 0;
-  auto gemm = [&](int epi, const void* W, const void* X, const void* bias, void* out, int N, int K, bool out_feeds_gemm) {
+  // prefill: a projection that runs on the 192 x 256 kernel reads its activations row-tile packed too (whole cache
+  // lines per request), so whoever produces them writes that layout -- the norms, the attention kernel, and the FFN
+  // up-projection when it is itself such a launch
+  const bool pk_qkv = !small && gemm_tile_takes_packed(T, p.n_qkv, h), pk_up = !small && gemm_tile_takes_packed(T, p.n_up, h);
+  const bool pk_o = !small && gemm_tile_takes_packed(T, h, qd), pk_down = pk_up && gemm_tile_takes_packed(T, h, F);
+  auto gemm = [&](int epi, const void* W, const void* X, const void* bias, void* out, int N, int K, bool out_feeds_gemm,
+                  bool x_packed, bool out_packed) {
     return small ? launch_gemm_skinny(dt, epi, W, X, bias, out, T, N, K, st, 1,
                                       kXPacked | (out_feeds_gemm ? kOutPacked : 0))
-                 : launch_gemm_tile(dt, epi, W, X, bias, out, T, N, K, st);
+                 : launch_gemm_tile(dt, epi, W, X, bias, out, T, N, K, st, (x_packed ? kXPacked : 0) | (out_packed ? kOutPacked : 0));
   };
   // residual projection: decode writes split-K partials (folded in by the next norm / cast),
   // prefill adds into the residual stream in its epilogue
-  auto resid_gemm = [&](const void* W, const void* X, const void* bias, int K) -> hipError_t {
-    if (!small) return launch_gemm_tile(dt, EPI_RESID32, W, X, bias, c->x32, T, h, K, st);
+  auto resid_gemm = [&](const void* W, const void* X, const void* bias, int K, bool x_packed) -> hipError_t {
+    if (!small) return launch_gemm_tile(dt, EPI_RESID32, W, X, bias, c->x32, T, h, K, st, x_packed ? kXPacked : 0);
     const int sp = gemm_skinny_splits(T, h, K);
     pending.part = c->part32;
     pending.nsplit = sp;
@@ -872,7 +878,7 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, 
     return launch_gemm_skinny(dt, EPI_PART32, W, X, bias, c->part32, T, h, K, st, sp, kXPacked);
   };
   kt.begin(SN_K_NORM);
-  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, pending, st, pk));
+  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n1g), at(p.n1b), c->u16, T, h, s.norm_eps, pending, st, pk | (pk_qkv ? 1 : 0)));
   pending = Fold{};
   kt.end(SN_K_NORM);
   // decode, 9..128 rows: the QKV projection has too few output features to give every compute unit a
@@ -883,14 +889,14 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, 
   if (qkv_splits)
     SN_HIP(c, launch_gemm_skinny(dt, EPI_PART32, at(p.wqkv), c->u16, at(p.bqkv), c->qkv_part32, T, p.n_qkv, h, st, qkv_splits, kXPacked));
   else
-    SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h, false));
+    SN_HIP(c, gemm(EPI_STORE16, at(p.wqkv), c->u16, at(p.bqkv), c->qkv16, p.n_qkv, h, false, pk_qkv, false));
   kt.end(SN_K_QKV);
   if (prefill) {
     kt.begin(SN_K_ROPE_APPEND);
     SN_HIP(c, launch_rope_append(dt, dt, c->qkv16, ix, kv, mirror_kv, c->inv_freq, T, Hq, Hkv, d, s.rope, st));
     kt.end(SN_K_ROPE_APPEND);
     kt.begin(SN_K_ATTN);
-    SN_HIP(c, launch_attn_prefill(dt, c->qkv16, kv, ix, c->attn16, n_qtiles, Hq, Hkv, d, st));
+    SN_HIP(c, launch_attn_prefill(dt, c->qkv16, kv, ix, c->attn16, n_qtiles, Hq, Hkv, d, st, pk_o ? 1 : 0));
     kt.end(SN_K_ATTN);
   } else {
     // decode: rotation and KV append are done by the attention kernel itself
@@ -905,17 +911,17 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, 
     kt.end(SN_K_ATTN);
   }
   kt.begin(SN_K_OPROJ);
-  SN_HIP(c, resid_gemm(at(p.wo), c->attn16, at(p.bo), qd));
+  SN_HIP(c, resid_gemm(at(p.wo), c->attn16, at(p.bo), qd, pk_o));
   kt.end(SN_K_OPROJ);
   kt.begin(SN_K_NORM);
-  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n2g), at(p.n2b), c->u16, T, h, s.norm_eps, pending, st, pk));
+  SN_HIP(c, launch_norm_fold(dt, s.norm == SN_NORM_LN, c->x32, at(p.n2g), at(p.n2b), c->u16, T, h, s.norm_eps, pending, st, pk | (pk_up ? 1 : 0)));
   pending = Fold{};
   kt.end(SN_K_NORM);
   kt.begin(SN_K_FFN_UP);
-  SN_HIP(c, gemm(s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup), c->act16, p.n_up, h, true));
+  SN_HIP(c, gemm(s.act == SN_ACT_SWIGLU ? EPI_SWIGLU16 : EPI_GELU16, at(p.wup), c->u16, at(p.bup), c->act16, p.n_up, h, true, pk_up, pk_down));
   kt.end(SN_K_FFN_UP);
   kt.begin(SN_K_FFN_DOWN);
-  SN_HIP(c, resid_gemm(at(p.wd), c->act16, at(p.bd), F));
+  SN_HIP(c, resid_gemm(at(p.wd), c->act16, at(p.bd), F, pk_down));
   kt.end(SN_K_FFN_DOWN);
   return SN_OK;
 }

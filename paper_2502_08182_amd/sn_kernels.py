@@ -34,7 +34,7 @@ def _lib():
             "sn_k_attn_decode_static": [i32, v, v, v, v, v, v, i32, i32, i32, i32, i32, i32, i32, v],
             "sn_k_attn_decode_append": [i32, v, v, v, v, i32, v, v, v, v, v, i32, i32, i32, i32, i32, i32, i32, v],
             "sn_k_attn_decode_append_planes": [i32, v, i32, i32, v, v, v, i32, v, v, v, v, v, i32, i32, i32, i32, i32, i32, i32, v],
-            "sn_k_attn_prefill": [i32, v, v, v, v, v, v, v, v, v, v, i32, i32, i32, i32, v],
+            "sn_k_attn_prefill": [i32, v, v, v, v, v, v, v, v, v, v, i32, i32, i32, i32, i32, v],
             "sn_k_cast_in": [i32, v, v, u64, v],
             "sn_k_cast_out": [i32, v, v, u64, v],
             "sn_k_copy": [v, v, u64, v],
@@ -134,9 +134,10 @@ def sn_k_attn_decode_append_planes(dtype, qkv_part, splits, plane_rows, kv, mirr
 
 
 def sn_k_attn_prefill(dtype, qkv16, kv, len_before, n_new, tok_start, kv_off, cap, tile_seq, tile_q0, out16,
-                      n_qtiles, Hq, Hkv, d, stream=0):
+                      n_qtiles, Hq, Hkv, d, packed_out=0, stream=0):
     _chk(_lib().sn_k_attn_prefill(dtype, _p(qkv16), _p(kv), _p(len_before), _p(n_new), _p(tok_start), _p(kv_off),
-                                  _p(cap), _p(tile_seq), _p(tile_q0), _p(out16), n_qtiles, Hq, Hkv, d, stream))
+                                  _p(cap), _p(tile_seq), _p(tile_q0), _p(out16), n_qtiles, Hq, Hkv, d, packed_out,
+                                  stream))
 
 
 def sn_k_cast_in(dtype, in16, x32, n, stream=0):

@@ -347,6 +347,12 @@ def test_gemm_tile_large_m_packed_activations(epi):
         outs.append(out)
     assert torch.equal(outs[0], outs[1])
     assert bool(torch.isfinite(outs[1].float()).all()) if epi == K.EPI_RESID32 else bool((outs[1] != 0x7e00).any())
+    if epi != K.EPI_RESID32:            # the 16-bit output written row-tile packed as well (it feeds the next projection)
+        Mp = (M + 15) // 16 * 16
+        outp = torch.zeros(Mp * N, dtype=torch.int16, device="cuda")
+        K.sn_k_gemm(DT["f16"], epi, K.PATH_TILE, dev16(tiled), dev16(K.pack_rows(xb)), None, outp, M, N * wide, Kd, 3)
+        torch.cuda.synchronize()
+        assert np.array_equal(K.unpack_rows(host16(outp), M, N), host16(outs[0]))
     with pytest.raises(sn.SnError):     # 128 x 256 kernel (fewer than 2048 tiles): row-major only
         K.sn_k_gemm(DT["f16"], epi, K.PATH_TILE, dev16(tiled), dev16(K.pack_rows(xb[:640])), None, outs[1], 640, N * wide, Kd, 1)
 
@@ -522,6 +528,12 @@ def test_attn_prefill(dtype, Hq, Hkv, d, rope):
     torch.cuda.synchronize()
     want, *_ = _oracle_attention(dtype, qkv, Kc, Vc, lens_before, n_new, tok_start, Hq, Hkv, d, rope)
     check(synth.widen(host16(out), dtype), want, dtype, "attn_prefill", per_row=True, bar=C_ATTN[dtype])
+    # the same launch writing its output row-tile packed (what feeds a packed output projection)
+    outp = torch.zeros((T + 15) // 16 * 16 * Hq * d, dtype=torch.int16, device="cuda")
+    K.sn_k_attn_prefill(DT[dtype], dv["qkv"], dv["kv"], dv["len_before"], dv["n_new"], dv["tok_start"], dv["kv_off"],
+                        dv["cap"], i32(tile_seq), i32(tile_q0), outp, len(tile_seq), Hq, Hkv, d, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(K.unpack_rows(host16(outp), T, Hq * d), host16(out))
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
