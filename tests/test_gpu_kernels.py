@@ -679,6 +679,18 @@ def test_packed_activation_layout_through_norm_gemm_and_attention(dtype):
             torch.cuda.synchronize()
             assert np.array_equal(host16(a), host16(ref))
             assert np.array_equal(K.unpack_rows(host16(b), M, N), host16(ref))
+    # many rows (a prefill's norm): the packed writer walks the rows tile by tile within an XCD; ragged row count
+    for M, h in ((1000, 416), (2051, 1024)):
+        x = (rng.standard_normal((M, h)) * 2).astype(np.float32)
+        g = synth.to_bits(1 + 0.1 * rng.standard_normal(h), dtype)
+        u_row = torch.zeros(M, h, dtype=torch.int16, device="cuda")
+        u_pk = torch.full(((M + 15) // 16 * 16 * h,), 0x7e00, dtype=torch.int16, device="cuda")
+        xd = torch.from_numpy(x).cuda()
+        K.sn_k_norm_fold(DT[dtype], False, xd, dev16(g), None, u_row, M, h, 1e-5, None, 0, None, 0)
+        K.sn_k_norm_fold(DT[dtype], False, xd, dev16(g), None, u_pk, M, h, 1e-5, None, 0, None, 1)
+        torch.cuda.synchronize()
+        assert np.array_equal(K.unpack_rows(host16(u_pk), M, h), host16(u_row))
+        assert np.array_equal(xd.cpu().numpy(), x)                    # no fold: the fp32 rows are left alone
     # decode attention writing packed output
     Hq, Hkv, d = 8, 2, 128
     lens_before = [5, 300, 0]
