@@ -211,7 +211,11 @@ int sn_placement_sched(int32_t L, int32_t N, int32_t schedule, uint8_t* offloade
 
 /* --- KV cache ------------------------------------------------------------------
  * Start a new set of sequences: per-sequence capacities in tokens (host, [batch]);
- * sum must fit max_batch*max_seq.  All lengths become 0. */
+ * sum must fit max_batch*max_seq.  All lengths become 0.  sn_step enforces the capacities
+ * given here; the slice of a sequence may be laid out with 8 rows more where the context
+ * has the room (a row count whose head-to-head stride, rows * head_dim * 4 bytes, is a
+ * multiple of 2^19 + 2^12 bytes makes every attention workgroup hit the same memory channel
+ * at the same time: less than half the bandwidth). */
 int sn_kv_reset(sn_ctx* ctx, int32_t batch, const int32_t* capacity);
 
 /* Shorten the cached sequences: len (host, [batch]) gives the new token counts, none larger than

@@ -99,7 +99,10 @@ int sn_k_rope_append(int32_t dtype, int32_t kv_value_dtype, void* qkv16, const i
  * appended first).  out16 [B][Hq*d].  splits S >= 1 key ranges; part: fp32 scratch
  * [B][Hq][S][d+2] (may be NULL when S == 1).  S == 0: the library's own choice for
  * max_len = max_b(len_before[b]) + 1, which must then be given.  packed_out != 0: out16
- * is written row-tile packed (K = Hq*d). */
+ * is written row-tile packed (K = Hq*d).  Performance note on the cap array: capacities for
+ * which cap[b] * d * 4 bytes is a multiple of 2^19 + 2^12 (1032 rows at d = 128) put every
+ * (sequence, KV head) region on the same memory channels at the same time and run at less than
+ * half speed; sn_kv_reset lays such sequences out with 8 rows more. */
 int sn_k_attn_decode(int32_t dtype, const void* qkv16, const void* kv, const int32_t* len_before,
                      const int32_t* kv_off, const int32_t* cap, void* out16, float* part, int32_t B,
                      int32_t Hq, int32_t Hkv, int32_t d, int32_t S, int32_t max_len,

@@ -555,19 +555,12 @@ __global__ __launch_bounds__(256, 2) void attn_decode_gqa128_kernel(
 #pragma unroll
   for (int e = 0; e < 8; ++e) o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // The range is walked in rounds of NW tiles, one per wavefront (so the workgroup reads NW * 8 KiB of K and of V
-  // side by side); every workgroup starts at a different round and wraps around.  All workgroups stream regions of
-  // the same size at the same pace, and when the stride between regions maps them onto few memory channels they
-  // would hit those channels in lock-step (8 x 32 heads with room for 1032 keys each, stride 516 KiB: 2.3 TB/s without the
-  // rotation, 5.2 with; other sizes lose 1-3 % to it).
-  // A wavefront's tile of the last round may lie past the end: clamped loads, every score masked.
+  // The range is walked in rounds of NW tiles, one per wavefront (the workgroup reads NW * 8 KiB of K and of V side
+  // by side).  A wavefront's tile of the last round may lie past the end: clamped loads, every score masked.
+  // (Starting every workgroup at a different round was tried against the one stride at which all workgroups hit
+  // the same memory channel in lock-step; it cost 3-9 % everywhere else, and the layout now avoids that stride.)
   const int nrounds = j1 > j0 ? (j1 - j0 + NW * 32 - 1) / (NW * 32) : 0;
-  const int rot = nrounds > 0 ? (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)nrounds) : 0;
-  auto tile_at = [&](int i) {         // this wavefront's tile of the i-th round of the walk; past the last round: that one again
-    int k = min(i, nrounds - 1) + rot;
-    if (k >= nrounds) k -= nrounds;
-    return j0 + (wave + NW * k) * 32;
-  };
+  auto tile_at = [&](int i) { return j0 + (wave + NW * min(i, nrounds - 1)) * 32; };   // past the last round: that one again
   if (nrounds > 0) {
     issue_k(tile_at(0));
     issue_v(tile_at(0));

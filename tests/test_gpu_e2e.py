@@ -240,6 +240,31 @@ def test_replacing_between_iterations_keeps_the_cache(c1):
     assert np.array_equal(np.stack(outs), ref[1])
 
 
+def test_capacity_at_the_resonant_stride_is_laid_out_with_spare_rows(c1):
+    """A per-sequence capacity whose head-to-head stride (rows x head_dim x 4 bytes) is a multiple of 2^19 + 2^12 bytes
+    -- 2064 rows at head dimension 64 -- gets 8 spare rows in the layout (all attention workgroups would otherwise hit
+    one memory channel in lock-step).  Nothing else changes: outputs are those of any other capacity, bit for bit, with
+    KV slices on the host as well, and the capacity the caller gave is still the limit a step may fill."""
+    w, layers, prompt, table, *_ = c1
+    assert w.shape.head_dim == 64
+    ref = gpu_run(w, layers, prompt, table, 0)
+    for N in (0, 2):
+        with Session(w.shape, w.batch, 2100) as se:
+            se.load_synthetic_weights(layers=layers)
+            se.place(N)
+            se.kv_reset([2064] * w.batch)
+            pre = se.step(list(w.prompt_lens), True, prompt)
+            outs = [se.step([1] * w.batch, False, table[t]) for t in range(w.decode_steps)]
+            assert np.array_equal(pre, ref[0]) and np.array_equal(np.stack(outs), ref[1])
+            # fill the sequences up to their capacity, then one token more must be refused
+            room = [2064 - (p + w.decode_steps) for p in w.prompt_lens]
+            filler = synth.to_bits(np.random.default_rng(3).standard_normal((sum(room), w.shape.hidden)), w.shape.dtype)
+            se.step(room, True, filler)
+            with pytest.raises(sn.SnError) as e:
+                se.step([1] * w.batch, False, table[0])
+            assert e.value.code == sn.SN_E_INVAL
+
+
 def test_weights_may_arrive_after_placement(c1):
     """A model larger than the host's pinned memory is loaded after sn_place: GPU-resident
     layers then have no host master until they are first offloaded (the master is copied
