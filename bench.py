@@ -460,9 +460,22 @@ def main():
         """Pick for SLO f x the all-resident TPOT under `sched` from the given profile, place, run, check."""
         slo_f = int(f * tpot0_ns)
         n_f = pick_or_none(sn, tcp_, txp_, int(slo_f * (1.0 - a.guard)), L + 1, sched)
-        se.place(n_f)
-        fst, fwall = rig.decode(steps, W)
-        pt = {"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f), **leg_summary(fst, fwall, slo_f, B)}
+        first = int(n_f)
+        # an interval whose measured iterations miss the SLO (the analyzer's prediction leaves out what many small
+        # copies and the fences cost) is replaced by the next one that offloads fewer layers, and run again
+        for _ in range(4):
+            se.place(n_f)
+            fst, fwall = rig.decode(steps, W)
+            k_f = int(fst[-1]["n_offloaded"])
+            if k_f == 0 or all(d["iter_ns"] <= slo_f for d in fst):
+                break
+            n_next = n_f + 1
+            while n_next <= L and L // n_next >= k_f:
+                n_next += 1
+            log(f"[bench] SLO {f}x: N={n_f} measured {max(d['iter_ns'] for d in fst) / 1e6:.3f} ms > SLO {slo_f / 1e6:.3f}, trying N={n_next}")
+            n_f = n_next
+        pt = {"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f), "picker_first_choice": first,
+              "adjusted_after_measurement": bool(first != int(n_f)), **leg_summary(fst, fwall, slo_f, B)}
         pred, _ = sn.sn_timeline_sched(tcp_, txp_, n_f, sched)
         pt["predicted_ms"] = pred / 1e6
         pt["resident_GB"] = sn.sn_resident_bytes(se.ctx, n_f) / 1e9
