@@ -128,11 +128,11 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
 // ---------------------------------------------------------------------------------
 // Workgroup id -> output tile, XCD-aware.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs, each
 // with its own L2.  An XCD gets a contiguous band of NT/8 feature tiles and walks it in groups of CB feature tiles:
-// inside a group, token tile by token tile.  The ~32-64 workgroups an XCD runs at once are then about 32/CB token
-// tiles x CB feature tiles: the CB workgroups of a token tile share its activations in that L2, and the weights of
-// the 8 groups in progress (8 x CB x 256 x K x 2 bytes, chosen to be at most half of the 256 MB memory-side cache)
-// stay in that cache for all the token tiles, instead of being streamed from HBM once per token tile (what a group as
-// wide as the whole band does when the band's weights exceed the cache: 57344 x 8192 re-read 683 times at 131072 rows).
+// inside a group, token tile by token tile.  The ~32 workgroups an XCD runs at once are then about 32/CB token
+// tiles x CB feature tiles: the CB workgroups of a token tile share its activations in that L2, the token tiles of
+// a group share its weights, and only the weights of the 8 groups in progress are live in the memory-side cache
+// (a group as wide as the whole band streams the band's weights once per token tile when they exceed that cache:
+// 57344 x 8192 re-read 683 times at 131072 rows).
 __device__ __forceinline__ void tile_of(int id, int NT, int TT, int CB, int& tn, int& tt) {
   if (NT % 8 == 0) {
     const int xcd = id & 7, j = id >> 3, band = NT >> 3;
@@ -146,11 +146,26 @@ __device__ __forceinline__ void tile_of(int id, int NT, int TT, int CB, int& tn,
   }
 }
 
-// Feature tiles per group for tile_of: the largest divisor of the band whose 8 groups' weights fit half the memory-side
-// cache, but two where the band allows it (two feature tiles per token tile halve the activation reads, which pays even
-// when the weights overflow: 8192 x 28672 at 65536 rows, 1.04 -> 1.10 PFLOP/s).  Measured at 65536 rows, 57344 x 8192
-// (band 28): whole band 0.905, groups of 7 1.08, of 4 1.14, of 2 1.12, of 1 1.09 PFLOP/s.
-static int tile_group(int NT, int K) {
+// Feature tiles per group for tile_of in the 192 x 256 kernel.  An XCD runs about 32 workgroups at once: 32/d token tiles x d feature tiles,
+// which fetch (32/d) x 192 + d x 256 operand rows per k step between them; the divisor d of the band that makes this
+// smallest wins, whether or not the weights of the 8 groups then fit the memory-side cache.  Measured at 131072 rows:
+// 57344 x 8192 (band 28) d = 4: 106 ms, 7: 107, 2: 109, 14: 112, 1: 120, 28: 128; 8192 x 28672 (band 4) d = 4: 52.3,
+// 2: 54.1, 1: 60.0; 10240 x 8192 (band 5) d = 5: 19.0, 1: 20.0.
+static int tile_group(int NT) {
+  if (NT % 8) return 1;
+  const int band = NT / 8;
+  int cb = 1;
+  long best = 32 * 192 + 256;
+  for (int d = 2; d <= band && d <= 32; ++d) {
+    const long rows = (32l * 192 + d - 1) / d + 256l * d;
+    if (band % d == 0 && rows < best) best = rows, cb = d;
+  }
+  return cb;
+}
+
+// The 128 x 256 kernel (two workgroups per CU, at most a few thousand tiles) keeps the rule it was tuned with: the
+// largest divisor of the band whose 8 groups' weights fit half the memory-side cache, but two where the band allows it.
+static int tile_group_lds(int NT, int K) {
   if (NT % 8) return 1;
   const int band = NT / 8;
   const long most = std::max(2l, (128l << 20) / (8l * 256 * K * 2));
@@ -669,7 +684,7 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
   constexpr int TI = kBigTileTokenTiles;
   if (N % 256 == 0 && K % (32 * kBigTileRing) == 0 &&
       (int64_t)(N / 256) * ((M + TI * 16 - 1) / (TI * 16)) >= kBigTileMinTiles) {
-    const int NT = N / 256, TT = (M + TI * 16 - 1) / (TI * 16), CB = tile_group(NT, K);
+    const int NT = N / 256, TT = (M + TI * 16 - 1) / (TI * 16), CB = tile_group(NT);
     dim3 grid(NT * TT), block(256);
     switch (epi) {
       case EPI_STORE16:
@@ -691,7 +706,7 @@ static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const 
   }
   if (xpacked || opacked) return hipErrorInvalidValue;
   if (N % 256 == 0 && K % 64 == 0) {
-    const int NT = N / 256, TT = (M + 127) / 128, CB = tile_group(NT, K);
+    const int NT = N / 256, TT = (M + 127) / 128, CB = tile_group_lds(NT, K);
     dim3 grid(NT * TT), block(256);
     switch (epi) {
       case EPI_STORE16:
