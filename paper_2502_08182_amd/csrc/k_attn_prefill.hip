@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill128_kernel(
     const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ kv, const int32_t* __restrict__ len_before,
     const int32_t* __restrict__ n_new, const int32_t* __restrict__ tok_start, const int32_t* __restrict__ kv_off,
     const int32_t* __restrict__ cap, const int32_t* __restrict__ tile_seq, const int32_t* __restrict__ tile_q0,
-    uint16_t* __restrict__ out, int Hq, int Hkv, int packed) {
+    uint16_t* __restrict__ out, int Hq, int Hkv, int packed, int n_qtiles) {
   constexpr int D = 128;
   constexpr int KT = 64;              // keys per step
   constexpr int RSK = D + 8;          // K tile row stride (elements)
@@ -288,11 +288,22 @@ __global__ __launch_bounds__(256, 2) void attn_prefill128_kernel(
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qc = lane & 31, half = lane >> 5;
-  const int tile = gridDim.x - 1 - blockIdx.x;           // longest tiles first
+  // Workgroup id -> (query tile, head).  Work items are numbered KV head by KV head, inside a KV head tile by tile from
+  // the back of the list (tiles are listed per sequence with the first query rising: the longest of a sequence come
+  // first, the short ones of the first sequence fill the end of the launch), inside a tile over the query heads that
+  // share the KV head.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs; XCD x takes the x-th
+  // eighth of that numbering in order, so the ~64 workgroups it runs at once are neighbouring tiles and heads of one
+  // (sequence, KV head) and find its K and V in that XCD's L2 (numbered head-major, tile-fastest, the workgroups in
+  // flight covered every sequence at once and four K / V reads out of five missed the L2).
+  const int G = Hq / Hkv;
+  const int n_items = n_qtiles * Hq, chunk = (n_items + 7) >> 3;
+  const int item = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+  if (item >= n_items) return;
+  const int hk = item / (n_qtiles * G), rem = item - hk * (n_qtiles * G);
+  const int tile = n_qtiles - 1 - rem / G;
+  const int hq = hk * G + rem % G;
   const int b = tile_seq[tile];
   const int q0 = tile_q0[tile];
-  const int hq = blockIdx.y;
-  const int hk = hq / (Hq / Hkv);
   const int nn = n_new[b];
   const int lb = len_before[b];
   const int total = lb + nn;
@@ -344,17 +355,21 @@ __global__ __launch_bounds__(256, 2) void attn_prefill128_kernel(
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int key = j0 + 4 * vkg + i;
-      R.v[i] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};                      // rows past the end must not carry NaN into 0 * v
-      if (key < total) R.v[i] = *reinterpret_cast<const u16x8*>(Vb + (size_t)key * D + vdc * 8);
+      const int key = min(j0 + 4 * vkg + i, total - 1);
+      R.v[i] = *reinterpret_cast<const u16x8*>(Vb + (size_t)key * D + vdc * 8);
     }
   };
-  auto lstore = [&](int buf, const Stage& R) {
+  auto lstore = [&](int buf, int j0, const Stage& R) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) *reinterpret_cast<u16x8*>(&ks[buf][(krow + 16 * i) * RSK + kch * 8]) = R.k[i];
     u32x4 w[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) w[i] = __builtin_bit_cast(u32x4, R.v[i]);
+    if (j0 + KT > total) {                               // rows past the end must not carry NaN into 0 * v
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (j0 + 4 * vkg + i >= total) w[i] = u32x4{0, 0, 0, 0};
+    }
 #pragma unroll
     for (int mm = 0; mm < 4; ++mm) {
       // dword mm of each key holds d = 2 mm (low half) and 2 mm + 1 (high half)
@@ -443,17 +458,18 @@ __global__ __launch_bounds__(256, 2) void attn_prefill128_kernel(
     }
   };
 
+  // kend >= 1, so there is a first tile.  Its store to LDS waits for every load issued so far, the query fragments
+  // included, on the only path into the loop: the waits the compiler places inside the loop then count the one tile
+  // in flight and nothing older (a path around that wait made it wait for all loads at the top of every step).
   const int nsteps = (kend + KT - 1) / KT;
   Stage R;
-  if (nsteps > 0) {
-    gload(0, R);
-    lstore(0, R);
-    if (nsteps > 1) gload(KT, R);
-  }
+  gload(0, R);
+  lstore(0, 0, R);
+  if (nsteps > 1) gload(KT, R);
   __syncthreads();
   for (int t = 0; t < nsteps; ++t) {
     compute(t & 1, t * KT);
-    if (t + 1 < nsteps) lstore((t + 1) & 1, R);          // that buffer was last read one barrier ago
+    if (t + 1 < nsteps) lstore((t + 1) & 1, (t + 1) * KT, R);   // that buffer was last read one barrier ago
     if (t + 2 < nsteps) gload((t + 2) * KT, R);
     __syncthreads();
   }
@@ -489,10 +505,11 @@ hipError_t launch_attn_prefill(int dtype, const void* qkv16, const void* kv, con
   SN_LAUNCH((attn_prefill_kernel<TT, DD>), grid, block, 0, st, (const uint16_t*)qkv16,               \
                      (const uint16_t*)kv, ix.len_before, ix.n_new, ix.tok_start, ix.kv_off, ix.cap, ix.tile_seq, \
                      ix.tile_q0, (uint16_t*)out16, Hq, Hkv, packed)
+  dim3 grid128(8 * ((n_qtiles * Hq + 7) / 8));
 #define SN_PREFILL128(TT)                                                                                    \
-  SN_LAUNCH((attn_prefill128_kernel<TT>), grid, block, 0, st, (const uint16_t*)qkv16,               \
+  SN_LAUNCH((attn_prefill128_kernel<TT>), grid128, block, 0, st, (const uint16_t*)qkv16,               \
                      (const uint16_t*)kv, ix.len_before, ix.n_new, ix.tok_start, ix.kv_off, ix.cap, ix.tile_seq, \
-                     ix.tile_q0, (uint16_t*)out16, Hq, Hkv, packed)
+                     ix.tile_q0, (uint16_t*)out16, Hq, Hkv, packed, n_qtiles)
   if (dtype == 0 && d == 64) SN_PREFILL(F16, 64);
   else if (dtype == 0 && d == 128) SN_PREFILL128(F16);
   else if (dtype == 1 && d == 64) SN_PREFILL(BF16, 64);
