@@ -506,7 +506,8 @@ def test_attn_decode_with_fused_append(dtype, Hq, Hkv, d, rope):
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,rope", [("f16", 4, 4, 64, False), ("bf16", 8, 8, 128, True),
                                                  ("bf16", 8, 2, 128, True), ("f16", 8, 2, 128, True),
-                                                 ("f16", 4, 4, 128, False), ("bf16", 4, 2, 64, True)])
+                                                 ("f16", 4, 4, 128, False), ("bf16", 4, 2, 64, True),
+                                                 ("f16", 6, 2, 128, True)])   # 36 work items: not a multiple of the 8 XCDs
 def test_attn_prefill(dtype, Hq, Hkv, d, rope):
     rng = np.random.default_rng(4)
     lens_before = [0, 0, 40, 0]
