@@ -146,18 +146,18 @@ __device__ __forceinline__ void tile_of(int id, int NT, int TT, int CB, int& tn,
   }
 }
 
-// Feature tiles per group for tile_of in the 192 x 256 kernel.  An XCD runs about 32 workgroups at once: 32/d token tiles x d feature tiles,
-// which fetch (32/d) x 192 + d x 256 operand rows per k step between them; the divisor d of the band that makes this
-// smallest wins, whether or not the weights of the 8 groups then fit the memory-side cache.  Measured at 131072 rows:
-// 57344 x 8192 (band 28) d = 4: 106 ms, 7: 107, 2: 109, 14: 112, 1: 120, 28: 128; 8192 x 28672 (band 4) d = 4: 52.3,
-// 2: 54.1, 1: 60.0; 10240 x 8192 (band 5) d = 5: 19.0, 1: 20.0.
+// Feature tiles per group for tile_of in the 256 x 256 kernel.  An XCD runs about 32 workgroups at once: 32/d token tiles
+// x d feature tiles, which fetch (32/d) x 256 + d x 256 operand rows per k step between them; the divisor d of the band
+// that makes this smallest wins, whether or not the weights of the 8 groups then fit the memory-side cache.  Measured
+// (with 192-token tiles) at 131072 rows: 57344 x 8192 (band 28) d = 4: 106 ms, 7: 107, 2: 109, 14: 112, 1: 120, 28: 128;
+// 8192 x 28672 (band 4) d = 4: 52.3, 2: 54.1, 1: 60.0; 10240 x 8192 (band 5) d = 5: 19.0, 1: 20.0.
 static int tile_group(int NT) {
   if (NT % 8) return 1;
   const int band = NT / 8;
   int cb = 1;
-  long best = 32 * 192 + 256;
+  long best = 32 * 256 + 256;
   for (int d = 2; d <= band && d <= 32; ++d) {
-    const long rows = (32l * 192 + d - 1) / d + 256l * d;
+    const long rows = (32l * 256 + d - 1) / d + 256l * d;
     if (band % d == 0 && rows < best) best = rows, cb = d;
   }
   return cb;
@@ -339,11 +339,13 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
 
 
 // ---------------------------------------------------------------------------------
-// many-tile path: 192 tokens x 256 features per workgroup, 192 x 64 per wavefront
+// many-tile path: 256 tokens x 256 features per workgroup, 256 x 64 per wavefront
 // ---------------------------------------------------------------------------------
-// One workgroup (4 wavefronts, one per SIMD, 512 registers each) per CU; a wavefront keeps 4 x 12
-// accumulator tiles: 64 features x all 192 tokens, 48 MFMAs per 32-wide k step for 4 weight fragments of
-// its own and 12 activation fragments from LDS (112 flop per byte fetched, against 87 for 128 x 256).
+// One workgroup (4 wavefronts, one per SIMD, 512 registers each) per CU; a wavefront keeps 4 x 16
+// accumulator tiles: 64 features x all 256 tokens, 64 MFMAs per 32-wide k step for 4 weight fragments of
+// its own and 16 activation fragments from LDS (128 flop per byte fetched, against 87 for 128 x 256; with 4 x 12
+// tiles, 192 tokens and 112 flop per byte, the same kernel measured 2-7 % slower: what a step costs beyond its
+// MFMAs is the time its bytes take through the CU's one vector-memory path).
 //   * weights of step t: global -> register set t % 4, requested three steps ahead (no weight is
 //     fetched twice by a workgroup, none passes through LDS);
 //   * activations of step t: global -> LDS buffer t % NB directly (global_load_lds_dwordx4: lane l's
@@ -351,14 +353,14 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
 //     token l % 16, k chunk l / 16), requested NB - 1 steps ahead, no registers involved; each fragment
 //     is re-read from LDS for the next step right after the four MFMAs that used it.
 // What makes a lone wavefront per SIMD work (each found by measurement):
-//   * memory requests are spread over the step -- one request, four MFMAs, one LDS read, twelve times --
+//   * memory requests are spread over the step -- one request, four MFMAs, one LDS read, and so on --
 //     because a wavefront that queues its seven requests at once stalls behind them and nothing else
-//     feeds its matrix core (1450 -> 1150 clocks per step);
+//     feeds its matrix core (1450 -> 1150 clocks per step of 48 MFMAs, measured with 192-token tiles);
 //   * the direct-to-LDS loads are inline assembly, so that the compiler does not serialise every LDS
 //     read behind the newest of them; their completion is awaited by hand: loads complete in issue
-//     order, each step issues 3 of them and 4 weight loads per wavefront, so "the activations
-//     of step t + 2 have landed" is s_waitcnt vmcnt(4 + 7 * (NB - 3)) at the end of step t (every
-//     step issues its 7 requests, the last ones redundantly, so the count always holds).  The waits the
+//     order, each step issues 4 of them and 4 weight loads per wavefront, so "the activations
+//     of step t + 2 have landed" is s_waitcnt vmcnt(4 + 8 * (NB - 3)) at the end of step t (every
+//     step issues its 8 requests, the last ones redundantly, so the count always holds).  The waits the
 //     compiler inserts for the weight registers count only its own loads and therefore wait for more
 //     than necessary -- never for less;
 //   * the MFMAs are inline assembly with the accumulator tied to its registers (see mma_inplace);
@@ -371,16 +373,16 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
 //     (see below), which spreads the epilogues' memory bursts over the other CUs' k loops.
 // Ring indices must be compile-time constants, hence the k loop is unrolled by the ring depth, which
 // must divide the number of k steps.  Token rows past M fetch row 0 and are never stored.
-// Measured at 32768 rows (MI355X): 0.97-1.11 PFLOP/s against 0.86-0.99 for the kernel above.
-// The 192 x 256 kernel runs one workgroup per CU, so it needs several rounds of tiles to amortise the
-// unevenness of the last round and its start-up stagger: measured break-even against the 128 x 256 kernel
-// (two workgroups per CU) in isolation is around four rounds of 256 tiles; inside an iteration, between
-// other kernels, it only pays from about eight.
-constexpr int kBigTileMinTiles = 2048;
-constexpr int kBigTileRing = 8;          // LDS buffers / weight register sets of the 192 x 256 kernel (look-ahead 7 k steps)
-constexpr int kBigTileWeightRing = 4;    // weight register sets of the 192 x 256 kernel (look-ahead 3 k steps)
+// Measured at 32768 rows (MI355X): 1.09-1.23 PFLOP/s against 0.86-0.99 for the kernel above.
+// This kernel runs one workgroup per CU, so it needs several rounds of tiles to amortise the
+// unevenness of the last round and its start-up stagger: measured (with 192-token tiles) break-even against the
+// 128 x 256 kernel (two workgroups per CU) in isolation is around four rounds of 256 tiles; inside an iteration,
+// between other kernels, it only pays from about eight -- six rounds of the 256-token tiles.
+constexpr int kBigTileMinTiles = 1536;
+constexpr int kBigTileRing = 8;          // LDS buffers / weight register sets of the 256 x 256 kernel (look-ahead 7 k steps)
+constexpr int kBigTileWeightRing = 4;    // weight register sets of the 256 x 256 kernel (look-ahead 3 k steps)
 constexpr int kBigTileFirstWave = 256;   // workgroups that start at once: one per CU
-constexpr int kBigTileTokenTiles = 12;  // 16-token tiles per workgroup (192 tokens): 4 x 12 accumulator tiles per wavefront
+constexpr int kBigTileTokenTiles = 16;  // 16-token tiles per workgroup (256 tokens): 4 x 16 accumulator tiles per wavefront
 
 template <int V>
 struct IC {
@@ -420,7 +422,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
   constexpr int NB = kBigTileRing;        // ring depth: LDS buffers and weight register sets
   constexpr int D = NB - 1;               // look-ahead in k steps
   constexpr int kTile = 64 * 8;           // elements of one 16 x 32 operand tile
-  static_assert(XT == 3 && FJ == 4 && D >= 3 && D <= 7, "the hand-written wait counts 3 + 4 loads per step");
+  static_assert(XT + FJ <= TI && FJ == 4 && D >= 3 && D <= 7 && FJ + (XT + FJ) * (D - 2) < 64,
+                "the hand-written wait counts XT + FJ loads per step in a 6-bit counter");
   __shared__ __attribute__((aligned(16))) uint16_t xs[NB][TI][kTile];   // 8 x 12 KiB
 
   const int lane = threadIdx.x & 63;
@@ -436,7 +439,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
   if (blockIdx.x < kBigTileFirstWave) {
     const int quarters = ((blockIdx.x >> 3) / CB) & 3;   // consecutive ids go to different XCDs: vary within an XCD, by
                                                          // token tile, so that the CB workgroups sharing one start together
-    const int naps = quarters * (S / 28 + 1);            // one nap = 127 * 64 clocks; a tile is ~1150 clocks per k step + epilogue
+    const int naps = quarters * (S / 21 + 1);            // one nap = 127 * 64 clocks; a tile is ~1500 clocks per k step + epilogue
     for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
   }
   const int t0 = tt * BM;
@@ -513,7 +516,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
       bf[i] = *reinterpret_cast<const u16x8*>(&xs[BN][i][lane * 8]);   // next step's fragment; after the last step: stale, unused
       __builtin_amdgcn_sched_barrier(0);
     }
-    wait_vmcnt<4 + 7 * (D - 2)>();         // this wavefront's share of the activations of step st + 2 has landed
+    wait_vmcnt<FJ + (XT + FJ) * (D - 2)>();   // this wavefront's share of the activations of step st + 2 has landed
     // Bare barrier (no fence): what it publishes are the direct-to-LDS loads just awaited, and the buffer
     // the next step overwrites was read into registers two steps ago.  A fence would also wait for the
     // fragment reads issued a moment ago, which are not needed before the next step.
@@ -556,7 +559,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
   const int nl = (lane >> 4) * 4;
   if (EPI == EPI_RESID32) {
     // fp32 read-modify-write of the residual stream, through the idle operand ring as well (see below):
-    // two halves of 96 tokens x 256 features x 4 bytes; 16-byte chunks swizzled by chunk ^ (token % 16);
+    // two halves of 128 tokens x 256 features x 4 bytes; 16-byte chunks swizzled by chunk ^ (token % 16);
     // afterwards every thread adds 16 contiguous bytes into the stream, a token's 1 KiB row as whole lines.
     static_assert(TI % 2 == 0 && (TI / 2) * 16 * 256 * 4 <= NB * TI * kTile * 2, "half the fp32 tile must fit the ring");
     float* fb = reinterpret_cast<float*>(&xs[0][0][0]);
@@ -608,7 +611,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
   }
   // 16-bit outputs.  A lane holds 4 consecutive features of one token per accumulator tile, so a direct
   // store writes 32-byte pieces of cache lines (measured: ~20 us per tile, a quarter of the kernel).  The
-  // tile is therefore transposed through the now idle operand ring: [192 tokens][OW features], 8-byte chunks
+  // tile is therefore transposed through the now idle operand ring: [256 tokens][OW features], 8-byte chunks
   // swizzled by chunk ^ (token % 16) so that the 16 tokens a store instruction covers hit 16 different
   // bank pairs; then every thread moves 16 contiguous bytes and a token's row leaves as whole lines.
   constexpr bool DUAL = EPI == EPI_SWIGLU16;
@@ -757,7 +760,7 @@ hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, co
   return launch_t<BF16>(epi, (const uint16_t*)W, (const uint16_t*)X, (const uint16_t*)bias, out, M, N, K, xpacked, opacked, st);
 }
 
-// Whether launch_gemm_tile would run this shape on the 192 x 256 kernel, the one that reads and writes row-tile
+// Whether launch_gemm_tile would run this shape on the 256 x 256 kernel, the one that reads and writes row-tile
 // packed activations.
 bool gemm_tile_takes_packed(int M, int N, int K) {
   constexpr int TI = kBigTileTokenTiles;

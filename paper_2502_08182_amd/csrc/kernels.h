@@ -82,7 +82,7 @@ int gemm_qkv_splits(int M, int N, int K);
 // Prefill path: any M.
 hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, const void* bias,
                             void* out, int M, int N, int K, hipStream_t st, int flags = 0);
-bool gemm_tile_takes_packed(int M, int N, int K);   // the 192 x 256 kernel applies: flags kXPacked / kOutPacked allowed
+bool gemm_tile_takes_packed(int M, int N, int K);   // the 256 x 256 kernel applies: flags kXPacked / kOutPacked allowed
 
 // Rotates q (in place) and k, and appends k, v rows to the layer's KV slice
 // ([seq][Hkv][K|V][cap][d]); mirror (may be null) is a second copy of the slice that

@@ -869,7 +869,7 @@ int run_layer(sn_ctx* c, int l, uint8_t* base, uint8_t* kv, uint8_t* mirror_kv, 
   // decode: activations between kernels are row-tile packed (inputs of the skinny GEMMs);
   // the QKV output stays row-major for the attention kernels
   const int pk = small ? 1 : 0;
-  // prefill: a projection that runs on the 192 x 256 kernel reads its activations row-tile packed too (whole cache
+  // prefill: a projection that runs on the 256 x 256 kernel reads its activations row-tile packed too (whole cache
   // lines per request), so whoever produces them writes that layout -- the norms, the attention kernel, and the FFN
   // up-projection when it is itself such a launch
   const bool pk_qkv = !small && gemm_tile_takes_packed(T, p.n_qkv, h), pk_up = !small && gemm_tile_takes_packed(T, p.n_up, h);

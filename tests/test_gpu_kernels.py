@@ -314,7 +314,7 @@ def test_gemm_tile(dtype, epi):
 
 @pytest.mark.parametrize("dtype,epi", [("f16", 0), ("f16", 1), ("bf16", 2), ("bf16", 3), ("f16", 3)])
 def test_gemm_tile_large_m(dtype, epi):
-    """With at least 2048 tiles (and K a multiple of 256) the prefill GEMM uses its 192-token x 256-feature
+    """With at least 1536 tiles (and K a multiple of 256) the prefill GEMM uses its 256-token x 256-feature
     workgroup tile: direct-to-LDS activation loads, an 8-deep operand ring (one, two and three trips of the
     unrolled k loop), outputs transposed through LDS, a ragged last token tile, the XCD-banded numbering
     (32 feature tiles) and the plain one (33).  The last case stays below the threshold (128 x 256 kernel)."""
@@ -325,7 +325,7 @@ def test_gemm_tile_large_m(dtype, epi):
 
 @pytest.mark.parametrize("epi", [0, 2, 3])
 def test_gemm_tile_large_m_packed_activations(epi):
-    """The 192 x 256 prefill GEMM reading row-tile packed activations (one contiguous KiB per 16-token x 32-k tile,
+    """The 256 x 256 prefill GEMM reading row-tile packed activations (one contiguous KiB per 16-token x 32-k tile,
     whole cache lines per request): the layout is a permutation of the operand fetch only, so the output must equal,
     bit for bit, that of the same launch on the row-major matrix -- which test_gemm_tile_large_m checks against the
     oracle.  Ragged last token tile; shapes the smaller kernels would take refuse the flag."""
