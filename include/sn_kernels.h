@@ -47,8 +47,7 @@ int sn_k_norm(int32_t dtype, int32_t is_ln, const void* x32, const void* gain, c
  * 16-row blocks (N = 2*ffn rows), bias = [gate | up], out16[M][N/2] = silu(g)*u.
  * path 0: weight-streaming decode kernel (M <= 128; a packed X holds 16*ceil(M/16) rows); path 1: tiled prefill kernel.
  * flags: 1 = X is row-tile packed; 2 = the 16-bit output (epilogues 0, 1, 3) is written row-tile packed.
- * Path 1 takes them only where its 256 x 256 kernel applies (N % 256 == 0, K % 256 == 0, at least 1536 tiles
- * of 256 rows x 256 features) and returns SN_E_INVAL otherwise: same values bit for bit, whole cache lines per
+ * Path 1 takes them only where its 256 x 256 kernel applies (N % 256 == 0, K % 256 == 0, M > 128) and returns SN_E_INVAL otherwise: same values bit for bit, whole cache lines per
  * activation request instead of half ones. */
 int sn_k_gemm(int32_t dtype, int32_t epilogue, int32_t path, const void* W, const void* X,
               const void* bias, void* out, int32_t M, int32_t N, int32_t K, int32_t flags,

@@ -7,8 +7,10 @@
 // D[feature][token]: a lane ends up with 4 consecutive features of one token, which
 // makes the row-major output store a short vector.
 //
-// Two kernels:
-//  * gemm_tile_lds_kernel -- the fast path (N % 256 == 0, K % 64 == 0).  A 256-thread
+// Three kernels:
+//  * gemm_tile_big_kernel (further down) -- N % 256 == 0, K % 256 == 0 and more than 128 token rows: 256 tokens x 256
+//    features per workgroup, one wavefront per SIMD; every full-size prefill runs on it.
+//  * gemm_tile_lds_kernel -- N % 256 == 0, K % 64 == 0, whatever the first does not take.  A 256-thread
 //    workgroup computes 128 tokens x 256 features; each wavefront owns 128 x 64 of it
 //    (32 accumulator tiles).  The activation slab (128 tokens x 64 k) is shared by the
 //    four wavefronts, so it is staged through LDS, double-buffered, already permuted
@@ -163,7 +165,7 @@ static int tile_group(int NT) {
   return cb;
 }
 
-// The 128 x 256 kernel (two workgroups per CU, at most a few thousand tiles) keeps the rule it was tuned with: the
+// The 128 x 256 kernel (two workgroups per CU) keeps the rule it was tuned with: the
 // largest divisor of the band whose 8 groups' weights fit half the memory-side cache, but two where the band allows it.
 static int tile_group_lds(int NT, int K) {
   if (NT % 8) return 1;
@@ -339,7 +341,7 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
 
 
 // ---------------------------------------------------------------------------------
-// many-tile path: 256 tokens x 256 features per workgroup, 256 x 64 per wavefront
+// main path: 256 tokens x 256 features per workgroup, 256 x 64 per wavefront
 // ---------------------------------------------------------------------------------
 // One workgroup (4 wavefronts, one per SIMD, 512 registers each) per CU; a wavefront keeps 4 x 16
 // accumulator tiles: 64 features x all 256 tokens, 64 MFMAs per 32-wide k step for 4 weight fragments of
@@ -369,19 +371,18 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_lds_kernel(
 //   * the epilogue fetches its bias values once per feature block (not per element: 20 -> 4 us per
 //     tile), transposes the tile through the idle operand ring and stores whole cache lines, and for
 //     the fp32 residual stream requests all its reads before using the first;
-//   * all tiles take the same time, so the first workgroup of each CU starts up to 3/4 of a tile late
-//     (see below), which spreads the epilogues' memory bursts over the other CUs' k loops.
+//   * all workgroups start together.  (While the epilogue still stored partial lines, starting the first workgroup of
+//     each CU up to 3/4 of a tile late spread the epilogues' bursts and gained 20 % on one shape; with the present
+//     epilogue the same stagger costs 1-7 % at many rounds of tiles and up to 30 % at three, so it is gone.)
 // Ring indices must be compile-time constants, hence the k loop is unrolled by the ring depth, which
 // must divide the number of k steps.  Token rows past M fetch row 0 and are never stored.
-// Measured at 32768 rows (MI355X): 1.09-1.23 PFLOP/s against 0.86-0.99 for the kernel above.
-// This kernel runs one workgroup per CU, so it needs several rounds of tiles to amortise the
-// unevenness of the last round and its start-up stagger: measured (with 192-token tiles) break-even against the
-// 128 x 256 kernel (two workgroups per CU) in isolation is around four rounds of 256 tiles; inside an iteration,
-// between other kernels, it only pays from about eight -- six rounds of the 256-token tiles.
-constexpr int kBigTileMinTiles = 1536;
+// Measured at 32768 rows (MI355X): 1.09-1.23 PFLOP/s against 0.86-0.99 for the kernel above; at 4096 rows
+// (12288 x 4096: 768 tiles, three rounds of one workgroup per CU) 0.32 ms against 0.52-0.56 ms, at 1024 rows
+// (4096 x 16384: 64 tiles) 0.29 against 0.39 ms.  It takes every shape with more than one 128-row tile of tokens
+// (below that half of its 256-token tile would be idle arithmetic) whose N and K are multiples of 256.
+constexpr int kBigTileMinRows = 129;
 constexpr int kBigTileRing = 8;          // LDS buffers / weight register sets of the 256 x 256 kernel (look-ahead 7 k steps)
 constexpr int kBigTileWeightRing = 4;    // weight register sets of the 256 x 256 kernel (look-ahead 3 k steps)
-constexpr int kBigTileFirstWave = 256;   // workgroups that start at once: one per CU
 constexpr int kBigTileTokenTiles = 16;  // 16-token tiles per workgroup (256 tokens): 4 x 16 accumulator tiles per wavefront
 
 template <int V>
@@ -432,16 +433,6 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_big_kernel(
 
   int tn, tt;                                // XCD-aware numbering, as in gemm_tile_lds_kernel
   tile_of(blockIdx.x, NT, TT, CB, tn, tt);
-  // All tiles take the same time, so without help every CU would reach its epilogue (a burst of stores, for the
-  // residual epilogue a read-modify-write of 384 KiB) at the same moment, again and again, and the memory system
-  // would alternate between idle and overrun.  The first workgroup of each CU therefore starts up to three
-  // quarters of a tile late; later workgroups inherit the offset because a CU holds one workgroup at a time.
-  if (blockIdx.x < kBigTileFirstWave) {
-    const int quarters = ((blockIdx.x >> 3) / CB) & 3;   // consecutive ids go to different XCDs: vary within an XCD, by
-                                                         // token tile, so that the CB workgroups sharing one start together
-    const int naps = quarters * (S / 21 + 1);            // one nap = 127 * 64 clocks; a tile is ~1500 clocks per k step + epilogue
-    for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
-  }
   const int t0 = tt * BM;
   const int nb0 = tn * 16 + wave * FJ;       // first of this wavefront's feature blocks
   const uint16_t* wp = W + ((size_t)nb0 * S) * 512 + lane * 8;
@@ -685,8 +676,7 @@ template <class T>
 static hipError_t launch_t(int epi, const uint16_t* W, const uint16_t* X, const uint16_t* bias, void* out, int M,
                            int N, int K, int xpacked, int opacked, hipStream_t st) {
   constexpr int TI = kBigTileTokenTiles;
-  if (N % 256 == 0 && K % (32 * kBigTileRing) == 0 &&
-      (int64_t)(N / 256) * ((M + TI * 16 - 1) / (TI * 16)) >= kBigTileMinTiles) {
+  if (N % 256 == 0 && K % (32 * kBigTileRing) == 0 && M >= kBigTileMinRows) {
     const int NT = N / 256, TT = (M + TI * 16 - 1) / (TI * 16), CB = tile_group(NT);
     dim3 grid(NT * TT), block(256);
     switch (epi) {
@@ -763,9 +753,7 @@ hipError_t launch_gemm_tile(int dtype, int epi, const void* W, const void* X, co
 // Whether launch_gemm_tile would run this shape on the 256 x 256 kernel, the one that reads and writes row-tile
 // packed activations.
 bool gemm_tile_takes_packed(int M, int N, int K) {
-  constexpr int TI = kBigTileTokenTiles;
-  return M > 0 && N % 256 == 0 && K % (32 * kBigTileRing) == 0 &&
-         (int64_t)(N / 256) * ((M + TI * 16 - 1) / (TI * 16)) >= kBigTileMinTiles;
+  return N % 256 == 0 && K % (32 * kBigTileRing) == 0 && M >= kBigTileMinRows;
 }
 
 }  // namespace sn

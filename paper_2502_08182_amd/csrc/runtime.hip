@@ -456,8 +456,9 @@ static int init_impl(sn_ctx* c, const sn_model_shape* shape, uint64_t budget, vo
   if (c->max_tokens < s.max_batch) c->max_tokens = s.max_batch;
   if (c->max_tokens > (int64_t)1 << 24) return fail(c, SN_E_INVAL, "max_tokens too large");
   const int L = s.n_layers;
-  // decode activations are stored in 16-row tiles: keep room for whole tiles
-  const uint64_t T = std::max<uint64_t>((uint64_t)c->max_tokens, (uint64_t)((std::min(s.max_batch, kMaxDecodeRows) + 15) / 16 * 16));
+  // activations between kernels are stored in 16-row tiles (decode always, prefill wherever the 256 x 256 projection kernel
+  // runs): a tile that holds the last rows occupies its full 16-row footprint, so every row buffer keeps room for whole tiles
+  const uint64_t T = (std::max<uint64_t>((uint64_t)c->max_tokens, (uint64_t)std::min(s.max_batch, kMaxDecodeRows)) + 15) / 16 * 16;
   const uint64_t qkv_ld = (uint64_t)c->pl.n_qkv, qd = (uint64_t)s.n_q_heads * s.head_dim;
 
   const uint64_t b_x32 = align_up(T * s.hidden * 4), b_u = align_up(T * s.hidden * 2);

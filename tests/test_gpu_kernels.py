@@ -314,12 +314,12 @@ def test_gemm_tile(dtype, epi):
 
 @pytest.mark.parametrize("dtype,epi", [("f16", 0), ("f16", 1), ("bf16", 2), ("bf16", 3), ("f16", 3)])
 def test_gemm_tile_large_m(dtype, epi):
-    """With at least 1536 tiles (and K a multiple of 256) the prefill GEMM uses its 256-token x 256-feature
+    """With more than 128 rows (and N, K multiples of 256) the prefill GEMM uses its 256-token x 256-feature
     workgroup tile: direct-to-LDS activation loads, an 8-deep operand ring (one, two and three trips of the
     unrolled k loop), outputs transposed through LDS, a ragged last token tile, the XCD-banded numbering
-    (32 feature tiles) and the plain one (33).  The last case stays below the threshold (128 x 256 kernel)."""
+    (32 feature tiles) and the plain one (33); a single round of few tiles (300 rows).  The last case, K = 224, stays with the 128 x 256 kernel."""
     wide = 2 if epi == K.EPI_SWIGLU16 else 1      # SwiGLU: N counts output features, the weight has 2 N rows
-    for i, (M, Nw, Kd) in enumerate([(12400, 8192, 256), (12300, 8448, 512), (12481, 8192, 768), (1250, 256, 224)]):
+    for i, (M, Nw, Kd) in enumerate([(12400, 8192, 256), (12300, 8448, 512), (12481, 8192, 768), (300, 1024, 512), (1250, 256, 224)]):
         _gemm_case(dtype, K.PATH_TILE, epi, M, Nw // wide, Kd, bias=(i % 2 == 0), seed=50 + i)
 
 
@@ -353,8 +353,8 @@ def test_gemm_tile_large_m_packed_activations(epi):
         K.sn_k_gemm(DT["f16"], epi, K.PATH_TILE, dev16(tiled), dev16(K.pack_rows(xb)), None, outp, M, N * wide, Kd, 3)
         torch.cuda.synchronize()
         assert np.array_equal(K.unpack_rows(host16(outp), M, N), host16(outs[0]))
-    with pytest.raises(sn.SnError):     # 128 x 256 kernel (fewer than 2048 tiles): row-major only
-        K.sn_k_gemm(DT["f16"], epi, K.PATH_TILE, dev16(tiled), dev16(K.pack_rows(xb[:640])), None, outs[1], 640, N * wide, Kd, 1)
+    with pytest.raises(sn.SnError):     # 128 x 256 kernel (at most 128 rows): row-major only
+        K.sn_k_gemm(DT["f16"], epi, K.PATH_TILE, dev16(tiled), dev16(K.pack_rows(xb[:112])), None, outs[1], 112, N * wide, Kd, 1)
 
 
 def _kv_setup(rng, dtype, lens_before, n_new, caps, Hq, Hkv, d, rope):
