@@ -1,6 +1,8 @@
 // Prefill attention: causal attention of a sequence's new tokens over its cached and
 // new keys, on the matrix cores (prefill is the computation-intensive phase, paper
-// Sec. 2.1).  One 256-thread workgroup handles kPrefillQTile = 128 query rows of one
+// Sec. 2.1).  Two kernels: attn_prefill128_kernel (head dimension 128, further down; every
+// full-size workload) and attn_prefill_kernel (any head dimension the library takes; in use for 64),
+// described here.  One 256-thread workgroup handles kPrefillQTile = 128 query rows of one
 // (sequence, query head); each wavefront owns 32 of them as two 16-query MFMA column tiles, so
 // every K and V fragment read from LDS feeds two products.  Keys are consumed 32 at a time,
 // staged through a pair of LDS tiles (K row-major, V transposed) shared by the four wavefronts:
