@@ -317,9 +317,11 @@ def test_gemm_tile_large_m(dtype, epi):
     """With more than 128 rows (and N, K multiples of 256) the prefill GEMM uses its 256-token x 256-feature
     workgroup tile: direct-to-LDS activation loads, an 8-deep operand ring (one, two and three trips of the
     unrolled k loop), outputs transposed through LDS, a ragged last token tile, the XCD-banded numbering
-    (32 feature tiles) and the plain one (33); a single round of few tiles (300 rows).  The last case, K = 224, stays with the 128 x 256 kernel."""
+    (32 feature tiles) and the plain one (33); a single round of few tiles (300 rows); the smallest row counts it takes (129: one
+    token tile with 127 idle rows; 257: a second tile for one row).  The last case, K = 224, stays with the 128 x 256 kernel."""
     wide = 2 if epi == K.EPI_SWIGLU16 else 1      # SwiGLU: N counts output features, the weight has 2 N rows
-    for i, (M, Nw, Kd) in enumerate([(12400, 8192, 256), (12300, 8448, 512), (12481, 8192, 768), (300, 1024, 512), (1250, 256, 224)]):
+    for i, (M, Nw, Kd) in enumerate([(12400, 8192, 256), (12300, 8448, 512), (12481, 8192, 768), (300, 1024, 512), (129, 512, 256), (257, 256, 512),
+                                      (1250, 256, 224)]):
         _gemm_case(dtype, K.PATH_TILE, epi, M, Nw // wide, Kd, bias=(i % 2 == 0), seed=50 + i)
 
 
