@@ -268,6 +268,29 @@ def pick_interval(tc: Sequence[int], tx: Sequence[int], slo: int, n_max: int, sc
     return n_min
 
 
+def refine_interval(tc: Sequence[int], tx: Sequence[int], N: int, schedule: int = PAPER) -> int:
+    """Among the intervals that keep as many layers on the host as N does, the one whose iteration is shortest
+    (the smallest such interval on a tie; N itself is a candidate).
+
+    The paper's objective is host memory: a smaller interval is better because it offloads more layers (Sec. 4.3),
+    and the optimal interval is the smallest that meets the SLO (Sec. 4.4).  Where L is not a multiple of N several
+    intervals offload the same floor(L / N) layers -- the same host memory, the same GPU footprint -- and the paper
+    does not choose between them; this does, by iteration time.  The result offloads what N offloads and is never
+    slower, so it meets every SLO and capacity bound that N meets.  N = L + 1 (nothing offloaded) stays."""
+    L = len(tc)
+    if N > L:
+        return N
+    K = L // N
+    best_n, best_t = N, timeline(tc, tx, N, schedule)[0]
+    for cand in range(N + 1, L + 1):
+        if L // cand != K:
+            break
+        t = timeline(tc, tx, cand, schedule)[0]
+        if t < best_t:
+            best_n, best_t = cand, t
+    return best_n
+
+
 # ---------------------------------------------------------------------------
 # the analyzer's closed form (Sec. 4.4, "Design"), reported beside the pick
 # ---------------------------------------------------------------------------

@@ -455,6 +455,50 @@ def test_what_is_offloaded_hand_worked_and_inventory():
             assert osch.max_tokens(L, N, w, kt, fx, budget, what) == t
 
 
+def test_refine_interval_hand_worked_closed_form_and_properties():
+    """Intervals that offload equally many layers (same floor(L / N): same host memory, Sec. 4.3) ranked by iteration
+    time.  Hand-worked: L = 8, c = 10.  With x = 65, T(N) = 80 + K max(0, 65 - 10 (N - 1)) under Fig. 7's schedule: one
+    offloaded layer for N = 5..8 with T = 105, 95, 85, 80, two for N = 3, 4 with T = 170, 150.  With x = 35 nothing
+    stalls from N = 5 on (35 <= 40): a tie, and the smallest interval stays."""
+    tc = [10] * 8
+    assert [osch.timeline(tc, [65] * 8, N)[0] for N in range(3, 9)] == [170, 150, 105, 95, 85, 80]
+    assert osch.refine_interval(tc, [65] * 8, 5) == 8
+    assert osch.refine_interval(tc, [65] * 8, 6) == 8
+    assert osch.refine_interval(tc, [65] * 8, 3) == 4
+    assert osch.refine_interval(tc, [65] * 8, 8) == 8
+    assert osch.refine_interval(tc, [65] * 8, 9) == 9            # nothing offloaded: unchanged
+    assert osch.refine_interval(tc, [35] * 8, 5) == 5            # tie: the smallest
+    assert osch.refine_interval(tc, [45] * 8, 5) == 6            # 45 <= 10 (N - 1) first holds at N = 6
+    # closed form for uniform times (N >= 2): T(N) = L c + K max(0, x - (N - 1) c) does not rise with N while K stays,
+    # so the answer is the first interval of the equal-K range without a stall, else the range's last
+    rnd = random.Random(23)
+    for _ in range(1500):
+        L = rnd.randint(2, 40)
+        c, x = rnd.randint(1, 50), rnd.randint(0, 900)
+        N = rnd.randint(2, L)
+        K = L // N
+        last = L // K                                             # largest interval that still offloads K layers
+        no_stall = [n for n in range(N, last + 1) if x <= (n - 1) * c]
+        assert osch.refine_interval([c] * L, [x] * L, N) == (no_stall[0] if no_stall else last)
+    # measured times: the result offloads what N offloads, is never slower than N and than any interval of its range,
+    # and is idempotent; the eager schedule never stalls longer, the continuous one is a steady state (both just run)
+    for _ in range(600):
+        L = rnd.randint(1, 24)
+        tc = [rnd.randint(1, 300) for _ in range(L)]
+        tx = [rnd.randint(0, 2500) for _ in range(L)]
+        N = rnd.randint(1, L + 1)
+        for sched in (osch.PAPER, osch.EAGER, osch.CONTINUOUS):
+            r = osch.refine_interval(tc, tx, N, sched)
+            assert r >= N and (L // r if r <= L else 0) == (L // N if N <= L else 0)
+            t_r = osch.timeline(tc, tx, r, sched)[0]
+            same_k = [n for n in range(1, L + 1) if n >= N and L // n == L // N] if N <= L else [N]
+            assert t_r == min(osch.timeline(tc, tx, n, sched)[0] for n in same_k)
+            assert r == min(n for n in same_k if osch.timeline(tc, tx, n, sched)[0] == t_r)
+            assert osch.refine_interval(tc, tx, r, sched) == r
+            for slo in (t_r, osch.timeline(tc, tx, N, sched)[0]):   # whatever N meets, the result meets
+                assert t_r <= slo or osch.timeline(tc, tx, N, sched)[0] > slo
+
+
 def test_paper_rule_never_exceeds_timeline_pick():
     rnd = random.Random(4)
     for _ in range(5000):
