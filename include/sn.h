@@ -310,6 +310,15 @@ int sn_pick_interval_from_times_sched(int32_t L, const int64_t* tc_ns, const int
                                       int32_t N_max, int32_t schedule, int32_t* N_out);
 /* Same, using the last sn_profile_layers result, the context's budget and its schedule. */
 int sn_pick_interval(sn_ctx* ctx, double slo_ms, int32_t* N_out);
+/* Sec. 4.3 / 4.4 order intervals by the layers they offload (smaller interval, more host memory) and take the
+ * smallest that meets the SLO.  Where L is not a multiple of N, several intervals offload the same
+ * floor(L / N) layers -- the same host memory and the same GPU footprint -- and the paper does not choose
+ * between them.  N_out = among the intervals N' >= N with floor(L / N') == floor(L / N), the one with the
+ * shortest iteration under `schedule` (the smallest on a tie; N itself is a candidate, so the result meets every
+ * latency and capacity bound N meets).  N = L + 1 is returned unchanged.  Pure, host only; host arrays [L];
+ * SN_E_INVAL for N outside 1..L+1, a negative time or an unknown schedule. */
+int sn_refine_interval_from_times(int32_t L, const int64_t* tc_ns, const int64_t* tx_ns, int32_t N, int32_t schedule,
+                                  int32_t* N_out);
 
 /* The analyzer's closed form (Sec. 4.4) for uniform times, reported beside the pick:
  * L_offload = floor(slo / t_trans); interval = floor(L / (L_offload + 1)) + 1. */

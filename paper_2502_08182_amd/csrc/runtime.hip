@@ -341,6 +341,16 @@ extern "C" int sn_pick_interval_from_times_sched(int32_t L, const int64_t* tc, c
   return SN_OK;
 }
 
+extern "C" int sn_refine_interval_from_times(int32_t L, const int64_t* tc, const int64_t* tx, int32_t N, int32_t schedule,
+                                             int32_t* N_out) {
+  if (L < 1 || !tc || !tx || !N_out || N < 1 || N > L + 1 || bad_sched(schedule))
+    return fail(nullptr, SN_E_INVAL, "sn_refine_interval_from_times: bad argument");
+  for (int l = 0; l < L; ++l)
+    if (tc[l] < 0 || tx[l] < 0) return fail(nullptr, SN_E_INVAL, "sn_refine_interval_from_times: negative time");
+  *N_out = refine_interval(L, tc, tx, N, schedule);
+  return SN_OK;
+}
+
 extern "C" int sn_timeline(int32_t L, const int64_t* tc, const int64_t* tx, int32_t N, int64_t* iter_ns,
                            int64_t* stall_total_ns) {
   if (L < 1 || !tc || !tx || !iter_ns) return fail(nullptr, SN_E_INVAL, "sn_timeline: bad argument");

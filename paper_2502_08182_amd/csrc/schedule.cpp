@@ -110,6 +110,21 @@ int min_interval(int L, const int64_t* tc, const int64_t* tx, int64_t slo, int s
   return all <= slo ? L + 1 : -1;
 }
 
+// Sec. 4.3 / 4.4 rank intervals by how many layers they offload; intervals with the same floor(L / N) offload the same
+// layers' worth of host memory and leave the same GPU footprint, and the paper does not choose between them.  Of
+// those, the shortest iteration (the smallest interval on a tie); N itself is a candidate, so the result is never slower.
+int refine_interval(int L, const int64_t* tc, const int64_t* tx, int N, int sched) {
+  if (N > L) return N;
+  const int K = offloaded_count(L, N);
+  int best = N;
+  int64_t best_t = iteration_time(L, tc, tx, N, nullptr, sched);
+  for (int cand = N + 1; cand <= L && offloaded_count(L, cand) == K; ++cand) {
+    const int64_t t = iteration_time(L, tc, tx, cand, nullptr, sched);
+    if (t < best_t) best = cand, best_t = t;
+  }
+  return best;
+}
+
 uint64_t resident_bytes(int L, int N, uint64_t state, uint64_t slot, uint64_t fixed) {
   const int K = offloaded_count(L, N);
   return (uint64_t)(L - K) * state + (K ? 2 * slot : 0) + fixed;

@@ -11,6 +11,7 @@ int trigger_lead(int N, int sched);               // layers between the trigger 
 int trigger_of(int N, int offloaded_layer, int sched = kSchedPaper);
 int64_t iteration_time(int L, const int64_t* tc, const int64_t* tx, int N, int64_t* stall_total, int sched = kSchedPaper);
 int min_interval(int L, const int64_t* tc, const int64_t* tx, int64_t slo, int sched = kSchedPaper);   // -1: none
+int refine_interval(int L, const int64_t* tc, const int64_t* tx, int N, int sched = kSchedPaper);     // fastest interval offloading as many layers as N
 uint64_t resident_bytes(int L, int N, uint64_t state, uint64_t slot, uint64_t fixed);
 int max_interval(int L, uint64_t budget, uint64_t state, uint64_t slot, uint64_t fixed);
 // `what`: the part of a host-resident layer's state kept on the host -- 0 whole state, 1 weights, 2 KV slice

@@ -31,7 +31,7 @@ EXPORTS = (
     "sn_read_hidden_f32",
     "sn_set_timing", "sn_set_kernel_timing_class", "sn_time_kernel_class", "sn_get_stats", "sn_get_layer_times", "sn_profile_layers", "sn_timeline",
     "sn_pick_interval_from_times", "sn_pick_interval", "sn_paper_rule",
-    "sn_set_schedule", "sn_placement_sched", "sn_timeline_sched", "sn_pick_interval_from_times_sched",
+    "sn_set_schedule", "sn_placement_sched", "sn_timeline_sched", "sn_pick_interval_from_times_sched", "sn_refine_interval_from_times",
     "sn_set_offload_part", "sn_offload_part", "sn_max_tokens_part", "sn_resident_bytes_part",
     "sn_kv_truncate", "sn_set_debug",
 )
@@ -124,6 +124,7 @@ def lib() -> C.CDLL:
         "sn_placement_sched": (C.c_int, [i32, i32, i32, C.POINTER(C.c_uint8), pi32]),
         "sn_timeline_sched": (C.c_int, [i32, pi64, pi64, i32, i32, pi64, pi64]),
         "sn_pick_interval_from_times_sched": (C.c_int, [i32, pi64, pi64, i64, i32, i32, pi32]),
+        "sn_refine_interval_from_times": (C.c_int, [i32, pi64, pi64, i32, i32, pi32]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -338,6 +339,14 @@ def sn_pick_interval_from_times_sched(tc: Sequence[int], tx: Sequence[int], slo_
     b, pb = _i64(tx)
     out = C.c_int32()
     _check(lib().sn_pick_interval_from_times_sched(a.size, pa, pb, int(slo_ns), int(n_max), schedule, C.byref(out)))
+    return out.value
+
+
+def sn_refine_interval_from_times(tc: Sequence[int], tx: Sequence[int], N: int, schedule: int = 0) -> int:
+    a, pa = _i64(tc)
+    b, pb = _i64(tx)
+    out = C.c_int32()
+    _check(lib().sn_refine_interval_from_times(a.size, pa, pb, int(N), schedule, C.byref(out)))
     return out.value
 
 

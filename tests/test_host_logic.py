@@ -257,6 +257,25 @@ def test_eager_schedule_agrees_with_the_oracle():
         sn.sn_timeline_sched([1], [1], 1, 3)
 
 
+def test_refine_interval_agrees_with_the_oracle():
+    """sn_refine_interval_from_times (the fastest of the intervals that offload as many layers as N) against the oracle,
+    exactly, for the three schedules; bad arguments are errors."""
+    rnd = random.Random(29)
+    for _ in range(1200):
+        L = rnd.randint(1, 40)
+        tc = [rnd.randint(1, 400) for _ in range(L)]
+        tx = [rnd.randint(0, 3000) for _ in range(L)]
+        N = rnd.randint(1, L + 1)
+        for mine, theirs in ((sn.SN_SCHED_PAPER, osch.PAPER), (sn.SN_SCHED_EAGER, osch.EAGER), (sn.SN_SCHED_CONTINUOUS, osch.CONTINUOUS)):
+            assert sn.sn_refine_interval_from_times(tc, tx, N, mine) == osch.refine_interval(tc, tx, N, theirs)
+    assert sn.sn_refine_interval_from_times([10] * 8, [65] * 8, 5) == 8
+    for bad in ((0, 0), (10, 0), (3, 7)):
+        with pytest.raises(sn.SnError):
+            sn.sn_refine_interval_from_times([10] * 8, [65] * 8, bad[0], bad[1])
+    with pytest.raises(sn.SnError):
+        sn.sn_refine_interval_from_times([10, -1], [5, 5], 1)
+
+
 def test_continuous_schedule_agrees_with_the_oracle():
     """Loads that run on across the iteration boundary: steady-state iteration time, the stalls of the
     last iteration and the picker against the oracle, exactly; triggers inside an iteration are the
