@@ -351,12 +351,26 @@ def main():
     n_paper = sn.sn_paper_rule(L, int(np.median(tx)), slo_ns)
     log(f"[bench] N_min(SLO)={n_min} N_max(cap)={n_max_cap} feasible_at_cap={feasible_at_cap} paper_rule={n_paper} "
         f"predicted T(N_min)={pred_ns / 1e6:.3f} ms")
-    n_run = n_pick_cap if feasible_at_cap else n_min
+    n_first = n_pick_cap if feasible_at_cap else n_min
+    # intervals that offload as many layers as the smallest one that meets the SLO hold the same host memory; of
+    # those, the one with the shortest predicted iteration runs (sn_refine_interval_from_times)
+    n_run = sn.sn_refine_interval_from_times(tc, tx, n_first, PAPER)
+    smallest_leg = None
+    if n_run != n_first:
+        se.place(n_first)
+        st1, wall1 = rig.decode(max(4, min(K, 16)), W)
+        smallest_leg = {"interval": int(n_first), **leg_summary(st1, wall1, slo_ns, B),
+                        "predicted_ms": sn.sn_timeline(tc, tx, n_first)[0] / 1e6}
+        log(f"[bench] smallest interval meeting the SLO N={n_first} (K={smallest_leg['n_offloaded']}): TPOT median "
+            f"{smallest_leg['tpot_median_ms']:.3f} ms max {smallest_leg['tpot_max_ms']:.3f} ms -> {smallest_leg['tokens_per_s']:.1f} tok/s, "
+            f"hidden {smallest_leg['hidden_fraction']:.3f}; same host memory at N={n_run}: predicted "
+            f"{sn.sn_timeline(tc, tx, n_run)[0] / 1e6:.3f} ms")
 
     # ---- the measured run at the picked interval: the headline ---------------------------------------------
     se.place(n_run)
     st, wall_ms = rig.decode(K, W)
     head = leg_summary(st, wall_ms, slo_ns, B)
+    pred_ns, _ = sn.sn_timeline(tc, tx, n_run)
     it = np.array([d["iter_ns"] for d in st], dtype=np.float64)
     value = B * 1e3 / wall_ms
     log(f"[bench] N={n_run} (K={head['n_offloaded']}): TPOT median {head['tpot_median_ms']:.3f} ms max {head['tpot_max_ms']:.3f} ms "
@@ -408,12 +422,15 @@ def main():
                                f"{w.prompt_lens[0] if min(w.prompt_lens) == max(w.prompt_lens) else f'{min(w.prompt_lens)}..{max(w.prompt_lens)}'}"
                                f", teacher-forced decode; HBM budget {w.hbm_budget / 1e9:.0f} GB; TPOT SLO {a.slo_factor}x all-resident",
                    "interval": int(n_run), "n_offloaded": head["n_offloaded"], "schedule": "paper (Fig. 7)",
+                   "interval_smallest_meeting_slo": int(n_first),
+                   "interval_rule": "smallest interval that meets the SLO (Sec. 4.3 / 4.4: the most layers on the host), then, of the "
+                                    "intervals that offload as many layers (same host memory), the one with the shortest predicted iteration",
                    "host_resident_GB": head["n_offloaded"] * (w_layer + seq_prof * B * kvtok) / 1e9,
                    "interval_over_cap": over_cap,
                    "admission_at_cap": ("feasible" if feasible_at_cap else
                                         f"SN_E_INFEASIBLE: smallest interval meeting the SLO is {n_min}, largest the {w.hbm_budget / 1e9:.0f} GB "
                                         f"cap holds is {n_max_cap}; under Sec. 4.5 this request goes back to the scheduler.  Timed with the "
-                                        f"cap lifted (the device holds 288 GB) at the smallest interval that meets the SLO")},
+                                        f"cap lifted (the device holds 288 GB) at the interval `interval_rule` gives")},
         "roofline": roofline,
         "slo": {"tpot_all_resident_ms": tpot0_ns / 1e6, "slo_ms": slo_ns / 1e6, "tpot_median_ms": head["tpot_median_ms"],
                 "tpot_max_ms": head["tpot_max_ms"], "every_iteration_within_slo": head["every_iteration_within_slo"],
@@ -430,6 +447,7 @@ def main():
                      "frac_of_peak": step_bytes / (tpot0_ns * 1e-9) / HBM_PEAK,
                      "all_resident_tokens_per_s": B / (tpot0_ns * 1e-9),
                      "roofline_tokens_per_s": B * HBM_PEAK / step_bytes},
+        "decode_at_smallest_interval_meeting_slo": smallest_leg,
         "decode_layer_breakdown": breakdown,
         "prefill": {"iter_ms_all_resident": pre0["iter_ns"] / 1e6, "tokens": T, "algorithmic_tflop": pre_flops / 1e12,
                     "all_resident_TFLOPs": pre_flops / (pre0["iter_ns"] * 1e-9) / 1e12,
@@ -460,6 +478,8 @@ def main():
         """Pick for SLO f x the all-resident TPOT under `sched` from the given profile, place, run, check."""
         slo_f = int(f * tpot0_ns)
         n_f = pick_or_none(sn, tcp_, txp_, int(slo_f * (1.0 - a.guard)), L + 1, sched)
+        smallest = int(n_f)
+        n_f = sn.sn_refine_interval_from_times(tcp_, txp_, n_f, sched)     # same layers on the host, shortest iteration
         first = int(n_f)
         # an interval whose measured iterations miss the SLO (the analyzer's prediction leaves out what many small
         # copies and the fences cost) is replaced by the next one that offloads fewer layers, and run again
@@ -474,7 +494,8 @@ def main():
                 n_next += 1
             log(f"[bench] SLO {f}x: N={n_f} measured {max(d['iter_ns'] for d in fst) / 1e6:.3f} ms > SLO {slo_f / 1e6:.3f}, trying N={n_next}")
             n_f = n_next
-        pt = {"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f), "picker_first_choice": first,
+        pt = {"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f), "smallest_interval_meeting_slo": smallest,
+              "picker_first_choice": first,
               "adjusted_after_measurement": bool(first != int(n_f)), **leg_summary(fst, fwall, slo_f, B)}
         pred, _ = sn.sn_timeline_sched(tcp_, txp_, n_f, sched)
         pt["predicted_ms"] = pred / 1e6
