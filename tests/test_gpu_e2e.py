@@ -401,6 +401,10 @@ def test_profiler_and_picker_agree_with_oracle(c1):
                 else:
                     assert sn.sn_pick_interval(se.ctx, slo_ns / 1e6) == want
                     assert sn.sn_timeline(tc, tx, want)[0] <= slo_ns
+                    # of the intervals that keep as many layers on the host, the fastest on these measured times
+                    refined = sn.sn_refine_interval_from_times(tc, tx, want)
+                    assert refined == osch.refine_interval(tc.tolist(), tx.tolist(), want)
+                    assert sn.sn_timeline(tc, tx, refined)[0] <= sn.sn_timeline(tc, tx, want)[0]
 
 
 def test_layer_compute_time_is_deterministic_at_a_real_layer_shape():
