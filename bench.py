@@ -492,7 +492,9 @@ def main():
             n_next = n_f + 1
             while n_next <= L and L // n_next >= k_f:
                 n_next += 1
-            log(f"[bench] SLO {f}x: N={n_f} measured {max(d['iter_ns'] for d in fst) / 1e6:.3f} ms > SLO {slo_f / 1e6:.3f}, trying N={n_next}")
+            log(f"[bench] SLO {f}x: N={n_f} measured {max(d['iter_ns'] for d in fst) / 1e6:.3f} ms > SLO {slo_f / 1e6:.3f}, trying N={n_next}"
+                + " (iterations, ms: " + " ".join("%.2f" % (d["iter_ns"] / 1e6) for d in fst)
+                + "; stalls, ms: " + " ".join("%.2f" % (d["stall_ns"] / 1e6) for d in fst) + ")")
             n_f = n_next
         pt = {"slo_factor": f, "slo_ms": slo_f / 1e6, "picked_interval": int(n_f), "smallest_interval_meeting_slo": smallest,
               "picker_first_choice": first,
