@@ -319,6 +319,9 @@ int sn_pick_interval(sn_ctx* ctx, double slo_ms, int32_t* N_out);
  * SN_E_INVAL for N outside 1..L+1, a negative time or an unknown schedule. */
 int sn_refine_interval_from_times(int32_t L, const int64_t* tc_ns, const int64_t* tx_ns, int32_t N, int32_t schedule,
                                   int32_t* N_out);
+/* Same, using the last sn_profile_layers result and the context's schedule (what one calls on sn_pick_interval's
+ * answer); SN_E_STATE before any profile. */
+int sn_refine_interval(sn_ctx* ctx, int32_t N, int32_t* N_out);
 
 /* The analyzer's closed form (Sec. 4.4) for uniform times, reported beside the pick:
  * L_offload = floor(slo / t_trans); interval = floor(L / (L_offload + 1)) + 1. */

@@ -1468,6 +1468,14 @@ extern "C" int sn_pick_interval(sn_ctx* c, double slo_ms, int32_t* N_out) {
   return SN_OK;
 }
 
+extern "C" int sn_refine_interval(sn_ctx* c, int32_t N, int32_t* N_out) {
+  if (!c || !N_out) return fail(c, SN_E_INVAL, "sn_refine_interval: null argument");
+  if (!c->has_profile) return fail(c, SN_E_STATE, "sn_refine_interval before sn_profile_layers");
+  const int rc = sn_refine_interval_from_times(c->shape.n_layers, c->prof_tc.data(), c->prof_tx.data(), N, c->sched, N_out);
+  if (rc) c->err = g_err;
+  return rc;
+}
+
 // =================================================================================
 // entry point for callers that cannot allocate
 // =================================================================================

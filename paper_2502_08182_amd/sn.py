@@ -31,7 +31,7 @@ EXPORTS = (
     "sn_read_hidden_f32",
     "sn_set_timing", "sn_set_kernel_timing_class", "sn_time_kernel_class", "sn_get_stats", "sn_get_layer_times", "sn_profile_layers", "sn_timeline",
     "sn_pick_interval_from_times", "sn_pick_interval", "sn_paper_rule",
-    "sn_set_schedule", "sn_placement_sched", "sn_timeline_sched", "sn_pick_interval_from_times_sched", "sn_refine_interval_from_times",
+    "sn_set_schedule", "sn_placement_sched", "sn_timeline_sched", "sn_pick_interval_from_times_sched", "sn_refine_interval_from_times", "sn_refine_interval",
     "sn_set_offload_part", "sn_offload_part", "sn_max_tokens_part", "sn_resident_bytes_part",
     "sn_kv_truncate", "sn_set_debug",
 )
@@ -119,6 +119,7 @@ def lib() -> C.CDLL:
         "sn_timeline": (C.c_int, [i32, pi64, pi64, i32, pi64, pi64]),
         "sn_pick_interval_from_times": (C.c_int, [i32, pi64, pi64, i64, i32, pi32]),
         "sn_pick_interval": (C.c_int, [ctx, C.c_double, pi32]),
+        "sn_refine_interval": (C.c_int, [ctx, i32, pi32]),
         "sn_paper_rule": (i32, [i32, i64, i64]),
         "sn_set_schedule": (C.c_int, [ctx, i32]),
         "sn_placement_sched": (C.c_int, [i32, i32, i32, C.POINTER(C.c_uint8), pi32]),
@@ -361,6 +362,12 @@ def sn_pick_interval_from_times(tc: Sequence[int], tx: Sequence[int], slo_ns: in
 def sn_pick_interval(ctx, slo_ms: float) -> int:
     out = C.c_int32()
     _check(lib().sn_pick_interval(ctx, float(slo_ms), C.byref(out)), ctx)
+    return out.value
+
+
+def sn_refine_interval(ctx, N: int) -> int:
+    out = C.c_int32()
+    _check(lib().sn_refine_interval(ctx, int(N), C.byref(out)), ctx)
     return out.value
 
 

@@ -404,6 +404,7 @@ def test_profiler_and_picker_agree_with_oracle(c1):
                     # of the intervals that keep as many layers on the host, the fastest on these measured times
                     refined = sn.sn_refine_interval_from_times(tc, tx, want)
                     assert refined == osch.refine_interval(tc.tolist(), tx.tolist(), want)
+                    assert sn.sn_refine_interval(se.ctx, want) == refined      # the same from the context's own profile
                     assert sn.sn_timeline(tc, tx, refined)[0] <= sn.sn_timeline(tc, tx, want)[0]
 
 
