@@ -89,6 +89,31 @@ class Record:
                 best = max(best, n)
         return best
 
+    def lookup_refined(self, phase: int, batch: int, seq: int, kind: int, value: int) -> Optional[int]:
+        """lookup(), then -- keeping the number of host-resident layers, floor(L / N), that its answer stands for
+        (Sec. 4.3: the same host memory) -- the interval whose iteration is shortest on the times of the cells that
+        were consulted, the longest of them counting (conservative, as the lookup itself); the smallest on a tie.
+        The paper does not choose between intervals that offload equally many layers (schedule.refine_interval)."""
+        n = self.lookup(phase, batch, seq, kind, value)
+        if n is None or n > self.L:
+            return n
+        batches = sorted({b for (p, b, _) in self.cells if p == phase})
+        seqs = sorted({s for (p, _, s) in self.cells if p == phase})
+        bb = {max([b for b in batches if b <= batch], default=None), min(b for b in batches if b >= batch)}
+        ss = {max([s for s in seqs if s <= seq], default=None), min(s for s in seqs if s >= seq)}
+        cells = [self.cells[(phase, b, s)] for b in bb for s in ss if b is not None and s is not None and (phase, b, s) in self.cells]
+
+        def worst(cand: int) -> int:
+            return max(schedule.timeline(c["tc"], c["tx"], cand)[0] for c in cells)
+        best_n, best_t = n, worst(n)
+        for cand in range(n + 1, self.L + 1):
+            if self.L // cand != self.L // n:
+                break
+            t = worst(cand)
+            if t < best_t:
+                best_n, best_t = cand, t
+        return best_n
+
     def table(self, phase: int, kind: int, value: int, batches: Sequence[int], seqs: Sequence[int]) -> List[List[int]]:
         """Rows: batch sizes; columns: sequence lengths; entry: lookup (0 = cannot meet, -1 = not covered)."""
         out = []

@@ -68,6 +68,31 @@ def test_hand_worked_cells():
             r.lookup(*q, ABS, 70)
 
 
+def test_refined_lookup_hand_worked():
+    """Intervals 3 and 4 both keep one of the four layers on the host (floor(4 / N) = 1).  Between the sizes the lookup answers
+    3; on the four corners' times T(3) = 65, 45, 45, 40 and T(4) = 55, 40, 40, 40: the slowest corner is faster at 4."""
+    r = _hand_record()
+    assert r.lookup(DEC, 6, 200, ABS, 70) == 3 and r.lookup_refined(DEC, 6, 200, ABS, 70) == 4
+    assert r.lookup_refined(DEC, 4, 256, ABS, 45) == 4          # its own cell: T(3) = 45, T(4) = 40
+    assert r.lookup_refined(DEC, 8, 256, ABS, 40) == 3          # T(3) = T(4) = 40: a tie, the smallest stays
+    assert r.lookup_refined(DEC, 8, 256, ABS, 44) == 2          # two layers on the host: interval 2 is alone
+    assert r.lookup_refined(DEC, 4, 128, ABS, 54) == 5          # nothing offloaded: unchanged
+    assert r.lookup_refined(DEC, 6, 200, ABS, 39) is None
+    with pytest.raises(orec.NotCovered):
+        r.lookup_refined(DEC, 9, 128, ABS, 70)
+    # a stored size reduces to the schedule's own refinement of that cell's interval
+    rng = random.Random(5)
+    for _ in range(200):
+        L = rng.randint(1, 20)
+        tc = [rng.randint(1, 300) for _ in range(L)]
+        tx = [rng.randint(0, 2500) for _ in range(L)]
+        rec = orec.Record(L)
+        rec.put(DEC, 2, 64, tc, tx, L + 1)
+        slo = rng.randint(sum(tc), 4 * sum(tc))
+        n = rec.lookup(DEC, 2, 64, ABS, slo)
+        assert rec.lookup_refined(DEC, 2, 64, ABS, slo) == osch.refine_interval(tc, tx, n)
+
+
 def test_capacity_bound_rejects():
     r = orec.Record(4)
     r.put(DEC, 4, 128, *_cell(25), n_max=2)
@@ -187,6 +212,11 @@ def test_library_record_agrees_with_the_oracle(tmp_path):
                 except orec.NotCovered:
                     want = "not covered"
                 assert _lib_answer(R.sn_record_lookup, c, phase, b, s, kind, val) == want, (case, phase, b, s, kind, val)
+                try:
+                    want_r = o.lookup_refined(phase, b, s, kind, val)
+                except orec.NotCovered:
+                    want_r = "not covered"
+                assert _lib_answer(R.sn_record_lookup_refined, c, phase, b, s, kind, val) == want_r, (case, phase, b, s, kind, val)
                 if (phase, b, s) in o.cells:
                     assert _lib_answer(R.sn_record_cell_interval, c, phase, b, s, kind, val) == \
                         o.cell_interval(phase, b, s, kind, val)
