@@ -753,27 +753,21 @@ def main():
         se.place(0)
         lens = sorted({int(round(p_mean + W + i * K / (a.repick - 1))) for i in range(a.repick)})
         t_rec = time.time()
-        cell_times = {}
         for sq in lens:      # as sn_record_profile, but without the capacity bound: over-cap points are run and labelled
             tcr, txr = sn.sn_profile_layers(se.ctx, L, False, B, sq, reps=1)
             R.sn_record_put(rec, R.SN_PHASE_DECODE, B, sq, tcr, txr, L + 1)
-            cell_times[sq] = (tcr, txr)
         t_rec = time.time() - t_rec
         slo_abs = int(slo_ns * (1.0 - a.guard))
 
         def look(cur_len, refine=True):
-            """The record's interval (the smallest that meets the bound, conservatively over the neighbouring cells), then --
-            same number of layers on the host -- the fastest such interval on the times of the next stored length."""
+            """The record's interval: the smallest that meets the bound, conservatively over the neighbouring cells; refined: of
+            the intervals that keep as many layers on the host, the fastest on those cells' times (sn_record_lookup_refined)."""
             try:
-                n = R.sn_record_lookup(rec, R.SN_PHASE_DECODE, B, cur_len, R.SN_SLO_ABS_NS, slo_abs)
+                return (R.sn_record_lookup_refined if refine else R.sn_record_lookup)(rec, R.SN_PHASE_DECODE, B, cur_len, R.SN_SLO_ABS_NS, slo_abs)
             except sn.SnError as e:
                 if e.code == sn.SN_E_INFEASIBLE:
                     return L + 1
                 raise
-            if not refine:
-                return n
-            tcr_, txr_ = cell_times[min([q for q in lens if q >= cur_len] or [lens[-1]])]
-            return sn.sn_refine_interval_from_times(tcr_, txr_, n, PAPER)
         se.kv_reset([p + W + K + 1 for p in w.prompt_lens])
         n_cur = look(p_mean)
         se.place(n_cur)

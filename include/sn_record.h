@@ -78,6 +78,13 @@ int sn_record_cell_interval(const sn_record* rec, int32_t phase, int32_t batch, 
 int sn_record_lookup(const sn_record* rec, int32_t phase, int32_t batch, int32_t seq, int32_t slo_kind,
                      int64_t slo_value, int32_t* N_out);
 
+/* sn_record_lookup, then -- keeping the number of host-resident layers floor(n_layers / N) its answer stands for
+ * (Sec. 4.3: the same host memory; the paper does not choose between intervals that offload equally many layers)
+ * -- the interval whose iteration under Fig. 7's schedule is shortest on the stored times of the cells that were
+ * consulted, the slowest of them counting; the smallest such interval on a tie.  Same errors as sn_record_lookup. */
+int sn_record_lookup_refined(const sn_record* rec, int32_t phase, int32_t batch, int32_t seq, int32_t slo_kind,
+                             int64_t slo_value, int32_t* N_out);
+
 /* A Table-1-like view for one bound: out[i * n_seqs + j] = lookup(batches[i], seqs[j]),
  * 0 where the bound cannot be met, -1 where the record does not cover the size. */
 int sn_record_table(const sn_record* rec, int32_t phase, int32_t slo_kind, int64_t slo_value, const int32_t* batches,

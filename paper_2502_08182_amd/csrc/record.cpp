@@ -179,8 +179,9 @@ extern "C" int sn_record_cell_interval(const sn_record* rec, int32_t phase, int3
   return cell_interval(rec, it->second, slo_kind, slo_value, N_out);
 }
 
-extern "C" int sn_record_lookup(const sn_record* rec, int32_t phase, int32_t batch, int32_t seq, int32_t slo_kind,
-                                int64_t slo_value, int32_t* N_out) {
+// The lookup proper; `used`, when given, receives the cells that were consulted.
+static int lookup_cells(const sn_record* rec, int32_t phase, int32_t batch, int32_t seq, int32_t slo_kind,
+                        int64_t slo_value, int32_t* N_out, std::vector<const Cell*>* used) {
   if (!rec || !N_out || bad_phase(phase) || batch < 1 || seq < 1) return SN_E_INVAL;
   // stored batch sizes and sequence lengths of this phase
   std::set<int32_t> bs, ss;
@@ -211,8 +212,37 @@ extern "C" int sn_record_lookup(const sn_record* rec, int32_t phase, int32_t bat
       const int rc = cell_interval(rec, it->second, slo_kind, slo_value, &n);
       if (rc != SN_OK) return rc;
       if (n > best) best = n;
+      if (used) used->push_back(&it->second);
     }
   *N_out = best;
+  return SN_OK;
+}
+
+extern "C" int sn_record_lookup(const sn_record* rec, int32_t phase, int32_t batch, int32_t seq, int32_t slo_kind,
+                                int64_t slo_value, int32_t* N_out) {
+  return lookup_cells(rec, phase, batch, seq, slo_kind, slo_value, N_out, nullptr);
+}
+
+extern "C" int sn_record_lookup_refined(const sn_record* rec, int32_t phase, int32_t batch, int32_t seq, int32_t slo_kind,
+                                        int64_t slo_value, int32_t* N_out) {
+  std::vector<const Cell*> used;
+  int32_t n = 0;
+  const int rc = lookup_cells(rec, phase, batch, seq, slo_kind, slo_value, &n, &used);
+  if (rc != SN_OK) return rc;
+  const int L = rec->L;
+  *N_out = n;
+  if (n > L || used.empty()) return SN_OK;
+  // of the intervals that offload as many layers as n, the one whose slowest consulted cell is fastest
+  auto worst = [&](int cand) {
+    int64_t t = 0;
+    for (const Cell* c : used) t = std::max(t, sn::iteration_time(L, c->tc.data(), c->tx.data(), cand, nullptr));
+    return t;
+  };
+  int64_t best_t = worst(n);
+  for (int cand = n + 1; cand <= L && sn::offloaded_count(L, cand) == sn::offloaded_count(L, n); ++cand) {
+    const int64_t t = worst(cand);
+    if (t < best_t) *N_out = cand, best_t = t;
+  }
   return SN_OK;
 }
 

@@ -13,7 +13,7 @@ SN_PHASE_DECODE, SN_PHASE_PREFILL = 0, 1
 SN_SLO_ABS_NS, SN_SLO_REL_PERMILLE = 0, 1
 
 EXPORTS = ("sn_record_create", "sn_record_destroy", "sn_record_layers", "sn_record_cells", "sn_record_put",
-           "sn_record_profile", "sn_record_get", "sn_record_cell_interval", "sn_record_lookup", "sn_record_table",
+           "sn_record_profile", "sn_record_get", "sn_record_cell_interval", "sn_record_lookup", "sn_record_lookup_refined", "sn_record_table",
            "sn_record_save", "sn_record_load")
 
 _ready = False
@@ -36,6 +36,7 @@ def _lib():
             "sn_record_get": (C.c_int, [rec, i32, i32, i32, pi64, pi64, pi32]),
             "sn_record_cell_interval": (C.c_int, [rec, i32, i32, i32, i32, i64, pi32]),
             "sn_record_lookup": (C.c_int, [rec, i32, i32, i32, i32, i64, pi32]),
+            "sn_record_lookup_refined": (C.c_int, [rec, i32, i32, i32, i32, i64, pi32]),
             "sn_record_table": (C.c_int, [rec, i32, i32, i64, pi32, i32, pi32, i32, pi32]),
             "sn_record_save": (C.c_int, [rec, C.c_char_p]),
             "sn_record_load": (C.c_int, [C.POINTER(rec), C.c_char_p]),
@@ -117,6 +118,12 @@ def sn_record_cell_interval(rec, phase: int, batch: int, seq: int, slo_kind: int
 def sn_record_lookup(rec, phase: int, batch: int, seq: int, slo_kind: int, slo_value: int) -> int:
     n = C.c_int32(0)
     _chk(_lib().sn_record_lookup(rec, phase, batch, seq, slo_kind, int(slo_value), C.byref(n)), "sn_record_lookup")
+    return int(n.value)
+
+
+def sn_record_lookup_refined(rec, phase: int, batch: int, seq: int, slo_kind: int, slo_value: int) -> int:
+    n = C.c_int32(0)
+    _chk(_lib().sn_record_lookup_refined(rec, phase, batch, seq, slo_kind, int(slo_value), C.byref(n)), "sn_record_lookup_refined")
     return int(n.value)
 
 

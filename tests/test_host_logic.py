@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
     assert sorted(sn_kernels.EXPORTS) == knames
     from paper_2502_08182_amd import sn_record
     rnames = [n for n in _declared_functions("sn_record.h") if n.startswith("sn_record_")]
-    assert len(rnames) == 12
+    assert len(rnames) == 13
     for n in rnames:
         assert hasattr(L, n), n
     assert sorted(sn_record.EXPORTS) == rnames
