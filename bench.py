@@ -358,7 +358,7 @@ def main():
     smallest_leg = None
     if n_run != n_first:
         se.place(n_first)
-        st1, wall1 = rig.decode(max(4, min(K, 16)), W)
+        st1, wall1 = rig.decode(min(K, 16), W)
         smallest_leg = {"interval": int(n_first), **leg_summary(st1, wall1, slo_ns, B),
                         "predicted_ms": sn.sn_timeline(tc, tx, n_first)[0] / 1e6}
         log(f"[bench] smallest interval meeting the SLO N={n_first} (K={smallest_leg['n_offloaded']}): TPOT median "
@@ -506,14 +506,14 @@ def main():
         pt["loads_issued_ahead_per_step"] = int(fst[-1]["n_preissued"])
         return pt
 
-    k_short = max(4, min(K, 16))
+    k_short = min(K, 16)
     extra_factors = [float(v) for v in a.slo_points.split(",") if v] if (a.full and a.slo_points) else []
 
     # ---- the picker at looser SLOs: pick, run, check every iteration (over-cap points labelled) ----
     if extra_factors:
         pts = []
         for f in extra_factors:
-            pts.append(decode_point(f, tc, tx, PAPER, max(4, min(K, 8))))
+            pts.append(decode_point(f, tc, tx, PAPER, min(K, 8)))
             log(f"[bench] SLO {f}x: picked N={pts[-1]['picked_interval']} (K={pts[-1]['n_offloaded']}), TPOT median "
                 f"{pts[-1]['tpot_median_ms']:.3f} max {pts[-1]['tpot_max_ms']:.3f} (predicted {pts[-1]['predicted_ms']:.3f}) "
                 f"within={pts[-1]['every_iteration_within_slo']} hidden {pts[-1]['hidden_fraction']:.3f}")
@@ -574,7 +574,7 @@ def main():
                 continue
             log(f"[bench] sweep N={N}: placing {L // N} layers on the host")
             se.place(N)
-            sst, swall = rig.decode(max(4, min(K, 8)), 1)
+            sst, swall = rig.decode(min(K, 8), 1)
             row = {"interval": N, **leg_summary(sst, swall, slo_ns, B)}
             pred, _ = sn.sn_timeline(tc, tx, N)
             row.update({"x_all_resident": row["tpot_median_ms"] * 1e6 / tpot0_ns, "predicted_ms": pred / 1e6,
