@@ -108,7 +108,11 @@ enum { SN_K_NORM = 0, SN_K_QKV = 1, SN_K_ROPE_APPEND = 2, SN_K_ATTN = 3, SN_K_OP
 /* Create a context for a model of this shape under an HBM budget (Sec. 4.5: the
  * maximum interval follows from the GPU's capacity).  hbm_budget_bytes == 0: no cap.
  * Allocates the pinned host master for all layers' weights and the device workspace.
- * hip_compute_stream: caller-owned hipStream_t on which sn_step enqueues kernels. */
+ * hip_compute_stream: caller-owned hipStream_t on which sn_step enqueues kernels.
+ * The first call on a device in a process also runs a burst of small copies on
+ * temporary streams (64 MB of pinned and of device memory for ~40 ms, released
+ * before it returns), so that the runtime's one-off copy-queue set-ups, each of
+ * which holds the calling thread for milliseconds, do not fall into an iteration. */
 int sn_init(sn_ctx** out, const sn_model_shape* shape, uint64_t hbm_budget_bytes,
             void* hip_compute_stream);
 void sn_destroy(sn_ctx* ctx);
